@@ -1,0 +1,195 @@
+"""ctypes front end of the CPU oracle (``aif_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's
+``cpu_baseline`` leg import this; the product package never does.
+
+All array arguments are NumPy arrays: float32 for anything that is stored in
+fp32 or bf16 (both widen to float32 exactly), int32 for ids.  Results come
+back as float64.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "aif_oracle.c")
+_LIB = os.path.join(_HERE, "libaif_oracle.so")
+
+OK, EINVAL, ESHAPE, ENOMEM, ERANGE = 0, 1, 2, 3, 5
+CROSS_NONE, CROSS_HADAMARD, CROSS_SEGDOT = 0, 1, 2
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc -O2 (no fast-math) into a shared object."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c99", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.aifo_sigmoid.restype = C.c_double
+        _lib.aifo_sigmoid.argtypes = [C.c_double]
+    return _lib
+
+
+def _f32(a) -> Optional[np.ndarray]:
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _p(a, ty):
+    return None if a is None else a.ctypes.data_as(C.POINTER(ty))
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code: int):
+        super().__init__(f"oracle status {code}")
+        self.code = code
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise OracleError(rc)
+
+
+def gather(table, ids) -> np.ndarray:
+    table = _f32(table)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    out = np.empty((ids.size, table.shape[1]), dtype=np.float64)
+    _check(lib().aifo_gather(_p(table, C.c_float), C.c_int64(table.shape[0]), table.shape[1],
+                             _p(ids, C.c_int32), ids.size, _p(out, C.c_double)))
+    return out
+
+
+def query(e, w_q, d_attn: int) -> np.ndarray:
+    e = np.ascontiguousarray(e, dtype=np.float64)
+    w_q = _f32(w_q)
+    q = np.empty(d_attn, dtype=np.float64)
+    lib().aifo_query(_p(e, C.c_double), _p(w_q, C.c_float), e.size, d_attn, _p(q, C.c_double))
+    return q
+
+
+def attention(q, K, V, n_heads: int = 1, return_weights: bool = False):
+    q = np.ascontiguousarray(q, dtype=np.float64)
+    K = _f32(K)
+    V = _f32(V)
+    L = K.shape[0]
+    d_attn = q.size
+    a = np.empty(d_attn, dtype=np.float64)
+    p = np.empty((n_heads, L), dtype=np.float64) if return_weights else None
+    lib().aifo_attention(_p(q, C.c_double), _p(K, C.c_float), _p(V, C.c_float), L, d_attn, n_heads,
+                         _p(a, C.c_double), _p(p, C.c_double))
+    return (a, p) if return_weights else a
+
+
+def cross(mode: int, user_operand, e, n_cross: int = 0, d_c: int = 0) -> np.ndarray:
+    e = np.ascontiguousarray(e, dtype=np.float64)
+    uc = _f32(user_operand)
+    width = lib().aifo_cross_width(mode, e.size, n_cross, d_c)
+    if width < 0:
+        raise OracleError(ESHAPE)
+    c = np.empty(width, dtype=np.float64)
+    _check(lib().aifo_cross(mode, _p(uc, C.c_float), n_cross, d_c, _p(e, C.c_double), e.size,
+                            _p(c, C.c_double)))
+    return c
+
+
+def _cat(arrs: Sequence[Optional[np.ndarray]], shapes) -> Optional[np.ndarray]:
+    if arrs is None:
+        return None
+    parts = []
+    for a, shp in zip(arrs, shapes):
+        if a is None:
+            parts.append(np.zeros(int(np.prod(shp)), dtype=np.float32))
+        else:
+            a = _f32(a)
+            assert tuple(a.shape) == tuple(shp), (a.shape, shp)
+            parts.append(a.reshape(-1))
+    return np.concatenate(parts) if parts else np.zeros(0, np.float32)
+
+
+def mlp(x, dims: Sequence[int], weights, biases=None) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    dims_a = np.ascontiguousarray(dims, dtype=np.int32)
+    nl = len(dims) - 1
+    w = _cat(weights, [(dims[l + 1], dims[l]) for l in range(nl)])
+    b = _cat(biases, [(dims[l + 1],) for l in range(nl)]) if biases is not None else None
+    z = np.empty(dims[-1], dtype=np.float64)
+    _check(lib().aifo_mlp(_p(x, C.c_double), nl, _p(dims_a, C.c_int32), _p(w, C.c_float),
+                          _p(b, C.c_float), _p(z, C.c_double)))
+    return z
+
+
+def sigmoid(z: float) -> float:
+    return float(lib().aifo_sigmoid(float(z)))
+
+
+@dataclass
+class Scores:
+    logits: np.ndarray            # [n] float64
+    scores: np.ndarray            # [n] float64, sigmoid(logit)
+    attn: np.ndarray              # [n, d_attn]
+    cross: np.ndarray             # [n, d_cross]
+
+
+def score(*, table, ids, user_vec, seq_keys, seq_vals, dims, weights, biases=None, w_q=None,
+          n_heads: int = 1, cross_mode: int = CROSS_HADAMARD, cross_vecs=None,
+          n_threads: int = 1) -> Scores:
+    """Steps 1-6 for the candidates ``ids`` of one request."""
+    table = _f32(table)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    user_vec = _f32(user_vec)
+    K = _f32(seq_keys)
+    V = _f32(seq_vals)
+    w_q = _f32(w_q)
+    cv = _f32(cross_vecs)
+    d_item = table.shape[1]
+    d_attn = K.shape[1]
+    L = K.shape[0]
+    assert V.shape == K.shape
+    n_cross, d_c = (cv.shape if (cv is not None and cross_mode == CROSS_SEGDOT) else (0, 0))
+    d_cross = lib().aifo_cross_width(cross_mode, d_item, n_cross, d_c)
+    if d_cross < 0:
+        raise OracleError(ESHAPE)
+    nl = len(dims) - 1
+    dims_a = np.ascontiguousarray(dims, dtype=np.int32)
+    w = _cat(weights, [(dims[l + 1], dims[l]) for l in range(nl)])
+    b = _cat(biases, [(dims[l + 1],) for l in range(nl)]) if biases is not None else None
+    n = ids.size
+    z = np.empty(n, np.float64)
+    y = np.empty(n, np.float64)
+    a = np.empty((n, d_attn), np.float64)
+    c = np.empty((n, max(d_cross, 0)), np.float64)
+    _check(lib().aifo_score(
+        _p(table, C.c_float), C.c_int64(table.shape[0]), d_item,
+        _p(w_q, C.c_float), d_attn, n_heads,
+        _p(user_vec, C.c_float), user_vec.size,
+        cross_mode, _p(cv, C.c_float), n_cross, d_c,
+        _p(K, C.c_float), _p(V, C.c_float), L,
+        nl, _p(dims_a, C.c_int32), _p(w, C.c_float), _p(b, C.c_float),
+        _p(ids, C.c_int32), n,
+        _p(z, C.c_double), _p(y, C.c_double), _p(a, C.c_double), _p(c, C.c_double),
+        n_threads))
+    return Scores(z, y, a, c)
+
+
+def topk(z, k: int):
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    idx = np.empty(max(k, 0), np.int32)
+    val = np.empty(max(k, 0), np.float64)
+    _check(lib().aifo_topk(_p(z, C.c_double), z.size, k, _p(idx, C.c_int32), _p(val, C.c_double)))
+    return idx, val

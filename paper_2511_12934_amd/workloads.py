@@ -1,0 +1,245 @@
+"""Seeded synthetic workloads shaped like the paper's pre-ranking traffic.
+
+This module only makes inputs (shapes, distributions, storage rounding).  It
+holds none of the scoring arithmetic and is the one module both the GPU tests
+and the CPU oracle tests draw their inputs from.
+
+The paper's traffic (Sec. 5.1, production logs) is not public; requests here
+follow its stated scale -- about 10^4 retrieved candidates per request cut to
+about 10^2, 1,000-item mini-batches (Sec. 1) -- with sizes per configuration
+C1..C5 below.  Values are N(0, 0.1^2) rounded once to the storage type;
+weights are Xavier-uniform with zero biases.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+CROSS_NONE, CROSS_HADAMARD, CROSS_SEGDOT = 0, 1, 2
+SEED_BASE = 0xA1F0000
+
+
+@dataclass(frozen=True)
+class Config:
+    name: str
+    index: int                  # 1..5, enters the seed
+    dtype: str                  # "f32" | "bf16": storage type of table, user tensors, weights
+    n_users: int
+    n_cand: int
+    n_items: int
+    d_item: int
+    id_dist: str                # "uniform" | "zipf"
+    seq_len: int
+    d_attn: int
+    n_heads: int
+    use_wq: bool
+    cross_mode: int
+    n_cross: int
+    d_cross_vec: int
+    d_user: int
+    mlp_dims: Tuple[int, ...]
+    top_k: int
+    zipf_s: float = 1.1
+
+    @property
+    def d_cross(self) -> int:
+        if self.cross_mode == CROSS_HADAMARD:
+            return self.d_item
+        if self.cross_mode == CROSS_SEGDOT:
+            return self.n_cross * (self.d_item // self.d_cross_vec)
+        return 0
+
+    @property
+    def d_in(self) -> int:
+        return self.d_user + self.d_item + self.d_attn + self.d_cross
+
+    @property
+    def seed(self) -> int:
+        return SEED_BASE + self.index
+
+    def scaled(self, **kw) -> "Config":
+        return replace(self, **kw)
+
+
+CONFIGS: Dict[str, Config] = {
+    "C1": Config("C1", 1, "f32", 1, 1_000, 100_000, 64, "uniform", 50, 32, 1, True,
+                 CROSS_HADAMARD, 0, 0, 64, (224, 128, 64, 1), 100),
+    "C2": Config("C2", 2, "bf16", 1, 10_000, 1_000_000, 64, "zipf", 1_000, 64, 1, False,
+                 CROSS_HADAMARD, 0, 0, 64, (256, 256, 128, 1), 200),
+    "C3": Config("C3", 3, "bf16", 64, 10_000, 10_000_000, 64, "zipf", 500, 64, 1, False,
+                 CROSS_HADAMARD, 0, 0, 64, (256, 512, 256, 1), 100),
+    "C4": Config("C4", 4, "bf16", 16, 20_000, 50_000_000, 128, "uniform", 200, 128, 4, False,
+                 CROSS_HADAMARD, 0, 0, 128, (512, 256, 1), 100),
+    "C5": Config("C5", 5, "bf16", 32, 10_000, 10_000_000, 256, "zipf", 2_000, 128, 8, True,
+                 CROSS_SEGDOT, 16, 64, 576, (1024, 1024, 512, 256, 1), 150),
+}
+for _c in CONFIGS.values():
+    assert _c.d_in == _c.mlp_dims[0], (_c.name, _c.d_in)
+
+
+# ----------------------------------------------------------------------------
+# storage rounding
+# ----------------------------------------------------------------------------
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """float32 -> bf16 bit patterns (uint16), round to nearest even."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    nan = (u & 0x7FFFFFFF) > 0x7F800000
+    r = (u + (0x7FFF + ((u >> 16) & 1))) >> 16
+    r = np.where(nan, (u >> 16) | 0x40, r)
+    return r.astype(np.uint16)
+
+
+def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
+    return (bits.astype(np.uint32) << 16).view(np.float32)
+
+
+def round_storage(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Round float32 values once to the storage type; result is float32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if dtype == "f32":
+        return x
+    if dtype == "bf16":
+        return bf16_to_f32(bf16_bits(x)).reshape(x.shape)
+    raise ValueError(dtype)
+
+
+# ----------------------------------------------------------------------------
+# model weights
+# ----------------------------------------------------------------------------
+@dataclass
+class Model:
+    dims: Tuple[int, ...]
+    weights: List[np.ndarray]           # W_l [out, in], float32 holding storage-rounded values
+    biases: List[np.ndarray]            # b_l [out]
+    w_q: Optional[np.ndarray]           # [d_attn, d_item] or None
+
+
+def _xavier(rng: np.random.Generator, fan_out: int, fan_in: int) -> np.ndarray:
+    lim = np.sqrt(6.0 / (fan_in + fan_out))
+    return rng.uniform(-lim, lim, size=(fan_out, fan_in)).astype(np.float32)
+
+
+def make_model(cfg: Config, seed: Optional[int] = None, bias_scale: float = 0.0) -> Model:
+    """Xavier-uniform weights; biases zero unless ``bias_scale`` is given (tests)."""
+    rng = np.random.default_rng((cfg.seed if seed is None else seed) ^ 0x5EED)
+    ws, bs = [], []
+    for l in range(len(cfg.mlp_dims) - 1):
+        ws.append(round_storage(_xavier(rng, cfg.mlp_dims[l + 1], cfg.mlp_dims[l]), cfg.dtype))
+        b = rng.standard_normal(cfg.mlp_dims[l + 1]).astype(np.float32) * bias_scale
+        bs.append(round_storage(b, cfg.dtype))
+    wq = round_storage(_xavier(rng, cfg.d_attn, cfg.d_item), cfg.dtype) if cfg.use_wq else None
+    return Model(tuple(cfg.mlp_dims), ws, bs, wq)
+
+
+# ----------------------------------------------------------------------------
+# user side
+# ----------------------------------------------------------------------------
+@dataclass
+class User:
+    user_vec: np.ndarray                # [d_user]
+    seq_keys: np.ndarray                # [L, d_attn]
+    seq_vals: np.ndarray                # [L, d_attn]
+    cross_vecs: Optional[np.ndarray]    # SEGDOT: [n_cross, d_cross_vec]; HADAMARD: None (= user_vec)
+
+
+def make_user(cfg: Config, rng: np.random.Generator, sigma: float = 0.1,
+              seq_len: Optional[int] = None) -> User:
+    L = cfg.seq_len if seq_len is None else seq_len
+    g = lambda *s: round_storage(rng.standard_normal(s).astype(np.float32) * sigma, cfg.dtype)
+    u = g(cfg.d_user)
+    k = g(L, cfg.d_attn)
+    v = g(L, cfg.d_attn)
+    cv = g(cfg.n_cross, cfg.d_cross_vec) if cfg.cross_mode == CROSS_SEGDOT else None
+    return User(u, k, v, cv)
+
+
+# ----------------------------------------------------------------------------
+# item table
+# ----------------------------------------------------------------------------
+def make_table_host(cfg: Config, rng: np.random.Generator, n_items: Optional[int] = None,
+                    sigma: float = 0.1) -> np.ndarray:
+    """Whole table on the host (small configurations only)."""
+    n = cfg.n_items if n_items is None else n_items
+    t = rng.standard_normal((n, cfg.d_item), dtype=np.float32) * np.float32(sigma)
+    return round_storage(t, cfg.dtype)
+
+
+def make_table_device(cfg: Config, device, n_items: Optional[int] = None, sigma: float = 0.1,
+                      chunk_rows: int = 4_000_000):
+    """Whole table filled on the device in chunks (tables too large for the host)."""
+    import torch
+
+    n = cfg.n_items if n_items is None else n_items
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    gen = torch.Generator(device=device)
+    gen.manual_seed(cfg.seed)
+    out = torch.empty((n, cfg.d_item), dtype=tdt, device=device)
+    for lo in range(0, n, chunk_rows):
+        hi = min(n, lo + chunk_rows)
+        blk = torch.randn((hi - lo, cfg.d_item), dtype=torch.float32, device=device, generator=gen)
+        out[lo:hi] = (blk * sigma).to(tdt)
+        del blk
+    return out
+
+
+# ----------------------------------------------------------------------------
+# candidate ids
+# ----------------------------------------------------------------------------
+class IdSampler:
+    """Candidate ids of one request: ``n`` distinct rows (a retrieval stage
+    returns a set), uniform or Zipf(s) over the table.  Zipf: P(rank r) ~ r^-s
+    on r in [1, n_items] by inverse CDF with the exact truncated normaliser;
+    rank -> row through a fixed seeded permutation so hot rows are scattered.
+    Ids repeat across users (the cross-request reuse of Sec. 1)."""
+
+    def __init__(self, cfg: Config, n_items: Optional[int] = None):
+        self.n_items = cfg.n_items if n_items is None else n_items
+        self.dist = cfg.id_dist
+        if self.dist == "zipf":
+            r = np.arange(1, self.n_items + 1, dtype=np.float64)
+            self.cdf = np.cumsum(r ** (-cfg.zipf_s))
+            self.cdf /= self.cdf[-1]
+            prng = np.random.default_rng(cfg.seed ^ 0x9E3779B9)
+            self.perm = prng.permutation(self.n_items).astype(np.int32)
+
+    def _draw(self, rng: np.random.Generator, m: int) -> np.ndarray:
+        if self.dist == "uniform":
+            return rng.integers(0, self.n_items, size=m, dtype=np.int64).astype(np.int32)
+        ranks = np.searchsorted(self.cdf, rng.random(m), side="left")
+        ranks = np.minimum(ranks, self.n_items - 1)
+        return self.perm[ranks]
+
+    def sample(self, rng: np.random.Generator, n: int) -> np.ndarray:
+        if n > self.n_items:
+            raise ValueError("more distinct candidates than table rows")
+        got: List[np.ndarray] = []
+        seen = set()
+        have = 0
+        while have < n:
+            d = self._draw(rng, max(2 * (n - have), 64))
+            _, first = np.unique(d, return_index=True)
+            d = d[np.sort(first)]
+            keep = np.fromiter((x not in seen for x in d.tolist()), dtype=bool, count=d.size)
+            d = d[keep][: n - have]
+            seen.update(d.tolist())
+            got.append(d)
+            have += d.size
+        return np.concatenate(got).astype(np.int32)
+
+
+@dataclass
+class Request:
+    user: User
+    ids: np.ndarray
+
+
+def make_requests(cfg: Config, n_users: Optional[int] = None, n_cand: Optional[int] = None,
+                  n_items: Optional[int] = None, seed: Optional[int] = None,
+                  sigma: float = 0.1) -> List[Request]:
+    rng = np.random.default_rng(cfg.seed if seed is None else seed)
+    sampler = IdSampler(cfg, n_items)
+    nu = cfg.n_users if n_users is None else n_users
+    nc = cfg.n_cand if n_cand is None else n_cand
+    return [Request(make_user(cfg, rng, sigma), sampler.sample(rng, nc)) for _ in range(nu)]
