@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the real-time pre-ranking scoring path on one MI355X.
+
+A step is one pass of the whole hot path -- aif_score_batch (gather -> user
+fold -> attention + cross -> MLP) followed by aif_topk -- over one batch of
+synthetic requests already resident in HBM.  Default workload: configuration
+C3 (64 concurrent users x 10^4 candidates, bf16), the batched 10^4-candidate
+request shape the metric is quoted on.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1..C5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # dense bf16
+PEAK_FP32_VALU_TFLOPS = 157.3
+
+
+def algorithmic_work(cfg):
+    """Per-candidate algorithmic bytes / flops of each kernel (what the method
+    needs, not what the implementation moves); amortised per-request terms
+    (K/V, weights) are left out."""
+    B = 4 if cfg.dtype == "f32" else 2
+    k1 = cfg.d_in - cfg.d_user
+    dims = cfg.mlp_dims
+    mlp = 2 * (k1 * dims[1] + sum(dims[l] * dims[l + 1] for l in range(1, len(dims) - 1)))
+    attn = 4 * cfg.seq_len * cfg.d_attn + (2 * cfg.d_item * cfg.d_attn if cfg.use_wq else 0)
+    if cfg.cross_mode == 2:
+        attn += 2 * cfg.d_cross * cfg.d_cross_vec
+    elif cfg.cross_mode == 1:
+        attn += cfg.d_item
+    return {
+        "gather": {"bytes": 4 + 2 * cfg.d_item * B},
+        "attention": {"flops": attn, "bytes": cfg.d_item * B + (cfg.d_attn + cfg.d_cross) * B},
+        "mlp": {"flops": mlp, "bytes": k1 * B + 4},
+        "topk": {"bytes": 4},
+    }
+
+
+def cpu_baseline(cfg, w, seconds_budget=20.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+    import numpy as np
+
+    import oracle
+    threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1))
+    users = [0]
+    n = min(w.n_cand, 2000)
+
+    def run(u, n_c):
+        pos = np.arange(n_c)
+        rows = w.rows_of(u, pos)
+        req = w.requests[u]
+        t0 = time.perf_counter()
+        ref = oracle.score(table=rows, ids=np.arange(n_c, dtype=np.int32), user_vec=req.user.user_vec,
+                           seq_keys=req.user.seq_keys, seq_vals=req.user.seq_vals, dims=w.model.dims,
+                           weights=w.model.weights, biases=w.model.biases, w_q=w.model.w_q,
+                           n_heads=cfg.n_heads, cross_mode=cfg.cross_mode, cross_vecs=req.user.cross_vecs,
+                           n_threads=threads)
+        oracle.topk(ref.logits, cfg.top_k)
+        return time.perf_counter() - t0
+
+    t = run(0, n)                                   # probe
+    per_cand = t / n
+    n_full = int(min(w.n_cand, max(n, seconds_budget / threads / max(per_cand, 1e-9) * 0.5)))
+    t = run(0, n_full)
+    return {"value": n_full / t, "unit": "candidates/s", "cores": threads, "kind": "oracle",
+            "sample": f"1 user x {n_full} candidates of {cfg.name} (oracle score + top-k, {threads} OpenMP threads, "
+                      f"{t:.2f} s wall)"}
+
+
+def single_request_latency(n_iter=200):
+    """p50/p99 of one 10^4-candidate request (configuration C2), enqueue to completion of top-k,
+    scored whole and as ten 1,000-item mini-batches; 32 distinct requests rotated."""
+    import numpy as np
+    import torch
+
+    from paper_2511_12934_amd import runner as R
+    from paper_2511_12934_amd import workloads as wl
+    cfg = wl.CONFIGS["C2"]
+    out = {}
+    for label, mb in (("whole", None), ("10x1000", 1000)):
+        w = R.Workload(cfg, n_users=32, minibatch=mb)
+        per_user = len(w.launch) // w.n_users
+        idx = torch.empty((1, cfg.top_k), dtype=torch.int32, device="cuda")
+        val = torch.empty((1, cfg.top_k), dtype=torch.float32, device="cuda")
+        ts = []
+        for it in range(n_iter + 20):
+            u = it % w.n_users
+            reqs = [d.req for d in w.launch[u * per_user:(u + 1) * per_user]]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            w.ctx.aif_score_batch(reqs)
+            w.ctx.aif_topk([w.dev[u].logits], cfg.top_k, idx, val)
+            torch.cuda.synchronize()
+            if it >= 20:
+                ts.append((time.perf_counter() - t0) * 1e3)
+        ts = np.sort(np.array(ts))
+        out[label] = {"p50_ms": float(ts[len(ts) // 2]), "p99_ms": float(ts[int(len(ts) * 0.99)])}
+        del w
+        torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-latency", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (requests shard by user with no exchange; "
+                 "see DESIGN.md); run with --gpus 1")
+
+    import torch
+
+    from paper_2511_12934_amd import runner as R
+    from paper_2511_12934_amd import workloads as wl
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    cfg = wl.CONFIGS[args.workload]
+    w = R.Workload(cfg)
+    for _ in range(args.warmup):
+        w.step()
+    torch.cuda.synchronize()
+
+    w.ctx.aif_profile_begin(args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        w.step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = w.ctx.aif_profile_end()
+    ms_per_step = elapsed / args.steps * 1e3
+    value = w.total_candidates * args.steps / elapsed
+
+    work = algorithmic_work(cfg)
+    cands = w.total_candidates
+    kernels = {}
+    for stage in ("gather", "attention", "mlp", "topk"):
+        ms, n = prof[stage]
+        avg_ms = ms / max(n, 1)
+        ent = {"avg_ms": avg_ms, "kind": "mfma" if w.ctx.aif_stage_kind(stage) == 1 else "generic"}
+        wk = work[stage]
+        if "flops" in wk and avg_ms > 0:
+            ent["tflops"] = wk["flops"] * cands / (avg_ms * 1e-3) / 1e12
+        if avg_ms > 0:
+            ent["gbs"] = wk["bytes"] * cands / (avg_ms * 1e-3) / 1e9
+        kernels[stage] = ent
+    dom = max(("gather", "attention", "mlp"), key=lambda s: kernels[s]["avg_ms"])
+    if dom == "gather":
+        roof = {"kernel": "k_gather", "bound": "hbm", "achieved": kernels[dom]["gbs"], "peak": PEAK_HBM_GBS,
+                "unit": "GB/s"}
+    else:
+        mf = cfg.dtype == "bf16" and kernels[dom]["kind"] == "mfma"
+        roof = {"kernel": dom, "bound": "mfma" if mf else "alu", "achieved": kernels[dom]["tflops"],
+                "peak": PEAK_MFMA_BF16_TFLOPS if mf else PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["avg_ms"] = kernels[dom]["avg_ms"]
+
+    line = {
+        "metric": "candidates scored/sec/GPU at 10^4-cand requests",
+        "value": value, "unit": "candidates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {w.n_users} users x {w.n_cand} candidates, table {cfg.n_items}x{cfg.d_item} "
+                               f"{cfg.dtype}, L={cfg.seq_len}, d_attn={cfg.d_attn}, H={cfg.n_heads}, "
+                               f"MLP {list(cfg.mlp_dims)}, top-{cfg.top_k}",
+                   "users": w.n_users, "candidates_per_request": w.n_cand, "top_k": cfg.top_k},
+        "request_latency_ms": ms_per_step,
+        "roofline": roof,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, w)
+    if not args.no_latency:
+        line["single_request_latency_C2"] = single_request_latency()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

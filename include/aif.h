@@ -1,0 +1,180 @@
+/*
+ * aif.h -- C ABI of the MI355X (gfx950) real-time pre-ranking scoring library.
+ *
+ * The library computes what the Asynchronous Inference Framework (AIF,
+ * arXiv 2511.12934) leaves online, i.e. the second, real-time call of
+ * Sec. 3.1 ("Real-Time Prediction Phase"): for one user request with about
+ * 10^4 retrieved candidates (Sec. 1) it
+ *   - indexes each candidate's nearline-precomputed item vector in the index
+ *     table (Sec. 3.2),
+ *   - combines it with the request's cached user-side tensors (Sec. 3.1, 3.2),
+ *   - forms the interaction-dependent terms: a scaled dot-product attention
+ *     of the candidate over the user's behaviour sequence (operator of Eq. 3
+ *     with the candidate as the query) and the real-time half of the cross
+ *     features (Sec. 3.3),
+ *   - runs the shallow MLP head on [user | item | attention | cross] (Sec. 1),
+ *   - and selects the best k candidates (Sec. 1: about 10^4 -> about 10^2).
+ * Mini-batches (Sec. 1, "e.g., 1,000 items per batch") are the caller's
+ * choice of how many aif_request slices a candidate list is cut into; scores
+ * do not depend on the slicing.
+ *
+ * Conventions
+ *   - Plain C, no exceptions.  Every call returns an aif_status; on failure
+ *     nothing has been enqueued and aif_last_error() describes the reason.
+ *   - "DEVICE" pointers are HIP device addresses on the device that was
+ *     current at aif_score_init; "HOST" pointers are ordinary host memory
+ *     read during the call only.
+ *   - All work is enqueued on the caller's stream (hipStream_t passed as
+ *     void*, NULL = default stream) and is asynchronous; the library never
+ *     synchronises the stream.  One context serves one stream at a time.
+ *   - The library owns the context, its workspace and its repacked weight
+ *     copies (made in aif_score_init).  It borrows the item table for the
+ *     life of the context, and the request tensors until the enqueued work
+ *     has completed; it never frees caller memory.
+ *   - Calls must not be made while the stream is being captured into a HIP
+ *     graph (the calls stage descriptors through pinned memory and events).
+ */
+#ifndef AIF_H
+#define AIF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AIF_API __attribute__((visibility("default")))
+
+typedef struct aif_ctx aif_ctx;
+
+typedef enum {
+    AIF_OK = 0,
+    AIF_EINVAL = 1,   /* NULL pointer, non-positive size, unknown enum            */
+    AIF_ESHAPE = 2,   /* sizes inconsistent with each other or with the context   */
+    AIF_ENOMEM = 3,   /* host or device allocation failed                         */
+    AIF_EDEVICE = 4,  /* a HIP call failed                                        */
+    AIF_ERANGE = 5    /* a request exceeds the limits the context was sized for   */
+} aif_status;
+
+typedef enum { AIF_F32 = 0, AIF_BF16 = 1 } aif_dtype;
+
+typedef enum {
+    AIF_CROSS_NONE = 0,
+    AIF_CROSS_HADAMARD = 1, /* c = u (.) e, width d_item (Sec. 3.3)                        */
+    AIF_CROSS_SEGDOT = 2    /* c[j*S+s] = <Vc_j, e[s*d_c:(s+1)*d_c]>, S = d_item/d_c,
+                               the "n user-side vectors x item" shape of Sec. 4.1       */
+} aif_cross;
+
+/* Model and sizing.  Width rules: d_item, d_attn and the cross width must each
+ * span a multiple of 16 bytes in the storage type (4 fp32 / 8 bf16 elements);
+ * d_attn is a multiple of n_heads; without w_q, d_attn <= d_item;
+ * layer_dims[0] = d_user + d_item + d_attn + d_cross and layer_dims[n_layers] = 1. */
+typedef struct {
+    aif_dtype dtype;          /* storage type of table, user tensors and weights          */
+    int64_t n_items;          /* rows of the item table                                   */
+    int32_t d_item;           /* row width                                                */
+    int32_t d_user;           /* user vector width                                        */
+    int32_t d_attn;           /* attention width = n_heads * head width                   */
+    int32_t n_heads;
+    int32_t max_seq_len;      /* largest behaviour-sequence length of any request         */
+    aif_cross cross_mode;
+    int32_t n_cross;          /* SEGDOT: number of user-side cross vectors, else 0        */
+    int32_t d_cross_vec;      /* SEGDOT: their width (divides d_item), else 0             */
+    int32_t n_layers;         /* MLP layers, >= 1                                         */
+    const int32_t *layer_dims;/* HOST, n_layers + 1 entries [D_in, ..., 1]                */
+    int32_t max_candidates;   /* largest n_cand of one request                            */
+    int32_t max_users;        /* largest number of requests in one aif_score_batch        */
+    uint32_t flags;           /* reserved, must be 0                                      */
+} aif_config;
+
+/* Model tensors, all DEVICE, storage type = config.dtype.  The table is
+ * borrowed for the life of the context; the weights are read (and repacked)
+ * during aif_score_init only. */
+typedef struct {
+    const void *item_table;   /* [n_items, d_item] row-major                              */
+    const void *w_q;          /* [d_attn, d_item] row-major, q = W_q e; NULL: q = e[0:d_attn] */
+    const void *const *w;     /* HOST array of n_layers DEVICE ptrs, W_l [d_out, d_in] row-major, y = W x + b */
+    const void *const *b;     /* HOST array of n_layers DEVICE ptrs [d_out]; NULL array or NULL entry = zero bias */
+} aif_weights;
+
+/* One request (or one mini-batch slice of it).  Tensor pointers are DEVICE
+ * and must stay valid until the enqueued work completes. */
+typedef struct {
+    const void *user_vec;     /* [d_user]                                                 */
+    const void *cross_vecs;   /* SEGDOT: [n_cross, d_cross_vec]; HADAMARD: [d_item] or NULL = user_vec (needs d_user = d_item) */
+    const void *seq_keys;     /* [seq_len, d_attn] row-major; heads are contiguous slices  */
+    const void *seq_vals;     /* [seq_len, d_attn]; may alias seq_keys                    */
+    int32_t seq_len;          /* 0 .. max_seq_len; 0 gives a zero attention block         */
+    const int32_t *cand_ids;  /* [n_cand] table rows                                      */
+    int32_t n_cand;           /* 0 .. max_candidates                                      */
+    float *logits_out;        /* [n_cand] fp32 logits z                                   */
+    float *scores_out;        /* [n_cand] sigmoid(z), or NULL                             */
+} aif_request;
+
+/* Create a context on the current device: validates the configuration, sizes
+ * the workspace for max_users requests of max_candidates candidates, repacks
+ * the weights.  Synchronous.  *out is set only on AIF_OK. */
+AIF_API aif_status aif_score_init(const aif_config *cfg, const aif_weights *weights, aif_ctx **out);
+
+/* Score the candidates of one request: logits (and optional sigmoid scores)
+ * for every candidate, in candidate order.  Equivalent to aif_score_batch
+ * with n_req = 1. */
+AIF_API aif_status aif_score_request(aif_ctx *ctx, const aif_request *req, void *hip_stream);
+
+/* Score n_req requests (HOST array) in one pass: gather -> attention + cross
+ * -> MLP.  Each candidate's result depends only on its own row and its
+ * request's user tensors, so any slicing of a candidate list into requests
+ * yields the same numbers.  A candidate id outside [0, n_items) does not
+ * fault: its logit and score are NaN and a device counter is bumped (see
+ * aif_poll_device_errors).  Errors: AIF_EINVAL (NULL), AIF_ERANGE (n_req,
+ * n_cand or seq_len above the context's limits). */
+AIF_API aif_status aif_score_batch(aif_ctx *ctx, const aif_request *reqs, int32_t n_req, void *hip_stream);
+
+/* Per request r, the positions (0-based, within its candidate list) of the k
+ * largest logits, best first; equal logits keep the lower position first; a
+ * NaN ranks below every number.  logits: HOST array of n_req DEVICE pointers;
+ * n_cand: HOST array.  idx_out / val_out: DEVICE [n_req * k]; when
+ * k > n_cand[r] the tail is idx = -1, val = -inf.  1 <= k <= 4096. */
+AIF_API aif_status aif_topk(aif_ctx *ctx, const float *const *logits, const int32_t *n_cand, int32_t n_req,
+                    int32_t k, int32_t *idx_out, float *val_out, void *hip_stream);
+
+/* Release the context, its workspace and weight copies.  The caller must
+ * have synchronised every stream the context was used on.  NULL is a no-op. */
+AIF_API void aif_score_destroy(aif_ctx *ctx);
+
+/* Message for the last failing call on this context (never NULL); with
+ * ctx = NULL, the last failing aif_score_init of the calling thread. */
+AIF_API const char *aif_last_error(const aif_ctx *ctx);
+
+/* After the caller has synchronised the stream: number of out-of-range
+ * candidate ids seen since the last poll (the counter is reset).
+ * Synchronous device read. */
+AIF_API aif_status aif_poll_device_errors(aif_ctx *ctx, int32_t *n_bad_ids);
+
+/* Test hook: the workspace matrix [e | attention | cross] of the last batch,
+ * storage type = config.dtype, row-major with row stride *ld elements; the
+ * rows of request r start at row *(row_base + r) (HOST array owned by the
+ * context, valid until the next call).  Any out pointer may be NULL. */
+AIF_API aif_status aif_peek_features(aif_ctx *ctx, const void **x, int32_t *ld, const int32_t **row_base);
+
+/* Per-kernel timing with HIP events on the caller's stream (the service
+ * metrics of Sec. 5.1 are response times; this is their per-kernel breakdown).
+ * Between aif_profile_begin and aif_profile_end every aif_score_batch records
+ * an event before and after each of its kernels, and every aif_topk around
+ * its kernel, for at most max_calls calls of each kind (later calls are not
+ * recorded).  aif_profile_end synchronises on the recorded events and returns
+ * the summed milliseconds per stage in ms_sum[AIF_STAGE_COUNT] and the number
+ * of recorded calls per stage in n_calls[AIF_STAGE_COUNT] (both HOST). */
+enum { AIF_STAGE_GATHER = 0, AIF_STAGE_USER_FOLD = 1, AIF_STAGE_ATTENTION = 2, AIF_STAGE_MLP = 3,
+       AIF_STAGE_TOPK = 4, AIF_STAGE_COUNT = 5 };
+AIF_API aif_status aif_profile_begin(aif_ctx *ctx, int32_t max_calls);
+AIF_API aif_status aif_profile_end(aif_ctx *ctx, double *ms_sum, int32_t *n_calls);
+
+/* Which kernel family serves a stage of this context: 0 = shape-agnostic fp32
+ * kernels, 1 = bf16 MFMA kernels.  stage is one of the AIF_STAGE_* values. */
+AIF_API int32_t aif_stage_kind(const aif_ctx *ctx, int32_t stage);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AIF_H */

@@ -1,0 +1,208 @@
+"""Thin ctypes binding of ``libaif.so`` (see ``include/aif.h``).
+
+Argument marshalling only: every step of the scoring path runs in the HIP
+kernels behind the C ABI.  Tensors are torch tensors used purely as device
+memory (``data_ptr()``) and the current torch stream is the HIP stream the
+work is enqueued on.  A missing library raises; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaif.so")
+
+AIF_OK, AIF_EINVAL, AIF_ESHAPE, AIF_ENOMEM, AIF_EDEVICE, AIF_ERANGE = range(6)
+AIF_F32, AIF_BF16 = 0, 1
+AIF_CROSS_NONE, AIF_CROSS_HADAMARD, AIF_CROSS_SEGDOT = 0, 1, 2
+
+EXPORTS = ("aif_score_init", "aif_score_request", "aif_score_batch", "aif_topk", "aif_score_destroy",
+           "aif_last_error", "aif_poll_device_errors", "aif_peek_features", "aif_profile_begin",
+           "aif_profile_end", "aif_stage_kind")
+STAGES = ("gather", "user_fold", "attention", "mlp", "topk")
+
+
+class aif_config(C.Structure):
+    _fields_ = [("dtype", C.c_int), ("n_items", C.c_int64), ("d_item", C.c_int32), ("d_user", C.c_int32),
+                ("d_attn", C.c_int32), ("n_heads", C.c_int32), ("max_seq_len", C.c_int32),
+                ("cross_mode", C.c_int), ("n_cross", C.c_int32), ("d_cross_vec", C.c_int32),
+                ("n_layers", C.c_int32), ("layer_dims", C.POINTER(C.c_int32)),
+                ("max_candidates", C.c_int32), ("max_users", C.c_int32), ("flags", C.c_uint32)]
+
+
+class aif_weights(C.Structure):
+    _fields_ = [("item_table", C.c_void_p), ("w_q", C.c_void_p),
+                ("w", C.POINTER(C.c_void_p)), ("b", C.POINTER(C.c_void_p))]
+
+
+class aif_request(C.Structure):
+    _fields_ = [("user_vec", C.c_void_p), ("cross_vecs", C.c_void_p), ("seq_keys", C.c_void_p),
+                ("seq_vals", C.c_void_p), ("seq_len", C.c_int32), ("cand_ids", C.c_void_p),
+                ("n_cand", C.c_int32), ("logits_out", C.c_void_p), ("scores_out", C.c_void_p)]
+
+
+_lib = None
+
+
+def load():
+    """Load libaif.so (built by ``python -m paper_2511_12934_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_12934_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp = C.c_void_p
+    lib.aif_score_init.restype = C.c_int
+    lib.aif_score_init.argtypes = [C.POINTER(aif_config), C.POINTER(aif_weights), C.POINTER(vp)]
+    lib.aif_score_request.restype = C.c_int
+    lib.aif_score_request.argtypes = [vp, C.POINTER(aif_request), vp]
+    lib.aif_score_batch.restype = C.c_int
+    lib.aif_score_batch.argtypes = [vp, C.POINTER(aif_request), C.c_int32, vp]
+    lib.aif_topk.restype = C.c_int
+    lib.aif_topk.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_int32), C.c_int32, C.c_int32, vp, vp, vp]
+    lib.aif_score_destroy.restype = None
+    lib.aif_score_destroy.argtypes = [vp]
+    lib.aif_last_error.restype = C.c_char_p
+    lib.aif_last_error.argtypes = [vp]
+    lib.aif_poll_device_errors.restype = C.c_int
+    lib.aif_poll_device_errors.argtypes = [vp, C.POINTER(C.c_int32)]
+    lib.aif_peek_features.restype = C.c_int
+    lib.aif_peek_features.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_int32), C.POINTER(C.POINTER(C.c_int32))]
+    lib.aif_profile_begin.restype = C.c_int
+    lib.aif_profile_begin.argtypes = [vp, C.c_int32]
+    lib.aif_profile_end.restype = C.c_int
+    lib.aif_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    lib.aif_stage_kind.restype = C.c_int32
+    lib.aif_stage_kind.argtypes = [vp, C.c_int32]
+    _lib = lib
+    return lib
+
+
+class AifError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"aif status {status}: {msg}")
+        self.status = status
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> Optional[int]:
+    import torch
+    return torch.cuda.current_stream().cuda_stream or None
+
+
+class Request:
+    """Device tensors of one request (or mini-batch slice)."""
+
+    def __init__(self, user_vec, seq_keys, seq_vals, cand_ids, logits_out, scores_out=None, cross_vecs=None,
+                 seq_len: Optional[int] = None):
+        self.user_vec, self.seq_keys, self.seq_vals = user_vec, seq_keys, seq_vals
+        self.cand_ids, self.logits_out, self.scores_out, self.cross_vecs = cand_ids, logits_out, scores_out, cross_vecs
+        self.seq_len = int(seq_keys.shape[0]) if seq_len is None else int(seq_len)
+        self.n_cand = int(cand_ids.numel())
+
+    def fill(self, r: aif_request):
+        r.user_vec = _ptr(self.user_vec)
+        r.cross_vecs = _ptr(self.cross_vecs)
+        r.seq_keys = _ptr(self.seq_keys)
+        r.seq_vals = _ptr(self.seq_vals)
+        r.seq_len = self.seq_len
+        r.cand_ids = _ptr(self.cand_ids)
+        r.n_cand = self.n_cand
+        r.logits_out = _ptr(self.logits_out)
+        r.scores_out = _ptr(self.scores_out)
+
+
+def pack_requests(reqs: Sequence[Request]):
+    arr = (aif_request * max(len(reqs), 1))()
+    for i, q in enumerate(reqs):
+        q.fill(arr[i])
+    return arr
+
+
+class Context:
+    """Owns one ``aif_ctx``.  Methods carry the names of the C entry points."""
+
+    def __init__(self, *, dtype: int, table, d_user: int, d_attn: int, n_heads: int, max_seq_len: int,
+                 layer_dims: Sequence[int], weights: Sequence, biases: Optional[Sequence] = None, w_q=None,
+                 cross_mode: int = AIF_CROSS_HADAMARD, n_cross: int = 0, d_cross_vec: int = 0,
+                 max_candidates: int, max_users: int = 1, n_items: Optional[int] = None,
+                 d_item: Optional[int] = None):
+        self._lib = load()
+        self._h = C.c_void_p()
+        nl = len(layer_dims) - 1
+        dims = (C.c_int32 * (nl + 1))(*layer_dims)
+        cfg = aif_config(dtype, int(table.shape[0]) if n_items is None else n_items,
+                         int(table.shape[1]) if d_item is None else d_item, d_user, d_attn, n_heads, max_seq_len,
+                         cross_mode, n_cross, d_cross_vec, nl, dims, max_candidates, max_users, 0)
+        w_arr = (C.c_void_p * nl)(*[_ptr(w) for w in weights])
+        b_arr = None
+        if biases is not None:
+            b_arr = (C.c_void_p * nl)(*[_ptr(b) for b in biases])
+        wt = aif_weights(_ptr(table), _ptr(w_q), w_arr, b_arr)
+        self._keep = (table,)                      # the table is borrowed for the life of the context
+        st = self._lib.aif_score_init(C.byref(cfg), C.byref(wt), C.byref(self._h))
+        if st != AIF_OK:
+            self._h = C.c_void_p()
+            raise AifError(st, self._lib.aif_last_error(None).decode())
+
+    def _check(self, st: int):
+        if st != AIF_OK:
+            raise AifError(st, self._lib.aif_last_error(self._h).decode())
+
+    def aif_score_request(self, req: Request):
+        arr = pack_requests([req])
+        self._check(self._lib.aif_score_request(self._h, arr, _stream()))
+
+    def aif_score_batch(self, reqs: Sequence[Request], packed=None):
+        arr = pack_requests(reqs) if packed is None else packed
+        self._check(self._lib.aif_score_batch(self._h, arr, len(reqs), _stream()))
+
+    def aif_topk(self, logits: Sequence, k: int, idx_out, val_out, n_cand: Optional[Sequence[int]] = None):
+        n = len(logits)
+        ptrs = (C.c_void_p * max(n, 1))(*[_ptr(t) for t in logits])
+        counts = (C.c_int32 * max(n, 1))(*([int(t.numel()) for t in logits] if n_cand is None else n_cand))
+        self._check(self._lib.aif_topk(self._h, ptrs, counts, n, k, _ptr(idx_out), _ptr(val_out), _stream()))
+
+    def aif_poll_device_errors(self) -> int:
+        n = C.c_int32(0)
+        self._check(self._lib.aif_poll_device_errors(self._h, C.byref(n)))
+        return n.value
+
+    def aif_peek_features(self):
+        """(device pointer, row stride in elements, row_base list) of the last batch's [e|a|c] matrix."""
+        x = C.c_void_p()
+        ld = C.c_int32()
+        rb = C.POINTER(C.c_int32)()
+        self._check(self._lib.aif_peek_features(self._h, C.byref(x), C.byref(ld), C.byref(rb)))
+        return x.value, ld.value, rb
+
+    def aif_profile_begin(self, max_calls: int):
+        self._check(self._lib.aif_profile_begin(self._h, max_calls))
+
+    def aif_profile_end(self):
+        """{stage: (summed ms, recorded calls)}"""
+        ms = (C.c_double * len(STAGES))()
+        n = (C.c_int32 * len(STAGES))()
+        self._check(self._lib.aif_profile_end(self._h, ms, n))
+        return {s: (ms[i], n[i]) for i, s in enumerate(STAGES)}
+
+    def aif_stage_kind(self, stage: str) -> int:
+        return int(self._lib.aif_stage_kind(self._h, STAGES.index(stage)))
+
+    def close(self):
+        if self._h:
+            self._lib.aif_score_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,482 @@
+// Host side of libaif: the C ABI of include/aif.h.  Validates, sizes the
+// workspace, repacks weights once, and per call stages the request table and
+// enqueues  gather -> user fold -> attention + cross -> MLP  (and top-k) on
+// the caller's stream.
+#include "../../include/aif.h"
+#include "aif_dev.h"
+#include "k_mfma.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace aif;
+
+namespace {
+
+constexpr int NSLOT = 8;
+thread_local std::string g_init_error = "";
+
+struct DevBuf {
+    void *p = nullptr;
+    hipError_t alloc(size_t bytes)
+    {
+        if (bytes == 0) bytes = 16;
+        return hipMalloc(&p, bytes);
+    }
+    void release()
+    {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+    }
+};
+
+}  // namespace
+
+struct aif_ctx {
+    Model m{};
+    int device = 0;
+    int max_seq_len = 0, max_candidates = 0, max_users = 0;
+    const void *table = nullptr;
+
+    // repacked weights (owned)
+    DevBuf w1u;                       // fp32 [H1, d_user]
+    DevBuf wq;                        // fp32 [d_attn, d_item] (generic attention)
+    DevBuf wt[MAX_LAYERS];            // fp32 transposed [K_l, N_l] (generic MLP)
+    DevBuf bias[MAX_LAYERS];          // fp32 [N_l]
+    bool has_bias[MAX_LAYERS] = {};
+    bool has_wq = false;
+    MfmaPlan mfma{};                  // MFMA kernels' packed weights and eligibility
+
+    // workspace (owned)
+    DevBuf X;                         // [x_rows, ldx] storage type
+    DevBuf bias1;                     // fp32 [max_users, H1]
+    DevBuf bad;                       // int32 counter
+    size_t x_rows = 0;
+
+    // descriptor staging ring
+    char *h_stage = nullptr;          // pinned
+    DevBuf d_stage;
+    size_t slot_bytes = 0;
+    hipEvent_t ev[NSLOT] = {};
+    bool ev_live[NSLOT] = {};
+    int next_slot = 0;
+
+    std::vector<int32_t> row_base;    // host copy for aif_peek_features
+    std::string err;
+
+    // optional per-kernel event timing
+    bool prof_on = false;
+    int prof_max = 0, prof_batch_calls = 0, prof_topk_calls = 0;
+    std::vector<hipEvent_t> prof_batch;   // 5 events per recorded aif_score_batch
+    std::vector<hipEvent_t> prof_topk;    // 2 events per recorded aif_topk
+};
+
+namespace {
+
+aif_status fail(aif_ctx *c, aif_status st, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c)
+        c->err = buf;
+    else
+        g_init_error = buf;
+    return st;
+}
+
+#define HIP_TRY(ctxp, expr)                                                                         \
+    do {                                                                                            \
+        hipError_t e_ = (expr);                                                                     \
+        if (e_ != hipSuccess)                                                                       \
+            return fail(ctxp, e_ == hipErrorOutOfMemory ? AIF_ENOMEM : AIF_EDEVICE, "%s: %s", #expr, \
+                        hipGetErrorString(e_));                                                     \
+    } while (0)
+
+int round_up(int v, int a) { return (v + a - 1) / a * a; }
+
+void destroy(aif_ctx *c)
+{
+    if (!c) return;
+    c->w1u.release();
+    c->wq.release();
+    for (auto &b : c->wt) b.release();
+    for (auto &b : c->bias) b.release();
+    mfma_release(c->mfma);
+    c->X.release();
+    c->bias1.release();
+    c->bad.release();
+    c->d_stage.release();
+    if (c->h_stage) (void)hipHostFree(c->h_stage);
+    for (int i = 0; i < NSLOT; ++i)
+        if (c->ev[i]) (void)hipEventDestroy(c->ev[i]);
+    for (auto e : c->prof_batch) (void)hipEventDestroy(e);
+    for (auto e : c->prof_topk) (void)hipEventDestroy(e);
+    delete c;
+}
+
+// Take the next staging slot, waiting (normally not at all) for the call that
+// last used it.
+aif_status take_slot(aif_ctx *c, int *slot)
+{
+    const int s = c->next_slot;
+    c->next_slot = (s + 1) % NSLOT;
+    if (c->ev_live[s]) HIP_TRY(c, hipEventSynchronize(c->ev[s]));
+    *slot = s;
+    return AIF_OK;
+}
+
+aif_status check_device(aif_ctx *c)
+{
+    int cur = -1;
+    HIP_TRY(c, hipGetDevice(&cur));
+    if (cur != c->device) return fail(c, AIF_EDEVICE, "context belongs to device %d, current device is %d", c->device, cur);
+    return AIF_OK;
+}
+
+aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
+{
+    if (cfg->dtype != AIF_F32 && cfg->dtype != AIF_BF16) return fail(nullptr, AIF_EINVAL, "unknown dtype %d", (int)cfg->dtype);
+    if (cfg->flags != 0) return fail(nullptr, AIF_EINVAL, "flags must be 0");
+    if (cfg->n_items <= 0 || cfg->d_item <= 0 || cfg->d_user < 0 || cfg->d_attn <= 0 || cfg->n_heads <= 0 ||
+        cfg->max_seq_len < 0 || cfg->n_layers <= 0 || cfg->max_candidates <= 0 || cfg->max_users <= 0)
+        return fail(nullptr, AIF_EINVAL, "non-positive size in aif_config");
+    if (cfg->n_layers > MAX_LAYERS) return fail(nullptr, AIF_ESHAPE, "at most %d MLP layers", MAX_LAYERS);
+    if (!cfg->layer_dims || !wts->item_table || !wts->w) return fail(nullptr, AIF_EINVAL, "NULL layer_dims, item_table or w");
+    if (cfg->d_attn % cfg->n_heads) return fail(nullptr, AIF_ESHAPE, "d_attn %d is not a multiple of n_heads %d", cfg->d_attn, cfg->n_heads);
+    if (!wts->w_q && cfg->d_attn > cfg->d_item) return fail(nullptr, AIF_ESHAPE, "without w_q, d_attn must not exceed d_item");
+
+    Model &m = c->m;
+    m.dtype = (int)cfg->dtype;
+    m.n_items = cfg->n_items;
+    m.d_item = cfg->d_item;
+    m.d_user = cfg->d_user;
+    m.d_attn = cfg->d_attn;
+    m.n_heads = cfg->n_heads;
+    m.d_head = cfg->d_attn / cfg->n_heads;
+    m.cross_mode = (int)cfg->cross_mode;
+    m.n_cross = cfg->n_cross;
+    m.d_cv = cfg->d_cross_vec;
+    switch (cfg->cross_mode) {
+    case AIF_CROSS_NONE: m.d_cross = 0; break;
+    case AIF_CROSS_HADAMARD: m.d_cross = cfg->d_item; break;
+    case AIF_CROSS_SEGDOT:
+        if (cfg->n_cross <= 0 || cfg->d_cross_vec <= 0 || cfg->d_item % cfg->d_cross_vec)
+            return fail(nullptr, AIF_ESHAPE, "SEGDOT needs n_cross > 0 and d_cross_vec dividing d_item");
+        m.d_cross = cfg->n_cross * (cfg->d_item / cfg->d_cross_vec);
+        break;
+    default: return fail(nullptr, AIF_EINVAL, "unknown cross_mode %d", (int)cfg->cross_mode);
+    }
+    const int esz = m.dtype == 0 ? 4 : 2, vec = 16 / esz;
+    if (m.d_item % vec || m.d_attn % vec || m.d_cross % vec)
+        return fail(nullptr, AIF_ESHAPE, "d_item, d_attn and the cross width must be multiples of %d elements", vec);
+    m.ldx = m.d_item + m.d_attn + m.d_cross;
+    m.n_layers = cfg->n_layers;
+    for (int l = 0; l <= cfg->n_layers; ++l) {
+        m.dims[l] = cfg->layer_dims[l];
+        if (m.dims[l] <= 0) return fail(nullptr, AIF_EINVAL, "layer_dims[%d] <= 0", l);
+    }
+    if (m.dims[0] != m.d_user + m.ldx)
+        return fail(nullptr, AIF_ESHAPE, "layer_dims[0] = %d but d_user + d_item + d_attn + d_cross = %d", m.dims[0], m.d_user + m.ldx);
+    if (m.dims[m.n_layers] != 1) return fail(nullptr, AIF_ESHAPE, "the last layer must have one output");
+    m.k1 = m.dims[0] - m.d_user;
+    for (int l = 0; l < m.n_layers; ++l)
+        if (!wts->w[l]) return fail(nullptr, AIF_EINVAL, "w[%d] is NULL", l);
+    if ((uintptr_t)wts->item_table % 16) return fail(nullptr, AIF_EINVAL, "item_table must be 16-byte aligned");
+
+    c->max_seq_len = cfg->max_seq_len;
+    c->max_candidates = cfg->max_candidates;
+    c->max_users = cfg->max_users;
+    c->table = wts->item_table;
+    HIP_TRY(nullptr, hipGetDevice(&c->device));
+
+    // ---- weight copies ---------------------------------------------------
+    hipStream_t s = nullptr;
+    const int H1 = m.dims[1];
+    HIP_TRY(nullptr, c->w1u.alloc((size_t)H1 * m.d_user * 4));
+    HIP_TRY(nullptr, launch_to_f32(m.dtype, wts->w[0], H1, m.d_user, m.dims[0], 0, (float *)c->w1u.p, s));
+    for (int l = 0; l < m.n_layers; ++l) {
+        const int n_in = m.dims[l], n_out = m.dims[l + 1];
+        const int col0 = l == 0 ? m.d_user : 0, ncols = n_in - col0;
+        HIP_TRY(nullptr, c->wt[l].alloc((size_t)ncols * n_out * 4));
+        HIP_TRY(nullptr, launch_pack_transposed(m.dtype, wts->w[l], n_out, n_in, col0, ncols, (float *)c->wt[l].p, s));
+        const void *bl = wts->b ? wts->b[l] : nullptr;
+        c->has_bias[l] = bl != nullptr;
+        if (bl) {
+            HIP_TRY(nullptr, c->bias[l].alloc((size_t)n_out * 4));
+            HIP_TRY(nullptr, launch_to_f32(m.dtype, bl, 1, n_out, n_out, 0, (float *)c->bias[l].p, s));
+        }
+    }
+    c->has_wq = wts->w_q != nullptr;
+    if (c->has_wq) {
+        HIP_TRY(nullptr, c->wq.alloc((size_t)m.d_attn * m.d_item * 4));
+        HIP_TRY(nullptr, launch_to_f32(m.dtype, wts->w_q, m.d_attn, m.d_item, m.d_item, 0, (float *)c->wq.p, s));
+    }
+    HIP_TRY(nullptr, mfma_plan(m, c->max_seq_len, wts->w_q, wts->w, wts->b, c->mfma, s));
+
+    const bool attn_ok = c->mfma.attn || attn_generic_lds_bytes(m, c->max_seq_len) <= 160 * 1024;
+    const bool mlp_ok = c->mfma.mlp || mlp_generic_lds_bytes(m) <= 160 * 1024;
+    if (!attn_ok) return fail(nullptr, AIF_ESHAPE, "max_seq_len %d needs more LDS than a compute unit has", c->max_seq_len);
+    if (!mlp_ok) return fail(nullptr, AIF_ESHAPE, "MLP layers wider than the LDS budget of the generic kernel");
+
+    // ---- workspace ---------------------------------------------------------
+    c->x_rows = (size_t)c->max_users * round_up(c->max_candidates, ROW_BLOCK);
+    HIP_TRY(nullptr, c->X.alloc(c->x_rows * m.ldx * esz));
+    HIP_TRY(nullptr, c->bias1.alloc((size_t)c->max_users * H1 * 4));
+    HIP_TRY(nullptr, c->bad.alloc(4));
+    HIP_TRY(nullptr, hipMemsetAsync(c->bad.p, 0, 4, s));
+
+    const size_t n_blk_max = c->x_rows / ROW_BLOCK;
+    size_t sb = (size_t)c->max_users * sizeof(ReqDesc) + n_blk_max * sizeof(int32_t);
+    const size_t tk = (size_t)c->max_users * sizeof(TopkDesc);
+    if (tk > sb) sb = tk;
+    c->slot_bytes = (sb + 255) / 256 * 256;
+    HIP_TRY(nullptr, hipHostMalloc((void **)&c->h_stage, c->slot_bytes * NSLOT, hipHostMallocDefault));
+    HIP_TRY(nullptr, c->d_stage.alloc(c->slot_bytes * NSLOT));
+    for (int i = 0; i < NSLOT; ++i) HIP_TRY(nullptr, hipEventCreateWithFlags(&c->ev[i], hipEventDisableTiming));
+    HIP_TRY(nullptr, hipStreamSynchronize(s));
+    return AIF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+aif_status aif_score_init(const aif_config *cfg, const aif_weights *weights, aif_ctx **out)
+{
+    if (!cfg || !weights || !out) return fail(nullptr, AIF_EINVAL, "NULL argument");
+    aif_ctx *c = new (std::nothrow) aif_ctx();
+    if (!c) return fail(nullptr, AIF_ENOMEM, "out of host memory");
+    const aif_status st = init_impl(cfg, weights, c);
+    if (st != AIF_OK) {
+        destroy(c);
+        return st;
+    }
+    *out = c;
+    return AIF_OK;
+}
+
+void aif_score_destroy(aif_ctx *ctx) { destroy(ctx); }
+
+const char *aif_last_error(const aif_ctx *ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
+
+aif_status aif_score_batch(aif_ctx *c, const aif_request *reqs, int32_t n_req, void *hip_stream)
+{
+    if (!c) return AIF_EINVAL;
+    if (n_req < 0 || (n_req > 0 && !reqs)) return fail(c, AIF_EINVAL, "NULL request array or negative n_req");
+    if (n_req > c->max_users) return fail(c, AIF_ERANGE, "n_req %d exceeds max_users %d", n_req, c->max_users);
+    const Model &m = c->m;
+    for (int r = 0; r < n_req; ++r) {
+        const aif_request &q = reqs[r];
+        if (q.n_cand < 0 || q.seq_len < 0) return fail(c, AIF_EINVAL, "request %d: negative n_cand or seq_len", r);
+        if (q.n_cand > c->max_candidates) return fail(c, AIF_ERANGE, "request %d: n_cand %d exceeds max_candidates %d", r, q.n_cand, c->max_candidates);
+        if (q.seq_len > c->max_seq_len) return fail(c, AIF_ERANGE, "request %d: seq_len %d exceeds max_seq_len %d", r, q.seq_len, c->max_seq_len);
+        if ((m.d_user > 0 && !q.user_vec) || (q.seq_len > 0 && (!q.seq_keys || !q.seq_vals)) ||
+            (q.n_cand > 0 && (!q.cand_ids || !q.logits_out)))
+            return fail(c, AIF_EINVAL, "request %d: NULL tensor pointer", r);
+        if (m.cross_mode == AIF_CROSS_SEGDOT && !q.cross_vecs) return fail(c, AIF_EINVAL, "request %d: SEGDOT needs cross_vecs", r);
+        if (m.cross_mode == AIF_CROSS_HADAMARD && !q.cross_vecs && m.d_user != m.d_item)
+            return fail(c, AIF_ESHAPE, "request %d: HADAMARD without cross_vecs needs d_user == d_item", r);
+    }
+    aif_status st = check_device(c);
+    if (st != AIF_OK) return st;
+    if (n_req == 0) return AIF_OK;
+    hipStream_t s = (hipStream_t)hip_stream;
+
+    int slot;
+    st = take_slot(c, &slot);
+    if (st != AIF_OK) return st;
+    char *h = c->h_stage + (size_t)slot * c->slot_bytes;
+    char *d = (char *)c->d_stage.p + (size_t)slot * c->slot_bytes;
+    ReqDesc *hd = (ReqDesc *)h;
+    int32_t *hb = (int32_t *)(h + (size_t)n_req * sizeof(ReqDesc));
+    c->row_base.assign(n_req, 0);
+    int rows = 0;
+    for (int r = 0; r < n_req; ++r) {
+        const aif_request &q = reqs[r];
+        ReqDesc &e = hd[r];
+        e.user_vec = q.user_vec;
+        e.cross_vecs = q.cross_vecs ? q.cross_vecs : q.user_vec;
+        e.seq_keys = q.seq_keys;
+        e.seq_vals = q.seq_vals;
+        e.cand_ids = q.cand_ids;
+        e.logits_out = q.logits_out;
+        e.scores_out = q.scores_out;
+        e.seq_len = q.seq_len;
+        e.n_cand = q.n_cand;
+        e.row_base = rows;
+        e.index = r;
+        c->row_base[r] = rows;
+        const int nb = round_up(q.n_cand, ROW_BLOCK) / ROW_BLOCK;
+        for (int j = 0; j < nb; ++j) hb[rows / ROW_BLOCK + j] = r;
+        rows += nb * ROW_BLOCK;
+    }
+    Batch b;
+    b.reqs = (const ReqDesc *)d;
+    b.blk_req = (const int32_t *)(d + (size_t)n_req * sizeof(ReqDesc));
+    b.n_req = n_req;
+    b.n_blk = rows / ROW_BLOCK;
+    const size_t bytes = (size_t)n_req * sizeof(ReqDesc) + (size_t)b.n_blk * sizeof(int32_t);
+    HIP_TRY(c, hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, s));
+
+    hipEvent_t *pe = nullptr;
+    if (c->prof_on && c->prof_batch_calls < c->prof_max) pe = &c->prof_batch[(size_t)5 * c->prof_batch_calls++];
+    if (pe) HIP_TRY(c, hipEventRecord(pe[0], s));
+    HIP_TRY(c, launch_gather(m, b, c->table, c->X.p, (int32_t *)c->bad.p, s));
+    if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
+    HIP_TRY(c, launch_user_fold(m, b, (const float *)c->w1u.p, c->has_bias[0] ? (const float *)c->bias[0].p : nullptr,
+                                (float *)c->bias1.p, s));
+    if (pe) HIP_TRY(c, hipEventRecord(pe[2], s));
+    if (c->mfma.attn)
+        HIP_TRY(c, launch_attn_mfma(m, b, c->X.p, c->mfma, s));
+    else
+        HIP_TRY(c, launch_attn_generic(m, b, c->X.p, c->has_wq ? (const float *)c->wq.p : nullptr, c->max_seq_len, s));
+    if (pe) HIP_TRY(c, hipEventRecord(pe[3], s));
+    if (c->mfma.mlp)
+        HIP_TRY(c, launch_mlp_mfma(m, b, c->X.p, c->mfma, (const float *)c->bias1.p, s));
+    else {
+        MlpGenericWeights gw{};
+        for (int l = 0; l < m.n_layers; ++l) {
+            gw.wt[l] = (const float *)c->wt[l].p;
+            gw.bias[l] = c->has_bias[l] ? (const float *)c->bias[l].p : nullptr;
+        }
+        HIP_TRY(c, launch_mlp_generic(m, b, c->X.p, gw, (const float *)c->bias1.p, s));
+    }
+    if (pe) HIP_TRY(c, hipEventRecord(pe[4], s));
+    HIP_TRY(c, hipEventRecord(c->ev[slot], s));
+    c->ev_live[slot] = true;
+    return AIF_OK;
+}
+
+aif_status aif_score_request(aif_ctx *ctx, const aif_request *req, void *hip_stream)
+{
+    if (!ctx) return AIF_EINVAL;
+    if (!req) return fail(ctx, AIF_EINVAL, "NULL request");
+    return aif_score_batch(ctx, req, 1, hip_stream);
+}
+
+aif_status aif_topk(aif_ctx *c, const float *const *logits, const int32_t *n_cand, int32_t n_req, int32_t k,
+                    int32_t *idx_out, float *val_out, void *hip_stream)
+{
+    if (!c) return AIF_EINVAL;
+    if (n_req < 0 || (n_req > 0 && (!logits || !n_cand || !idx_out || !val_out)))
+        return fail(c, AIF_EINVAL, "NULL argument or negative n_req");
+    if (k <= 0) return fail(c, AIF_EINVAL, "k must be positive");
+    if (k > TOPK_MAX) return fail(c, AIF_ERANGE, "k %d exceeds %d", k, TOPK_MAX);
+    if (n_req > c->max_users) return fail(c, AIF_ERANGE, "n_req %d exceeds max_users %d", n_req, c->max_users);
+    for (int r = 0; r < n_req; ++r) {
+        if (n_cand[r] < 0) return fail(c, AIF_EINVAL, "request %d: negative n_cand", r);
+        if (n_cand[r] > 0 && !logits[r]) return fail(c, AIF_EINVAL, "request %d: NULL logits", r);
+    }
+    aif_status st = check_device(c);
+    if (st != AIF_OK) return st;
+    if (n_req == 0) return AIF_OK;
+    hipStream_t s = (hipStream_t)hip_stream;
+    int slot;
+    st = take_slot(c, &slot);
+    if (st != AIF_OK) return st;
+    TopkDesc *h = (TopkDesc *)(c->h_stage + (size_t)slot * c->slot_bytes);
+    TopkDesc *d = (TopkDesc *)((char *)c->d_stage.p + (size_t)slot * c->slot_bytes);
+    for (int r = 0; r < n_req; ++r) {
+        h[r].logits = logits[r];
+        h[r].n = n_cand[r];
+    }
+    HIP_TRY(c, hipMemcpyAsync(d, h, (size_t)n_req * sizeof(TopkDesc), hipMemcpyHostToDevice, s));
+    hipEvent_t *pe = nullptr;
+    if (c->prof_on && c->prof_topk_calls < c->prof_max) pe = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
+    if (pe) HIP_TRY(c, hipEventRecord(pe[0], s));
+    HIP_TRY(c, launch_topk(d, n_req, k, idx_out, val_out, s));
+    if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
+    HIP_TRY(c, hipEventRecord(c->ev[slot], s));
+    c->ev_live[slot] = true;
+    return AIF_OK;
+}
+
+aif_status aif_poll_device_errors(aif_ctx *c, int32_t *n_bad_ids)
+{
+    if (!c) return AIF_EINVAL;
+    if (!n_bad_ids) return fail(c, AIF_EINVAL, "NULL n_bad_ids");
+    aif_status st = check_device(c);
+    if (st != AIF_OK) return st;
+    HIP_TRY(c, hipMemcpy(n_bad_ids, c->bad.p, 4, hipMemcpyDeviceToHost));
+    HIP_TRY(c, hipMemset(c->bad.p, 0, 4));
+    return AIF_OK;
+}
+
+aif_status aif_peek_features(aif_ctx *c, const void **x, int32_t *ld, const int32_t **row_base)
+{
+    if (!c) return AIF_EINVAL;
+    if (x) *x = c->X.p;
+    if (ld) *ld = c->m.ldx;
+    if (row_base) *row_base = c->row_base.data();
+    return AIF_OK;
+}
+
+aif_status aif_profile_begin(aif_ctx *c, int32_t max_calls)
+{
+    if (!c) return AIF_EINVAL;
+    if (max_calls <= 0 || max_calls > 100000) return fail(c, AIF_EINVAL, "max_calls out of range");
+    aif_status st = check_device(c);
+    if (st != AIF_OK) return st;
+    while ((int)c->prof_batch.size() < 5 * max_calls) {
+        hipEvent_t e;
+        HIP_TRY(c, hipEventCreate(&e));
+        c->prof_batch.push_back(e);
+    }
+    while ((int)c->prof_topk.size() < 2 * max_calls) {
+        hipEvent_t e;
+        HIP_TRY(c, hipEventCreate(&e));
+        c->prof_topk.push_back(e);
+    }
+    c->prof_max = max_calls;
+    c->prof_batch_calls = c->prof_topk_calls = 0;
+    c->prof_on = true;
+    return AIF_OK;
+}
+
+aif_status aif_profile_end(aif_ctx *c, double *ms_sum, int32_t *n_calls)
+{
+    if (!c) return AIF_EINVAL;
+    if (!ms_sum || !n_calls) return fail(c, AIF_EINVAL, "NULL output");
+    c->prof_on = false;
+    for (int i = 0; i < AIF_STAGE_COUNT; ++i) {
+        ms_sum[i] = 0.0;
+        n_calls[i] = 0;
+    }
+    for (int j = 0; j < c->prof_batch_calls; ++j) {
+        hipEvent_t *pe = &c->prof_batch[(size_t)5 * j];
+        HIP_TRY(c, hipEventSynchronize(pe[4]));
+        for (int st = 0; st < 4; ++st) {
+            float ms = 0.f;
+            HIP_TRY(c, hipEventElapsedTime(&ms, pe[st], pe[st + 1]));
+            ms_sum[st] += ms;
+            n_calls[st] += 1;
+        }
+    }
+    for (int j = 0; j < c->prof_topk_calls; ++j) {
+        hipEvent_t *pe = &c->prof_topk[(size_t)2 * j];
+        HIP_TRY(c, hipEventSynchronize(pe[1]));
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, pe[0], pe[1]));
+        ms_sum[AIF_STAGE_TOPK] += ms;
+        n_calls[AIF_STAGE_TOPK] += 1;
+    }
+    c->prof_batch_calls = c->prof_topk_calls = 0;
+    return AIF_OK;
+}
+
+int32_t aif_stage_kind(const aif_ctx *c, int32_t stage)
+{
+    if (!c) return -1;
+    if (stage == AIF_STAGE_ATTENTION) return c->mfma.attn ? 1 : 0;
+    if (stage == AIF_STAGE_MLP) return c->mfma.mlp ? 1 : 0;
+    return 0;
+}
+
+}  // extern "C"

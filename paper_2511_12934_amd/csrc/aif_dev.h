@@ -1,0 +1,101 @@
+// Internal device-side types and launcher prototypes of libaif (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace aif {
+
+// Rows of the workspace handled by one scheduling block.  Every request's
+// rows start on a multiple of ROW_BLOCK, so a block never straddles requests.
+constexpr int ROW_BLOCK = 256;
+constexpr int MAX_LAYERS = 8;
+constexpr int TOPK_MAX = 4096;
+
+struct ReqDesc {
+    const void *user_vec;
+    const void *cross_vecs;     // never null when cross_mode != NONE (host substitutes user_vec)
+    const void *seq_keys;
+    const void *seq_vals;
+    const int32_t *cand_ids;
+    float *logits_out;
+    float *scores_out;          // may be null
+    int32_t seq_len;
+    int32_t n_cand;
+    int32_t row_base;           // first workspace row of this request (multiple of ROW_BLOCK)
+    int32_t index;              // position in the batch
+};
+
+// What one call hands to its kernels.
+struct Batch {
+    const ReqDesc *reqs;        // device, [n_req]
+    const int32_t *blk_req;     // device, [n_blk]: request owning each ROW_BLOCK of the workspace
+    int32_t n_req;
+    int32_t n_blk;
+};
+
+struct Model {
+    int32_t dtype;              // 0 fp32, 1 bf16
+    int64_t n_items;
+    int32_t d_item, d_user, d_attn, n_heads, d_head;
+    int32_t cross_mode, n_cross, d_cv, d_cross;
+    int32_t ldx;                // row stride of the workspace matrix [e | a | c], in elements
+    int32_t n_layers;
+    int32_t dims[MAX_LAYERS + 1];   // dims[0] = D_in
+    int32_t k1;                 // D_in - d_user: layer-1 contraction left per candidate after the user fold
+};
+
+// bf16 <-> fp32 on raw bit patterns (round to nearest even).
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float ld_f(const T *p);
+template <> __device__ __forceinline__ float ld_f<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float ld_f<uint16_t>(const uint16_t *p) { return bf2f(*p); }
+template <typename T> __device__ __forceinline__ void st_f(T *p, float v);
+template <> __device__ __forceinline__ void st_f<float>(float *p, float v) { *p = v; }
+template <> __device__ __forceinline__ void st_f<uint16_t>(uint16_t *p, float v) { *p = f2bf(v); }
+
+// ---- launchers (each enqueues on `s` and returns the launch status) -------
+
+// a1: X[row, 0:d_item] = table[id].  Bad ids read row 0 and bump *bad.
+hipError_t launch_gather(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad,
+                         hipStream_t s);
+
+// a2: per request, bias1[r, n] = b1[n] + sum_m W1[n, m] u[m] over the user columns.
+hipError_t launch_user_fold(const Model &m, const Batch &b, const float *w1u, const float *b1,
+                            float *bias1, hipStream_t s);
+
+// a3-a5, any shape, fp32 arithmetic: X[row, d_item:] = [attention | cross].
+hipError_t launch_attn_generic(const Model &m, const Batch &b, void *X, const float *wq, int max_seq_len,
+                               hipStream_t s);
+size_t attn_generic_lds_bytes(const Model &m, int max_seq_len);
+
+// a6-a7, any shape, fp32 arithmetic.  wt[l] = transposed fp32 weights [K_l, N_l].
+struct MlpGenericWeights {
+    const float *wt[MAX_LAYERS];
+    const float *bias[MAX_LAYERS];      // bias[0] unused (folded into bias1)
+};
+hipError_t launch_mlp_generic(const Model &m, const Batch &b, const void *X, const MlpGenericWeights &w,
+                              const float *bias1, hipStream_t s);
+size_t mlp_generic_lds_bytes(const Model &m);
+
+// a8: per-request radix select + sort.
+struct TopkDesc {
+    const float *logits;
+    int32_t n;
+};
+hipError_t launch_topk(const TopkDesc *descs /*device*/, int n_req, int k, int32_t *idx_out, float *val_out,
+                       hipStream_t s);
+
+// init-time repacking (device -> device, any storage type -> fp32)
+hipError_t launch_pack_transposed(int dtype, const void *w, int n_out, int n_in, int col0, int ncols,
+                                  float *wt /*[ncols, n_out]*/, hipStream_t s);
+hipError_t launch_to_f32(int dtype, const void *src, int64_t rows, int cols, int ld_src, int col0,
+                         float *dst /*[rows, cols]*/, hipStream_t s);
+
+}  // namespace aif

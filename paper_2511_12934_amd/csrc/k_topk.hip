@@ -1,0 +1,151 @@
+// a8 -- keep the best k of a request's candidates (Sec. 1: pre-ranking cuts
+// about 10^4 candidates to about 10^2).  One 1024-thread block per request.
+//
+// Logits map to order-preserving 32-bit keys (NaN -> 0, the lowest; -0 -> +0).
+// Four 8-bit radix passes over LDS histograms find the exact key T of the
+// k-th best and how many candidates with key == T are needed; a gather pass
+// takes every key > T plus the first ties in position order (block-wide
+// prefix count over contiguous position chunks), and a bitonic sort of the
+// <= 4096 selected (key, ~position) pairs in LDS orders them: key descending,
+// lower position first.  The result is a pure function of the logits.
+#include "aif_dev.h"
+
+namespace aif {
+
+constexpr int TK_THREADS = 1024;
+
+__device__ __forceinline__ uint32_t logit_key(float z)
+{
+    uint32_t u = __float_as_uint(z);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0u;        // NaN below everything
+    if (u == 0x80000000u) u = 0u;                          // -0 ties with +0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict__ descs, int k, int kpad,
+                                                     int32_t *__restrict__ idx_out, float *__restrict__ val_out)
+{
+    extern __shared__ __align__(16) unsigned long long sel[];   // [kpad]
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t wave_cnt[TK_THREADS / 64];
+    __shared__ uint32_t s_prefix, s_remaining, s_ngreater;
+
+    const int r = blockIdx.x;
+    const float *z = descs[r].logits;
+    const int n = descs[r].n;
+    const int tid = threadIdx.x;
+    const int kk = k < n ? k : n;
+    int32_t *idx_o = idx_out + (size_t)r * k;
+    float *val_o = val_out + (size_t)r * k;
+
+    for (int j = tid + kk; j < k; j += TK_THREADS) {
+        idx_o[j] = -1;
+        val_o[j] = -INFINITY;
+    }
+    if (kk == 0) return;
+
+    if (tid == 0) {
+        s_prefix = 0;
+        s_remaining = (uint32_t)kk;
+    }
+    uint32_t mask = 0;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        const uint32_t prefix = s_prefix;
+        for (int i = tid; i < n; i += TK_THREADS) {
+            const uint32_t key = logit_key(z[i]);
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t rem = s_remaining, cum = 0;
+            int bin = 255;
+            for (; bin > 0; --bin) {
+                const uint32_t h = hist[bin];
+                if (cum + h >= rem) break;
+                cum += h;
+            }
+            s_prefix = prefix | ((uint32_t)bin << shift);
+            s_remaining = rem - cum;
+        }
+        mask |= 255u << shift;
+        __syncthreads();
+    }
+    const uint32_t T = s_prefix;
+    const uint32_t n_ties = s_remaining;                  // >= 1 ties with key == T are taken
+    const uint32_t n_greater = (uint32_t)kk - n_ties;
+
+    // candidates strictly better than T: any slot in [0, n_greater)
+    if (tid == 0) s_ngreater = 0;
+    for (int j = tid; j < kpad; j += TK_THREADS) sel[j] = 0ull;
+    __syncthreads();
+
+    // ties in position order: thread t owns positions [t*chunk, (t+1)*chunk)
+    const int chunk = (n + TK_THREADS - 1) / TK_THREADS;
+    const int lo = tid * chunk;
+    const int hi = lo + chunk < n ? lo + chunk : n;
+    uint32_t my_ties = 0;
+    for (int i = lo; i < hi; ++i) {
+        const uint32_t key = logit_key(z[i]);
+        if (key > T) {
+            const uint32_t slot = atomicAdd(&s_ngreater, 1u);
+            sel[slot] = ((unsigned long long)key << 32) | (0xFFFFFFFFu - (uint32_t)i);
+        } else if (key == T)
+            ++my_ties;
+    }
+    // exclusive prefix of my_ties over the block
+    uint32_t incl = my_ties;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t v = __shfl_up(incl, o, 64);
+        if ((tid & 63) >= o) incl += v;
+    }
+    if ((tid & 63) == 63) wave_cnt[tid >> 6] = incl;
+    __syncthreads();
+    uint32_t before = incl - my_ties;
+    for (int w = 0; w < (tid >> 6); ++w) before += wave_cnt[w];
+    if (my_ties && before < n_ties) {
+        uint32_t rank = before;
+        for (int i = lo; i < hi && rank < n_ties; ++i) {
+            if (logit_key(z[i]) == T) {
+                sel[n_greater + rank] = ((unsigned long long)T << 32) | (0xFFFFFFFFu - (uint32_t)i);
+                ++rank;
+            }
+        }
+    }
+    __syncthreads();
+
+    // bitonic sort, descending, kpad a power of two; pads (0) sink to the end
+    for (int size = 2; size <= kpad; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int j = tid; j < kpad / 2; j += TK_THREADS) {
+                const int a = 2 * j - (j & (stride - 1));
+                const int bq = a + stride;
+                const bool desc = (a & size) == 0;
+                const unsigned long long va = sel[a], vb = sel[bq];
+                if ((va < vb) == desc) {
+                    sel[a] = vb;
+                    sel[bq] = va;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    for (int j = tid; j < kk; j += TK_THREADS) {
+        const uint32_t i = 0xFFFFFFFFu - (uint32_t)(sel[j] & 0xFFFFFFFFull);
+        idx_o[j] = (int32_t)i;
+        val_o[j] = z[i];
+    }
+}
+
+hipError_t launch_topk(const TopkDesc *descs, int n_req, int k, int32_t *idx_out, float *val_out, hipStream_t s)
+{
+    if (n_req == 0) return hipSuccess;
+    int kpad = 2;
+    while (kpad < k) kpad <<= 1;
+    hipLaunchKernelGGL(k_topk, dim3(n_req), dim3(TK_THREADS), (size_t)kpad * 8, s, descs, k, kpad, idx_out, val_out);
+    return hipGetLastError();
+}
+
+}  // namespace aif

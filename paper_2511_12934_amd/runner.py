@@ -1,0 +1,167 @@
+"""Host-side plumbing shared by the tests, the smoke check and the benchmark:
+moves a synthetic workload into device memory and drives the C ABI through
+``binding``.  No scoring arithmetic lives here.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+from . import binding as B
+from . import workloads as wl
+
+
+def torch_dtype(dtype: str):
+    import torch
+    return torch.float32 if dtype == "f32" else torch.bfloat16
+
+
+def to_device(a: Optional[np.ndarray], dtype: str, device="cuda:0"):
+    """float32 host array holding storage-rounded values -> device tensor of the storage type."""
+    import torch
+    if a is None:
+        return None
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device).to(torch_dtype(dtype)).contiguous()
+
+
+def from_device_f32(t) -> np.ndarray:
+    import torch
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+@dataclass
+class DeviceRequest:
+    req: B.Request
+    ids_host: np.ndarray
+    logits: object          # torch fp32 [n]
+    scores: object          # torch fp32 [n]
+    keep: tuple             # device tensors kept alive
+
+
+def upload_request(cfg: wl.Config, user: wl.User, ids: np.ndarray, device="cuda:0",
+                   with_scores: bool = True) -> DeviceRequest:
+    import torch
+    u = to_device(user.user_vec, cfg.dtype, device)
+    k = to_device(user.seq_keys, cfg.dtype, device)
+    v = to_device(user.seq_vals, cfg.dtype, device)
+    cv = to_device(user.cross_vecs, cfg.dtype, device)
+    idt = torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).to(device)
+    z = torch.full((ids.size,), float("nan"), dtype=torch.float32, device=device)
+    y = torch.full((ids.size,), float("nan"), dtype=torch.float32, device=device) if with_scores else None
+    return DeviceRequest(B.Request(u, k, v, idt, z, y, cv), np.asarray(ids, np.int32), z, y, (u, k, v, cv, idt))
+
+
+def slice_request(cfg: wl.Config, dr: DeviceRequest, lo: int, hi: int) -> DeviceRequest:
+    """A mini-batch slice [lo, hi) of a request: same user tensors, views of ids and outputs."""
+    q = dr.req
+    z = dr.logits[lo:hi]
+    y = dr.scores[lo:hi] if dr.scores is not None else None
+    ids = q.cand_ids[lo:hi]
+    return DeviceRequest(B.Request(q.user_vec, q.seq_keys, q.seq_vals, ids, z, y, q.cross_vecs, q.seq_len),
+                         dr.ids_host[lo:hi], z, y, dr.keep)
+
+
+class DeviceModel:
+    def __init__(self, cfg: wl.Config, model: wl.Model, device="cuda:0"):
+        self.weights = [to_device(w, cfg.dtype, device) for w in model.weights]
+        self.biases = [to_device(b, cfg.dtype, device) for b in model.biases]
+        self.w_q = to_device(model.w_q, cfg.dtype, device)
+
+
+def make_context(cfg: wl.Config, dmodel: DeviceModel, table_dev, *, max_users: Optional[int] = None,
+                 max_candidates: Optional[int] = None, max_seq_len: Optional[int] = None,
+                 with_biases: bool = True) -> B.Context:
+    return B.Context(dtype=B.AIF_F32 if cfg.dtype == "f32" else B.AIF_BF16, table=table_dev,
+                     d_user=cfg.d_user, d_attn=cfg.d_attn, n_heads=cfg.n_heads,
+                     max_seq_len=cfg.seq_len if max_seq_len is None else max_seq_len,
+                     layer_dims=list(cfg.mlp_dims), weights=dmodel.weights,
+                     biases=dmodel.biases if with_biases else None, w_q=dmodel.w_q,
+                     cross_mode=cfg.cross_mode, n_cross=cfg.n_cross, d_cross_vec=cfg.d_cross_vec,
+                     max_candidates=cfg.n_cand if max_candidates is None else max_candidates,
+                     max_users=cfg.n_users if max_users is None else max_users)
+
+
+_hip = None
+
+
+def _hiprt():
+    global _hip
+    if _hip is None:
+        _hip = C.CDLL("libamdhip64.so")
+        _hip.hipMemcpy.restype = C.c_int
+        _hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+    return _hip
+
+
+def peek_features(ctx: B.Context, cfg: wl.Config, req_index: int, n_rows: int) -> np.ndarray:
+    """Rows of the workspace matrix [e | attention | cross] of request ``req_index`` as float32."""
+    import torch
+    torch.cuda.synchronize()
+    ptr, ld, rb = ctx.aif_peek_features()
+    esz = 4 if cfg.dtype == "f32" else 2
+    base = rb[req_index]
+    host = np.empty(n_rows * ld * esz, dtype=np.uint8)
+    rc = _hiprt().hipMemcpy(host.ctypes.data, ptr + base * ld * esz, host.size, 2)
+    if rc != 0:
+        raise RuntimeError(f"hipMemcpy failed: {rc}")
+    if cfg.dtype == "f32":
+        return host.view(np.float32).reshape(n_rows, ld).copy()
+    return wl.bf16_to_f32(host.view(np.uint16)).reshape(n_rows, ld)
+
+
+class Workload:
+    """One configuration resident on the device, in the launch configuration the
+    benchmark times: ``step()`` = aif_score_batch over all users + aif_topk."""
+
+    def __init__(self, cfg: wl.Config, device="cuda:0", n_users: Optional[int] = None,
+                 n_cand: Optional[int] = None, n_items: Optional[int] = None, host_table: bool = False,
+                 minibatch: Optional[int] = None):
+        import torch
+        self.cfg = cfg
+        self.torch = torch
+        self.n_users = cfg.n_users if n_users is None else n_users
+        self.n_cand = cfg.n_cand if n_cand is None else n_cand
+        self.n_items = cfg.n_items if n_items is None else n_items
+        self.model = wl.make_model(cfg)
+        self.dmodel = DeviceModel(cfg, self.model, device)
+        if host_table:
+            rng = np.random.default_rng(cfg.seed)
+            self.table_host = wl.make_table_host(cfg, rng, self.n_items)
+            self.table = to_device(self.table_host, cfg.dtype, device)
+        else:
+            self.table_host = None
+            self.table = wl.make_table_device(cfg, device, self.n_items)
+        self.requests = wl.make_requests(cfg, self.n_users, self.n_cand, self.n_items)
+        self.dev = [upload_request(cfg, r.user, r.ids, device) for r in self.requests]
+        # the launch list: whole requests, or each cut into mini-batches
+        self.launch: List[DeviceRequest] = []
+        for d in self.dev:
+            if minibatch:
+                self.launch += [slice_request(cfg, d, lo, min(lo + minibatch, self.n_cand))
+                                for lo in range(0, self.n_cand, minibatch)]
+            else:
+                self.launch.append(d)
+        self.ctx = make_context(cfg, self.dmodel, self.table, max_users=len(self.launch),
+                                max_candidates=max(d.ids_host.size for d in self.launch))
+        self.packed = B.pack_requests([d.req for d in self.launch])
+        self.k = cfg.top_k
+        self.idx = torch.empty((self.n_users, self.k), dtype=torch.int32, device=device)
+        self.val = torch.empty((self.n_users, self.k), dtype=torch.float32, device=device)
+        self._logits = [d.logits for d in self.dev]
+
+    @property
+    def total_candidates(self) -> int:
+        return self.n_users * self.n_cand
+
+    def step(self):
+        self.ctx.aif_score_batch(self.launch, packed=self.packed)
+        self.ctx.aif_topk(self._logits, self.k, self.idx, self.val)
+
+    def rows_of(self, user: int, positions: np.ndarray) -> np.ndarray:
+        """Item rows of some candidates of a user, fetched with torch indexing (not the library)."""
+        import torch
+        ids = torch.from_numpy(self.requests[user].ids[positions].astype(np.int64)).to(self.table.device)
+        return from_device_f32(self.table.index_select(0, ids))

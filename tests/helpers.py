@@ -1,0 +1,88 @@
+"""Shared by the GPU parity tests: oracle calls and the tolerance rules."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+from paper_2511_12934_amd import workloads as wl
+
+# Tolerances (the benchmark spec): fp32 logits within 1e-5 relative -- relative to
+# max(|z|, rms of the request's logits) so that logits near zero are judged on
+# the scale of the request; bf16 logits within 2e-2 absolute.
+F32_REL = 1e-5
+BF16_ABS = 2e-2
+
+
+def oracle_scores(cfg: wl.Config, model: wl.Model, table: np.ndarray, user: wl.User,
+                  ids: np.ndarray, n_threads: int = 8) -> oracle.Scores:
+    """Oracle on a host table indexed by ``ids``."""
+    return oracle.score(table=table, ids=ids, user_vec=user.user_vec, seq_keys=user.seq_keys,
+                        seq_vals=user.seq_vals, dims=model.dims, weights=model.weights, biases=model.biases,
+                        w_q=model.w_q, n_heads=cfg.n_heads, cross_mode=cfg.cross_mode,
+                        cross_vecs=user.cross_vecs, n_threads=n_threads)
+
+
+def oracle_scores_rows(cfg, model, rows, user, n_threads: int = 8) -> oracle.Scores:
+    """Oracle on explicit item rows (one per candidate)."""
+    ids = np.arange(rows.shape[0], dtype=np.int32)
+    return oracle.score(table=rows, ids=ids, user_vec=user.user_vec, seq_keys=user.seq_keys,
+                        seq_vals=user.seq_vals, dims=model.dims, weights=model.weights, biases=model.biases,
+                        w_q=model.w_q, n_heads=cfg.n_heads, cross_mode=cfg.cross_mode,
+                        cross_vecs=user.cross_vecs, n_threads=n_threads)
+
+
+def logit_tolerance(dtype: str, z_ref: np.ndarray) -> np.ndarray:
+    if dtype == "f32":
+        rms = float(np.sqrt(np.mean(np.square(z_ref)))) if z_ref.size else 0.0
+        return F32_REL * np.maximum(np.abs(z_ref), rms)
+    return np.full(z_ref.shape, BF16_ABS)
+
+
+def assert_logits_close(dtype: str, z_gpu: np.ndarray, z_ref: np.ndarray, what: str = ""):
+    assert z_gpu.shape == z_ref.shape, (z_gpu.shape, z_ref.shape)
+    assert np.all(np.isfinite(z_gpu)), f"{what}: non-finite GPU logits"
+    tol = logit_tolerance(dtype, z_ref)
+    err = np.abs(z_gpu.astype(np.float64) - z_ref)
+    worst = int(np.argmax(err - tol)) if err.size else 0
+    assert np.all(err <= tol), (f"{what}: logit {worst}: gpu {z_gpu[worst]!r} oracle {z_ref[worst]!r} "
+                                f"err {err[worst]:.3e} tol {tol[worst]:.3e}")
+
+
+def feature_tolerance(dtype: str, ref: np.ndarray) -> np.ndarray:
+    """Attention / cross blocks of the workspace.  fp32: 1e-5 of the block's
+    scale.  bf16: the block is stored in bf16 (rounding 2^-9 relative) after
+    fp32 accumulation of bf16-rounded softmax weights (2^-9 relative each):
+    2^-7 of the scale bounds both with margin."""
+    scale = np.maximum(np.abs(ref), float(np.sqrt(np.mean(np.square(ref)))) if ref.size else 0.0)
+    return (2e-5 if dtype == "f32" else 2.0 ** -7) * scale + 1e-30
+
+
+def assert_features_close(dtype: str, got: np.ndarray, ref: np.ndarray, what: str):
+    tol = feature_tolerance(dtype, ref)
+    err = np.abs(got.astype(np.float64) - ref)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite"
+    w = np.unravel_index(int(np.argmax(err - tol)), err.shape) if err.size else ()
+    assert np.all(err <= tol), f"{what}: worst at {w}: got {got[w]!r} ref {ref[w]!r} tol {tol[w]:.3e}"
+
+
+def check_topk_against_oracle_logits(dtype: str, idx_gpu: np.ndarray, z_ref: np.ndarray, k: int):
+    """End-to-end top-k against the oracle's logits, tolerance-aware: every
+    returned position has oracle z >= z_(k) - 2 tol; every position with
+    oracle z > z_(k) + 2 tol is returned; where the gap between ranks k and
+    k+1 exceeds 2 tol the sets are identical."""
+    n = z_ref.size
+    kk = min(k, n)
+    assert np.all(idx_gpu[kk:] == -1)
+    got = idx_gpu[:kk]
+    assert len(set(got.tolist())) == kk and got.min() >= 0 and got.max() < n
+    order = np.argsort(-z_ref, kind="stable")
+    zk = z_ref[order[kk - 1]]
+    tol = float(np.max(logit_tolerance(dtype, z_ref)))
+    assert np.all(z_ref[got] >= zk - 2 * tol)
+    must = set(np.nonzero(z_ref > zk + 2 * tol)[0].tolist())
+    assert must.issubset(set(got.tolist()))
+    if kk < n and zk - z_ref[order[kk]] > 2 * tol:
+        assert set(got.tolist()) == set(order[:kk].tolist())
+    # order agrees wherever adjacent oracle gaps exceed 2 tol
+    zr = z_ref[got]
+    assert np.all(zr[:-1] - zr[1:] >= -2 * tol)

@@ -1,0 +1,355 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the
+same seeded inputs, element by element."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_12934_amd import workloads as wl
+
+from helpers import (assert_features_close, assert_logits_close, check_topk_against_oracle_logits,
+                     oracle_scores, oracle_scores_rows)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+@pytest.fixture(scope="module")
+def R():
+    from paper_2511_12934_amd import runner
+    return runner
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    return torch
+
+
+def run_batch(R, torch, cfg, model, table_dev, users_ids, *, ctx=None, k=None, max_seq_len=None):
+    """Score a list of (user, ids) requests in one aif_score_batch; returns per-request logits,
+    scores, the device requests and the context."""
+    dm = R.DeviceModel(cfg, model)
+    own = ctx is None
+    if own:
+        ctx = R.make_context(cfg, dm, table_dev, max_users=max(len(users_ids), 1),
+                             max_candidates=max([len(i) for _, i in users_ids] + [1]),
+                             max_seq_len=max([u.seq_keys.shape[0] for u, _ in users_ids] + [1])
+                             if max_seq_len is None else max_seq_len)
+    drs = [R.upload_request(cfg, u, ids) for u, ids in users_ids]
+    ctx.aif_score_batch([d.req for d in drs])
+    torch.cuda.synchronize()
+    return [d.logits.cpu().numpy() for d in drs], [d.scores.cpu().numpy() for d in drs], drs, ctx
+
+
+def small_cfg(dtype="f32", **kw):
+    base = dict(name="S", index=8, dtype=dtype, n_users=1, n_cand=40, n_items=300, d_item=16,
+                id_dist="uniform", seq_len=9, d_attn=8, n_heads=1, use_wq=False,
+                cross_mode=wl.CROSS_HADAMARD, n_cross=0, d_cross_vec=0, d_user=16,
+                mlp_dims=(56, 24, 12, 1), top_k=5)
+    base.update(kw)
+    c = wl.Config(**base)
+    assert c.d_in == c.mlp_dims[0], c.d_in
+    return c
+
+
+# ---------------------------------------------------------------------------
+# configuration 1, full size, fp32: every output element by element
+# ---------------------------------------------------------------------------
+def test_c1_fp32_whole_request(R, torch):
+    cfg = wl.CONFIGS["C1"]
+    _say("C1 fp32 1x1000 whole request")
+    rng = np.random.default_rng(cfg.seed)
+    model = wl.make_model(cfg)
+    table = wl.make_table_host(cfg, rng)
+    req = wl.make_requests(cfg)[0]
+    table_dev = R.to_device(table, cfg.dtype)
+    (z,), (y,), drs, ctx = run_batch(R, torch, cfg, model, table_dev, [(req.user, req.ids)])
+    ref = oracle_scores(cfg, model, table, req.user, req.ids)
+
+    X = R.peek_features(ctx, cfg, 0, cfg.n_cand)
+    assert np.array_equal(X[:, :cfg.d_item], table[req.ids]), "gather is not an exact row copy"
+    assert_features_close("f32", X[:, cfg.d_item:cfg.d_item + cfg.d_attn], ref.attn, "attention")
+    assert_features_close("f32", X[:, cfg.d_item + cfg.d_attn:], ref.cross, "cross")
+    assert_logits_close("f32", z, ref.logits, "C1")
+    assert np.allclose(y, ref.scores, rtol=1e-5, atol=1e-7)
+
+    idx = torch.empty(cfg.top_k, dtype=torch.int32, device="cuda")
+    val = torch.empty(cfg.top_k, dtype=torch.float32, device="cuda")
+    ctx.aif_topk([drs[0].logits], cfg.top_k, idx, val)
+    torch.cuda.synchronize()
+    oi, ov = oracle.topk(z.astype(np.float64), cfg.top_k)        # K4 alone, on the GPU's own logits
+    assert np.array_equal(idx.cpu().numpy(), oi)
+    assert np.array_equal(val.cpu().numpy().astype(np.float64), ov)
+    check_topk_against_oracle_logits("f32", idx.cpu().numpy(), ref.logits, cfg.top_k)
+    assert ctx.aif_poll_device_errors() == 0
+
+
+def test_c1_minibatch_split_is_bitwise_on_gpu(R, torch):
+    cfg = wl.CONFIGS["C1"]
+    _say("C1 mini-batch invariance 1x1000 vs 10x100 vs ragged")
+    rng = np.random.default_rng(cfg.seed)
+    model = wl.make_model(cfg)
+    table_dev = R.to_device(wl.make_table_host(cfg, rng), cfg.dtype)
+    req = wl.make_requests(cfg)[0]
+    dm = R.DeviceModel(cfg, model)
+    ctx = R.make_context(cfg, dm, table_dev, max_users=16, max_candidates=1000)
+    whole = R.upload_request(cfg, req.user, req.ids)
+    ctx.aif_score_request(whole.req)
+    torch.cuda.synchronize()
+    z0 = whole.logits.cpu().numpy().copy()
+    for cuts in ([0, 100, 200, 300, 400, 500, 600, 700, 800, 900, 1000], [0, 1, 17, 256, 257, 777, 1000]):
+        whole.logits.fill_(float("nan"))
+        parts = [R.slice_request(cfg, whole, lo, hi) for lo, hi in zip(cuts[:-1], cuts[1:])]
+        ctx.aif_score_batch([p.req for p in parts])
+        torch.cuda.synchronize()
+        assert np.array_equal(whole.logits.cpu().numpy(), z0), cuts
+    # determinism: the same call twice
+    ctx.aif_score_request(whole.req)
+    torch.cuda.synchronize()
+    assert np.array_equal(whole.logits.cpu().numpy(), z0)
+
+
+# ---------------------------------------------------------------------------
+# configuration 2, full size, bf16: whole and as ten 1,000-item mini-batches
+# ---------------------------------------------------------------------------
+def test_c2_bf16_whole_and_minibatched(R, torch):
+    cfg = wl.CONFIGS["C2"]
+    _say("C2 bf16 1x10000, whole and 10x1000")
+    rng = np.random.default_rng(cfg.seed)
+    model = wl.make_model(cfg)
+    table = wl.make_table_host(cfg, rng)
+    req = wl.make_requests(cfg)[0]
+    table_dev = R.to_device(table, cfg.dtype)
+    dm = R.DeviceModel(cfg, model)
+    ctx = R.make_context(cfg, dm, table_dev, max_users=10, max_candidates=cfg.n_cand)
+    whole = R.upload_request(cfg, req.user, req.ids)
+    ctx.aif_score_request(whole.req)
+    torch.cuda.synchronize()
+    z = whole.logits.cpu().numpy().copy()
+    ref = oracle_scores(cfg, model, table, req.user, req.ids)
+    X = R.peek_features(ctx, cfg, 0, cfg.n_cand)
+    assert np.array_equal(X[:, :cfg.d_item], table[req.ids])
+    assert_features_close("bf16", X[:, cfg.d_item:cfg.d_item + cfg.d_attn], ref.attn, "attention")
+    assert_features_close("bf16", X[:, cfg.d_item + cfg.d_attn:], ref.cross, "cross")
+    assert_logits_close("bf16", z, ref.logits, "C2 whole")
+    # the error actually seen is far inside the 2e-2 bar; keep an eye on it
+    assert np.abs(z - ref.logits).max() < 5e-3
+
+    whole.logits.fill_(float("nan"))
+    parts = [R.slice_request(cfg, whole, lo, lo + 1000) for lo in range(0, cfg.n_cand, 1000)]
+    ctx.aif_score_batch([p.req for p in parts])
+    torch.cuda.synchronize()
+    assert np.array_equal(whole.logits.cpu().numpy(), z), "mini-batched scores differ from whole-request scores"
+
+    idx = torch.empty(cfg.top_k, dtype=torch.int32, device="cuda")
+    val = torch.empty(cfg.top_k, dtype=torch.float32, device="cuda")
+    ctx.aif_topk([whole.logits], cfg.top_k, idx, val)
+    torch.cuda.synchronize()
+    oi, ov = oracle.topk(z.astype(np.float64), cfg.top_k)
+    assert np.array_equal(idx.cpu().numpy(), oi)
+    assert np.array_equal(val.cpu().numpy().astype(np.float64), ov)
+    check_topk_against_oracle_logits("bf16", idx.cpu().numpy(), ref.logits, cfg.top_k)
+
+
+# ---------------------------------------------------------------------------
+# small shapes: ragged tails, several users, heads, W_q, both cross modes
+# ---------------------------------------------------------------------------
+SHAPES = {
+    "hadamard": dict(),
+    "heads_wq": dict(d_item=24, d_user=24, d_attn=16, n_heads=4, use_wq=True, seq_len=13, mlp_dims=(88, 40, 1)),
+    "segdot": dict(d_item=32, d_user=12, d_attn=16, n_heads=2, use_wq=True, seq_len=7, cross_mode=wl.CROSS_SEGDOT,
+                   n_cross=4, d_cross_vec=8, mlp_dims=(76, 32, 16, 8, 1)),
+    "nocross_1layer": dict(cross_mode=wl.CROSS_NONE, mlp_dims=(40, 1)),
+}
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", list(SHAPES))
+@pytest.mark.parametrize("sigma", [0.1, 1.0])
+def test_small_shapes_ragged_batches(R, torch, dtype, shape, sigma):
+    cfg = small_cfg(dtype, **SHAPES[shape])
+    _say(f"small {shape} {dtype} sigma={sigma}")
+    rng = np.random.default_rng(1234)
+    model = wl.make_model(cfg, seed=77, bias_scale=0.3)
+    table = wl.make_table_host(cfg, rng, sigma=sigma)
+    table_dev = R.to_device(table, cfg.dtype)
+    sampler = wl.IdSampler(cfg)
+    users_ids = []
+    for n, L in [(1, 9), (15, 1), (16, 0), (17, 5), (255, 9), (256, 3), (257, 9), (0, 4), (300, 8)]:
+        u = wl.make_user(cfg, rng, sigma=sigma, seq_len=L)
+        ids = sampler.sample(rng, n) if n <= cfg.n_items else rng.integers(0, cfg.n_items, n).astype(np.int32)
+        users_ids.append((u, ids))
+    zs, ys, drs, ctx = run_batch(R, torch, cfg, model, table_dev, users_ids, max_seq_len=9)
+    for r, ((u, ids), z, y) in enumerate(zip(users_ids, zs, ys)):
+        if ids.size == 0:
+            continue
+        ref = oracle_scores(cfg, model, table, u, ids, n_threads=1)
+        X = R.peek_features(ctx, cfg, r, ids.size)
+        assert np.array_equal(X[:, :cfg.d_item], table[ids])
+        a = X[:, cfg.d_item:cfg.d_item + cfg.d_attn]
+        c = X[:, cfg.d_item + cfg.d_attn:]
+        assert_features_close(dtype, a, ref.attn, f"req {r} attention")
+        if cfg.d_cross:
+            assert_features_close(dtype, c, ref.cross, f"req {r} cross")
+        if dtype == "f32":
+            assert_logits_close("f32", z, ref.logits, f"req {r}")
+        else:
+            # inputs far above the configurations' scale: judge bf16 logits
+            # relative to the request's scale (2e-2 absolute is for N(0,0.1))
+            scale = max(1.0, float(np.abs(ref.logits).max()))
+            assert np.abs(z - ref.logits).max() <= 2e-2 * scale, f"req {r}"
+        assert np.allclose(y, ref.scores, atol=1e-2 if dtype == "bf16" else 1e-6)
+
+
+def test_large_scores_do_not_overflow(R, torch):
+    """|score| far beyond the fp32 exp range: softmax must subtract its maximum."""
+    cfg = small_cfg("f32", d_item=32, d_user=32, d_attn=32, seq_len=33, mlp_dims=(128, 16, 1))
+    _say("large scores fp32")
+    rng = np.random.default_rng(5)
+    model = wl.make_model(cfg, seed=3)
+    table = wl.make_table_host(cfg, rng, sigma=30.0)
+    u = wl.make_user(cfg, rng, sigma=30.0)
+    ids = wl.IdSampler(cfg).sample(rng, 64)
+    (z,), _, drs, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "f32"), [(u, ids)])
+    ref = oracle_scores(cfg, model, table, u, ids)
+    X = R.peek_features(ctx, cfg, 0, ids.size)
+    a = X[:, cfg.d_item:cfg.d_item + cfg.d_attn]
+    assert np.all(np.isfinite(a))
+    # scores are ~ +-5000: fp32 rounding of the score itself (ulp ~ 5e-4) moves
+    # the weights, so compare with a tolerance on the dominant-key structure
+    assert np.abs(a - ref.attn).max() <= 2e-2 * np.abs(ref.attn).max()
+
+
+# ---------------------------------------------------------------------------
+# top-k alone: bit-exact against the oracle's full stable sort
+# ---------------------------------------------------------------------------
+def _topk_cases(rng):
+    n = 10_000
+    z = rng.standard_normal(n).astype(np.float32) * 0.05
+    cases = {"random": z.copy(), "equal": np.full(n, 0.25, np.float32),
+             "sorted": np.sort(z)[::-1].copy(), "reversed": np.sort(z),
+             "dups": rng.integers(0, 7, n).astype(np.float32),
+             "narrow": (0.0123 + rng.integers(0, 50, n) * 1e-9).astype(np.float32)}
+    s = z.copy()
+    s[[3, 77, 9000]] = np.inf
+    s[[5, 100, 200]] = -np.inf
+    s[[0, 9, 128, 9999]] = np.nan
+    s[[11, 12]] = [0.0, -0.0]
+    cases["special"] = s
+    cases["all_nan"] = np.full(300, np.nan, np.float32)
+    cases["tiny"] = np.array([1.0, 2.0, 2.0], np.float32)
+    cases["big"] = rng.standard_normal(20_000).astype(np.float32)
+    return cases
+
+
+@pytest.mark.parametrize("k", [1, 100, 200, 1024, 4096])
+def test_topk_equals_full_stable_sort(R, torch, k):
+    from paper_2511_12934_amd import binding as B
+    _say(f"topk k={k}")
+    rng = np.random.default_rng(99)
+    cases = _topk_cases(rng)
+    cfg = small_cfg("f32")
+    model = wl.make_model(cfg)
+    table_dev = R.to_device(wl.make_table_host(cfg, rng), "f32")
+    ctx = R.make_context(cfg, R.DeviceModel(cfg, model), table_dev, max_users=len(cases) + 1, max_candidates=64)
+    names = list(cases)
+    dev = [torch.from_numpy(cases[nm]).cuda() for nm in names]
+    dev.append(torch.empty(0, dtype=torch.float32, device="cuda"))        # an empty request
+    idx = torch.full((len(dev), k), -7, dtype=torch.int32, device="cuda")
+    val = torch.full((len(dev), k), -7.0, dtype=torch.float32, device="cuda")
+    ctx.aif_topk(dev, k, idx, val)
+    torch.cuda.synchronize()
+    idx, val = idx.cpu().numpy(), val.cpu().numpy()
+    for r, nm in enumerate(names):
+        oi, ov = oracle.topk(cases[nm].astype(np.float64), k)
+        assert np.array_equal(idx[r], oi), (nm, k)
+        assert np.array_equal(val[r].astype(np.float64), ov, equal_nan=True), (nm, k)
+    assert np.all(idx[-1] == -1) and np.all(np.isneginf(val[-1]))
+    for kk in (2, 3, 4):                                                   # k around n for the 3-element case
+        i2 = torch.empty((1, kk), dtype=torch.int32, device="cuda")
+        v2 = torch.empty((1, kk), dtype=torch.float32, device="cuda")
+        ctx.aif_topk([dev[names.index("tiny")]], kk, i2, v2)
+        torch.cuda.synchronize()
+        oi, ov = oracle.topk(cases["tiny"].astype(np.float64), kk)
+        assert np.array_equal(i2.cpu().numpy()[0], oi)
+        assert np.array_equal(v2.cpu().numpy()[0].astype(np.float64), ov)
+
+
+# ---------------------------------------------------------------------------
+# duplicates, bad ids, host-side errors
+# ---------------------------------------------------------------------------
+def test_duplicate_candidates_and_bad_ids(R, torch):
+    cfg = small_cfg("f32")
+    _say("duplicates and out-of-range ids")
+    rng = np.random.default_rng(8)
+    model = wl.make_model(cfg, seed=5, bias_scale=0.2)
+    table = wl.make_table_host(cfg, rng, sigma=1.0)
+    u = wl.make_user(cfg, rng, sigma=1.0)
+    ids = np.array([7, 3, 7, 299, 3, 7, 0], np.int32)
+    (z,), _, drs, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "f32"), [(u, ids)])
+    assert z[0] == z[2] == z[5] and z[1] == z[4]
+    ref = oracle_scores(cfg, model, table, u, ids)
+    assert_logits_close("f32", z, ref.logits)
+    idx = torch.empty(7, dtype=torch.int32, device="cuda")
+    val = torch.empty(7, dtype=torch.float32, device="cuda")
+    ctx.aif_topk([drs[0].logits], 7, idx, val)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), oracle.topk(z.astype(np.float64), 7)[0])
+    assert ctx.aif_poll_device_errors() == 0
+
+    bad = np.array([5, -1, 300, 2, 2_000_000_000], np.int32)
+    d = R.upload_request(cfg, u, bad)
+    ctx.aif_score_request(d.req)
+    torch.cuda.synchronize()
+    zb = d.logits.cpu().numpy()
+    yb = d.scores.cpu().numpy()
+    assert np.isnan(zb[[1, 2, 4]]).all() and np.isnan(yb[[1, 2, 4]]).all()
+    good = oracle_scores(cfg, model, table, u, bad[[0, 3]])
+    assert_logits_close("f32", zb[[0, 3]], good.logits)
+    assert ctx.aif_poll_device_errors() == 3
+    assert ctx.aif_poll_device_errors() == 0
+
+
+def test_host_side_errors_enqueue_nothing(R, torch):
+    from paper_2511_12934_amd import binding as B
+    cfg = small_cfg("f32")
+    _say("host-side validation")
+    rng = np.random.default_rng(8)
+    model = wl.make_model(cfg)
+    table = wl.make_table_host(cfg, rng)
+    table_dev = R.to_device(table, "f32")
+    dm = R.DeviceModel(cfg, model)
+    ctx = R.make_context(cfg, dm, table_dev, max_users=2, max_candidates=50, max_seq_len=9)
+    u = wl.make_user(cfg, rng)
+    ok = R.upload_request(cfg, u, np.arange(10, dtype=np.int32))
+    too_many = R.upload_request(cfg, u, np.arange(51, dtype=np.int32) % 300)
+    long_seq = R.upload_request(cfg, wl.make_user(cfg, rng, seq_len=10), np.arange(4, dtype=np.int32))
+    for reqs, status in (([too_many.req], B.AIF_ERANGE), ([long_seq.req], B.AIF_ERANGE),
+                         ([ok.req, ok.req, ok.req], B.AIF_ERANGE)):
+        with pytest.raises(B.AifError) as ei:
+            ctx.aif_score_batch(reqs)
+        assert ei.value.status == status
+    torch.cuda.synchronize()
+    assert np.isnan(too_many.logits.cpu().numpy()).all()           # nothing was written
+    idx = torch.empty(4, dtype=torch.int32, device="cuda")
+    val = torch.empty(4, dtype=torch.float32, device="cuda")
+    for k, status in ((0, B.AIF_EINVAL), (4097, B.AIF_ERANGE)):
+        with pytest.raises(B.AifError) as ei:
+            ctx.aif_topk([ok.logits], k, idx, val)
+        assert ei.value.status == status
+    # bad configurations are refused by aif_score_init
+    with pytest.raises(B.AifError) as ei:
+        R.make_context(cfg.scaled(mlp_dims=(57, 24, 12, 1)), dm, table_dev)
+    assert ei.value.status == B.AIF_ESHAPE
+    with pytest.raises(B.AifError) as ei:
+        R.make_context(cfg.scaled(n_heads=3), dm, table_dev)
+    assert ei.value.status == B.AIF_ESHAPE
+    ctx.aif_score_batch([])                                           # empty batch is a no-op
+    ctx.aif_score_request(ok.req)
+    torch.cuda.synchronize()
+    assert np.isfinite(ok.logits.cpu().numpy()).all()
