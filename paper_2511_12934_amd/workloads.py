@@ -214,6 +214,8 @@ class IdSampler:
     def sample(self, rng: np.random.Generator, n: int) -> np.ndarray:
         if n > self.n_items:
             raise ValueError("more distinct candidates than table rows")
+        if n <= 0:
+            return np.zeros(0, np.int32)
         got: List[np.ndarray] = []
         seen = set()
         have = 0
