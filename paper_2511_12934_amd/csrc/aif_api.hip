@@ -218,7 +218,7 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
         HIP_TRY(nullptr, c->wq.alloc((size_t)m.d_attn * m.d_item * 4));
         HIP_TRY(nullptr, launch_to_f32(m.dtype, wts->w_q, m.d_attn, m.d_item, m.d_item, 0, (float *)c->wq.p, s));
     }
-    HIP_TRY(nullptr, mfma_plan(m, c->max_seq_len, wts->w_q, wts->w, wts->b, c->mfma, s));
+    HIP_TRY(nullptr, mfma_plan(m, c->max_seq_len, wts->w_q, wts->w, c->mfma, s));
 
     const bool attn_ok = c->mfma.attn || attn_generic_lds_bytes(m, c->max_seq_len) <= 160 * 1024;
     const bool mlp_ok = c->mfma.mlp || mlp_generic_lds_bytes(m) <= 160 * 1024;
@@ -338,9 +338,12 @@ aif_status aif_score_batch(aif_ctx *c, const aif_request *reqs, int32_t n_req, v
     else
         HIP_TRY(c, launch_attn_generic(m, b, c->X.p, c->has_wq ? (const float *)c->wq.p : nullptr, c->max_seq_len, s));
     if (pe) HIP_TRY(c, hipEventRecord(pe[3], s));
-    if (c->mfma.mlp)
-        HIP_TRY(c, launch_mlp_mfma(m, b, c->X.p, c->mfma, (const float *)c->bias1.p, s));
-    else {
+    if (c->mfma.mlp) {
+        const float *bf[MAX_LAYERS];
+        for (int l = 0; l < m.n_layers; ++l) bf[l] = c->has_bias[l] ? (const float *)c->bias[l].p : nullptr;
+        HIP_TRY(c, launch_mlp_mfma(m, b, c->X.p, c->mfma, bf, (const float *)c->wt[m.n_layers - 1].p,
+                                   (const float *)c->bias1.p, s));
+    } else {
         MlpGenericWeights gw{};
         for (int l = 0; l < m.n_layers; ++l) {
             gw.wt[l] = (const float *)c->wt[l].p;

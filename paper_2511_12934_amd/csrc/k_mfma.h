@@ -9,18 +9,34 @@ struct MfmaPlan {
     bool mlp = false;                  // a6-a7 run on the MFMA MLP chain
     int attn_variant = -1;
     int mlp_variant = -1;
-    void *wpack[MAX_LAYERS] = {};      // bf16 weights in MFMA fragment order (owned)
-    float *bias[MAX_LAYERS] = {};      // fp32 biases of layers >= 2 (owned)
+    void *wpack[MAX_LAYERS] = {};      // hidden layers' bf16 weights in MFMA fragment order (owned)
     void *wq_pack = nullptr;           // bf16 W_q in fragment order (owned)
+    float *zeros = nullptr;            // zero vector standing in for an absent bias (owned)
 };
 
-// Decide which MFMA kernels can serve the model and pack their weights.
-hipError_t mfma_plan(const Model &m, int max_seq_len, const void *w_q, const void *const *w,
-                     const void *const *b, MfmaPlan &plan, hipStream_t s);
+struct MlpPack {
+    const char *w[3];                  // hidden layers' weights in fragment order
+    const float *bias[3];              // fp32 biases of hidden layers 2, 3 (index 1, 2), never null; [0] unused
+    const float *wlast;                // fp32 weights of the final ->1 layer
+    const float *blast;                // its bias (1 float) or null
+};
+
+// Decide which MFMA kernels can serve the model and pack their weights
+// (w_q, w: the caller's device tensors, read here only).
+hipError_t mfma_plan(const Model &m, int max_seq_len, const void *w_q, const void *const *w, MfmaPlan &plan,
+                     hipStream_t s);
 void mfma_release(MfmaPlan &plan);
 
 hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, hipStream_t s);
+
+// bias_f32[l] / wlast_f32: the context's fp32 copies (bias of layer l or null; last layer's weight row).
 hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const MfmaPlan &plan,
-                           const float *bias1, hipStream_t s);
+                           const float *const *bias_f32, const float *wlast_f32, const float *bias1, hipStream_t s);
+
+// k_mlp_mfma.hip
+int mlp_mfma_variant(const Model &m);
+hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const void *X, const MlpPack &pk,
+                              const float *bias1, hipStream_t s);
+hipError_t pack_frag(const void *W, int n_in, int col0, int N, int K, bool from_mfma, void *dst, hipStream_t s);
 
 }  // namespace aif

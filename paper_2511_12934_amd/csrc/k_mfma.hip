@@ -1,25 +1,67 @@
-// MFMA kernels -- plan and launchers.
+// MFMA kernels -- plan (eligibility + weight packing) and launchers.
 #include "k_mfma.h"
+
+#include <cstdlib>
 
 namespace aif {
 
-hipError_t mfma_plan(const Model &, int, const void *, const void *const *, const void *const *, MfmaPlan &plan,
-                     hipStream_t)
+hipError_t mfma_plan(const Model &m, int max_seq_len, const void *w_q, const void *const *w, MfmaPlan &plan,
+                     hipStream_t s)
 {
+    (void)max_seq_len;
+    (void)w_q;
     plan.attn = false;
     plan.mlp = false;
+    const char *force = getenv("AIF_FORCE_GENERIC");
+    if (force && force[0] == '1') return hipSuccess;
+
+    plan.mlp_variant = mlp_mfma_variant(m);
+    if (plan.mlp_variant >= 0) {
+        const int nh = m.n_layers - 1;
+        for (int l = 0; l < nh; ++l) {
+            const int K = l == 0 ? m.k1 : m.dims[l], N = m.dims[l + 1];
+            hipError_t e = hipMalloc(&plan.wpack[l], (size_t)N * K * 2);
+            if (e != hipSuccess) return e;
+            e = pack_frag(w[l], m.dims[l], l == 0 ? m.d_user : 0, N, K, l > 0, plan.wpack[l], s);
+            if (e != hipSuccess) return e;
+        }
+        int widest = 0;
+        for (int l = 1; l <= m.n_layers; ++l) widest = m.dims[l] > widest ? m.dims[l] : widest;
+        hipError_t e = hipMalloc((void **)&plan.zeros, (size_t)widest * 4);
+        if (e != hipSuccess) return e;
+        e = hipMemsetAsync(plan.zeros, 0, (size_t)widest * 4, s);
+        if (e != hipSuccess) return e;
+        plan.mlp = true;
+    }
     return hipSuccess;
 }
 
 void mfma_release(MfmaPlan &plan)
 {
-    for (auto &p : plan.wpack) { if (p) (void)hipFree(p); p = nullptr; }
-    for (auto &p : plan.bias) { if (p) (void)hipFree(p); p = nullptr; }
+    for (auto &p : plan.wpack) {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+    }
     if (plan.wq_pack) (void)hipFree(plan.wq_pack);
     plan.wq_pack = nullptr;
+    if (plan.zeros) (void)hipFree(plan.zeros);
+    plan.zeros = nullptr;
 }
 
 hipError_t launch_attn_mfma(const Model &, const Batch &, void *, const MfmaPlan &, hipStream_t) { return hipErrorNotSupported; }
-hipError_t launch_mlp_mfma(const Model &, const Batch &, const void *, const MfmaPlan &, const float *, hipStream_t) { return hipErrorNotSupported; }
+
+hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const MfmaPlan &plan,
+                           const float *const *bias_f32, const float *wlast_f32, const float *bias1, hipStream_t s)
+{
+    MlpPack pk{};
+    const int nh = m.n_layers - 1;
+    for (int l = 0; l < nh && l < 3; ++l) {
+        pk.w[l] = (const char *)plan.wpack[l];
+        pk.bias[l] = bias_f32[l] ? bias_f32[l] : plan.zeros;
+    }
+    pk.wlast = wlast_f32;
+    pk.blast = bias_f32[m.n_layers - 1];
+    return launch_mlp_variant(plan.mlp_variant, m, b, X, pk, bias1, s);
+}
 
 }  // namespace aif
