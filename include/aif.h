@@ -98,7 +98,8 @@ typedef struct {
 } aif_weights;
 
 /* One request (or one mini-batch slice of it).  Tensor pointers are DEVICE
- * and must stay valid until the enqueued work completes. */
+ * and must stay valid until the enqueued work completes; user_vec,
+ * cross_vecs, seq_keys and seq_vals must be 16-byte aligned. */
 typedef struct {
     const void *user_vec;     /* [d_user]                                                 */
     const void *cross_vecs;   /* SEGDOT: [n_cross, d_cross_vec]; HADAMARD: [d_item] or NULL = user_vec (needs d_user = d_item) */

@@ -218,7 +218,7 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
         HIP_TRY(nullptr, c->wq.alloc((size_t)m.d_attn * m.d_item * 4));
         HIP_TRY(nullptr, launch_to_f32(m.dtype, wts->w_q, m.d_attn, m.d_item, m.d_item, 0, (float *)c->wq.p, s));
     }
-    HIP_TRY(nullptr, mfma_plan(m, c->max_seq_len, wts->w_q, wts->w, c->mfma, s));
+    HIP_TRY(nullptr, mfma_plan(m, c->max_seq_len, c->max_users, wts->w_q, wts->w, c->mfma, s));
 
     const bool attn_ok = c->mfma.attn || attn_generic_lds_bytes(m, c->max_seq_len) <= 160 * 1024;
     const bool mlp_ok = c->mfma.mlp || mlp_generic_lds_bytes(m) <= 160 * 1024;
@@ -280,6 +280,8 @@ aif_status aif_score_batch(aif_ctx *c, const aif_request *reqs, int32_t n_req, v
         if ((m.d_user > 0 && !q.user_vec) || (q.seq_len > 0 && (!q.seq_keys || !q.seq_vals)) ||
             (q.n_cand > 0 && (!q.cand_ids || !q.logits_out)))
             return fail(c, AIF_EINVAL, "request %d: NULL tensor pointer", r);
+        if (((uintptr_t)q.user_vec | (uintptr_t)q.cross_vecs | (uintptr_t)q.seq_keys | (uintptr_t)q.seq_vals) % 16)
+            return fail(c, AIF_EINVAL, "request %d: user tensors must be 16-byte aligned", r);
         if (m.cross_mode == AIF_CROSS_SEGDOT && !q.cross_vecs) return fail(c, AIF_EINVAL, "request %d: SEGDOT needs cross_vecs", r);
         if (m.cross_mode == AIF_CROSS_HADAMARD && !q.cross_vecs && m.d_user != m.d_item)
             return fail(c, AIF_ESHAPE, "request %d: HADAMARD without cross_vecs needs d_user == d_item", r);

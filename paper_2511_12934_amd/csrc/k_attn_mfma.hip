@@ -1,0 +1,296 @@
+// a3-a5 on the matrix cores -- target attention of every candidate over the
+// request's behaviour sequence, Softmax(q K^T / sqrt(d_h)) V (operator of
+// Eq. 3 with the candidate as the query), plus the real-time half of the
+// cross features (Sec. 3.3).
+//
+// Everything is formed transposed so that a lane owns ONE candidate:
+//   S^T = K q^T   (A = 32 keys x d_h, B = candidates as columns)
+//   O^T = V^T P^T (A = 32 features x 32 keys, B = the probabilities)
+// A 32x32 MFMA result leaves, in lane (candidate c, half h), the scores of keys
+// 8q + 4h + i of that candidate.  The softmax reduction over keys is therefore
+// in-lane plus one exchange between the two halves, and the sixteen
+// probabilities a lane holds are, as they stand, two k-steps of the B operand
+// of the second product -- V is stored once per request in the matching key
+// order (k_pack_kv), so P never moves between lanes or through LDS.
+//
+// The request's K and V (shared by all its candidates and mini-batches,
+// Sec. 3.1) are packed once per call into MFMA fragment order and streamed
+// through LDS, two 32-key tiles per stage, double buffered, with direct-to-LDS
+// loads; all waves of a block share them.
+//
+// Softmax is shift invariant, so instead of a running maximum (and the
+// rescaling of O it forces) each candidate subtracts the bound
+// |q| max_t |k_t| / sqrt(d_h) >= every score (Cauchy-Schwarz).  If that bound
+// is large enough to risk underflow (exponent range wider than 2^-80) the wave
+// first takes the true maximum in an extra pass over K.  Both are the exact
+// softmax up to rounding.
+#include "k_mfma.h"
+
+namespace aif {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef const void __attribute__((address_space(1))) *gptr_t;
+typedef void __attribute__((address_space(3))) *lptr_t;
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float BOUND_LIMIT = 40.f;      // exponents stay within [-80, 0]
+
+template <int NFRAG, int WAVES>
+__device__ __forceinline__ void stage_frags(const char *__restrict__ src, char *dst)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int f0 = 0; f0 < NFRAG; f0 += WAVES) {
+        const int f = f0 + wave;
+        if (NFRAG % WAVES == 0 || f < NFRAG)
+            __builtin_amdgcn_global_load_lds((gptr_t)(src + f * 1024 + lane * 16), (lptr_t)(dst + f * 1024), 16, 0, 0);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// a2 -- per request: K and V into fragment order, and max_t |k_t| per head.
+// Layout per request: chunk(head, key tile kt) = FR fragments of 1 KB at
+// ((head * nktp + kt) * FR) KB:  JS K-fragments  [lane][s] = K[32kt + lane%32][o + 16j + 8(lane/32) + s]
+// then 2*FT V-fragments (jj, ft): [lane][s] = V[32kt + 16jj + 8(s/4) + 4(lane/32) + s%4][o + 32ft + lane%32]
+// with o = head * DH; keys >= seq_len read as zero.
+// ---------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void k_pack_kv(Model m, Batch b, char *__restrict__ kvpack, size_t pack_stride,
+                                                 float *__restrict__ kmax, int nktp)
+{
+    constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32;
+    const int r = blockIdx.z, hd = blockIdx.y, st = blockIdx.x;
+    const ReqDesc *rd = b.reqs + r;
+    const int L = rd->seq_len;
+    const int nkt2 = (((L + 31) >> 5) + 1) & ~1;
+    if (2 * st >= nkt2) return;
+    const uint16_t *K = (const uint16_t *)rd->seq_keys, *V = (const uint16_t *)rd->seq_vals;
+    const int da = m.d_attn, o = hd * DH;
+    uint16_t *dst = (uint16_t *)(kvpack + (size_t)r * pack_stride + ((size_t)(hd * nktp + 2 * st) * FR) * 1024);
+    for (int e = threadIdx.x; e < 2 * FR * 512; e += 256) {
+        const int k2 = e / (FR * 512), rem = e - k2 * (FR * 512);
+        const int frag = rem >> 9, lane = (rem >> 3) & 63, s = rem & 7;
+        const int kt = 2 * st + k2;
+        uint16_t val = 0;
+        if (frag < JS) {
+            const int t = 32 * kt + (lane & 31), f = o + 16 * frag + 8 * (lane >> 5) + s;
+            if (t < L) val = K[(size_t)t * da + f];
+        } else {
+            const int fv = frag - JS, jj = fv / FT, ft = fv - jj * FT;
+            const int t = 32 * kt + 16 * jj + 8 * (s >> 2) + 4 * (lane >> 5) + (s & 3), f = o + 32 * ft + (lane & 31);
+            if (t < L) val = V[(size_t)t * da + f];
+        }
+        dst[e] = val;
+    }
+    if (threadIdx.x < 64) {
+        const int t = 64 * st + threadIdx.x;
+        float ss = 0.f;
+        if (t < L)
+            for (int f = 0; f < DH; ++f) {
+                const float v = bf2f(K[(size_t)t * da + o + f]);
+                ss += v * v;
+            }
+        float nrm = sqrtf(ss);
+#pragma unroll
+        for (int off = 32; off; off >>= 1) nrm = fmaxf(nrm, __shfl_xor(nrm, off, 64));
+        // round the bound up a little: it must dominate the fp32-accumulated score
+        if (threadIdx.x == 0) atomicMax((int *)(kmax + (size_t)r * m.n_heads + hd), __float_as_int(nrm * 1.001f));
+    }
+}
+
+__global__ void k_zero_f32(float *p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+// ---------------------------------------------------------------------------
+// attention + Hadamard cross.  One wave = 32 candidates, all heads in turn.
+// ---------------------------------------------------------------------------
+template <int DH, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, uint16_t *__restrict__ X,
+                                                         const char *__restrict__ kvpack, size_t pack_stride,
+                                                         const float *__restrict__ kmax, int nktp)
+{
+    constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32, STAGE_BYTES = 2 * FR * 1024, ROWS = WAVES * 32;
+    static_assert(ROW_BLOCK % ROWS == 0, "tile");
+    extern __shared__ __align__(16) char lds[];
+
+    const int tile = blockIdx.x;
+    const int r = b.blk_req[tile / (ROW_BLOCK / ROWS)];
+    if (r < 0) return;
+    const ReqDesc rd = b.reqs[r];
+    const int row0 = tile * ROWS;
+    const int local0 = row0 - rd.row_base;
+    if (rd.n_cand - local0 <= 0) return;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, h = lane >> 5;
+    const int L = rd.seq_len, H = m.n_heads;
+    const int nkt = (L + 31) >> 5, nst = (nkt + 1) >> 1, total = H * nst;
+    const char *pk = kvpack + (size_t)r * pack_stride;
+    const int local = local0 + wave * 32 + col;
+    const bool live = local < rd.n_cand;
+    uint16_t *xrow = X + (size_t)(row0 + wave * 32 + col) * m.ldx;
+    const bf16x8 *xrow8 = (const bf16x8 *)xrow;
+    const float c = LOG2E / sqrtf((float)DH);
+
+    if (total > 0) stage_frags<2 * FR, WAVES>(pk, lds);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    int it = 0, buf = 0;
+    for (int hd = 0; hd < H; ++hd) {
+        bf16x8 q[JS];
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < JS; ++j) {
+            q[j] = xrow8[hd * (DH / 8) + 2 * j + h];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) ss += (float)q[j][s] * (float)q[j][s];
+        }
+        ss += __shfl_xor(ss, 32, 64);
+        float mc = c * sqrtf(ss) * 1.001f * kmax[(size_t)r * H + hd];
+        if (__any(mc > BOUND_LIMIT)) {
+            // rare: take the true maximum with an extra pass over K (read straight from memory)
+            float mx = -INFINITY;
+            for (int kt = 0; kt < nkt; ++kt) {
+                const char *src = pk + ((size_t)(hd * nktp + kt) * FR) * 1024 + lane * 16;
+                f32x16 S;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) S[i] = 0.f;
+#pragma unroll
+                for (int j = 0; j < JS; ++j)
+                    S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(src + j * 1024), q[j], S, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (t < L) mx = fmaxf(mx, S[v]);
+                }
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            mc = c * mx;
+        }
+
+        f32x16 O[FT];
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[ft][i] = 0.f;
+        float l = 0.f;
+
+        for (int st = 0; st < nst; ++st) {
+            if (it + 1 < total) {
+                const int nh = (it + 1) / nst, ns = (it + 1) - nh * nst;
+                stage_frags<2 * FR, WAVES>(pk + ((size_t)(nh * nktp + 2 * ns) * FR) * 1024, lds + (buf ^ 1) * STAGE_BYTES);
+            }
+#pragma unroll
+            for (int k2 = 0; k2 < 2; ++k2) {
+                const int kt = 2 * st + k2;
+                const char *base = lds + buf * STAGE_BYTES + k2 * FR * 1024 + lane * 16;
+                f32x16 S;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) S[i] = 0.f;
+#pragma unroll
+                for (int j = 0; j < JS; ++j)
+                    S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + j * 1024), q[j], S, 0, 0, 0);
+                float p[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(fmaf(S[v], c, -mc));
+                if (32 * kt + 32 > L) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
+                        if (t >= L) p[v] = 0.f;
+                    }
+                }
+                bf16x8 P0, P1;
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    l += p[v] + p[8 + v];
+                    P0[v] = (__bf16)p[v];
+                    P1[v] = (__bf16)p[8 + v];
+                }
+#pragma unroll
+                for (int ft = 0; ft < FT; ++ft) {
+                    O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + (JS + ft) * 1024), P0, O[ft], 0, 0, 0);
+                    O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + (JS + FT + ft) * 1024), P1, O[ft], 0, 0, 0);
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            buf ^= 1;
+            ++it;
+        }
+
+        l += __shfl_xor(l, 32, 64);
+        const float inv = L > 0 ? 1.0f / l : 0.f;
+        if (live) {
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(O[ft][4 * qd + i] * inv);
+                    *(bf16x4 *)(xrow + m.d_item + hd * DH + 32 * ft + 8 * qd + 4 * h) = o4;
+                }
+        }
+    }
+
+    if (m.cross_mode == 1 && live) {
+        const bf16x8 *uc = (const bf16x8 *)rd.cross_vecs;
+        bf16x8 *xc = (bf16x8 *)(xrow + m.d_item + m.d_attn);
+        for (int pc = h; pc < m.d_item / 8; pc += 2) {
+            const bf16x8 e = xrow8[pc], u = uc[pc];
+            bf16x8 o8;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)e[s] * (float)u[s]);
+            xc[pc] = o8;
+        }
+    }
+}
+
+// ---- dispatch -----------------------------------------------------------------
+int attn_mfma_variant(const Model &m, bool has_wq)
+{
+    if (m.dtype != 1 || has_wq) return -1;
+    if (m.cross_mode != 0 && m.cross_mode != 1) return -1;
+    if (m.d_head == 64) return 0;
+    if (m.d_head == 32) return 1;
+    return -1;
+}
+
+size_t attn_pack_stride(const Model &m, int max_seq_len, int *nktp_out)
+{
+    const int nktp = ((((max_seq_len + 31) >> 5) + 1) & ~1);
+    if (nktp_out) *nktp_out = nktp;
+    return (size_t)m.n_heads * nktp * (m.d_head / 8) * 1024;
+}
+
+template <int DH, int WAVES>
+static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char *kvpack, size_t stride, float *kmax,
+                                   int nktp, hipStream_t s)
+{
+    constexpr int LDS = 2 * 2 * (DH / 8) * 1024, ROWS = WAVES * 32;
+    hipLaunchKernelGGL(k_zero_f32, dim3((b.n_req * m.n_heads + 255) / 256), dim3(256), 0, s, kmax, b.n_req * m.n_heads);
+    if (nktp > 0)
+        hipLaunchKernelGGL(k_pack_kv<DH>, dim3(nktp / 2, m.n_heads, b.n_req), dim3(256), 0, s, m, b, kvpack, stride, kmax, nktp);
+    hipLaunchKernelGGL((k_attn_mfma<DH, WAVES>), dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), LDS, s, m, b,
+                       (uint16_t *)X, (const char *)kvpack, stride, (const float *)kmax, nktp);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_variant(int variant, const Model &m, const Batch &b, void *X, char *kvpack, size_t stride,
+                               float *kmax, int nktp, hipStream_t s)
+{
+    if (b.n_blk == 0) return hipSuccess;
+    switch (variant) {
+    case 0: return launch_attn_spec<64, 8>(m, b, X, kvpack, stride, kmax, nktp, s);
+    case 1: return launch_attn_spec<32, 8>(m, b, X, kvpack, stride, kmax, nktp, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace aif

@@ -12,6 +12,10 @@ struct MfmaPlan {
     void *wpack[MAX_LAYERS] = {};      // hidden layers' bf16 weights in MFMA fragment order (owned)
     void *wq_pack = nullptr;           // bf16 W_q in fragment order (owned)
     float *zeros = nullptr;            // zero vector standing in for an absent bias (owned)
+    char *kvpack = nullptr;            // per-request K/V in fragment order (owned workspace)
+    float *kmax = nullptr;             // per request and head: max_t |k_t| (owned workspace)
+    size_t pack_stride = 0;            // bytes of kvpack per request
+    int nktp = 0;                      // key tiles per head the pack layout is sized for
 };
 
 struct MlpPack {
@@ -23,8 +27,8 @@ struct MlpPack {
 
 // Decide which MFMA kernels can serve the model and pack their weights
 // (w_q, w: the caller's device tensors, read here only).
-hipError_t mfma_plan(const Model &m, int max_seq_len, const void *w_q, const void *const *w, MfmaPlan &plan,
-                     hipStream_t s);
+hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, const void *w_q, const void *const *w,
+                     MfmaPlan &plan, hipStream_t s);
 void mfma_release(MfmaPlan &plan);
 
 hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, hipStream_t s);
@@ -38,5 +42,11 @@ int mlp_mfma_variant(const Model &m);
 hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const void *X, const MlpPack &pk,
                               const float *bias1, hipStream_t s);
 hipError_t pack_frag(const void *W, int n_in, int col0, int N, int K, bool from_mfma, void *dst, hipStream_t s);
+
+// k_attn_mfma.hip
+int attn_mfma_variant(const Model &m, bool has_wq);
+size_t attn_pack_stride(const Model &m, int max_seq_len, int *nktp_out);
+hipError_t launch_attn_variant(int variant, const Model &m, const Batch &b, void *X, char *kvpack, size_t stride,
+                               float *kmax, int nktp, hipStream_t s);
 
 }  // namespace aif

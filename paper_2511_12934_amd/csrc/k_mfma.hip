@@ -5,15 +5,23 @@
 
 namespace aif {
 
-hipError_t mfma_plan(const Model &m, int max_seq_len, const void *w_q, const void *const *w, MfmaPlan &plan,
-                     hipStream_t s)
+hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, const void *w_q, const void *const *w,
+                     MfmaPlan &plan, hipStream_t s)
 {
-    (void)max_seq_len;
-    (void)w_q;
     plan.attn = false;
     plan.mlp = false;
     const char *force = getenv("AIF_FORCE_GENERIC");
     if (force && force[0] == '1') return hipSuccess;
+
+    plan.attn_variant = attn_mfma_variant(m, w_q != nullptr);
+    if (plan.attn_variant >= 0) {
+        plan.pack_stride = attn_pack_stride(m, max_seq_len, &plan.nktp);
+        hipError_t e = hipMalloc((void **)&plan.kvpack, plan.pack_stride * max_users + 16);
+        if (e != hipSuccess) return e;
+        e = hipMalloc((void **)&plan.kmax, (size_t)max_users * m.n_heads * 4);
+        if (e != hipSuccess) return e;
+        plan.attn = true;
+    }
 
     plan.mlp_variant = mlp_mfma_variant(m);
     if (plan.mlp_variant >= 0) {
@@ -46,9 +54,16 @@ void mfma_release(MfmaPlan &plan)
     plan.wq_pack = nullptr;
     if (plan.zeros) (void)hipFree(plan.zeros);
     plan.zeros = nullptr;
+    if (plan.kvpack) (void)hipFree(plan.kvpack);
+    plan.kvpack = nullptr;
+    if (plan.kmax) (void)hipFree(plan.kmax);
+    plan.kmax = nullptr;
 }
 
-hipError_t launch_attn_mfma(const Model &, const Batch &, void *, const MfmaPlan &, hipStream_t) { return hipErrorNotSupported; }
+hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, hipStream_t s)
+{
+    return launch_attn_variant(plan.attn_variant, m, b, X, plan.kvpack, plan.pack_stride, plan.kmax, plan.nktp, s);
+}
 
 hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const MfmaPlan &plan,
                            const float *const *bias_f32, const float *wlast_f32, const float *bias1, hipStream_t s)

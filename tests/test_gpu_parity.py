@@ -206,6 +206,58 @@ def test_small_shapes_ragged_batches(R, torch, dtype, shape, sigma):
         assert np.allclose(y, ref.scores, atol=1e-2 if dtype == "bf16" else 1e-6)
 
 
+# shapes the bf16 MFMA kernels serve (attention d_head 64 / 32, the MLP chains of C2-C4), with
+# ragged sequence lengths and candidate counts, at the configurations' scale and far above it
+MFMA_SHAPES = {
+    "c3_like": dict(d_item=64, d_user=64, d_attn=64, n_heads=1, mlp_dims=(256, 512, 256, 1)),
+    "c2_like": dict(d_item=64, d_user=64, d_attn=64, n_heads=1, mlp_dims=(256, 256, 128, 1)),
+    "c4_like": dict(d_item=128, d_user=128, d_attn=128, n_heads=4, mlp_dims=(512, 256, 1)),
+}
+
+
+@pytest.mark.parametrize("shape", list(MFMA_SHAPES))
+@pytest.mark.parametrize("sigma", [0.1, 1.0, 4.0])
+def test_mfma_kernels_ragged_and_large_inputs(R, torch, shape, sigma):
+    cfg = small_cfg("bf16", n_items=5000, seq_len=200, **MFMA_SHAPES[shape])
+    _say(f"mfma {shape} sigma={sigma}")
+    rng = np.random.default_rng(4321)
+    model = wl.make_model(cfg, seed=11, bias_scale=0.2)
+    table = wl.make_table_host(cfg, rng, sigma=sigma)
+    table_dev = R.to_device(table, cfg.dtype)
+    sampler = wl.IdSampler(cfg)
+    users_ids = []
+    for n, L in [(1, 200), (31, 1), (32, 0), (33, 31), (255, 32), (256, 33), (257, 63), (700, 64), (64, 65), (300, 199)]:
+        users_ids.append((wl.make_user(cfg, rng, sigma=sigma, seq_len=L), sampler.sample(rng, n)))
+    zs, ys, drs, ctx = run_batch(R, torch, cfg, model, table_dev, users_ids, max_seq_len=200)
+    assert ctx.aif_stage_kind("attention") == 1 and ctx.aif_stage_kind("mlp") == 1, "MFMA kernels not selected"
+    for r, ((u, ids), z) in enumerate(zip(users_ids, zs)):
+        ref = oracle_scores(cfg, model, table, u, ids, n_threads=4)
+        X = R.peek_features(ctx, cfg, r, ids.size)
+        assert np.array_equal(X[:, :cfg.d_item], table[ids])
+        assert_features_close("bf16", X[:, cfg.d_item:cfg.d_item + cfg.d_attn], ref.attn, f"req {r} attention")
+        assert_features_close("bf16", X[:, cfg.d_item + cfg.d_attn:], ref.cross, f"req {r} cross")
+        if sigma == 0.1:
+            assert_logits_close("bf16", z, ref.logits, f"req {r}")
+        else:
+            scale = max(1.0, float(np.abs(ref.logits).max()))
+            assert np.abs(z - ref.logits).max() <= 2e-2 * scale, f"req {r}"
+
+
+def test_forced_generic_kernels_on_bf16_config(R, torch, monkeypatch):
+    """The shape-agnostic kernels must also serve a bf16 model the MFMA kernels cover."""
+    monkeypatch.setenv("AIF_FORCE_GENERIC", "1")
+    cfg = wl.CONFIGS["C3"].scaled(n_items=3000)
+    _say("C3 shape on the generic kernels")
+    rng = np.random.default_rng(7)
+    model = wl.make_model(cfg)
+    table = wl.make_table_host(cfg, rng, n_items=3000)
+    u = wl.make_user(cfg, rng)
+    ids = wl.IdSampler(cfg, 3000).sample(rng, 300)
+    (z,), _, drs, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), [(u, ids)])
+    assert ctx.aif_stage_kind("attention") == 0 and ctx.aif_stage_kind("mlp") == 0
+    assert_logits_close("bf16", z, oracle_scores(cfg, model, table, u, ids).logits)
+
+
 def test_large_scores_do_not_overflow(R, torch):
     """|score| far beyond the fp32 exp range: softmax must subtract its maximum."""
     cfg = small_cfg("f32", d_item=32, d_user=32, d_attn=32, seq_len=33, mlp_dims=(128, 16, 1))
