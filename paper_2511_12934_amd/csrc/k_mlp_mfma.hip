@@ -29,134 +29,162 @@ constexpr int cmax(int a, int b) { return a > b ? a : b; }
 typedef const void __attribute__((address_space(1))) *gptr_t;
 typedef void __attribute__((address_space(3))) *lptr_t;
 
-// Copy one row tile of packed weights (KS fragments of 1 KB) global -> LDS with
-// the direct-to-LDS load: a wave moves whole fragments, lane i's 16 bytes land
-// at fragment base + 16 i, no register staging.  The wave then has the loads
-// in flight; wait_stage() + a block barrier make them visible.
-template <int KS, int WAVES>
-__device__ __forceinline__ void stage_tile(const char *__restrict__ src, char *dst)
+template <int N> struct IC { static constexpr int value = N; };
+template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&f)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int f0 = 0; f0 < KS; f0 += WAVES) {
-        const int f = f0 + wave;
-        if (KS % WAVES == 0 || f < KS)
-            __builtin_amdgcn_global_load_lds((gptr_t)(src + f * 1024 + lane * 16), (lptr_t)(dst + f * 1024), 16, 0, 0);
+    if constexpr (I < N) {
+        f(IC<I>{});
+        static_for<I + 1, N>(f);
     }
 }
-__device__ __forceinline__ void wait_stage() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 __device__ __forceinline__ float relu(float x) { return __builtin_amdgcn_fmed3f(x, 0.f, __builtin_inff()); }
 
-// One hidden layer for this wave's CT column tiles.  in: KIN/16 B-fragments per
-// column tile.  !FINAL: out receives NOUT/16 fragments (ReLU, bf16).  FINAL:
-// zpart[c] += wlast . relu(h) over the features this lane holds.  sbias / swl:
-// this layer's bias and the final layer's weights, fp32 in LDS.
-template <int CT, int KIN, int NOUT, bool FINAL, int WAVES, int NEXT_KS, int BUFBYTES>
-__device__ __forceinline__ void mlp_layer(const bf16x8 (&in)[CT][KIN / 16], bf16x8 (&out)[CT][NOUT / 16],
-                                          float (&zpart)[CT], const char *__restrict__ wsrc,
-                                          const char *__restrict__ next_src, const float *sbias, const float *swl,
-                                          char *lds, int &buf)
+// Static description of the chain: hidden layer l contracts KIN(l) inputs into
+// NOUT(l) features; its weights are streamed in stages of U(l) row tiles
+// (32 features each) chosen so that every wave moves the same number of 1 KB
+// fragments per stage.
+template <int K1, int H1, int H2, int H3, int WAVES> struct Chain {
+    static constexpr int NH = H3 ? 3 : (H2 ? 2 : 1);
+    static constexpr int kin(int l) { return l == 0 ? K1 : (l == 1 ? H1 : H2); }
+    static constexpr int nout(int l) { return l == 0 ? H1 : (l == 1 ? H2 : H3); }
+    static constexpr int ks(int l) { return kin(l) / 16; }                     // fragments per row tile
+    static constexpr int unit(int l) { return ks(l) % WAVES == 0 ? 1 : ((2 * ks(l)) % WAVES == 0 ? 2 : 4); }
+    static constexpr int nstage(int l) { return nout(l) / 32 / unit(l); }
+    static constexpr int frags(int l) { return unit(l) * ks(l); }              // fragments per stage
+    static constexpr int total() { return nstage(0) + (NH > 1 ? nstage(1) : 0) + (NH > 2 ? nstage(2) : 0); }
+    static constexpr int layer_of(int i) { return i < nstage(0) ? 0 : (i < nstage(0) + nstage(1) ? 1 : 2); }
+    static constexpr int first(int l) { return l == 0 ? 0 : (l == 1 ? nstage(0) : nstage(0) + nstage(1)); }
+    static constexpr int loads(int i) { return i < total() ? frags(layer_of(i)) / WAVES : 0; }   // per wave
+    static constexpr int slot_frags() { return cmax(frags(0), cmax(NH > 1 ? frags(1) : 0, NH > 2 ? frags(2) : 0)); }
+    static constexpr int HL = NH == 1 ? H1 : (NH == 2 ? H2 : H3);              // width entering the ->1 layer
+    static constexpr int bias_floats = H1 + H2 + H3 + HL;
+    static constexpr int slots() { return (4 * slot_frags() * 1024 + 4 * bias_floats <= 160 * 1024) ? 4 : 3; }
+    static constexpr int lds_bytes() { return slots() * slot_frags() * 1024 + 4 * bias_floats; }
+    static_assert(nout(0) % (32 * unit(0)) == 0, "layer 1 width");
+    static_assert(NH < 2 || nout(1) % (32 * unit(1)) == 0, "layer 2 width");
+    static_assert(NH < 3 || nout(2) % (32 * unit(2)) == 0, "layer 3 width");
+};
+
+// Direct-to-LDS load of 16 bytes per lane: lane j's bytes land at lds_dst + 16 j
+// (lds_dst = wave-uniform LDS byte address, handed over in M0).  Written as
+// assembly so that the compiler does not see a store to LDS: with the builtin
+// it makes later LDS reads of unrelated data (the biases) wait for every
+// outstanding weight load, which defeats the prefetch distance.  Completion is
+// tracked by hand with wait_vmcnt<>() + a block barrier.
+__device__ __forceinline__ void dma16(const char *gsrc, uint32_t lds_dst)
 {
-    constexpr int KS = KIN / 16, RT = NOUT / 32, BYTES = KIN * 64;
-    const int lane = threadIdx.x & 63, h = lane >> 5;
-#pragma unroll
-    for (int r = 0; r < RT; ++r) {
-        __builtin_amdgcn_sched_barrier(0);
-        if (r + 1 < RT)
-            stage_tile<KS, WAVES>(wsrc + (size_t)(r + 1) * BYTES, lds + (buf ^ 1) * BUFBYTES);
-        else if (NEXT_KS > 0)
-            stage_tile<(NEXT_KS > 0 ? NEXT_KS : 1), WAVES>(next_src, lds + (buf ^ 1) * BUFBYTES);
+    uint32_t keep;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep)
+                 : "s"(lds_dst), "v"(gsrc)
+                 : "memory");
+}
 
-        f32x16 acc[CT];
+// Copy stage i of the weight stream global -> LDS slot: a wave moves whole 1 KB
+// fragments, no register staging.
+template <class C, int WAVES, int I>
+__device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
+{
+    if constexpr (I < C::total()) {
+        constexpr int l = C::layer_of(I), nf = C::frags(l);
+        const int lane = threadIdx.x & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const char *src = pk.w[l] + (size_t)(I - C::first(l)) * nf * 1024 + lane * 16;
+        const uint32_t dst = (uint32_t)(uintptr_t)(lptr_t)lds + (I % C::slots()) * C::slot_frags() * 1024;
 #pragma unroll
-        for (int c = 0; c < CT; ++c)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
-
-        // A fragments come from LDS in groups of G, the next group in flight
-        // while the current one feeds the matrix cores; the scheduling
-        // barriers keep the compiler from hoisting every load of the tile
-        // (which would not fit the register file next to the activations).
-        const char *w = lds + buf * BUFBYTES + lane * 16;
-        constexpr int G = 4, NG = KS / G;
-        static_assert(KS % G == 0, "k-steps per tile");
-        bf16x8 a[2][G];
-#pragma unroll
-        for (int t = 0; t < G; ++t) a[0][t] = *(const bf16x8 *)(w + t * 1024);
-#pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            if (g + 1 < NG) {
-#pragma unroll
-                for (int t = 0; t < G; ++t) a[(g + 1) & 1][t] = *(const bf16x8 *)(w + ((g + 1) * G + t) * 1024);
-            }
-#pragma unroll
-            for (int t = 0; t < G; ++t) {
-#pragma unroll
-                for (int c = 0; c < CT; ++c)
-                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[g & 1][t], in[c][g * G + t], acc[c], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        float4 bv[4], wl[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            bv[q] = *(const float4 *)(sbias + 32 * r + 8 * q + 4 * h);
-            if (FINAL) wl[q] = *(const float4 *)(swl + 32 * r + 8 * q + 4 * h);
-        }
-        if (FINAL) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                for (int c = 0; c < CT; ++c) {
-                    zpart[c] += wl[q].x * relu(acc[c][4 * q + 0] + bv[q].x) + wl[q].y * relu(acc[c][4 * q + 1] + bv[q].y) +
-                                wl[q].z * relu(acc[c][4 * q + 2] + bv[q].z) + wl[q].w * relu(acc[c][4 * q + 3] + bv[q].w);
-                }
-            }
-            // pin the partial sums here: left alone the compiler postpones the whole
-            // dot product to the end of the kernel and spills every tile's outputs
-#pragma unroll
-            for (int c = 0; c < CT; ++c) asm volatile("" : "+v"(zpart[c]));
-        } else {
-#pragma unroll
-            for (int c = 0; c < CT; ++c) {
-                bf16x8 lo, hi;
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    lo[4 * q + 0] = (__bf16)relu(acc[c][4 * q + 0] + bv[q].x);
-                    lo[4 * q + 1] = (__bf16)relu(acc[c][4 * q + 1] + bv[q].y);
-                    lo[4 * q + 2] = (__bf16)relu(acc[c][4 * q + 2] + bv[q].z);
-                    lo[4 * q + 3] = (__bf16)relu(acc[c][4 * q + 3] + bv[q].w);
-                    hi[4 * q + 0] = (__bf16)relu(acc[c][8 + 4 * q + 0] + bv[2 + q].x);
-                    hi[4 * q + 1] = (__bf16)relu(acc[c][8 + 4 * q + 1] + bv[2 + q].y);
-                    hi[4 * q + 2] = (__bf16)relu(acc[c][8 + 4 * q + 2] + bv[2 + q].z);
-                    hi[4 * q + 3] = (__bf16)relu(acc[c][8 + 4 * q + 3] + bv[2 + q].w);
-                }
-                asm volatile("" : "+v"(lo), "+v"(hi));       // convert now, keep 8 registers not 16
-                out[c][2 * r] = lo;
-                out[c][2 * r + 1] = hi;
-            }
-        }
-        wait_stage();
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);      // nothing of the next row tile moves above this point
-        buf ^= 1;
+        for (int f0 = 0; f0 < nf; f0 += WAVES) dma16(src + (f0 + wave) * 1024, dst + (f0 + wave) * 1024);
     }
+}
+
+// Epilogue of one 32-feature row tile, cut into four parts (q = 0..3: the four
+// features 8q + 4h + i a lane holds): bias + ReLU, then either two bf16
+// B-fragments of the next layer (lo <- q = 0, 1; hi <- q = 2, 3) or, for the
+// last hidden layer, the partial dot with the ->1 layer's weights.
+template <int CT, bool FINAL, int Q>
+__device__ __forceinline__ void epilogue_part(const f32x16 (&acc)[CT], bf16x8 (&lo)[CT], bf16x8 (&hi)[CT],
+                                              float (&zpart)[CT], const float *sbias, const float *swl, int h)
+{
+    const float4 bv = *(const float4 *)(sbias + 8 * Q + 4 * h);
+    if constexpr (FINAL) {
+        const float4 wl = *(const float4 *)(swl + 8 * Q + 4 * h);
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            zpart[c] += wl.x * relu(acc[c][4 * Q + 0] + bv.x) + wl.y * relu(acc[c][4 * Q + 1] + bv.y) +
+                        wl.z * relu(acc[c][4 * Q + 2] + bv.z) + wl.w * relu(acc[c][4 * Q + 3] + bv.w);
+            asm volatile("" : "+v"(zpart[c]));      // keep the partial dot here (see the convert below)
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            bf16x8 &dst = Q < 2 ? lo[c] : hi[c];
+            constexpr int o = 4 * (Q & 1);
+            dst[o + 0] = (__bf16)relu(acc[c][4 * Q + 0] + bv.x);
+            dst[o + 1] = (__bf16)relu(acc[c][4 * Q + 1] + bv.y);
+            dst[o + 2] = (__bf16)relu(acc[c][4 * Q + 2] + bv.z);
+            dst[o + 3] = (__bf16)relu(acc[c][4 * Q + 3] + bv.w);
+            // convert now: left alone the compiler keeps the fp32 values (twice the registers) until first use
+            if constexpr ((Q & 1) == 1) asm volatile("" : "+v"(dst));
+        }
+    }
+}
+
+// MFMA loop of one row tile, acc = W_tile . in, with the four epilogue parts of
+// the PREVIOUS row tile slipped in between the groups of MFMAs: the vector ALU
+// work then runs while the matrix cores are busy instead of after them.
+// A fragments come from LDS in groups of G, the next group in flight while the
+// current one feeds the matrix cores; the scheduling barriers keep the compiler
+// from hoisting every load of the tile (which would not fit the register file
+// next to the activations).
+template <int CT, int KS, class Epi>
+__device__ __forceinline__ void tile_mfma(const char *w, const bf16x8 (&in)[CT][KS], f32x16 (&acc)[CT], Epi &&epi)
+{
+#pragma unroll
+    for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
+    constexpr int G = 4, NG = KS / G;
+    static_assert(KS % G == 0 && NG >= 2, "k-steps per tile");
+    bf16x8 a[2][G];
+#pragma unroll
+    for (int t = 0; t < G; ++t) a[0][t] = *(const bf16x8 *)(w + t * 1024);
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, NG>([&](auto gi) {
+        constexpr int g = decltype(gi)::value;
+        if constexpr (g + 1 < NG) {
+#pragma unroll
+            for (int t = 0; t < G; ++t) a[(g + 1) & 1][t] = *(const bf16x8 *)(w + ((g + 1) * G + t) * 1024);
+        }
+#pragma unroll
+        for (int t = 0; t < G; ++t) {
+#pragma unroll
+            for (int c = 0; c < CT; ++c)
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[g & 1][t], in[c][g * G + t], acc[c], 0, 0, 0);
+        }
+        // epilogue parts of the previous tile that belong to this group
+        static_for<0, 4>([&](auto qi) {
+            constexpr int q = decltype(qi)::value;
+            // never in the last group: the first tile of a layer consumes, in its last
+            // k-steps, the fragments the previous layer's last tile completes here
+            constexpr int at = (q * NG) / 4 < NG - 2 ? (q * NG) / 4 : NG - 2;
+            if constexpr (at == g) epi(qi);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+    });
 }
 
 // K1: layer-1 contraction after the user fold; H1..H3: hidden widths (0 = absent).
 template <int K1, int H1, int H2, int H3, int CT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void k_mlp_mfma(Model m, Batch b, const uint16_t *__restrict__ X,
-                                                        MlpPack pk, const float *__restrict__ bias1)
+__global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, const uint16_t *__restrict__ X,
+                                                           MlpPack pk, const float *__restrict__ bias1)
 {
-    constexpr int THREADS = WAVES * 64, ROWS = WAVES * 32 * CT;
-    constexpr int NH = H3 ? 3 : (H2 ? 2 : 1);
-    constexpr int HL = NH == 1 ? H1 : (NH == 2 ? H2 : H3);          // width entering the final ->1 layer
-    constexpr int KMAX = cmax(K1, cmax(NH >= 2 ? H1 : 0, NH >= 3 ? H2 : 0));
-    constexpr int BUFBYTES = KMAX * 64;
+    using C = Chain<K1, H1, H2, H3, WAVES>;
+    constexpr int THREADS = WAVES * 64, ROWS = WAVES * 32 * CT, NS = C::total(), D = C::slots() - 1;
     static_assert(ROW_BLOCK % ROWS == 0, "tile");
-    extern __shared__ __align__(16) char lds[];
-    float *sb1 = (float *)(lds + 2 * BUFBYTES), *sb2 = sb1 + H1, *sb3 = sb2 + H2, *swl = sb3 + H3;
+    extern __shared__ __align__(16) char lds[];                 // the weight ring, then biases and last-layer weights
+    float *sb1 = (float *)(lds + C::slots() * C::slot_frags() * 1024), *sb2 = sb1 + H1, *sb3 = sb2 + H2, *swl = sb3 + H3;
 
     const int tile = blockIdx.x;
     const int r = b.blk_req[tile / (ROW_BLOCK / ROWS)];
@@ -167,7 +195,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_mlp_mfma(Model m, Batch b, const
     if (rd.n_cand - local0 <= 0) return;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, h = lane >> 5;
-    stage_tile<K1 / 16, WAVES>(pk.w[0], lds);
+    issue_stage<C, WAVES, 0>(pk, lds);
 
     bf16x8 xin[CT][K1 / 16];
 #pragma unroll
@@ -177,34 +205,94 @@ __global__ __launch_bounds__(WAVES * 64) void k_mlp_mfma(Model m, Batch b, const
         for (int j = 0; j < K1 / 16; ++j) xin[c][j] = xr[2 * j + h];
     }
     for (int i = threadIdx.x; i < H1; i += THREADS) sb1[i] = bias1[(size_t)r * H1 + i];
-    if (NH >= 2)
+    if (C::NH >= 2)
         for (int i = threadIdx.x; i < H2; i += THREADS) sb2[i] = pk.bias[1][i];
-    if (NH >= 3)
+    if (C::NH >= 3)
         for (int i = threadIdx.x; i < H3; i += THREADS) sb3[i] = pk.bias[2][i];
-    for (int i = threadIdx.x; i < HL; i += THREADS) swl[i] = pk.wlast[i];
-    wait_stage();
+    for (int i = threadIdx.x; i < C::HL; i += THREADS) swl[i] = pk.wlast[i];
+    // loads retire in order: once only the later stages' loads are outstanding,
+    // stage 0, the inputs and the biases have arrived
+    static_for<1, D>([&](auto s) { issue_stage<C, WAVES, decltype(s)::value>(pk, lds); });
+    {
+        constexpr int pend = [] { int n = 0; for (int s = 1; s < D; ++s) n += C::loads(s); return n; }();
+        wait_vmcnt<pend>();
+    }
     __syncthreads();
 
-    int buf = 0;
     float zpart[CT];
 #pragma unroll
     for (int c = 0; c < CT; ++c) zpart[c] = 0.f;
+    bf16x8 h1[CT][C::NH >= 2 ? H1 / 16 : 1];
+    bf16x8 h2[CT][C::NH >= 3 ? H2 / 16 : 1];
+    f32x16 accA[CT], accB[CT];              // current / previous row tile (ping-pong)
+    bf16x8 lo[CT], hi[CT];
 
-    if constexpr (NH == 1) {
-        bf16x8 dummy[CT][H1 / 16];
-        mlp_layer<CT, K1, H1, true, WAVES, 0, BUFBYTES>(xin, dummy, zpart, pk.w[0], nullptr, sb1, swl, lds, buf);
-    } else if constexpr (NH == 2) {
-        bf16x8 h1[CT][H1 / 16];
-        mlp_layer<CT, K1, H1, false, WAVES, H1 / 16, BUFBYTES>(xin, h1, zpart, pk.w[0], pk.w[1], sb1, swl, lds, buf);
-        bf16x8 dummy[CT][H2 / 16];
-        mlp_layer<CT, H1, H2, true, WAVES, 0, BUFBYTES>(h1, dummy, zpart, pk.w[1], nullptr, sb2, swl, lds, buf);
-    } else {
-        bf16x8 h1[CT][H1 / 16];
-        mlp_layer<CT, K1, H1, false, WAVES, H1 / 16, BUFBYTES>(xin, h1, zpart, pk.w[0], pk.w[1], sb1, swl, lds, buf);
-        bf16x8 h2[CT][H2 / 16];
-        mlp_layer<CT, H1, H2, false, WAVES, H2 / 16, BUFBYTES>(h1, h2, zpart, pk.w[1], pk.w[2], sb2, swl, lds, buf);
-        bf16x8 dummy[CT][H3 / 16];
-        mlp_layer<CT, H2, H3, true, WAVES, 0, BUFBYTES>(h2, dummy, zpart, pk.w[2], nullptr, sb3, swl, lds, buf);
+    // epilogue part Q of row tile RT of layer L, acting on `acc`; when the tile's
+    // last part is done its two fragments are filed as k-steps 2 RT, 2 RT + 1 of the next layer
+    auto epi_part = [&](auto lc, auto rtc, auto qc, const f32x16(&acc)[CT]) {
+        constexpr int L = decltype(lc)::value, RT = decltype(rtc)::value, Q = decltype(qc)::value;
+        constexpr bool FIN = L == C::NH - 1;
+        const float *sb = L == 0 ? sb1 : (L == 1 ? sb2 : sb3);
+        epilogue_part<CT, FIN, Q>(acc, lo, hi, zpart, sb + 32 * RT, swl + 32 * RT, h);
+        if constexpr (!FIN && Q == 3) {
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+                if constexpr (L == 0) {
+                    h1[c][2 * RT] = lo[c];
+                    h1[c][2 * RT + 1] = hi[c];
+                } else {
+                    h2[c][2 * RT] = lo[c];
+                    h2[c][2 * RT + 1] = hi[c];
+                }
+            }
+        }
+    };
+
+    // row tiles are numbered through all hidden layers: T -> (layer, row tile in layer)
+    constexpr int RT0 = H1 / 32, RT1 = C::NH > 1 ? H2 / 32 : 0, RT2 = C::NH > 2 ? H3 / 32 : 0, NT = RT0 + RT1 + RT2;
+    auto run_tile = [&](auto tc, const char *w) {
+        constexpr int T = decltype(tc)::value;
+        constexpr int L = T < RT0 ? 0 : (T < RT0 + RT1 ? 1 : 2);
+        constexpr int RT = T - (L == 0 ? 0 : (L == 1 ? RT0 : RT0 + RT1));
+        constexpr int PT = T - 1;                                       // previous tile (epilogue pending)
+        constexpr int PL = PT < RT0 ? 0 : (PT < RT0 + RT1 ? 1 : 2);
+        constexpr int PRT = PT - (PL == 0 ? 0 : (PL == 1 ? RT0 : RT0 + RT1));
+        auto &cur = (T & 1) ? accB : accA;
+        auto &prev = (T & 1) ? accA : accB;
+        auto epi = [&](auto qc) {
+            if constexpr (T > 0) epi_part(IC<PL>{}, IC<PRT>{}, qc, prev);
+        };
+        if constexpr (L == 0)
+            tile_mfma<CT, K1 / 16>(w, xin, cur, epi);
+        else if constexpr (L == 1)
+            tile_mfma<CT, H1 / 16>(w, h1, cur, epi);
+        else
+            tile_mfma<CT, H2 / 16>(w, h2, cur, epi);
+    };
+
+    static_for<0, NS>([&](auto si) {
+        constexpr int I = decltype(si)::value;
+        constexpr int l = C::layer_of(I), U = C::unit(l), KS = C::ks(l);
+        __builtin_amdgcn_sched_barrier(0);
+        issue_stage<C, WAVES, I + D>(pk, lds);       // its slot was read last in stage I - 1
+        const char *w0 = lds + (I % C::slots()) * C::slot_frags() * 1024 + lane * 16;
+        static_for<0, U>([&](auto uc) {
+            constexpr int u = decltype(uc)::value;
+            constexpr int T = (l == 0 ? 0 : (l == 1 ? RT0 : RT0 + RT1)) + (I - C::first(l)) * U + u;
+            run_tile(IC<T>{}, w0 + u * KS * 1024);
+        });
+        if constexpr (I + 1 < NS) {
+            // stage I + 1 must have landed; stages I + 2 .. I + D may still be in flight
+            constexpr int pend = [] { int n = 0; for (int s = I + 2; s <= I + D; ++s) n += C::loads(s); return n; }();
+            wait_vmcnt<pend>();
+            __syncthreads();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    {   // the last tile's epilogue has nothing left to hide behind
+        constexpr int PL = C::NH - 1, PRT = (PL == 0 ? RT0 : (PL == 1 ? RT1 : RT2)) - 1;
+        auto &prev = ((NT - 1) & 1) ? accB : accA;
+        static_for<0, 4>([&](auto qc) { epi_part(IC<PL>{}, IC<PRT>{}, qc, prev); });
     }
 
     const float bl = pk.blast ? pk.blast[0] : 0.f;
@@ -251,9 +339,8 @@ template <int K1, int H1, int H2, int H3, int CT, int WAVES>
 static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, const MlpPack &pk, const float *bias1,
                               hipStream_t s)
 {
-    constexpr int NH = H3 ? 3 : (H2 ? 2 : 1);
-    constexpr int KMAX = cmax(K1, cmax(NH >= 2 ? H1 : 0, NH >= 3 ? H2 : 0));
-    constexpr int LDS = 2 * KMAX * 64 + 4 * (H1 + H2 + H3 + (NH == 1 ? H1 : (NH == 2 ? H2 : H3)));
+    using C = Chain<K1, H1, H2, H3, WAVES>;
+    constexpr int LDS = C::lds_bytes();
     constexpr int ROWS = WAVES * 32 * CT;
     auto kern = k_mlp_mfma<K1, H1, H2, H3, CT, WAVES>;
     static bool attr_set = false;
