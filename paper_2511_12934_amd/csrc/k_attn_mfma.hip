@@ -50,7 +50,7 @@ __device__ __forceinline__ void stage_frags(const char *__restrict__ src, char *
 }
 
 // ---------------------------------------------------------------------------
-// a2 -- per request: K and V into fragment order, and max_t |k_t| per head.
+// a2 -- per request: K and V into fragment order, and max |k_t| per head and 64-key stage.
 // Layout per request: chunk(head, key tile kt) = FR fragments of 1 KB at
 // ((head * nktp + kt) * FR) KB:  JS K-fragments  [lane][s] = K[32kt + lane%32][o + 16j + 8(lane/32) + s]
 // then 2*FT V-fragments (jj, ft): [lane][s] = V[32kt + 16jj + 8(s/4) + 4(lane/32) + s%4][o + 32ft + lane%32]
@@ -58,7 +58,7 @@ __device__ __forceinline__ void stage_frags(const char *__restrict__ src, char *
 // ---------------------------------------------------------------------------
 template <int DH>
 __global__ __launch_bounds__(256) void k_pack_kv(Model m, Batch b, char *__restrict__ kvpack, size_t pack_stride,
-                                                 float *__restrict__ kmax, int nktp)
+                                                 float *__restrict__ kmax_part, int nktp)
 {
     constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32;
     const int r = blockIdx.z, hd = blockIdx.y, st = blockIdx.x;
@@ -68,42 +68,54 @@ __global__ __launch_bounds__(256) void k_pack_kv(Model m, Batch b, char *__restr
     if (2 * st >= nkt2) return;
     const uint16_t *K = (const uint16_t *)rd->seq_keys, *V = (const uint16_t *)rd->seq_vals;
     const int da = m.d_attn, o = hd * DH;
-    uint16_t *dst = (uint16_t *)(kvpack + (size_t)r * pack_stride + ((size_t)(hd * nktp + 2 * st) * FR) * 1024);
-    for (int e = threadIdx.x; e < 2 * FR * 512; e += 256) {
-        const int k2 = e / (FR * 512), rem = e - k2 * (FR * 512);
-        const int frag = rem >> 9, lane = (rem >> 3) & 63, s = rem & 7;
-        const int kt = 2 * st + k2;
-        uint16_t val = 0;
+    uint4 *dst = (uint4 *)(kvpack + (size_t)r * pack_stride + ((size_t)(hd * nktp + 2 * st) * FR) * 1024);
+    // one 16-byte piece (a lane's share of a fragment) per thread and step
+    for (int pc = threadIdx.x; pc < 2 * FR * 64; pc += 256) {
+        const int k2 = pc / (FR * 64), rem = pc - k2 * (FR * 64);
+        const int frag = rem >> 6, lane = rem & 63;
+        const int kt = 2 * st + k2, hh = lane >> 5;
+        uint4 out = make_uint4(0, 0, 0, 0);
         if (frag < JS) {
-            const int t = 32 * kt + (lane & 31), f = o + 16 * frag + 8 * (lane >> 5) + s;
-            if (t < L) val = K[(size_t)t * da + f];
+            const int t = 32 * kt + (lane & 31);
+            if (t < L) out = *(const uint4 *)(K + (size_t)t * da + o + 16 * frag + 8 * hh);
         } else {
             const int fv = frag - JS, jj = fv / FT, ft = fv - jj * FT;
-            const int t = 32 * kt + 16 * jj + 8 * (s >> 2) + 4 * (lane >> 5) + (s & 3), f = o + 32 * ft + (lane & 31);
-            if (t < L) val = V[(size_t)t * da + f];
+            const int f = o + 32 * ft + (lane & 31), t0 = 32 * kt + 16 * jj + 4 * hh;
+            uint32_t w[4];
+#pragma unroll
+            for (int p2 = 0; p2 < 4; ++p2) {                 // slots 2 p2 and 2 p2 + 1
+                const int ta = t0 + 8 * ((2 * p2) >> 2) + ((2 * p2) & 3), tb = ta + 1;
+                const uint32_t lo = ta < L ? V[(size_t)ta * da + f] : 0u;
+                const uint32_t hi = tb < L ? V[(size_t)tb * da + f] : 0u;
+                w[p2] = lo | (hi << 16);
+            }
+            out = make_uint4(w[0], w[1], w[2], w[3]);
         }
-        dst[e] = val;
+        dst[pc] = out;
     }
+    // largest key norm among this stage's 64 keys
     if (threadIdx.x < 64) {
         const int t = 64 * st + threadIdx.x;
         float ss = 0.f;
-        if (t < L)
-            for (int f = 0; f < DH; ++f) {
-                const float v = bf2f(K[(size_t)t * da + o + f]);
-                ss += v * v;
+        if (t < L) {
+            const uint4 *kr = (const uint4 *)(K + (size_t)t * da + o);
+#pragma unroll
+            for (int i = 0; i < DH / 8; ++i) {
+                const uint4 q = kr[i];
+                const uint32_t ws[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float a0 = __uint_as_float(ws[j] << 16), a1 = __uint_as_float(ws[j] & 0xFFFF0000u);
+                    ss += a0 * a0 + a1 * a1;
+                }
             }
+        }
         float nrm = sqrtf(ss);
 #pragma unroll
         for (int off = 32; off; off >>= 1) nrm = fmaxf(nrm, __shfl_xor(nrm, off, 64));
         // round the bound up a little: it must dominate the fp32-accumulated score
-        if (threadIdx.x == 0) atomicMax((int *)(kmax + (size_t)r * m.n_heads + hd), __float_as_int(nrm * 1.001f));
+        if (threadIdx.x == 0) kmax_part[((size_t)r * m.n_heads + hd) * (nktp / 2) + st] = nrm * 1.001f;
     }
-}
-
-__global__ void k_zero_f32(float *p, int n)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0.f;
 }
 
 // ---------------------------------------------------------------------------
@@ -151,7 +163,11 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, uint
             for (int s = 0; s < 8; ++s) ss += (float)q[j][s] * (float)q[j][s];
         }
         ss += __shfl_xor(ss, 32, 64);
-        float mc = c * sqrtf(ss) * 1.001f * kmax[(size_t)r * H + hd];
+        float km = 0.f;
+        for (int i = lane; i < nst; i += 64) km = fmaxf(km, kmax[((size_t)r * H + hd) * (nktp / 2) + i]);
+#pragma unroll
+        for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
+        float mc = c * sqrtf(ss) * 1.001f * km;
         if (__any(mc > BOUND_LIMIT)) {
             // rare: take the true maximum with an extra pass over K (read straight from memory)
             float mx = -INFINITY;
@@ -274,7 +290,6 @@ static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char
                                    int nktp, hipStream_t s)
 {
     constexpr int LDS = 2 * 2 * (DH / 8) * 1024, ROWS = WAVES * 32;
-    hipLaunchKernelGGL(k_zero_f32, dim3((b.n_req * m.n_heads + 255) / 256), dim3(256), 0, s, kmax, b.n_req * m.n_heads);
     if (nktp > 0)
         hipLaunchKernelGGL(k_pack_kv<DH>, dim3(nktp / 2, m.n_heads, b.n_req), dim3(256), 0, s, m, b, kvpack, stride, kmax, nktp);
     hipLaunchKernelGGL((k_attn_mfma<DH, WAVES>), dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), LDS, s, m, b,

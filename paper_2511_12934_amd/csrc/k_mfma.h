@@ -13,7 +13,7 @@ struct MfmaPlan {
     void *wq_pack = nullptr;           // bf16 W_q in fragment order (owned)
     float *zeros = nullptr;            // zero vector standing in for an absent bias (owned)
     char *kvpack = nullptr;            // per-request K/V in fragment order (owned workspace)
-    float *kmax = nullptr;             // per request and head: max_t |k_t| (owned workspace)
+    float *kmax = nullptr;             // per request, head and 64-key stage: max |k_t| (owned workspace)
     size_t pack_stride = 0;            // bytes of kvpack per request
     int nktp = 0;                      // key tiles per head the pack layout is sized for
 };

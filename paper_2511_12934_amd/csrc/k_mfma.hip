@@ -18,7 +18,7 @@ hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, const void 
         plan.pack_stride = attn_pack_stride(m, max_seq_len, &plan.nktp);
         hipError_t e = hipMalloc((void **)&plan.kvpack, plan.pack_stride * max_users + 16);
         if (e != hipSuccess) return e;
-        e = hipMalloc((void **)&plan.kmax, (size_t)max_users * m.n_heads * 4);
+        e = hipMalloc((void **)&plan.kmax, (size_t)max_users * m.n_heads * (plan.nktp / 2 + 1) * 4);
         if (e != hipSuccess) return e;
         plan.attn = true;
     }

@@ -28,7 +28,8 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
     extern __shared__ __align__(16) unsigned long long sel[];   // [kpad]
     __shared__ uint32_t hist[256];
     __shared__ uint32_t wave_cnt[TK_THREADS / 64];
-    __shared__ uint32_t s_prefix, s_remaining, s_ngreater;
+    __shared__ uint32_t sfx_tmp[256];
+    __shared__ uint32_t s_prefix, s_remaining, s_ngreater, s_prefix_next, s_remaining_next;
 
     const int r = blockIdx.x;
     const float *z = descs[r].logits;
@@ -58,16 +59,34 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
             if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
         }
         __syncthreads();
-        if (tid == 0) {
-            uint32_t rem = s_remaining, cum = 0;
-            int bin = 255;
-            for (; bin > 0; --bin) {
-                const uint32_t h = hist[bin];
-                if (cum + h >= rem) break;
-                cum += h;
+        // bin holding the rem-th best: suffix sums S[b] = sum_{b' >= b} hist[b'] over the 256 bins
+        // (four waves, one bin per thread); the bin b with S[b] >= rem > S[b + 1] is unique
+        if (tid < 256) {
+            const uint32_t hv = hist[tid];
+            uint32_t sfx = hv;                              // inclusive suffix sum within the wave
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t v = __shfl_down(sfx, o, 64);
+                if ((tid & 63) + o < 64) sfx += v;
             }
-            s_prefix = prefix | ((uint32_t)bin << shift);
-            s_remaining = rem - cum;
+            if ((tid & 63) == 0) wave_cnt[tid >> 6] = sfx;
+            sfx_tmp[tid] = sfx;
+        }
+        __syncthreads();
+        if (tid < 256) {
+            uint32_t above = 0;                             // bins of the higher waves
+            for (int w = (tid >> 6) + 1; w < 4; ++w) above += wave_cnt[w];
+            const uint32_t incl = sfx_tmp[tid] + above, excl = incl - hist[tid];
+            const uint32_t rem = s_remaining;
+            if (incl >= rem && excl < rem) {
+                s_prefix_next = prefix | ((uint32_t)tid << shift);
+                s_remaining_next = rem - excl;
+            }
+        }
+        __syncthreads();
+        if (tid == 0) {
+            s_prefix = s_prefix_next;
+            s_remaining = s_remaining_next;
         }
         mask |= 255u << shift;
         __syncthreads();
