@@ -15,8 +15,8 @@
 //
 // The request's K and V (shared by all its candidates and mini-batches,
 // Sec. 3.1) are packed once per call into MFMA fragment order and streamed
-// through LDS, two 32-key tiles per stage, double buffered, with direct-to-LDS
-// loads; all waves of a block share them.
+// through a four-slot ring in LDS, two 32-key tiles per stage, three stages in
+// flight, with direct-to-LDS loads; all waves of a block share them.
 //
 // Softmax is shift invariant, so instead of a running maximum (and the
 // rescaling of O it forces) each candidate subtracts the bound
@@ -25,28 +25,26 @@
 // first takes the true maximum in an extra pass over K.  Both are the exact
 // softmax up to rounding.
 #include "k_mfma.h"
+#include "mfma_util.h"
 
 namespace aif {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef const void __attribute__((address_space(1))) *gptr_t;
-typedef void __attribute__((address_space(3))) *lptr_t;
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float BOUND_LIMIT = 40.f;      // exponents stay within [-80, 0]
 
+// Copy NFRAG fragments of 1 KB global -> LDS; every wave moves NFRAG / WAVES of them.
 template <int NFRAG, int WAVES>
-__device__ __forceinline__ void stage_frags(const char *__restrict__ src, char *dst)
+__device__ __forceinline__ void stage_frags(const char *__restrict__ src, uint32_t lds_dst)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    static_assert(NFRAG % WAVES == 0, "every wave issues the same number of loads");
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll
-    for (int f0 = 0; f0 < NFRAG; f0 += WAVES) {
-        const int f = f0 + wave;
-        if (NFRAG % WAVES == 0 || f < NFRAG)
-            __builtin_amdgcn_global_load_lds((gptr_t)(src + f * 1024 + lane * 16), (lptr_t)(dst + f * 1024), 16, 0, 0);
-    }
+    for (int f0 = 0; f0 < NFRAG; f0 += WAVES) dma16(src + (f0 + wave) * 1024 + lane * 16, lds_dst + (f0 + wave) * 1024);
 }
 
 // ---------------------------------------------------------------------------
@@ -148,11 +146,19 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, uint
     const bf16x8 *xrow8 = (const bf16x8 *)xrow;
     const float c = LOG2E / sqrtf((float)DH);
 
-    if (total > 0) stage_frags<2 * FR, WAVES>(pk, lds);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    constexpr int SLOTS = 4, DIST = SLOTS - 1, LPW = 2 * FR / WAVES;      // ring, prefetch distance, loads per wave and stage
+    const uint32_t ring = lds_address(lds);
+    auto stage_src = [&](int i) {
+        const int sh = i / nst, ss = i - sh * nst;
+        return pk + ((size_t)(sh * nktp + 2 * ss) * FR) * 1024;
+    };
+    // The compiler does not know of the hand-issued loads: wherever it waits for a load of its own it
+    // waits for all of them.  So this block's own loads (query rows, key-norm bounds) are issued first.
+    for (int i = 0; i < DIST && i < total; ++i) stage_frags<2 * FR, WAVES>(stage_src(i), ring + i * STAGE_BYTES);
+    wait_vmcnt<0>();
     __syncthreads();
 
-    int it = 0, buf = 0;
+    int it = 0;
     for (int hd = 0; hd < H; ++hd) {
         bf16x8 q[JS];
         float ss = 0.f;
@@ -197,10 +203,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, uint
         float l = 0.f;
 
         for (int st = 0; st < nst; ++st) {
-            if (it + 1 < total) {
-                const int nh = (it + 1) / nst, ns = (it + 1) - nh * nst;
-                stage_frags<2 * FR, WAVES>(pk + ((size_t)(nh * nktp + 2 * ns) * FR) * 1024, lds + (buf ^ 1) * STAGE_BYTES);
-            }
+            // stage it + DIST goes into the slot stage it - 1 was read from
+            if (it + DIST < total) stage_frags<2 * FR, WAVES>(stage_src(it + DIST), ring + ((it + DIST) % SLOTS) * STAGE_BYTES);
+            const int buf = it % SLOTS;
 #pragma unroll
             for (int k2 = 0; k2 < 2; ++k2) {
                 const int kt = 2 * st + k2;
@@ -234,9 +239,17 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, uint
                     O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + (JS + FT + ft) * 1024), P1, O[ft], 0, 0, 0);
                 }
             }
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            // stage it + 1 must have landed; the later ones (as far as they exist) may stay in flight
+            {
+                const int later = total - 2 - it;
+                if (later >= 2)
+                    wait_vmcnt<2 * LPW>();
+                else if (later == 1)
+                    wait_vmcnt<LPW>();
+                else
+                    wait_vmcnt<0>();
+            }
             __syncthreads();
-            buf ^= 1;
             ++it;
         }
 
@@ -289,7 +302,7 @@ template <int DH, int WAVES>
 static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char *kvpack, size_t stride, float *kmax,
                                    int nktp, hipStream_t s)
 {
-    constexpr int LDS = 2 * 2 * (DH / 8) * 1024, ROWS = WAVES * 32;
+    constexpr int LDS = 4 * 2 * (DH / 8) * 1024, ROWS = WAVES * 32;
     if (nktp > 0)
         hipLaunchKernelGGL(k_pack_kv<DH>, dim3(nktp / 2, m.n_heads, b.n_req), dim3(256), 0, s, m, b, kvpack, stride, kmax, nktp);
     hipLaunchKernelGGL((k_attn_mfma<DH, WAVES>), dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), LDS, s, m, b,

@@ -18,6 +18,7 @@
 // tiles of 32 candidates.  The user block of layer 1 arrives as the per-request
 // bias (user fold), the final ->1 layer is a dot product in the epilogue.
 #include "k_mfma.h"
+#include "mfma_util.h"
 
 namespace aif {
 
@@ -26,8 +27,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
-typedef const void __attribute__((address_space(1))) *gptr_t;
-typedef void __attribute__((address_space(3))) *lptr_t;
 
 template <int N> struct IC { static constexpr int value = N; };
 template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&f)
@@ -38,7 +37,6 @@ template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&
     }
 }
 
-template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 __device__ __forceinline__ float relu(float x) { return __builtin_amdgcn_fmed3f(x, 0.f, __builtin_inff()); }
 
@@ -67,21 +65,6 @@ template <int K1, int H1, int H2, int H3, int WAVES> struct Chain {
     static_assert(NH < 2 || nout(1) % (32 * unit(1)) == 0, "layer 2 width");
     static_assert(NH < 3 || nout(2) % (32 * unit(2)) == 0, "layer 3 width");
 };
-
-// Direct-to-LDS load of 16 bytes per lane: lane j's bytes land at lds_dst + 16 j
-// (lds_dst = wave-uniform LDS byte address, handed over in M0).  Written as
-// assembly so that the compiler does not see a store to LDS: with the builtin
-// it makes later LDS reads of unrelated data (the biases) wait for every
-// outstanding weight load, which defeats the prefetch distance.  Completion is
-// tracked by hand with wait_vmcnt<>() + a block barrier.
-__device__ __forceinline__ void dma16(const char *gsrc, uint32_t lds_dst)
-{
-    uint32_t keep;
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
-                 : "=&s"(keep)
-                 : "s"(lds_dst), "v"(gsrc)
-                 : "memory");
-}
 
 // Copy stage i of the weight stream global -> LDS slot: a wave moves whole 1 KB
 // fragments, no register staging.
