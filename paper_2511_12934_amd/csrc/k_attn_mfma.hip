@@ -129,21 +129,27 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, uint
     extern __shared__ __align__(16) char lds[];
 
     const int tile = blockIdx.x;
+    const int row0 = tile * ROWS;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, h = lane >> 5;
+    uint16_t *xrow = X + (size_t)(row0 + wave * 32 + col) * m.ldx;
+    const bf16x8 *xrow8 = (const bf16x8 *)xrow;
+    // The block's start is a chain of dependent memory round trips; keep it short.  The query rows
+    // do not depend on the request lookup (a padded row is still inside the workspace): ask first.
+    bf16x8 q[JS];
+#pragma unroll
+    for (int j = 0; j < JS; ++j) q[j] = xrow8[2 * j + h];
+
     const int r = b.blk_req[tile / (ROW_BLOCK / ROWS)];
     if (r < 0) return;
     const ReqDesc rd = b.reqs[r];
-    const int row0 = tile * ROWS;
     const int local0 = row0 - rd.row_base;
     if (rd.n_cand - local0 <= 0) return;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, h = lane >> 5;
     const int L = rd.seq_len, H = m.n_heads;
     const int nkt = (L + 31) >> 5, nst = (nkt + 1) >> 1, total = H * nst;
     const char *pk = kvpack + (size_t)r * pack_stride;
     const int local = local0 + wave * 32 + col;
     const bool live = local < rd.n_cand;
-    uint16_t *xrow = X + (size_t)(row0 + wave * 32 + col) * m.ldx;
-    const bf16x8 *xrow8 = (const bf16x8 *)xrow;
     const float c = LOG2E / sqrtf((float)DH);
 
     constexpr int SLOTS = 4, DIST = SLOTS - 1, LPW = 2 * FR / WAVES;      // ring, prefetch distance, loads per wave and stage
@@ -152,25 +158,33 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, uint
         const int sh = i / nst, ss = i - sh * nst;
         return pk + ((size_t)(sh * nktp + 2 * ss) * FR) * 1024;
     };
+    auto load_kmax = [&](int hd) {
+        float km = 0.f;
+        for (int i = lane; i < nst; i += 64) km = fmaxf(km, kmax[((size_t)r * H + hd) * (nktp / 2) + i]);
+        return km;
+    };
     // The compiler does not know of the hand-issued loads: wherever it waits for a load of its own it
-    // waits for all of them.  So this block's own loads (query rows, key-norm bounds) are issued first.
+    // waits for all of them.  So the first head's key-norm bounds are asked for before the ring is
+    // primed, and everything is waited for once.
+    float km = load_kmax(0);
     for (int i = 0; i < DIST && i < total; ++i) stage_frags<2 * FR, WAVES>(stage_src(i), ring + i * STAGE_BYTES);
     wait_vmcnt<0>();
     __syncthreads();
 
     int it = 0;
     for (int hd = 0; hd < H; ++hd) {
-        bf16x8 q[JS];
+        if (hd > 0) {
+#pragma unroll
+            for (int j = 0; j < JS; ++j) q[j] = xrow8[hd * (DH / 8) + 2 * j + h];
+            km = load_kmax(hd);
+        }
         float ss = 0.f;
 #pragma unroll
         for (int j = 0; j < JS; ++j) {
-            q[j] = xrow8[hd * (DH / 8) + 2 * j + h];
 #pragma unroll
             for (int s = 0; s < 8; ++s) ss += (float)q[j][s] * (float)q[j][s];
         }
         ss += __shfl_xor(ss, 32, 64);
-        float km = 0.f;
-        for (int i = lane; i < nst; i += 64) km = fmaxf(km, kmax[((size_t)r * H + hd) * (nktp / 2) + i]);
 #pragma unroll
         for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
         float mc = c * sqrtf(ss) * 1.001f * km;

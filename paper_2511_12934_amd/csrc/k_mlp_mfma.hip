@@ -170,16 +170,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, co
     float *sb1 = (float *)(lds + C::slots() * C::slot_frags() * 1024), *sb2 = sb1 + H1, *sb3 = sb2 + H2, *swl = sb3 + H3;
 
     const int tile = blockIdx.x;
-    const int r = b.blk_req[tile / (ROW_BLOCK / ROWS)];
-    if (r < 0) return;
-    const ReqDesc rd = b.reqs[r];
     const int row0 = tile * ROWS;
-    const int local0 = row0 - rd.row_base;
-    if (rd.n_cand - local0 <= 0) return;
-
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, h = lane >> 5;
-    issue_stage<C, WAVES, 0>(pk, lds);
-
+    // The block's start is a chain of dependent memory round trips; keep it short: the weight stream
+    // and the input rows do not depend on the request lookup (a padded row is still inside the
+    // workspace), so they are asked for first.
+    static_for<0, D>([&](auto s) { issue_stage<C, WAVES, decltype(s)::value>(pk, lds); });
     bf16x8 xin[CT][K1 / 16];
 #pragma unroll
     for (int c = 0; c < CT; ++c) {
@@ -187,19 +183,20 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, co
 #pragma unroll
         for (int j = 0; j < K1 / 16; ++j) xin[c][j] = xr[2 * j + h];
     }
+    const int r = b.blk_req[tile / (ROW_BLOCK / ROWS)];
+    const ReqDesc rd = b.reqs[r < 0 ? 0 : r];
+    const int local0 = row0 - rd.row_base;
+    if (r < 0 || rd.n_cand - local0 <= 0) {         // never taken when a tile is a whole scheduling block
+        wait_vmcnt<0>();                            // no load may still be heading for this block's LDS
+        return;
+    }
     for (int i = threadIdx.x; i < H1; i += THREADS) sb1[i] = bias1[(size_t)r * H1 + i];
     if (C::NH >= 2)
         for (int i = threadIdx.x; i < H2; i += THREADS) sb2[i] = pk.bias[1][i];
     if (C::NH >= 3)
         for (int i = threadIdx.x; i < H3; i += THREADS) sb3[i] = pk.bias[2][i];
     for (int i = threadIdx.x; i < C::HL; i += THREADS) swl[i] = pk.wlast[i];
-    // loads retire in order: once only the later stages' loads are outstanding,
-    // stage 0, the inputs and the biases have arrived
-    static_for<1, D>([&](auto s) { issue_stage<C, WAVES, decltype(s)::value>(pk, lds); });
-    {
-        constexpr int pend = [] { int n = 0; for (int s = 1; s < D; ++s) n += C::loads(s); return n; }();
-        wait_vmcnt<pend>();
-    }
+    wait_vmcnt<0>();
     __syncthreads();
 
     float zpart[CT];
