@@ -47,18 +47,32 @@ def algorithmic_work(cfg):
     }
 
 
-def cpu_baseline(cfg, w, seconds_budget=20.0):
-    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+def measured_traffic(workload, stage):
+    """HBM bytes per launch of a stage's kernel as rocprofv3's FETCH_SIZE + WRITE_SIZE counters gave them
+    (scaled by a copy kernel of known size); read from the committed counter summary, None if it has no
+    line for this workload and stage.  Line format: ``traffic_bytes_per_launch <workload> <stage> <bytes>``."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
+    try:
+        with open(path) as f:
+            for ln in f:
+                t = ln.split()
+                if len(t) == 4 and t[0] == "traffic_bytes_per_launch" and t[1] == workload and t[2] == stage:
+                    return float(t[3])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(cfg, w, seconds_budget=15.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload:
+    whole requests of the first few users, as many as fit in about ``seconds_budget`` of wall time."""
     import numpy as np
 
     import oracle
     threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1))
-    users = [0]
-    n = min(w.n_cand, 2000)
 
     def run(u, n_c):
-        pos = np.arange(n_c)
-        rows = w.rows_of(u, pos)
+        rows = w.rows_of(u, np.arange(n_c))
         req = w.requests[u]
         t0 = time.perf_counter()
         ref = oracle.score(table=rows, ids=np.arange(n_c, dtype=np.int32), user_vec=req.user.user_vec,
@@ -69,13 +83,17 @@ def cpu_baseline(cfg, w, seconds_budget=20.0):
         oracle.topk(ref.logits, cfg.top_k)
         return time.perf_counter() - t0
 
-    t = run(0, n)                                   # probe
-    per_cand = t / n
-    n_full = int(min(w.n_cand, max(n, seconds_budget / threads / max(per_cand, 1e-9) * 0.5)))
-    t = run(0, n_full)
-    return {"value": n_full / t, "unit": "candidates/s", "cores": threads, "kind": "oracle",
-            "sample": f"1 user x {n_full} candidates of {cfg.name} (oracle score + top-k, {threads} OpenMP threads, "
-                      f"{t:.2f} s wall)"}
+    n_probe = min(w.n_cand, 1000)
+    per_cand = run(0, n_probe) / n_probe               # probe (also warms the thread pool)
+    t_request = per_cand * w.n_cand
+    if t_request > seconds_budget:                      # not even one whole request fits: part of one
+        n_users, n_c = 1, max(n_probe, int(w.n_cand * seconds_budget / t_request))
+    else:
+        n_users, n_c = int(min(w.n_users, max(1, seconds_budget // t_request))), w.n_cand
+    t = sum(run(u, n_c) for u in range(n_users))
+    return {"value": n_users * n_c / t, "unit": "candidates/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n_users} request(s) x {n_c} candidates of {cfg.name} (oracle score + top-k, "
+                      f"{threads} OpenMP threads, {t:.1f} s wall, {t * threads:.0f} core-seconds)"}
 
 
 def single_request_latency(n_iter=200):
@@ -117,6 +135,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--id-sets", type=int, default=4,
+                    help="distinct candidate lists per user, taken in turn by consecutive steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true")
     args = ap.parse_args()
@@ -131,7 +151,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     cfg = wl.CONFIGS[args.workload]
-    w = R.Workload(cfg)
+    w = R.Workload(cfg, n_sets=args.id_sets)
     for _ in range(args.warmup):
         w.step()
     torch.cuda.synchronize()
@@ -168,7 +188,7 @@ def main():
         roof = {"kernel": dom, "bound": "mfma" if mf else "alu", "achieved": kernels[dom]["tflops"],
                 "peak": PEAK_MFMA_BF16_TFLOPS if mf else PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = measured_traffic(cfg.name, dom)
     roof["avg_ms"] = kernels[dom]["avg_ms"]
 
     line = {
@@ -179,7 +199,8 @@ def main():
         "config": {"workload": f"{cfg.name}: {w.n_users} users x {w.n_cand} candidates, table {cfg.n_items}x{cfg.d_item} "
                                f"{cfg.dtype}, L={cfg.seq_len}, d_attn={cfg.d_attn}, H={cfg.n_heads}, "
                                f"MLP {list(cfg.mlp_dims)}, top-{cfg.top_k}",
-                   "users": w.n_users, "candidates_per_request": w.n_cand, "top_k": cfg.top_k},
+                   "users": w.n_users, "candidates_per_request": w.n_cand, "top_k": cfg.top_k,
+                   "candidate_lists_rotated": args.id_sets},
         "request_latency_ms": ms_per_step,
         "roofline": roof,
         "kernels": kernels,

@@ -114,11 +114,16 @@ def peek_features(ctx: B.Context, cfg: wl.Config, req_index: int, n_rows: int) -
 
 class Workload:
     """One configuration resident on the device, in the launch configuration the
-    benchmark times: ``step()`` = aif_score_batch over all users + aif_topk."""
+    benchmark times: ``step()`` = aif_score_batch over all users + aif_topk.
+
+    With ``n_sets`` > 1 the same users arrive with ``n_sets`` different candidate
+    lists and ``step()`` takes them in turn, so that consecutive steps do not
+    gather the same table rows out of the caches (set 0 is the configuration's
+    own list; the others are drawn by the same sampler with later seeds)."""
 
     def __init__(self, cfg: wl.Config, device="cuda:0", n_users: Optional[int] = None,
                  n_cand: Optional[int] = None, n_items: Optional[int] = None, host_table: bool = False,
-                 minibatch: Optional[int] = None):
+                 minibatch: Optional[int] = None, n_sets: int = 1):
         import torch
         self.cfg = cfg
         self.torch = torch
@@ -147,6 +152,20 @@ class Workload:
         self.ctx = make_context(cfg, self.dmodel, self.table, max_users=len(self.launch),
                                 max_candidates=max(d.ids_host.size for d in self.launch))
         self.packed = B.pack_requests([d.req for d in self.launch])
+        # further candidate lists for the same users: only ids differ, outputs and user tensors are shared
+        self.sets = [(self.launch, self.packed)]
+        for si in range(1, n_sets):
+            if minibatch:
+                raise ValueError("n_sets > 1 is for whole requests")
+            lst = []
+            for d, ids in zip(self.dev, wl.make_id_lists(cfg, si, self.n_users, self.n_cand, self.n_items)):
+                idt = torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).to(device)
+                q = d.req
+                lst.append(DeviceRequest(B.Request(q.user_vec, q.seq_keys, q.seq_vals, idt, d.logits, d.scores,
+                                                   q.cross_vecs, q.seq_len), ids, d.logits, d.scores,
+                                         d.keep + (idt,)))
+            self.sets.append((lst, B.pack_requests([x.req for x in lst])))
+        self._turn = 0
         self.k = cfg.top_k
         self.idx = torch.empty((self.n_users, self.k), dtype=torch.int32, device=device)
         self.val = torch.empty((self.n_users, self.k), dtype=torch.float32, device=device)
@@ -157,7 +176,9 @@ class Workload:
         return self.n_users * self.n_cand
 
     def step(self):
-        self.ctx.aif_score_batch(self.launch, packed=self.packed)
+        launch, packed = self.sets[self._turn % len(self.sets)]
+        self._turn += 1
+        self.ctx.aif_score_batch(launch, packed=packed)
         self.ctx.aif_topk(self._logits, self.k, self.idx, self.val)
 
     def rows_of(self, user: int, positions: np.ndarray) -> np.ndarray:

@@ -245,3 +245,13 @@ def make_requests(cfg: Config, n_users: Optional[int] = None, n_cand: Optional[i
     nu = cfg.n_users if n_users is None else n_users
     nc = cfg.n_cand if n_cand is None else n_cand
     return [Request(make_user(cfg, rng, sigma), sampler.sample(rng, nc)) for _ in range(nu)]
+
+
+def make_id_lists(cfg: Config, set_index: int, n_users: Optional[int] = None, n_cand: Optional[int] = None,
+                  n_items: Optional[int] = None) -> List[np.ndarray]:
+    """Another candidate list per user, same sampler, its own seed (set 0 is make_requests' own)."""
+    rng = np.random.default_rng(cfg.seed + 7919 * set_index)
+    sampler = IdSampler(cfg, n_items)
+    nu = cfg.n_users if n_users is None else n_users
+    nc = cfg.n_cand if n_cand is None else n_cand
+    return [sampler.sample(rng, nc) for _ in range(nu)]
