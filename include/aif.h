@@ -152,11 +152,14 @@ AIF_API const char *aif_last_error(const aif_ctx *ctx);
  * Synchronous device read. */
 AIF_API aif_status aif_poll_device_errors(aif_ctx *ctx, int32_t *n_bad_ids);
 
-/* Test hook: the workspace matrix [e | attention | cross] of the last batch,
- * storage type = config.dtype, row-major with row stride *ld elements; the
- * rows of request r start at row *(row_base + r) (HOST array owned by the
- * context, valid until the next call).  Any out pointer may be NULL. */
-AIF_API aif_status aif_peek_features(aif_ctx *ctx, const void **x, int32_t *ld, const int32_t **row_base);
+/* Test hook: rows [first_row, first_row + n_rows) of the feature matrix
+ * [e | attention | cross] that the last batch left for its request number
+ * `request`, copied to the HOST buffer out as a row-major
+ * [n_rows, d_item + d_attn + d_cross] matrix of config.dtype (the library's
+ * own layout in device memory is not part of the interface).  Synchronous;
+ * the caller has synchronised the stream of that batch.  Rows at or beyond
+ * the request's n_cand are unspecified. */
+AIF_API aif_status aif_peek_features(aif_ctx *ctx, int32_t request, int32_t first_row, int32_t n_rows, void *out);
 
 /* Per-kernel timing with HIP events on the caller's stream (the service
  * metrics of Sec. 5.1 are response times; this is their per-kernel breakdown).

@@ -71,7 +71,7 @@ def load():
     lib.aif_poll_device_errors.restype = C.c_int
     lib.aif_poll_device_errors.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.aif_peek_features.restype = C.c_int
-    lib.aif_peek_features.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_int32), C.POINTER(C.POINTER(C.c_int32))]
+    lib.aif_peek_features.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp]
     lib.aif_profile_begin.restype = C.c_int
     lib.aif_profile_begin.argtypes = [vp, C.c_int32]
     lib.aif_profile_end.restype = C.c_int
@@ -175,13 +175,9 @@ class Context:
         self._check(self._lib.aif_poll_device_errors(self._h, C.byref(n)))
         return n.value
 
-    def aif_peek_features(self):
-        """(device pointer, row stride in elements, row_base list) of the last batch's [e|a|c] matrix."""
-        x = C.c_void_p()
-        ld = C.c_int32()
-        rb = C.POINTER(C.c_int32)()
-        self._check(self._lib.aif_peek_features(self._h, C.byref(x), C.byref(ld), C.byref(rb)))
-        return x.value, ld.value, rb
+    def aif_peek_features(self, request: int, first_row: int, n_rows: int, out_ptr: int):
+        """Rows of the last batch's [e | attention | cross] matrix of one request into a host buffer."""
+        self._check(self._lib.aif_peek_features(self._h, request, first_row, n_rows, out_ptr))
 
     def aif_profile_begin(self, max_calls: int):
         self._check(self._lib.aif_profile_begin(self._h, max_calls))

@@ -219,6 +219,11 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
         HIP_TRY(nullptr, launch_to_f32(m.dtype, wts->w_q, m.d_attn, m.d_item, m.d_item, 0, (float *)c->wq.p, s));
     }
     HIP_TRY(nullptr, mfma_plan(m, c->max_seq_len, c->max_users, wts->w_q, wts->w, c->mfma, s));
+    // both consumers of the workspace read MFMA fragments: keep it in fragment order (x_offset)
+    {
+        const char *rm = getenv("AIF_X_ROW_MAJOR");      // testing: the MFMA kernels on the row-major layout
+        m.x_tiled = (c->mfma.attn && c->mfma.mlp && !(rm && rm[0] == '1')) ? 1 : 0;
+    }
 
     const bool attn_ok = c->mfma.attn || attn_generic_lds_bytes(m, c->max_seq_len) <= 160 * 1024;
     const bool mlp_ok = c->mfma.mlp || mlp_generic_lds_bytes(m) <= 160 * 1024;
@@ -414,12 +419,27 @@ aif_status aif_poll_device_errors(aif_ctx *c, int32_t *n_bad_ids)
     return AIF_OK;
 }
 
-aif_status aif_peek_features(aif_ctx *c, const void **x, int32_t *ld, const int32_t **row_base)
+aif_status aif_peek_features(aif_ctx *c, int32_t request, int32_t first_row, int32_t n_rows, void *out)
 {
     if (!c) return AIF_EINVAL;
-    if (x) *x = c->X.p;
-    if (ld) *ld = c->m.ldx;
-    if (row_base) *row_base = c->row_base.data();
+    if (request < 0 || (size_t)request >= c->row_base.size()) return fail(c, AIF_EINVAL, "request %d is not in the last batch", request);
+    if (first_row < 0 || n_rows < 0 || !out) return fail(c, AIF_EINVAL, "bad row range or NULL out");
+    const Model &m = c->m;
+    const size_t row0 = (size_t)c->row_base[request] + first_row;
+    if (row0 + n_rows > c->x_rows) return fail(c, AIF_EINVAL, "rows beyond the workspace");
+    aif_status st = check_device(c);
+    if (st != AIF_OK) return st;
+    if (n_rows == 0) return AIF_OK;
+    // whole tiles to the host, then piece by piece into row-major order
+    const XLayout xl = x_layout(m);
+    const size_t t0 = row0 / X_TILE, t1 = (row0 + n_rows - 1) / X_TILE + 1;
+    std::vector<char> tiles((t1 - t0) * xl.tile_bytes);
+    HIP_TRY(c, hipMemcpy(tiles.data(), (const char *)c->X.p + t0 * xl.tile_bytes, tiles.size(), hipMemcpyDeviceToHost));
+    const uint32_t row_bytes = xl.tile_bytes / X_TILE, pieces = row_bytes / 16;
+    for (int32_t i = 0; i < n_rows; ++i)
+        for (uint32_t p = 0; p < pieces; ++p)
+            memcpy((char *)out + (size_t)i * row_bytes + 16 * p,
+                   tiles.data() + x_offset(xl, (uint32_t)(row0 + i - t0 * X_TILE), p), 16);
     return AIF_OK;
 }
 

@@ -38,11 +38,31 @@ struct Model {
     int64_t n_items;
     int32_t d_item, d_user, d_attn, n_heads, d_head;
     int32_t cross_mode, n_cross, d_cv, d_cross;
-    int32_t ldx;                // row stride of the workspace matrix [e | a | c], in elements
+    int32_t ldx;                // width of the workspace matrix [e | a | c], in elements
+    int32_t x_tiled;            // layout of the workspace inside each tile of X_TILE rows, see x_offset
     int32_t n_layers;
     int32_t dims[MAX_LAYERS + 1];   // dims[0] = D_in
     int32_t k1;                 // D_in - d_user: layer-1 contraction left per candidate after the user fold
 };
+
+// Where the workspace keeps 16-byte piece `piece` of row `row` (byte offset).  Rows are grouped in
+// tiles of X_TILE = 32 (one MFMA column tile).  Row-major inside the tile, or -- when both consumers
+// are the MFMA kernels -- "tiled": pieces ordered [piece][row], so that the 32 rows' copies of one
+// piece are one contiguous 512 B run and a wave's B-fragment load (pieces 2j and 2j + 1 of 32 rows)
+// is one contiguous 1 KB instead of 64 strided 16 B accesses.  A tile takes the same bytes either way.
+constexpr int X_TILE = 32;
+struct XLayout {
+    uint32_t tile_bytes, row_stride, piece_stride;
+};
+__host__ __device__ inline XLayout x_layout(const Model &m)
+{
+    const uint32_t row_bytes = (uint32_t)m.ldx * (m.dtype == 0 ? 4u : 2u);
+    return m.x_tiled ? XLayout{row_bytes * X_TILE, 16u, 16u * X_TILE} : XLayout{row_bytes * X_TILE, row_bytes, 16u};
+}
+__host__ __device__ inline size_t x_offset(const XLayout &l, uint32_t row, uint32_t piece)
+{
+    return (size_t)(row / X_TILE) * l.tile_bytes + (size_t)(row % X_TILE) * l.row_stride + (size_t)piece * l.piece_stride;
+}
 
 // bf16 <-> fp32 on raw bit patterns (round to nearest even).
 __device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }

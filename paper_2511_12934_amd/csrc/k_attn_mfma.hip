@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256) void k_pack_kv(Model m, Batch b, char *__restr
 // attention + Hadamard cross.  One wave = 32 candidates, all heads in turn.
 // ---------------------------------------------------------------------------
 template <int DH, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, uint16_t *__restrict__ X,
+__global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char *__restrict__ X, XLayout xl,
                                                          const char *__restrict__ kvpack, size_t pack_stride,
                                                          const float *__restrict__ kmax, int nktp)
 {
@@ -128,16 +128,22 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, uint
     static_assert(ROW_BLOCK % ROWS == 0, "tile");
     extern __shared__ __align__(16) char lds[];
 
-    const int tile = blockIdx.x;
+    // Workgroups go to the 8 XCDs in turn, each with an L2 of its own.  Give every XCD a contiguous
+    // run of tiles, so the blocks that stream one request's K/V share an L2 instead of all eight
+    // fetching it.
+    const int per_xcd = gridDim.x >> 3;
+    const int bid = blockIdx.x;
+    const int tile = bid < 8 * per_xcd ? (bid & 7) * per_xcd + (bid >> 3) : bid;
     const int row0 = tile * ROWS;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, h = lane >> 5;
-    uint16_t *xrow = X + (size_t)(row0 + wave * 32 + col) * m.ldx;
-    const bf16x8 *xrow8 = (const bf16x8 *)xrow;
+    // this lane's candidate: piece p of its row is at xrow + p * xl.piece_stride
+    char *xrow = X + x_offset(xl, row0 + wave * 32 + col, 0);
+    auto piece = [&](int p) { return (bf16x8 *)(xrow + (size_t)p * xl.piece_stride); };
     // The block's start is a chain of dependent memory round trips; keep it short.  The query rows
     // do not depend on the request lookup (a padded row is still inside the workspace): ask first.
     bf16x8 q[JS];
 #pragma unroll
-    for (int j = 0; j < JS; ++j) q[j] = xrow8[2 * j + h];
+    for (int j = 0; j < JS; ++j) q[j] = *piece(2 * j + h);
 
     const int r = b.blk_req[tile / (ROW_BLOCK / ROWS)];
     if (r < 0) return;
@@ -175,7 +181,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, uint
     for (int hd = 0; hd < H; ++hd) {
         if (hd > 0) {
 #pragma unroll
-            for (int j = 0; j < JS; ++j) q[j] = xrow8[hd * (DH / 8) + 2 * j + h];
+            for (int j = 0; j < JS; ++j) q[j] = *piece(hd * (DH / 8) + 2 * j + h);
             km = load_kmax(hd);
         }
         float ss = 0.f;
@@ -277,20 +283,21 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, uint
                     bf16x4 o4;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(O[ft][4 * qd + i] * inv);
-                    *(bf16x4 *)(xrow + m.d_item + hd * DH + 32 * ft + 8 * qd + 4 * h) = o4;
+                    // features 8 qd + 4 h + i of this tile: half h of one piece
+                    *((bf16x4 *)piece((m.d_item + hd * DH) / 8 + 4 * ft + qd) + h) = o4;
                 }
         }
     }
 
     if (m.cross_mode == 1 && live) {
         const bf16x8 *uc = (const bf16x8 *)rd.cross_vecs;
-        bf16x8 *xc = (bf16x8 *)(xrow + m.d_item + m.d_attn);
+        const int pc0 = (m.d_item + m.d_attn) / 8;
         for (int pc = h; pc < m.d_item / 8; pc += 2) {
-            const bf16x8 e = xrow8[pc], u = uc[pc];
+            const bf16x8 e = *piece(pc), u = uc[pc];
             bf16x8 o8;
 #pragma unroll
             for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)e[s] * (float)u[s]);
-            xc[pc] = o8;
+            *piece(pc0 + pc) = o8;
         }
     }
 }
@@ -320,7 +327,7 @@ static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char
     if (nktp > 0)
         hipLaunchKernelGGL(k_pack_kv<DH>, dim3(nktp / 2, m.n_heads, b.n_req), dim3(256), 0, s, m, b, kvpack, stride, kmax, nktp);
     hipLaunchKernelGGL((k_attn_mfma<DH, WAVES>), dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), LDS, s, m, b,
-                       (uint16_t *)X, (const char *)kvpack, stride, (const float *)kmax, nktp);
+                       (char *)X, x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp);
     return hipGetLastError();
 }
 

@@ -4,10 +4,10 @@
 //
 // Rows are moved as 16-byte pieces.  A row of R bytes is handled by R/16
 // neighbouring lanes, so a wave reads 64*16 B spread over 1024/R rows with
-// every byte of each touched row used, and writes one contiguous run of the
-// workspace (rows of one request are consecutive, row stride ldx).  Each
-// thread first fetches UNROLL ids, then has UNROLL independent row loads in
-// flight before its first store.
+// every byte of each touched row used, and writes whole 128 B runs of the
+// workspace in either of its layouts (x_offset).  Each thread first fetches
+// UNROLL ids, then has UNROLL independent row loads in flight before its first
+// store.
 #include "aif_dev.h"
 
 namespace aif {
@@ -17,7 +17,7 @@ constexpr int GATHER_UNROLL = 4;
 // LOG_RV >= 0: a row is 2^LOG_RV pieces of 16 bytes (shift instead of divide); LOG_RV < 0: any count.
 template <int LOG_RV>
 __global__ __launch_bounds__(256) void k_gather(const uint4 *__restrict__ table, int64_t n_items, int row_vec,
-                                                Batch b, uint4 *__restrict__ X, int ldx_vec,
+                                                Batch b, char *__restrict__ X, XLayout xl,
                                                 int32_t *__restrict__ bad)
 {
     const int blk = blockIdx.x;
@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void k_gather(const uint4 *__restrict__ table,
     if (nrows <= 0) return;
     if (nrows > ROW_BLOCK) nrows = ROW_BLOCK;
     const int32_t *ids = rd->cand_ids + local0;
-    uint4 *out = X + (size_t)(row_base + local0) * ldx_vec;
+    char *out = X + (size_t)((row_base + local0) / X_TILE) * xl.tile_bytes;     // blocks start on tile boundaries
     if (LOG_RV >= 0) row_vec = 1 << LOG_RV;
     const int total = nrows * row_vec;
     int n_bad = 0;
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void k_gather(const uint4 *__restrict__ table,
             if (idx < total) {
                 // streaming stores: measured 1.5x faster than plain ones here (the rows are written once,
                 // at a stride, and the reads that follow come from another kernel)
-                uint4 *p = out + (size_t)row[j] * ldx_vec + piece[j];
+                uint4 *p = (uint4 *)(out + x_offset(xl, row[j], piece[j]));
                 __builtin_nontemporal_store(v[j].x, &p->x);
                 __builtin_nontemporal_store(v[j].y, &p->y);
                 __builtin_nontemporal_store(v[j].z, &p->z);
@@ -76,10 +76,10 @@ hipError_t launch_gather(const Model &m, const Batch &b, const void *table, void
     if (b.n_blk == 0) return hipSuccess;
     const int esz = m.dtype == 0 ? 4 : 2;
     const int row_vec = m.d_item * esz / 16;
-    const int ldx_vec = m.ldx * esz / 16;
+    const XLayout xl = x_layout(m);
     auto go = [&](auto kern) {
-        hipLaunchKernelGGL(kern, dim3(b.n_blk), dim3(256), 0, s, (const uint4 *)table, m.n_items, row_vec, b, (uint4 *)X,
-                           ldx_vec, bad);
+        hipLaunchKernelGGL(kern, dim3(b.n_blk), dim3(256), 0, s, (const uint4 *)table, m.n_items, row_vec, b, (char *)X,
+                           xl, bad);
     };
     switch (row_vec) {
     case 8: go(k_gather<3>); break;

@@ -160,7 +160,7 @@ __device__ __forceinline__ void tile_mfma(const char *w, const bf16x8 (&in)[CT][
 
 // K1: layer-1 contraction after the user fold; H1..H3: hidden widths (0 = absent).
 template <int K1, int H1, int H2, int H3, int CT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, const uint16_t *__restrict__ X,
+__global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, const char *__restrict__ X, XLayout xl,
                                                            MlpPack pk, const float *__restrict__ bias1)
 {
     using C = Chain<K1, H1, H2, H3, WAVES>;
@@ -179,9 +179,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, co
     bf16x8 xin[CT][K1 / 16];
 #pragma unroll
     for (int c = 0; c < CT; ++c) {
-        const bf16x8 *xr = (const bf16x8 *)(X + (size_t)(row0 + (wave * CT + c) * 32 + col) * m.ldx);
+        const char *xr = X + x_offset(xl, row0 + (wave * CT + c) * 32 + col, h);
 #pragma unroll
-        for (int j = 0; j < K1 / 16; ++j) xin[c][j] = xr[2 * j + h];
+        for (int j = 0; j < K1 / 16; ++j) xin[c][j] = *(const bf16x8 *)(xr + (size_t)(2 * j) * xl.piece_stride);
     }
     const int r = b.blk_req[tile / (ROW_BLOCK / ROWS)];
     const ReqDesc rd = b.reqs[r < 0 ? 0 : r];
@@ -329,8 +329,8 @@ static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, con
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), LDS, s, m, b, (const uint16_t *)X, pk,
-                       bias1);
+    hipLaunchKernelGGL(kern, dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), LDS, s, m, b, (const char *)X, x_layout(m),
+                       pk, bias1);
     return hipGetLastError();
 }
 

@@ -4,7 +4,6 @@ moves a synthetic workload into device memory and drives the C ABI through
 """
 from __future__ import annotations
 
-import ctypes as C
 from dataclasses import dataclass
 from typing import List, Optional, Sequence
 
@@ -84,32 +83,16 @@ def make_context(cfg: wl.Config, dmodel: DeviceModel, table_dev, *, max_users: O
                      max_users=cfg.n_users if max_users is None else max_users)
 
 
-_hip = None
-
-
-def _hiprt():
-    global _hip
-    if _hip is None:
-        _hip = C.CDLL("libamdhip64.so")
-        _hip.hipMemcpy.restype = C.c_int
-        _hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
-    return _hip
-
-
 def peek_features(ctx: B.Context, cfg: wl.Config, req_index: int, n_rows: int) -> np.ndarray:
-    """Rows of the workspace matrix [e | attention | cross] of request ``req_index`` as float32."""
+    """Rows of the feature matrix [e | attention | cross] of request ``req_index`` as float32."""
     import torch
     torch.cuda.synchronize()
-    ptr, ld, rb = ctx.aif_peek_features()
-    esz = 4 if cfg.dtype == "f32" else 2
-    base = rb[req_index]
-    host = np.empty(n_rows * ld * esz, dtype=np.uint8)
-    rc = _hiprt().hipMemcpy(host.ctypes.data, ptr + base * ld * esz, host.size, 2)
-    if rc != 0:
-        raise RuntimeError(f"hipMemcpy failed: {rc}")
+    ld = cfg.d_item + cfg.d_attn + cfg.d_cross
+    host = np.empty(n_rows * ld, dtype=np.float32 if cfg.dtype == "f32" else np.uint16)
+    ctx.aif_peek_features(req_index, 0, n_rows, host.ctypes.data)
     if cfg.dtype == "f32":
-        return host.view(np.float32).reshape(n_rows, ld).copy()
-    return wl.bf16_to_f32(host.view(np.uint16)).reshape(n_rows, ld)
+        return host.reshape(n_rows, ld)
+    return wl.bf16_to_f32(host).reshape(n_rows, ld)
 
 
 class Workload:

@@ -258,6 +258,27 @@ def test_forced_generic_kernels_on_bf16_config(R, torch, monkeypatch):
     assert_logits_close("bf16", z, oracle_scores(cfg, model, table, u, ids).logits)
 
 
+def test_mfma_kernels_on_row_major_workspace(R, torch, monkeypatch):
+    """The MFMA kernels take the workspace in either layout (fragment order when both of them consume it,
+    row-major when one consumer is a shape-agnostic kernel): same results, bit for bit."""
+    cfg = wl.CONFIGS["C3"].scaled(n_items=3000)
+    _say("C3 shape, MFMA kernels, row-major workspace vs fragment order")
+    rng = np.random.default_rng(11)
+    model = wl.make_model(cfg)
+    table = wl.make_table_host(cfg, rng, n_items=3000)
+    u = wl.make_user(cfg, rng)
+    ids = wl.IdSampler(cfg, 3000).sample(rng, 333)
+    (z0,), _, _, ctx0 = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), [(u, ids)])
+    X0 = R.peek_features(ctx0, cfg, 0, ids.size)
+    monkeypatch.setenv("AIF_X_ROW_MAJOR", "1")
+    (z1,), _, _, ctx1 = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), [(u, ids)])
+    assert ctx1.aif_stage_kind("attention") == 1 and ctx1.aif_stage_kind("mlp") == 1
+    X1 = R.peek_features(ctx1, cfg, 0, ids.size)
+    assert np.array_equal(X0, X1)
+    assert np.array_equal(z0, z1)
+    assert_logits_close("bf16", z1, oracle_scores(cfg, model, table, u, ids).logits)
+
+
 def test_large_scores_do_not_overflow(R, torch):
     """|score| far beyond the fp32 exp range: softmax must subtract its maximum."""
     cfg = small_cfg("f32", d_item=32, d_user=32, d_attn=32, seq_len=33, mlp_dims=(128, 16, 1))
