@@ -13,10 +13,10 @@
 // layer's weights are stored in that order once, at init.  Activations of all
 // layers therefore stay in registers: no LDS round trip, no transpose.
 //
-// Weights stream through LDS (double buffered, one 32-feature row tile per
-// stage) and are shared by the waves of the block; each wave owns CT column
-// tiles of 32 candidates.  The user block of layer 1 arrives as the per-request
-// bias (user fold), the final ->1 layer is a dot product in the epilogue.
+// Weights stream through a ring in LDS, shared by the waves of the block; each
+// wave owns one column tile of 32 candidates.  The user block of layer 1
+// arrives as the per-request bias (user fold), the final ->1 layer is a dot
+// product in the epilogue.
 #include "k_mfma.h"
 #include "mfma_util.h"
 
@@ -24,8 +24,6 @@ namespace aif {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
 
 template <int N> struct IC { static constexpr int value = N; };
@@ -40,134 +38,86 @@ template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&
 
 __device__ __forceinline__ float relu(float x) { return __builtin_amdgcn_fmed3f(x, 0.f, __builtin_inff()); }
 
-// Static description of the chain: hidden layer l contracts KIN(l) inputs into
-// NOUT(l) features; its weights are streamed in stages of U(l) row tiles
-// (32 features each) chosen so that every wave moves the same number of 1 KB
-// fragments per stage.
-template <int K1, int H1, int H2, int H3, int WAVES> struct Chain {
+// Static description of the chain.  The weights of all hidden layers form ONE
+// stream of 1 KB fragments (fragment = the A operand of one MFMA: 32 output
+// features x 16 contraction indices), in the order the MFMAs consume them:
+// layer by layer, row tile by row tile, k-step by k-step.  The stream is cut
+// into stages of SF fragments that travel through a ring of SLOTS slots in LDS.
+template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS> struct Chain {
     static constexpr int NH = H3 ? 3 : (H2 ? 2 : 1);
     static constexpr int kin(int l) { return l == 0 ? K1 : (l == 1 ? H1 : H2); }
     static constexpr int nout(int l) { return l == 0 ? H1 : (l == 1 ? H2 : H3); }
-    static constexpr int ks(int l) { return kin(l) / 16; }                     // fragments per row tile
-    static constexpr int unit(int l) { return ks(l) % WAVES == 0 ? 1 : ((2 * ks(l)) % WAVES == 0 ? 2 : 4); }
-    static constexpr int nstage(int l) { return nout(l) / 32 / unit(l); }
-    static constexpr int frags(int l) { return unit(l) * ks(l); }              // fragments per stage
-    static constexpr int total() { return nstage(0) + (NH > 1 ? nstage(1) : 0) + (NH > 2 ? nstage(2) : 0); }
-    static constexpr int layer_of(int i) { return i < nstage(0) ? 0 : (i < nstage(0) + nstage(1) ? 1 : 2); }
-    static constexpr int first(int l) { return l == 0 ? 0 : (l == 1 ? nstage(0) : nstage(0) + nstage(1)); }
-    static constexpr int loads(int i) { return i < total() ? frags(layer_of(i)) / WAVES : 0; }   // per wave
-    static constexpr int slot_frags() { return cmax(frags(0), cmax(NH > 1 ? frags(1) : 0, NH > 2 ? frags(2) : 0)); }
+    static constexpr int ks(int l) { return kin(l) / 16; }                     // k-steps (fragments) per row tile
+    static constexpr int nfl(int l) { return l < NH ? nout(l) / 32 * ks(l) : 0; }   // fragments of layer l
+    static constexpr int fbase(int l) { int n = 0; for (int i = 0; i < l; ++i) n += nfl(i); return n; }
+    static constexpr int nf() { return fbase(3); }
+    static constexpr int ns() { return nf() / SF; }
+    static constexpr int tbase(int l) { int n = 0; for (int i = 0; i < l && i < NH; ++i) n += nout(i) / 32; return n; }
+    static constexpr int nt() { return tbase(3); }
+    // fragment F of the stream -> layer, global row tile, k-step, byte offset in the ring
+    static constexpr int flayer(int F) { return F < fbase(1) ? 0 : (F < fbase(2) ? 1 : 2); }
+    static constexpr int ftile(int F) { return tbase(flayer(F)) + (F - fbase(flayer(F))) / ks(flayer(F)); }
+    static constexpr int fk(int F) { return (F - fbase(flayer(F))) % ks(flayer(F)); }
+    static constexpr int foff(int F) { return ((F / SF) % SLOTS) * SF * 1024 + (F % SF) * 1024; }
+    static constexpr int tlayer(int T) { return T < tbase(1) ? 0 : (T < tbase(2) ? 1 : 2); }
+    static constexpr int trt(int T) { return T - tbase(tlayer(T)); }
+    // The epilogue of row tile T - 1 runs in four parts at k-steps epos(0..3) of row tile T, and at
+    // k-step kinit the accumulator of row tile T + 1 is preloaded with its biases.
+    static constexpr int estep(int KS) { return (KS - 8) / 4 < 1 ? 1 : (KS - 8) / 4; }
+    static constexpr int epos(int q, int KS) { return 1 + q * estep(KS); }
+    static constexpr int kinit(int KS) { return epos(3, KS) + 1; }
+    static constexpr int LPW = SF / WAVES;                                      // loads per wave and stage
     static constexpr int HL = NH == 1 ? H1 : (NH == 2 ? H2 : H3);              // width entering the ->1 layer
     static constexpr int bias_floats = H1 + H2 + H3 + HL;
-    static constexpr int slots() { return (4 * slot_frags() * 1024 + 4 * bias_floats <= 160 * 1024) ? 4 : 3; }
-    static constexpr int lds_bytes() { return slots() * slot_frags() * 1024 + 4 * bias_floats; }
-    static_assert(nout(0) % (32 * unit(0)) == 0, "layer 1 width");
-    static_assert(NH < 2 || nout(1) % (32 * unit(1)) == 0, "layer 2 width");
-    static_assert(NH < 3 || nout(2) % (32 * unit(2)) == 0, "layer 3 width");
+    static constexpr int ring_bytes = SLOTS * SF * 1024;
+    static constexpr int lds_bytes = ring_bytes + 4 * bias_floats;
+    static_assert(SF % WAVES == 0, "every wave moves the same number of fragments per stage");
+    static_assert(nfl(0) % SF == 0 && nfl(1) % SF == 0 && nfl(2) % SF == 0, "a stage lies inside one layer");
+    static_assert(SLOTS >= 3, "a stage is confirmed half a stage before its first read");
+    static_assert(lds_bytes <= 160 * 1024, "LDS");
 };
 
-// Copy stage i of the weight stream global -> LDS slot: a wave moves whole 1 KB
+// Copy stage I of the weight stream global -> LDS slot: a wave moves whole 1 KB
 // fragments, no register staging.
-template <class C, int WAVES, int I>
+template <class C, int WAVES, int SF, int SLOTS, int I>
 __device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
 {
-    if constexpr (I < C::total()) {
-        constexpr int l = C::layer_of(I), nf = C::frags(l);
+    if constexpr (I < C::ns()) {
+        constexpr int l = C::flayer(I * SF);
         const int lane = threadIdx.x & 63;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const char *src = pk.w[l] + (size_t)(I - C::first(l)) * nf * 1024 + lane * 16;
-        const uint32_t dst = (uint32_t)(uintptr_t)(lptr_t)lds + (I % C::slots()) * C::slot_frags() * 1024;
+        const char *src = pk.w[l] + (size_t)(I * SF - C::fbase(l)) * 1024 + lane * 16;
+        const uint32_t dst = lds_address(lds) + (I % SLOTS) * SF * 1024;
 #pragma unroll
-        for (int f0 = 0; f0 < nf; f0 += WAVES) dma16(src + (f0 + wave) * 1024, dst + (f0 + wave) * 1024);
+        for (int f0 = 0; f0 < SF; f0 += WAVES) dma16(src + (f0 + wave) * 1024, dst + (f0 + wave) * 1024);
     }
-}
-
-// Epilogue of one 32-feature row tile, cut into four parts (q = 0..3: the four
-// features 8q + 4h + i a lane holds): bias + ReLU, then either two bf16
-// B-fragments of the next layer (lo <- q = 0, 1; hi <- q = 2, 3) or, for the
-// last hidden layer, the partial dot with the ->1 layer's weights.
-template <int CT, bool FINAL, int Q>
-__device__ __forceinline__ void epilogue_part(const f32x16 (&acc)[CT], bf16x8 (&lo)[CT], bf16x8 (&hi)[CT],
-                                              float (&zpart)[CT], const float *sbias, const float *swl, int h)
-{
-    const float4 bv = *(const float4 *)(sbias + 8 * Q + 4 * h);
-    if constexpr (FINAL) {
-        const float4 wl = *(const float4 *)(swl + 8 * Q + 4 * h);
-#pragma unroll
-        for (int c = 0; c < CT; ++c) {
-            zpart[c] += wl.x * relu(acc[c][4 * Q + 0] + bv.x) + wl.y * relu(acc[c][4 * Q + 1] + bv.y) +
-                        wl.z * relu(acc[c][4 * Q + 2] + bv.z) + wl.w * relu(acc[c][4 * Q + 3] + bv.w);
-            asm volatile("" : "+v"(zpart[c]));      // keep the partial dot here (see the convert below)
-        }
-    } else {
-#pragma unroll
-        for (int c = 0; c < CT; ++c) {
-            bf16x8 &dst = Q < 2 ? lo[c] : hi[c];
-            constexpr int o = 4 * (Q & 1);
-            dst[o + 0] = (__bf16)relu(acc[c][4 * Q + 0] + bv.x);
-            dst[o + 1] = (__bf16)relu(acc[c][4 * Q + 1] + bv.y);
-            dst[o + 2] = (__bf16)relu(acc[c][4 * Q + 2] + bv.z);
-            dst[o + 3] = (__bf16)relu(acc[c][4 * Q + 3] + bv.w);
-            // convert now: left alone the compiler keeps the fp32 values (twice the registers) until first use
-            if constexpr ((Q & 1) == 1) asm volatile("" : "+v"(dst));
-        }
-    }
-}
-
-// MFMA loop of one row tile, acc = W_tile . in, with the four epilogue parts of
-// the PREVIOUS row tile slipped in between the groups of MFMAs: the vector ALU
-// work then runs while the matrix cores are busy instead of after them.
-// A fragments come from LDS in groups of G, the next group in flight while the
-// current one feeds the matrix cores; the scheduling barriers keep the compiler
-// from hoisting every load of the tile (which would not fit the register file
-// next to the activations).
-template <int CT, int KS, class Epi>
-__device__ __forceinline__ void tile_mfma(const char *w, const bf16x8 (&in)[CT][KS], f32x16 (&acc)[CT], Epi &&epi)
-{
-#pragma unroll
-    for (int c = 0; c < CT; ++c)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
-    constexpr int G = 4, NG = KS / G;
-    static_assert(KS % G == 0 && NG >= 2, "k-steps per tile");
-    bf16x8 a[2][G];
-#pragma unroll
-    for (int t = 0; t < G; ++t) a[0][t] = *(const bf16x8 *)(w + t * 1024);
-    __builtin_amdgcn_sched_barrier(0);
-    static_for<0, NG>([&](auto gi) {
-        constexpr int g = decltype(gi)::value;
-        if constexpr (g + 1 < NG) {
-#pragma unroll
-            for (int t = 0; t < G; ++t) a[(g + 1) & 1][t] = *(const bf16x8 *)(w + ((g + 1) * G + t) * 1024);
-        }
-#pragma unroll
-        for (int t = 0; t < G; ++t) {
-#pragma unroll
-            for (int c = 0; c < CT; ++c)
-                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[g & 1][t], in[c][g * G + t], acc[c], 0, 0, 0);
-        }
-        // epilogue parts of the previous tile that belong to this group
-        static_for<0, 4>([&](auto qi) {
-            constexpr int q = decltype(qi)::value;
-            // never in the last group: the first tile of a layer consumes, in its last
-            // k-steps, the fragments the previous layer's last tile completes here
-            constexpr int at = (q * NG) / 4 < NG - 2 ? (q * NG) / 4 : NG - 2;
-            if constexpr (at == g) epi(qi);
-        });
-        __builtin_amdgcn_sched_barrier(0);
-    });
 }
 
 // K1: layer-1 contraction after the user fold; H1..H3: hidden widths (0 = absent).
-template <int K1, int H1, int H2, int H3, int CT, int WAVES>
+// One wave = 32 candidates; a block = WAVES waves sharing the weight ring.
+//
+// The body is one straight line of nf() steps, one MFMA each.  Step F
+//   - asks LDS for the fragment of step F + RING - 1 (a ring of RING fragment registers keeps the
+//     matrix cores fed across row tiles and stages without a bubble at their boundaries),
+//   - issues its MFMA,
+//   - may carry a part of the previous row tile's epilogue (ReLU, conversion to the next layer's
+//     B fragments, or the partial dot with the ->1 layer) so the vector ALU works under the MFMAs,
+//   - may preload the next row tile's accumulator with its biases (the bias add costs nothing then),
+//   - in the middle of stage I: waits for its own share of stage I + 1, meets the other waves at
+//     the block barrier (after which stage I + 1 is complete in LDS and stage I - 1 is no longer
+//     read by anyone) and refills the slot of stage I - 1 with stage I + SLOTS - 1.
+// The barrier is hand-issued: the compiler's own would first drain the LDS reads in flight.
+template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS>
 __global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, const char *__restrict__ X, XLayout xl,
                                                            MlpPack pk, const float *__restrict__ bias1)
 {
-    using C = Chain<K1, H1, H2, H3, WAVES>;
-    constexpr int THREADS = WAVES * 64, ROWS = WAVES * 32 * CT, NS = C::total(), D = C::slots() - 1;
+    using C = Chain<K1, H1, H2, H3, WAVES, SF, SLOTS>;
+    constexpr int THREADS = WAVES * 64, ROWS = WAVES * 32, NF = C::nf(), NS = C::ns(), NT = C::nt(), D = SLOTS - 1;
+    constexpr int RING = 8;
     static_assert(ROW_BLOCK % ROWS == 0, "tile");
+    static_assert(SF / 2 >= RING, "fragment prefetch never runs past a confirmed stage");
     extern __shared__ __align__(16) char lds[];                 // the weight ring, then biases and last-layer weights
-    float *sb1 = (float *)(lds + C::slots() * C::slot_frags() * 1024), *sb2 = sb1 + H1, *sb3 = sb2 + H2, *swl = sb3 + H3;
+    float *sb1 = (float *)(lds + C::ring_bytes), *sb2 = sb1 + H1, *sb3 = sb2 + H2, *swl = sb3 + H3;
 
     const int tile = blockIdx.x;
     const int row0 = tile * ROWS;
@@ -175,13 +125,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, co
     // The block's start is a chain of dependent memory round trips; keep it short: the weight stream
     // and the input rows do not depend on the request lookup (a padded row is still inside the
     // workspace), so they are asked for first.
-    static_for<0, D>([&](auto s) { issue_stage<C, WAVES, decltype(s)::value>(pk, lds); });
-    bf16x8 xin[CT][K1 / 16];
+    static_for<0, D>([&](auto s) { issue_stage<C, WAVES, SF, SLOTS, decltype(s)::value>(pk, lds); });
+    bf16x8 xin[K1 / 16];
+    {
+        const char *xr = X + x_offset(xl, row0 + wave * 32 + col, h);
 #pragma unroll
-    for (int c = 0; c < CT; ++c) {
-        const char *xr = X + x_offset(xl, row0 + (wave * CT + c) * 32 + col, h);
-#pragma unroll
-        for (int j = 0; j < K1 / 16; ++j) xin[c][j] = *(const bf16x8 *)(xr + (size_t)(2 * j) * xl.piece_stride);
+        for (int j = 0; j < K1 / 16; ++j) xin[j] = *(const bf16x8 *)(xr + (size_t)(2 * j) * xl.piece_stride);
     }
     const int r = b.blk_req[tile / (ROW_BLOCK / ROWS)];
     const ReqDesc rd = b.reqs[r < 0 ? 0 : r];
@@ -199,93 +148,102 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, co
     wait_vmcnt<0>();
     __syncthreads();
 
-    float zpart[CT];
-#pragma unroll
-    for (int c = 0; c < CT; ++c) zpart[c] = 0.f;
-    bf16x8 h1[CT][C::NH >= 2 ? H1 / 16 : 1];
-    bf16x8 h2[CT][C::NH >= 3 ? H2 / 16 : 1];
-    f32x16 accA[CT], accB[CT];              // current / previous row tile (ping-pong)
-    bf16x8 lo[CT], hi[CT];
+    float zpart = 0.f;
+    bf16x8 h1[C::NH >= 2 ? H1 / 16 : 1];
+    bf16x8 h2[C::NH >= 3 ? H2 / 16 : 1];
+    f32x16 acc[2];                          // row tiles T and T - 1 (ping-pong)
+    bf16x8 areg[RING];
+    float4 wlv[4];                          // the ->1 layer's weights for the row tile in flight
 
-    // epilogue part Q of row tile RT of layer L, acting on `acc`; when the tile's
-    // last part is done its two fragments are filed as k-steps 2 RT, 2 RT + 1 of the next layer
-    auto epi_part = [&](auto lc, auto rtc, auto qc, const f32x16(&acc)[CT]) {
-        constexpr int L = decltype(lc)::value, RT = decltype(rtc)::value, Q = decltype(qc)::value;
-        constexpr bool FIN = L == C::NH - 1;
-        const float *sb = L == 0 ? sb1 : (L == 1 ? sb2 : sb3);
-        epilogue_part<CT, FIN, Q>(acc, lo, hi, zpart, sb + 32 * RT, swl + 32 * RT, h);
-        if constexpr (!FIN && Q == 3) {
+    const char *wl0 = lds + lane * 16;
+    auto bias_of = [&](int T) { const int L = C::tlayer(T); return (L == 0 ? sb1 : (L == 1 ? sb2 : sb3)) + 32 * C::trt(T) + 4 * h; };
+    auto preload_acc = [&](auto tc) {                           // acc of row tile T <- its biases
+        constexpr int T = decltype(tc)::value;
+        const float *sb = bias_of(T);
 #pragma unroll
-            for (int c = 0; c < CT; ++c) {
-                if constexpr (L == 0) {
-                    h1[c][2 * RT] = lo[c];
-                    h1[c][2 * RT + 1] = hi[c];
-                } else {
-                    h2[c][2 * RT] = lo[c];
-                    h2[c][2 * RT + 1] = hi[c];
-                }
-            }
+        for (int q = 0; q < 4; ++q) {
+            const float4 bv = *(const float4 *)(sb + 8 * q);
+            acc[T & 1][4 * q + 0] = bv.x;
+            acc[T & 1][4 * q + 1] = bv.y;
+            acc[T & 1][4 * q + 2] = bv.z;
+            acc[T & 1][4 * q + 3] = bv.w;
+        }
+    };
+    // part Q of the epilogue of row tile T: the four features 8 Q + 4 h + i of this lane's candidate
+    auto epi_part = [&](auto tc, auto qc) {
+        constexpr int T = decltype(tc)::value, Q = decltype(qc)::value, L = C::tlayer(T), RT = C::trt(T);
+        const f32x16 &a = acc[T & 1];
+        if constexpr (L == C::NH - 1) {
+            zpart += wlv[Q].x * relu(a[4 * Q + 0]) + wlv[Q].y * relu(a[4 * Q + 1]) + wlv[Q].z * relu(a[4 * Q + 2]) +
+                     wlv[Q].w * relu(a[4 * Q + 3]);
+            asm volatile("" : "+v"(zpart));         // keep the partial dot here
+        } else {
+            // slot s of half h <-> feature 16 j + 8 (s / 4) + 4 h + s % 4: parts 0, 1 fill k-step 2 RT, parts 2, 3 k-step 2 RT + 1
+            bf16x8 &dst = [&]() -> bf16x8 & {
+                if constexpr (L == 0)
+                    return h1[2 * RT + (Q >> 1)];
+                else
+                    return h2[2 * RT + (Q >> 1)];
+            }();
+            constexpr int o = 4 * (Q & 1);
+            dst[o + 0] = (__bf16)relu(a[4 * Q + 0]);
+            dst[o + 1] = (__bf16)relu(a[4 * Q + 1]);
+            dst[o + 2] = (__bf16)relu(a[4 * Q + 2]);
+            dst[o + 3] = (__bf16)relu(a[4 * Q + 3]);
+            // convert now: left alone the compiler keeps the fp32 values (twice the registers) until first use
+            if constexpr ((Q & 1) == 1) asm volatile("" : "+v"(dst));
         }
     };
 
-    // row tiles are numbered through all hidden layers: T -> (layer, row tile in layer)
-    constexpr int RT0 = H1 / 32, RT1 = C::NH > 1 ? H2 / 32 : 0, RT2 = C::NH > 2 ? H3 / 32 : 0, NT = RT0 + RT1 + RT2;
-    auto run_tile = [&](auto tc, const char *w) {
-        constexpr int T = decltype(tc)::value;
-        constexpr int L = T < RT0 ? 0 : (T < RT0 + RT1 ? 1 : 2);
-        constexpr int RT = T - (L == 0 ? 0 : (L == 1 ? RT0 : RT0 + RT1));
-        constexpr int PT = T - 1;                                       // previous tile (epilogue pending)
-        constexpr int PL = PT < RT0 ? 0 : (PT < RT0 + RT1 ? 1 : 2);
-        constexpr int PRT = PT - (PL == 0 ? 0 : (PL == 1 ? RT0 : RT0 + RT1));
-        auto &cur = (T & 1) ? accB : accA;
-        auto &prev = (T & 1) ? accA : accB;
-        auto epi = [&](auto qc) {
-            if constexpr (T > 0) epi_part(IC<PL>{}, IC<PRT>{}, qc, prev);
-        };
-        if constexpr (L == 0)
-            tile_mfma<CT, K1 / 16>(w, xin, cur, epi);
-        else if constexpr (L == 1)
-            tile_mfma<CT, H1 / 16>(w, h1, cur, epi);
-        else
-            tile_mfma<CT, H2 / 16>(w, h2, cur, epi);
-    };
+    preload_acc(IC<0>{});
+    static_for<0, RING - 1>([&](auto fc) {
+        constexpr int F = decltype(fc)::value;
+        areg[F] = *(const bf16x8 *)(wl0 + C::foff(F));
+    });
+    __builtin_amdgcn_sched_barrier(0);
 
-    static_for<0, NS>([&](auto si) {
-        constexpr int I = decltype(si)::value;
-        constexpr int l = C::layer_of(I), U = C::unit(l), KS = C::ks(l);
-        __builtin_amdgcn_sched_barrier(0);
-        issue_stage<C, WAVES, I + D>(pk, lds);       // its slot was read last in stage I - 1
-        const char *w0 = lds + (I % C::slots()) * C::slot_frags() * 1024 + lane * 16;
-        static_for<0, U>([&](auto uc) {
-            constexpr int u = decltype(uc)::value;
-            constexpr int T = (l == 0 ? 0 : (l == 1 ? RT0 : RT0 + RT1)) + (I - C::first(l)) * U + u;
-            run_tile(IC<T>{}, w0 + u * KS * 1024);
-        });
-        if constexpr (I + 1 < NS) {
-            // stage I + 1 must have landed; stages I + 2 .. I + D may still be in flight
-            constexpr int pend = [] { int n = 0; for (int s = I + 2; s <= I + D; ++s) n += C::loads(s); return n; }();
-            wait_vmcnt<pend>();
-            __syncthreads();
+    static_for<0, NF>([&](auto fc) {
+        constexpr int F = decltype(fc)::value;
+        constexpr int L = C::flayer(F), T = C::ftile(F), K = C::fk(F), KS = C::ks(L), I = F / SF;
+        if constexpr (F % SF == SF / 2 && I + 1 < NS) {
+            // stage I + 1 must have landed; the stages after it (as far as they exist) may stay in flight
+            constexpr int last = I + D - 1 < NS - 1 ? I + D - 1 : NS - 1;
+            wait_vmcnt<(last - (I + 1)) * C::LPW>();
+            asm volatile("s_barrier" ::: "memory");
+            issue_stage<C, WAVES, SF, SLOTS, I + D>(pk, lds);
+        }
+        if constexpr (F + RING - 1 < NF) areg[(F + RING - 1) % RING] = *(const bf16x8 *)(wl0 + C::foff(F + RING - 1));
+        if constexpr (L == 0)
+            acc[T & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[F % RING], xin[K], acc[T & 1], 0, 0, 0);
+        else if constexpr (L == 1)
+            acc[T & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[F % RING], h1[K], acc[T & 1], 0, 0, 0);
+        else
+            acc[T & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[F % RING], h2[K], acc[T & 1], 0, 0, 0);
+        if constexpr (T > 0) {
+            static_for<0, 4>([&](auto qc) {
+                if constexpr (K == C::epos(decltype(qc)::value, KS)) epi_part(IC<T - 1>{}, qc);
+            });
+        }
+        if constexpr (K == C::kinit(KS)) {
+            if constexpr (T + 1 < NT) preload_acc(IC<T + 1>{});
+            if constexpr (L == C::NH - 1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) wlv[q] = *(const float4 *)(swl + 32 * C::trt(T) + 8 * q + 4 * h);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
     });
-    {   // the last tile's epilogue has nothing left to hide behind
-        constexpr int PL = C::NH - 1, PRT = (PL == 0 ? RT0 : (PL == 1 ? RT1 : RT2)) - 1;
-        auto &prev = ((NT - 1) & 1) ? accB : accA;
-        static_for<0, 4>([&](auto qc) { epi_part(IC<PL>{}, IC<PRT>{}, qc, prev); });
-    }
+    // the last row tile's epilogue has nothing left to hide behind
+    static_for<0, 4>([&](auto qc) { epi_part(IC<NT - 1>{}, qc); });
 
     const float bl = pk.blast ? pk.blast[0] : 0.f;
-#pragma unroll
-    for (int c = 0; c < CT; ++c) {
-        float z = zpart[c] + __shfl_xor(zpart[c], 32, 64) + bl;
-        const int local = local0 + (wave * CT + c) * 32 + col;
-        if (h == 0 && local < rd.n_cand) {
-            const int64_t id = rd.cand_ids[local];
-            if (id < 0 || id >= m.n_items) z = __uint_as_float(0x7FC00000u);
-            rd.logits_out[local] = z;
-            if (rd.scores_out) rd.scores_out[local] = 1.0f / (1.0f + __expf(-z));
-        }
+    float z = zpart + __shfl_xor(zpart, 32, 64) + bl;
+    const int local = local0 + wave * 32 + col;
+    if (h == 0 && local < rd.n_cand) {
+        const int64_t id = rd.cand_ids[local];
+        if (id < 0 || id >= m.n_items) z = __uint_as_float(0x7FC00000u);
+        rd.logits_out[local] = z;
+        if (rd.scores_out) rd.scores_out[local] = 1.0f / (1.0f + __expf(-z));
     }
 }
 
@@ -315,14 +273,14 @@ hipError_t pack_frag(const void *W, int n_in, int col0, int N, int K, bool from_
 }
 
 // ---- dispatch -----------------------------------------------------------------
-template <int K1, int H1, int H2, int H3, int CT, int WAVES>
+template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS>
 static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, const MlpPack &pk, const float *bias1,
                               hipStream_t s)
 {
-    using C = Chain<K1, H1, H2, H3, WAVES>;
-    constexpr int LDS = C::lds_bytes();
-    constexpr int ROWS = WAVES * 32 * CT;
-    auto kern = k_mlp_mfma<K1, H1, H2, H3, CT, WAVES>;
+    using C = Chain<K1, H1, H2, H3, WAVES, SF, SLOTS>;
+    constexpr int LDS = C::lds_bytes;
+    constexpr int ROWS = WAVES * 32;
+    auto kern = k_mlp_mfma<K1, H1, H2, H3, WAVES, SF, SLOTS>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -350,9 +308,9 @@ hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const
 {
     if (b.n_blk == 0) return hipSuccess;
     switch (variant) {
-    case 0: return launch_spec<192, 256, 128, 0, 1, 8>(m, b, X, pk, bias1, s);
-    case 1: return launch_spec<192, 512, 256, 0, 1, 8>(m, b, X, pk, bias1, s);
-    case 2: return launch_spec<384, 256, 0, 0, 1, 8>(m, b, X, pk, bias1, s);
+    case 0: return launch_spec<192, 256, 128, 0, 8, 32, 4>(m, b, X, pk, bias1, s);
+    case 1: return launch_spec<192, 512, 256, 0, 8, 32, 4>(m, b, X, pk, bias1, s);
+    case 2: return launch_spec<384, 256, 0, 0, 8, 32, 4>(m, b, X, pk, bias1, s);
     default: return hipErrorInvalidValue;
     }
 }
