@@ -56,6 +56,7 @@ struct aif_ctx {
     DevBuf bias1;                     // fp32 [max_users, H1]
     DevBuf bad;                       // int32 counter
     size_t x_rows = 0;
+    int n_cu = 256;                   // compute units of the device (sizes the attention groups)
 
     // descriptor staging ring
     char *h_stage = nullptr;          // pinned
@@ -238,7 +239,15 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
     HIP_TRY(nullptr, hipMemsetAsync(c->bad.p, 0, 4, s));
 
     const size_t n_blk_max = c->x_rows / ROW_BLOCK;
-    size_t sb = (size_t)c->max_users * sizeof(ReqDesc) + n_blk_max * sizeof(int32_t);
+    size_t sb = (size_t)c->max_users * sizeof(ReqDesc) + (n_blk_max + 4) * sizeof(int32_t) +
+                attn_max_groups(c->x_rows, c->max_users) * sizeof(AttnGroup);
+    {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        HIP_TRY(nullptr, hipGetDevice(&dev));
+        HIP_TRY(nullptr, hipGetDeviceProperties(&prop, dev));
+        c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    }
     const size_t tk = (size_t)c->max_users * sizeof(TopkDesc);
     if (tk > sb) sb = tk;
     c->slot_bytes = (sb + 255) / 256 * 256;
@@ -329,7 +338,11 @@ aif_status aif_score_batch(aif_ctx *c, const aif_request *reqs, int32_t n_req, v
     b.blk_req = (const int32_t *)(d + (size_t)n_req * sizeof(ReqDesc));
     b.n_req = n_req;
     b.n_blk = rows / ROW_BLOCK;
-    const size_t bytes = (size_t)n_req * sizeof(ReqDesc) + (size_t)b.n_blk * sizeof(int32_t);
+    // groups of tiles for the attention kernel that keeps K/V resident, 16-byte aligned after blk_req
+    const size_t goff = ((size_t)n_req * sizeof(ReqDesc) + (size_t)b.n_blk * sizeof(int32_t) + 15) / 16 * 16;
+    b.n_groups = c->mfma.attn ? attn_plan_groups(m, hd, n_req, c->n_cu, (AttnGroup *)(h + goff)) : 0;
+    b.groups = (const AttnGroup *)(d + goff);
+    const size_t bytes = goff + (size_t)b.n_groups * sizeof(AttnGroup);
     HIP_TRY(c, hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, s));
 
     hipEvent_t *pe = nullptr;

@@ -25,12 +25,20 @@ struct ReqDesc {
     int32_t index;              // position in the batch
 };
 
+// A run of 32-candidate tiles of ONE request, the unit of work of the attention kernel that keeps
+// the request's K/V resident in LDS: tiles [t0, t1), numbered within the request.
+struct AttnGroup {
+    int32_t r, t0, t1, pad;
+};
+
 // What one call hands to its kernels.
 struct Batch {
     const ReqDesc *reqs;        // device, [n_req]
     const int32_t *blk_req;     // device, [n_blk]: request owning each ROW_BLOCK of the workspace
+    const AttnGroup *groups;    // device, [n_groups]; n_groups = 0: the batch does not use them
     int32_t n_req;
     int32_t n_blk;
+    int32_t n_groups;
 };
 
 struct Model {

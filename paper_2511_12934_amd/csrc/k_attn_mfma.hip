@@ -302,6 +302,254 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
     }
 }
 
+// ---------------------------------------------------------------------------
+// The same computation with the request's K/V RESIDENT in LDS.  All candidates of
+// a request share its behaviour sequence (Sec. 3.1), so when the packed K/V of all
+// heads fit in one CU's LDS a workgroup loads them once and then serves a whole
+// group of 32-candidate tiles of that request: after the one barrier that follows
+// the load its 16 waves run free of each other, one tile at a time each, and the
+// four waves of a SIMD fill one another's waits.  Inside a tile the S product of
+// key tile t + 1 is issued before the exponentials of key tile t, so the matrix
+// cores work under the vector ALU.  Per candidate the arithmetic, and its order,
+// is that of k_attn_mfma: the two kernels give the same bits.
+// ---------------------------------------------------------------------------
+constexpr int RES_WAVES = 16;
+constexpr int RES_LDS_FRAGS = 152;            // 1 KB fragments of K/V that may stay resident
+constexpr int RES_MAX_HEADS = 64;
+constexpr int RES_MAX_ITEM_PIECES = 256;      // d_item / 8 the Hadamard operand may have to stay in LDS
+constexpr int RES_LDS_BYTES = RES_LDS_FRAGS * 1024 + RES_MAX_HEADS * 4 + RES_MAX_ITEM_PIECES * 16;
+
+template <int DH>
+__global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, char *__restrict__ X, XLayout xl,
+                                                             const char *__restrict__ kvpack, size_t pack_stride,
+                                                             const float *__restrict__ kmax, int nktp)
+{
+    constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32;
+    extern __shared__ __align__(16) char lds[];
+    float *skm = (float *)(lds + RES_LDS_FRAGS * 1024);         // [n_heads] max |k_t|
+    bf16x8 *su = (bf16x8 *)(skm + RES_MAX_HEADS);               // the request's Hadamard operand
+
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), col = lane & 31, h = lane >> 5;
+    const AttnGroup g = b.groups[blockIdx.x];
+    const int r = g.r;
+    const ReqDesc rd = b.reqs[r];
+    const int L = rd.seq_len, H = m.n_heads;
+    const int nkt = (L + 31) >> 5, nkt2 = (nkt + 1) & ~1, head_frags = nkt2 * FR;
+    const char *pk = kvpack + (size_t)r * pack_stride;
+
+    // the whole pack -> LDS, heads back to back (in the pack a head takes nktp key tiles)
+    {
+        const uint32_t ring = lds_address(lds);
+        const int nfrag = H * head_frags;
+        for (int f = wave; f < nfrag; f += RES_WAVES) {
+            const int hd = f / head_frags, rem = f - hd * head_frags;
+            dma16(pk + ((size_t)hd * nktp * FR + rem) * 1024 + lane * 16, ring + f * 1024);
+        }
+    }
+    for (int hd = wave; hd < H; hd += RES_WAVES) {
+        float km = 0.f;
+        for (int i = lane; i < nkt2 / 2; i += 64) km = fmaxf(km, kmax[((size_t)r * H + hd) * (nktp / 2) + i]);
+#pragma unroll
+        for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
+        if (lane == 0) skm[hd] = km;
+    }
+    if (m.cross_mode == 1)
+        for (int i = threadIdx.x; i < m.d_item / 8; i += RES_WAVES * 64) su[i] = ((const bf16x8 *)rd.cross_vecs)[i];
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    const float c = LOG2E / sqrtf((float)DH);
+    const char *kv0 = lds + lane * 16;
+    const int pc_cross = (m.d_item + m.d_attn) / 8;             // first piece of the cross block
+    const bool hadamard = m.cross_mode == 1;
+
+    // A wave's work is the sequence of (tile, head) items of its tiles.  The only global reads an
+    // item needs are its query pieces; they are asked for as soon as the previous item has issued
+    // its last S product (the registers are free from then on), so their latency passes under that
+    // item's last exponentials, second product and stores instead of stalling the wave.
+    const int my_tiles = g.t1 - g.t0 > wave ? (g.t1 - g.t0 - wave + RES_WAVES - 1) / RES_WAVES : 0;
+    const int n_items = my_tiles * H;
+    auto row_of = [&](int it) { return X + x_offset(xl, rd.row_base + (g.t0 + wave + RES_WAVES * (it / H)) * 32 + col, 0); };
+    bf16x8 q[JS];
+    if (n_items > 0) {
+        const char *xr = row_of(0);
+#pragma unroll
+        for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(2 * j + h) * xl.piece_stride);
+    }
+    for (int it = 0; it < n_items; ++it) {
+        const int hd = it % H;
+        const int local = (g.t0 + wave + RES_WAVES * (it / H)) * 32 + col;
+        const bool live = local < rd.n_cand;
+        char *xrow = row_of(it);
+        auto piece = [&](int p) { return (bf16x8 *)(xrow + (size_t)p * xl.piece_stride); };
+
+        // real-time half of the cross features: the query pieces ARE item-vector pieces (no W_q here),
+        // so the ones this lane holds are multiplied in place; the stores drain under the attention loop
+        if (hadamard && live) {
+#pragma unroll
+            for (int j = 0; j < JS; ++j) {
+                const int pc = hd * (DH / 8) + 2 * j + h;
+                if (pc < m.d_item / 8) {
+                    const bf16x8 u = su[pc];
+                    bf16x8 o8;
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)q[j][s] * (float)u[s]);
+                    *piece(pc_cross + pc) = o8;
+                }
+            }
+            // item-vector pieces beyond the attention width (d_item > d_attn)
+            if (hd == H - 1)
+                for (int pc = m.d_attn / 8 + h; pc < m.d_item / 8; pc += 2) {
+                    const bf16x8 e = *piece(pc), u = su[pc];
+                    bf16x8 o8;
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)e[s] * (float)u[s]);
+                    *piece(pc_cross + pc) = o8;
+                }
+        }
+
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < JS; ++j) {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) ss += (float)q[j][s] * (float)q[j][s];
+        }
+        ss += __shfl_xor(ss, 32, 64);
+        const char *kvh = kv0 + (size_t)hd * head_frags * 1024;
+        auto s_tile = [&](int kt) {
+            const char *base = kvh + kt * FR * 1024;
+            f32x16 S;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) S[i] = 0.f;
+#pragma unroll
+            for (int j = 0; j < JS; ++j)
+                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + j * 1024), q[j], S, 0, 0, 0);
+            return S;
+        };
+        float mc = c * sqrtf(ss) * 1.001f * skm[hd];
+        if (__any(mc > BOUND_LIMIT)) {
+            // rare: take the true maximum with an extra pass over K
+            float mx = -INFINITY;
+            for (int kt = 0; kt < nkt; ++kt) {
+                const f32x16 S = s_tile(kt);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (t < L) mx = fmaxf(mx, S[v]);
+                }
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            mc = c * mx;
+        }
+
+        f32x16 O[FT];
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[ft][i] = 0.f;
+        float l = 0.f;
+        // exponentials, row sums and the second product of key tile kt
+        auto finish_tile = [&](int kt, const f32x16 &S, bool ragged) {
+            const char *base = kvh + kt * FR * 1024;
+            float p[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(fmaf(S[v], c, -mc));
+            if (ragged) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (t >= L) p[v] = 0.f;
+                }
+            }
+            bf16x8 P0, P1;
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                l += p[v] + p[8 + v];
+                P0[v] = (__bf16)p[v];
+                P1[v] = (__bf16)p[8 + v];
+            }
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft) {
+                O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + (JS + ft) * 1024), P0, O[ft], 0, 0, 0);
+                O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + (JS + FT + ft) * 1024), P1, O[ft], 0, 0, 0);
+            }
+        };
+        // S of key tile t + 1 goes to the matrix cores BEFORE the exponentials of key tile t (the
+        // scheduling barriers hold the order), two tiles per trip so the accumulators swap without copies
+        f32x16 S;
+        if (nkt > 0) {
+            S = s_tile(0);
+            int kt = 0;
+            for (; kt + 2 < nkt; kt += 2) {
+                const f32x16 S1 = s_tile(kt + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                finish_tile(kt, S, false);
+                __builtin_amdgcn_sched_barrier(0);
+                S = s_tile(kt + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                finish_tile(kt + 1, S1, false);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (kt + 1 < nkt) {
+                const f32x16 S1 = s_tile(kt + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                finish_tile(kt, S, false);
+                S = S1;
+            }
+        }
+        // the last S product of this item is on its way: the next item's query may take the registers
+        if (it + 1 < n_items) {
+            const char *xr = row_of(it + 1);
+            const int hn = (it + 1) % H;
+#pragma unroll
+            for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(hn * (DH / 8) + 2 * j + h) * xl.piece_stride);
+        }
+        if (nkt > 0) finish_tile(nkt - 1, S, 32 * nkt > L);
+
+        l += __shfl_xor(l, 32, 64);
+        const float inv = L > 0 ? 1.0f / l : 0.f;
+        if (live) {
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(O[ft][4 * qd + i] * inv);
+                    *((bf16x4 *)piece((m.d_item + hd * DH) / 8 + 4 * ft + qd) + h) = o4;
+                }
+        }
+    }
+}
+
+// Host: groups of tiles for k_attn_res, or 0 when some request's K/V do not fit.
+size_t attn_max_groups(size_t x_rows, int max_users) { return x_rows / (32 * RES_WAVES) + (size_t)max_users + 1; }
+
+int attn_plan_groups(const Model &m, const ReqDesc *reqs, int n_req, int n_cu, AttnGroup *out)
+{
+    if (m.n_heads > RES_MAX_HEADS || m.d_item / 8 > RES_MAX_ITEM_PIECES) return 0;
+    const int FR = m.d_head / 8;
+    long total = 0;
+    for (int r = 0; r < n_req; ++r) {
+        const int nkt2 = ((((reqs[r].seq_len + 31) >> 5) + 1) & ~1);
+        if ((long)m.n_heads * nkt2 * FR > RES_LDS_FRAGS) return 0;
+        total += (reqs[r].n_cand + 31) / 32;
+    }
+    // about one group per CU, each a whole number of rounds of the 16 waves
+    long per = (total + n_cu - 1) / n_cu;
+    per = (per + RES_WAVES - 1) / RES_WAVES * RES_WAVES;
+    if (per < RES_WAVES) per = RES_WAVES;
+    int n = 0;
+    for (int r = 0; r < n_req; ++r) {
+        const int tiles = (reqs[r].n_cand + 31) / 32;
+        if (tiles == 0) continue;
+        const int ng = (int)((tiles + per - 1) / per);
+        for (int i = 0; i < ng; ++i)          // even split: sizes differ by at most one tile
+            out[n++] = AttnGroup{r, (int)((long)tiles * i / ng), (int)((long)tiles * (i + 1) / ng), 0};
+    }
+    return n;
+}
+
 // ---- dispatch -----------------------------------------------------------------
 int attn_mfma_variant(const Model &m, bool has_wq)
 {
@@ -326,6 +574,19 @@ static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char
     constexpr int LDS = 4 * 2 * (DH / 8) * 1024, ROWS = WAVES * 32;
     if (nktp > 0)
         hipLaunchKernelGGL(k_pack_kv<DH>, dim3(nktp / 2, m.n_heads, b.n_req), dim3(256), 0, s, m, b, kvpack, stride, kmax, nktp);
+    if (b.n_groups > 0) {
+        constexpr int RES_LDS = RES_LDS_BYTES;
+        auto kern = k_attn_res<DH>;
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, RES_LDS);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(kern, dim3(b.n_groups), dim3(RES_WAVES * 64), RES_LDS, s, m, b, (char *)X, x_layout(m),
+                           (const char *)kvpack, stride, (const float *)kmax, nktp);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL((k_attn_mfma<DH, WAVES>), dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), LDS, s, m, b,
                        (char *)X, x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp);
     return hipGetLastError();

@@ -31,6 +31,13 @@ hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, const void 
                      MfmaPlan &plan, hipStream_t s);
 void mfma_release(MfmaPlan &plan);
 
+// Host side: can every request of the batch keep its packed K/V (all heads) in one CU's LDS?  If so,
+// cut the requests into groups of tiles for the resident attention kernel (about one group per CU and
+// round of 16 waves) and return their number; 0 if some request does not fit (the streaming kernel
+// serves the batch then).  `out` has room for attn_max_groups() entries.
+int attn_plan_groups(const Model &m, const ReqDesc *reqs /*host*/, int n_req, int n_cu, AttnGroup *out /*host*/);
+size_t attn_max_groups(size_t x_rows, int max_users);
+
 hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, hipStream_t s);
 
 // bias_f32[l] / wlast_f32: the context's fp32 copies (bias of layer l or null; last layer's weight row).
