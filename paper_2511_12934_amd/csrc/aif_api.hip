@@ -253,7 +253,7 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
     c->slot_bytes = (sb + 255) / 256 * 256;
     HIP_TRY(nullptr, hipHostMalloc((void **)&c->h_stage, c->slot_bytes * NSLOT, hipHostMallocDefault));
     HIP_TRY(nullptr, c->d_stage.alloc(c->slot_bytes * NSLOT));
-    for (int i = 0; i < NSLOT; ++i) HIP_TRY(nullptr, hipEventCreateWithFlags(&c->ev[i], hipEventDisableTiming));
+    for (int i = 0; i < NSLOT; ++i) HIP_TRY(nullptr, hipEventCreateWithFlags(&c->ev[i], hipEventDisableTiming | hipEventDisableSystemFence));
     HIP_TRY(nullptr, hipStreamSynchronize(s));
     return AIF_OK;
 }
@@ -464,12 +464,12 @@ aif_status aif_profile_begin(aif_ctx *c, int32_t max_calls)
     if (st != AIF_OK) return st;
     while ((int)c->prof_batch.size() < 5 * max_calls) {
         hipEvent_t e;
-        HIP_TRY(c, hipEventCreate(&e));
+        HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableSystemFence));
         c->prof_batch.push_back(e);
     }
     while ((int)c->prof_topk.size() < 2 * max_calls) {
         hipEvent_t e;
-        HIP_TRY(c, hipEventCreate(&e));
+        HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableSystemFence));
         c->prof_topk.push_back(e);
     }
     c->prof_max = max_calls;

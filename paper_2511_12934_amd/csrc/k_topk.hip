@@ -3,7 +3,10 @@
 //
 // Logits map to order-preserving 32-bit keys (NaN -> 0, the lowest; -0 -> +0).
 // Four 8-bit radix passes over LDS histograms find the exact key T of the
-// k-th best and how many candidates with key == T are needed; a gather pass
+// k-th best and how many candidates with key == T are needed (the keys of the
+// first 16 K candidates stay in registers between the passes; logits of one
+// request crowd into a few bins of the leading byte, so each wave first counts
+// its lanes per bin by ballot and adds once per bin); a gather pass
 // takes every key > T plus the first ties in position order (block-wide
 // prefix count over contiguous position chunks), and a bitonic sort of the
 // <= 4096 selected (key, ~position) pairs in LDS orders them: key descending,
@@ -13,6 +16,26 @@
 namespace aif {
 
 constexpr int TK_THREADS = 1024;
+constexpr int TK_CACHED = 16;              // keys per thread kept in registers
+
+// hist[bin] += 1 for every active lane.  Up to TK_AGG distinct bins of the wave are added with one
+// atomic each (lanes counted by ballot); lanes left after that add on their own.
+constexpr int TK_AGG = 3;
+__device__ __forceinline__ void hist_add(uint32_t *hist, bool active, uint32_t bin)
+{
+    unsigned long long todo = __ballot(active);
+#pragma unroll
+    for (int round = 0; round < TK_AGG; ++round) {
+        if (!todo) return;
+        const int leader = __ffsll((long long)todo) - 1;
+        const uint32_t lb = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);      // leader is wave-uniform
+        const unsigned long long same = __ballot(active && bin == lb);
+        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[lb], (uint32_t)__popcll(same));
+        if (bin == lb) active = false;
+        todo &= ~same;
+    }
+    if (active) atomicAdd(&hist[bin], 1u);
+}
 
 __device__ __forceinline__ uint32_t logit_key(float z)
 {
@@ -28,8 +51,7 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
     extern __shared__ __align__(16) unsigned long long sel[];   // [kpad]
     __shared__ uint32_t hist[256];
     __shared__ uint32_t wave_cnt[TK_THREADS / 64];
-    __shared__ uint32_t sfx_tmp[256];
-    __shared__ uint32_t s_prefix, s_remaining, s_ngreater, s_prefix_next, s_remaining_next;
+    __shared__ uint32_t s_prefix[2], s_remaining[2], s_ngreater, s_key_count;   // [pass parity]
 
     const int r = blockIdx.x;
     const float *z = descs[r].logits;
@@ -46,109 +68,163 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
     if (kk == 0) return;
 
     if (tid == 0) {
-        s_prefix = 0;
-        s_remaining = (uint32_t)kk;
+        s_prefix[0] = 0;
+        s_remaining[0] = (uint32_t)kk;
     }
+    if (tid < 256) hist[tid] = 0;
+    uint32_t kreg[TK_CACHED];
+#pragma unroll
+    for (int j = 0; j < TK_CACHED; ++j) {
+        const int i = tid + j * TK_THREADS;
+        kreg[j] = i < n ? logit_key(z[i]) : 0u;
+    }
+    __syncthreads();
     uint32_t mask = 0;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
-        const uint32_t prefix = s_prefix;
-        for (int i = tid; i < n; i += TK_THREADS) {
-            const uint32_t key = logit_key(z[i]);
-            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    int par = 0;
+    for (int shift = 24; shift >= 0; shift -= 8, par ^= 1) {
+        const uint32_t prefix = s_prefix[par];
+#pragma unroll
+        for (int j = 0; j < TK_CACHED; ++j) {
+            const int i = tid + j * TK_THREADS;
+            if (j * TK_THREADS < n)                                 // uniform over the block
+                hist_add(hist, i < n && (kreg[j] & mask) == prefix, (kreg[j] >> shift) & 255u);
+        }
+        for (int i0 = TK_CACHED * TK_THREADS; i0 < n; i0 += TK_THREADS) {
+            const int i = i0 + tid;
+            const uint32_t key = i < n ? logit_key(z[i]) : 0u;
+            hist_add(hist, i < n && (key & mask) == prefix, (key >> shift) & 255u);
         }
         __syncthreads();
         // bin holding the rem-th best: suffix sums S[b] = sum_{b' >= b} hist[b'] over the 256 bins
         // (four waves, one bin per thread); the bin b with S[b] >= rem > S[b + 1] is unique
+        uint32_t hv = 0, sfx = 0;
         if (tid < 256) {
-            const uint32_t hv = hist[tid];
-            uint32_t sfx = hv;                              // inclusive suffix sum within the wave
+            hv = hist[tid];
+            hist[tid] = 0;                                  // ready for the next pass
+            sfx = hv;                                       // inclusive suffix sum within the wave
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
                 const uint32_t v = __shfl_down(sfx, o, 64);
                 if ((tid & 63) + o < 64) sfx += v;
             }
             if ((tid & 63) == 0) wave_cnt[tid >> 6] = sfx;
-            sfx_tmp[tid] = sfx;
         }
         __syncthreads();
         if (tid < 256) {
             uint32_t above = 0;                             // bins of the higher waves
             for (int w = (tid >> 6) + 1; w < 4; ++w) above += wave_cnt[w];
-            const uint32_t incl = sfx_tmp[tid] + above, excl = incl - hist[tid];
-            const uint32_t rem = s_remaining;
+            const uint32_t incl = sfx + above, excl = incl - hv;
+            const uint32_t rem = s_remaining[par];
             if (incl >= rem && excl < rem) {
-                s_prefix_next = prefix | ((uint32_t)tid << shift);
-                s_remaining_next = rem - excl;
+                s_prefix[par ^ 1] = prefix | ((uint32_t)tid << shift);
+                s_remaining[par ^ 1] = rem - excl;
+                s_key_count = hv;                           // after the last pass: candidates with key == T
             }
-        }
-        __syncthreads();
-        if (tid == 0) {
-            s_prefix = s_prefix_next;
-            s_remaining = s_remaining_next;
         }
         mask |= 255u << shift;
         __syncthreads();
     }
-    const uint32_t T = s_prefix;
-    const uint32_t n_ties = s_remaining;                  // >= 1 ties with key == T are taken
+    const uint32_t T = s_prefix[par];
+    const uint32_t n_ties = s_remaining[par];             // >= 1 ties with key == T are taken
     const uint32_t n_greater = (uint32_t)kk - n_ties;
+    const bool all_ties = s_key_count == n_ties;          // every candidate with key == T is selected
 
     // candidates strictly better than T: any slot in [0, n_greater)
     if (tid == 0) s_ngreater = 0;
     for (int j = tid; j < kpad; j += TK_THREADS) sel[j] = 0ull;
     __syncthreads();
 
-    // ties in position order: thread t owns positions [t*chunk, (t+1)*chunk)
-    const int chunk = (n + TK_THREADS - 1) / TK_THREADS;
-    const int lo = tid * chunk;
-    const int hi = lo + chunk < n ? lo + chunk : n;
-    uint32_t my_ties = 0;
-    for (int i = lo; i < hi; ++i) {
-        const uint32_t key = logit_key(z[i]);
-        if (key > T) {
-            const uint32_t slot = atomicAdd(&s_ngreater, 1u);
-            sel[slot] = ((unsigned long long)key << 32) | (0xFFFFFFFFu - (uint32_t)i);
-        } else if (key == T)
-            ++my_ties;
-    }
-    // exclusive prefix of my_ties over the block
-    uint32_t incl = my_ties;
+    if (all_ties) {
+        // the usual case (no duplicates straddling the cut): everything with key >= T, any slot order
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t v = __shfl_up(incl, o, 64);
-        if ((tid & 63) >= o) incl += v;
-    }
-    if ((tid & 63) == 63) wave_cnt[tid >> 6] = incl;
-    __syncthreads();
-    uint32_t before = incl - my_ties;
-    for (int w = 0; w < (tid >> 6); ++w) before += wave_cnt[w];
-    if (my_ties && before < n_ties) {
-        uint32_t rank = before;
-        for (int i = lo; i < hi && rank < n_ties; ++i) {
-            if (logit_key(z[i]) == T) {
-                sel[n_greater + rank] = ((unsigned long long)T << 32) | (0xFFFFFFFFu - (uint32_t)i);
-                ++rank;
+        for (int j = 0; j < TK_CACHED; ++j) {
+            const int i = tid + j * TK_THREADS;
+            if (i < n && kreg[j] >= T) {
+                const uint32_t slot = atomicAdd(&s_ngreater, 1u);
+                sel[slot] = ((unsigned long long)kreg[j] << 32) | (0xFFFFFFFFu - (uint32_t)i);
+            }
+        }
+        for (int i = TK_CACHED * TK_THREADS + tid; i < n; i += TK_THREADS) {
+            const uint32_t key = logit_key(z[i]);
+            if (key >= T) {
+                const uint32_t slot = atomicAdd(&s_ngreater, 1u);
+                sel[slot] = ((unsigned long long)key << 32) | (0xFFFFFFFFu - (uint32_t)i);
+            }
+        }
+    } else {
+        // ties in position order: thread t owns positions [t*chunk, (t+1)*chunk)
+        const int chunk = (n + TK_THREADS - 1) / TK_THREADS;
+        const int lo = tid * chunk;
+        const int hi = lo + chunk < n ? lo + chunk : n;
+        uint32_t my_ties = 0;
+        for (int i = lo; i < hi; ++i) {
+            const uint32_t key = logit_key(z[i]);
+            if (key > T) {
+                const uint32_t slot = atomicAdd(&s_ngreater, 1u);
+                sel[slot] = ((unsigned long long)key << 32) | (0xFFFFFFFFu - (uint32_t)i);
+            } else if (key == T)
+                ++my_ties;
+        }
+        // exclusive prefix of my_ties over the block
+        uint32_t incl = my_ties;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t v = __shfl_up(incl, o, 64);
+            if ((tid & 63) >= o) incl += v;
+        }
+        if ((tid & 63) == 63) wave_cnt[tid >> 6] = incl;
+        __syncthreads();
+        uint32_t before = incl - my_ties;
+        for (int w = 0; w < (tid >> 6); ++w) before += wave_cnt[w];
+        if (my_ties && before < n_ties) {
+            uint32_t rank = before;
+            for (int i = lo; i < hi && rank < n_ties; ++i) {
+                if (logit_key(z[i]) == T) {
+                    sel[n_greater + rank] = ((unsigned long long)T << 32) | (0xFFFFFFFFu - (uint32_t)i);
+                    ++rank;
+                }
             }
         }
     }
     __syncthreads();
 
     // bitonic sort, descending, kpad a power of two; pads (0) sink to the end
-    for (int size = 2; size <= kpad; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int j = tid; j < kpad / 2; j += TK_THREADS) {
-                const int a = 2 * j - (j & (stride - 1));
-                const int bq = a + stride;
-                const bool desc = (a & size) == 0;
-                const unsigned long long va = sel[a], vb = sel[bq];
-                if ((va < vb) == desc) {
-                    sel[a] = vb;
-                    sel[bq] = va;
+    if (kpad <= 128) {
+        // one wave does it alone: its LDS accesses complete in order, no block barrier per step
+        if (tid < 64) {
+            for (int size = 2; size <= kpad; size <<= 1) {
+                for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                    if (tid < kpad / 2) {
+                        const int a = 2 * tid - (tid & (stride - 1));
+                        const int bq = a + stride;
+                        const bool desc = (a & size) == 0;
+                        const unsigned long long va = sel[a], vb = sel[bq];
+                        if ((va < vb) == desc) {
+                            sel[a] = vb;
+                            sel[bq] = va;
+                        }
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
                 }
             }
-            __syncthreads();
+        }
+        __syncthreads();
+    } else {
+        for (int size = 2; size <= kpad; size <<= 1) {
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                for (int j = tid; j < kpad / 2; j += TK_THREADS) {
+                    const int a = 2 * j - (j & (stride - 1));
+                    const int bq = a + stride;
+                    const bool desc = (a & size) == 0;
+                    const unsigned long long va = sel[a], vb = sel[bq];
+                    if ((va < vb) == desc) {
+                        sel[a] = vb;
+                        sel[bq] = va;
+                    }
+                }
+                __syncthreads();
+            }
         }
     }
     for (int j = tid; j < kk; j += TK_THREADS) {
