@@ -43,7 +43,7 @@ struct aif_ctx {
     const void *table = nullptr;
 
     // repacked weights (owned)
-    DevBuf w1u;                       // fp32 [H1, d_user]
+    DevBuf w1u;                       // fp32 [d_user, H1]: user columns of layer 1, transposed
     DevBuf wq;                        // fp32 [d_attn, d_item] (generic attention)
     DevBuf wt[MAX_LAYERS];            // fp32 transposed [K_l, N_l] (generic MLP)
     DevBuf bias[MAX_LAYERS];          // fp32 [N_l]
@@ -201,7 +201,7 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
     hipStream_t s = nullptr;
     const int H1 = m.dims[1];
     HIP_TRY(nullptr, c->w1u.alloc((size_t)H1 * m.d_user * 4));
-    HIP_TRY(nullptr, launch_to_f32(m.dtype, wts->w[0], H1, m.d_user, m.dims[0], 0, (float *)c->w1u.p, s));
+    HIP_TRY(nullptr, launch_pack_transposed(m.dtype, wts->w[0], H1, m.dims[0], 0, m.d_user, (float *)c->w1u.p, s));
     for (int l = 0; l < m.n_layers; ++l) {
         const int n_in = m.dims[l], n_out = m.dims[l + 1];
         const int col0 = l == 0 ? m.d_user : 0, ncols = n_in - col0;
@@ -348,13 +348,21 @@ aif_status aif_score_batch(aif_ctx *c, const aif_request *reqs, int32_t n_req, v
     hipEvent_t *pe = nullptr;
     if (c->prof_on && c->prof_batch_calls < c->prof_max) pe = &c->prof_batch[(size_t)5 * c->prof_batch_calls++];
     if (pe) HIP_TRY(c, hipEventRecord(pe[0], s));
-    HIP_TRY(c, launch_gather(m, b, c->table, c->X.p, (int32_t *)c->bad.p, s));
-    if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
-    HIP_TRY(c, launch_user_fold(m, b, (const float *)c->w1u.p, c->has_bias[0] ? (const float *)c->bias[0].p : nullptr,
-                                (float *)c->bias1.p, s));
+    const bool fused = stage_fusable(m, c->mfma);
+    if (fused) {
+        // gather, user fold and K/V packing as one launch; timed as the gather stage
+        HIP_TRY(c, launch_stage(m, b, c->table, c->X.p, (int32_t *)c->bad.p, (const float *)c->w1u.p,
+                                c->has_bias[0] ? (const float *)c->bias[0].p : nullptr, (float *)c->bias1.p, c->mfma, s));
+        if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
+    } else {
+        HIP_TRY(c, launch_gather(m, b, c->table, c->X.p, (int32_t *)c->bad.p, s));
+        if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
+        HIP_TRY(c, launch_user_fold(m, b, (const float *)c->w1u.p, c->has_bias[0] ? (const float *)c->bias[0].p : nullptr,
+                                    (float *)c->bias1.p, s));
+    }
     if (pe) HIP_TRY(c, hipEventRecord(pe[2], s));
     if (c->mfma.attn)
-        HIP_TRY(c, launch_attn_mfma(m, b, c->X.p, c->mfma, s));
+        HIP_TRY(c, launch_attn_mfma(m, b, c->X.p, c->mfma, fused, s));
     else
         HIP_TRY(c, launch_attn_generic(m, b, c->X.p, c->has_wq ? (const float *)c->wq.p : nullptr, c->max_seq_len, s));
     if (pe) HIP_TRY(c, hipEventRecord(pe[3], s));

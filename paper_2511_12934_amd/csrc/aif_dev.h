@@ -94,7 +94,8 @@ template <> __device__ __forceinline__ void st_f<uint16_t>(uint16_t *p, float v)
 hipError_t launch_gather(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad,
                          hipStream_t s);
 
-// a2: per request, bias1[r, n] = b1[n] + sum_m W1[n, m] u[m] over the user columns.
+// a2: per request, bias1[r, n] = b1[n] + sum_m W1[n, m] u[m] over the user columns (w1u: those columns
+// transposed, fp32 [d_user, H1]).
 hipError_t launch_user_fold(const Model &m, const Batch &b, const float *w1u, const float *b1,
                             float *bias1, hipStream_t s);
 

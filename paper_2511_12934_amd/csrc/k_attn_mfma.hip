@@ -25,6 +25,7 @@
 // first takes the true maximum in an extra pass over K.  Both are the exact
 // softmax up to rounding.
 #include "k_mfma.h"
+#include "k_stage.h"
 #include "mfma_util.h"
 
 namespace aif {
@@ -48,72 +49,14 @@ __device__ __forceinline__ void stage_frags(const char *__restrict__ src, uint32
 }
 
 // ---------------------------------------------------------------------------
-// a2 -- per request: K and V into fragment order, and max |k_t| per head and 64-key stage.
-// Layout per request: chunk(head, key tile kt) = FR fragments of 1 KB at
-// ((head * nktp + kt) * FR) KB:  JS K-fragments  [lane][s] = K[32kt + lane%32][o + 16j + 8(lane/32) + s]
-// then 2*FT V-fragments (jj, ft): [lane][s] = V[32kt + 16jj + 8(s/4) + 4(lane/32) + s%4][o + 32ft + lane%32]
-// with o = head * DH; keys >= seq_len read as zero.
+// a2 -- per request: K and V into fragment order, and max |k_t| per head and 64-key stage
+// (body and layout: pack_kv_block).
 // ---------------------------------------------------------------------------
 template <int DH>
 __global__ __launch_bounds__(256) void k_pack_kv(Model m, Batch b, char *__restrict__ kvpack, size_t pack_stride,
                                                  float *__restrict__ kmax_part, int nktp)
 {
-    constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32;
-    const int r = blockIdx.z, hd = blockIdx.y, st = blockIdx.x;
-    const ReqDesc *rd = b.reqs + r;
-    const int L = rd->seq_len;
-    const int nkt2 = (((L + 31) >> 5) + 1) & ~1;
-    if (2 * st >= nkt2) return;
-    const uint16_t *K = (const uint16_t *)rd->seq_keys, *V = (const uint16_t *)rd->seq_vals;
-    const int da = m.d_attn, o = hd * DH;
-    uint4 *dst = (uint4 *)(kvpack + (size_t)r * pack_stride + ((size_t)(hd * nktp + 2 * st) * FR) * 1024);
-    // one 16-byte piece (a lane's share of a fragment) per thread and step
-    for (int pc = threadIdx.x; pc < 2 * FR * 64; pc += 256) {
-        const int k2 = pc / (FR * 64), rem = pc - k2 * (FR * 64);
-        const int frag = rem >> 6, lane = rem & 63;
-        const int kt = 2 * st + k2, hh = lane >> 5;
-        uint4 out = make_uint4(0, 0, 0, 0);
-        if (frag < JS) {
-            const int t = 32 * kt + (lane & 31);
-            if (t < L) out = *(const uint4 *)(K + (size_t)t * da + o + 16 * frag + 8 * hh);
-        } else {
-            const int fv = frag - JS, jj = fv / FT, ft = fv - jj * FT;
-            const int f = o + 32 * ft + (lane & 31), t0 = 32 * kt + 16 * jj + 4 * hh;
-            uint32_t w[4];
-#pragma unroll
-            for (int p2 = 0; p2 < 4; ++p2) {                 // slots 2 p2 and 2 p2 + 1
-                const int ta = t0 + 8 * ((2 * p2) >> 2) + ((2 * p2) & 3), tb = ta + 1;
-                const uint32_t lo = ta < L ? V[(size_t)ta * da + f] : 0u;
-                const uint32_t hi = tb < L ? V[(size_t)tb * da + f] : 0u;
-                w[p2] = lo | (hi << 16);
-            }
-            out = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-        dst[pc] = out;
-    }
-    // largest key norm among this stage's 64 keys
-    if (threadIdx.x < 64) {
-        const int t = 64 * st + threadIdx.x;
-        float ss = 0.f;
-        if (t < L) {
-            const uint4 *kr = (const uint4 *)(K + (size_t)t * da + o);
-#pragma unroll
-            for (int i = 0; i < DH / 8; ++i) {
-                const uint4 q = kr[i];
-                const uint32_t ws[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float a0 = __uint_as_float(ws[j] << 16), a1 = __uint_as_float(ws[j] & 0xFFFF0000u);
-                    ss += a0 * a0 + a1 * a1;
-                }
-            }
-        }
-        float nrm = sqrtf(ss);
-#pragma unroll
-        for (int off = 32; off; off >>= 1) nrm = fmaxf(nrm, __shfl_xor(nrm, off, 64));
-        // round the bound up a little: it must dominate the fp32-accumulated score
-        if (threadIdx.x == 0) kmax_part[((size_t)r * m.n_heads + hd) * (nktp / 2) + st] = nrm * 1.001f;
-    }
+    pack_kv_block<DH>(blockIdx.z, blockIdx.y, blockIdx.x, m, b, kvpack, pack_stride, kmax_part, nktp);
 }
 
 // ---------------------------------------------------------------------------
@@ -569,10 +512,10 @@ size_t attn_pack_stride(const Model &m, int max_seq_len, int *nktp_out)
 
 template <int DH, int WAVES>
 static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char *kvpack, size_t stride, float *kmax,
-                                   int nktp, hipStream_t s)
+                                   int nktp, bool kv_packed, hipStream_t s)
 {
     constexpr int LDS = 4 * 2 * (DH / 8) * 1024, ROWS = WAVES * 32;
-    if (nktp > 0)
+    if (nktp > 0 && !kv_packed)
         hipLaunchKernelGGL(k_pack_kv<DH>, dim3(nktp / 2, m.n_heads, b.n_req), dim3(256), 0, s, m, b, kvpack, stride, kmax, nktp);
     if (b.n_groups > 0) {
         constexpr int RES_LDS = RES_LDS_BYTES;
@@ -593,12 +536,12 @@ static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char
 }
 
 hipError_t launch_attn_variant(int variant, const Model &m, const Batch &b, void *X, char *kvpack, size_t stride,
-                               float *kmax, int nktp, hipStream_t s)
+                               float *kmax, int nktp, bool kv_packed, hipStream_t s)
 {
     if (b.n_blk == 0) return hipSuccess;
     switch (variant) {
-    case 0: return launch_attn_spec<64, 8>(m, b, X, kvpack, stride, kmax, nktp, s);
-    case 1: return launch_attn_spec<32, 8>(m, b, X, kvpack, stride, kmax, nktp, s);
+    case 0: return launch_attn_spec<64, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s);
+    case 1: return launch_attn_spec<32, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -3,7 +3,7 @@
 // candidate per wave (attention) or sixteen per block (MLP); accumulation in
 // fp32 in a fixed order per candidate, so results do not depend on how a
 // candidate list is sliced into requests.
-#include "aif_dev.h"
+#include "k_stage.h"
 
 namespace aif {
 
@@ -24,29 +24,20 @@ __device__ __forceinline__ float wave_sum(float v)
 // a2 -- user fold.  [u|e|a|c] W1^T = u W1u^T + [e|a|c] W1rest^T: the first
 // term is the same for every candidate of a request (the paper's own point:
 // interaction-independent work is done once, Sec. 2), so it becomes a
-// per-request bias.  One wave per output feature.
+// per-request bias.  One thread per output feature.
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void k_user_fold(Model m, Batch b, const float *__restrict__ w1u,
                                                    const float *__restrict__ b1, float *__restrict__ bias1)
 {
-    const int r = blockIdx.y;
-    const int lane = threadIdx.x & 63;
-    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int h1 = m.dims[1];
-    if (n >= h1) return;
-    const T *u = (const T *)b.reqs[r].user_vec;
-    float acc = 0.f;
-    for (int k = lane; k < m.d_user; k += 64) acc += w1u[(size_t)n * m.d_user + k] * ld_f<T>(u + k);
-    acc = wave_sum(acc);
-    if (lane == 0) bias1[(size_t)r * h1 + n] = acc + (b1 ? b1[n] : 0.f);
+    user_fold_block<T>(blockIdx.y, blockIdx.x, m, b, w1u, b1, bias1);
 }
 
 hipError_t launch_user_fold(const Model &m, const Batch &b, const float *w1u, const float *b1, float *bias1,
                             hipStream_t s)
 {
     if (b.n_req == 0) return hipSuccess;
-    dim3 grid((m.dims[1] + 3) / 4, b.n_req);
+    dim3 grid((m.dims[1] + 255) / 256, b.n_req);
     if (m.dtype == 0)
         hipLaunchKernelGGL(k_user_fold<float>, grid, dim3(256), 0, s, m, b, w1u, b1, bias1);
     else

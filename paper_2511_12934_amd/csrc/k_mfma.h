@@ -38,7 +38,13 @@ void mfma_release(MfmaPlan &plan);
 int attn_plan_groups(const Model &m, const ReqDesc *reqs /*host*/, int n_req, int n_cu, AttnGroup *out /*host*/);
 size_t attn_max_groups(size_t x_rows, int max_users);
 
-hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, hipStream_t s);
+// kv_packed: the batch's K/V are already in fragment order (launch_stage did it)
+hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s);
+
+// k_stage.hip: gather + user fold + K/V packing as one launch (bf16 models served by the MFMA attention kernel)
+bool stage_fusable(const Model &m, const MfmaPlan &plan);
+hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad, const float *w1u,
+                        const float *b1, float *bias1, const MfmaPlan &plan, hipStream_t s);
 
 // bias_f32[l] / wlast_f32: the context's fp32 copies (bias of layer l or null; last layer's weight row).
 hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const MfmaPlan &plan,
@@ -54,6 +60,6 @@ hipError_t pack_frag(const void *W, int n_in, int col0, int N, int K, bool from_
 int attn_mfma_variant(const Model &m, bool has_wq);
 size_t attn_pack_stride(const Model &m, int max_seq_len, int *nktp_out);
 hipError_t launch_attn_variant(int variant, const Model &m, const Batch &b, void *X, char *kvpack, size_t stride,
-                               float *kmax, int nktp, hipStream_t s);
+                               float *kmax, int nktp, bool kv_packed, hipStream_t s);
 
 }  // namespace aif

@@ -60,9 +60,9 @@ void mfma_release(MfmaPlan &plan)
     plan.kmax = nullptr;
 }
 
-hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, hipStream_t s)
+hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s)
 {
-    return launch_attn_variant(plan.attn_variant, m, b, X, plan.kvpack, plan.pack_stride, plan.kmax, plan.nktp, s);
+    return launch_attn_variant(plan.attn_variant, m, b, X, plan.kvpack, plan.pack_stride, plan.kmax, plan.nktp, kv_packed, s);
 }
 
 hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const MfmaPlan &plan,

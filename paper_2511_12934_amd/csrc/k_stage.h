@@ -1,0 +1,163 @@
+// Bodies of the three kernels that stage a batch before the attention kernel
+// -- a1 gather, a2 user fold, a2 K/V packing -- as device functions of a
+// 256-thread block, so that each can be launched alone or all three as one
+// grid (k_stage): they are independent of one another, the gather is bound by
+// HBM and the other two by latency, so one launch hides the small ones under
+// the gather and saves two launches.
+#pragma once
+#include "aif_dev.h"
+
+namespace aif {
+
+constexpr int GATHER_UNROLL = 4;
+
+// a1 -- one ROW_BLOCK of the workspace: X[row, 0:d_item] = table[id].
+// LOG_RV >= 0: a row is 2^LOG_RV pieces of 16 bytes (shift instead of divide); LOG_RV < 0: any count.
+template <int LOG_RV>
+__device__ __forceinline__ void gather_block(int blk, const uint4 *__restrict__ table, int64_t n_items, int row_vec,
+                                             const Batch &b, char *__restrict__ X, const XLayout &xl,
+                                             int32_t *__restrict__ bad)
+{
+    const int r = b.blk_req[blk];
+    if (r < 0) return;
+    const ReqDesc *rd = b.reqs + r;
+    const int row_base = rd->row_base;
+    const int local0 = blk * ROW_BLOCK - row_base;
+    int nrows = rd->n_cand - local0;
+    if (nrows <= 0) return;
+    if (nrows > ROW_BLOCK) nrows = ROW_BLOCK;
+    const int32_t *ids = rd->cand_ids + local0;
+    char *out = X + (size_t)((row_base + local0) / X_TILE) * xl.tile_bytes;     // blocks start on tile boundaries
+    if (LOG_RV >= 0) row_vec = 1 << LOG_RV;
+    const int total = nrows * row_vec;
+    int n_bad = 0;
+    for (int base = threadIdx.x; base < total; base += 256 * GATHER_UNROLL) {
+        uint4 v[GATHER_UNROLL];
+        int row[GATHER_UNROLL], piece[GATHER_UNROLL];
+        int64_t id[GATHER_UNROLL];
+#pragma unroll
+        for (int j = 0; j < GATHER_UNROLL; ++j) {
+            const int idx = base + j * 256;
+            row[j] = LOG_RV >= 0 ? idx >> LOG_RV : idx / row_vec;
+            piece[j] = idx - row[j] * row_vec;
+            id[j] = idx < total ? ids[row[j]] : 0;
+        }
+#pragma unroll
+        for (int j = 0; j < GATHER_UNROLL; ++j) {
+            if (id[j] < 0 || id[j] >= n_items) {
+                id[j] = 0;
+                if (piece[j] == 0) ++n_bad;
+            }
+            if (base + j * 256 < total) v[j] = table[(size_t)id[j] * row_vec + piece[j]];
+        }
+#pragma unroll
+        for (int j = 0; j < GATHER_UNROLL; ++j) {
+            const int idx = base + j * 256;
+            if (idx < total) {
+                // streaming stores: measured 1.5x faster than plain ones here (the rows are written once,
+                // at a stride, and the reads that follow come from another kernel)
+                uint4 *p = (uint4 *)(out + x_offset(xl, row[j], piece[j]));
+                __builtin_nontemporal_store(v[j].x, &p->x);
+                __builtin_nontemporal_store(v[j].y, &p->y);
+                __builtin_nontemporal_store(v[j].z, &p->z);
+                __builtin_nontemporal_store(v[j].w, &p->w);
+            }
+        }
+    }
+    if (n_bad) atomicAdd(bad, n_bad);
+}
+
+// a2 -- user fold: 256 consecutive layer-1 features n = 256 * part + thread of request r,
+// bias1[r, n] = b1[n] + sum_k W1[n, k] u[k] over the user columns, k in order (w1ut = those
+// columns transposed, [d_user, H1], so that the threads of a wave read consecutive words).
+template <typename T>
+__device__ __forceinline__ void user_fold_block(int r, int part, const Model &m, const Batch &b,
+                                                const float *__restrict__ w1ut, const float *__restrict__ b1,
+                                                float *__restrict__ bias1)
+{
+    const int n = part * 256 + threadIdx.x;
+    const int h1 = m.dims[1];
+    if (n >= h1) return;
+    const T *u = (const T *)b.reqs[r].user_vec;
+    float acc = b1 ? b1[n] : 0.f;
+    int k = 0;
+    for (; k + 4 <= m.d_user; k += 4) {             // four independent loads in flight
+        const float w0 = w1ut[(size_t)k * h1 + n], w1 = w1ut[(size_t)(k + 1) * h1 + n];
+        const float w2 = w1ut[(size_t)(k + 2) * h1 + n], w3 = w1ut[(size_t)(k + 3) * h1 + n];
+        acc = fmaf(w0, ld_f<T>(u + k), acc);
+        acc = fmaf(w1, ld_f<T>(u + k + 1), acc);
+        acc = fmaf(w2, ld_f<T>(u + k + 2), acc);
+        acc = fmaf(w3, ld_f<T>(u + k + 3), acc);
+    }
+    for (; k < m.d_user; ++k) acc = fmaf(w1ut[(size_t)k * h1 + n], ld_f<T>(u + k), acc);
+    bias1[(size_t)r * h1 + n] = acc;
+}
+
+// a2 -- K and V of request r, head hd, 64-key stage st into MFMA fragment order, and max |k_t| of the stage.
+// Layout per request: chunk(head, key tile kt) = FR fragments of 1 KB at
+// ((head * nktp + kt) * FR) KB:  JS K-fragments  [lane][s] = K[32kt + lane%32][o + 16j + 8(lane/32) + s]
+// then 2*FT V-fragments (jj, ft): [lane][s] = V[32kt + 16jj + 8(s/4) + 4(lane/32) + s%4][o + 32ft + lane%32]
+// with o = head * DH; keys >= seq_len read as zero.
+template <int DH>
+__device__ __forceinline__ void pack_kv_block(int r, int hd, int st, const Model &m, const Batch &b,
+                                              char *__restrict__ kvpack, size_t pack_stride,
+                                              float *__restrict__ kmax_part, int nktp)
+{
+    constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32;
+    const ReqDesc *rd = b.reqs + r;
+    const int L = rd->seq_len;
+    const int nkt2 = (((L + 31) >> 5) + 1) & ~1;
+    if (2 * st >= nkt2) return;
+    const uint16_t *K = (const uint16_t *)rd->seq_keys, *V = (const uint16_t *)rd->seq_vals;
+    const int da = m.d_attn, o = hd * DH;
+    uint4 *dst = (uint4 *)(kvpack + (size_t)r * pack_stride + ((size_t)(hd * nktp + 2 * st) * FR) * 1024);
+    // one 16-byte piece (a lane's share of a fragment) per thread and step
+    for (int pc = threadIdx.x; pc < 2 * FR * 64; pc += 256) {
+        const int k2 = pc / (FR * 64), rem = pc - k2 * (FR * 64);
+        const int frag = rem >> 6, lane = rem & 63;
+        const int kt = 2 * st + k2, hh = lane >> 5;
+        uint4 out = make_uint4(0, 0, 0, 0);
+        if (frag < JS) {
+            const int t = 32 * kt + (lane & 31);
+            if (t < L) out = *(const uint4 *)(K + (size_t)t * da + o + 16 * frag + 8 * hh);
+        } else {
+            const int fv = frag - JS, jj = fv / FT, ft = fv - jj * FT;
+            const int f = o + 32 * ft + (lane & 31), t0 = 32 * kt + 16 * jj + 4 * hh;
+            uint32_t w[4];
+#pragma unroll
+            for (int p2 = 0; p2 < 4; ++p2) {                 // slots 2 p2 and 2 p2 + 1
+                const int ta = t0 + 8 * ((2 * p2) >> 2) + ((2 * p2) & 3), tb = ta + 1;
+                const uint32_t lo = ta < L ? V[(size_t)ta * da + f] : 0u;
+                const uint32_t hi = tb < L ? V[(size_t)tb * da + f] : 0u;
+                w[p2] = lo | (hi << 16);
+            }
+            out = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        dst[pc] = out;
+    }
+    // largest key norm among this stage's 64 keys
+    if (threadIdx.x < 64) {
+        const int t = 64 * st + threadIdx.x;
+        float ss = 0.f;
+        if (t < L) {
+            const uint4 *kr = (const uint4 *)(K + (size_t)t * da + o);
+#pragma unroll
+            for (int i = 0; i < DH / 8; ++i) {
+                const uint4 q = kr[i];
+                const uint32_t ws[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float a0 = __uint_as_float(ws[j] << 16), a1 = __uint_as_float(ws[j] & 0xFFFF0000u);
+                    ss += a0 * a0 + a1 * a1;
+                }
+            }
+        }
+        float nrm = sqrtf(ss);
+#pragma unroll
+        for (int off = 32; off; off >>= 1) nrm = fmaxf(nrm, __shfl_xor(nrm, off, 64));
+        // round the bound up a little: it must dominate the fp32-accumulated score
+        if (threadIdx.x == 0) kmax_part[((size_t)r * m.n_heads + hd) * (nktp / 2) + st] = nrm * 1.001f;
+    }
+}
+
+}  // namespace aif

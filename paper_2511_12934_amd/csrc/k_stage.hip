@@ -1,0 +1,90 @@
+// a1 + a2 in one launch for the bf16 MFMA path: the blocks of one grid take the
+// three staging jobs of a batch -- K/V packing, user fold, gather -- by block
+// index.  The jobs do not depend on one another; all are read by the attention
+// kernel that follows.  The small, latency-bound jobs come first in the grid so
+// that they run under the HBM-bound gather instead of before or after it.
+#include "k_mfma.h"
+#include "k_stage.h"
+
+namespace aif {
+
+struct StageArgs {
+    Model m;
+    Batch b;
+    const uint4 *table;
+    char *X;
+    XLayout xl;
+    int32_t *bad;
+    const float *w1u, *b1;
+    float *bias1;
+    char *kvpack;
+    size_t pack_stride;
+    float *kmax;
+    int32_t nktp, row_vec;
+    int32_t n_pack, n_fold;         // blocks of the first two jobs
+    int32_t stages, quads;          // 64-key stages per head (nktp / 2); blocks of 256 layer-1 features
+};
+
+template <int LOG_RV, int DH>
+__global__ __launch_bounds__(256) void k_stage(StageArgs a)
+{
+    int idx = blockIdx.x;
+    if (idx < a.n_pack) {
+        const int st = idx % a.stages, rest = idx / a.stages;
+        pack_kv_block<DH>(rest / a.m.n_heads, rest % a.m.n_heads, st, a.m, a.b, a.kvpack, a.pack_stride, a.kmax, a.nktp);
+        return;
+    }
+    idx -= a.n_pack;
+    if (idx < a.n_fold) {
+        user_fold_block<uint16_t>(idx / a.quads, idx % a.quads, a.m, a.b, a.w1u, a.b1, a.bias1);
+        return;
+    }
+    idx -= a.n_fold;
+    gather_block<LOG_RV>(idx, a.table, a.m.n_items, a.row_vec, a.b, a.X, a.xl, a.bad);
+}
+
+template <int DH>
+static hipError_t launch_stage_dh(const StageArgs &a, int n_gather, hipStream_t s)
+{
+    const dim3 grid(a.n_pack + a.n_fold + n_gather);
+    switch (a.row_vec) {
+    case 8: hipLaunchKernelGGL((k_stage<3, DH>), grid, dim3(256), 0, s, a); break;
+    case 16: hipLaunchKernelGGL((k_stage<4, DH>), grid, dim3(256), 0, s, a); break;
+    case 32: hipLaunchKernelGGL((k_stage<5, DH>), grid, dim3(256), 0, s, a); break;
+    default: hipLaunchKernelGGL((k_stage<-1, DH>), grid, dim3(256), 0, s, a); break;
+    }
+    return hipGetLastError();
+}
+
+bool stage_fusable(const Model &m, const MfmaPlan &plan)
+{
+    return m.dtype == 1 && plan.attn && (m.d_head == 64 || m.d_head == 32);
+}
+
+hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad, const float *w1u,
+                        const float *b1, float *bias1, const MfmaPlan &plan, hipStream_t s)
+{
+    if (b.n_req == 0) return hipSuccess;
+    StageArgs a;
+    a.m = m;
+    a.b = b;
+    a.table = (const uint4 *)table;
+    a.X = (char *)X;
+    a.xl = x_layout(m);
+    a.bad = bad;
+    a.w1u = w1u;
+    a.b1 = b1;
+    a.bias1 = bias1;
+    a.kvpack = plan.kvpack;
+    a.pack_stride = plan.pack_stride;
+    a.kmax = plan.kmax;
+    a.nktp = plan.nktp;
+    a.row_vec = m.d_item * 2 / 16;
+    a.stages = plan.nktp / 2;
+    a.quads = (m.dims[1] + 255) / 256;
+    a.n_pack = b.n_req * m.n_heads * a.stages;
+    a.n_fold = b.n_req * a.quads;
+    return m.d_head == 64 ? launch_stage_dh<64>(a, b.n_blk, s) : launch_stage_dh<32>(a, b.n_blk, s);
+}
+
+}  // namespace aif
