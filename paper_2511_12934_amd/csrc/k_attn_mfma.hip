@@ -34,6 +34,13 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
+// Streaming stores for the attention and cross blocks: they are written once and read by the next
+// kernel, and lines left dirty in the eight L2s would have to be written back when the kernel ends.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store_stream(bf16x8 *p, bf16x8 v) { __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), (u32x4 *)p); }
+__device__ __forceinline__ void store_stream(bf16x4 *p, bf16x4 v) { __builtin_nontemporal_store(__builtin_bit_cast(u32x2, v), (u32x2 *)p); }
+
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float BOUND_LIMIT = 40.f;      // exponents stay within [-80, 0]
 
@@ -227,7 +234,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
 #pragma unroll
                     for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(O[ft][4 * qd + i] * inv);
                     // features 8 qd + 4 h + i of this tile: half h of one piece
-                    *((bf16x4 *)piece((m.d_item + hd * DH) / 8 + 4 * ft + qd) + h) = o4;
+                    store_stream((bf16x4 *)piece((m.d_item + hd * DH) / 8 + 4 * ft + qd) + h, o4);
                 }
         }
     }
@@ -240,7 +247,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
             bf16x8 o8;
 #pragma unroll
             for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)e[s] * (float)u[s]);
-            *piece(pc0 + pc) = o8;
+            store_stream(piece(pc0 + pc), o8);
         }
     }
 }
@@ -260,7 +267,7 @@ constexpr int RES_WAVES = 16;
 constexpr int RES_LDS_FRAGS = 152;            // 1 KB fragments of K/V that may stay resident
 constexpr int RES_MAX_HEADS = 64;
 constexpr int RES_MAX_ITEM_PIECES = 256;      // d_item / 8 the Hadamard operand may have to stay in LDS
-constexpr int RES_LDS_BYTES = RES_LDS_FRAGS * 1024 + RES_MAX_HEADS * 4 + RES_MAX_ITEM_PIECES * 16;
+constexpr int RES_LDS_BYTES = RES_LDS_FRAGS * 1024 + RES_MAX_HEADS * 4 + RES_MAX_ITEM_PIECES * 16 + 16;
 
 template <int DH>
 __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, char *__restrict__ X, XLayout xl,
@@ -271,6 +278,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     extern __shared__ __align__(16) char lds[];
     float *skm = (float *)(lds + RES_LDS_FRAGS * 1024);         // [n_heads] max |k_t|
     bf16x8 *su = (bf16x8 *)(skm + RES_MAX_HEADS);               // the request's Hadamard operand
+    int *s_next = (int *)(su + RES_MAX_ITEM_PIECES);            // next tile of the group nobody has taken yet
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), col = lane & 31, h = lane >> 5;
     const AttnGroup g = b.groups[blockIdx.x];
@@ -298,6 +306,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     }
     if (m.cross_mode == 1)
         for (int i = threadIdx.x; i < m.d_item / 8; i += RES_WAVES * 64) su[i] = ((const bf16x8 *)rd.cross_vecs)[i];
+    if (threadIdx.x == 0) *s_next = RES_WAVES;
     wait_vmcnt<0>();
     __syncthreads();
 
@@ -306,24 +315,34 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     const int pc_cross = (m.d_item + m.d_attn) / 8;             // first piece of the cross block
     const bool hadamard = m.cross_mode == 1;
 
-    // A wave's work is the sequence of (tile, head) items of its tiles.  The only global reads an
-    // item needs are its query pieces; they are asked for as soon as the previous item has issued
-    // its last S product (the registers are free from then on), so their latency passes under that
-    // item's last exponentials, second product and stores instead of stalling the wave.
-    const int my_tiles = g.t1 - g.t0 > wave ? (g.t1 - g.t0 - wave + RES_WAVES - 1) / RES_WAVES : 0;
-    const int n_items = my_tiles * H;
-    auto row_of = [&](int it) { return X + x_offset(xl, rd.row_base + (g.t0 + wave + RES_WAVES * (it / H)) * 32 + col, 0); };
+    // A wave's work is a sequence of (tile, head) items.  Tiles are handed out on demand -- the SIMD
+    // favours its older waves, so with a fixed share per wave the young ones would finish the kernel
+    // alone.  The only global reads an item needs are its query pieces; they are asked for as soon as
+    // the previous item has issued its last S product (the registers are free from then on), so their
+    // latency passes under that item's last exponentials, second product and stores.
+    const int n_tiles = g.t1 - g.t0;
+    auto row_of = [&](int tile) { return X + x_offset(xl, rd.row_base + (g.t0 + tile) * 32 + col, 0); };
+    auto take_tile = [&]() {
+        int t = 0;
+        if (lane == 0) t = atomicAdd(s_next, 1);
+        return __builtin_amdgcn_readfirstlane(t);
+    };
     bf16x8 q[JS];
-    if (n_items > 0) {
-        const char *xr = row_of(0);
+    int tile = wave, hd = 0;
+    if (tile < n_tiles) {
+        const char *xr = row_of(tile);
 #pragma unroll
         for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(2 * j + h) * xl.piece_stride);
     }
-    for (int it = 0; it < n_items; ++it) {
-        const int hd = it % H;
-        const int local = (g.t0 + wave + RES_WAVES * (it / H)) * 32 + col;
+    while (tile < n_tiles) {
+        int next_tile = tile, next_hd = hd + 1;
+        if (next_hd == H) {
+            next_hd = 0;
+            next_tile = take_tile();
+        }
+        const int local = (g.t0 + tile) * 32 + col;
         const bool live = local < rd.n_cand;
-        char *xrow = row_of(it);
+        char *xrow = row_of(tile);
         auto piece = [&](int p) { return (bf16x8 *)(xrow + (size_t)p * xl.piece_stride); };
 
         // real-time half of the cross features: the query pieces ARE item-vector pieces (no W_q here),
@@ -337,7 +356,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                     bf16x8 o8;
 #pragma unroll
                     for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)q[j][s] * (float)u[s]);
-                    *piece(pc_cross + pc) = o8;
+                    store_stream(piece(pc_cross + pc), o8);
                 }
             }
             // item-vector pieces beyond the attention width (d_item > d_attn)
@@ -347,7 +366,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                     bf16x8 o8;
 #pragma unroll
                     for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)e[s] * (float)u[s]);
-                    *piece(pc_cross + pc) = o8;
+                    store_stream(piece(pc_cross + pc), o8);
                 }
         }
 
@@ -441,11 +460,10 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
             }
         }
         // the last S product of this item is on its way: the next item's query may take the registers
-        if (it + 1 < n_items) {
-            const char *xr = row_of(it + 1);
-            const int hn = (it + 1) % H;
+        if (next_tile < n_tiles) {
+            const char *xr = row_of(next_tile);
 #pragma unroll
-            for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(hn * (DH / 8) + 2 * j + h) * xl.piece_stride);
+            for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(next_hd * (DH / 8) + 2 * j + h) * xl.piece_stride);
         }
         if (nkt > 0) finish_tile(nkt - 1, S, 32 * nkt > L);
 
@@ -459,9 +477,11 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                     bf16x4 o4;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(O[ft][4 * qd + i] * inv);
-                    *((bf16x4 *)piece((m.d_item + hd * DH) / 8 + 4 * ft + qd) + h) = o4;
+                    store_stream((bf16x4 *)piece((m.d_item + hd * DH) / 8 + 4 * ft + qd) + h, o4);
                 }
         }
+        tile = next_tile;
+        hd = next_hd;
     }
 }
 
