@@ -243,6 +243,56 @@ def test_mfma_kernels_ragged_and_large_inputs(R, torch, shape, sigma):
             assert np.abs(z - ref.logits).max() <= 2e-2 * scale, f"req {r}"
 
 
+def test_resident_and_streaming_attention_give_the_same_bits(R, torch):
+    """A request whose K/V fit in LDS is served by the resident attention kernel; in a batch with a
+    request whose K/V do not fit, by the streaming one.  Its results must not depend on the company."""
+    cfg = small_cfg("bf16", n_items=5000, seq_len=1100, **MFMA_SHAPES["c3_like"])
+    _say("resident vs streaming attention, same request")
+    rng = np.random.default_rng(99)
+    model = wl.make_model(cfg, seed=5, bias_scale=0.2)
+    table = wl.make_table_host(cfg, rng)
+    table_dev = R.to_device(table, cfg.dtype)
+    sampler = wl.IdSampler(cfg)
+    ua, ia = wl.make_user(cfg, rng, seq_len=333), sampler.sample(rng, 777)
+    ub, ib = wl.make_user(cfg, rng, seq_len=1100), sampler.sample(rng, 300)     # 35 key tiles x 8 KB > LDS
+    dm = R.DeviceModel(cfg, model)
+    ctx = R.make_context(cfg, dm, table_dev, max_users=2, max_candidates=1024, max_seq_len=1100)
+    da, db = R.upload_request(cfg, ua, ia), R.upload_request(cfg, ub, ib)
+    ctx.aif_score_batch([da.req])
+    torch.cuda.synchronize()
+    z_alone = da.logits.cpu().numpy().copy()
+    x_alone = R.peek_features(ctx, cfg, 0, ia.size)
+    da.logits.fill_(float("nan"))
+    ctx.aif_score_batch([da.req, db.req])
+    torch.cuda.synchronize()
+    assert np.array_equal(R.peek_features(ctx, cfg, 0, ia.size), x_alone)
+    assert np.array_equal(da.logits.cpu().numpy(), z_alone)
+    assert_logits_close("bf16", z_alone, oracle_scores(cfg, model, table, ua, ia, n_threads=4).logits, "resident")
+    assert_logits_close("bf16", db.logits.cpu().numpy(), oracle_scores(cfg, model, table, ub, ib, n_threads=4).logits, "streaming")
+
+
+def test_mfma_attention_with_item_vector_wider_than_attention(R, torch):
+    """d_item > d_attn without W_q: the query is the leading slice, the Hadamard cross still spans the whole
+    item vector; the MLP of this shape has no MFMA variant, so the workspace stays row-major."""
+    cfg = small_cfg("bf16", n_items=4000, seq_len=150, d_item=128, d_user=128, d_attn=64, n_heads=1,
+                    mlp_dims=(448, 64, 1))
+    _say("MFMA attention, d_item 128 > d_attn 64, generic MLP")
+    rng = np.random.default_rng(123)
+    model = wl.make_model(cfg, seed=2, bias_scale=0.2)
+    table = wl.make_table_host(cfg, rng)
+    sampler = wl.IdSampler(cfg)
+    users_ids = [(wl.make_user(cfg, rng, seq_len=L), sampler.sample(rng, n)) for n, L in [(600, 150), (45, 77)]]
+    zs, _, _, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), users_ids, max_seq_len=150)
+    assert ctx.aif_stage_kind("attention") == 1 and ctx.aif_stage_kind("mlp") == 0
+    for r, ((u, ids), z) in enumerate(zip(users_ids, zs)):
+        ref = oracle_scores(cfg, model, table, u, ids, n_threads=4)
+        X = R.peek_features(ctx, cfg, r, ids.size)
+        assert np.array_equal(X[:, :cfg.d_item], table[ids])
+        assert_features_close("bf16", X[:, cfg.d_item:cfg.d_item + cfg.d_attn], ref.attn, f"req {r} attention")
+        assert_features_close("bf16", X[:, cfg.d_item + cfg.d_attn:], ref.cross, f"req {r} cross")
+        assert_logits_close("bf16", z, ref.logits, f"req {r}")
+
+
 def test_forced_generic_kernels_on_bf16_config(R, torch, monkeypatch):
     """The shape-agnostic kernels must also serve a bf16 model the MFMA kernels cover."""
     monkeypatch.setenv("AIF_FORCE_GENERIC", "1")
