@@ -19,6 +19,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "aif_oracle.c")
+_SRCS = [_SRC, os.path.join(_HERE, "aif_lsh_oracle.c")]
 _LIB = os.path.join(_HERE, "libaif_oracle.so")
 
 OK, EINVAL, ESHAPE, ENOMEM, ERANGE = 0, 1, 2, 3, 5
@@ -27,10 +28,10 @@ CROSS_NONE, CROSS_HADAMARD, CROSS_SEGDOT = 0, 1, 2
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc -O2 (no fast-math) into a shared object."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS)
     if force or stale:
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c99", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+            ["gcc", "-O2", "-std=c99", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, *_SRCS, "-lm"]
         )
     return _LIB
 
@@ -193,3 +194,96 @@ def topk(z, k: int):
     val = np.empty(max(k, 0), np.float64)
     _check(lib().aifo_topk(_p(z, C.c_double), z.size, k, _p(idx, C.c_int32), _p(val, C.c_double)))
     return idx, val
+
+
+# ---------------------------------------------------------------------------
+# LSH behaviour modelling (aif_lsh_oracle.c; Sec. 4.3, Eq. 5-9, Table 3)
+# ---------------------------------------------------------------------------
+def _u8(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.uint8)
+
+
+def lsh_pack_bits(bits) -> np.ndarray:
+    """d' bits (0/1) -> d'/8 bytes, first bit most significant."""
+    bits = _u8(bits)
+    out = np.empty(bits.size // 8, dtype=np.uint8)
+    lib().aifo_lsh_pack_bits(_p(bits, C.c_uint8), C.c_int(bits.size), _p(out, C.c_uint8))
+    return out
+
+
+def lsh_sign(M, w_hash) -> np.ndarray:
+    """Eq. 5: signatures [n, d'/8] of embeddings M [n, d] under hyperplanes w_hash [d', d]."""
+    M, w_hash = _f32(M), _f32(w_hash)
+    n, d = M.shape
+    d_bits = w_hash.shape[0]
+    sig = np.empty((n, d_bits // 8), dtype=np.uint8)
+    rc = lib().aifo_lsh_sign(_p(M, C.c_float), C.c_int(n), C.c_int(d), _p(w_hash, C.c_float), C.c_int(d_bits),
+                             _p(sig, C.c_uint8))
+    if rc:
+        raise OracleError(rc)
+    return sig
+
+
+def lsh_equal_bits(a, b) -> int:
+    """Eq. 6 numerator: number of equal bits of two signatures."""
+    a, b = _u8(a), _u8(b)
+    f = lib().aifo_lsh_equal_bits
+    f.restype = C.c_int
+    return int(f(_p(a, C.c_uint8), _p(b, C.c_uint8), C.c_int(a.size)))
+
+
+def lsh_din(equal, d_bits: int, u_seq) -> np.ndarray:
+    """Eq. 8 for one candidate from its equal-bit counts [L] and U~ [L, d]."""
+    equal = np.ascontiguousarray(equal, dtype=np.int32)
+    u_seq = _f32(u_seq)
+    L, d = u_seq.shape
+    a = np.empty(d, dtype=np.float64)
+    lib().aifo_lsh_din(_p(equal, C.c_int32), C.c_int(L), C.c_int(d_bits), _p(u_seq, C.c_float), C.c_int(d),
+                       _p(a, C.c_double))
+    return a
+
+
+def simtier(equal, d_bits: int, n_tiers: int) -> np.ndarray:
+    """Eq. 9 for one candidate: counts per tier."""
+    equal = np.ascontiguousarray(equal, dtype=np.int32)
+    out = np.empty(n_tiers, dtype=np.int32)
+    lib().aifo_simtier(_p(equal, C.c_int32), C.c_int(equal.size), C.c_int(d_bits), C.c_int(n_tiers),
+                       _p(out, C.c_int32))
+    return out
+
+
+@dataclass
+class LshResult:
+    din: np.ndarray         # [n, d] float64
+    tiers: np.ndarray       # [n, n_tiers] int32
+    equal: Optional[np.ndarray]   # [n, L] int32 when asked for
+
+
+def lsh_request(*, sig_table, ids, seq_sig, u_seq, n_tiers: int, want_equal: bool = False,
+                n_threads: int = 1) -> LshResult:
+    """One request of the LSH path: signature lookup, Eq. 7, Eq. 8 and Eq. 9 for every candidate."""
+    sig_table, seq_sig, u_seq = _u8(sig_table), _u8(seq_sig), _f32(u_seq)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    n_items, nb = sig_table.shape
+    L, d = u_seq.shape
+    assert seq_sig.shape == (L, nb)
+    n = ids.size
+    din = np.empty((n, d), dtype=np.float64)
+    tiers = np.empty((n, n_tiers), dtype=np.int32)
+    eq = np.empty((n, L), dtype=np.int32) if want_equal else None
+    f = lib().aifo_lsh_request
+    f.restype = C.c_int
+    rc = f(_p(sig_table, C.c_uint8), C.c_int64(n_items), C.c_int(8 * nb), _p(ids, C.c_int32), C.c_int(n),
+           _p(seq_sig, C.c_uint8), _p(u_seq, C.c_float), C.c_int(L), C.c_int(d), C.c_int(n_tiers),
+           _p(din, C.c_double), _p(tiers, C.c_int32), _p(eq, C.c_int32), C.c_int(n_threads))
+    if rc:
+        raise OracleError(rc)
+    return LshResult(din, tiers, eq)
+
+
+def lsh_similarity_cost(b: float, l: float, widths: Sequence[float]) -> float:
+    """Table 3: b * l * (sum of the widths entering the attention / similarity modules)."""
+    w = np.ascontiguousarray(widths, dtype=np.float64)
+    f = lib().aifo_lsh_similarity_cost
+    f.restype = C.c_double
+    return float(f(C.c_double(b), C.c_double(l), _p(w, C.c_double), C.c_int(w.size)))
