@@ -22,6 +22,9 @@ EXPORTS = ("aif_score_init", "aif_score_request", "aif_score_batch", "aif_topk",
            "aif_last_error", "aif_poll_device_errors", "aif_peek_features", "aif_profile_begin",
            "aif_profile_end", "aif_stage_kind")
 STAGES = ("gather", "user_fold", "attention", "mlp", "topk")
+LSH_EXPORTS = ("aif_lsh_init", "aif_lsh_batch", "aif_lsh_destroy", "aif_lsh_last_error",
+               "aif_lsh_poll_device_errors", "aif_lsh_profile_begin", "aif_lsh_profile_end")
+LSH_STAGES = ("user", "din", "simtier")
 
 
 class aif_config(C.Structure):
@@ -41,6 +44,18 @@ class aif_request(C.Structure):
     _fields_ = [("user_vec", C.c_void_p), ("cross_vecs", C.c_void_p), ("seq_keys", C.c_void_p),
                 ("seq_vals", C.c_void_p), ("seq_len", C.c_int32), ("cand_ids", C.c_void_p),
                 ("n_cand", C.c_int32), ("logits_out", C.c_void_p), ("scores_out", C.c_void_p)]
+
+
+class aif_lsh_config(C.Structure):
+    _fields_ = [("n_items", C.c_int64), ("d_bits", C.c_int32), ("d_out", C.c_int32), ("n_tiers", C.c_int32),
+                ("dtype", C.c_int), ("max_seq_len", C.c_int32), ("max_candidates", C.c_int32),
+                ("max_users", C.c_int32)]
+
+
+class aif_lsh_request(C.Structure):
+    _fields_ = [("seq_sigs", C.c_void_p), ("seq_emb", C.c_void_p), ("seq_len", C.c_int32),
+                ("cand_ids", C.c_void_p), ("n_cand", C.c_int32), ("din_out", C.c_void_p),
+                ("tier_out", C.c_void_p)]
 
 
 _lib = None
@@ -78,6 +93,20 @@ def load():
     lib.aif_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     lib.aif_stage_kind.restype = C.c_int32
     lib.aif_stage_kind.argtypes = [vp, C.c_int32]
+    lib.aif_lsh_init.restype = C.c_int
+    lib.aif_lsh_init.argtypes = [C.POINTER(aif_lsh_config), vp, C.POINTER(vp)]
+    lib.aif_lsh_batch.restype = C.c_int
+    lib.aif_lsh_batch.argtypes = [vp, C.POINTER(aif_lsh_request), C.c_int32, vp]
+    lib.aif_lsh_destroy.restype = None
+    lib.aif_lsh_destroy.argtypes = [vp]
+    lib.aif_lsh_last_error.restype = C.c_char_p
+    lib.aif_lsh_last_error.argtypes = [vp]
+    lib.aif_lsh_poll_device_errors.restype = C.c_int
+    lib.aif_lsh_poll_device_errors.argtypes = [vp, C.POINTER(C.c_int32)]
+    lib.aif_lsh_profile_begin.restype = C.c_int
+    lib.aif_lsh_profile_begin.argtypes = [vp, C.c_int32]
+    lib.aif_lsh_profile_end.restype = C.c_int
+    lib.aif_lsh_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     _lib = lib
     return lib
 
@@ -195,6 +224,80 @@ class Context:
     def close(self):
         if self._h:
             self._lib.aif_score_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class LshRequest:
+    """Device tensors of one request of the LSH path."""
+
+    def __init__(self, seq_sigs, seq_emb, cand_ids, din_out, tier_out, seq_len: Optional[int] = None):
+        self.seq_sigs, self.seq_emb, self.cand_ids, self.din_out, self.tier_out = seq_sigs, seq_emb, cand_ids, din_out, tier_out
+        self.seq_len = int(seq_sigs.shape[0]) if seq_len is None else int(seq_len)
+        self.n_cand = int(cand_ids.numel())
+
+    def fill(self, r: aif_lsh_request):
+        r.seq_sigs = _ptr(self.seq_sigs)
+        r.seq_emb = _ptr(self.seq_emb)
+        r.seq_len = self.seq_len
+        r.cand_ids = _ptr(self.cand_ids)
+        r.n_cand = self.n_cand
+        r.din_out = _ptr(self.din_out)
+        r.tier_out = _ptr(self.tier_out)
+
+
+def pack_lsh_requests(reqs: Sequence[LshRequest]):
+    arr = (aif_lsh_request * max(len(reqs), 1))()
+    for i, q in enumerate(reqs):
+        q.fill(arr[i])
+    return arr
+
+
+class LshContext:
+    """Owns one ``aif_lsh_ctx``.  Methods carry the names of the C entry points."""
+
+    def __init__(self, *, sig_table, d_out: int, n_tiers: int, dtype: int, max_seq_len: int, max_candidates: int,
+                 max_users: int = 1):
+        self._lib = load()
+        self._h = C.c_void_p()
+        cfg = aif_lsh_config(int(sig_table.shape[0]), 8 * int(sig_table.shape[1]), d_out, n_tiers, dtype, max_seq_len,
+                             max_candidates, max_users)
+        self._keep = (sig_table,)
+        st = self._lib.aif_lsh_init(C.byref(cfg), _ptr(sig_table), C.byref(self._h))
+        if st != AIF_OK:
+            self._h = C.c_void_p()
+            raise AifError(st, self._lib.aif_lsh_last_error(None).decode())
+
+    def _check(self, st: int):
+        if st != AIF_OK:
+            raise AifError(st, self._lib.aif_lsh_last_error(self._h).decode())
+
+    def aif_lsh_batch(self, reqs: Sequence[LshRequest], packed=None):
+        arr = pack_lsh_requests(reqs) if packed is None else packed
+        self._check(self._lib.aif_lsh_batch(self._h, arr, len(reqs), _stream()))
+
+    def aif_lsh_poll_device_errors(self) -> int:
+        n = C.c_int32(0)
+        self._check(self._lib.aif_lsh_poll_device_errors(self._h, C.byref(n)))
+        return n.value
+
+    def aif_lsh_profile_begin(self, max_calls: int):
+        self._check(self._lib.aif_lsh_profile_begin(self._h, max_calls))
+
+    def aif_lsh_profile_end(self):
+        ms = (C.c_double * len(LSH_STAGES))()
+        n = (C.c_int32 * len(LSH_STAGES))()
+        self._check(self._lib.aif_lsh_profile_end(self._h, ms, n))
+        return {s: (ms[i], n[i]) for i, s in enumerate(LSH_STAGES)}
+
+    def close(self):
+        if self._h:
+            self._lib.aif_lsh_destroy(self._h)
             self._h = C.c_void_p()
 
     def __del__(self):

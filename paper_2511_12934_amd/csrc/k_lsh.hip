@@ -1,0 +1,321 @@
+// LSH-based long-sequence behaviour modelling (Sec. 4.3): signature similarity
+// by XNOR + population count (Eq. 6, 7), LSH-DIN (Eq. 8) and SimTier (Eq. 9).
+//
+// SimTier needs every (candidate, history item) similarity, so its kernel walks
+// the b x l pairs: a lane owns one candidate, the history signatures are the
+// same for all lanes and arrive through scalar loads, a pair costs two XNORs,
+// two population counts and a handful of integer instructions that bump one
+// byte of a packed 64-bit histogram (eight tiers, flushed before a byte can
+// overflow).  Plain integer work, bound by the vector ALU.
+//
+// LSH-DIN does NOT need the pairs.  Eq. 8 has no softmax: the weight of
+// history item t is (number of equal bits) / d' = (1/d') sum_k [b_ik == b_tk],
+// so
+//     DIN_i = (1/d') sum_k A[b_ik][k],   A[s][k] = sum over t with b_tk == s of U~_t,
+// and the 2 d' vectors A[s][k] belong to the user alone.  They are formed once
+// per request (a2 of this path: user-side staging, in chunks of the history
+// summed in a fixed order), after which a candidate costs d' additions per
+// output feature instead of l multiply-adds.  Same value as Eq. 8 up to the
+// order of the fp32 additions.
+#include "aif_lsh_dev.h"
+
+namespace aif {
+
+__device__ __forceinline__ float lsh_ld(const void *p, int dtype, size_t i)
+{
+    return dtype == 0 ? ((const float *)p)[i] : __uint_as_float(((uint32_t)((const uint16_t *)p)[i]) << 16);
+}
+
+// ---------------------------------------------------------------------------
+// user side, partial sums.  Block (chunk, request); a work item is (bit k, group of 16 features).
+// ---------------------------------------------------------------------------
+constexpr int LSH_TSUB = 128;           // history items staged in LDS at a time
+
+__global__ __launch_bounds__(256) void k_lsh_user_partial(LshModel m, LshBatch b, int max_chunks, float *__restrict__ part)
+{
+    extern __shared__ __align__(16) char lds[];
+    const int r = blockIdx.y, chunk = blockIdx.x;
+    const LshReqDesc rd = b.reqs[r];
+    const int t_lo = chunk * LSH_TCHUNK;
+    if (t_lo >= rd.seq_len) return;
+    const int t_hi = min(rd.seq_len, t_lo + LSH_TCHUNK);
+    const int d = m.d_out, nb = m.d_bits / 8, jg = d / 16, items = m.d_bits * jg;
+    float *su = (float *)lds;                               // [LSH_TSUB][d]
+    uint8_t *ss = (uint8_t *)(su + LSH_TSUB * d);           // [LSH_TSUB][nb]
+    float *out = part + ((size_t)r * max_chunks + chunk) * 2 * m.d_bits * d;
+
+    for (int item0 = 0; item0 < items; item0 += 256) {
+        const int item = item0 + threadIdx.x;
+        const bool work = item < items;
+        const int k = work ? item / jg : 0, j0 = work ? (item - k * jg) * 16 : 0;
+        float a0[16], a1[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) a0[i] = a1[i] = 0.f;
+        for (int ts = t_lo; ts < t_hi; ts += LSH_TSUB) {
+            const int nt = min(LSH_TSUB, t_hi - ts);
+            __syncthreads();
+            for (int i = threadIdx.x; i < nt * d; i += 256) su[i] = lsh_ld(rd.seq_emb, m.dtype, (size_t)ts * d + i);
+            for (int i = threadIdx.x; i < nt * nb; i += 256) ss[i] = rd.seq_sigs[(size_t)ts * nb + i];
+            __syncthreads();
+            if (work) {
+                // sums of the staged items first, then into the chunk's sums: short chains of additions
+                float s0[16], s1[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s0[i] = s1[i] = 0.f;
+                for (int t = 0; t < nt; ++t) {
+                    // bit k of a signature: byte k / 8, first bit most significant
+                    const float bit = (float)((ss[t * nb + (k >> 3)] >> (7 - (k & 7))) & 1);
+                    const float4 *u4 = (const float4 *)(su + t * d + j0);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 u = u4[q];
+                        s1[4 * q + 0] = fmaf(bit, u.x, s1[4 * q + 0]);
+                        s1[4 * q + 1] = fmaf(bit, u.y, s1[4 * q + 1]);
+                        s1[4 * q + 2] = fmaf(bit, u.z, s1[4 * q + 2]);
+                        s1[4 * q + 3] = fmaf(bit, u.w, s1[4 * q + 3]);
+                        s0[4 * q + 0] = fmaf(1.f - bit, u.x, s0[4 * q + 0]);
+                        s0[4 * q + 1] = fmaf(1.f - bit, u.y, s0[4 * q + 1]);
+                        s0[4 * q + 2] = fmaf(1.f - bit, u.z, s0[4 * q + 2]);
+                        s0[4 * q + 3] = fmaf(1.f - bit, u.w, s0[4 * q + 3]);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    a0[i] += s0[i];
+                    a1[i] += s1[i];
+                }
+            }
+        }
+        if (work) {
+            float4 *o0 = (float4 *)(out + (size_t)k * d + j0);
+            float4 *o1 = (float4 *)(out + (size_t)(m.d_bits + k) * d + j0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                o0[q] = make_float4(a0[4 * q], a0[4 * q + 1], a0[4 * q + 2], a0[4 * q + 3]);
+                o1[q] = make_float4(a1[4 * q], a1[4 * q + 1], a1[4 * q + 2], a1[4 * q + 3]);
+            }
+        }
+    }
+}
+
+hipError_t launch_lsh_user_partial(const LshModel &m, const LshBatch &b, int grid_chunks, int max_chunks, float *part,
+                                   hipStream_t s)
+{
+    if (b.n_req == 0 || grid_chunks == 0) return hipSuccess;
+    const size_t lds = (size_t)LSH_TSUB * (m.d_out * 4 + m.d_bits / 8);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_lsh_user_partial, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_lsh_user_partial, dim3(grid_chunks, b.n_req), dim3(256), lds, s, m, b, max_chunks, part);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_lsh_user_reduce(LshModel m, LshBatch b, int max_chunks, const float *__restrict__ part,
+                                                         float *__restrict__ A)
+{
+    const int r = blockIdx.y;
+    const size_t n = (size_t)2 * m.d_bits * m.d_out;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int L = b.reqs[r].seq_len;
+    const int chunks = (L + LSH_TCHUNK - 1) / LSH_TCHUNK;
+    float acc = 0.f;
+    for (int c = 0; c < chunks; ++c) acc += part[((size_t)r * max_chunks + c) * n + i];
+    A[(size_t)r * n + i] = acc;
+}
+
+hipError_t launch_lsh_user_reduce(const LshModel &m, const LshBatch &b, int max_chunks, const float *part, float *A,
+                                  hipStream_t s)
+{
+    if (b.n_req == 0) return hipSuccess;
+    const size_t n = (size_t)2 * m.d_bits * m.d_out;
+    hipLaunchKernelGGL(k_lsh_user_reduce, dim3((unsigned)((n + 255) / 256), b.n_req), dim3(256), 0, s, m, b, max_chunks, part, A);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 8.  Block = LSH_BLOCK candidates of one request; d / 16 threads per candidate, 16 features each.
+// The user's table A[2][d'][d] is staged in LDS in slices of KC bits.
+// ---------------------------------------------------------------------------
+constexpr int LSH_DIN_LDS = 64 * 1024;
+
+__global__ __launch_bounds__(256) void k_lsh_din(LshModel m, LshBatch b, const uint8_t *__restrict__ sig_table,
+                                                 const float *__restrict__ A, int32_t *__restrict__ bad)
+{
+    extern __shared__ __align__(16) char lds[];
+    float *sa = (float *)lds;                                   // [2][kc][d]
+    const int blk = blockIdx.x;
+    const int r = b.blk_req[blk];
+    if (r < 0) return;
+    const LshReqDesc rd = b.reqs[r];
+    const int local0 = blk * LSH_BLOCK - rd.cand_base;
+    const int nrows = min(LSH_BLOCK, rd.n_cand - local0);
+    if (nrows <= 0) return;
+    const int d = m.d_out, jg = d / 16, nb = m.d_bits / 8;
+    const int per_round = 256 / jg;                             // candidates served at once
+    const int kc = min(m.d_bits, LSH_DIN_LDS / (2 * d * 4)) & ~7;   // bits per slice, whole bytes
+    const float *Ar = A + (size_t)r * 2 * m.d_bits * d;
+    const int sub = threadIdx.x / jg, j0 = (threadIdx.x - sub * jg) * 16;
+    const float inv = 1.0f / (float)m.d_bits;
+    int n_bad = 0;
+
+    for (int c0 = 0; c0 < nrows; c0 += per_round) {
+        const int cand = c0 + sub;
+        const bool live = sub < per_round && cand < nrows;
+        int64_t id = live ? rd.cand_ids[local0 + cand] : 0;
+        const bool ok = id >= 0 && id < m.n_items;
+        if (!ok) {
+            id = 0;
+            if (live && j0 == 0) ++n_bad;
+        }
+        const uint8_t *sig = sig_table + (size_t)id * nb;
+        float acc[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        for (int k0 = 0; k0 < m.d_bits; k0 += kc) {
+            const int kn = min(kc, m.d_bits - k0);
+            __syncthreads();
+            if (c0 == 0 || kc < m.d_bits) {                     // the whole table fits: staged once
+                for (int i = threadIdx.x; i < 2 * kn * d / 4; i += 256) {
+                    const int s = i / (kn * d / 4), rem = i - s * (kn * d / 4);
+                    ((float4 *)sa)[i] = ((const float4 *)(Ar + ((size_t)s * m.d_bits + k0) * d))[rem];
+                }
+            }
+            __syncthreads();
+            if (live) {
+                for (int kb = 0; kb < kn; kb += 8) {
+                    const uint32_t byte = sig[(k0 + kb) >> 3];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int bit = (byte >> (7 - u)) & 1;
+                        const float4 *a4 = (const float4 *)(sa + ((size_t)bit * kn + kb + u) * d + j0);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float4 v = a4[q];
+                            acc[4 * q + 0] += v.x;
+                            acc[4 * q + 1] += v.y;
+                            acc[4 * q + 2] += v.z;
+                            acc[4 * q + 3] += v.w;
+                        }
+                    }
+                }
+            }
+        }
+        if (live) {
+            float4 *o = (float4 *)(rd.din_out + (size_t)(local0 + cand) * d + j0);
+            const float nanv = __uint_as_float(0x7FC00000u);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                o[q] = ok ? make_float4(acc[4 * q] * inv, acc[4 * q + 1] * inv, acc[4 * q + 2] * inv, acc[4 * q + 3] * inv)
+                          : make_float4(nanv, nanv, nanv, nanv);
+        }
+    }
+    if (n_bad) atomicAdd(bad, n_bad);
+}
+
+hipError_t launch_lsh_din(const LshModel &m, const LshBatch &b, const uint8_t *sig_table, const float *A, int32_t *bad,
+                          hipStream_t s)
+{
+    if (b.n_blk == 0) return hipSuccess;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_lsh_din, hipFuncAttributeMaxDynamicSharedMemorySize, LSH_DIN_LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_lsh_din, dim3(b.n_blk), dim3(256), LSH_DIN_LDS, s, m, b, sig_table, A, bad);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 6, 7, 9.  A lane owns one candidate and walks the whole history.
+// DW = signature width in 32-bit words.
+// ---------------------------------------------------------------------------
+template <int DW>
+__global__ __launch_bounds__(256) void k_lsh_simtier(LshModel m, LshBatch b, const uint8_t *__restrict__ sig_table)
+{
+    const int blk = blockIdx.x;
+    const int r = b.blk_req[blk];
+    if (r < 0) return;
+    const LshReqDesc rd = b.reqs[r];
+    const int local = blk * LSH_BLOCK - rd.cand_base + threadIdx.x;
+    const bool live = local < rd.n_cand;
+    int64_t id = live ? rd.cand_ids[local] : 0;
+    const bool ok = id >= 0 && id < m.n_items;
+    if (!ok) id = 0;
+    uint32_t sig[DW];
+    {
+        const uint32_t *p = (const uint32_t *)(sig_table + (size_t)id * (DW * 4));
+#pragma unroll
+        for (int w = 0; w < DW; ++w) sig[w] = p[w];
+    }
+    const uint32_t *__restrict__ hs = (const uint32_t *)rd.seq_sigs;    // the same for every lane: scalar loads
+    const int L = rd.seq_len;
+    const uint32_t n_tiers = (uint32_t)m.n_tiers, mul = (uint32_t)m.tier_mul;
+    uint32_t total[LSH_MAX_TIERS];
+#pragma unroll
+    for (int j = 0; j < LSH_MAX_TIERS; ++j) total[j] = 0;
+    unsigned long long packed = 0;                          // eight byte-wide tier counters
+
+    auto visit = [&](const uint32_t *h) {
+        uint32_t equal = 0;
+#pragma unroll
+        for (int w = 0; w < DW; ++w) equal += __builtin_popcount(~(sig[w] ^ h[w]));
+        // tier = min(N - 1, floor(equal N / d')): the multiply-shift is exact for equal N <= 2048, d' <= 256
+        uint32_t tier = (equal * n_tiers * mul) >> 20;
+        tier = tier < n_tiers - 1 ? tier : n_tiers - 1;
+        packed += 1ull << (8 * tier);
+    };
+    auto flush = [&]() {
+#pragma unroll
+        for (int j = 0; j < LSH_MAX_TIERS; ++j) total[j] += (uint32_t)(packed >> (8 * j)) & 255u;
+        packed = 0;
+    };
+    constexpr int UNROLL = 16, PER_FLUSH = 15;              // 240 increments at most between flushes
+    int t = 0;
+    while (t + UNROLL <= L) {
+        const int stop = min(L - UNROLL + 1, t + UNROLL * PER_FLUSH);
+        for (; t < stop; t += UNROLL) {
+            uint32_t h[UNROLL * DW];
+#pragma unroll
+            for (int u = 0; u < UNROLL * DW; ++u) h[u] = hs[(size_t)t * DW + u];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) visit(h + u * DW);
+        }
+        flush();
+    }
+    for (; t < L; ++t) {
+        uint32_t h[DW];
+#pragma unroll
+        for (int w = 0; w < DW; ++w) h[w] = hs[(size_t)t * DW + w];
+        visit(h);
+    }
+    flush();
+    if (live) {
+        int32_t *o = rd.tier_out + (size_t)local * m.n_tiers;
+        for (int j = 0; j < m.n_tiers; ++j) o[j] = ok ? (int32_t)total[j] : -1;
+    }
+}
+
+hipError_t launch_lsh_simtier(const LshModel &m, const LshBatch &b, const uint8_t *sig_table, hipStream_t s)
+{
+    if (b.n_blk == 0) return hipSuccess;
+    const dim3 grid(b.n_blk), block(256);
+    switch (m.d_bits / 32) {
+    case 1: hipLaunchKernelGGL(k_lsh_simtier<1>, grid, block, 0, s, m, b, sig_table); break;
+    case 2: hipLaunchKernelGGL(k_lsh_simtier<2>, grid, block, 0, s, m, b, sig_table); break;
+    case 3: hipLaunchKernelGGL(k_lsh_simtier<3>, grid, block, 0, s, m, b, sig_table); break;
+    case 4: hipLaunchKernelGGL(k_lsh_simtier<4>, grid, block, 0, s, m, b, sig_table); break;
+    case 5: hipLaunchKernelGGL(k_lsh_simtier<5>, grid, block, 0, s, m, b, sig_table); break;
+    case 6: hipLaunchKernelGGL(k_lsh_simtier<6>, grid, block, 0, s, m, b, sig_table); break;
+    case 7: hipLaunchKernelGGL(k_lsh_simtier<7>, grid, block, 0, s, m, b, sig_table); break;
+    case 8: hipLaunchKernelGGL(k_lsh_simtier<8>, grid, block, 0, s, m, b, sig_table); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace aif

@@ -169,3 +169,68 @@ class Workload:
         import torch
         ids = torch.from_numpy(self.requests[user].ids[positions].astype(np.int64)).to(self.table.device)
         return from_device_f32(self.table.index_select(0, ids))
+
+
+# ---------------------------------------------------------------------------
+# LSH behaviour modelling (include/aif_lsh.h)
+# ---------------------------------------------------------------------------
+@dataclass
+class LshDeviceRequest:
+    req: B.LshRequest
+    ids_host: np.ndarray
+    din: object             # torch fp32 [n, d_out]
+    tiers: object           # torch int32 [n, n_tiers]
+    keep: tuple
+
+
+def upload_lsh_request(cfg: wl.LshConfig, user: wl.LshUser, ids: np.ndarray, device="cuda:0") -> LshDeviceRequest:
+    import torch
+    sig = torch.from_numpy(np.ascontiguousarray(user.seq_sigs)).to(device)
+    emb = to_device(user.seq_emb, cfg.dtype, device) if user.seq_emb.size else torch.empty((0, cfg.d_out), dtype=torch_dtype(cfg.dtype), device=device)
+    idt = torch.from_numpy(np.ascontiguousarray(ids, dtype=np.int32)).to(device)
+    din = torch.full((ids.size, cfg.d_out), float("nan"), dtype=torch.float32, device=device)
+    tiers = torch.full((ids.size, cfg.n_tiers), -7, dtype=torch.int32, device=device)
+    return LshDeviceRequest(B.LshRequest(sig, emb, idt, din, tiers, seq_len=user.seq_sigs.shape[0]),
+                            np.asarray(ids, np.int32), din, tiers, (sig, emb, idt))
+
+
+def slice_lsh_request(dr: LshDeviceRequest, lo: int, hi: int) -> LshDeviceRequest:
+    q = dr.req
+    return LshDeviceRequest(B.LshRequest(q.seq_sigs, q.seq_emb, q.cand_ids[lo:hi], dr.din[lo:hi], dr.tiers[lo:hi], q.seq_len),
+                            dr.ids_host[lo:hi], dr.din[lo:hi], dr.tiers[lo:hi], dr.keep)
+
+
+def make_lsh_context(cfg: wl.LshConfig, sig_table_dev, *, max_users: Optional[int] = None,
+                     max_candidates: Optional[int] = None, max_seq_len: Optional[int] = None) -> B.LshContext:
+    return B.LshContext(sig_table=sig_table_dev, d_out=cfg.d_out, n_tiers=cfg.n_tiers,
+                        dtype=B.AIF_F32 if cfg.dtype == "f32" else B.AIF_BF16,
+                        max_seq_len=cfg.seq_len if max_seq_len is None else max_seq_len,
+                        max_candidates=cfg.n_cand if max_candidates is None else max_candidates,
+                        max_users=cfg.n_users if max_users is None else max_users)
+
+
+class LshWorkload:
+    """One LSH configuration resident on the device; ``step()`` = one aif_lsh_batch over all users."""
+
+    def __init__(self, cfg: wl.LshConfig, device="cuda:0", n_users: Optional[int] = None,
+                 n_cand: Optional[int] = None, n_items: Optional[int] = None, seq_len: Optional[int] = None):
+        import torch
+        self.cfg = cfg
+        self.n_users = cfg.n_users if n_users is None else n_users
+        self.n_cand = cfg.n_cand if n_cand is None else n_cand
+        self.n_items = cfg.n_items if n_items is None else n_items
+        self.seq_len = cfg.seq_len if seq_len is None else seq_len
+        self.table_host = wl.make_sig_table_host(cfg, self.n_items)
+        self.table = torch.from_numpy(self.table_host).to(device)
+        self.requests = wl.make_lsh_requests(cfg, self.n_users, self.n_cand, self.n_items, self.seq_len)
+        self.dev = [upload_lsh_request(cfg, r.user, r.ids, device) for r in self.requests]
+        self.ctx = make_lsh_context(cfg, self.table, max_users=self.n_users, max_candidates=self.n_cand,
+                                    max_seq_len=self.seq_len)
+        self.packed = B.pack_lsh_requests([d.req for d in self.dev])
+
+    @property
+    def total_candidates(self) -> int:
+        return self.n_users * self.n_cand
+
+    def step(self):
+        self.ctx.aif_lsh_batch([d.req for d in self.dev], packed=self.packed)

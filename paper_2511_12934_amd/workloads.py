@@ -255,3 +255,105 @@ def make_id_lists(cfg: Config, set_index: int, n_users: Optional[int] = None, n_
     nu = cfg.n_users if n_users is None else n_users
     nc = cfg.n_cand if n_cand is None else n_cand
     return [sampler.sample(rng, nc) for _ in range(nu)]
+
+
+# ----------------------------------------------------------------------------
+# LSH behaviour modelling (Sec. 4.3): synthetic signatures and history embeddings
+# ----------------------------------------------------------------------------
+@dataclass(frozen=True)
+class LshConfig:
+    """Shapes of one LSH workload.  Signatures are stand-ins for hashed multi-modal embeddings: items
+    belong to clusters and an item's signature is its cluster's prototype with every bit flipped with
+    probability ``flip`` (so similarities spread over the tiers as those of related and unrelated items
+    do); nothing of the method is computed here."""
+    name: str
+    index: int
+    dtype: str            # storage of the projected history embeddings
+    n_users: int
+    n_cand: int
+    n_items: int
+    d_bits: int           # d' of Eq. 5
+    d_out: int            # d of Eq. 8
+    n_tiers: int          # N of Eq. 9
+    seq_len: int
+    n_clusters: int = 64
+    flip: float = 0.15
+
+    @property
+    def seed(self) -> int:
+        return SEED_BASE + 100 + self.index
+
+    def scaled(self, **kw) -> "LshConfig":
+        return replace(self, **kw)
+
+
+LSH_CONFIGS: Dict[str, LshConfig] = {
+    # small: the oracle finishes it in seconds
+    "L1": LshConfig("L1", 1, "f32", 1, 1_000, 100_000, 64, 64, 8, 2_000),
+    # the long-sequence case: 64 users x 10^4 candidates, 10^4 history items each, 64-bit signatures
+    # (d_lsh = 8 bytes = d / 8, Sec. 5.2.3), 64-wide bf16 history embeddings, 8 tiers
+    "L2": LshConfig("L2", 2, "bf16", 64, 10_000, 10_000_000, 64, 64, 8, 10_000),
+    # wider signatures and outputs, fewer users, l = 10^5 (the scale Sec. 4.3 quotes)
+    "L3": LshConfig("L3", 3, "bf16", 8, 10_000, 10_000_000, 128, 128, 8, 100_000),
+}
+
+
+def _flip_bits(rng: np.random.Generator, proto: np.ndarray, flip: float) -> np.ndarray:
+    """proto [n, nbytes] uint8 -> each bit flipped with probability flip."""
+    n, nb = proto.shape
+    mask = np.packbits(rng.random((n, nb * 8)) < flip, axis=1)
+    return np.bitwise_xor(proto, mask)
+
+
+def make_lsh_prototypes(cfg: LshConfig) -> np.ndarray:
+    rng = np.random.default_rng(cfg.seed)
+    return rng.integers(0, 256, (cfg.n_clusters, cfg.d_bits // 8), dtype=np.uint8)
+
+
+def make_sig_table_host(cfg: LshConfig, n_items: Optional[int] = None, chunk: int = 1 << 18) -> np.ndarray:
+    """Signature table [n_items, d_bits / 8] uint8 (item i belongs to cluster i mod n_clusters)."""
+    n = cfg.n_items if n_items is None else n_items
+    protos = make_lsh_prototypes(cfg)
+    rng = np.random.default_rng(cfg.seed + 1)
+    out = np.empty((n, cfg.d_bits // 8), dtype=np.uint8)
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        out[lo:hi] = _flip_bits(rng, protos[np.arange(lo, hi) % cfg.n_clusters], cfg.flip)
+    return out
+
+
+@dataclass
+class LshUser:
+    seq_sigs: np.ndarray      # [L, d_bits / 8] uint8
+    seq_emb: np.ndarray       # [L, d_out] float32 holding storage-rounded values
+
+
+def make_lsh_user(cfg: LshConfig, rng: np.random.Generator, seq_len: Optional[int] = None, sigma: float = 0.1) -> LshUser:
+    """A user's history: items drawn from a few favoured clusters, their signatures and embeddings."""
+    L = cfg.seq_len if seq_len is None else seq_len
+    protos = make_lsh_prototypes(cfg)
+    fav = rng.choice(cfg.n_clusters, size=min(8, cfg.n_clusters), replace=False)
+    cl = fav[rng.integers(0, fav.size, L)]
+    sigs = _flip_bits(rng, protos[cl], cfg.flip) if L else np.zeros((0, cfg.d_bits // 8), np.uint8)
+    emb = round_storage(rng.standard_normal((L, cfg.d_out)).astype(np.float32) * sigma, cfg.dtype)
+    return LshUser(sigs, emb)
+
+
+@dataclass
+class LshRequestHost:
+    user: LshUser
+    ids: np.ndarray
+
+
+def make_lsh_requests(cfg: LshConfig, n_users: Optional[int] = None, n_cand: Optional[int] = None,
+                      n_items: Optional[int] = None, seq_len: Optional[int] = None) -> List[LshRequestHost]:
+    rng = np.random.default_rng(cfg.seed + 2)
+    nu = cfg.n_users if n_users is None else n_users
+    nc = cfg.n_cand if n_cand is None else n_cand
+    ni = cfg.n_items if n_items is None else n_items
+    out = []
+    for _ in range(nu):
+        user = make_lsh_user(cfg, rng, seq_len)
+        ids = rng.choice(ni, size=nc, replace=False).astype(np.int32) if nc <= ni else rng.integers(0, ni, nc).astype(np.int32)
+        out.append(LshRequestHost(user, ids))
+    return out

@@ -8,8 +8,8 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    src = open(os.path.join(ROOT, "include", "aif.h")).read()
+def _declared(header="aif.h"):
+    src = open(os.path.join(ROOT, "include", header)).read()
     return sorted(set(re.findall(r"AIF_API\s+[\w\s\*]+?\b(aif_\w+)\s*\(", src)))
 
 
@@ -28,6 +28,9 @@ def test_library_exports_every_declared_symbol():
     for name in _declared():
         assert hasattr(lib, name), name
     assert set(binding.EXPORTS) == set(_declared())
+    for name in _declared("aif_lsh.h"):
+        assert hasattr(lib, name), name
+    assert set(binding.LSH_EXPORTS) == set(_declared("aif_lsh.h"))
 
 
 def test_binding_structs_match_the_c_layout():
@@ -38,6 +41,10 @@ def test_binding_structs_match_the_c_layout():
     assert ctypes.sizeof(B.aif_config) == 80
     assert B.aif_config.n_items.offset == 8 and B.aif_config.layer_dims.offset == 56
     assert ctypes.sizeof(B.aif_weights) == 32
+    # aif_lsh.h
+    assert ctypes.sizeof(B.aif_lsh_config) == 40 and B.aif_lsh_config.d_bits.offset == 8
+    assert ctypes.sizeof(B.aif_lsh_request) == 56
+    assert B.aif_lsh_request.cand_ids.offset == 24 and B.aif_lsh_request.din_out.offset == 40
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
