@@ -8,6 +8,9 @@ C3 (64 concurrent users x 10^4 candidates, bf16), the batched 10^4-candidate
 request shape the metric is quoted on.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1..C5]
+
+``--workload L1..L3`` times the LSH behaviour-modelling path instead (aif_lsh_batch: user-side bit
+tables -> LSH-DIN -> SimTier over every candidate x history pair); same JSON contract, its own metric.
 """
 from __future__ import annotations
 
@@ -24,6 +27,8 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 PEAK_MFMA_BF16_TFLOPS = 2500.0   # dense bf16
 PEAK_FP32_VALU_TFLOPS = 157.3
+# 32-bit integer vector ALU: the fp32 figure counts 2 flops per FMA and 2 lanes per packed instruction
+PEAK_INT_VALU_TOPS = PEAK_FP32_VALU_TFLOPS / 4
 
 
 def algorithmic_work(cfg):
@@ -129,12 +134,102 @@ def single_request_latency(n_iter=200):
     return out
 
 
+def lsh_pair_ops(cfg):
+    """Algorithmic integer operations per (candidate, history item) pair of SimTier: per 32-bit word of the
+    signatures one XNOR and one population count (Eq. 6), then tier index (multiply, shift, clamp) and the
+    count increment (Eq. 9)."""
+    return 2 * (cfg.d_bits // 32) + 4
+
+
+def lsh_cpu_baseline(cfg, w, seconds_budget=15.0):
+    import numpy as np
+
+    import oracle
+    threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1))
+
+    def run(u, n_c):
+        rq = w.requests[u]
+        t0 = time.perf_counter()
+        oracle.lsh_request(sig_table=w.table_host, ids=rq.ids[:n_c], seq_sig=rq.user.seq_sigs, u_seq=rq.user.seq_emb,
+                           n_tiers=cfg.n_tiers, n_threads=threads)
+        return time.perf_counter() - t0
+
+    n_probe = min(w.n_cand, 200)
+    per_cand = run(0, n_probe) / n_probe                # probe (also warms the thread pool)
+    t_request = per_cand * w.n_cand
+    if t_request > seconds_budget:
+        n_users, n_c = 1, max(n_probe, int(w.n_cand * seconds_budget / t_request))
+    else:
+        n_users, n_c = int(min(w.n_users, max(1, seconds_budget // t_request))), w.n_cand
+    t = sum(run(u, n_c) for u in range(n_users))
+    return {"value": n_users * n_c / t, "unit": "candidates/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n_users} request(s) x {n_c} candidates of {cfg.name}, history {w.seq_len} (oracle Eq. 6-9, "
+                      f"{threads} OpenMP threads, {t:.1f} s wall, {t * threads:.0f} core-seconds)"}
+
+
+def main_lsh(args):
+    import torch
+
+    from paper_2511_12934_amd import runner as R
+    from paper_2511_12934_amd import workloads as wl
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    cfg = wl.LSH_CONFIGS[args.workload]
+    w = R.LshWorkload(cfg)
+    for _ in range(args.warmup):
+        w.step()
+    torch.cuda.synchronize()
+    w.ctx.aif_lsh_profile_begin(args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        w.step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = w.ctx.aif_lsh_profile_end()
+    ms_per_step = elapsed / args.steps * 1e3
+    cands = w.total_candidates
+    pairs = cands * w.seq_len
+    kernels = {st: {"avg_ms": ms / max(n, 1)} for st, (ms, n) in prof.items()}
+    kernels["simtier"]["tops"] = lsh_pair_ops(cfg) * pairs / (kernels["simtier"]["avg_ms"] * 1e-3) / 1e12
+    kernels["simtier"]["pairs_per_s"] = pairs / (kernels["simtier"]["avg_ms"] * 1e-3)
+    # LSH-DIN: bytes the method needs per candidate: id + signature read, d_out fp32 written
+    kernels["din"]["gbs"] = (4 + cfg.d_bits // 8 + 4 * cfg.d_out) * cands / (kernels["din"]["avg_ms"] * 1e-3) / 1e9
+    dom = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+    if dom == "simtier":
+        roof = {"kernel": "k_lsh_simtier", "bound": "alu", "achieved": kernels[dom]["tops"], "peak": PEAK_INT_VALU_TOPS,
+                "unit": "Top/s"}
+    elif dom == "din":
+        roof = {"kernel": "k_lsh_din", "bound": "hbm", "achieved": kernels[dom]["gbs"], "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    else:
+        flops = 4.0 * cfg.d_bits * cfg.d_out * w.seq_len * w.n_users       # two masked multiply-adds per (t, k, j)
+        roof = {"kernel": "k_lsh_user_partial", "bound": "alu", "achieved": flops / (kernels[dom]["avg_ms"] * 1e-3) / 1e12,
+                "peak": PEAK_FP32_VALU_TFLOPS / 2, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = measured_traffic(cfg.name, dom)
+    roof["avg_ms"] = kernels[dom]["avg_ms"]
+    line = {
+        "metric": "candidates served/sec/GPU by the LSH behaviour modelling (LSH-DIN + SimTier)",
+        "value": cands * args.steps / elapsed, "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u32" if dom == "simtier" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {w.n_users} users x {w.n_cand} candidates x {w.seq_len} history items, "
+                               f"{cfg.d_bits}-bit signatures (table {cfg.n_items} rows), d={cfg.d_out} {cfg.dtype}, "
+                               f"{cfg.n_tiers} tiers",
+                   "users": w.n_users, "candidates_per_request": w.n_cand, "seq_len": w.seq_len},
+        "pairs_per_s": pairs * args.steps / elapsed,
+        "roofline": roof, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = lsh_cpu_baseline(cfg, w)
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5", "L1", "L2", "L3"])
     ap.add_argument("--id-sets", type=int, default=4,
                     help="distinct candidate lists per user, taken in turn by consecutive steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -143,6 +238,9 @@ def main():
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (requests shard by user with no exchange; "
                  "see DESIGN.md); run with --gpus 1")
+
+    if args.workload.startswith("L"):
+        return main_lsh(args)
 
     import torch
 

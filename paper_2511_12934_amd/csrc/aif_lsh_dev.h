@@ -6,7 +6,7 @@
 namespace aif {
 
 constexpr int LSH_BLOCK = 256;          // candidates per scheduling block
-constexpr int LSH_TCHUNK = 2048;        // history items whose user-side sums one block forms
+constexpr int LSH_TCHUNK = 512;         // history items whose user-side sums one block forms
 constexpr int LSH_MAX_TIERS = 8;
 
 struct LshReqDesc {

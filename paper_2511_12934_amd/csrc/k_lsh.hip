@@ -254,7 +254,9 @@ __global__ __launch_bounds__(256) void k_lsh_simtier(LshModel m, LshBatch b, con
     }
     const uint32_t *__restrict__ hs = (const uint32_t *)rd.seq_sigs;    // the same for every lane: scalar loads
     const int L = rd.seq_len;
-    const uint32_t n_tiers = (uint32_t)m.n_tiers, mul = (uint32_t)m.tier_mul;
+    // 8 * tier = min(8 (N - 1), ((equal * N * tier_mul) >> 17) & ~7); equal <= 256 and N * tier_mul < 2^19 fit a
+    // 24-bit multiply, and the multiply-shift is exact for equal N <= 2048, d' <= 256
+    const uint32_t scale = (uint32_t)m.n_tiers * (uint32_t)m.tier_mul, top8 = 8u * (uint32_t)(m.n_tiers - 1);
     uint32_t total[LSH_MAX_TIERS];
 #pragma unroll
     for (int j = 0; j < LSH_MAX_TIERS; ++j) total[j] = 0;
@@ -264,10 +266,9 @@ __global__ __launch_bounds__(256) void k_lsh_simtier(LshModel m, LshBatch b, con
         uint32_t equal = 0;
 #pragma unroll
         for (int w = 0; w < DW; ++w) equal += __builtin_popcount(~(sig[w] ^ h[w]));
-        // tier = min(N - 1, floor(equal N / d')): the multiply-shift is exact for equal N <= 2048, d' <= 256
-        uint32_t tier = (equal * n_tiers * mul) >> 20;
-        tier = tier < n_tiers - 1 ? tier : n_tiers - 1;
-        packed += 1ull << (8 * tier);
+        uint32_t tier8 = (__umul24(equal, scale) >> 17) & ~7u;
+        tier8 = tier8 < top8 ? tier8 : top8;
+        packed += 1ull << tier8;
     };
     auto flush = [&]() {
 #pragma unroll

@@ -27,10 +27,10 @@ def torch():
 
 def din_tolerance(u_seq, L, d_bits):
     """Per output feature j.  Every U~[t, j] enters the GPU's sum exactly d' times (once per bit, in the table
-    of the value the candidate's bit takes) through chains of at most 128 (staged items) + 16 (stagings per
-    chunk) + chunks + d' (bits) fp32 additions, then one division by d'.  The standard bound for a sum,
+    of the value the candidate's bit takes) through chains of at most 128 (staged items) + 4 (stagings per
+    chunk of 512) + chunks + d' (bits) fp32 additions, then one division by d'.  The standard bound for a sum,
     n u sum|x| with u = 2^-24, over the d' copies and divided by d' gives  n 2^-24 sum_t |U~[t, j]|."""
-    n = 128 + 16 + (L + 2047) // 2048 + d_bits + 2
+    n = 128 + 4 + (L + 511) // 512 + d_bits + 2
     return n * 2.0 ** -24 * np.abs(u_seq.astype(np.float64)).sum(0) + 1e-30
 
 
@@ -79,7 +79,7 @@ def test_shapes_ragged(R, torch, dtype, d_bits, d_out, n_tiers):
     table = wl.make_sig_table_host(cfg)
     rng = np.random.default_rng(d_bits + d_out)
     users_ids = []
-    for n, L in [(1, 1), (5, 0), (255, 15), (256, 16), (257, 17), (700, 255), (33, 256), (64, 2049), (300, 4100)]:
+    for n, L in [(1, 1), (5, 0), (255, 15), (256, 16), (257, 17), (700, 255), (33, 256), (64, 513), (300, 1100)]:
         users_ids.append((wl.make_lsh_user(cfg, rng, seq_len=L, sigma=1.0), rng.integers(0, cfg.n_items, n).astype(np.int32)))
     check(R, torch, cfg, table, users_ids)
 
@@ -124,3 +124,33 @@ def test_bad_ids_and_host_errors(R, torch):
         ctx.aif_lsh_batch([big.req])                      # n_cand beyond max_candidates
     with pytest.raises(AifError):
         ctx.aif_lsh_batch([d.req, d.req, d.req])          # more requests than max_users
+
+
+@pytest.mark.parametrize("name", ["L2", "L3"])
+def test_full_size_config_sampled(R, torch, name):
+    """The configurations bench.py can time, at full size and in its launch configuration (one aif_lsh_batch over
+    all users): sampled candidates against the oracle one by one, and properties that hold at any size."""
+    cfg = wl.LSH_CONFIGS[name]
+    _say(f"{name} full size {cfg.n_users} x {cfg.n_cand} x {cfg.seq_len}")
+    w = R.LshWorkload(cfg)
+    w.step()
+    torch.cuda.synchronize()
+    _say("step done")
+    assert w.ctx.aif_lsh_poll_device_errors() == 0
+    rng = np.random.default_rng(77)
+    for u in sorted({0, cfg.n_users - 1, int(rng.integers(0, cfg.n_users))}):
+        rq = w.requests[u]
+        tiers = w.dev[u].tiers.cpu().numpy()
+        assert np.all(tiers.sum(1) == cfg.seq_len), "a candidate's tier counts must add up to the history length"
+        pos = np.unique(np.concatenate([[0, 255, 256, cfg.n_cand - 1], rng.integers(0, cfg.n_cand, 60)]))
+        ref = oracle.lsh_request(sig_table=w.table_host, ids=rq.ids[pos], seq_sig=rq.user.seq_sigs, u_seq=rq.user.seq_emb,
+                                 n_tiers=cfg.n_tiers, n_threads=8)
+        assert np.array_equal(tiers[pos], ref.tiers), f"user {u}"
+        din = w.dev[u].din.cpu().numpy()[pos].astype(np.float64)
+        tol = din_tolerance(rq.user.seq_emb, cfg.seq_len, cfg.d_bits)
+        assert np.all(np.abs(din - ref.din) <= tol[None, :]), (u, np.abs(din - ref.din).max(), tol.max())
+        _say(f"user {u}: max |d DIN| = {np.abs(din - ref.din).max():.3e} (bar {tol.min():.3e})")
+    d0, t0 = w.dev[0].din.clone(), w.dev[0].tiers.clone()
+    w.step()
+    torch.cuda.synchronize()
+    assert torch.equal(d0, w.dev[0].din) and torch.equal(t0, w.dev[0].tiers)
