@@ -54,17 +54,22 @@ def algorithmic_work(cfg):
 
 def measured_traffic(workload, stage):
     """HBM bytes per launch of a stage's kernel as rocprofv3's FETCH_SIZE + WRITE_SIZE counters gave them
-    (scaled by a copy kernel of known size); read from the committed counter summary, None if it has no
+    (scaled by a copy kernel of known size); read from the committed counter summaries under profiles/, None if none has a
     line for this workload and stage.  Line format: ``traffic_bytes_per_launch <workload> <stage> <bytes>``."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_counters.txt")
+    folder = os.path.join(ROOT, "profiles")
     try:
-        with open(path) as f:
-            for ln in f:
-                t = ln.split()
-                if len(t) == 4 and t[0] == "traffic_bytes_per_launch" and t[1] == workload and t[2] == stage:
-                    return float(t[3])
+        names = sorted(n for n in os.listdir(folder) if n.endswith(".txt"))
     except OSError:
-        pass
+        return None
+    for name in names:
+        try:
+            with open(os.path.join(folder, name)) as f:
+                for ln in f:
+                    t = ln.split()
+                    if len(t) == 4 and t[0] == "traffic_bytes_per_launch" and t[1] == workload and t[2] == stage:
+                        return float(t[3])
+        except OSError:
+            pass
     return None
 
 
