@@ -144,7 +144,11 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
 #pragma unroll
         for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
         float mc = c * sqrtf(ss) * 1.001f * km;
-        if (__any(mc > BOUND_LIMIT)) {
+        // A candidate's choice between the bound and the true maximum depends on its own row only
+        // (rows past the end of the request hold whatever the workspace held before and take no part),
+        // so its bits do not depend on which candidates share its wave.
+        const bool need_max = live && mc > BOUND_LIMIT;
+        if (__any(need_max)) {
             // rare: take the true maximum with an extra pass over K (read straight from memory)
             float mx = -INFINITY;
             for (int kt = 0; kt < nkt; ++kt) {
@@ -162,7 +166,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
                 }
             }
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            mc = c * mx;
+            if (need_max) mc = c * mx;
         }
 
         f32x16 O[FT];
@@ -389,7 +393,8 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
             return S;
         };
         float mc = c * sqrtf(ss) * 1.001f * skm[hd];
-        if (__any(mc > BOUND_LIMIT)) {
+        const bool need_max = live && mc > BOUND_LIMIT;      // per candidate, as in k_attn_mfma
+        if (__any(need_max)) {
             // rare: take the true maximum with an extra pass over K
             float mx = -INFINITY;
             for (int kt = 0; kt < nkt; ++kt) {
@@ -401,7 +406,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                 }
             }
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            mc = c * mx;
+            if (need_max) mc = c * mx;
         }
 
         f32x16 O[FT];

@@ -329,6 +329,33 @@ def test_mfma_kernels_on_row_major_workspace(R, torch, monkeypatch):
     assert_logits_close("bf16", z1, oracle_scores(cfg, model, table, u, ids).logits)
 
 
+def test_stale_workspace_rows_do_not_change_a_candidates_bits(R, torch):
+    """Rows of the workspace past the end of a request keep what an earlier call left there.  A call with
+    huge-valued rows (their softmax takes the true maximum instead of the norm bound) is followed, on the same
+    context, by a shorter request at the configurations' scale whose last tile ends among those rows: its
+    candidates must come out bit for bit as on a fresh context."""
+    cfg = wl.CONFIGS["C3"].scaled(n_items=3000)
+    _say("C3 shape, stale huge rows in the padded tail of the last tile")
+    rng = np.random.default_rng(23)
+    model = wl.make_model(cfg)
+    table = wl.make_table_host(cfg, rng, n_items=3000)
+    table[:1500] = wl.round_storage(table[:1500] * 300.0, "bf16")
+    u_big = wl.make_user(cfg, rng, sigma=30.0)
+    u = wl.make_user(cfg, rng)
+    ids_big = rng.permutation(1500)[:64].astype(np.int32)
+    ids = (1500 + rng.permutation(1500)[:40]).astype(np.int32)
+    table_dev = R.to_device(table, "bf16")
+    (zb,), _, _, ctx = run_batch(R, torch, cfg, model, table_dev, [(u_big, ids_big)], max_seq_len=cfg.seq_len)
+    assert np.all(np.isfinite(zb))
+    (z1,), _, _, _ = run_batch(R, torch, cfg, model, table_dev, [(u, ids)], ctx=ctx)
+    X1 = R.peek_features(ctx, cfg, 0, ids.size)
+    (z0,), _, _, ctx0 = run_batch(R, torch, cfg, model, table_dev, [(u, ids)], max_seq_len=cfg.seq_len)
+    X0 = R.peek_features(ctx0, cfg, 0, ids.size)
+    assert np.array_equal(X0, X1)
+    assert np.array_equal(z0, z1)
+    assert_logits_close("bf16", z1, oracle_scores(cfg, model, table, u, ids).logits)
+
+
 def test_large_scores_do_not_overflow(R, torch):
     """|score| far beyond the fp32 exp range: softmax must subtract its maximum."""
     cfg = small_cfg("f32", d_item=32, d_user=32, d_attn=32, seq_len=33, mlp_dims=(128, 16, 1))
