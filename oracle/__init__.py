@@ -19,11 +19,11 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "aif_oracle.c")
-_SRCS = [_SRC, os.path.join(_HERE, "aif_lsh_oracle.c")]
+_SRCS = [_SRC, os.path.join(_HERE, "aif_lsh_oracle.c"), os.path.join(_HERE, "aif_bea_oracle.c")]
 _LIB = os.path.join(_HERE, "libaif_oracle.so")
 
 OK, EINVAL, ESHAPE, ENOMEM, ERANGE = 0, 1, 2, 3, 5
-CROSS_NONE, CROSS_HADAMARD, CROSS_SEGDOT = 0, 1, 2
+CROSS_NONE, CROSS_HADAMARD, CROSS_SEGDOT, CROSS_BEA = 0, 1, 2, 3
 
 
 def build(force: bool = False) -> str:
@@ -162,7 +162,7 @@ def score(*, table, ids, user_vec, seq_keys, seq_vals, dims, weights, biases=Non
     d_attn = K.shape[1]
     L = K.shape[0]
     assert V.shape == K.shape
-    n_cross, d_c = (cv.shape if (cv is not None and cross_mode == CROSS_SEGDOT) else (0, 0))
+    n_cross, d_c = (cv.shape if (cv is not None and cross_mode in (CROSS_SEGDOT, CROSS_BEA)) else (0, 0))
     d_cross = lib().aifo_cross_width(cross_mode, d_item, n_cross, d_c)
     if d_cross < 0:
         raise OracleError(ESHAPE)
@@ -186,6 +186,32 @@ def score(*, table, ids, user_vec, seq_keys, seq_vals, dims, weights, biases=Non
         _p(z, C.c_double), _p(y, C.c_double), _p(a, C.c_double), _p(c, C.c_double),
         n_threads))
     return Scores(z, y, a, c)
+
+
+def bea_attention_weights(X, Y) -> np.ndarray:
+    """Algorithm 1, steps 1 and 3: Softmax over the rows of Y of <X_r, Y_j> / sqrt(d); X [rows, d], Y [cols, d]."""
+    X, Y = _f32(X), _f32(Y)
+    rows, d = X.shape
+    cols = Y.shape[0]
+    assert Y.shape[1] == d
+    out = np.empty((rows, cols), dtype=np.float64)
+    f = lib().aifo_bea_attention_weights
+    f.restype = C.c_int
+    _check(f(_p(X, C.c_float), C.c_int(rows), _p(Y, C.c_float), C.c_int(cols), C.c_int(d), _p(out, C.c_double)))
+    return out
+
+
+def bea_weighted_sum(w_hat, V) -> np.ndarray:
+    """Algorithm 1, step 4: v^ = w^ V; w^ [b, n], V [n, d']."""
+    w_hat = np.ascontiguousarray(w_hat, dtype=np.float64)
+    V = _f32(V)
+    b, n = w_hat.shape
+    assert V.shape[0] == n
+    out = np.empty((b, V.shape[1]), dtype=np.float64)
+    f = lib().aifo_bea_weighted_sum
+    f.restype = None
+    f(_p(w_hat, C.c_double), C.c_int(b), C.c_int(n), _p(V, C.c_float), C.c_int(V.shape[1]), _p(out, C.c_double))
+    return out
 
 
 def topk(z, k: int):

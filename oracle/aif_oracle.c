@@ -42,7 +42,10 @@
 #include <string.h>
 
 enum { AIFO_OK = 0, AIFO_EINVAL = 1, AIFO_ESHAPE = 2, AIFO_ENOMEM = 3, AIFO_ERANGE = 5 };
-enum { AIFO_CROSS_NONE = 0, AIFO_CROSS_HADAMARD = 1, AIFO_CROSS_SEGDOT = 2 };
+enum { AIFO_CROSS_NONE = 0, AIFO_CROSS_HADAMARD = 1, AIFO_CROSS_SEGDOT = 2, AIFO_CROSS_BEA = 3 };
+
+/* aif_bea_oracle.c: step 4 of Algorithm 1 */
+void aifo_bea_weighted_sum(const double *w_hat, int b, int n, const float *V, int d_out, double *v_hat);
 
 /* Step 1 (Sec. 3.2): e_i = T[id_i, :].  An id outside the table is an error. */
 int aifo_gather(const float *table, int64_t n_items, int d_item,
@@ -105,13 +108,18 @@ int aifo_cross_width(int mode, int d_item, int n_cross, int d_c)
 {
     if (mode == AIFO_CROSS_HADAMARD) return d_item;
     if (mode == AIFO_CROSS_SEGDOT) return (d_c > 0 && d_item % d_c == 0) ? n_cross * (d_item / d_c) : -1;
+    if (mode == AIFO_CROSS_BEA) return (n_cross > 0 && n_cross <= d_item && d_c > 0) ? d_c : -1;
     return 0;
 }
 
 /* Step 4 (Sec. 3.3, real-time generation from the cached user component):
  *   HADAMARD: c_m = u_m * e_m          (user operand [d_item])
  *   SEGDOT:   c[j*S + s] = <Vc_j, e[s*d_c : (s+1)*d_c]>,  S = d_item / d_c,
- *             Vc is [n_cross, d_c]. */
+ *             Vc is [n_cross, d_c].
+ *   BEA:      (Sec. 4.1, Algorithm 1, step 4) the item row ends with the
+ *             candidate's n = n_cross bridge weights w^ (the nearline pipeline
+ *             stores them with the item vector); the user operand is V
+ *             [n, d_c]; c = w^ V, width d_c. */
 int aifo_cross(int mode, const float *uc, int n_cross, int d_c,
                const double *e, int d_item, double *c)
 {
@@ -130,6 +138,11 @@ int aifo_cross(int mode, const float *uc, int n_cross, int d_c,
                     acc += (double)uc[(size_t)j * d_c + m] * e[s * d_c + m];
                 c[j * S + s] = acc;
             }
+        return AIFO_OK;
+    }
+    if (mode == AIFO_CROSS_BEA) {
+        if (n_cross <= 0 || n_cross > d_item || d_c <= 0) return AIFO_ESHAPE;
+        aifo_bea_weighted_sum(e + (d_item - n_cross), 1, n_cross, uc, d_c, c);
         return AIFO_OK;
     }
     return AIFO_EINVAL;

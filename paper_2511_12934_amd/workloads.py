@@ -17,7 +17,7 @@ from typing import Dict, List, Optional, Tuple
 
 import numpy as np
 
-CROSS_NONE, CROSS_HADAMARD, CROSS_SEGDOT = 0, 1, 2
+CROSS_NONE, CROSS_HADAMARD, CROSS_SEGDOT, CROSS_BEA = 0, 1, 2, 3
 SEED_BASE = 0xA1F0000
 
 
@@ -49,6 +49,8 @@ class Config:
             return self.d_item
         if self.cross_mode == CROSS_SEGDOT:
             return self.n_cross * (self.d_item // self.d_cross_vec)
+        if self.cross_mode == CROSS_BEA:
+            return self.d_cross_vec
         return 0
 
     @property
@@ -141,7 +143,7 @@ class User:
     user_vec: np.ndarray                # [d_user]
     seq_keys: np.ndarray                # [L, d_attn]
     seq_vals: np.ndarray                # [L, d_attn]
-    cross_vecs: Optional[np.ndarray]    # SEGDOT: [n_cross, d_cross_vec]; HADAMARD: None (= user_vec)
+    cross_vecs: Optional[np.ndarray]    # SEGDOT, BEA: [n_cross, d_cross_vec]; HADAMARD: None (= user_vec)
 
 
 def make_user(cfg: Config, rng: np.random.Generator, sigma: float = 0.1,
@@ -151,7 +153,7 @@ def make_user(cfg: Config, rng: np.random.Generator, sigma: float = 0.1,
     u = g(cfg.d_user)
     k = g(L, cfg.d_attn)
     v = g(L, cfg.d_attn)
-    cv = g(cfg.n_cross, cfg.d_cross_vec) if cfg.cross_mode == CROSS_SEGDOT else None
+    cv = g(cfg.n_cross, cfg.d_cross_vec) if cfg.cross_mode in (CROSS_SEGDOT, CROSS_BEA) else None
     return User(u, k, v, cv)
 
 
@@ -160,9 +162,14 @@ def make_user(cfg: Config, rng: np.random.Generator, sigma: float = 0.1,
 # ----------------------------------------------------------------------------
 def make_table_host(cfg: Config, rng: np.random.Generator, n_items: Optional[int] = None,
                     sigma: float = 0.1) -> np.ndarray:
-    """Whole table on the host (small configurations only)."""
+    """Whole table on the host (small configurations only).  With the BEA cross block (Sec. 4.1) the
+    last n_cross entries of a row are the item's bridge weights as the nearline pipeline would have
+    left them: non-negative, summing to one (normalised exponentials, i.e. uniform on the simplex)."""
     n = cfg.n_items if n_items is None else n_items
     t = rng.standard_normal((n, cfg.d_item), dtype=np.float32) * np.float32(sigma)
+    if cfg.cross_mode == CROSS_BEA:
+        w = rng.exponential(size=(n, cfg.n_cross))
+        t[:, cfg.d_item - cfg.n_cross:] = (w / w.sum(axis=1, keepdims=True)).astype(np.float32)
     return round_storage(t, cfg.dtype)
 
 
@@ -178,8 +185,12 @@ def make_table_device(cfg: Config, device, n_items: Optional[int] = None, sigma:
     out = torch.empty((n, cfg.d_item), dtype=tdt, device=device)
     for lo in range(0, n, chunk_rows):
         hi = min(n, lo + chunk_rows)
-        blk = torch.randn((hi - lo, cfg.d_item), dtype=torch.float32, device=device, generator=gen)
-        out[lo:hi] = (blk * sigma).to(tdt)
+        blk = torch.randn((hi - lo, cfg.d_item), dtype=torch.float32, device=device, generator=gen) * sigma
+        if cfg.cross_mode == CROSS_BEA:         # bridge weights in the row's tail, as in make_table_host
+            w = torch.empty((hi - lo, cfg.n_cross), dtype=torch.float32, device=device).exponential_(generator=gen)
+            blk[:, cfg.d_item - cfg.n_cross:] = w / w.sum(dim=1, keepdim=True)
+            del w
+        out[lo:hi] = blk.to(tdt)
         del blk
     return out
 

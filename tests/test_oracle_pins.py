@@ -44,6 +44,9 @@ def numpy_path(table, ids, u, K, V, dims, Ws, bs, w_q=None, H=1, cross_mode=1, c
         S_ = E.shape[1] // cv64.shape[1]
         Eseg = E.reshape(n, S_, cv64.shape[1])
         Cx = np.einsum("jm,nsm->njs", cv64, Eseg).reshape(n, -1)
+    elif cross_mode == wl.CROSS_BEA:
+        cv64 = np.asarray(cv, np.float64)                             # V [n_bridges, d']
+        Cx = E[:, E.shape[1] - cv64.shape[0]:] @ cv64
     else:
         Cx = np.zeros((n, 0))
     X = np.concatenate([np.broadcast_to(u64, (n, u64.size)), E, A, Cx], axis=1)
@@ -343,13 +346,16 @@ def _score(cfg, model, table, user, ids, **kw):
                         cross_mode=cfg.cross_mode, cross_vecs=user.cross_vecs, **kw)
 
 
-@pytest.mark.parametrize("variant", ["hadamard", "wq_heads", "segdot"])
+@pytest.mark.parametrize("variant", ["hadamard", "wq_heads", "segdot", "bea"])
 def test_whole_path_brute_force_against_numpy_reference(variant):
     if variant == "hadamard":
         cfg = tiny_cfg()
     elif variant == "wq_heads":
         cfg = tiny_cfg(d_item=6, d_user=6, d_attn=4, n_heads=2, use_wq=True, seq_len=4,
                        mlp_dims=(22, 7, 3, 1))
+    elif variant == "bea":
+        cfg = tiny_cfg(d_item=8, d_user=5, d_attn=4, n_heads=2, seq_len=4,
+                       cross_mode=wl.CROSS_BEA, n_cross=3, d_cross_vec=5, mlp_dims=(22, 6, 1))
     else:
         cfg = tiny_cfg(d_item=8, d_user=5, d_attn=4, n_heads=2, use_wq=True, seq_len=4,
                        cross_mode=wl.CROSS_SEGDOT, n_cross=3, d_cross_vec=4, mlp_dims=(23, 6, 1))
