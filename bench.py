@@ -234,7 +234,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5", "L1", "L2", "L3"])
+    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5", "B3", "L1", "L2", "L3"])
     ap.add_argument("--id-sets", type=int, default=4,
                     help="distinct candidate lists per user, taken in turn by consecutive steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -61,8 +61,15 @@ typedef enum { AIF_F32 = 0, AIF_BF16 = 1 } aif_dtype;
 typedef enum {
     AIF_CROSS_NONE = 0,
     AIF_CROSS_HADAMARD = 1, /* c = u (.) e, width d_item (Sec. 3.3)                        */
-    AIF_CROSS_SEGDOT = 2    /* c[j*S+s] = <Vc_j, e[s*d_c:(s+1)*d_c]>, S = d_item/d_c,
+    AIF_CROSS_SEGDOT = 2,   /* c[j*S+s] = <Vc_j, e[s*d_c:(s+1)*d_c]>, S = d_item/d_c,
                                the "n user-side vectors x item" shape of Sec. 4.1       */
+    AIF_CROSS_BEA = 3       /* Bridge Embedding Approximation, Sec. 4.1, Algorithm 1 step 4
+                               (the online weighted sum): the item row ENDS with the
+                               candidate's n_cross bridge weights w^ (the nearline pipeline
+                               stores them with the item vector), the request brings the n_cross
+                               asynchronously inferred user-side vectors V [n_cross, d_cross_vec];
+                               c = w^ V, width d_cross_vec.  The whole row, weights included,
+                               is still the "item" block of the MLP input.                  */
 } aif_cross;
 
 /* Model and sizing.  Width rules: d_item, d_attn and the cross width must each
@@ -78,8 +85,8 @@ typedef struct {
     int32_t n_heads;
     int32_t max_seq_len;      /* largest behaviour-sequence length of any request         */
     aif_cross cross_mode;
-    int32_t n_cross;          /* SEGDOT: number of user-side cross vectors, else 0        */
-    int32_t d_cross_vec;      /* SEGDOT: their width (divides d_item), else 0             */
+    int32_t n_cross;          /* SEGDOT: number of user-side cross vectors; BEA: number of bridges (<= d_item); else 0 */
+    int32_t d_cross_vec;      /* SEGDOT: their width (divides d_item); BEA: width d' of the user-side vectors; else 0 */
     int32_t n_layers;         /* MLP layers, >= 1                                         */
     const int32_t *layer_dims;/* HOST, n_layers + 1 entries [D_in, ..., 1]                */
     int32_t max_candidates;   /* largest n_cand of one request                            */
@@ -102,7 +109,7 @@ typedef struct {
  * cross_vecs, seq_keys and seq_vals must be 16-byte aligned. */
 typedef struct {
     const void *user_vec;     /* [d_user]                                                 */
-    const void *cross_vecs;   /* SEGDOT: [n_cross, d_cross_vec]; HADAMARD: [d_item] or NULL = user_vec (needs d_user = d_item) */
+    const void *cross_vecs;   /* SEGDOT, BEA: [n_cross, d_cross_vec] row-major; HADAMARD: [d_item] or NULL = user_vec (needs d_user = d_item) */
     const void *seq_keys;     /* [seq_len, d_attn] row-major; heads are contiguous slices  */
     const void *seq_vals;     /* [seq_len, d_attn]; may alias seq_keys                    */
     int32_t seq_len;          /* 0 .. max_seq_len; 0 gives a zero attention block         */

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libaif.so")
 
 AIF_OK, AIF_EINVAL, AIF_ESHAPE, AIF_ENOMEM, AIF_EDEVICE, AIF_ERANGE = range(6)
 AIF_F32, AIF_BF16 = 0, 1
-AIF_CROSS_NONE, AIF_CROSS_HADAMARD, AIF_CROSS_SEGDOT = 0, 1, 2
+AIF_CROSS_NONE, AIF_CROSS_HADAMARD, AIF_CROSS_SEGDOT, AIF_CROSS_BEA = 0, 1, 2, 3
 
 EXPORTS = ("aif_score_init", "aif_score_request", "aif_score_batch", "aif_topk", "aif_score_destroy",
            "aif_last_error", "aif_poll_device_errors", "aif_peek_features", "aif_profile_begin",

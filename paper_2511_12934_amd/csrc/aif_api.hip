@@ -172,6 +172,11 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
             return fail(nullptr, AIF_ESHAPE, "SEGDOT needs n_cross > 0 and d_cross_vec dividing d_item");
         m.d_cross = cfg->n_cross * (cfg->d_item / cfg->d_cross_vec);
         break;
+    case AIF_CROSS_BEA:
+        if (cfg->n_cross <= 0 || cfg->n_cross > cfg->d_item || cfg->d_cross_vec <= 0)
+            return fail(nullptr, AIF_ESHAPE, "BEA needs 0 < n_cross <= d_item and d_cross_vec > 0");
+        m.d_cross = cfg->d_cross_vec;
+        break;
     default: return fail(nullptr, AIF_EINVAL, "unknown cross_mode %d", (int)cfg->cross_mode);
     }
     const int esz = m.dtype == 0 ? 4 : 2, vec = 16 / esz;
@@ -296,7 +301,8 @@ aif_status aif_score_batch(aif_ctx *c, const aif_request *reqs, int32_t n_req, v
             return fail(c, AIF_EINVAL, "request %d: NULL tensor pointer", r);
         if (((uintptr_t)q.user_vec | (uintptr_t)q.cross_vecs | (uintptr_t)q.seq_keys | (uintptr_t)q.seq_vals) % 16)
             return fail(c, AIF_EINVAL, "request %d: user tensors must be 16-byte aligned", r);
-        if (m.cross_mode == AIF_CROSS_SEGDOT && !q.cross_vecs) return fail(c, AIF_EINVAL, "request %d: SEGDOT needs cross_vecs", r);
+        if ((m.cross_mode == AIF_CROSS_SEGDOT || m.cross_mode == AIF_CROSS_BEA) && !q.cross_vecs)
+            return fail(c, AIF_EINVAL, "request %d: SEGDOT and BEA need cross_vecs", r);
         if (m.cross_mode == AIF_CROSS_HADAMARD && !q.cross_vecs && m.d_user != m.d_item)
             return fail(c, AIF_ESHAPE, "request %d: HADAMARD without cross_vecs needs d_user == d_item", r);
     }

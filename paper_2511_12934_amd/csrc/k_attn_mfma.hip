@@ -42,6 +42,27 @@ __device__ __forceinline__ void store_stream(bf16x8 *p, bf16x8 v) { __builtin_no
 __device__ __forceinline__ void store_stream(bf16x4 *p, bf16x4 v) { __builtin_nontemporal_store(__builtin_bit_cast(u32x2, v), (u32x2 *)p); }
 
 constexpr float LOG2E = 1.4426950408889634f;
+
+// BEA cross block (Sec. 4.1, Algorithm 1 step 4) on the matrix cores: C^T = V^T w^T with the
+// candidates as columns.  The contraction runs over the row's last 16 * ksb entries (the "window",
+// ksb = ceil(n_cross / 16) k-steps); window entries in front of the n_cross bridge weights meet
+// zero rows of V.  The A operand of k-step ks and feature tile ft is the fragment
+//   [lane][s] = Vpad[16 ks + 8 (lane / 32) + s][32 ft + lane % 32],  Vpad[w] = V[w - pad] or 0, pad = 16 ksb - n_cross
+// and the B operand of a lane (candidate c, half h) is piece d_item / 8 - 2 ksb + 2 ks + h of its row.
+struct BeaGeom {
+    int ksb, ftc, pad, piece0;
+};
+__host__ __device__ inline BeaGeom bea_geom(const Model &m)
+{
+    const int ksb = (m.n_cross + 15) / 16;
+    return BeaGeom{ksb, m.d_cv / 32, 16 * ksb - m.n_cross, m.d_item / 8 - 2 * ksb};
+}
+constexpr int BEA_MAX_FRAGS = 4;             // ksb * ftc fragments of 1 KB the kernels keep
+__device__ __forceinline__ uint16_t bea_a_element(const uint16_t *V, const Model &m, const BeaGeom &g, int ks, int ft, int lane, int s)
+{
+    const int w = 16 * ks + 8 * (lane >> 5) + s - g.pad;
+    return w >= 0 ? V[(size_t)w * m.d_cv + 32 * ft + (lane & 31)] : (uint16_t)0;
+}
 constexpr float BOUND_LIMIT = 40.f;      // exponents stay within [-80, 0]
 
 // Copy NFRAG fragments of 1 KB global -> LDS; every wave moves NFRAG / WAVES of them.
@@ -254,6 +275,33 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
             store_stream(piece(pc0 + pc), o8);
         }
     }
+    if (m.cross_mode == 3) {
+        const BeaGeom g = bea_geom(m);
+        const uint16_t *Vu = (const uint16_t *)rd.cross_vecs;
+        const int pc0 = (m.d_item + m.d_attn) / 8;
+        for (int ft = 0; ft < g.ftc; ++ft) {
+            f32x16 Cc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) Cc[i] = 0.f;
+            for (int ks = 0; ks < g.ksb; ++ks) {
+                uint16_t a8[8];
+#pragma unroll
+                for (int sl = 0; sl < 8; ++sl) a8[sl] = bea_a_element(Vu, m, g, ks, ft, lane, sl);
+                bf16x8 A;
+                __builtin_memcpy(&A, a8, 16);
+                Cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, *piece(g.piece0 + 2 * ks + h), Cc, 0, 0, 0);
+            }
+            if (live) {
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o4[i] = (__bf16)Cc[4 * qd + i];
+                    store_stream((bf16x4 *)piece(pc0 + 4 * ft + qd) + h, o4);
+                }
+            }
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -310,6 +358,17 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     }
     if (m.cross_mode == 1)
         for (int i = threadIdx.x; i < m.d_item / 8; i += RES_WAVES * 64) su[i] = ((const bf16x8 *)rd.cross_vecs)[i];
+    const bool bea = m.cross_mode == 3;
+    const BeaGeom bg = bea_geom(m);
+    if (bea) {
+        // the request's user-side vectors as A fragments (k-step major), in the LDS the Hadamard operand would take
+        uint16_t *sa = (uint16_t *)su;
+        const uint16_t *Vu = (const uint16_t *)rd.cross_vecs;
+        for (int i = threadIdx.x; i < bg.ksb * bg.ftc * 512; i += RES_WAVES * 64) {
+            const int sl = i & 7, ln = (i >> 3) & 63, f = i >> 9;
+            sa[i] = bea_a_element(Vu, m, bg, f / bg.ftc, f % bg.ftc, ln, sl);
+        }
+    }
     if (threadIdx.x == 0) *s_next = RES_WAVES;
     wait_vmcnt<0>();
     __syncthreads();
@@ -372,6 +431,26 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                     for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)e[s] * (float)u[s]);
                     store_stream(piece(pc_cross + pc), o8);
                 }
+        }
+
+        // Algorithm 1 step 4, once per tile: the row's bridge weights against the user-side vectors
+        if (bea && hd == 0) {
+            for (int ft = 0; ft < bg.ftc; ++ft) {
+                f32x16 Cc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) Cc[i] = 0.f;
+                for (int ks = 0; ks < bg.ksb; ++ks)
+                    Cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(su[(ks * bg.ftc + ft) * 64 + lane], *piece(bg.piece0 + 2 * ks + h), Cc, 0, 0, 0);
+                if (live) {
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd) {
+                        bf16x4 o4;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) o4[i] = (__bf16)Cc[4 * qd + i];
+                        store_stream((bf16x4 *)piece(pc_cross + 4 * ft + qd) + h, o4);
+                    }
+                }
+            }
         }
 
         float ss = 0.f;
@@ -522,7 +601,12 @@ int attn_plan_groups(const Model &m, const ReqDesc *reqs, int n_req, int n_cu, A
 int attn_mfma_variant(const Model &m, bool has_wq)
 {
     if (m.dtype != 1 || has_wq) return -1;
-    if (m.cross_mode != 0 && m.cross_mode != 1) return -1;
+    if (m.cross_mode == 3) {
+        // BEA on the matrix cores: whole 32-feature tiles, the window inside the row, fragments within budget
+        const BeaGeom g = bea_geom(m);
+        if (m.d_cv % 32 || g.piece0 < 0 || g.ksb * g.ftc > BEA_MAX_FRAGS) return -1;
+    } else if (m.cross_mode != 0 && m.cross_mode != 1)
+        return -1;
     if (m.d_head == 64) return 0;
     if (m.d_head == 32) return 1;
     return -1;

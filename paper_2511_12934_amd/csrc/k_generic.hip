@@ -138,6 +138,14 @@ __global__ __launch_bounds__(256) void k_attn_generic(Model m, Batch b, T *__res
                     for (int k = 0; k < m.d_cv; ++k) acc += ld_f<T>(uc + (size_t)j * m.d_cv + k) * sh_e[sg * m.d_cv + k];
                     st_f<T>(xc + idx, acc);
                 }
+            } else if (m.cross_mode == 3) {
+                // Algorithm 1 step 4: the row's trailing n_cross entries weigh the user-side vectors
+                const int w0 = m.d_item - m.n_cross;
+                for (int idx = lane; idx < m.d_cv; idx += 64) {
+                    float acc = 0.f;
+                    for (int j = 0; j < m.n_cross; ++j) acc += sh_e[w0 + j] * ld_f<T>(uc + (size_t)j * m.d_cv + idx);
+                    st_f<T>(xc + idx, acc);
+                }
             }
         }
         __syncthreads();

@@ -76,6 +76,11 @@ CONFIGS: Dict[str, Config] = {
                  CROSS_HADAMARD, 0, 0, 128, (512, 256, 1), 100),
     "C5": Config("C5", 5, "bf16", 32, 10_000, 10_000_000, 256, "zipf", 2_000, 128, 8, True,
                  CROSS_SEGDOT, 16, 64, 576, (1024, 1024, 512, 256, 1), 150),
+    # C3 with its cross block formed by the Bridge Embedding Approximation (Sec. 4.1): 16 bridges (the
+    # paper's quality plateau is at about 10), the item row = 48-wide vector + 16 bridge weights, the user
+    # side brings 16 vectors of width 64.
+    "B3": Config("B3", 6, "bf16", 64, 10_000, 10_000_000, 64, "zipf", 500, 64, 1, False,
+                 CROSS_BEA, 16, 64, 64, (256, 512, 256, 1), 100),
 }
 for _c in CONFIGS.values():
     assert _c.d_in == _c.mlp_dims[0], (_c.name, _c.d_in)

@@ -1,4 +1,4 @@
-"""Configurations 3-5 at full size, in the launch configuration the benchmark
+"""Configurations 3-5 (and C3 with the BEA cross block) at full size, in the launch configuration the benchmark
 times (one aif_score_batch over all users + one aif_topk): sampled candidates
 against the oracle one by one, top-k of every user against the oracle's full
 stable sort of the GPU's logits, and the properties that hold at any size."""
@@ -13,7 +13,7 @@ from helpers import assert_features_close, assert_logits_close, oracle_scores_ro
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
+@pytest.mark.parametrize("name", ["C3", "C4", "C5", "B3"])
 def test_full_size_batched_config(name):
     import torch
     from paper_2511_12934_amd import runner as R

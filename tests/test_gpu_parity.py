@@ -356,6 +356,70 @@ def test_stale_workspace_rows_do_not_change_a_candidates_bits(R, torch):
     assert_logits_close("bf16", z1, oracle_scores(cfg, model, table, u, ids).logits)
 
 
+# ---------------------------------------------------------------------------
+# Bridge Embedding Approximation as the cross block (Sec. 4.1, Algorithm 1 step 4)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,n_bridges,d_out", [("f32", 5, 12), ("f32", 16, 4), ("bf16", 10, 40), ("bf16", 3, 8)])
+def test_bea_cross_on_the_shape_agnostic_kernels(R, torch, dtype, n_bridges, d_out):
+    d_item = 24
+    cfg = small_cfg(dtype, d_item=d_item, d_user=8, d_attn=8, seq_len=7, cross_mode=wl.CROSS_BEA, n_cross=n_bridges,
+                    d_cross_vec=d_out, mlp_dims=(8 + d_item + 8 + d_out, 16, 1), n_cand=75)
+    _say(f"BEA generic {dtype} n={n_bridges} d'={d_out}")
+    rng = np.random.default_rng(31)
+    model = wl.make_model(cfg, seed=4, bias_scale=0.3)
+    table = wl.make_table_host(cfg, rng)
+    u = wl.make_user(cfg, rng, sigma=1.0)
+    ids = wl.IdSampler(cfg).sample(rng, cfg.n_cand)
+    (z,), _, _, ctx = run_batch(R, torch, cfg, model, R.to_device(table, dtype), [(u, ids)])
+    assert ctx.aif_stage_kind("attention") == 0
+    ref = oracle_scores(cfg, model, table, u, ids)
+    X = R.peek_features(ctx, cfg, 0, ids.size)
+    assert np.array_equal(X[:, :d_item], table[ids])
+    assert_features_close(dtype, X[:, d_item + cfg.d_attn:], ref.cross, "BEA cross")
+    assert_logits_close(dtype, z, ref.logits, "BEA generic")
+
+
+@pytest.mark.parametrize("shape", ["resident_16", "resident_pad_10", "resident_two_ksteps_20", "streaming_16",
+                                   "heads32_wide_item"])
+def test_bea_cross_on_the_mfma_kernels(R, torch, shape):
+    """The weighted sum as an MFMA inside both attention kernels: 16 bridges (one k-step), 10 (window entries in
+    front of the weights meet zero rows), 20 (two k-steps), the streaming kernel (L = 1000), and 4 heads of 32 with
+    a 128-wide row and a 32-wide output."""
+    base = wl.CONFIGS["B3"]
+    if shape == "resident_16":
+        cfg = base.scaled(n_items=3000)
+    elif shape == "resident_pad_10":
+        cfg = base.scaled(n_items=3000, n_cross=10)
+    elif shape == "resident_two_ksteps_20":
+        cfg = base.scaled(n_items=3000, n_cross=20)
+    elif shape == "streaming_16":
+        cfg = base.scaled(n_items=3000, seq_len=1000, mlp_dims=(256, 256, 128, 1))
+    else:
+        cfg = wl.CONFIGS["C4"].scaled(n_items=3000, cross_mode=wl.CROSS_BEA, n_cross=16, d_cross_vec=32, d_user=96,
+                                      mlp_dims=(384, 64, 1))
+    assert cfg.d_in == cfg.mlp_dims[0]
+    _say(f"BEA MFMA {shape}")
+    rng = np.random.default_rng(37)
+    model = wl.make_model(cfg, bias_scale=0.05)
+    table = wl.make_table_host(cfg, rng, n_items=3000)
+    users = [wl.make_user(cfg, rng, sigma=s) for s in (0.1, 1.0)]
+    sampler = wl.IdSampler(cfg, 3000)
+    reqs = [(users[0], sampler.sample(rng, 333)), (users[1], sampler.sample(rng, 600))]
+    zs, _, _, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), reqs)
+    assert ctx.aif_stage_kind("attention") == 1
+    for i, (u, ids) in enumerate(reqs):
+        ref = oracle_scores(cfg, model, table, u, ids)
+        X = R.peek_features(ctx, cfg, i, ids.size)
+        assert np.array_equal(X[:, :cfg.d_item], table[ids])
+        assert_features_close("bf16", X[:, cfg.d_item:cfg.d_item + cfg.d_attn], ref.attn, "attention")
+        # fp32 accumulation of at most 32 products of bf16 values, one rounding to bf16 on the way out
+        c = X[:, cfg.d_item + cfg.d_attn:]
+        tol = 2.0 ** -8 * np.abs(ref.cross) + 2.0 ** -16 * np.abs(ref.cross).max() + 1e-30
+        assert np.all(np.abs(c - ref.cross) <= tol), f"BEA cross, request {i}"
+        if i == 0:
+            assert_logits_close("bf16", zs[i], ref.logits, f"BEA {shape}")
+
+
 def test_large_scores_do_not_overflow(R, torch):
     """|score| far beyond the fp32 exp range: softmax must subtract its maximum."""
     cfg = small_cfg("f32", d_item=32, d_user=32, d_attn=32, seq_len=33, mlp_dims=(128, 16, 1))
