@@ -7,7 +7,9 @@ synthetic requests already resident in HBM.  Default workload: configuration
 C3 (64 concurrent users x 10^4 candidates, bf16), the batched 10^4-candidate
 request shape the metric is quoted on.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1..C5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1..C5 | B3]
+
+``--workload B3`` is C3 with the cross block formed by the Bridge Embedding Approximation (Sec. 4.1).
 
 ``--workload L1..L3`` times the LSH behaviour-modelling path instead (aif_lsh_batch: user-side bit
 tables -> LSH-DIN -> SimTier over every candidate x history pair); same JSON contract, its own metric.
@@ -44,6 +46,8 @@ def algorithmic_work(cfg):
         attn += 2 * cfg.d_cross * cfg.d_cross_vec
     elif cfg.cross_mode == 1:
         attn += cfg.d_item
+    elif cfg.cross_mode == 3:
+        attn += 2 * cfg.n_cross * cfg.d_cross_vec
     return {
         "gather": {"bytes": 4 + 2 * cfg.d_item * B},
         "attention": {"flops": attn, "bytes": cfg.d_item * B + (cfg.d_attn + cfg.d_cross) * B},
