@@ -19,7 +19,8 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "aif_oracle.c")
-_SRCS = [_SRC, os.path.join(_HERE, "aif_lsh_oracle.c"), os.path.join(_HERE, "aif_bea_oracle.c")]
+_SRCS = [_SRC, os.path.join(_HERE, "aif_lsh_oracle.c"), os.path.join(_HERE, "aif_bea_oracle.c"),
+         os.path.join(_HERE, "aif_user_oracle.c")]
 _LIB = os.path.join(_HERE, "libaif_oracle.so")
 
 OK, EINVAL, ESHAPE, ENOMEM, ERANGE = 0, 1, 2, 3, 5
@@ -212,6 +213,75 @@ def bea_weighted_sum(w_hat, V) -> np.ndarray:
     f.restype = None
     f(_p(w_hat, C.c_double), C.c_int(b), C.c_int(n), _p(V, C.c_float), C.c_int(V.shape[1]), _p(out, C.c_double))
     return out
+
+
+# ---------------------------------------------------------------------------
+# user-side asynchronous network (aif_user_oracle.c; Sec. 3.1, Eq. 1-3)
+# ---------------------------------------------------------------------------
+def user_project(x, W) -> np.ndarray:
+    """Eq. 1: rows of x [rows, d_raw] times W^T, W [d, d_raw]."""
+    x, W = _f32(x), _f32(W)
+    rows, d_raw = x.shape
+    d = W.shape[0]
+    assert W.shape[1] == d_raw
+    out = np.empty((rows, d), dtype=np.float64)
+    f = lib().aifo_user_project
+    f.restype = None
+    f(_p(x, C.c_float), C.c_int(rows), C.c_int(d_raw), _p(W, C.c_float), C.c_int(d), _p(out, C.c_double))
+    return out
+
+
+def user_attend(Q, S) -> np.ndarray:
+    """Attention core of Eq. 2 / Eq. 3: Softmax(Q S^T / sqrt(d)) S; Q [rows, d], S [l, d] (float64)."""
+    Q = np.ascontiguousarray(Q, dtype=np.float64)
+    S = np.ascontiguousarray(S, dtype=np.float64)
+    rows, d = Q.shape
+    l = S.shape[0]
+    out = np.empty((rows, d), dtype=np.float64)
+    f = lib().aifo_user_attend
+    f.restype = C.c_int
+    _check(f(_p(Q, C.c_double), C.c_int(rows), _p(S, C.c_double), C.c_int(l), C.c_int(d), _p(out, C.c_double)))
+    return out
+
+
+def user_ffn(x, W, b=None) -> np.ndarray:
+    """FFN of Eq. 2 (one layer, ReLU): max(0, W x + b) per row; x [rows, d] float64."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    W, b = _f32(W), _f32(b)
+    rows, d = x.shape
+    y = np.empty((rows, d), dtype=np.float64)
+    f = lib().aifo_user_ffn
+    f.restype = None
+    f(_p(x, C.c_double), C.c_int(rows), C.c_int(d), _p(W, C.c_float), _p(b, C.c_float), _p(y, C.c_double))
+    return y
+
+
+def user_pool(y) -> np.ndarray:
+    """Pooling of Eq. 2 (mean over positions)."""
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    rows, d = y.shape
+    out = np.empty(d, dtype=np.float64)
+    f = lib().aifo_user_pool
+    f.restype = None
+    f(_p(y, C.c_double), C.c_int(rows), C.c_int(d), _p(out, C.c_double))
+    return out
+
+
+def user_network(*, profile, seq, w_profile, w_seq, w_ffn, b_ffn=None):
+    """Eq. 1-3 for one user: (user_vec [2 d] = [self-attention | profile-attention], seq_hat [l, d])."""
+    profile, seq = _f32(profile).reshape(-1), _f32(seq)
+    w_profile, w_seq, w_ffn, b_ffn = _f32(w_profile), _f32(w_seq), _f32(w_ffn), _f32(b_ffn)
+    l, d_raw = seq.shape
+    d = w_seq.shape[0]
+    assert profile.size == d_raw and w_profile.shape == (d, d_raw) and w_seq.shape == (d, d_raw) and w_ffn.shape == (d, d)
+    uv = np.empty(2 * d, dtype=np.float64)
+    sh = np.empty((l, d), dtype=np.float64)
+    f = lib().aifo_user_network
+    f.restype = C.c_int
+    _check(f(_p(profile, C.c_float), _p(seq, C.c_float), C.c_int(l), C.c_int(d_raw), C.c_int(d),
+             _p(w_profile, C.c_float), _p(w_seq, C.c_float), _p(w_ffn, C.c_float), _p(b_ffn, C.c_float),
+             _p(uv, C.c_double), _p(sh, C.c_double)))
+    return uv, sh
 
 
 def topk(z, k: int):
