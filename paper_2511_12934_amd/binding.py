@@ -25,6 +25,9 @@ STAGES = ("gather", "user_fold", "attention", "mlp", "topk")
 LSH_EXPORTS = ("aif_lsh_init", "aif_lsh_batch", "aif_lsh_destroy", "aif_lsh_last_error",
                "aif_lsh_poll_device_errors", "aif_lsh_profile_begin", "aif_lsh_profile_end")
 LSH_STAGES = ("user", "din", "simtier")
+USER_EXPORTS = ("aif_user_init", "aif_user_precompute", "aif_user_destroy", "aif_user_last_error",
+                "aif_user_attention_kind", "aif_user_profile_begin", "aif_user_profile_end")
+USER_STAGES = ("project", "attention", "ffn_pool")
 
 
 class aif_config(C.Structure):
@@ -56,6 +59,20 @@ class aif_lsh_request(C.Structure):
     _fields_ = [("seq_sigs", C.c_void_p), ("seq_emb", C.c_void_p), ("seq_len", C.c_int32),
                 ("cand_ids", C.c_void_p), ("n_cand", C.c_int32), ("din_out", C.c_void_p),
                 ("tier_out", C.c_void_p)]
+
+
+class aif_user_config(C.Structure):
+    _fields_ = [("dtype", C.c_int), ("d_raw", C.c_int32), ("d", C.c_int32), ("max_seq_len", C.c_int32),
+                ("max_users", C.c_int32)]
+
+
+class aif_user_weights(C.Structure):
+    _fields_ = [("w_profile", C.c_void_p), ("w_seq", C.c_void_p), ("w_ffn", C.c_void_p), ("b_ffn", C.c_void_p)]
+
+
+class aif_user_request(C.Structure):
+    _fields_ = [("profile", C.c_void_p), ("seq", C.c_void_p), ("seq_len", C.c_int32),
+                ("user_vec_out", C.c_void_p), ("seq_out", C.c_void_p)]
 
 
 _lib = None
@@ -107,6 +124,20 @@ def load():
     lib.aif_lsh_profile_begin.argtypes = [vp, C.c_int32]
     lib.aif_lsh_profile_end.restype = C.c_int
     lib.aif_lsh_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+    lib.aif_user_init.restype = C.c_int
+    lib.aif_user_init.argtypes = [C.POINTER(aif_user_config), C.POINTER(aif_user_weights), C.POINTER(vp)]
+    lib.aif_user_precompute.restype = C.c_int
+    lib.aif_user_precompute.argtypes = [vp, C.POINTER(aif_user_request), C.c_int32, vp]
+    lib.aif_user_destroy.restype = None
+    lib.aif_user_destroy.argtypes = [vp]
+    lib.aif_user_last_error.restype = C.c_char_p
+    lib.aif_user_last_error.argtypes = [vp]
+    lib.aif_user_attention_kind.restype = C.c_int32
+    lib.aif_user_attention_kind.argtypes = [vp]
+    lib.aif_user_profile_begin.restype = C.c_int
+    lib.aif_user_profile_begin.argtypes = [vp, C.c_int32]
+    lib.aif_user_profile_end.restype = C.c_int
+    lib.aif_user_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     _lib = lib
     return lib
 
@@ -298,6 +329,74 @@ class LshContext:
     def close(self):
         if self._h:
             self._lib.aif_lsh_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class UserRequest:
+    """Device tensors of one user of the user-side network (include/aif_user.h)."""
+
+    def __init__(self, profile, seq, user_vec_out, seq_out, seq_len: Optional[int] = None):
+        self.profile, self.seq, self.user_vec_out, self.seq_out = profile, seq, user_vec_out, seq_out
+        self.seq_len = int(seq.shape[0]) if seq_len is None else int(seq_len)
+
+    def fill(self, r: aif_user_request):
+        r.profile = _ptr(self.profile)
+        r.seq = _ptr(self.seq)
+        r.seq_len = self.seq_len
+        r.user_vec_out = _ptr(self.user_vec_out)
+        r.seq_out = _ptr(self.seq_out)
+
+
+def pack_user_requests(reqs: Sequence[UserRequest]):
+    arr = (aif_user_request * max(len(reqs), 1))()
+    for i, q in enumerate(reqs):
+        q.fill(arr[i])
+    return arr
+
+
+class UserContext:
+    """Owns one ``aif_user_ctx``.  Methods carry the names of the C entry points."""
+
+    def __init__(self, *, dtype: int, d_raw: int, d: int, w_profile, w_seq, w_ffn, b_ffn=None, max_seq_len: int,
+                 max_users: int = 1):
+        self._lib = load()
+        self._h = C.c_void_p()
+        cfg = aif_user_config(dtype, d_raw, d, max_seq_len, max_users)
+        wts = aif_user_weights(_ptr(w_profile), _ptr(w_seq), _ptr(w_ffn), _ptr(b_ffn))
+        st = self._lib.aif_user_init(C.byref(cfg), C.byref(wts), C.byref(self._h))
+        if st != AIF_OK:
+            self._h = C.c_void_p()
+            raise AifError(st, self._lib.aif_user_last_error(None).decode())
+
+    def _check(self, st: int):
+        if st != AIF_OK:
+            raise AifError(st, self._lib.aif_user_last_error(self._h).decode())
+
+    def aif_user_precompute(self, reqs: Sequence[UserRequest], packed=None, stream: Optional[int] = None):
+        arr = pack_user_requests(reqs) if packed is None else packed
+        self._check(self._lib.aif_user_precompute(self._h, arr, len(reqs), _stream() if stream is None else stream))
+
+    def aif_user_attention_kind(self) -> int:
+        return int(self._lib.aif_user_attention_kind(self._h))
+
+    def aif_user_profile_begin(self, max_calls: int):
+        self._check(self._lib.aif_user_profile_begin(self._h, max_calls))
+
+    def aif_user_profile_end(self):
+        ms = (C.c_double * len(USER_STAGES))()
+        n = (C.c_int32 * len(USER_STAGES))()
+        self._check(self._lib.aif_user_profile_end(self._h, ms, n))
+        return {s: (ms[i], n[i]) for i, s in enumerate(USER_STAGES)}
+
+    def close(self):
+        if self._h:
+            self._lib.aif_user_destroy(self._h)
             self._h = C.c_void_p()
 
     def __del__(self):

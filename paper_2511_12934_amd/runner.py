@@ -5,7 +5,7 @@ moves a synthetic workload into device memory and drives the C ABI through
 from __future__ import annotations
 
 from dataclasses import dataclass
-from typing import List, Optional, Sequence
+from typing import Tuple, List, Optional, Sequence
 
 import numpy as np
 
@@ -234,3 +234,49 @@ class LshWorkload:
 
     def step(self):
         self.ctx.aif_lsh_batch([d.req for d in self.dev], packed=self.packed)
+
+
+# ---------------------------------------------------------------------------
+# user-side asynchronous network (include/aif_user.h)
+# ---------------------------------------------------------------------------
+@dataclass
+class UserNetDevice:
+    req: B.UserRequest
+    user_vec: "object"       # torch [2 d]
+    seq_out: "object"        # torch [L, d]
+    keep: Tuple = ()
+
+
+def make_user_context(cfg: wl.UserNetConfig, model: wl.UserNetModel, *, max_users: Optional[int] = None,
+                      max_seq_len: Optional[int] = None, device="cuda:0") -> B.UserContext:
+    w = [to_device(a, cfg.dtype, device) for a in (model.w_profile, model.w_seq, model.w_ffn, model.b_ffn)]
+    return B.UserContext(dtype=B.AIF_F32 if cfg.dtype == "f32" else B.AIF_BF16, d_raw=cfg.d_raw, d=cfg.d,
+                         w_profile=w[0], w_seq=w[1], w_ffn=w[2], b_ffn=w[3],
+                         max_seq_len=cfg.seq_len if max_seq_len is None else max_seq_len,
+                         max_users=cfg.n_users if max_users is None else max_users)
+
+
+def upload_raw_user(cfg: wl.UserNetConfig, user: wl.RawUser, device="cuda:0") -> UserNetDevice:
+    import torch
+    p = to_device(user.profile, cfg.dtype, device)
+    sq = to_device(user.seq, cfg.dtype, device)
+    L = user.seq.shape[0]
+    uv = torch.zeros(2 * cfg.d, dtype=torch_dtype(cfg.dtype), device=device)
+    so = torch.zeros((max(L, 1), cfg.d), dtype=torch_dtype(cfg.dtype), device=device)
+    return UserNetDevice(B.UserRequest(p, sq, uv, so, L), uv, so, (p, sq))
+
+
+class UserNetWorkload:
+    """The user side of one configuration resident on the device: ``step()`` = aif_user_precompute over all users."""
+
+    def __init__(self, cfg: wl.UserNetConfig, device="cuda:0", n_users: Optional[int] = None):
+        self.cfg = cfg
+        self.n_users = cfg.n_users if n_users is None else n_users
+        self.model = wl.make_user_net_model(cfg)
+        self.users = wl.make_raw_users(cfg, self.n_users)
+        self.dev = [upload_raw_user(cfg, u, device) for u in self.users]
+        self.ctx = make_user_context(cfg, self.model, max_users=self.n_users, device=device)
+        self.packed = B.pack_user_requests([d.req for d in self.dev])
+
+    def step(self, stream: Optional[int] = None):
+        self.ctx.aif_user_precompute([d.req for d in self.dev], packed=self.packed, stream=stream)

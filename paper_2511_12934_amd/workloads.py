@@ -81,6 +81,11 @@ CONFIGS: Dict[str, Config] = {
     # side brings 16 vectors of width 64.
     "B3": Config("B3", 6, "bf16", 64, 10_000, 10_000_000, 64, "zipf", 500, 64, 1, False,
                  CROSS_BEA, 16, 64, 64, (256, 512, 256, 1), 100),
+    # C3 fed by the asynchronous user-side network (Sec. 3.1): the cached user vector is
+    # [U_self_attention | U_profile_attention] (2 x 64), keys = values = the projected sequence, the Hadamard
+    # operand is U_profile_attention.  See USER_CONFIGS["U3"] for the network that produces them.
+    "A3": Config("A3", 7, "bf16", 64, 10_000, 10_000_000, 64, "zipf", 500, 64, 1, False,
+                 CROSS_HADAMARD, 0, 0, 128, (320, 512, 256, 1), 100),
 }
 for _c in CONFIGS.values():
     assert _c.d_in == _c.mlp_dims[0], (_c.name, _c.d_in)
@@ -159,6 +164,8 @@ def make_user(cfg: Config, rng: np.random.Generator, sigma: float = 0.1,
     k = g(L, cfg.d_attn)
     v = g(L, cfg.d_attn)
     cv = g(cfg.n_cross, cfg.d_cross_vec) if cfg.cross_mode in (CROSS_SEGDOT, CROSS_BEA) else None
+    if cfg.cross_mode == CROSS_HADAMARD and cfg.d_user != cfg.d_item:
+        cv = u[cfg.d_user - cfg.d_item:].copy()         # the trailing d_item entries of the user vector
     return User(u, k, v, cv)
 
 
@@ -373,3 +380,65 @@ def make_lsh_requests(cfg: LshConfig, n_users: Optional[int] = None, n_cand: Opt
         ids = rng.choice(ni, size=nc, replace=False).astype(np.int32) if nc <= ni else rng.integers(0, ni, nc).astype(np.int32)
         out.append(LshRequestHost(user, ids))
     return out
+
+
+# ----------------------------------------------------------------------------
+# user-side asynchronous network (Sec. 3.1, Eq. 1-3): raw embeddings and weights
+# ----------------------------------------------------------------------------
+@dataclass(frozen=True)
+class UserNetConfig:
+    name: str
+    index: int
+    dtype: str
+    n_users: int
+    seq_len: int
+    d_raw: int            # d^U: width of the profile / behaviour embeddings
+    d: int                # common width after Eq. 1
+
+    @property
+    def seed(self) -> int:
+        return SEED_BASE + 200 + self.index
+
+    def scaled(self, **kw) -> "UserNetConfig":
+        return replace(self, **kw)
+
+
+USER_CONFIGS: Dict[str, UserNetConfig] = {
+    # small, fp32: the user side of C1 (L = 50, attention width 32)
+    "U1": UserNetConfig("U1", 1, "f32", 1, 50, 48, 32),
+    # the user side of C3 / A3: 64 concurrent users, L = 500, 128-wide raw embeddings projected to 64
+    "U3": UserNetConfig("U3", 3, "bf16", 64, 500, 128, 64),
+}
+
+
+@dataclass
+class UserNetModel:
+    w_profile: np.ndarray     # [d, d_raw]
+    w_seq: np.ndarray         # [d, d_raw]
+    w_ffn: np.ndarray         # [d, d]
+    b_ffn: np.ndarray         # [d]
+
+
+def make_user_net_model(cfg: UserNetConfig, seed: Optional[int] = None, bias_scale: float = 0.0) -> UserNetModel:
+    """Xavier-uniform weights; the FFN bias is zero unless ``bias_scale`` is given (tests)."""
+    rng = np.random.default_rng((cfg.seed if seed is None else seed) ^ 0x5EED)
+    r = lambda a: round_storage(a, cfg.dtype)
+    return UserNetModel(r(_xavier(rng, cfg.d, cfg.d_raw)), r(_xavier(rng, cfg.d, cfg.d_raw)), r(_xavier(rng, cfg.d, cfg.d)),
+                        r(rng.standard_normal(cfg.d).astype(np.float32) * bias_scale))
+
+
+@dataclass
+class RawUser:
+    profile: np.ndarray       # [d_raw]
+    seq: np.ndarray           # [L, d_raw]
+
+
+def make_raw_user(cfg: UserNetConfig, rng: np.random.Generator, sigma: float = 0.1, seq_len: Optional[int] = None) -> RawUser:
+    L = cfg.seq_len if seq_len is None else seq_len
+    g = lambda *s: round_storage(rng.standard_normal(s).astype(np.float32) * sigma, cfg.dtype)
+    return RawUser(g(cfg.d_raw), g(L, cfg.d_raw))
+
+
+def make_raw_users(cfg: UserNetConfig, n_users: Optional[int] = None, seed: Optional[int] = None, sigma: float = 0.1) -> List[RawUser]:
+    rng = np.random.default_rng(cfg.seed if seed is None else seed)
+    return [make_raw_user(cfg, rng, sigma) for _ in range(cfg.n_users if n_users is None else n_users)]

@@ -31,6 +31,9 @@ def test_library_exports_every_declared_symbol():
     for name in _declared("aif_lsh.h"):
         assert hasattr(lib, name), name
     assert set(binding.LSH_EXPORTS) == set(_declared("aif_lsh.h"))
+    for name in _declared("aif_user.h"):
+        assert hasattr(lib, name), name
+    assert set(binding.USER_EXPORTS) == set(_declared("aif_user.h"))
 
 
 def test_binding_structs_match_the_c_layout():
@@ -45,6 +48,9 @@ def test_binding_structs_match_the_c_layout():
     assert ctypes.sizeof(B.aif_lsh_config) == 40 and B.aif_lsh_config.d_bits.offset == 8
     assert ctypes.sizeof(B.aif_lsh_request) == 56
     assert B.aif_lsh_request.cand_ids.offset == 24 and B.aif_lsh_request.din_out.offset == 40
+    # aif_user.h
+    assert ctypes.sizeof(B.aif_user_config) == 20 and ctypes.sizeof(B.aif_user_weights) == 32
+    assert ctypes.sizeof(B.aif_user_request) == 40 and B.aif_user_request.user_vec_out.offset == 24
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
