@@ -11,6 +11,9 @@ request shape the metric is quoted on.  Prints ONE JSON line.
 
 ``--workload B3`` is C3 with the cross block formed by the Bridge Embedding Approximation (Sec. 4.1).
 
+``--workload U1|U3`` times the user-side asynchronous network alone (aif_user_precompute, Sec. 3.1 Eq. 1-3);
+``--workload A3`` the two phases of Sec. 3.1 together: the user network of the next batch of users on one stream
+beside the real-time scoring of the current batch on another (and, for comparison, both on one stream).
 ``--workload L1..L3`` times the LSH behaviour-modelling path instead (aif_lsh_batch: user-side bit
 tables -> LSH-DIN -> SimTier over every candidate x history pair); same JSON contract, its own metric.
 """
@@ -233,12 +236,151 @@ def main_lsh(args):
     print(json.dumps(line))
 
 
+def user_net_work(cfg):
+    """Algorithmic flops per user of the user-side network: Eq. 1 projections, the two attentions (every position
+    and the profile over the l positions), the FFN."""
+    L, d, dr = cfg.seq_len, cfg.d, cfg.d_raw
+    return {"project": 2 * (L + 1) * dr * d, "attention": 4 * (L + 1) * L * d, "ffn_pool": 2 * L * d * d + L * d}
+
+
+def user_cpu_baseline(cfg, w, seconds_budget=15.0):
+    import oracle
+    t0 = time.perf_counter()
+    n = 0
+    for u in w.users:
+        oracle.user_network(profile=u.profile, seq=u.seq, w_profile=w.model.w_profile, w_seq=w.model.w_seq,
+                            w_ffn=w.model.w_ffn, b_ffn=w.model.b_ffn)
+        n += 1
+        if time.perf_counter() - t0 > seconds_budget:
+            break
+    t = time.perf_counter() - t0
+    return {"value": n / t, "unit": "users/s", "cores": 1, "kind": "oracle",
+            "sample": f"{n} user(s) of {cfg.name}, l = {cfg.seq_len} (oracle Eq. 1-3, one thread, {t:.1f} s wall)"}
+
+
+def main_user(args):
+    import torch
+
+    from paper_2511_12934_amd import runner as R
+    from paper_2511_12934_amd import workloads as wl
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    cfg = wl.USER_CONFIGS[args.workload]
+    w = R.UserNetWorkload(cfg)
+    for _ in range(args.warmup):
+        w.step()
+    torch.cuda.synchronize()
+    w.ctx.aif_user_profile_begin(args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        w.step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = w.ctx.aif_user_profile_end()
+    ms_per_step = elapsed / args.steps * 1e3
+    work = user_net_work(cfg)
+    mf = w.ctx.aif_user_attention_kind() == 1
+    kernels = {}
+    for st in ("project", "attention", "ffn_pool"):
+        ms, n = prof[st]
+        avg = ms / max(n, 1)
+        kernels[st] = {"avg_ms": avg, "tflops": work[st] * w.n_users / (avg * 1e-3) / 1e12 if avg > 0 else None}
+    kernels["attention"]["kind"] = "mfma" if mf else "generic"
+    dom = max(kernels, key=lambda k: kernels[k]["avg_ms"])
+    on_mfma = dom == "attention" and mf
+    roof = {"kernel": dom, "bound": "mfma" if on_mfma else "alu", "achieved": kernels[dom]["tflops"],
+            "peak": PEAK_MFMA_BF16_TFLOPS if on_mfma else PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = measured_traffic(cfg.name, dom)
+    roof["avg_ms"] = kernels[dom]["avg_ms"]
+    line = {
+        "metric": "users served/sec/GPU by the asynchronous user-side network (Eq. 1-3)",
+        "value": w.n_users * args.steps / elapsed, "unit": "users/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {w.n_users} users x {cfg.seq_len} positions, raw width {cfg.d_raw}, "
+                               f"d = {cfg.d}, {cfg.dtype}", "users": w.n_users, "seq_len": cfg.seq_len},
+        "roofline": roof, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = user_cpu_baseline(cfg, w)
+    print(json.dumps(line))
+
+
+def main_async(args):
+    import torch
+
+    from paper_2511_12934_amd import runner as R
+    from paper_2511_12934_amd import workloads as wl
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    cfg, ucfg = wl.CONFIGS["A3"], wl.USER_CONFIGS["U3"]
+    p = R.AsyncPipeline(cfg, ucfg)
+
+    # the first steps on a stream that has not run yet are slow (tens of ms once): warm both modes up well
+    warm = max(args.warmup, 30)
+    warm += warm % 2
+
+    def timed(overlap, profile):
+        if overlap:
+            p.prime()
+        for i in range(warm):
+            p.step(i, overlap)
+        torch.cuda.synchronize()
+        if profile:
+            p.ctx.aif_profile_begin(args.steps)
+            p.uctx.aif_user_profile_begin(args.steps)
+        t0 = time.perf_counter()
+        for i in range(warm, warm + args.steps):
+            p.step(i, overlap)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        return el, (p.ctx.aif_profile_end(), p.uctx.aif_user_profile_end()) if profile else None
+
+    serial, (prof, uprof) = timed(False, True)
+    over, _ = timed(True, False)
+    ms_per_step = over / args.steps * 1e3
+    work = algorithmic_work(cfg)
+    cands = p.total_candidates
+    kernels = {}
+    for stage in ("gather", "attention", "mlp", "topk"):
+        ms, n = prof[stage]
+        avg_ms = ms / max(n, 1)
+        ent = {"avg_ms": avg_ms, "kind": "mfma" if p.ctx.aif_stage_kind(stage) == 1 else "generic"}
+        if "flops" in work[stage] and avg_ms > 0:
+            ent["tflops"] = work[stage]["flops"] * cands / (avg_ms * 1e-3) / 1e12
+        if avg_ms > 0:
+            ent["gbs"] = work[stage]["bytes"] * cands / (avg_ms * 1e-3) / 1e9
+        kernels[stage] = ent
+    for st in ("project", "attention", "ffn_pool"):
+        ms, n = uprof[st]
+        kernels["user_" + st] = {"avg_ms": ms / max(n, 1)}
+    roof = {"kernel": "mlp", "bound": "mfma", "achieved": kernels["mlp"]["tflops"], "peak": PEAK_MFMA_BF16_TFLOPS,
+            "unit": "TFLOP/s", "frac": kernels["mlp"]["tflops"] / PEAK_MFMA_BF16_TFLOPS,
+            "traffic": measured_traffic(cfg.name, "mlp"), "avg_ms": kernels["mlp"]["avg_ms"],
+            "note": "per-kernel times from the one-stream run (kernels of the two streams share the device in the overlapped one)"}
+    line = {
+        "metric": "candidates scored/sec/GPU at 10^4-cand requests", "value": cands * args.steps / over,
+        "unit": "candidates/s", "n_gpus": 1, "steps": args.steps, "warmup": warm, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"A3: per step the user-side network (Eq. 1-3) of the next {p.n_users} users (l = {ucfg.seq_len}, "
+                               f"raw width {ucfg.d_raw}) on one stream beside scoring + top-{cfg.top_k} of {p.n_users} users x "
+                               f"{p.n_cand} candidates on another; table {cfg.n_items}x{cfg.d_item} {cfg.dtype}, "
+                               f"MLP {list(cfg.mlp_dims)}", "users": p.n_users, "candidates_per_request": p.n_cand,
+                   "top_k": cfg.top_k},
+        "one_stream_ms_per_step": serial / args.steps * 1e3,
+        "user_network_ms": sum(kernels["user_" + st]["avg_ms"] for st in ("project", "attention", "ffn_pool")),
+        "roofline": roof, "kernels": kernels,
+    }
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5", "B3", "L1", "L2", "L3"])
+    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5", "B3", "A3", "U1", "U3", "L1", "L2", "L3"])
     ap.add_argument("--id-sets", type=int, default=4,
                     help="distinct candidate lists per user, taken in turn by consecutive steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -250,6 +392,10 @@ def main():
 
     if args.workload.startswith("L"):
         return main_lsh(args)
+    if args.workload.startswith("U"):
+        return main_user(args)
+    if args.workload == "A3":
+        return main_async(args)
 
     import torch
 

@@ -10,6 +10,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -29,7 +30,8 @@ struct aif_user_ctx {
     int device = 0, n_cu = 256;
     int max_seq_len = 0, max_users = 0;
     size_t x_rows = 0;
-    void *wseq_t = nullptr, *wprof_t = nullptr, *wffn_t = nullptr, *b_ffn = nullptr;   // fp32 copies (owned)
+    void *wseq_t = nullptr, *wprof = nullptr, *wffn_t = nullptr, *b_ffn = nullptr;   // fp32 copies (owned)
+    void *wseq_frag = nullptr, *wffn_frag = nullptr;                                  // bf16 MFMA fragments (owned)
     void *X = nullptr, *part = nullptr;                                               // workspace (owned)
     MfmaPlan mfma{};
     char *h_stage = nullptr;
@@ -73,7 +75,7 @@ int round_up(int v, int a) { return (v + a - 1) / a * a; }
 void udestroy(aif_user_ctx *c)
 {
     if (!c) return;
-    for (void *p : {c->wseq_t, c->wprof_t, c->wffn_t, c->b_ffn, c->X, c->part, c->d_stage})
+    for (void *p : {c->wseq_t, c->wprof, c->wffn_t, c->b_ffn, c->wseq_frag, c->wffn_frag, c->X, c->part, c->d_stage})
         if (p) (void)hipFree(p);
     mfma_release(c->mfma);
     if (c->h_stage) (void)hipHostFree(c->h_stage);
@@ -126,17 +128,30 @@ aif_status uinit(const aif_user_config *cfg, const aif_user_weights *wts, aif_us
     hipStream_t s = nullptr;
     const size_t pw = (size_t)cfg->d_raw * cfg->d * 4, fw = (size_t)cfg->d * cfg->d * 4;
     USER_TRY(nullptr, hipMalloc(&c->wseq_t, pw));
-    USER_TRY(nullptr, hipMalloc(&c->wprof_t, pw));
+    USER_TRY(nullptr, hipMalloc(&c->wprof, pw));
     USER_TRY(nullptr, hipMalloc(&c->wffn_t, fw));
     USER_TRY(nullptr, launch_pack_transposed(m.dtype, wts->w_seq, cfg->d, cfg->d_raw, 0, cfg->d_raw, (float *)c->wseq_t, s));
-    USER_TRY(nullptr, launch_pack_transposed(m.dtype, wts->w_profile, cfg->d, cfg->d_raw, 0, cfg->d_raw, (float *)c->wprof_t, s));
+    USER_TRY(nullptr, launch_to_f32(m.dtype, wts->w_profile, cfg->d, cfg->d_raw, cfg->d_raw, 0, (float *)c->wprof, s));
     USER_TRY(nullptr, launch_pack_transposed(m.dtype, wts->w_ffn, cfg->d, cfg->d, 0, cfg->d, (float *)c->wffn_t, s));
     if (wts->b_ffn) {
         USER_TRY(nullptr, hipMalloc(&c->b_ffn, (size_t)cfg->d * 4));
         USER_TRY(nullptr, launch_to_f32(m.dtype, wts->b_ffn, 1, cfg->d, cfg->d, 0, (float *)c->b_ffn, s));
     }
-    c->w = UserWeights{(const float *)c->wseq_t, (const float *)c->wprof_t, (const float *)c->wffn_t,
-                       (const float *)c->b_ffn, cfg->d_raw, cfg->d, m.dtype};
+    c->w = UserWeights{(const float *)c->wseq_t, (const float *)c->wprof, (const float *)c->wffn_t,
+                       (const float *)c->b_ffn, cfg->d_raw, cfg->d, m.dtype, nullptr, nullptr, USER_FFN_ROWS};
+    {
+        const char *force = getenv("AIF_FORCE_GENERIC");
+        const bool generic = force && force[0] == '1';
+        if (!generic && m.dtype == 1 && (cfg->d == 32 || cfg->d == 64 || cfg->d == 128) && cfg->d_raw % 16 == 0) {
+            USER_TRY(nullptr, hipMalloc(&c->wseq_frag, (size_t)cfg->d * cfg->d_raw * 2));
+            USER_TRY(nullptr, hipMalloc(&c->wffn_frag, (size_t)cfg->d * cfg->d * 2));
+            USER_TRY(nullptr, pack_frag(wts->w_seq, cfg->d_raw, 0, cfg->d, cfg->d_raw, false, c->wseq_frag, s));
+            USER_TRY(nullptr, pack_frag(wts->w_ffn, cfg->d, 0, cfg->d, cfg->d, false, c->wffn_frag, s));
+            c->w.wseq_frag = c->wseq_frag;
+            c->w.wffn_frag = c->wffn_frag;
+            c->w.part_rows = 32;
+        }
+    }
 
     // the attention kernels: MFMA when the shape is one they serve, else the shape-agnostic one
     const void *no_w[1] = {nullptr};
@@ -146,7 +161,7 @@ aif_status uinit(const aif_user_config *cfg, const aif_user_weights *wts, aif_us
 
     c->x_rows = (size_t)c->max_users * round_up(c->max_seq_len + 1, ROW_BLOCK);
     USER_TRY(nullptr, hipMalloc(&c->X, c->x_rows * m.ldx * esz));
-    USER_TRY(nullptr, hipMalloc(&c->part, c->x_rows / USER_FFN_ROWS * cfg->d * 4));
+    USER_TRY(nullptr, hipMalloc(&c->part, c->x_rows / 32 * cfg->d * 4));
     const size_t n_blk_max = c->x_rows / ROW_BLOCK;
     const size_t sb = (size_t)c->max_users * (sizeof(ReqDesc) + sizeof(UserDesc)) + (n_blk_max + 4) * sizeof(int32_t) + 16 +
                       attn_max_groups(c->x_rows, c->max_users) * sizeof(AttnGroup);

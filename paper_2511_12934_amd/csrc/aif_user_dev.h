@@ -22,10 +22,14 @@ struct UserDesc {
 
 struct UserWeights {
     const float *wseq_t;        // [d_raw, d] fp32: W_seq transposed
-    const float *wprof_t;       // [d_raw, d]
+    const float *wprof;         // [d, d_raw] fp32: W_profile as given (row-major)
     const float *wffn_t;        // [d, d]
     const float *b_ffn;         // [d] or null
     int32_t d_raw, d, dtype;
+    // bf16 MFMA variants of the projection and the FFN (d = 32, 64 or 128, d_raw a multiple of 16): the
+    // weights as A fragments, [row tile][k-step][lane][8], as pack_frag lays them out; null = not used
+    const void *wseq_frag, *wffn_frag;
+    int32_t part_rows;          // positions summed into one partial of the pooling (USER_FFN_ROWS, or 32 with MFMA)
 };
 
 // Eq. 1: X[row, 0:d] = W x for every sequence position and the profile; U^_seq also to the user's seq_out.

@@ -10,6 +10,128 @@
 
 namespace aif {
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// The projected profile: a wave per output feature, its lanes share the input features (coalesced reads of
+// the row-major weight row) and meet in a fixed butterfly.
+template <typename T>
+__device__ __forceinline__ void project_profile(const UserWeights &w, const UserDesc &ud, T *__restrict__ X, int nthreads)
+{
+    const T *pr = (const T *)ud.profile;
+    const int d = w.d, lane = threadIdx.x & 63;
+    for (int n = threadIdx.x >> 6; n < d; n += nthreads >> 6) {
+        float acc = 0.f;
+        for (int m = lane; m < w.d_raw; m += 64) acc = fmaf(w.wprof[(size_t)n * w.d_raw + m], ld_f<T>(pr + m), acc);
+#pragma unroll
+        for (int o = 32; o; o >>= 1) acc += __shfl_xor(acc, o, 64);
+        if (lane == 0) st_f<T>(X + (size_t)(ud.row_base + ud.seq_len) * (2 * d) + n, acc);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 1 on the matrix cores (bf16): U^_seq^T = W_seq U_seq^T, positions as the
+// columns of the B operand.  A wave owns 32 positions; lane (position c, half h)
+// reads eight consecutive input features of its position per k-step straight
+// from the caller's row-major sequence and receives sixteen output features of
+// that position per 32-feature tile (features 8 q + 4 h + i), which it writes as
+// four 8-byte pieces to the workspace row and to the user's seq_out.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void k_user_project_mfma(UserWeights w, const UserDesc *__restrict__ users,
+                                                           const int32_t *__restrict__ blk_req, uint16_t *__restrict__ X)
+{
+    constexpr int FT = D / 32, ROWS = 128, SUB = ROW_BLOCK / ROWS;
+    const int u = blk_req[blockIdx.x / SUB];
+    if (u < 0) return;
+    const UserDesc ud = users[u];
+    const int row0 = blockIdx.x * ROWS, local0 = row0 - ud.row_base, L = ud.seq_len;
+    if (local0 > L) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, h = lane >> 5;
+    const int li = local0 + wave * 32 + col;
+    const int KS = w.d_raw / 16;
+    if (local0 + wave * 32 < L) {                               // wave-uniform: some position of this wave exists
+        const uint16_t *src = (const uint16_t *)ud.seq + (size_t)(li < L ? li : 0) * w.d_raw + 8 * h;
+        const bf16x8 *wf = (const bf16x8 *)w.wseq_frag + lane;
+        f32x16 acc[FT];
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[ft][i] = 0.f;
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 b = *(const bf16x8 *)(src + 16 * ks);
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft)
+                acc[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[(size_t)(ft * KS + ks) * 64], b, acc[ft], 0, 0, 0);
+        }
+        if (li < L) {
+            uint16_t *xr = X + (size_t)(row0 + wave * 32 + col) * (2 * D), *so = (uint16_t *)ud.seq_out + (size_t)li * D;
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o4[i] = (__bf16)acc[ft][4 * q + i];
+                    const int f = 32 * ft + 8 * q + 4 * h;
+                    *(bf16x4 *)(xr + f) = o4;
+                    *(bf16x4 *)(so + f) = o4;
+                }
+        }
+    }
+    if (L >= local0 && L < local0 + ROWS) project_profile<uint16_t>(w, ud, X, 256);
+}
+
+// ---------------------------------------------------------------------------
+// FFN of Eq. 2 on the matrix cores (bf16) and the pooling share of 32 positions:
+// Y^T = W_ffn A^T with the accumulators preloaded with the bias, ReLU, positions
+// past the end zeroed, then the sum over the wave's 32 positions (the lanes of a
+// half) by a fixed butterfly.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void k_user_ffn_mfma(UserWeights w, const UserDesc *__restrict__ users,
+                                                       const int32_t *__restrict__ blk_req, const uint16_t *__restrict__ X,
+                                                       float *__restrict__ part)
+{
+    constexpr int FT = D / 32, KS = D / 16, ROWS = 128, SUB = ROW_BLOCK / ROWS;
+    const int u = blk_req[blockIdx.x / SUB];
+    if (u < 0) return;
+    const UserDesc ud = users[u];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, h = lane >> 5;
+    const int row0 = blockIdx.x * ROWS + wave * 32, local0 = row0 - ud.row_base, L = ud.seq_len;
+    if (local0 >= L) return;
+    const uint16_t *src = X + (size_t)(row0 + col) * (2 * D) + D + 8 * h;      // rows past L are inside the workspace
+    const bf16x8 *wf = (const bf16x8 *)w.wffn_frag + lane;
+    bf16x8 b[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) b[ks] = *(const bf16x8 *)(src + 16 * ks);
+    const bool live = local0 + col < L;
+#pragma unroll
+    for (int ft = 0; ft < FT; ++ft) {
+        f32x16 acc;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[4 * q + i] = w.b_ffn ? w.b_ffn[32 * ft + 8 * q + 4 * h + i] : 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[(size_t)(ft * KS + ks) * 64], b[ks], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float y = live ? fmaxf(acc[v], 0.f) : 0.f;
+#pragma unroll
+            for (int o = 1; o < 32; o <<= 1) y += __shfl_xor(y, o, 64);
+            acc[v] = y;
+        }
+        if (col == 0) {
+            float *dst = part + (size_t)(row0 / 32) * D + 32 * ft + 4 * h;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) *(float4 *)(dst + 8 * q) = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Eq. 1.  One block = USER_PROJ_ROWS rows of one user.  The rows are staged in
 // LDS transposed (xs[m][row]) so that a thread reads the eight rows it owns for
@@ -66,14 +188,7 @@ __global__ __launch_bounds__(256) void k_user_project(UserWeights w, const UserD
         }
     }
     // the profile row, if it falls into this block
-    if (L >= local0 && L < local0 + RT) {
-        const T *pr = (const T *)ud.profile;
-        for (int n = threadIdx.x; n < d; n += 256) {
-            float acc = 0.f;
-            for (int m = 0; m < d_raw; ++m) acc = fmaf(w.wprof_t[(size_t)m * d + n], ld_f<T>(pr + m), acc);
-            st_f<T>(X + (size_t)(ud.row_base + L) * (2 * d) + n, acc);
-        }
-    }
+    if (L >= local0 && L < local0 + RT) project_profile<T>(w, ud, X, 256);
 }
 
 size_t user_project_lds_bytes(int d_raw) { return (size_t)d_raw * USER_PROJ_ROWS * sizeof(float); }
@@ -82,6 +197,16 @@ hipError_t launch_user_project(const UserWeights &w, const UserDesc *users, cons
                                hipStream_t s)
 {
     if (n_blk == 0) return hipSuccess;
+    if (w.wseq_frag) {
+        const dim3 g(n_blk * (ROW_BLOCK / 128));
+        switch (w.d) {
+        case 32: hipLaunchKernelGGL(k_user_project_mfma<32>, g, dim3(256), 0, s, w, users, blk_req, (uint16_t *)X); break;
+        case 64: hipLaunchKernelGGL(k_user_project_mfma<64>, g, dim3(256), 0, s, w, users, blk_req, (uint16_t *)X); break;
+        case 128: hipLaunchKernelGGL(k_user_project_mfma<128>, g, dim3(256), 0, s, w, users, blk_req, (uint16_t *)X); break;
+        default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
     const size_t lds = user_project_lds_bytes(w.d_raw);
     const dim3 grid(n_blk * (ROW_BLOCK / USER_PROJ_ROWS));
     if (w.dtype == 0) {
@@ -155,6 +280,16 @@ hipError_t launch_user_ffn_partial(const UserWeights &w, const UserDesc *users, 
                                    const void *X, float *part, hipStream_t s)
 {
     if (n_blk == 0) return hipSuccess;
+    if (w.wffn_frag) {
+        const dim3 g(n_blk * (ROW_BLOCK / 128));
+        switch (w.d) {
+        case 32: hipLaunchKernelGGL(k_user_ffn_mfma<32>, g, dim3(256), 0, s, w, users, blk_req, (const uint16_t *)X, part); break;
+        case 64: hipLaunchKernelGGL(k_user_ffn_mfma<64>, g, dim3(256), 0, s, w, users, blk_req, (const uint16_t *)X, part); break;
+        case 128: hipLaunchKernelGGL(k_user_ffn_mfma<128>, g, dim3(256), 0, s, w, users, blk_req, (const uint16_t *)X, part); break;
+        default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
     const size_t lds = user_ffn_lds_bytes(w.d);
     const dim3 grid(n_blk * (ROW_BLOCK / USER_FFN_ROWS));
     if (w.dtype == 0) {
@@ -176,8 +311,8 @@ __global__ __launch_bounds__(256) void k_user_combine(UserWeights w, const UserD
 {
     const UserDesc ud = users[blockIdx.x];
     const int d = w.d, L = ud.seq_len;
-    const int nb = (L + USER_FFN_ROWS - 1) / USER_FFN_ROWS;
-    const size_t b0 = (size_t)ud.row_base / USER_FFN_ROWS;
+    const int nb = (L + w.part_rows - 1) / w.part_rows;
+    const size_t b0 = (size_t)ud.row_base / w.part_rows;
     T *out = (T *)ud.user_vec_out;
     for (int n = threadIdx.x; n < d; n += 256) {
         float sum = 0.f;

@@ -280,3 +280,90 @@ class UserNetWorkload:
 
     def step(self, stream: Optional[int] = None):
         self.ctx.aif_user_precompute([d.req for d in self.dev], packed=self.packed, stream=stream)
+
+
+class AsyncPipeline:
+    """Steady state of the two phases of Sec. 3.1 on one device: while the real-time phase scores the candidates
+    of one batch of users (stream ``s_score``), the pre-computation phase runs the user-side network for the next
+    batch (stream ``s_user``), as it would beside retrieval.  The cached user tensors are double-buffered; a
+    scoring call waits for the event that marks its buffer complete, a pre-computation waits until the scoring
+    call that last read its buffer has finished.  ``step(i, overlap=False)`` runs the same work on one stream."""
+
+    def __init__(self, cfg: wl.Config, ucfg: wl.UserNetConfig, device="cuda:0", n_items: Optional[int] = None,
+                 n_cand: Optional[int] = None, n_users: Optional[int] = None):
+        import torch
+        assert cfg.d_user == 2 * ucfg.d and cfg.d_attn == ucfg.d and cfg.d_item == ucfg.d and cfg.dtype == ucfg.dtype
+        self.cfg, self.ucfg, self.torch = cfg, ucfg, torch
+        self.n_users = cfg.n_users if n_users is None else n_users
+        self.n_cand = cfg.n_cand if n_cand is None else n_cand
+        self.n_items = cfg.n_items if n_items is None else n_items
+        self.model = wl.make_model(cfg)
+        self.dmodel = DeviceModel(cfg, self.model, device)
+        self.umodel = wl.make_user_net_model(ucfg)
+        self.table = wl.make_table_device(cfg, device, self.n_items)
+        self.uctx = make_user_context(ucfg, self.umodel, max_users=self.n_users, device=device)
+        self.ctx = make_context(cfg, self.dmodel, self.table, max_users=self.n_users, max_candidates=self.n_cand,
+                                max_seq_len=ucfg.seq_len)
+        self.raw, self.udev, self.upacked, self.ids, self.reqs, self.packed, self.logits = [], [], [], [], [], [], []
+        for b in range(2):
+            raw = wl.make_raw_users(ucfg, self.n_users, seed=ucfg.seed + 31 * b)
+            udev = [upload_raw_user(ucfg, u, device) for u in raw]
+            ids = wl.make_id_lists(cfg, b, self.n_users, self.n_cand, self.n_items)
+            reqs, zs = [], []
+            for d, idl in zip(udev, ids):
+                idt = torch.from_numpy(np.ascontiguousarray(idl, dtype=np.int32)).to(device)
+                z = torch.full((idl.size,), float("nan"), dtype=torch.float32, device=device)
+                reqs.append(B.Request(d.user_vec, d.seq_out, d.seq_out, idt, z, None, d.user_vec[ucfg.d:], d.req.seq_len))
+                zs.append(z)
+            self.raw.append(raw)
+            self.udev.append(udev)
+            self.upacked.append(B.pack_user_requests([d.req for d in udev]))
+            self.ids.append(ids)
+            self.reqs.append(reqs)
+            self.packed.append(B.pack_requests(reqs))
+            self.logits.append(zs)
+        self.k = cfg.top_k
+        self.idx = torch.empty((self.n_users, self.k), dtype=torch.int32, device=device)
+        self.val = torch.empty((self.n_users, self.k), dtype=torch.float32, device=device)
+        self.s_score = torch.cuda.Stream(device=device)
+        self.s_user = torch.cuda.Stream(device=device)
+        self.u_done = [torch.cuda.Event() for _ in range(2)]
+        self.s_done = [torch.cuda.Event() for _ in range(2)]
+        self._s_recorded = [False, False]
+
+    @property
+    def total_candidates(self) -> int:
+        return self.n_users * self.n_cand
+
+    def _precompute(self, b: int):
+        self.uctx.aif_user_precompute([d.req for d in self.udev[b]], packed=self.upacked[b])
+
+    def _score(self, b: int):
+        self.ctx.aif_score_batch(self.reqs[b], packed=self.packed[b])
+        self.ctx.aif_topk(self.logits[b], self.k, self.idx, self.val)
+
+    def prime(self):
+        """User tensors of buffer 0, before the first overlapped step."""
+        torch = self.torch
+        with torch.cuda.stream(self.s_user):
+            self._precompute(0)
+            self.u_done[0].record()
+
+    def step(self, i: int, overlap: bool = True):
+        torch = self.torch
+        b, nb = i % 2, 1 - i % 2
+        if not overlap:
+            with torch.cuda.stream(self.s_score):
+                self._precompute(b)
+                self._score(b)
+            return
+        with torch.cuda.stream(self.s_user):
+            if self._s_recorded[nb]:
+                self.s_user.wait_event(self.s_done[nb])
+            self._precompute(nb)
+            self.u_done[nb].record()
+        with torch.cuda.stream(self.s_score):
+            self.s_score.wait_event(self.u_done[b])
+            self._score(b)
+            self.s_done[b].record()
+            self._s_recorded[b] = True

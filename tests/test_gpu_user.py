@@ -65,7 +65,8 @@ def test_u1_fp32_whole_configuration(R, torch):
 
 
 @pytest.mark.parametrize("dtype,d_raw,d,lens", [("f32", 12, 8, (0, 1, 7, 65)), ("bf16", 24, 16, (3, 33, 130)),
-                                                ("bf16", 40, 72, (50,)), ("f32", 256, 128, (40,))])
+                                                ("bf16", 40, 72, (50,)), ("f32", 256, 128, (40,)),
+                                                ("bf16", 64, 128, (70, 33, 128))])
 def test_shape_agnostic_kernels_on_odd_shapes(R, torch, dtype, d_raw, d, lens):
     cfg = wl.UserNetConfig("T", 9, dtype, len(lens), max(lens), d_raw, d)
     _say(f"user net generic {dtype} d_raw={d_raw} d={d} lens={lens}")
@@ -92,6 +93,19 @@ def test_mfma_attention_path(R, torch, d, lens, sigma):
     assert ctx.aif_user_attention_kind() == 1
     for i, u in enumerate(users):
         check_user("bf16", got[i], oracle_user(model, u), d, f"MFMA user {i} (L={lens[i]})")
+
+
+def test_forced_generic_kernels_agree_with_the_oracle_on_the_mfma_shape(R, torch, monkeypatch):
+    monkeypatch.setenv("AIF_FORCE_GENERIC", "1")
+    cfg = wl.UserNetConfig("T", 12, "bf16", 2, 140, 128, 64)
+    _say("user net, bf16 d=64 on the shape-agnostic kernels")
+    model = wl.make_user_net_model(cfg, bias_scale=0.05)
+    rng = np.random.default_rng(8)
+    users = [wl.make_raw_user(cfg, rng, seq_len=L) for L in (140, 65)]
+    got, _, ctx = run_users(R, torch, cfg, model, users)
+    assert ctx.aif_user_attention_kind() == 0
+    for i, u in enumerate(users):
+        check_user("bf16", got[i], oracle_user(model, u), cfg.d, f"forced generic user {i}")
 
 
 def test_a_users_result_does_not_depend_on_its_batch(R, torch):
