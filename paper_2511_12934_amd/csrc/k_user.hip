@@ -14,19 +14,26 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-// The projected profile: a wave per output feature, its lanes share the input features (coalesced reads of
-// the row-major weight row) and meet in a fixed butterfly.
+// The projected profile: four adjacent lanes share an output feature, each takes a quarter of the input
+// features (d_raw is a multiple of four), they meet in a fixed two-step butterfly.  All of a thread's loads are
+// independent, so the row costs about one round trip to memory.
 template <typename T>
 __device__ __forceinline__ void project_profile(const UserWeights &w, const UserDesc &ud, T *__restrict__ X, int nthreads)
 {
     const T *pr = (const T *)ud.profile;
-    const int d = w.d, lane = threadIdx.x & 63;
-    for (int n = threadIdx.x >> 6; n < d; n += nthreads >> 6) {
+    const int d = w.d, q = threadIdx.x & 3, chunk = w.d_raw >> 2;
+    for (int n0 = 0; n0 < d; n0 += nthreads >> 2) {
+        const int n = n0 + (threadIdx.x >> 2);
         float acc = 0.f;
-        for (int m = lane; m < w.d_raw; m += 64) acc = fmaf(w.wprof[(size_t)n * w.d_raw + m], ld_f<T>(pr + m), acc);
-#pragma unroll
-        for (int o = 32; o; o >>= 1) acc += __shfl_xor(acc, o, 64);
-        if (lane == 0) st_f<T>(X + (size_t)(ud.row_base + ud.seq_len) * (2 * d) + n, acc);
+        if (n < d) {
+            const float *wr = w.wprof + (size_t)n * w.d_raw + q * chunk;
+            const T *px = pr + q * chunk;
+#pragma unroll 8
+            for (int m = 0; m < chunk; ++m) acc = fmaf(wr[m], ld_f<T>(px + m), acc);
+        }
+        acc += __shfl_xor(acc, 1, 64);
+        acc += __shfl_xor(acc, 2, 64);
+        if (n < d && q == 0) st_f<T>(X + (size_t)(ud.row_base + ud.seq_len) * (2 * d) + n, acc);
     }
 }
 
@@ -59,11 +66,21 @@ __global__ __launch_bounds__(256) void k_user_project_mfma(UserWeights w, const 
         for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[ft][i] = 0.f;
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 b = *(const bf16x8 *)(src + 16 * ks);
+        // all of a group's input pieces are asked for before its first MFMA: the loads are independent, and one
+        // round trip to memory per group instead of one per k-step is what this short kernel's time is made of
+        constexpr int G = 8;
+        for (int k0 = 0; k0 < KS; k0 += G) {
+            bf16x8 b[G];
 #pragma unroll
-            for (int ft = 0; ft < FT; ++ft)
-                acc[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[(size_t)(ft * KS + ks) * 64], b, acc[ft], 0, 0, 0);
+            for (int j = 0; j < G; ++j)
+                if (k0 + j < KS) b[j] = *(const bf16x8 *)(src + 16 * (k0 + j));
+#pragma unroll
+            for (int j = 0; j < G; ++j)
+                if (k0 + j < KS) {
+#pragma unroll
+                    for (int ft = 0; ft < FT; ++ft)
+                        acc[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[(size_t)(ft * KS + k0 + j) * 64], b[j], acc[ft], 0, 0, 0);
+                }
         }
         if (li < L) {
             uint16_t *xr = X + (size_t)(row0 + wave * 32 + col) * (2 * D), *so = (uint16_t *)ud.seq_out + (size_t)li * D;
