@@ -14,6 +14,8 @@ request shape the metric is quoted on.  Prints ONE JSON line.
 ``--workload U1|U3`` times the user-side asynchronous network alone (aif_user_precompute, Sec. 3.1 Eq. 1-3);
 ``--workload A3`` the two phases of Sec. 3.1 together: the user network of the next batch of users on one stream
 beside the real-time scoring of the current batch on another (and, for comparison, both on one stream).
+``--workload N3`` times the nearline incremental update of the item table (aif_update_rows, Sec. 3.4): 10^6 rows
+of C3's 10^7-row table per step.
 ``--workload L1..L3`` times the LSH behaviour-modelling path instead (aif_lsh_batch: user-side bit
 tables -> LSH-DIN -> SimTier over every candidate x history pair); same JSON contract, its own metric.
 """
@@ -375,12 +377,66 @@ def main_async(args):
     print(json.dumps(line))
 
 
+def main_update(args, n_upd=1_000_000):
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2511_12934_amd import runner as R
+    from paper_2511_12934_amd import workloads as wl
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    cfg = wl.CONFIGS["C3"]
+    w = R.Workload(cfg, n_users=1, n_cand=1000)
+    rng = np.random.default_rng(cfg.seed + 77)
+    # four id lists taken in turn, so a step does not rewrite the rows the last one left in the caches
+    id_sets = [torch.from_numpy(rng.permutation(cfg.n_items)[:n_upd].astype(np.int32)).to("cuda:0") for _ in range(4)]
+    rows = (torch.randn((n_upd, cfg.d_item), device="cuda:0") * 0.1).to(torch.bfloat16)
+    for i in range(args.warmup):
+        w.ctx.aif_update_rows(id_sets[i % 4], rows)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(args.steps):
+        w.ctx.aif_update_rows(id_sets[i % 4], rows)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert w.ctx.aif_poll_device_errors() == 0
+    kern_ms = sum(ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)) / args.steps
+    bytes_per_row = 4 + 2 * cfg.d_item * 2
+    gbs = bytes_per_row * n_upd / (kern_ms * 1e-3) / 1e9
+    line = {
+        "metric": "item-table rows updated/sec/GPU (nearline incremental update)", "value": n_upd * args.steps / elapsed,
+        "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"N3: {n_upd} distinct rows of C3's table ({cfg.n_items}x{cfg.d_item} bf16) per step, "
+                               "four id lists in turn", "rows_per_step": n_upd},
+        "roofline": {"kernel": "k_update_rows", "bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": gbs / PEAK_HBM_GBS, "traffic": measured_traffic("N3", "update"), "avg_ms": kern_ms},
+    }
+    if not args.no_cpu_baseline:
+        n_t, n_u = 1_000_000, 200_000
+        t = np.zeros((n_t, cfg.d_item), np.float32)
+        ids = rng.permutation(n_t)[:n_u].astype(np.int32)
+        r = rng.standard_normal((n_u, cfg.d_item)).astype(np.float32)
+        reps, c0 = 0, time.perf_counter()
+        while time.perf_counter() - c0 < 5.0:
+            oracle.update_rows(t, ids, r, inplace=True)
+            reps += 1
+        ct = time.perf_counter() - c0
+        line["cpu_baseline"] = {"value": reps * n_u / ct, "unit": "rows/s", "cores": 1, "kind": "oracle",
+                                "sample": f"{reps} update(s) of {n_u} rows of a {n_t}x{cfg.d_item} fp32 table (oracle, one thread, {ct:.1f} s wall)"}
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5", "B3", "A3", "U1", "U3", "L1", "L2", "L3"])
+    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5", "B3", "A3", "U1", "U3", "N3", "L1", "L2", "L3"])
     ap.add_argument("--id-sets", type=int, default=4,
                     help="distinct candidate lists per user, taken in turn by consecutive steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -396,6 +452,8 @@ def main():
         return main_user(args)
     if args.workload == "A3":
         return main_async(args)
+    if args.workload == "N3":
+        return main_update(args)
 
     import torch
 

@@ -146,6 +146,23 @@ AIF_API aif_status aif_score_batch(aif_ctx *ctx, const aif_request *reqs, int32_
 AIF_API aif_status aif_topk(aif_ctx *ctx, const float *const *logits, const int32_t *n_cand, int32_t n_req,
                     int32_t k, int32_t *idx_out, float *val_out, void *hip_stream);
 
+/* Nearline maintenance of the item table (Sec. 3.4: the index table of nearline results "supports both full
+ * and incremental updates").
+ *
+ * Incremental: row ids[i] of the context's item table becomes rows[i, :] (ids: DEVICE [n] int32; rows: DEVICE
+ * [n, d_item] row-major, config.dtype, 16-byte aligned).  The table handed to aif_score_init (or
+ * aif_swap_table) is written: it must be writable device memory.  Asynchronous on hip_stream and ordered with
+ * it: scoring calls enqueued earlier on the stream read the old rows, later ones the new rows.  The ids of
+ * one call must be distinct (a nearline batch is keyed by item); with a repeated id the row holds pieces of
+ * either source.  An id outside [0, n_items) writes nothing and bumps the counter read by
+ * aif_poll_device_errors.  Errors: AIF_EINVAL (NULL with n > 0, negative n, misaligned rows). */
+AIF_API aif_status aif_update_rows(aif_ctx *ctx, const int32_t *ids, const void *rows, int32_t n, void *hip_stream);
+
+/* Full update: later calls on this context read new_table (DEVICE [n_items, d_item] row-major, config.dtype,
+ * 16-byte aligned, borrowed like the first one).  Host-side only; calls already enqueued keep the old table,
+ * which the caller keeps alive until they complete. */
+AIF_API aif_status aif_swap_table(aif_ctx *ctx, const void *new_table, int64_t n_items);
+
 /* Release the context, its workspace and weight copies.  The caller must
  * have synchronised every stream the context was used on.  NULL is a no-op. */
 AIF_API void aif_score_destroy(aif_ctx *ctx);

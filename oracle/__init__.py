@@ -77,6 +77,22 @@ def gather(table, ids) -> np.ndarray:
     return out
 
 
+def update_rows(table, ids, rows, inplace: bool = False):
+    """Incremental update of the index table (Sec. 3.4): returns (updated copy, number of skipped ids);
+    ``inplace`` updates a C-contiguous float32 table itself."""
+    t = table if inplace else np.array(table, dtype=np.float32, order="C", copy=True)
+    assert t.dtype == np.float32 and t.flags.c_contiguous
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    rows = _f32(rows)
+    assert rows.shape == (ids.size, t.shape[1])
+    skipped = C.c_int(0)
+    f = lib().aifo_update_rows
+    f.restype = None
+    f(_p(t, C.c_float), C.c_int64(t.shape[0]), C.c_int(t.shape[1]), _p(ids, C.c_int32), _p(rows, C.c_float),
+      C.c_int(ids.size), C.byref(skipped))
+    return t, skipped.value
+
+
 def query(e, w_q, d_attn: int) -> np.ndarray:
     e = np.ascontiguousarray(e, dtype=np.float64)
     w_q = _f32(w_q)

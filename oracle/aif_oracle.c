@@ -60,6 +60,22 @@ int aifo_gather(const float *table, int64_t n_items, int d_item,
     return AIFO_OK;
 }
 
+/* Nearline maintenance of the index table (Sec. 3.4: the table of nearline results "supports both full and
+ * incremental updates").  Incremental update: row ids[i] of the table becomes rows[i, :], entries applied in
+ * order (a later entry for the same id replaces an earlier one); ids outside the table are skipped and
+ * counted in *n_skipped.  A full update is a new table: nothing to compute. */
+void aifo_update_rows(float *table, int64_t n_items, int d_item,
+                      const int32_t *ids, const float *rows, int n, int *n_skipped)
+{
+    int skipped = 0;
+    for (int i = 0; i < n; ++i) {
+        int64_t id = ids[i];
+        if (id < 0 || id >= n_items) { ++skipped; continue; }
+        for (int m = 0; m < d_item; ++m) table[(size_t)id * d_item + m] = rows[(size_t)i * d_item + m];
+    }
+    if (n_skipped) *n_skipped = skipped;
+}
+
 /* Step 2: q = W_q e (W_q is [d_attn, d_item], no bias; form of Eq. 1), or the
  * first d_attn coordinates of e when w_q is NULL. */
 void aifo_query(const double *e, const float *w_q, int d_item, int d_attn, double *q)

@@ -20,7 +20,7 @@ AIF_CROSS_NONE, AIF_CROSS_HADAMARD, AIF_CROSS_SEGDOT, AIF_CROSS_BEA = 0, 1, 2, 3
 
 EXPORTS = ("aif_score_init", "aif_score_request", "aif_score_batch", "aif_topk", "aif_score_destroy",
            "aif_last_error", "aif_poll_device_errors", "aif_peek_features", "aif_profile_begin",
-           "aif_profile_end", "aif_stage_kind")
+           "aif_profile_end", "aif_stage_kind", "aif_update_rows", "aif_swap_table")
 STAGES = ("gather", "user_fold", "attention", "mlp", "topk")
 LSH_EXPORTS = ("aif_lsh_init", "aif_lsh_batch", "aif_lsh_destroy", "aif_lsh_last_error",
                "aif_lsh_poll_device_errors", "aif_lsh_profile_begin", "aif_lsh_profile_end")
@@ -110,6 +110,10 @@ def load():
     lib.aif_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     lib.aif_stage_kind.restype = C.c_int32
     lib.aif_stage_kind.argtypes = [vp, C.c_int32]
+    lib.aif_update_rows.restype = C.c_int
+    lib.aif_update_rows.argtypes = [vp, vp, vp, C.c_int32, vp]
+    lib.aif_swap_table.restype = C.c_int
+    lib.aif_swap_table.argtypes = [vp, vp, C.c_int64]
     lib.aif_lsh_init.restype = C.c_int
     lib.aif_lsh_init.argtypes = [C.POINTER(aif_lsh_config), vp, C.POINTER(vp)]
     lib.aif_lsh_batch.restype = C.c_int
@@ -234,6 +238,13 @@ class Context:
         n = C.c_int32(0)
         self._check(self._lib.aif_poll_device_errors(self._h, C.byref(n)))
         return n.value
+
+    def aif_update_rows(self, ids, rows, n: Optional[int] = None):
+        self._check(self._lib.aif_update_rows(self._h, _ptr(ids), _ptr(rows), int(ids.numel()) if n is None else n, _stream()))
+
+    def aif_swap_table(self, new_table, n_items: Optional[int] = None):
+        self._check(self._lib.aif_swap_table(self._h, _ptr(new_table), int(new_table.shape[0]) if n_items is None else n_items))
+        self._keep = self._keep + (new_table,)     # the old table may still be read by enqueued work
 
     def aif_peek_features(self, request: int, first_row: int, n_rows: int, out_ptr: int):
         """Rows of the last batch's [e | attention | cross] matrix of one request into a host buffer."""

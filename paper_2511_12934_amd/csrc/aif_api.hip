@@ -435,6 +435,27 @@ aif_status aif_topk(aif_ctx *c, const float *const *logits, const int32_t *n_can
     return AIF_OK;
 }
 
+aif_status aif_update_rows(aif_ctx *c, const int32_t *ids, const void *rows, int32_t n, void *hip_stream)
+{
+    if (!c) return AIF_EINVAL;
+    if (n < 0 || (n > 0 && (!ids || !rows))) return fail(c, AIF_EINVAL, "NULL ids or rows, or negative n");
+    if ((uintptr_t)rows % 16 || (uintptr_t)ids % 4) return fail(c, AIF_EINVAL, "rows must be 16-byte aligned, ids 4-byte aligned");
+    aif_status st = check_device(c);
+    if (st != AIF_OK) return st;
+    HIP_TRY(c, launch_update_rows(c->m, const_cast<void *>(c->table), ids, rows, n, (int32_t *)c->bad.p, (hipStream_t)hip_stream));
+    return AIF_OK;
+}
+
+aif_status aif_swap_table(aif_ctx *c, const void *new_table, int64_t n_items)
+{
+    if (!c) return AIF_EINVAL;
+    if (!new_table || n_items <= 0) return fail(c, AIF_EINVAL, "NULL table or non-positive n_items");
+    if ((uintptr_t)new_table % 16) return fail(c, AIF_EINVAL, "item_table must be 16-byte aligned");
+    c->table = new_table;
+    c->m.n_items = n_items;
+    return AIF_OK;
+}
+
 aif_status aif_poll_device_errors(aif_ctx *c, int32_t *n_bad_ids)
 {
     if (!c) return AIF_EINVAL;

@@ -94,6 +94,10 @@ template <> __device__ __forceinline__ void st_f<uint16_t>(uint16_t *p, float v)
 hipError_t launch_gather(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad,
                          hipStream_t s);
 
+// Sec. 3.4, incremental update: table[ids[i]] = rows[i] in 16-byte pieces; bad ids write nothing and bump *bad.
+hipError_t launch_update_rows(const Model &m, void *table, const int32_t *ids, const void *rows, int n, int32_t *bad,
+                              hipStream_t s);
+
 // a2: per request, bias1[r, n] = b1[n] + sum_m W1[n, m] u[m] over the user columns (w1u: those columns
 // transposed, fp32 [d_user, H1]).
 hipError_t launch_user_fold(const Model &m, const Batch &b, const float *w1u, const float *b1,

@@ -41,4 +41,51 @@ hipError_t launch_gather(const Model &m, const Batch &b, const void *table, void
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Incremental update of the table (Sec. 3.4): the gather run backwards -- rows arrive contiguous and leave
+// for random rows of the table.  Same piece-per-lane layout, four pieces in flight per thread.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_update_rows(uint4 *__restrict__ table, int64_t n_items, int row_vec,
+                                                     const int32_t *__restrict__ ids, const uint4 *__restrict__ rows,
+                                                     int n, int32_t *__restrict__ bad)
+{
+    constexpr int U = 4;
+    const size_t total = (size_t)n * row_vec;
+    const size_t base = ((size_t)blockIdx.x * U) * 256 + threadIdx.x;
+    uint4 v[U];
+    int64_t id[U];
+    int piece[U];
+    int n_bad = 0;
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        const size_t idx = base + (size_t)j * 256;
+        const size_t row = idx / row_vec;
+        piece[j] = (int)(idx - row * row_vec);
+        id[j] = -1;
+        if (idx < total) {
+            id[j] = ids[row];
+            v[j] = rows[idx];
+            if (id[j] < 0 || id[j] >= n_items) {
+                id[j] = -1;
+                if (piece[j] == 0) ++n_bad;
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j)
+        if (id[j] >= 0) table[(size_t)id[j] * row_vec + piece[j]] = v[j];
+    if (n_bad) atomicAdd(bad, n_bad);
+}
+
+hipError_t launch_update_rows(const Model &m, void *table, const int32_t *ids, const void *rows, int n, int32_t *bad,
+                              hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    const int row_vec = m.d_item * (m.dtype == 0 ? 4 : 2) / 16;
+    const size_t total = (size_t)n * row_vec;
+    hipLaunchKernelGGL(k_update_rows, dim3((unsigned)((total + 1023) / 1024)), dim3(256), 0, s, (uint4 *)table, m.n_items,
+                       row_vec, ids, (const uint4 *)rows, n, bad);
+    return hipGetLastError();
+}
+
 }  // namespace aif

@@ -420,6 +420,72 @@ def test_bea_cross_on_the_mfma_kernels(R, torch, shape):
             assert_logits_close("bf16", zs[i], ref.logits, f"BEA {shape}")
 
 
+# ---------------------------------------------------------------------------
+# nearline maintenance of the item table (Sec. 3.4): incremental and full updates
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_incremental_table_update_is_exact_and_ordered_with_the_stream(R, torch, name):
+    """aif_update_rows against the oracle's update, bit for bit on the whole table; a scoring call enqueued before
+    the update reads the old rows and one enqueued after it the new ones, with no host synchronisation between."""
+    cfg = wl.CONFIGS[name].scaled(n_items=5000)
+    _say(f"{name} incremental update of 700 (+3 bad) of 5000 rows")
+    rng = np.random.default_rng(41)
+    model = wl.make_model(cfg)
+    table = wl.make_table_host(cfg, rng, n_items=5000)
+    u = wl.make_user(cfg, rng)
+    ids = wl.IdSampler(cfg, 5000).sample(rng, 600)
+    others = rng.permutation(np.setdiff1d(np.arange(5000, dtype=np.int32), ids))[:400]
+    upd_ids = np.concatenate([ids[:300], others]).astype(np.int32)      # distinct; half of the scored candidates change
+    upd_ids = np.concatenate([upd_ids, np.array([-1, 5000, 2 ** 30], np.int32)])
+    upd_rows = wl.round_storage(rng.standard_normal((703, cfg.d_item)).astype(np.float32) * 0.1, cfg.dtype)
+    new_table, skipped = oracle.update_rows(table, upd_ids, upd_rows)
+    assert skipped == 3
+
+    table_dev = R.to_device(table, cfg.dtype)
+    dm = R.DeviceModel(cfg, model)
+    ctx = R.make_context(cfg, dm, table_dev, max_users=1, max_candidates=600, max_seq_len=cfg.seq_len)
+    before, after = R.upload_request(cfg, u, ids), R.upload_request(cfg, u, ids)
+    di = torch.from_numpy(upd_ids).to("cuda:0")
+    dr = R.to_device(upd_rows, cfg.dtype)
+    ctx.aif_score_batch([before.req])
+    ctx.aif_update_rows(di, dr)
+    ctx.aif_score_batch([after.req])
+    torch.cuda.synchronize()
+    assert ctx.aif_poll_device_errors() == 3
+    assert np.array_equal(R.from_device_f32(table_dev), new_table), "table after the update"
+    z0, z1 = before.logits.cpu().numpy(), after.logits.cpu().numpy()
+    assert_logits_close(cfg.dtype, z0, oracle_scores(cfg, model, table, u, ids).logits, "before the update")
+    assert_logits_close(cfg.dtype, z1, oracle_scores(cfg, model, new_table, u, ids).logits, "after the update")
+    assert np.array_equal(z0[300:], z1[300:]) and not np.array_equal(z0[:300], z1[:300])
+    # empty update and host-side errors
+    ctx.aif_update_rows(di[:0], dr[:0])
+    from paper_2511_12934_amd import binding as B
+    with pytest.raises(B.AifError):
+        ctx.aif_update_rows(di, None)
+
+
+def test_full_table_update_swaps_the_table_for_later_calls(R, torch):
+    cfg = wl.CONFIGS["C2"].scaled(n_items=3000)
+    _say("C2 full update: swap to a table of another size")
+    rng = np.random.default_rng(43)
+    model = wl.make_model(cfg)
+    t0 = wl.make_table_host(cfg, rng, n_items=3000)
+    t1 = wl.make_table_host(cfg, rng, n_items=4000)
+    u = wl.make_user(cfg, rng)
+    ids = np.concatenate([wl.IdSampler(cfg, 3000).sample(rng, 400), np.array([3500], np.int32)])
+    d0, d1 = R.to_device(t0, "bf16"), R.to_device(t1, "bf16")
+    ctx = R.make_context(cfg, R.DeviceModel(cfg, model), d0, max_users=1, max_candidates=401, max_seq_len=cfg.seq_len)
+    a, b = R.upload_request(cfg, u, ids), R.upload_request(cfg, u, ids)
+    ctx.aif_score_batch([a.req])
+    ctx.aif_swap_table(d1)
+    ctx.aif_score_batch([b.req])
+    torch.cuda.synchronize()
+    za, zb = a.logits.cpu().numpy(), b.logits.cpu().numpy()
+    assert np.isnan(za[400]) and ctx.aif_poll_device_errors() == 1      # row 3500 exists in the new table only
+    assert_logits_close("bf16", za[:400], oracle_scores(cfg, model, t0, u, ids[:400]).logits, "old table")
+    assert_logits_close("bf16", zb, oracle_scores(cfg, model, t1, u, ids).logits, "new table")
+
+
 def test_large_scores_do_not_overflow(R, torch):
     """|score| far beyond the fp32 exp range: softmax must subtract its maximum."""
     cfg = small_cfg("f32", d_item=32, d_user=32, d_attn=32, seq_len=33, mlp_dims=(128, 16, 1))

@@ -69,6 +69,30 @@ def tiny_cfg(**kw):
     return c
 
 
+# ------------------------------------------------- nearline table update
+def test_update_rows_is_an_indexed_assignment_that_skips_bad_ids():
+    rng = RNG(12)
+    t = rng.standard_normal((50, 6)).astype(np.float32)
+    ids = rng.permutation(50)[:20].astype(np.int32)
+    rows = rng.standard_normal((20, 6)).astype(np.float32)
+    got, skipped = oracle.update_rows(t, ids, rows)
+    ref = t.copy()
+    ref[ids] = rows                                      # NumPy's own indexed assignment (distinct ids)
+    assert skipped == 0 and np.array_equal(got, ref)
+    untouched = np.setdiff1d(np.arange(50), ids)
+    assert np.array_equal(got[untouched], t[untouched]) and not np.array_equal(got[ids], t[ids])
+    # ids outside the table are skipped and counted; a later entry for an id replaces an earlier one
+    ids2 = np.array([3, -1, 50, 3, 7], np.int32)
+    rows2 = np.arange(30, dtype=np.float32).reshape(5, 6)
+    got2, skipped2 = oracle.update_rows(t, ids2, rows2)
+    assert skipped2 == 2
+    assert np.array_equal(got2[3], rows2[3]) and np.array_equal(got2[7], rows2[4])
+    rest = np.setdiff1d(np.arange(50), [3, 7])
+    assert np.array_equal(got2[rest], t[rest])
+    # scoring reads the updated row
+    assert np.array_equal(oracle.gather(got2, np.array([7], np.int32))[0], rows2[4].astype(np.float64))
+
+
 # ------------------------------------------------------------------ gather
 def test_gather_is_row_copy_and_rejects_bad_ids():
     rng = RNG(1)
