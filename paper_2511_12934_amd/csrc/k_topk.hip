@@ -11,6 +11,18 @@
 // prefix count over contiguous position chunks), and a bitonic sort of the
 // <= 4096 selected (key, ~position) pairs in LDS orders them: key descending,
 // lower position first.  The result is a pure function of the logits.
+//
+// Before that, a shortcut that usually settles the request in one counting pass
+// (requests of at most 16 K candidates): the logits are counted into 2048 bins
+// that are equal intervals of [min, max] of the request's finite logits -- a
+// monotone map, so every candidate of a higher bin beats every candidate of a
+// lower one and equal logits share a bin.  The bin b* that holds the k-th best
+// is read off the suffix sums; the candidates of the bins >= b* (k plus a
+// handful when the logits are spread out) are collected and each finds its rank
+// among them by counting, on the same (key, ~position) pairs as the sort.  When
+// those bins hold more than 1024 candidates (logits piled on one value) or the
+// request has no two distinct finite logits, the radix passes take over.  Both
+// routes give the same result: the exact top k in the order stated above.
 #include "aif_dev.h"
 
 namespace aif {
@@ -45,6 +57,23 @@ __device__ __forceinline__ uint32_t logit_key(float z)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+__device__ __forceinline__ float key_logit(uint32_t key)      // inverse of logit_key (key 0 gives a NaN)
+{
+    return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
+}
+
+constexpr int TKF_BINS = 2048;              // two per thread
+constexpr int TKF_SELMAX = 1024;            // candidates the shortcut may have to rank
+
+__device__ __forceinline__ int value_bin(uint32_t key, float lo, float scale)
+{
+    const float v = key_logit(key);
+    if (key == 0u || v == -INFINITY) return 0;                  // NaN and -inf: lowest bin (the key orders them inside it)
+    if (v == INFINITY) return TKF_BINS - 1;
+    const int b = (int)((v - lo) * scale);
+    return b < TKF_BINS - 1 ? b : TKF_BINS - 1;
+}
+
 __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict__ descs, int k, int kpad,
                                                      int32_t *__restrict__ idx_out, float *__restrict__ val_out)
 {
@@ -52,6 +81,9 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
     __shared__ uint32_t hist[256];
     __shared__ uint32_t wave_cnt[TK_THREADS / 64];
     __shared__ uint32_t s_prefix[2], s_remaining[2], s_ngreater, s_key_count;   // [pass parity]
+    __shared__ uint32_t fhist[TKF_BINS];
+    __shared__ float s_lo[TK_THREADS / 64], s_hi[TK_THREADS / 64];
+    __shared__ uint32_t s_bstar, s_total, s_cnt;
 
     const int r = blockIdx.x;
     const float *z = descs[r].logits;
@@ -78,6 +110,90 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
         const int i = tid + j * TK_THREADS;
         kreg[j] = i < n ? logit_key(z[i]) : 0u;
     }
+    // ---- shortcut: one counting pass over value bins -------------------------------------------------
+    if (n <= TK_CACHED * TK_THREADS) {
+        float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < TK_CACHED; ++j) {
+            const float v = key_logit(kreg[j]);
+            if (tid + j * TK_THREADS < n && fabsf(v) < INFINITY) {      // finite (a NaN compares false)
+                lo = fminf(lo, v);
+                hi = fmaxf(hi, v);
+            }
+        }
+#pragma unroll
+        for (int o = 32; o; o >>= 1) {
+            lo = fminf(lo, __shfl_xor(lo, o, 64));
+            hi = fmaxf(hi, __shfl_xor(hi, o, 64));
+        }
+        if ((tid & 63) == 0) {
+            s_lo[tid >> 6] = lo;
+            s_hi[tid >> 6] = hi;
+        }
+        fhist[tid] = 0;
+        fhist[tid + TK_THREADS] = 0;
+        if (tid == 0) s_cnt = 0;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < TK_THREADS / 64; ++w) {
+            lo = fminf(lo, s_lo[w]);
+            hi = fmaxf(hi, s_hi[w]);
+        }
+        const float scale = (float)TKF_BINS / (hi - lo);
+        if (hi > lo && scale < INFINITY) {                              // the same decision in every thread
+#pragma unroll
+            for (int j = 0; j < TK_CACHED; ++j)
+                if (tid + j * TK_THREADS < n) atomicAdd(&fhist[value_bin(kreg[j], lo, scale)], 1u);
+            __syncthreads();
+            // suffix sums over the bins, two bins a thread: S[b] = candidates in bins >= b
+            const uint32_t h0 = fhist[2 * tid], h1 = fhist[2 * tid + 1];
+            uint32_t sfx = h0 + h1;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t v = __shfl_down(sfx, o, 64);
+                if ((tid & 63) + o < 64) sfx += v;
+            }
+            if ((tid & 63) == 0) wave_cnt[tid >> 6] = sfx;
+            __syncthreads();
+            uint32_t s_even = sfx;                                      // S[2 tid]
+            for (int w = (tid >> 6) + 1; w < TK_THREADS / 64; ++w) s_even += wave_cnt[w];
+            const uint32_t s_odd = s_even - h0;                         // S[2 tid + 1]
+            if (s_even >= (uint32_t)kk && s_odd < (uint32_t)kk) {
+                s_bstar = 2 * tid;
+                s_total = s_even;
+            }
+            if (s_odd >= (uint32_t)kk && s_odd - h1 < (uint32_t)kk) {
+                s_bstar = 2 * tid + 1;
+                s_total = s_odd;
+            }
+            __syncthreads();
+            const uint32_t total = s_total;
+            if (total <= (uint32_t)TKF_SELMAX) {
+                const int bstar = (int)s_bstar;
+#pragma unroll
+                for (int j = 0; j < TK_CACHED; ++j) {
+                    const int i = tid + j * TK_THREADS;
+                    if (i < n && value_bin(kreg[j], lo, scale) >= bstar)
+                        sel[atomicAdd(&s_cnt, 1u)] = ((unsigned long long)kreg[j] << 32) | (0xFFFFFFFFu - (uint32_t)i);
+                }
+                __syncthreads();
+                // rank by counting: the pairs are distinct, so the ranks are a permutation
+                if ((uint32_t)tid < total) {
+                    const unsigned long long mine = sel[tid];
+                    uint32_t rank = 0;
+                    for (uint32_t j = 0; j < total; ++j) rank += sel[j] > mine ? 1u : 0u;
+                    if (rank < (uint32_t)kk) {
+                        const uint32_t i = 0xFFFFFFFFu - (uint32_t)(mine & 0xFFFFFFFFull);
+                        idx_o[rank] = (int32_t)i;
+                        val_o[rank] = z[i];
+                    }
+                }
+                return;
+            }
+        }
+    }
+
+    // ---- radix select -----------------------------------------------------------------------------------
     __syncthreads();
     uint32_t mask = 0;
     int par = 0;
@@ -239,7 +355,8 @@ hipError_t launch_topk(const TopkDesc *descs, int n_req, int k, int32_t *idx_out
     if (n_req == 0) return hipSuccess;
     int kpad = 2;
     while (kpad < k) kpad <<= 1;
-    hipLaunchKernelGGL(k_topk, dim3(n_req), dim3(TK_THREADS), (size_t)kpad * 8, s, descs, k, kpad, idx_out, val_out);
+    const int sel_slots = kpad > TKF_SELMAX ? kpad : TKF_SELMAX;
+    hipLaunchKernelGGL(k_topk, dim3(n_req), dim3(TK_THREADS), (size_t)sel_slots * 8, s, descs, k, kpad, idx_out, val_out);
     return hipGetLastError();
 }
 

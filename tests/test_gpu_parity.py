@@ -524,6 +524,17 @@ def _topk_cases(rng):
     cases["all_nan"] = np.full(300, np.nan, np.float32)
     cases["tiny"] = np.array([1.0, 2.0, 2.0], np.float32)
     cases["big"] = rng.standard_normal(20_000).astype(np.float32)
+    # aimed at the value-bin shortcut: ties straddling the cut inside one bin, an outlier that squeezes every other
+    # logit into one bin, fewer candidates than k, only two distinct values, huge range
+    cases["coarse"] = np.round(z, 3)
+    o = z.copy()
+    o[4321] = 1e6
+    cases["outlier"] = o
+    cases["few"] = rng.standard_normal(700).astype(np.float32)
+    cases["two_values"] = np.where(rng.random(n) < 0.01, 1.0, -1.0).astype(np.float32)
+    h = z.copy()
+    h[[1, 2]] = [3e38, -3e38]
+    cases["huge_range"] = h
     return cases
 
 
