@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the real-time pre-ranking scoring path on one MI355X.
 
-A step is one pass of the whole hot path -- aif_score_batch (gather -> user
-fold -> attention + cross -> MLP) followed by aif_topk -- over one batch of
+A step is one pass of the whole hot path -- aif_score_topk = aif_score_batch
+(gather -> user fold -> attention + cross -> MLP) followed by aif_topk -- over one batch of
 synthetic requests already resident in HBM.  Default workload: configuration
 C3 (64 concurrent users x 10^4 candidates, bf16), the batched 10^4-candidate
 request shape the metric is quoted on.  Prints ONE JSON line.
@@ -136,8 +136,11 @@ def single_request_latency(n_iter=200):
             reqs = [d.req for d in w.launch[u * per_user:(u + 1) * per_user]]
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            w.ctx.aif_score_batch(reqs)
-            w.ctx.aif_topk([w.dev[u].logits], cfg.top_k, idx, val)
+            if mb is None:
+                w.ctx.aif_score_topk(reqs, cfg.top_k, idx, val)
+            else:
+                w.ctx.aif_score_batch(reqs)
+                w.ctx.aif_topk([w.dev[u].logits], cfg.top_k, idx, val)
             torch.cuda.synchronize()
             if it >= 20:
                 ts.append((time.perf_counter() - t0) * 1e3)

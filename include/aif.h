@@ -146,6 +146,14 @@ AIF_API aif_status aif_score_batch(aif_ctx *ctx, const aif_request *reqs, int32_
 AIF_API aif_status aif_topk(aif_ctx *ctx, const float *const *logits, const int32_t *n_cand, int32_t n_req,
                     int32_t k, int32_t *idx_out, float *val_out, void *hip_stream);
 
+/* aif_score_batch followed by aif_topk over the same requests (Sec. 1: the purpose of the stage is the cut
+ * from about 10^4 to about 10^2), as one call: request r's k best positions go to idx_out / val_out
+ * [r * k, (r + 1) * k) (DEVICE), exactly as aif_topk would leave them from logits_out of request r.  One
+ * descriptor upload instead of two: the shortest path for a single request.  For a candidate list cut into
+ * mini-batch slices use aif_score_batch and one aif_topk over the whole list.  Errors as the two calls. */
+AIF_API aif_status aif_score_topk(aif_ctx *ctx, const aif_request *reqs, int32_t n_req, int32_t k, int32_t *idx_out,
+                                  float *val_out, void *hip_stream);
+
 /* Nearline maintenance of the item table (Sec. 3.4: the index table of nearline results "supports both full
  * and incremental updates").
  *

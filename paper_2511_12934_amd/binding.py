@@ -20,7 +20,7 @@ AIF_CROSS_NONE, AIF_CROSS_HADAMARD, AIF_CROSS_SEGDOT, AIF_CROSS_BEA = 0, 1, 2, 3
 
 EXPORTS = ("aif_score_init", "aif_score_request", "aif_score_batch", "aif_topk", "aif_score_destroy",
            "aif_last_error", "aif_poll_device_errors", "aif_peek_features", "aif_profile_begin",
-           "aif_profile_end", "aif_stage_kind", "aif_update_rows", "aif_swap_table")
+           "aif_profile_end", "aif_stage_kind", "aif_update_rows", "aif_swap_table", "aif_score_topk")
 STAGES = ("gather", "user_fold", "attention", "mlp", "topk")
 LSH_EXPORTS = ("aif_lsh_init", "aif_lsh_batch", "aif_lsh_destroy", "aif_lsh_last_error",
                "aif_lsh_poll_device_errors", "aif_lsh_profile_begin", "aif_lsh_profile_end")
@@ -110,6 +110,8 @@ def load():
     lib.aif_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     lib.aif_stage_kind.restype = C.c_int32
     lib.aif_stage_kind.argtypes = [vp, C.c_int32]
+    lib.aif_score_topk.restype = C.c_int
+    lib.aif_score_topk.argtypes = [vp, C.POINTER(aif_request), C.c_int32, C.c_int32, vp, vp, vp]
     lib.aif_update_rows.restype = C.c_int
     lib.aif_update_rows.argtypes = [vp, vp, vp, C.c_int32, vp]
     lib.aif_swap_table.restype = C.c_int
@@ -227,6 +229,10 @@ class Context:
     def aif_score_batch(self, reqs: Sequence[Request], packed=None):
         arr = pack_requests(reqs) if packed is None else packed
         self._check(self._lib.aif_score_batch(self._h, arr, len(reqs), _stream()))
+
+    def aif_score_topk(self, reqs: Sequence[Request], k: int, idx_out, val_out, packed=None):
+        arr = pack_requests(reqs) if packed is None else packed
+        self._check(self._lib.aif_score_topk(self._h, arr, len(reqs), k, _ptr(idx_out), _ptr(val_out), _stream()))
 
     def aif_topk(self, logits: Sequence, k: int, idx_out, val_out, n_cand: Optional[Sequence[int]] = None):
         n = len(logits)

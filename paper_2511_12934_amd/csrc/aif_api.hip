@@ -253,8 +253,7 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
         HIP_TRY(nullptr, hipGetDeviceProperties(&prop, dev));
         c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     }
-    const size_t tk = (size_t)c->max_users * sizeof(TopkDesc);
-    if (tk > sb) sb = tk;
+    sb += (size_t)c->max_users * sizeof(TopkDesc) + 16;     // aif_score_topk stages both tables in one slot
     c->slot_bytes = (sb + 255) / 256 * 256;
     HIP_TRY(nullptr, hipHostMalloc((void **)&c->h_stage, c->slot_bytes * NSLOT, hipHostMallocDefault));
     HIP_TRY(nullptr, c->d_stage.alloc(c->slot_bytes * NSLOT));
@@ -285,10 +284,14 @@ void aif_score_destroy(aif_ctx *ctx) { destroy(ctx); }
 
 const char *aif_last_error(const aif_ctx *ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
 
-aif_status aif_score_batch(aif_ctx *c, const aif_request *reqs, int32_t n_req, void *hip_stream)
+// Score n_req requests; with k > 0 also select each request's k best (one staging copy, one more launch).
+static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req, int32_t k, int32_t *idx_out,
+                             float *val_out, void *hip_stream)
 {
     if (!c) return AIF_EINVAL;
     if (n_req < 0 || (n_req > 0 && !reqs)) return fail(c, AIF_EINVAL, "NULL request array or negative n_req");
+    if (k > 0 && n_req > 0 && (!idx_out || !val_out)) return fail(c, AIF_EINVAL, "NULL idx_out or val_out");
+    if (k > TOPK_MAX) return fail(c, AIF_ERANGE, "k %d exceeds %d", k, TOPK_MAX);
     if (n_req > c->max_users) return fail(c, AIF_ERANGE, "n_req %d exceeds max_users %d", n_req, c->max_users);
     const Model &m = c->m;
     for (int r = 0; r < n_req; ++r) {
@@ -348,7 +351,16 @@ aif_status aif_score_batch(aif_ctx *c, const aif_request *reqs, int32_t n_req, v
     const size_t goff = ((size_t)n_req * sizeof(ReqDesc) + (size_t)b.n_blk * sizeof(int32_t) + 15) / 16 * 16;
     b.n_groups = c->mfma.attn ? attn_plan_groups(m, hd, n_req, c->n_cu, (AttnGroup *)(h + goff)) : 0;
     b.groups = (const AttnGroup *)(d + goff);
-    const size_t bytes = goff + (size_t)b.n_groups * sizeof(AttnGroup);
+    size_t bytes = goff + (size_t)b.n_groups * sizeof(AttnGroup);
+    const size_t toff = (bytes + 15) / 16 * 16;
+    if (k > 0) {
+        TopkDesc *ht = (TopkDesc *)(h + toff);
+        for (int r = 0; r < n_req; ++r) {
+            ht[r].logits = reqs[r].logits_out;
+            ht[r].n = reqs[r].n_cand;
+        }
+        bytes = toff + (size_t)n_req * sizeof(TopkDesc);
+    }
     HIP_TRY(c, hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, s));
 
     hipEvent_t *pe = nullptr;
@@ -386,9 +398,29 @@ aif_status aif_score_batch(aif_ctx *c, const aif_request *reqs, int32_t n_req, v
         HIP_TRY(c, launch_mlp_generic(m, b, c->X.p, gw, (const float *)c->bias1.p, s));
     }
     if (pe) HIP_TRY(c, hipEventRecord(pe[4], s));
+    if (k > 0) {
+        hipEvent_t *pt = nullptr;
+        if (c->prof_on && c->prof_topk_calls < c->prof_max) pt = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
+        if (pt) HIP_TRY(c, hipEventRecord(pt[0], s));
+        HIP_TRY(c, launch_topk((const TopkDesc *)(d + toff), n_req, k, idx_out, val_out, s));
+        if (pt) HIP_TRY(c, hipEventRecord(pt[1], s));
+    }
     HIP_TRY(c, hipEventRecord(c->ev[slot], s));
     c->ev_live[slot] = true;
     return AIF_OK;
+}
+
+aif_status aif_score_batch(aif_ctx *c, const aif_request *reqs, int32_t n_req, void *hip_stream)
+{
+    return score_impl(c, reqs, n_req, 0, nullptr, nullptr, hip_stream);
+}
+
+aif_status aif_score_topk(aif_ctx *c, const aif_request *reqs, int32_t n_req, int32_t k, int32_t *idx_out,
+                          float *val_out, void *hip_stream)
+{
+    if (!c) return AIF_EINVAL;
+    if (k <= 0) return fail(c, AIF_EINVAL, "k must be positive");
+    return score_impl(c, reqs, n_req, k, idx_out, val_out, hip_stream);
 }
 
 aif_status aif_score_request(aif_ctx *ctx, const aif_request *req, void *hip_stream)

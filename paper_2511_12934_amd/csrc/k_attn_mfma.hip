@@ -644,13 +644,32 @@ static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char
     return hipGetLastError();
 }
 
+// A batch too small to give every compute unit an eight-wave block of the streaming kernel (a single
+// 10^4-candidate request is 40 of them) is cut into two-wave blocks instead: same arithmetic per candidate,
+// four times as many compute units at work.
+static bool small_batch(const Batch &b)
+{
+    static int n_cu = 0;
+    if (!n_cu) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        n_cu = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+                   ? prop.multiProcessorCount : 256;
+    }
+    return b.n_blk < n_cu;
+}
+
 hipError_t launch_attn_variant(int variant, const Model &m, const Batch &b, void *X, char *kvpack, size_t stride,
                                float *kmax, int nktp, bool kv_packed, hipStream_t s)
 {
     if (b.n_blk == 0) return hipSuccess;
     switch (variant) {
-    case 0: return launch_attn_spec<64, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s);
-    case 1: return launch_attn_spec<32, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s);
+    case 0:
+        return small_batch(b) ? launch_attn_spec<64, 2>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s)
+                              : launch_attn_spec<64, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s);
+    case 1:
+        return small_batch(b) ? launch_attn_spec<32, 2>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s)
+                              : launch_attn_spec<32, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -97,7 +97,8 @@ def peek_features(ctx: B.Context, cfg: wl.Config, req_index: int, n_rows: int) -
 
 class Workload:
     """One configuration resident on the device, in the launch configuration the
-    benchmark times: ``step()`` = aif_score_batch over all users + aif_topk.
+    benchmark times: ``step()`` = aif_score_topk over all users (aif_score_batch + aif_topk when the
+    requests are cut into mini-batches).
 
     With ``n_sets`` > 1 the same users arrive with ``n_sets`` different candidate
     lists and ``step()`` takes them in turn, so that consecutive steps do not
@@ -149,6 +150,7 @@ class Workload:
                                          d.keep + (idt,)))
             self.sets.append((lst, B.pack_requests([x.req for x in lst])))
         self._turn = 0
+        self.whole_requests = not minibatch
         self.k = cfg.top_k
         self.idx = torch.empty((self.n_users, self.k), dtype=torch.int32, device=device)
         self.val = torch.empty((self.n_users, self.k), dtype=torch.float32, device=device)
@@ -161,8 +163,11 @@ class Workload:
     def step(self):
         launch, packed = self.sets[self._turn % len(self.sets)]
         self._turn += 1
-        self.ctx.aif_score_batch(launch, packed=packed)
-        self.ctx.aif_topk(self._logits, self.k, self.idx, self.val)
+        if self.whole_requests:             # one request per user: scoring and selection as one call
+            self.ctx.aif_score_topk(launch, self.k, self.idx, self.val, packed=packed)
+        else:                               # mini-batch slices: one selection over each user's whole list
+            self.ctx.aif_score_batch(launch, packed=packed)
+            self.ctx.aif_topk(self._logits, self.k, self.idx, self.val)
 
     def rows_of(self, user: int, positions: np.ndarray) -> np.ndarray:
         """Item rows of some candidates of a user, fetched with torch indexing (not the library)."""

@@ -571,6 +571,40 @@ def test_topk_equals_full_stable_sort(R, torch, k):
         assert np.array_equal(v2.cpu().numpy()[0].astype(np.float64), ov)
 
 
+def test_score_topk_is_score_batch_followed_by_topk(R, torch):
+    """The one-call form leaves exactly what the two calls leave: logits and selections, bit for bit, for ragged
+    requests including one shorter than k and an empty one."""
+    cfg = wl.CONFIGS["C2"].scaled(n_items=4000)
+    _say("aif_score_topk vs aif_score_batch + aif_topk")
+    rng = np.random.default_rng(47)
+    model = wl.make_model(cfg)
+    table_dev = R.to_device(wl.make_table_host(cfg, rng, n_items=4000), "bf16")
+    sampler = wl.IdSampler(cfg, 4000)
+    sizes = (1500, 37, 0, 700)
+    users = [wl.make_user(cfg, rng) for _ in sizes]
+    k = 200
+    dm = R.DeviceModel(cfg, model)
+    outs = []
+    for fused in (False, True):
+        ctx = R.make_context(cfg, dm, table_dev, max_users=len(sizes), max_candidates=max(sizes), max_seq_len=cfg.seq_len)
+        drs = [R.upload_request(cfg, u, sampler.sample(np.random.default_rng(100 + i), n)) for i, (u, n) in enumerate(zip(users, sizes))]
+        idx = torch.full((len(sizes), k), -7, dtype=torch.int32, device="cuda")
+        val = torch.full((len(sizes), k), -7.0, dtype=torch.float32, device="cuda")
+        if fused:
+            ctx.aif_score_topk([d.req for d in drs], k, idx, val)
+        else:
+            ctx.aif_score_batch([d.req for d in drs])
+            ctx.aif_topk([d.logits for d in drs], k, idx, val)
+        torch.cuda.synchronize()
+        outs.append(([d.logits.cpu().numpy() for d in drs], idx.cpu().numpy(), val.cpu().numpy()))
+    for a, b in zip(outs[0][0], outs[1][0]):
+        assert np.array_equal(a, b)
+    assert np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][2], outs[1][2])
+    for r, n in enumerate(sizes):
+        oi, _ = oracle.topk(outs[1][0][r].astype(np.float64), k)
+        assert np.array_equal(outs[1][1][r], oi)
+
+
 # ---------------------------------------------------------------------------
 # duplicates, bad ids, host-side errors
 # ---------------------------------------------------------------------------
