@@ -224,7 +224,8 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
         HIP_TRY(nullptr, c->wq.alloc((size_t)m.d_attn * m.d_item * 4));
         HIP_TRY(nullptr, launch_to_f32(m.dtype, wts->w_q, m.d_attn, m.d_item, m.d_item, 0, (float *)c->wq.p, s));
     }
-    HIP_TRY(nullptr, mfma_plan(m, c->max_seq_len, c->max_users, wts->w_q, wts->w, c->mfma, s));
+    c->x_rows = (size_t)c->max_users * round_up(c->max_candidates, ROW_BLOCK);
+    HIP_TRY(nullptr, mfma_plan(m, c->max_seq_len, c->max_users, c->x_rows, wts->w_q, wts->w, c->mfma, s));
     // both consumers of the workspace read MFMA fragments: keep it in fragment order (x_offset)
     {
         const char *rm = getenv("AIF_X_ROW_MAJOR");      // testing: the MFMA kernels on the row-major layout

@@ -155,7 +155,7 @@ aif_status uinit(const aif_user_config *cfg, const aif_user_weights *wts, aif_us
 
     // the attention kernels: MFMA when the shape is one they serve, else the shape-agnostic one
     const void *no_w[1] = {nullptr};
-    USER_TRY(nullptr, mfma_plan(m, c->max_seq_len, c->max_users, nullptr, no_w, c->mfma, s));
+    USER_TRY(nullptr, mfma_plan(m, c->max_seq_len, c->max_users, 0, nullptr, no_w, c->mfma, s));
     if (!c->mfma.attn && attn_generic_lds_bytes(m, c->max_seq_len) > 160 * 1024)
         return ufail(nullptr, AIF_ESHAPE, "max_seq_len %d needs more LDS than a compute unit has", c->max_seq_len);
 

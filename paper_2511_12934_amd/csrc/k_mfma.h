@@ -16,7 +16,9 @@ struct MfmaPlan {
     float *kmax = nullptr;             // per request, head and 64-key stage: max |k_t| (owned workspace)
     size_t pack_stride = 0;            // bytes of kvpack per request
     int nktp = 0;                      // key tiles per head the pack layout is sized for
+    char *hbuf[2] = {};                // layered MLP: hidden activations between launches, ping-pong (owned workspace)
 };
+constexpr int MLP_VARIANT_LAYERS = 100;   // mlp_variant of the one-launch-per-layer path (k_mlp_layers.hip)
 
 struct MlpPack {
     const char *w[3];                  // hidden layers' weights in fragment order
@@ -27,7 +29,7 @@ struct MlpPack {
 
 // Decide which MFMA kernels can serve the model and pack their weights
 // (w_q, w: the caller's device tensors, read here only).
-hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, const void *w_q, const void *const *w,
+hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, size_t x_rows, const void *w_q, const void *const *w,
                      MfmaPlan &plan, hipStream_t s);
 void mfma_release(MfmaPlan &plan);
 
@@ -55,6 +57,12 @@ int mlp_mfma_variant(const Model &m);
 hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const void *X, const MlpPack &pk,
                               const float *bias1, hipStream_t s);
 hipError_t pack_frag(const void *W, int n_in, int col0, int N, int K, bool from_mfma, void *dst, hipStream_t s);
+
+// k_mlp_layers.hip: wide heads, one launch per layer
+bool mlp_layers_ok(const Model &m);
+size_t mlp_layers_buf_bytes(const Model &m, size_t x_rows, int which);
+hipError_t launch_mlp_layers(const Model &m, const Batch &b, const void *X, const MlpPack &pk, const float *bias1,
+                             char *const *hbuf, hipStream_t s);
 
 // k_attn_mfma.hip
 int attn_mfma_variant(const Model &m, bool has_wq);

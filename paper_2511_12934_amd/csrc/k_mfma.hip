@@ -5,7 +5,7 @@
 
 namespace aif {
 
-hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, const void *w_q, const void *const *w,
+hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, size_t x_rows, const void *w_q, const void *const *w,
                      MfmaPlan &plan, hipStream_t s)
 {
     plan.attn = false;
@@ -24,6 +24,15 @@ hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, const void 
     }
 
     plan.mlp_variant = mlp_mfma_variant(m);
+    if (plan.mlp_variant < 0 && mlp_layers_ok(m)) {
+        plan.mlp_variant = MLP_VARIANT_LAYERS;
+        for (int i = 0; i < 2; ++i) {
+            const size_t bytes = mlp_layers_buf_bytes(m, x_rows, i);
+            if (!bytes) continue;
+            hipError_t e = hipMalloc((void **)&plan.hbuf[i], bytes);
+            if (e != hipSuccess) return e;
+        }
+    }
     if (plan.mlp_variant >= 0) {
         const int nh = m.n_layers - 1;
         for (int l = 0; l < nh; ++l) {
@@ -58,6 +67,10 @@ void mfma_release(MfmaPlan &plan)
     plan.kvpack = nullptr;
     if (plan.kmax) (void)hipFree(plan.kmax);
     plan.kmax = nullptr;
+    for (auto &p : plan.hbuf) {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+    }
 }
 
 hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s)
@@ -76,6 +89,7 @@ hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const 
     }
     pk.wlast = wlast_f32;
     pk.blast = bias_f32[m.n_layers - 1];
+    if (plan.mlp_variant == MLP_VARIANT_LAYERS) return launch_mlp_layers(m, b, X, pk, bias1, plan.hbuf, s);
     return launch_mlp_variant(plan.mlp_variant, m, b, X, pk, bias1, s);
 }
 

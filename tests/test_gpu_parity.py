@@ -421,6 +421,37 @@ def test_bea_cross_on_the_mfma_kernels(R, torch, shape):
 
 
 # ---------------------------------------------------------------------------
+# wide heads: the MLP one launch per layer
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("shape", ["two_hidden_tiled", "three_hidden_tiled", "row_major_after_generic_attention"])
+def test_layered_mlp_for_wide_heads(R, torch, shape):
+    """Hidden widths that are multiples of 256 and not one of the fused chains: layer by layer through HBM in
+    fragment order.  Ragged requests, non-zero biases, both workspace layouts."""
+    base = wl.CONFIGS["C3"].scaled(n_items=3000)
+    if shape == "two_hidden_tiled":
+        cfg = base.scaled(mlp_dims=(256, 256, 256, 1))
+    elif shape == "three_hidden_tiled":
+        cfg = base.scaled(mlp_dims=(256, 512, 256, 256, 1))
+    else:
+        cfg = base.scaled(mlp_dims=(256, 768, 256, 1), use_wq=True)
+    _say(f"layered MLP {shape} {cfg.mlp_dims}")
+    rng = np.random.default_rng(53)
+    model = wl.make_model(cfg, bias_scale=0.05)
+    table = wl.make_table_host(cfg, rng, n_items=3000)
+    sampler = wl.IdSampler(cfg, 3000)
+    reqs = [(wl.make_user(cfg, rng), sampler.sample(rng, n)) for n in (300, 1, 257, 600)]
+    zs, _, _, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), reqs)
+    assert ctx.aif_stage_kind("mlp") == 1
+    assert ctx.aif_stage_kind("attention") == (0 if cfg.use_wq else 1)
+    for i, (u, ids) in enumerate(reqs):
+        assert_logits_close("bf16", zs[i], oracle_scores(cfg, model, table, u, ids).logits, f"layered {shape} request {i}")
+    # slices of a request give the same bits as the whole
+    u, ids = reqs[3]
+    parts, _, _, _ = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), [(u, ids[:256]), (u, ids[256:])])
+    assert np.array_equal(np.concatenate(parts), zs[3])
+
+
+# ---------------------------------------------------------------------------
 # nearline maintenance of the item table (Sec. 3.4): incremental and full updates
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("name", ["C1", "C2"])
