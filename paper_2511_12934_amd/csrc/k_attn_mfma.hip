@@ -575,6 +575,7 @@ size_t attn_max_groups(size_t x_rows, int max_users) { return x_rows / (32 * RES
 int attn_plan_groups(const Model &m, const ReqDesc *reqs, int n_req, int n_cu, AttnGroup *out)
 {
     if (m.n_heads > RES_MAX_HEADS || m.d_item / 8 > RES_MAX_ITEM_PIECES) return 0;
+    if (m.d_head != 64 && m.d_head != 32) return 0;       // the resident kernel has these two head widths
     const int FR = m.d_head / 8;
     long total = 0;
     for (int r = 0; r < n_req; ++r) {
@@ -600,6 +601,7 @@ int attn_plan_groups(const Model &m, const ReqDesc *reqs, int n_req, int n_cu, A
 // ---- dispatch -----------------------------------------------------------------
 int attn_mfma_variant(const Model &m, bool has_wq)
 {
+    if (attn_proj_ok(m, has_wq)) return ATTN_VARIANT_PROJ;
     if (m.dtype != 1 || has_wq) return -1;
     if (m.cross_mode == 3) {
         // BEA on the matrix cores: whole 32-feature tiles, the window inside the row, fragments within budget
@@ -614,6 +616,7 @@ int attn_mfma_variant(const Model &m, bool has_wq)
 
 size_t attn_pack_stride(const Model &m, int max_seq_len, int *nktp_out)
 {
+    if (m.d_head == 16) return attn_proj_pack_stride(m, max_seq_len, nktp_out);
     const int nktp = ((((max_seq_len + 31) >> 5) + 1) & ~1);
     if (nktp_out) *nktp_out = nktp;
     return (size_t)m.n_heads * nktp * (m.d_head / 8) * 1024;
@@ -659,11 +662,15 @@ static bool small_batch(const Batch &b)
     return b.n_blk < n_cu;
 }
 
-hipError_t launch_attn_variant(int variant, const Model &m, const Batch &b, void *X, char *kvpack, size_t stride,
-                               float *kmax, int nktp, bool kv_packed, hipStream_t s)
+hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s)
 {
     if (b.n_blk == 0) return hipSuccess;
-    switch (variant) {
+    char *kvpack = plan.kvpack;
+    float *kmax = plan.kmax;
+    const size_t stride = plan.pack_stride;
+    const int nktp = plan.nktp;
+    switch (plan.attn_variant) {
+    case ATTN_VARIANT_PROJ: return launch_attn_proj(m, b, X, plan, small_batch(b), s);
     case 0:
         return small_batch(b) ? launch_attn_spec<64, 2>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s)
                               : launch_attn_spec<64, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s);

@@ -1,0 +1,428 @@
+// a3-a5 on the matrix cores for models with a query projection and 16-wide
+// heads -- q = W_q e (the reading of Eq. 1's projection for the candidate
+// side), target attention of every candidate over the request's behaviour
+// sequence, Softmax(q K^T / sqrt(d_h)) V per head (operator of Eq. 3 with the
+// candidate as the query), and the real-time half of the cross features
+// (Sec. 3.3): Hadamard, or the dot products of the request's cross vectors
+// with the segments of the item vector.
+//
+// As in k_attn_mfma everything is formed transposed so that a lane owns ONE
+// candidate (column c = lane % 32, half h = lane / 32):
+//   Q^T = W_q E^T      A = 32 query features x 16 item features, B = the row's 16-byte pieces
+//   S^T = K q^T        A = 32 keys x 16 (one head), B = the head's query
+//   O^T = V^T P^T      A = [16 features of the head ; a row of ones ; zeros] x 16 keys, B = the probabilities
+// A 32x32 result leaves rows 8 (i / 4) + 4 h + i % 4 in register i of lane (c, h).
+// The contraction index of a product may be assigned to (half, slot) in any
+// way as long as both operands agree, so
+//   - registers 8 (hd % 2) .. + 7 of feature tile hd / 2 of Q^T are, as they
+//     stand, the B operand of head hd's score product (K is packed with its
+//     16 dimensions in that order),
+//   - the sixteen probabilities of a key tile are two k-steps of the B operand
+//     of the second product (V packed in that key order), as in k_attn_mfma.
+// With 16-wide heads the vector ALU (one exponential per score) is what binds,
+// not the matrix cores, so the matrix cores take everything they can:
+//   - the query is scaled by log2(e) / sqrt(d_h) before it is rounded to bf16,
+//     and the score product accumulates onto -bound, so the product's result
+//     is the exponent itself (no multiply-add per score);
+//   - the sixteen empty rows of the second product's A operand hold a row of
+//     ones: row 16 of O^T is the softmax denominator (no add per score), and
+//     it is the sum of the ROUNDED probabilities, the weights that multiply V;
+//   - ones and V are zero for keys past the end of the sequence: no masking.
+// What is left per score is one v_exp_f32 and half a bf16 conversion.
+//
+// bound = |q'| max_t |k_t| >= every score (Cauchy-Schwarz) replaces the running
+// maximum; when it is large enough to risk underflow the wave takes the true
+// maximum in an extra pass over K.  Both are the exact softmax up to rounding.
+//
+// K/V packed per request (k_pack_kv16) stream through a three-slot ring in
+// LDS, eight 32-key tiles (24 KB) per stage, by direct-to-LDS loads.
+#include "k_mfma.h"
+#include "mfma_util.h"
+
+namespace aif {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2p __attribute__((ext_vector_type(2)));
+
+namespace {
+
+constexpr float P_LOG2E = 1.4426950408889634f;
+constexpr float P_BOUND_LIMIT = 57.f;        // in log2 units: exponents stay within [-114, 0]
+constexpr int P_NT = 8;                      // key tiles per stage
+constexpr int P_STAGE_FRAGS = 3 * P_NT;      // K, V of keys 0-15, V of keys 16-31 per tile
+constexpr int P_STAGE_BYTES = P_STAGE_FRAGS * 1024;
+constexpr int P_SLOTS = 3, P_DIST = P_SLOTS - 1;
+constexpr int P_MAX_HEADS = 32;
+constexpr int P_MAX_CROSS_FRAGS = 4;         // d_cross_vec <= 64
+constexpr int P_LDS_BYTES = P_SLOTS * P_STAGE_BYTES + P_MAX_HEADS * 4 + P_MAX_CROSS_FRAGS * 1024;
+
+__device__ __forceinline__ void store_stream4(void *p, bf16x4 v)
+{
+    __builtin_nontemporal_store(__builtin_bit_cast(u32x2p, v), (u32x2p *)p);
+}
+
+// ---------------------------------------------------------------------------
+// a2 -- K and V of request r, head hd, stage st (P_NT key tiles) into fragment order, and the largest
+// key norm of the stage.  Per request: chunk(head, key tile kt) = 3 fragments of 1 KB at
+// ((head * nktp + kt) * 3) KB, with o = 16 head:
+//   K:      [lane][s] = K[32 kt + lane % 32][o + 8 (s / 4) + 4 (lane / 32) + s % 4]
+//   V, jj:  [lane][s] = row lane % 32 of [V^T ; 1 ; 0] at key 32 kt + 16 jj + 8 (s / 4) + 4 (lane / 32) + s % 4
+// Keys >= seq_len read as zero in all rows, the row of ones included.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_pack_kv16(Model m, Batch b, char *__restrict__ kvpack, size_t pack_stride,
+                                                   float *__restrict__ kmax, int nktp)
+{
+    __shared__ float red[4];
+    const int st = blockIdx.x, hd = blockIdx.y, r = blockIdx.z;
+    const ReqDesc *rd = b.reqs + r;
+    const int L = rd->seq_len, nkt = (L + 31) >> 5;
+    if (P_NT * st >= nkt) return;
+    const uint16_t *K = (const uint16_t *)rd->seq_keys, *V = (const uint16_t *)rd->seq_vals;
+    const int da = m.d_attn, o = hd * 16;
+    uint4 *dst = (uint4 *)(kvpack + (size_t)r * pack_stride + ((size_t)(hd * nktp + P_NT * st) * 3) * 1024);
+    for (int pc = threadIdx.x; pc < P_STAGE_FRAGS * 64; pc += 256) {
+        const int tl = pc / 192, rem = pc - tl * 192, frag = rem >> 6, lane = rem & 63;
+        const int kt = P_NT * st + tl, hh = lane >> 5, row = lane & 31;
+        if (kt >= nkt) break;                    // tiles past the sequence are never read by the arithmetic
+        uint4 out = make_uint4(0, 0, 0, 0);
+        if (frag == 0) {
+            const int t = 32 * kt + row;
+            if (t < L) {
+                const uint2 lo = *(const uint2 *)(K + (size_t)t * da + o + 4 * hh);
+                const uint2 hi = *(const uint2 *)(K + (size_t)t * da + o + 8 + 4 * hh);
+                out = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            }
+        } else if (row <= 16) {
+            const int t0 = 32 * kt + 16 * (frag - 1) + 4 * hh;
+            uint32_t w[4];
+#pragma unroll
+            for (int p2 = 0; p2 < 4; ++p2) {     // slots 2 p2 and 2 p2 + 1
+                const int ta = t0 + 8 * (p2 >> 1) + 2 * (p2 & 1), tb = ta + 1;
+                uint32_t lo = 0, hi = 0;
+                if (ta < L) lo = row < 16 ? V[(size_t)ta * da + o + row] : 0x3F80u;
+                if (tb < L) hi = row < 16 ? V[(size_t)tb * da + o + row] : 0x3F80u;
+                w[p2] = lo | (hi << 16);
+            }
+            out = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        dst[pc] = out;
+    }
+    // largest key norm among this stage's 256 keys
+    {
+        const int t = 32 * P_NT * st + threadIdx.x;
+        float ss = 0.f;
+        if (t < L) {
+            const uint4 *kr = (const uint4 *)(K + (size_t)t * da + o);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint4 q = kr[i];
+                const uint32_t ws[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float a0 = __uint_as_float(ws[j] << 16), a1 = __uint_as_float(ws[j] & 0xFFFF0000u);
+                    ss += a0 * a0 + a1 * a1;
+                }
+            }
+        }
+        float nrm = sqrtf(ss);
+#pragma unroll
+        for (int off = 32; off; off >>= 1) nrm = fmaxf(nrm, __shfl_xor(nrm, off, 64));
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = nrm;
+        __syncthreads();
+        // rounded up a little: the bound must dominate the fp32-accumulated score
+        if (threadIdx.x == 0)
+            kmax[((size_t)r * m.n_heads + hd) * (nktp / P_NT) + st] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])) * 1.001f;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// projection + attention + cross.  One wave = 32 candidates, all heads in turn.
+// NFT = d_attn / 32 feature tiles of the query = n_heads / 2.
+// ---------------------------------------------------------------------------
+template <int NFT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_attn_proj(Model m, Batch b, char *__restrict__ X, XLayout xl,
+                                                         const char *__restrict__ wq_pack,
+                                                         const char *__restrict__ kvpack, size_t pack_stride,
+                                                         const float *__restrict__ kmax, int nktp)
+{
+    constexpr int ROWS = WAVES * 32, H = 2 * NFT;
+    constexpr int LPW = (P_STAGE_FRAGS + WAVES - 1) / WAVES;       // loads per wave and stage
+    static_assert(ROW_BLOCK % ROWS == 0, "tile");
+    static_assert(P_STAGE_FRAGS % WAVES == 0, "every wave issues the same number of loads");
+    extern __shared__ __align__(16) char lds[];
+    float *skm = (float *)(lds + P_SLOTS * P_STAGE_BYTES);         // [H] max |k_t|
+    bf16x8 *sa = (bf16x8 *)(skm + P_MAX_HEADS);                    // cross vectors as A fragments
+
+    // every XCD (own L2) takes a contiguous run of tiles, so the blocks that stream one request's K/V share an L2
+    const int per_xcd = gridDim.x >> 3;
+    const int bid = blockIdx.x;
+    const int tile = bid < 8 * per_xcd ? (bid & 7) * per_xcd + (bid >> 3) : bid;
+    const int row0 = tile * ROWS;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), col = lane & 31, h = lane >> 5;
+    char *xrow = X + x_offset(xl, row0 + wave * 32 + col, 0);
+    auto piece = [&](int p) { return (bf16x8 *)(xrow + (size_t)p * xl.piece_stride); };
+
+    const int r = b.blk_req[tile / (ROW_BLOCK / ROWS)];
+    if (r < 0) return;
+    const ReqDesc rd = b.reqs[r];
+    const int local0 = row0 - rd.row_base;
+    if (rd.n_cand - local0 <= 0) return;
+
+    const int L = rd.seq_len;
+    const int nkt = (L + 31) >> 5, nst = (nkt + P_NT - 1) / P_NT, total = H * nst, nstp = nktp / P_NT;
+    const char *pk = kvpack + (size_t)r * pack_stride;
+    const bool live = local0 + wave * 32 + col < rd.n_cand;
+    const uint32_t ring = lds_address(lds);
+    auto stage_src = [&](int i) {
+        const int sh = i / nst, ss = i - sh * nst;
+        return pk + ((size_t)(sh * nktp + P_NT * ss) * 3) * 1024;
+    };
+    auto stage_load = [&](int i) {
+        const char *src = stage_src(i) + lane * 16;
+        const uint32_t dst = ring + (i % P_SLOTS) * P_STAGE_BYTES;
+#pragma unroll
+        for (int f0 = 0; f0 < P_STAGE_FRAGS; f0 += WAVES) dma16(src + (f0 + wave) * 1024, dst + (f0 + wave) * 1024);
+    };
+
+    // ---- block set-up: key-norm bounds and the cross vectors as A fragments -----------------------------
+    for (int hd = wave; hd < H; hd += WAVES) {
+        float km = 0.f;
+        for (int i = lane; i < nst; i += 64) km = fmaxf(km, kmax[((size_t)r * H + hd) * nstp + i]);
+#pragma unroll
+        for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
+        if (lane == 0) skm[hd] = km;
+    }
+    const int ksc = m.d_cv / 16;                  // SEGDOT: k-steps per segment of the item vector
+    if (m.cross_mode == 2) {
+        // fragment kk: [lane][s] = Vc[lane % 32][16 kk + 8 (lane / 32) + s], rows >= n_cross zero
+        const uint16_t *Vc = (const uint16_t *)rd.cross_vecs;
+        uint16_t *sa16 = (uint16_t *)sa;
+        for (int i = threadIdx.x; i < ksc * 512; i += WAVES * 64) {
+            const int sl = i & 7, ln = (i >> 3) & 63, kk = i >> 9, row = ln & 31;
+            sa16[i] = row < m.n_cross ? Vc[(size_t)row * m.d_cv + 16 * kk + 8 * (ln >> 5) + sl] : (uint16_t)0;
+        }
+    }
+    __syncthreads();
+
+    // ---- query projection Q^T = W_q E^T, and the cross block from the same row pieces ---------------------
+    const int KS = m.d_item / 16;                 // a multiple of 4
+    const int pc_cross = (m.d_item + m.d_attn) / 8;
+    f32x16 Q[NFT];
+#pragma unroll
+    for (int ft = 0; ft < NFT; ++ft)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) Q[ft][i] = 0.f;
+    {
+        const bf16x8 *wq = (const bf16x8 *)wq_pack + lane;
+        const bf16x8 *uc = (const bf16x8 *)rd.cross_vecs;
+        const int nseg = m.cross_mode == 2 ? m.d_item / m.d_cv : 0;
+        f32x16 Cc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) Cc[i] = 0.f;
+        for (int j0 = 0; j0 < KS; j0 += 4) {
+            bf16x8 e[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) e[u] = *piece(2 * (j0 + u) + h);
+#pragma unroll
+            for (int ft = 0; ft < NFT; ++ft) {
+                bf16x8 a[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) a[u] = wq[((size_t)ft * KS + j0 + u) * 64];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) Q[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], e[u], Q[ft], 0, 0, 0);
+            }
+            if (m.cross_mode == 1 && live) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int pc = 2 * (j0 + u) + h;
+                    const bf16x8 uv = uc[pc];
+                    bf16x8 o8;
+#pragma unroll
+                    for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)e[u][s] * (float)uv[s]);
+                    *piece(pc_cross + pc) = o8;
+                }
+            }
+            if (m.cross_mode == 2) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int j = j0 + u, seg = j / ksc, kk = j - seg * ksc;
+                    Cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa[kk * 64 + lane], e[u], Cc, 0, 0, 0);
+                    if (kk == ksc - 1) {
+                        // cross feature (vector row, segment) sits at column row * nseg + seg of the cross block
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const int row = 8 * (i >> 2) + 4 * h + (i & 3);
+                            if (live && row < m.n_cross) {
+                                const int cc = row * nseg + seg;
+                                ((__bf16 *)piece(pc_cross + (cc >> 3)))[cc & 7] = (__bf16)Cc[i];
+                            }
+                            Cc[i] = 0.f;
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    // ring primed only now: the compiler waits for ALL outstanding loads wherever it waits for one of its own
+    for (int i = 0; i < P_DIST && i < total; ++i) stage_load(i);
+
+    // queries of all heads, scaled so that the score product yields the exponent to base 2
+    const float cs = P_LOG2E * 0.25f;             // log2(e) / sqrt(16)
+    bf16x8 q[H];
+#pragma unroll
+    for (int hd = 0; hd < H; ++hd)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) q[hd][s] = (__bf16)(Q[hd >> 1][8 * (hd & 1) + s] * cs);
+
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    const char *kv0 = lds + lane * 16;
+    int it = 0;
+#pragma unroll
+    for (int hd = 0; hd < H; ++hd) {
+        float ss = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) ss += (float)q[hd][s] * (float)q[hd][s];
+        ss += __shfl_xor(ss, 32, 64);
+        float mc = sqrtf(ss) * 1.001f * skm[hd];
+        // per candidate: its bits do not depend on which candidates share its wave
+        const bool need_max = live && mc > P_BOUND_LIMIT;
+        if (__any(need_max)) {
+            // rare: the true maximum, by an extra pass over K read straight from memory
+            float mx = -INFINITY;
+            for (int kt = 0; kt < nkt; ++kt) {
+                f32x16 S;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) S[i] = 0.f;
+                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(pk + ((size_t)(hd * nktp + kt) * 3) * 1024 + lane * 16),
+                                                            q[hd], S, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (t < L) mx = fmaxf(mx, S[v]);
+                }
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            if (need_max) mc = mx;
+        }
+        f32x16 NEG;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) NEG[i] = -mc;
+
+        f32x16 O;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[i] = 0.f;
+
+        for (int st = 0; st < nst; ++st) {
+            // stage it + P_DIST goes into the slot stage it - 1 was read from
+            if (it + P_DIST < total) stage_load(it + P_DIST);
+            const char *sb = kv0 + (it % P_SLOTS) * P_STAGE_BYTES;
+            const int ntl = nkt - P_NT * st;        // tiles of this stage (>= P_NT: all)
+            auto s_tile = [&](int tl) {
+                return __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(sb + tl * 3072), q[hd], NEG, 0, 0, 0);
+            };
+            auto finish_tile = [&](int tl, const f32x16 &S) {
+                bf16x8 P0, P1;
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    P0[v] = (__bf16)__builtin_amdgcn_exp2f(S[v]);
+                    P1[v] = (__bf16)__builtin_amdgcn_exp2f(S[8 + v]);
+                }
+                O = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(sb + tl * 3072 + 1024), P0, O, 0, 0, 0);
+                O = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(sb + tl * 3072 + 2048), P1, O, 0, 0, 0);
+            };
+            // the score product of tile t + 1 goes to the matrix cores BEFORE the exponentials of tile t
+            f32x16 Sa = s_tile(0), Sb;
+#pragma unroll
+            for (int tl = 0; tl < P_NT; tl += 2) {
+                if (tl + 1 < ntl) Sb = s_tile(tl + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (tl < ntl) finish_tile(tl, Sa);
+                __builtin_amdgcn_sched_barrier(0);
+                if (tl + 2 < P_NT && tl + 2 < ntl) Sa = s_tile(tl + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                if (tl + 1 < ntl) finish_tile(tl + 1, Sb);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // stage it + 1 must have landed; the one after it (if it exists) may stay in flight
+            if (total - 2 - it >= 1)
+                wait_vmcnt<LPW>();
+            else
+                wait_vmcnt<0>();
+            __syncthreads();
+            ++it;
+        }
+
+        // row 16 of O^T (register 8 of half 0; half 1 holds row 20, zeros) is the sum of the probabilities
+        float l = O[8];
+        l += __shfl_xor(l, 32, 64);
+        const float inv = L > 0 ? 1.0f / l : 0.f;
+        if (live) {
+            bf16x4 o0, o1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                o0[i] = (__bf16)(O[i] * inv);
+                o1[i] = (__bf16)(O[4 + i] * inv);
+            }
+            // features 4 h + i and 8 + 4 h + i of head hd: half h of two consecutive pieces
+            const int p0 = (m.d_item + hd * 16) / 8;
+            store_stream4((bf16x4 *)piece(p0) + h, o0);
+            store_stream4((bf16x4 *)piece(p0 + 1) + h, o1);
+        }
+    }
+}
+
+template <int NFT, int WAVES>
+hipError_t launch_proj_spec(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, hipStream_t s)
+{
+    constexpr int ROWS = WAVES * 32;
+    auto kern = k_attn_proj<NFT, WAVES>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), P_LDS_BYTES, s, m, b, (char *)X,
+                       x_layout(m), (const char *)plan.wq_pack, (const char *)plan.kvpack, plan.pack_stride,
+                       (const float *)plan.kmax, plan.nktp);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Shapes the kernel serves: bf16, W_q present, 16-wide heads (2, 4 or 8 of them), item vectors a multiple of
+// 64 wide; cross NONE, HADAMARD, or SEGDOT with at most 32 vectors of a width that is a multiple of 16 up to 64.
+bool attn_proj_ok(const Model &m, bool has_wq)
+{
+    if (m.dtype != 1 || !has_wq || m.d_head != 16 || m.d_item % 64) return false;
+    if (m.n_heads != 2 && m.n_heads != 4 && m.n_heads != 8) return false;
+    if (m.cross_mode == 2) return m.n_cross <= 32 && m.d_cv % 16 == 0 && m.d_cv <= 16 * P_MAX_CROSS_FRAGS;
+    return m.cross_mode == 0 || m.cross_mode == 1;
+}
+
+size_t attn_proj_pack_stride(const Model &m, int max_seq_len, int *nktp_out)
+{
+    const int nktp = (((max_seq_len + 31) >> 5) + P_NT - 1) / P_NT * P_NT;
+    if (nktp_out) *nktp_out = nktp;
+    return (size_t)m.n_heads * nktp * 3 * 1024;
+}
+
+hipError_t launch_attn_proj(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool small, hipStream_t s)
+{
+    if (plan.nktp > 0)
+        hipLaunchKernelGGL(k_pack_kv16, dim3(plan.nktp / P_NT, m.n_heads, b.n_req), dim3(256), 0, s, m, b, plan.kvpack,
+                           plan.pack_stride, plan.kmax, plan.nktp);
+    switch (m.n_heads) {
+    case 2: return small ? launch_proj_spec<1, 2>(m, b, X, plan, s) : launch_proj_spec<1, 8>(m, b, X, plan, s);
+    case 4: return small ? launch_proj_spec<2, 2>(m, b, X, plan, s) : launch_proj_spec<2, 8>(m, b, X, plan, s);
+    case 8: return small ? launch_proj_spec<4, 2>(m, b, X, plan, s) : launch_proj_spec<4, 8>(m, b, X, plan, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace aif

@@ -67,7 +67,12 @@ hipError_t launch_mlp_layers(const Model &m, const Batch &b, const void *X, cons
 // k_attn_mfma.hip
 int attn_mfma_variant(const Model &m, bool has_wq);
 size_t attn_pack_stride(const Model &m, int max_seq_len, int *nktp_out);
-hipError_t launch_attn_variant(int variant, const Model &m, const Batch &b, void *X, char *kvpack, size_t stride,
-                               float *kmax, int nktp, bool kv_packed, hipStream_t s);
+hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s);
+constexpr int ATTN_VARIANT_PROJ = 2;      // attn_variant of the projection + 16-wide-heads kernel (k_attn_proj.hip)
+
+// k_attn_proj.hip: query projection, 16-wide heads, Hadamard / segment-dot cross
+bool attn_proj_ok(const Model &m, bool has_wq);
+size_t attn_proj_pack_stride(const Model &m, int max_seq_len, int *nktp_out);
+hipError_t launch_attn_proj(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool small, hipStream_t s);
 
 }  // namespace aif

@@ -20,6 +20,12 @@ hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, size_t x_ro
         if (e != hipSuccess) return e;
         e = hipMalloc((void **)&plan.kmax, (size_t)max_users * m.n_heads * (plan.nktp / 2 + 1) * 4);
         if (e != hipSuccess) return e;
+        if (plan.attn_variant == ATTN_VARIANT_PROJ) {
+            e = hipMalloc(&plan.wq_pack, (size_t)m.d_attn * m.d_item * 2);
+            if (e != hipSuccess) return e;
+            e = pack_frag(w_q, m.d_item, 0, m.d_attn, m.d_item, false, plan.wq_pack, s);
+            if (e != hipSuccess) return e;
+        }
         plan.attn = true;
     }
 
@@ -75,7 +81,7 @@ void mfma_release(MfmaPlan &plan)
 
 hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s)
 {
-    return launch_attn_variant(plan.attn_variant, m, b, X, plan.kvpack, plan.pack_stride, plan.kmax, plan.nktp, kv_packed, s);
+    return launch_attn_variant(m, b, X, plan, kv_packed, s);
 }
 
 hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const MfmaPlan &plan,

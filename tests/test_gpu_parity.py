@@ -452,6 +452,90 @@ def test_layered_mlp_for_wide_heads(R, torch, shape):
 
 
 # ---------------------------------------------------------------------------
+# query projection + 16-wide heads on the matrix cores (the shape of configuration 5)
+# ---------------------------------------------------------------------------
+PROJ_SHAPES = {
+    # C5's model: 8 heads of 16 over a 256-wide item vector, 16 cross vectors x 4 segments, layered MLP
+    "c5_like": dict(d_item=256, d_user=576, d_attn=128, n_heads=8, use_wq=True, cross_mode=wl.CROSS_SEGDOT,
+                    n_cross=16, d_cross_vec=64, mlp_dims=(1024, 1024, 512, 256, 1)),
+    # Hadamard cross, fused MLP chain (workspace in fragment order)
+    "hadamard_4_heads": dict(d_item=64, d_user=64, d_attn=64, n_heads=4, use_wq=True, mlp_dims=(256, 256, 128, 1)),
+    # fewer cross vectors than MFMA rows, narrow segments, shape-agnostic MLP (row-major workspace)
+    "segdot_6_vectors_2_heads": dict(d_item=128, d_user=16, d_attn=32, n_heads=2, use_wq=True,
+                                     cross_mode=wl.CROSS_SEGDOT, n_cross=6, d_cross_vec=32, mlp_dims=(200, 64, 1)),
+    "no_cross_8_heads": dict(d_item=64, d_user=8, d_attn=128, n_heads=8, use_wq=True, cross_mode=wl.CROSS_NONE,
+                             mlp_dims=(200, 32, 1)),
+}
+
+
+def _projected_attention_tolerance(cfg, model, rows, user, ref_attn):
+    """The kernel rounds the projected, scaled query to bf16 (unit roundoff 2^-8) before the score product; the
+    oracle never rounds.  A score moves by at most ds = 2^-8 sum_k |q_k K_tk| / sqrt(d_h), the softmax weights by
+    at most 2 max_t ds in total, the output by that times max |V|.  Added to the bf16 tolerance of the block."""
+    from helpers import feature_tolerance
+    dh = cfg.d_attn // cfg.n_heads
+    q = np.abs(rows.astype(np.float64) @ model.w_q.astype(np.float64).T)               # [n, d_attn]
+    K = np.abs(user.seq_keys.astype(np.float64))
+    tol = feature_tolerance("bf16", ref_attn)
+    if K.shape[0] == 0:
+        return tol
+    vmax = np.abs(user.seq_vals.astype(np.float64)).max(axis=0)                        # [d_attn]
+    extra = np.zeros_like(tol)
+    for h in range(cfg.n_heads):
+        sl = slice(h * dh, (h + 1) * dh)
+        ds = 2.0 ** -8 * (q[:, sl] @ K[:, sl].T).max(axis=1) / np.sqrt(dh)             # [n]
+        extra[:, sl] = 2.0 * ds[:, None] * vmax[None, sl]
+    return tol + extra
+
+
+@pytest.mark.parametrize("shape", list(PROJ_SHAPES))
+@pytest.mark.parametrize("sigma", [0.1, 1.0, 4.0])
+def test_projection_attention_with_16_wide_heads(R, torch, shape, sigma):
+    """W_q, heads of 16, Hadamard / segment-dot / no cross: ragged candidate counts and sequence lengths (none, one
+    key, around the 32-key tile and the 256-key stage), at the configurations' scale and far above it (the
+    softmax then needs the true maximum instead of the norm bound)."""
+    cfg = small_cfg("bf16", n_items=5000, seq_len=530, **PROJ_SHAPES[shape])
+    _say(f"projection attention {shape} sigma={sigma}")
+    rng = np.random.default_rng(777)
+    model = wl.make_model(cfg, seed=13, bias_scale=0.2)
+    table = wl.make_table_host(cfg, rng, sigma=sigma)
+    table_dev = R.to_device(table, cfg.dtype)
+    sampler = wl.IdSampler(cfg)
+    users_ids = []
+    for n, L in [(1, 530), (31, 1), (32, 0), (33, 31), (255, 32), (256, 33), (257, 255), (700, 256), (64, 257),
+                 (300, 513)]:
+        users_ids.append((wl.make_user(cfg, rng, sigma=sigma, seq_len=L), sampler.sample(rng, n)))
+    zs, ys, drs, ctx = run_batch(R, torch, cfg, model, table_dev, users_ids, max_seq_len=530)
+    assert ctx.aif_stage_kind("attention") == 1, "MFMA attention not selected"
+    for r, ((u, ids), z) in enumerate(zip(users_ids, zs)):
+        ref = oracle_scores(cfg, model, table, u, ids, n_threads=4)
+        X = R.peek_features(ctx, cfg, r, ids.size)
+        assert np.array_equal(X[:, :cfg.d_item], table[ids])
+        a = X[:, cfg.d_item:cfg.d_item + cfg.d_attn]
+        assert np.all(np.isfinite(a)), f"req {r}: non-finite attention"
+        tol = _projected_attention_tolerance(cfg, model, table[ids], u, ref.attn)
+        err = np.abs(a.astype(np.float64) - ref.attn)
+        w = np.unravel_index(int(np.argmax(err - tol)), err.shape)
+        assert np.all(err <= tol), f"req {r} attention: worst at {w}: got {a[w]!r} ref {ref.attn[w]!r} tol {tol[w]:.3e}"
+        if cfg.d_cross:
+            assert_features_close("bf16", X[:, cfg.d_item + cfg.d_attn:], ref.cross, f"req {r} cross")
+        if sigma == 0.1:
+            assert_logits_close("bf16", z, ref.logits, f"req {r}")
+        else:
+            # far above the configurations' scale the logit is a small difference of large terms: the MLP input is
+            # stored in bf16, and a segment-dot entry of magnitude c (here up to ~200) carries up to 2^-9 c of
+            # rounding into layer 1.  Judge relative to the larger of the logits and 5 % of the largest input.
+            x_max = float(np.abs(ref.cross).max()) if cfg.d_cross else 0.0
+            scale = max(1.0, float(np.abs(ref.logits).max()), 0.05 * x_max)
+            assert np.abs(z - ref.logits).max() <= 2e-2 * scale, f"req {r}"
+    # slices of a request give the same bits as the whole, whatever shares their waves
+    u, ids = users_ids[7]
+    parts, _, _, _ = run_batch(R, torch, cfg, model, table_dev, [(u, ids[:256]), (u, ids[256:300]), (u, ids[300:])],
+                               max_seq_len=530)
+    assert np.array_equal(np.concatenate(parts), zs[7])
+
+
+# ---------------------------------------------------------------------------
 # nearline maintenance of the item table (Sec. 3.4): incremental and full updates
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("name", ["C1", "C2"])
