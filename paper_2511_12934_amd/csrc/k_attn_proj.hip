@@ -69,7 +69,8 @@ __device__ __forceinline__ void store_stream4(void *p, bf16x4 v)
 // ((head * nktp + kt) * 3) KB, with o = 16 head:
 //   K:      [lane][s] = K[32 kt + lane % 32][o + 8 (s / 4) + 4 (lane / 32) + s % 4]
 //   V, jj:  [lane][s] = row lane % 32 of [V^T ; 1 ; 0] at key 32 kt + 16 jj + 8 (s / 4) + 4 (lane / 32) + s % 4
-// Keys >= seq_len read as zero in all rows, the row of ones included.
+// Keys >= seq_len read as zero in all rows, the row of ones included; a stage is written whole, so the
+// tiles between the end of the sequence and the end of its last stage are zero and add nothing.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_pack_kv16(Model m, Batch b, char *__restrict__ kvpack, size_t pack_stride,
                                                    float *__restrict__ kmax, int nktp)
@@ -85,7 +86,6 @@ __global__ __launch_bounds__(256) void k_pack_kv16(Model m, Batch b, char *__res
     for (int pc = threadIdx.x; pc < P_STAGE_FRAGS * 64; pc += 256) {
         const int tl = pc / 192, rem = pc - tl * 192, frag = rem >> 6, lane = rem & 63;
         const int kt = P_NT * st + tl, hh = lane >> 5, row = lane & 31;
-        if (kt >= nkt) break;                    // tiles past the sequence are never read by the arithmetic
         uint4 out = make_uint4(0, 0, 0, 0);
         if (frag == 0) {
             const int t = 32 * kt + row;
@@ -142,13 +142,12 @@ __global__ __launch_bounds__(256) void k_pack_kv16(Model m, Batch b, char *__res
 // NFT = d_attn / 32 feature tiles of the query = n_heads / 2.
 // ---------------------------------------------------------------------------
 template <int NFT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void k_attn_proj(Model m, Batch b, char *__restrict__ X, XLayout xl,
+__global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, char *__restrict__ X, XLayout xl,
                                                          const char *__restrict__ wq_pack,
                                                          const char *__restrict__ kvpack, size_t pack_stride,
                                                          const float *__restrict__ kmax, int nktp)
 {
     constexpr int ROWS = WAVES * 32, H = 2 * NFT;
-    constexpr int LPW = (P_STAGE_FRAGS + WAVES - 1) / WAVES;       // loads per wave and stage
     static_assert(ROW_BLOCK % ROWS == 0, "tile");
     static_assert(P_STAGE_FRAGS % WAVES == 0, "every wave issues the same number of loads");
     extern __shared__ __align__(16) char lds[];
@@ -186,7 +185,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_proj(Model m, Batch b, char
         for (int f0 = 0; f0 < P_STAGE_FRAGS; f0 += WAVES) dma16(src + (f0 + wave) * 1024, dst + (f0 + wave) * 1024);
     };
 
-    // ---- block set-up: key-norm bounds and the cross vectors as A fragments -----------------------------
+    // ---- block set-up: W_q into the LDS the ring will take later (its fragments are read by all waves),
+    // key-norm bounds, the cross vectors as A fragments -------------------------------------------------
+    const int KS = m.d_item / 16;                 // a multiple of 4
+    for (int f = wave; f < NFT * KS; f += WAVES) dma16(wq_pack + (size_t)f * 1024 + lane * 16, ring + f * 1024);
     for (int hd = wave; hd < H; hd += WAVES) {
         float km = 0.f;
         for (int i = lane; i < nst; i += 64) km = fmaxf(km, kmax[((size_t)r * H + hd) * nstp + i]);
@@ -204,79 +206,69 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_proj(Model m, Batch b, char
             sa16[i] = row < m.n_cross ? Vc[(size_t)row * m.d_cv + 16 * kk + 8 * (ln >> 5) + sl] : (uint16_t)0;
         }
     }
+    wait_vmcnt<0>();
     __syncthreads();
 
-    // ---- query projection Q^T = W_q E^T, and the cross block from the same row pieces ---------------------
-    const int KS = m.d_item / 16;                 // a multiple of 4
+    // ---- query projection Q^T = W_q E^T; queries of all heads scaled so that the score product yields
+    // the exponent to base 2 -------------------------------------------------------------------------
     const int pc_cross = (m.d_item + m.d_attn) / 8;
-    f32x16 Q[NFT];
-#pragma unroll
-    for (int ft = 0; ft < NFT; ++ft)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) Q[ft][i] = 0.f;
+    bf16x8 q[H];
     {
-        const bf16x8 *wq = (const bf16x8 *)wq_pack + lane;
-        const bf16x8 *uc = (const bf16x8 *)rd.cross_vecs;
-        const int nseg = m.cross_mode == 2 ? m.d_item / m.d_cv : 0;
-        f32x16 Cc;
+        f32x16 Q[NFT];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) Cc[i] = 0.f;
+        for (int ft = 0; ft < NFT; ++ft)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) Q[ft][i] = 0.f;
+        const bf16x8 *wq = (const bf16x8 *)lds + lane;
         for (int j0 = 0; j0 < KS; j0 += 4) {
             bf16x8 e[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) e[u] = *piece(2 * (j0 + u) + h);
 #pragma unroll
-            for (int ft = 0; ft < NFT; ++ft) {
-                bf16x8 a[4];
+            for (int ft = 0; ft < NFT; ++ft)
 #pragma unroll
-                for (int u = 0; u < 4; ++u) a[u] = wq[((size_t)ft * KS + j0 + u) * 64];
+                for (int u = 0; u < 4; ++u)
+                    Q[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq[(ft * KS + j0 + u) * 64], e[u], Q[ft], 0, 0, 0);
+        }
+        const float cs = P_LOG2E * 0.25f;         // log2(e) / sqrt(16)
 #pragma unroll
-                for (int u = 0; u < 4; ++u) Q[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], e[u], Q[ft], 0, 0, 0);
-            }
-            if (m.cross_mode == 1 && live) {
+        for (int hd = 0; hd < H; ++hd)
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int pc = 2 * (j0 + u) + h;
-                    const bf16x8 uv = uc[pc];
-                    bf16x8 o8;
+            for (int s = 0; s < 8; ++s) q[hd][s] = (__bf16)(Q[hd >> 1][8 * (hd & 1) + s] * cs);
+    }
+    __syncthreads();                              // every wave has read W_q: the ring may take its place
+    for (int i = 0; i < P_DIST && i < total; ++i) stage_load(i);
+
+    // ---- the cross block, from the same row pieces (a second pass over them, under the ring's first loads) ----
+    if (m.cross_mode == 1 && live) {
+        const bf16x8 *uc = (const bf16x8 *)rd.cross_vecs;
+        for (int pc = h; pc < m.d_item / 8; pc += 2) {
+            const bf16x8 e = *piece(pc), uv = uc[pc];
+            bf16x8 o8;
 #pragma unroll
-                    for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)e[u][s] * (float)uv[s]);
-                    *piece(pc_cross + pc) = o8;
-                }
-            }
-            if (m.cross_mode == 2) {
+            for (int sl = 0; sl < 8; ++sl) o8[sl] = (__bf16)((float)e[sl] * (float)uv[sl]);
+            *piece(pc_cross + pc) = o8;
+        }
+    }
+    if (m.cross_mode == 2) {
+        const int nseg = m.d_item / m.d_cv;
+        for (int seg = 0; seg < nseg; ++seg) {
+            f32x16 Cc;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int j = j0 + u, seg = j / ksc, kk = j - seg * ksc;
-                    Cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa[kk * 64 + lane], e[u], Cc, 0, 0, 0);
-                    if (kk == ksc - 1) {
-                        // cross feature (vector row, segment) sits at column row * nseg + seg of the cross block
+            for (int i = 0; i < 16; ++i) Cc[i] = 0.f;
+            for (int kk = 0; kk < ksc; ++kk)
+                Cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa[kk * 64 + lane], *piece(2 * (seg * ksc + kk) + h), Cc, 0, 0, 0);
+            // cross feature (vector row, segment) sits at column row * nseg + seg of the cross block
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const int row = 8 * (i >> 2) + 4 * h + (i & 3);
-                            if (live && row < m.n_cross) {
-                                const int cc = row * nseg + seg;
-                                ((__bf16 *)piece(pc_cross + (cc >> 3)))[cc & 7] = (__bf16)Cc[i];
-                            }
-                            Cc[i] = 0.f;
-                        }
-                    }
+            for (int i = 0; i < 16; ++i) {
+                const int row = 8 * (i >> 2) + 4 * h + (i & 3);
+                if (live && row < m.n_cross) {
+                    const int cc = row * nseg + seg;
+                    ((__bf16 *)piece(pc_cross + (cc >> 3)))[cc & 7] = (__bf16)Cc[i];
                 }
             }
         }
     }
-
-    // ring primed only now: the compiler waits for ALL outstanding loads wherever it waits for one of its own
-    for (int i = 0; i < P_DIST && i < total; ++i) stage_load(i);
-
-    // queries of all heads, scaled so that the score product yields the exponent to base 2
-    const float cs = P_LOG2E * 0.25f;             // log2(e) / sqrt(16)
-    bf16x8 q[H];
-#pragma unroll
-    for (int hd = 0; hd < H; ++hd)
-#pragma unroll
-        for (int s = 0; s < 8; ++s) q[hd][s] = (__bf16)(Q[hd >> 1][8 * (hd & 1) + s] * cs);
-
     wait_vmcnt<0>();
     __syncthreads();
 
@@ -317,43 +309,37 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_proj(Model m, Batch b, char
 #pragma unroll
         for (int i = 0; i < 16; ++i) O[i] = 0.f;
 
+        // The head's key tiles are one stream: the score product of tile t + 1 (its K fragment read from
+        // LDS a tile ahead) is issued as soon as the last exponential of tile t has read the accumulator,
+        // between the two halves of tile t's second product, and runs under them -- across stage
+        // boundaries too, because the block's one barrier per stage sits in the MIDDLE of a stage: there
+        // stage it + 1 is confirmed (every wave waits for its own share of the loads, then the barrier), and
+        // stage it + 2 is sent into the slot of stage it - 1, which every wave has left.  After the last
+        // tile of the head the product computed ahead belongs to no one and is dropped.
+        bf16x8 Kf = *(const bf16x8 *)(kv0 + (it % P_SLOTS) * P_STAGE_BYTES);
+        f32x16 S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Kf, q[hd], NEG, 0, 0, 0);
         for (int st = 0; st < nst; ++st) {
-            // stage it + P_DIST goes into the slot stage it - 1 was read from
-            if (it + P_DIST < total) stage_load(it + P_DIST);
             const char *sb = kv0 + (it % P_SLOTS) * P_STAGE_BYTES;
-            const int ntl = nkt - P_NT * st;        // tiles of this stage (>= P_NT: all)
-            auto s_tile = [&](int tl) {
-                return __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(sb + tl * 3072), q[hd], NEG, 0, 0, 0);
-            };
-            auto finish_tile = [&](int tl, const f32x16 &S) {
+            const char *sbn = kv0 + ((it + 1) % P_SLOTS) * P_STAGE_BYTES;
+#pragma unroll
+            for (int tl = 0; tl < P_NT; ++tl) {
+                const bf16x8 V0 = *(const bf16x8 *)(sb + tl * 3072 + 1024);
+                const bf16x8 V1 = *(const bf16x8 *)(sb + tl * 3072 + 2048);
+                Kf = *(const bf16x8 *)(tl + 1 < P_NT ? sb + (tl + 1) * 3072 : sbn);
                 bf16x8 P0, P1;
 #pragma unroll
-                for (int v = 0; v < 8; ++v) {
-                    P0[v] = (__bf16)__builtin_amdgcn_exp2f(S[v]);
-                    P1[v] = (__bf16)__builtin_amdgcn_exp2f(S[8 + v]);
-                }
-                O = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(sb + tl * 3072 + 1024), P0, O, 0, 0, 0);
-                O = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(sb + tl * 3072 + 2048), P1, O, 0, 0, 0);
-            };
-            // the score product of tile t + 1 goes to the matrix cores BEFORE the exponentials of tile t
-            f32x16 Sa = s_tile(0), Sb;
+                for (int v = 0; v < 8; ++v) P0[v] = (__bf16)__builtin_amdgcn_exp2f(S[v]);
+                O = __builtin_amdgcn_mfma_f32_32x32x16_bf16(V0, P0, O, 0, 0, 0);
 #pragma unroll
-            for (int tl = 0; tl < P_NT; tl += 2) {
-                if (tl + 1 < ntl) Sb = s_tile(tl + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                if (tl < ntl) finish_tile(tl, Sa);
-                __builtin_amdgcn_sched_barrier(0);
-                if (tl + 2 < P_NT && tl + 2 < ntl) Sa = s_tile(tl + 2);
-                __builtin_amdgcn_sched_barrier(0);
-                if (tl + 1 < ntl) finish_tile(tl + 1, Sb);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int v = 0; v < 8; ++v) P1[v] = (__bf16)__builtin_amdgcn_exp2f(S[8 + v]);
+                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Kf, q[hd], NEG, 0, 0, 0);
+                O = __builtin_amdgcn_mfma_f32_32x32x16_bf16(V1, P1, O, 0, 0, 0);
+                if (tl == P_NT / 2 - 1) {
+                    wait_vmcnt<0>();
+                    asm volatile("s_barrier" ::: "memory");
+                    if (it + P_DIST < total) stage_load(it + P_DIST);
+                }
             }
-            // stage it + 1 must have landed; the one after it (if it exists) may stay in flight
-            if (total - 2 - it >= 1)
-                wait_vmcnt<LPW>();
-            else
-                wait_vmcnt<0>();
-            __syncthreads();
             ++it;
         }
 
@@ -396,10 +382,11 @@ hipError_t launch_proj_spec(const Model &m, const Batch &b, void *X, const MfmaP
 }  // namespace
 
 // Shapes the kernel serves: bf16, W_q present, 16-wide heads (2, 4 or 8 of them), item vectors a multiple of
-// 64 wide; cross NONE, HADAMARD, or SEGDOT with at most 32 vectors of a width that is a multiple of 16 up to 64.
+// 64 wide and W_q small enough for LDS (72 KB); cross NONE, HADAMARD, or SEGDOT with at most 32 vectors of a width that is a multiple of 16 up to 64.
 bool attn_proj_ok(const Model &m, bool has_wq)
 {
     if (m.dtype != 1 || !has_wq || m.d_head != 16 || m.d_item % 64) return false;
+    if ((size_t)m.d_attn * m.d_item * 2 > (size_t)P_SLOTS * P_STAGE_BYTES) return false;     // W_q is staged in the ring's LDS
     if (m.n_heads != 2 && m.n_heads != 4 && m.n_heads != 8) return false;
     if (m.cross_mode == 2) return m.n_cross <= 32 && m.d_cv % 16 == 0 && m.d_cv <= 16 * P_MAX_CROSS_FRAGS;
     return m.cross_mode == 0 || m.cross_mode == 1;
