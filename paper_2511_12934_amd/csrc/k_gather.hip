@@ -21,6 +21,14 @@ __global__ __launch_bounds__(256) void k_gather(const uint4 *__restrict__ table,
     gather_block<LOG_RV>(blockIdx.x, table, n_items, row_vec, b, X, xl, bad);
 }
 
+// the workspace in fragment order: through LDS (gather_block_tiled)
+template <int LOG_RV>
+__global__ __launch_bounds__(256) void k_gather_tiled(const uint4 *__restrict__ table, int64_t n_items, Batch b,
+                                                      char *__restrict__ X, XLayout xl, int32_t *__restrict__ bad)
+{
+    gather_block_tiled<LOG_RV>(blockIdx.x, table, n_items, b, X, xl, bad);
+}
+
 hipError_t launch_gather(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad,
                          hipStream_t s)
 {
@@ -32,6 +40,15 @@ hipError_t launch_gather(const Model &m, const Batch &b, const void *table, void
         hipLaunchKernelGGL(kern, dim3(b.n_blk), dim3(256), 0, s, (const uint4 *)table, m.n_items, row_vec, b, (char *)X,
                            xl, bad);
     };
+    if (m.x_tiled && (row_vec == 8 || row_vec == 16 || row_vec == 32)) {
+        auto got = [&](auto kern) {
+            hipLaunchKernelGGL(kern, dim3(b.n_blk), dim3(256), 0, s, (const uint4 *)table, m.n_items, b, (char *)X, xl, bad);
+        };
+        if (row_vec == 8) got(k_gather_tiled<3>);
+        if (row_vec == 16) got(k_gather_tiled<4>);
+        if (row_vec == 32) got(k_gather_tiled<5>);
+        return hipGetLastError();
+    }
     switch (row_vec) {
     case 8: go(k_gather<3>); break;
     case 16: go(k_gather<4>); break;

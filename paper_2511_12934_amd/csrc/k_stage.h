@@ -67,6 +67,82 @@ __device__ __forceinline__ void gather_block(int blk, const uint4 *__restrict__ 
     if (n_bad) atomicAdd(bad, n_bad);
 }
 
+// a1 for the workspace in fragment order -- the same copy through LDS.  In that layout a 32-row tile keeps
+// its 16-byte pieces as [piece][row], so rows written piece by piece land 512 bytes apart, 16 bytes at a
+// time.  Here the block instead reads 1024 pieces per trip as whole rows (every byte of a touched row,
+// four independent loads per thread), sets them down in LDS in tile order, and writes the tiles' item
+// blocks as contiguous 16 KB-per-32-piece runs; the next trip's rows are already in flight during the
+// exchange, and the two LDS buffers take turns so one barrier per trip is enough.
+template <int LOG_RV>
+__device__ __forceinline__ void gather_block_tiled(int blk, const uint4 *__restrict__ table, int64_t n_items,
+                                                   const Batch &b, char *__restrict__ X, const XLayout &xl,
+                                                   int32_t *__restrict__ bad)
+{
+    constexpr int RV = 1 << LOG_RV;                      // pieces per row: 8, 16 or 32
+    constexpr int ROWS = 1024 >> LOG_RV;                 // rows per trip
+    constexpr int PSTR = LOG_RV == 3 ? 544 : 528;        // LDS bytes per 32-row run of one piece: no bank conflicts either way
+    constexpr int BUF = 32 * PSTR;                       // 32 runs per trip
+    static_assert(LOG_RV >= 3 && LOG_RV <= 5 && ROW_BLOCK % ROWS == 0, "row widths of 128, 256, 512 bytes");
+    __shared__ __align__(16) char buf[2 * BUF];
+    __shared__ int32_t sid[ROW_BLOCK];
+
+    const int r = b.blk_req[blk];
+    if (r < 0) return;
+    const ReqDesc *rd = b.reqs + r;
+    const int row_base = rd->row_base;
+    const int local0 = blk * ROW_BLOCK - row_base;
+    int nrows = rd->n_cand - local0;
+    if (nrows <= 0) return;
+    if (nrows > ROW_BLOCK) nrows = ROW_BLOCK;
+    char *out = X + (size_t)((row_base + local0) / X_TILE) * xl.tile_bytes;
+    {
+        int64_t id = 0;
+        if ((int)threadIdx.x < nrows) {
+            id = rd->cand_ids[local0 + threadIdx.x];
+            if (id < 0 || id >= n_items) {
+                id = 0;
+                atomicAdd(bad, 1);
+            }
+        }
+        sid[threadIdx.x] = (int32_t)id;
+    }
+    __syncthreads();
+
+    uint4 v[4];
+    auto fetch = [&](int trip) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int idx = threadIdx.x + 256 * j, row = trip * ROWS + (idx >> LOG_RV), piece = idx & (RV - 1);
+            v[j] = row < nrows ? table[(size_t)sid[row] * RV + piece] : make_uint4(0, 0, 0, 0);
+        }
+    };
+    const int ntrip = (nrows + ROWS - 1) / ROWS;
+    fetch(0);
+    for (int trip = 0; trip < ntrip; ++trip) {
+        char *lb = buf + (trip & 1) * BUF;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int idx = threadIdx.x + 256 * j, row = idx >> LOG_RV, piece = idx & (RV - 1);
+            *(uint4 *)(lb + ((row >> 5) * RV + piece) * PSTR + (row & 31) * 16) = v[j];
+        }
+        if (trip + 1 < ntrip) fetch(trip + 1);
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int idx = threadIdx.x + 256 * j, run = idx >> 5, row = idx & 31;      // run = (tile of the trip, piece)
+            const int tt = run >> LOG_RV, piece = run & (RV - 1);
+            if (trip * ROWS + tt * 32 + row < nrows) {
+                const uint4 w = *(const uint4 *)(lb + run * PSTR + row * 16);
+                uint4 *p = (uint4 *)(out + (size_t)(trip * (ROWS / 32) + tt) * xl.tile_bytes + (size_t)piece * xl.piece_stride + row * 16);
+                __builtin_nontemporal_store(w.x, &p->x);
+                __builtin_nontemporal_store(w.y, &p->y);
+                __builtin_nontemporal_store(w.z, &p->z);
+                __builtin_nontemporal_store(w.w, &p->w);
+            }
+        }
+    }
+}
+
 // a2 -- user fold: 256 consecutive layer-1 features n = 256 * part + thread of request r,
 // bias1[r, n] = b1[n] + sum_k W1[n, k] u[k] over the user columns, k in order (w1ut = those
 // columns transposed, [d_user, H1], so that the threads of a wave read consecutive words).

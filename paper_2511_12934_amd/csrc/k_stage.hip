@@ -40,6 +40,12 @@ __global__ __launch_bounds__(256) void k_stage(StageArgs a)
         return;
     }
     idx -= a.n_fold;
+    if constexpr (LOG_RV >= 3 && LOG_RV <= 5) {
+        if (a.m.x_tiled) {
+            gather_block_tiled<LOG_RV>(idx, a.table, a.m.n_items, a.b, a.X, a.xl, a.bad);
+            return;
+        }
+    }
     gather_block<LOG_RV>(idx, a.table, a.m.n_items, a.row_vec, a.b, a.X, a.xl, a.bad);
 }
 
