@@ -150,6 +150,7 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
     constexpr int ROWS = WAVES * 32, H = 2 * NFT;
     static_assert(ROW_BLOCK % ROWS == 0, "tile");
     static_assert(P_STAGE_FRAGS % WAVES == 0, "every wave issues the same number of loads");
+    static_assert(P_DIST == 2, "the ring is primed with two stages, one before and one after the cross block");
     extern __shared__ __align__(16) char lds[];
     float *skm = (float *)(lds + P_SLOTS * P_STAGE_BYTES);         // [H] max |k_t|
     bf16x8 *sa = (bf16x8 *)(skm + P_MAX_HEADS);                    // cross vectors as A fragments
@@ -237,9 +238,9 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
             for (int s = 0; s < 8; ++s) q[hd][s] = (__bf16)(Q[hd >> 1][8 * (hd & 1) + s] * cs);
     }
     __syncthreads();                              // every wave has read W_q: the ring may take its place
-    for (int i = 0; i < P_DIST && i < total; ++i) stage_load(i);
+    if (total > 0) stage_load(0);
 
-    // ---- the cross block, from the same row pieces (a second pass over them, under the ring's first loads) ----
+    // ---- the cross block, from the same row pieces (a second pass over them, under the ring's first load) ----
     if (m.cross_mode == 1 && live) {
         const bf16x8 *uc = (const bf16x8 *)rd.cross_vecs;
         for (int pc = h; pc < m.d_item / 8; pc += 2) {
@@ -251,24 +252,40 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
         }
     }
     if (m.cross_mode == 2) {
-        const int nseg = m.d_item / m.d_cv;
+        // A lane ends up with single features of its candidate, 2 bytes each and far apart in the row: they
+        // are gathered in LDS (a private strip of the ring's last two slots per wave, rows padded by 16
+        // bytes) and leave as whole 16-byte pieces.
+        const int nseg = m.d_item / m.d_cv, sstr = m.d_cross * 2 + 16;
+        char *scr = lds + P_STAGE_BYTES + wave * (2 * P_STAGE_BYTES / WAVES);
         for (int seg = 0; seg < nseg; ++seg) {
             f32x16 Cc;
 #pragma unroll
             for (int i = 0; i < 16; ++i) Cc[i] = 0.f;
-            for (int kk = 0; kk < ksc; ++kk)
-                Cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa[kk * 64 + lane], *piece(2 * (seg * ksc + kk) + h), Cc, 0, 0, 0);
+            for (int kk0 = 0; kk0 < ksc; kk0 += 4) {
+                bf16x8 e[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (kk0 + u < ksc) e[u] = *piece(2 * (seg * ksc + kk0 + u) + h);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (kk0 + u < ksc) Cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa[(kk0 + u) * 64 + lane], e[u], Cc, 0, 0, 0);
+            }
             // cross feature (vector row, segment) sits at column row * nseg + seg of the cross block
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int row = 8 * (i >> 2) + 4 * h + (i & 3);
-                if (live && row < m.n_cross) {
-                    const int cc = row * nseg + seg;
-                    ((__bf16 *)piece(pc_cross + (cc >> 3)))[cc & 7] = (__bf16)Cc[i];
-                }
+                if (row < m.n_cross) *(__bf16 *)(scr + col * sstr + (row * nseg + seg) * 2) = (__bf16)Cc[i];
             }
         }
+        const int npc = m.d_cross / 8;
+        for (int idx = lane; idx < 32 * npc; idx += 64) {
+            const int cand = idx & 31, pc = idx >> 5;
+            if (local0 + wave * 32 + cand < rd.n_cand)
+                *(bf16x8 *)(X + x_offset(xl, row0 + wave * 32 + cand, pc_cross + pc)) = *(const bf16x8 *)(scr + cand * sstr + pc * 16);
+        }
     }
+    __syncthreads();                              // the strips have been read: the ring's second slot may fill
+    if (total > 1) stage_load(1);
     wait_vmcnt<0>();
     __syncthreads();
 
@@ -388,7 +405,8 @@ bool attn_proj_ok(const Model &m, bool has_wq)
     if (m.dtype != 1 || !has_wq || m.d_head != 16 || m.d_item % 64) return false;
     if ((size_t)m.d_attn * m.d_item * 2 > (size_t)P_SLOTS * P_STAGE_BYTES) return false;     // W_q is staged in the ring's LDS
     if (m.n_heads != 2 && m.n_heads != 4 && m.n_heads != 8) return false;
-    if (m.cross_mode == 2) return m.n_cross <= 32 && m.d_cv % 16 == 0 && m.d_cv <= 16 * P_MAX_CROSS_FRAGS;
+    if (m.cross_mode == 2)      // the cross block of 32 candidates passes through a 6 KB strip of LDS
+        return m.n_cross <= 32 && m.d_cv % 16 == 0 && m.d_cv <= 16 * P_MAX_CROSS_FRAGS && m.d_cross * 2 + 16 <= 2 * P_STAGE_BYTES / 8 / 32;
     return m.cross_mode == 0 || m.cross_mode == 1;
 }
 

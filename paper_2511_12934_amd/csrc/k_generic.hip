@@ -37,7 +37,7 @@ hipError_t launch_user_fold(const Model &m, const Batch &b, const float *w1u, co
                             hipStream_t s)
 {
     if (b.n_req == 0) return hipSuccess;
-    dim3 grid((m.dims[1] + 255) / 256, b.n_req);
+    dim3 grid((m.dims[1] + FOLD_FEATS - 1) / FOLD_FEATS, b.n_req);
     if (m.dtype == 0)
         hipLaunchKernelGGL(k_user_fold<float>, grid, dim3(256), 0, s, m, b, w1u, b1, bias1);
     else

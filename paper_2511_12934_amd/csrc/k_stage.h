@@ -143,30 +143,39 @@ __device__ __forceinline__ void gather_block_tiled(int blk, const uint4 *__restr
     }
 }
 
-// a2 -- user fold: 256 consecutive layer-1 features n = 256 * part + thread of request r,
-// bias1[r, n] = b1[n] + sum_k W1[n, k] u[k] over the user columns, k in order (w1ut = those
-// columns transposed, [d_user, H1], so that the threads of a wave read consecutive words).
+// a2 -- user fold: FOLD_FEATS consecutive layer-1 features n = FOLD_FEATS * part + thread % 64 of request r,
+// bias1[r, n] = b1[n] + sum_k W1[n, k] u[k] over the user columns (w1ut = those columns transposed,
+// [d_user, H1], so that the threads of a wave read consecutive words).  The job is a chain of dependent
+// loads, so the columns are cut into four runs, one per wave of the 256-thread block, eight loads in flight
+// each; the four partial sums are added in run order (a fixed order: the same bits in every call).
+constexpr int FOLD_FEATS = 64;
 template <typename T>
 __device__ __forceinline__ void user_fold_block(int r, int part, const Model &m, const Batch &b,
                                                 const float *__restrict__ w1ut, const float *__restrict__ b1,
                                                 float *__restrict__ bias1)
 {
-    const int n = part * 256 + threadIdx.x;
+    __shared__ float part_sum[3][FOLD_FEATS];
+    const int lane = threadIdx.x & 63, run = threadIdx.x >> 6;
+    const int n = part * FOLD_FEATS + lane;
     const int h1 = m.dims[1];
-    if (n >= h1) return;
+    const bool on = n < h1;
     const T *u = (const T *)b.reqs[r].user_vec;
-    float acc = b1 ? b1[n] : 0.f;
-    int k = 0;
-    for (; k + 4 <= m.d_user; k += 4) {             // four independent loads in flight
-        const float w0 = w1ut[(size_t)k * h1 + n], w1 = w1ut[(size_t)(k + 1) * h1 + n];
-        const float w2 = w1ut[(size_t)(k + 2) * h1 + n], w3 = w1ut[(size_t)(k + 3) * h1 + n];
-        acc = fmaf(w0, ld_f<T>(u + k), acc);
-        acc = fmaf(w1, ld_f<T>(u + k + 1), acc);
-        acc = fmaf(w2, ld_f<T>(u + k + 2), acc);
-        acc = fmaf(w3, ld_f<T>(u + k + 3), acc);
+    const int per = (m.d_user + 3) / 4, k0 = run * per, k1 = min(m.d_user, k0 + per);
+    float acc = 0.f;
+    if (on) {
+        int k = k0;
+        for (; k + 8 <= k1; k += 8) {
+            float w[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w[j] = w1ut[(size_t)(k + j) * h1 + n];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc = fmaf(w[j], ld_f<T>(u + k + j), acc);
+        }
+        for (; k < k1; ++k) acc = fmaf(w1ut[(size_t)k * h1 + n], ld_f<T>(u + k), acc);
     }
-    for (; k < m.d_user; ++k) acc = fmaf(w1ut[(size_t)k * h1 + n], ld_f<T>(u + k), acc);
-    bias1[(size_t)r * h1 + n] = acc;
+    if (run > 0) part_sum[run - 1][lane] = acc;
+    __syncthreads();
+    if (run == 0 && on) bias1[(size_t)r * h1 + n] = (((b1 ? b1[n] : 0.f) + acc) + part_sum[0][lane]) + (part_sum[1][lane] + part_sum[2][lane]);
 }
 
 // a2 -- K and V of request r, head hd, 64-key stage st into MFMA fragment order, and max |k_t| of the stage.

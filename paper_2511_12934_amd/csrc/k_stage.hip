@@ -22,7 +22,7 @@ struct StageArgs {
     float *kmax;
     int32_t nktp, row_vec;
     int32_t n_pack, n_fold;         // blocks of the first two jobs
-    int32_t stages, quads;          // 64-key stages per head (nktp / 2); blocks of 256 layer-1 features
+    int32_t stages, quads;          // 64-key stages per head (nktp / 2); blocks of FOLD_FEATS layer-1 features
 };
 
 template <int LOG_RV, int DH>
@@ -87,7 +87,7 @@ hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void 
     a.nktp = plan.nktp;
     a.row_vec = m.d_item * 2 / 16;
     a.stages = plan.nktp / 2;
-    a.quads = (m.dims[1] + 255) / 256;
+    a.quads = (m.dims[1] + FOLD_FEATS - 1) / FOLD_FEATS;
     a.n_pack = b.n_req * m.n_heads * a.stages;
     a.n_fold = b.n_req * a.quads;
     return m.d_head == 64 ? launch_stage_dh<64>(a, b.n_blk, s) : launch_stage_dh<32>(a, b.n_blk, s);
