@@ -4,7 +4,7 @@
 // Logits map to order-preserving 32-bit keys (NaN -> 0, the lowest; -0 -> +0).
 // Four 8-bit radix passes over LDS histograms find the exact key T of the
 // k-th best and how many candidates with key == T are needed (the keys of the
-// first 16 K candidates stay in registers between the passes; logits of one
+// first 20 K candidates stay in registers between the passes; logits of one
 // request crowd into a few bins of the leading byte, so each wave first counts
 // its lanes per bin by ballot and adds once per bin); a gather pass
 // takes every key > T plus the first ties in position order (block-wide
@@ -13,7 +13,7 @@
 // lower position first.  The result is a pure function of the logits.
 //
 // Before that, a shortcut that usually settles the request in one counting pass
-// (requests of at most 16 K candidates): the logits are counted into 2048 bins
+// (requests of at most 20 K candidates): the logits are counted into 2048 bins
 // that are equal intervals of [min, max] of the request's finite logits -- a
 // monotone map, so every candidate of a higher bin beats every candidate of a
 // lower one and equal logits share a bin.  The bin b* that holds the k-th best
@@ -28,7 +28,7 @@
 namespace aif {
 
 constexpr int TK_THREADS = 1024;
-constexpr int TK_CACHED = 16;              // keys per thread kept in registers
+constexpr int TK_CACHED = 20;              // keys per thread kept in registers (20 K candidates: the largest configured request)
 
 // hist[bin] += 1 for every active lane.  Up to TK_AGG distinct bins of the wave are added with one
 // atomic each (lanes counted by ballot); lanes left after that add on their own.

@@ -639,6 +639,9 @@ def _topk_cases(rng):
     cases["all_nan"] = np.full(300, np.nan, np.float32)
     cases["tiny"] = np.array([1.0, 2.0, 2.0], np.float32)
     cases["big"] = rng.standard_normal(20_000).astype(np.float32)
+    # more candidates than the kernel keeps in registers (the tail is re-read from memory in every pass), with ties
+    cases["bigger"] = np.round(rng.standard_normal(23_456).astype(np.float32), 2)
+    cases["bigger_dups"] = rng.integers(0, 3, 30_000).astype(np.float32)
     # aimed at the value-bin shortcut: ties straddling the cut inside one bin, an outlier that squeezes every other
     # logit into one bin, fewer candidates than k, only two distinct values, huge range
     cases["coarse"] = np.round(z, 3)
