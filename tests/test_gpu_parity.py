@@ -758,6 +758,32 @@ def test_duplicate_candidates_and_bad_ids(R, torch):
     assert ctx.aif_poll_device_errors() == 0
 
 
+@pytest.mark.parametrize("shape", ["c3_like", "c4_like"])
+def test_bad_ids_on_the_fragment_order_workspace(R, torch, shape):
+    """The MFMA path (gather through LDS into the fragment-order workspace): out-of-range ids give NaN logits and
+    are counted once each, their neighbours are untouched; ragged request sizes around the 32-row tile."""
+    cfg = small_cfg("bf16", n_items=3000, seq_len=40, **MFMA_SHAPES[shape])
+    _say(f"bad ids, fragment-order workspace, {shape}")
+    rng = np.random.default_rng(31)
+    model = wl.make_model(cfg, seed=3, bias_scale=0.1)
+    table = wl.make_table_host(cfg, rng)
+    u = wl.make_user(cfg, rng)
+    ids = rng.integers(0, 3000, 300).astype(np.int32)
+    bad_pos = np.array([0, 31, 32, 255, 256, 299])
+    ids_bad = ids.copy()
+    ids_bad[bad_pos] = [-1, 3000, 2_000_000_000, -5, 3001, -2_000_000_000]
+    (z_bad,), _, _, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), [(u, ids_bad)])
+    assert ctx.aif_stage_kind("attention") == 1 and ctx.aif_stage_kind("mlp") == 1
+    assert ctx.aif_poll_device_errors() == bad_pos.size
+    assert np.isnan(z_bad[bad_pos]).all()
+    good = np.setdiff1d(np.arange(ids.size), bad_pos)
+    ref = oracle_scores(cfg, model, table, u, ids[good], n_threads=4)
+    assert_logits_close("bf16", z_bad[good], ref.logits, "neighbours of bad ids")
+    (z_ok,), _, _, ctx2 = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), [(u, ids)])
+    assert np.array_equal(z_ok[good], z_bad[good])
+    assert ctx2.aif_poll_device_errors() == 0
+
+
 def test_host_side_errors_enqueue_nothing(R, torch):
     from paper_2511_12934_amd import binding as B
     cfg = small_cfg("f32")
