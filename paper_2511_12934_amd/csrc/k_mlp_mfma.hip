@@ -24,6 +24,8 @@ namespace aif {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef const f32x4 __attribute__((address_space(3))) *lds_f32x4_t;
 
 
 template <int N> struct IC { static constexpr int value = N; };
@@ -58,7 +60,9 @@ template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS> struct C
     static constexpr int flayer(int F) { return F < fbase(1) ? 0 : (F < fbase(2) ? 1 : 2); }
     static constexpr int ftile(int F) { return tbase(flayer(F)) + (F - fbase(flayer(F))) / ks(flayer(F)); }
     static constexpr int fk(int F) { return (F - fbase(flayer(F))) % ks(flayer(F)); }
-    static constexpr int foff(int F) { return ((F / SF) % SLOTS) * SF * 1024 + (F % SF) * 1024; }
+    // a block runs the stream twice (two tiles): pass P continues the ring where pass P - 1 left it
+    static constexpr int slot(int I, int P) { return (I + P * ns()) % SLOTS; }
+    static constexpr int foff(int F, int P) { return slot(F / SF, P) * SF * 1024 + (F % SF) * 1024; }
     static constexpr int tlayer(int T) { return T < tbase(1) ? 0 : (T < tbase(2) ? 1 : 2); }
     static constexpr int trt(int T) { return T - tbase(tlayer(T)); }
     // The epilogue of row tile T - 1 runs in four parts at k-steps epos(0..3) of row tile T, and at
@@ -68,7 +72,7 @@ template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS> struct C
     static constexpr int kinit(int KS) { return epos(3, KS) + 1; }
     static constexpr int LPW = SF / WAVES;                                      // loads per wave and stage
     static constexpr int HL = NH == 1 ? H1 : (NH == 2 ? H2 : H3);              // width entering the ->1 layer
-    static constexpr int bias_floats = H1 + H2 + H3 + HL;
+    static constexpr int bias_floats = 2 * H1 + H2 + H3 + HL;                  // layer-1 biases (per request): one set per tile of the pair
     static constexpr int ring_bytes = SLOTS * SF * 1024;
     static constexpr int lds_bytes = ring_bytes + 4 * bias_floats;
     static_assert(SF % WAVES == 0, "every wave moves the same number of fragments per stage");
@@ -79,17 +83,17 @@ template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS> struct C
 
 // Copy stage I of the weight stream global -> LDS slot: a wave moves whole 1 KB
 // fragments, no register staging.
-template <class C, int WAVES, int SF, int SLOTS, int I>
+template <class C, int WAVES, int SF, int SLOTS, int I, int P = 0>
 __device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
 {
     if constexpr (I < C::ns()) {
         constexpr int l = C::flayer(I * SF);
         const int lane = threadIdx.x & 63;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const char *src = pk.w[l] + (size_t)(I * SF - C::fbase(l)) * 1024 + lane * 16;
-        const uint32_t dst = lds_address(lds) + (I % SLOTS) * SF * 1024;
+        const char *src = pk.w[l] + (size_t)(I * SF - C::fbase(l)) * 1024 + wave * 1024;     // wave-uniform
+        const uint32_t dst = lds_address(lds) + C::slot(I, P) * SF * 1024 + wave * 1024;
 #pragma unroll
-        for (int f0 = 0; f0 < SF; f0 += WAVES) dma16(src + (f0 + wave) * 1024, dst + (f0 + wave) * 1024);
+        for (int f0 = 0; f0 < SF; f0 += WAVES) dma16_s(src + f0 * 1024, lane * 16, dst + f0 * 1024);
     }
 }
 
@@ -107,39 +111,75 @@ __device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
 //     the block barrier (after which stage I + 1 is complete in LDS and stage I - 1 is no longer
 //     read by anyone) and refills the slot of stage I - 1 with stage I + SLOTS - 1.
 // The barrier is hand-issued: the compiler's own would first drain the LDS reads in flight.
+//
+// A block takes TWO tiles of 256 candidates, 2 g and 2 g + 1, and runs the body twice.  What a block has to
+// wait for in a row before its first MFMA -- request lookup, then its biases, then the first weights: 12,000
+// cycles against the 36,000 of a tile's stream on the 256 -> 512 -> 256 head -- is paid once per pair: the
+// second tile's weight stream, fragment registers and bias preload are the first tile's running on (pass 1
+// finds every stage in the ring slot where pass 0's count leaves it), its request's descriptor comes by
+// scalar loads at the block's start and its layer-1 biases by a direct-to-LDS load into a second buffer.
+// Only its input rows cannot come early (no register is free before the first tile's last MFMA): they are
+// asked for at the first tile's end and the second tile's first MFMAs wait for them.
 template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS>
-__global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, const char *__restrict__ X, XLayout xl,
-                                                           MlpPack pk, const float *__restrict__ bias1)
+__global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(int64_t n_items, const ReqDesc *__restrict__ reqs,
+                                                           const int32_t *__restrict__ blk_req, const char *__restrict__ X,
+                                                           XLayout xl, MlpPack pk, const float *__restrict__ bias1, int n_pairs)
 {
     using C = Chain<K1, H1, H2, H3, WAVES, SF, SLOTS>;
     constexpr int THREADS = WAVES * 64, ROWS = WAVES * 32, NF = C::nf(), NS = C::ns(), NT = C::nt(), D = SLOTS - 1;
-    constexpr int RING = 8;
+    constexpr int RING = 4;
+    constexpr int IB = NS - D;                                  // stage whose first step sends the second tile's biases
     static_assert(ROW_BLOCK % ROWS == 0, "tile");
     static_assert(SF / 2 >= RING, "fragment prefetch never runs past a confirmed stage");
+    static_assert(NF % RING == 0 && NT % 2 == 0, "fragment registers and accumulators carry over into the second tile");
+    static_assert(NF - C::ks(C::NH - 1) + C::kinit(C::ks(C::NH - 1)) > (NS - 1) * SF + SF / 2,
+                  "the second tile's biases are first read after the last stage's barrier, which confirms them");
+    static_assert(IB >= 1 && H1 * 4 % 1024 == 0 && H1 * 4 / 1024 <= WAVES, "the second tile's biases: one 1 KB load per wave, landed D stages later");
     extern __shared__ __align__(16) char lds[];                 // the weight ring, then biases and last-layer weights
-    float *sb1 = (float *)(lds + C::ring_bytes), *sb2 = sb1 + H1, *sb3 = sb2 + H2, *swl = sb3 + H3;
+    float *sb1 = (float *)(lds + C::ring_bytes), *sb2 = sb1 + 2 * H1, *sb3 = sb2 + H2, *swl = sb3 + H3;
+    // what the end of a tile needs of its request (two whole descriptors would not fit the scalar registers)
+    struct Out {
+        const int32_t *cand_ids;
+        float *logits_out, *scores_out;
+        int32_t n_cand, row_base;
+    };
+    auto out_of = [&](int r) {
+        const ReqDesc *q = reqs + r;
+        return Out{q->cand_ids, q->logits_out, q->scores_out, q->n_cand, q->row_base};
+    };
 
-    const int tile = blockIdx.x;
-    const int row0 = tile * ROWS;
+    // blocks 0 .. n_pairs - 1 take two tiles each, the blocks after them the remaining tiles one by one
+    const bool has_next = (int)blockIdx.x < n_pairs;
+    const int tile0 = has_next ? 2 * (int)blockIdx.x : (int)blockIdx.x + n_pairs;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, h = lane >> 5;
+    const int wave_u = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // The block's start is a chain of dependent memory round trips; keep it short: the weight stream
-    // and the input rows do not depend on the request lookup (a padded row is still inside the
-    // workspace), so they are asked for first.
+    // and the input rows do not depend on the request lookup, so they are asked for first.
     static_for<0, D>([&](auto s) { issue_stage<C, WAVES, SF, SLOTS, decltype(s)::value>(pk, lds); });
     bf16x8 xin[K1 / 16];
-    {
-        const char *xr = X + x_offset(xl, row0 + wave * 32 + col, h);
+    auto load_xin = [&](int t) {
+        const char *xr = X + x_offset(xl, t * ROWS + wave * 32 + col, h);
 #pragma unroll
         for (int j = 0; j < K1 / 16; ++j) xin[j] = *(const bf16x8 *)(xr + (size_t)(2 * j) * xl.piece_stride);
-    }
-    const int r = b.blk_req[tile / (ROW_BLOCK / ROWS)];
-    const ReqDesc rd = b.reqs[r < 0 ? 0 : r];
-    const int local0 = row0 - rd.row_base;
-    if (r < 0 || rd.n_cand - local0 <= 0) {         // never taken when a tile is a whole scheduling block
-        wait_vmcnt<0>();                            // no load may still be heading for this block's LDS
-        return;
-    }
-    for (int i = threadIdx.x; i < H1; i += THREADS) sb1[i] = bias1[(size_t)r * H1 + i];
+    };
+    load_xin(tile0);
+    const int r0 = blk_req[tile0 / (ROW_BLOCK / ROWS)];
+    const int r1 = has_next ? blk_req[(tile0 + 1) / (ROW_BLOCK / ROWS)] : r0;
+    const Out rd0 = out_of(r0), rd1 = out_of(r1);
+    // Which lanes will store a result, and which of them carry an id outside the table, is settled here, as two
+    // wave masks per tile: the tile's end then has no load to wait for before its stores.
+    uint64_t live0, bad0, live1, bad1;
+    auto id_masks = [&](int tile, const Out &rd, uint64_t &live, uint64_t &bad) {
+        const int local = tile * ROWS - rd.row_base + wave * 32 + col;
+        const bool lv = h == 0 && local < rd.n_cand;
+        const int64_t id = lv ? (int64_t)rd.cand_ids[local] : 0;
+        live = __ballot(lv);
+        bad = __ballot(lv && (id < 0 || id >= n_items));
+    };
+    id_masks(tile0, rd0, live0, bad0);
+    id_masks(has_next ? tile0 + 1 : tile0, rd1, live1, bad1);
+    const float bl = pk.blast ? pk.blast[0] : 0.f;
+    for (int i = threadIdx.x; i < H1; i += THREADS) sb1[i] = bias1[(size_t)r0 * H1 + i];
     if (C::NH >= 2)
         for (int i = threadIdx.x; i < H2; i += THREADS) sb2[i] = pk.bias[1][i];
     if (C::NH >= 3)
@@ -153,20 +193,24 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, co
     bf16x8 h2[C::NH >= 3 ? H2 / 16 : 1];
     f32x16 acc[2];                          // row tiles T and T - 1 (ping-pong)
     bf16x8 areg[RING];
-    float4 wlv[4];                          // the ->1 layer's weights for the row tile in flight
+    f32x4 wlv[4];                           // the ->1 layer's weights for the row tile in flight
 
     const char *wl0 = lds + lane * 16;
-    auto bias_of = [&](int T) { const int L = C::tlayer(T); return (L == 0 ? sb1 : (L == 1 ? sb2 : sb3)) + 32 * C::trt(T) + 4 * h; };
-    auto preload_acc = [&](auto tc) {                           // acc of row tile T <- its biases
-        constexpr int T = decltype(tc)::value;
-        const float *sb = bias_of(T);
+    // Biases and ->1 weights are read as (one opaque per-lane base) + (immediate offset): left to itself the
+    // compiler forms every such address in a register of its own, keeps the first tile's for the second and
+    // spills them, and each reload waits for the whole weight ring in flight.
+    uint32_t bb = lds_address(sb1) + 16 * h;
+    asm volatile("" : "+v"(bb));
+    constexpr int OB2 = 2 * H1, OB3 = OB2 + H2, OWL = OB3 + H3;         // float offsets of sb2, sb3, swl from sb1
+    auto lds4 = [&](int float_off) -> f32x4 { return *(lds_f32x4_t)(uintptr_t)(bb + 4 * float_off); };
+    auto preload_from = [&](int float_off, f32x16 &a) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const float4 bv = *(const float4 *)(sb + 8 * q);
-            acc[T & 1][4 * q + 0] = bv.x;
-            acc[T & 1][4 * q + 1] = bv.y;
-            acc[T & 1][4 * q + 2] = bv.z;
-            acc[T & 1][4 * q + 3] = bv.w;
+            const f32x4 bv = lds4(float_off + 8 * q);
+            a[4 * q + 0] = bv.x;
+            a[4 * q + 1] = bv.y;
+            a[4 * q + 2] = bv.z;
+            a[4 * q + 3] = bv.w;
         }
     };
     // part Q of the epilogue of row tile T: the four features 8 Q + 4 h + i of this lane's candidate
@@ -194,57 +238,99 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(Model m, Batch b, co
             if constexpr ((Q & 1) == 1) asm volatile("" : "+v"(dst));
         }
     };
+    auto finish = [&](int tile, const Out &rd, uint64_t live, uint64_t bad) {      // the tile's logits and scores
+        float z = zpart + __shfl_xor(zpart, 32, 64) + bl;
+        const int local = tile * ROWS - rd.row_base + wave * 32 + col;
+        if ((live >> lane) & 1) {
+            if ((bad >> lane) & 1) z = __uint_as_float(0x7FC00000u);
+            rd.logits_out[local] = z;
+            if (rd.scores_out) rd.scores_out[local] = 1.0f / (1.0f + __expf(-z));
+        }
+    };
 
-    preload_acc(IC<0>{});
+    preload_from(0, acc[0]);
     static_for<0, RING - 1>([&](auto fc) {
         constexpr int F = decltype(fc)::value;
-        areg[F] = *(const bf16x8 *)(wl0 + C::foff(F));
+        areg[F] = *(const bf16x8 *)(wl0 + C::foff(F, 0));
     });
     __builtin_amdgcn_sched_barrier(0);
 
-    static_for<0, NF>([&](auto fc) {
-        constexpr int F = decltype(fc)::value;
-        constexpr int L = C::flayer(F), T = C::ftile(F), K = C::fk(F), KS = C::ks(L), I = F / SF;
-        if constexpr (F % SF == SF / 2 && I + 1 < NS) {
-            // stage I + 1 must have landed; the stages after it (as far as they exist) may stay in flight
-            constexpr int last = I + D - 1 < NS - 1 ? I + D - 1 : NS - 1;
-            wait_vmcnt<(last - (I + 1)) * C::LPW>();
-            asm volatile("s_barrier" ::: "memory");
-            issue_stage<C, WAVES, SF, SLOTS, I + D>(pk, lds);
-        }
-        if constexpr (F + RING - 1 < NF) areg[(F + RING - 1) % RING] = *(const bf16x8 *)(wl0 + C::foff(F + RING - 1));
-        if constexpr (L == 0)
-            acc[T & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[F % RING], xin[K], acc[T & 1], 0, 0, 0);
-        else if constexpr (L == 1)
-            acc[T & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[F % RING], h1[K], acc[T & 1], 0, 0, 0);
-        else
-            acc[T & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[F % RING], h2[K], acc[T & 1], 0, 0, 0);
-        if constexpr (T > 0) {
-            static_for<0, 4>([&](auto qc) {
-                if constexpr (K == C::epos(decltype(qc)::value, KS)) epi_part(IC<T - 1>{}, qc);
-            });
-        }
-        if constexpr (K == C::kinit(KS)) {
-            if constexpr (T + 1 < NT) preload_acc(IC<T + 1>{});
-            if constexpr (L == C::NH - 1) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) wlv[q] = *(const float4 *)(swl + 32 * C::trt(T) + 8 * q + 4 * h);
+    // pass P of the body; `more`: another pass follows (pass 0 of a complete pair)
+    auto pass = [&](auto pc, bool more) {
+        constexpr int P = decltype(pc)::value;
+        static_for<0, NF>([&](auto fc) {
+            constexpr int F = decltype(fc)::value;
+            constexpr int L = C::flayer(F), T = C::ftile(F), K = C::fk(F), KS = C::ks(L), I = F / SF;
+            if constexpr (P == 0 && F == IB * SF) {
+                // the second tile's layer-1 biases travel to the second buffer (waves 0 .. H1 / 256 - 1, 1 KB each).
+                // They are older than the stages sent from here on, so D stages later they have landed, like a stage.
+                if (more && wave_u < H1 * 4 / 1024)
+                    dma16_s((const char *)(bias1 + (size_t)r1 * H1) + wave_u * 1024, lane_off16_now(),
+                            lds_address(sb1 + H1) + wave_u * 1024);
             }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    });
-    // the last row tile's epilogue has nothing left to hide behind
-    static_for<0, 4>([&](auto qc) { epi_part(IC<NT - 1>{}, qc); });
+            if constexpr (F % SF == SF / 2) {
+                if constexpr (I + D < NS) {
+                    // stage I + 1 must have landed; the D - 2 stages after it may stay in flight
+                    wait_vmcnt<(D - 2) * C::LPW>();
+                    asm volatile("s_barrier" ::: "memory");
+                    issue_stage<C, WAVES, SF, SLOTS, I + D, P>(pk, lds);
+                } else {
+                    bool on = false;
+                    if constexpr (P == 0) on = more;
+                    if (on) {
+                        // the stream runs on into the second tile: stage I + D is its stage I + D - NS
+                        wait_vmcnt<(D - 2) * C::LPW>();
+                        asm volatile("s_barrier" ::: "memory");
+                        issue_stage<C, WAVES, SF, SLOTS, I + D - NS, 1>(pk, lds);
+                    } else if constexpr (I + 1 < NS) {
+                        // the block's last tile: nothing more is sent; stages I + 2 .. NS - 1 may stay in flight
+                        wait_vmcnt<(NS - 1 - (I + 1)) * C::LPW>();
+                        asm volatile("s_barrier" ::: "memory");
+                    }
+                }
+            }
+            if constexpr (F + RING - 1 < NF)
+                areg[(F + RING - 1) % RING] = *(const bf16x8 *)(wl0 + C::foff(F + RING - 1, P));
+            else if constexpr (P == 0)      // the second tile's first fragments (read, and never used, when there is none:
+                                            // an assignment under a condition would keep the old registers alive all along)
+                areg[(F + RING - 1) % RING] = *(const bf16x8 *)(wl0 + C::foff(F + RING - 1 - NF, 1));
+            if constexpr (L == 0)
+                acc[T & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[F % RING], xin[K], acc[T & 1], 0, 0, 0);
+            else if constexpr (L == 1)
+                acc[T & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[F % RING], h1[K], acc[T & 1], 0, 0, 0);
+            else
+                acc[T & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(areg[F % RING], h2[K], acc[T & 1], 0, 0, 0);
+            if constexpr (T > 0) {
+                static_for<0, 4>([&](auto qc) {
+                    if constexpr (K == C::epos(decltype(qc)::value, KS)) epi_part(IC<T - 1>{}, qc);
+                });
+            }
+            if constexpr (K == C::kinit(KS)) {
+                if constexpr (T + 1 < NT) {                       // acc of row tile T + 1 <- its biases
+                    constexpr int L1 = C::tlayer(T + 1);
+                    preload_from((L1 == 0 ? P * H1 : (L1 == 1 ? OB2 : OB3)) + 32 * C::trt(T + 1), acc[(T + 1) & 1]);
+                } else if constexpr (P == 0)                      // the second tile's first row tile (NT is even)
+                    preload_from(H1, acc[0]);
+                if constexpr (L == C::NH - 1) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) wlv[q] = lds4(OWL + 32 * C::trt(T) + 8 * q);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        // every register is free again: the second tile's input rows (the first's once more if there is no
+        // second: unconditional, or the old rows' registers would have to stay alive through the whole tile)
+        if constexpr (P == 0) load_xin(more ? tile0 + 1 : tile0);
+        // the last row tile's epilogue has nothing left to hide behind
+        static_for<0, 4>([&](auto qc) { epi_part(IC<NT - 1>{}, qc); });
+    };
 
-    const float bl = pk.blast ? pk.blast[0] : 0.f;
-    float z = zpart + __shfl_xor(zpart, 32, 64) + bl;
-    const int local = local0 + wave * 32 + col;
-    if (h == 0 && local < rd.n_cand) {
-        const int64_t id = rd.cand_ids[local];
-        if (id < 0 || id >= m.n_items) z = __uint_as_float(0x7FC00000u);
-        rd.logits_out[local] = z;
-        if (rd.scores_out) rd.scores_out[local] = 1.0f / (1.0f + __expf(-z));
-    }
+    pass(IC<0>{}, has_next);
+    finish(tile0, rd0, live0, bad0);
+    if (!has_next) return;
+    zpart = 0.f;
+    pass(IC<1>{}, false);
+    finish(tile0 + 1, rd1, live1, bad1);
 }
 
 // ---- weights into fragment order --------------------------------------------
@@ -273,6 +359,18 @@ hipError_t pack_frag(const void *W, int n_in, int col0, int N, int K, bool from_
 }
 
 // ---- dispatch -----------------------------------------------------------------
+static int n_cu()
+{
+    static int n = 0;
+    if (!n) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        n = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+                ? prop.multiProcessorCount : 256;
+    }
+    return n;
+}
+
 template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS>
 static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, const MlpPack &pk, const float *bias1,
                               hipStream_t s)
@@ -287,8 +385,15 @@ static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, con
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), LDS, s, m, b, (const char *)X, x_layout(m),
-                       pk, bias1);
+    // Two tiles per block where there are tiles to spare: the last two per compute unit go one per block, after
+    // the pairs, so that the launch ends evenly (a pair on a unit while others idle would cost more than the
+    // pairs save), and a batch of up to that many tiles keeps every unit it can reach busy.
+    const int n_tiles = b.n_blk * (ROW_BLOCK / ROWS);
+    int n_single = n_tiles < 2 * n_cu() ? n_tiles : 2 * n_cu();
+    if ((n_tiles - n_single) & 1) ++n_single;
+    const int n_pairs = (n_tiles - n_single) / 2;
+    hipLaunchKernelGGL(kern, dim3(n_pairs + n_single), dim3(WAVES * 64), LDS, s, m.n_items, b.reqs, b.blk_req, (const char *)X,
+                       x_layout(m), pk, bias1, n_pairs);
     return hipGetLastError();
 }
 
