@@ -35,7 +35,7 @@ def test_full_size_batched_config(name):
         assert np.array_equal(idx[u], oi), f"user {u}"
         assert np.array_equal(val[u].astype(np.float64), ov), f"user {u}"
     # sampled candidates of sampled users against the oracle
-    users = sorted({0, cfg.n_users - 1, int(rng.integers(0, cfg.n_users))})
+    users = sorted({0, 1, cfg.n_users - 1, int(rng.integers(0, cfg.n_users))})
     for u in users:
         pos = np.unique(np.concatenate([[0, 255, 256, cfg.n_cand - 1], rng.integers(0, cfg.n_cand, 124)]))
         rows = w.rows_of(u, pos)

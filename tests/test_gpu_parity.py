@@ -243,6 +243,42 @@ def test_mfma_kernels_ragged_and_large_inputs(R, torch, shape, sigma):
             assert np.abs(z - ref.logits).max() <= 2e-2 * scale, f"req {r}"
 
 
+@pytest.mark.parametrize("shape", list(MFMA_SHAPES))
+def test_mlp_chain_blocks_that_take_two_tiles(R, torch, shape):
+    """A batch with more 256-candidate tiles than twice the compute units: the MLP chain's blocks then take two
+    tiles each, here mostly of two different requests (different layer-1 biases, outputs, ragged ends).
+    Sampled requests against the oracle; every request bit for bit against the same request scored alone
+    (few tiles: one per block)."""
+    cfg = small_cfg("bf16", n_items=5000, seq_len=12, **MFMA_SHAPES[shape])
+    _say(f"two-tile blocks {shape}")
+    rng = np.random.default_rng(977)
+    model = wl.make_model(cfg, seed=12, bias_scale=0.2)
+    table = wl.make_table_host(cfg, rng, sigma=1.0)
+    table_dev = R.to_device(table, cfg.dtype)
+    sampler = wl.IdSampler(cfg)
+    sizes = [200, 300, 257, 256, 31, 513, 1]
+    users_ids = []
+    for r in range(640):
+        users_ids.append((wl.make_user(cfg, rng, sigma=1.0, seq_len=int(rng.integers(0, 13))),
+                          sampler.sample(rng, sizes[r % len(sizes)])))
+    n_tiles = sum((ids.size + 255) // 256 for _, ids in users_ids)
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    assert n_tiles > 2 * n_cu + 64, "the batch is too small for two-tile blocks on this device"
+    zs, ys, drs, ctx = run_batch(R, torch, cfg, model, table_dev, users_ids, max_seq_len=12)
+    assert ctx.aif_stage_kind("mlp") == 1, "MFMA chain not selected"
+    assert ctx.aif_poll_device_errors() == 0
+    for r in list(range(24)) + list(range(len(users_ids) - 8, len(users_ids))):
+        u, ids = users_ids[r]
+        ref = oracle_scores(cfg, model, table, u, ids, n_threads=8)
+        scale = max(1.0, float(np.abs(ref.logits).max()))
+        assert np.all(np.isfinite(zs[r])) and np.abs(zs[r] - ref.logits).max() <= 2e-2 * scale, f"req {r}"
+    for r, (u, ids) in enumerate(users_ids):
+        alone = R.upload_request(cfg, u, ids)
+        ctx.aif_score_request(alone.req)
+        torch.cuda.synchronize()
+        assert np.array_equal(alone.logits.cpu().numpy(), zs[r]), f"req {r}: batch and single call differ"
+
+
 def test_resident_and_streaming_attention_give_the_same_bits(R, torch):
     """A request whose K/V fit in LDS is served by the resident attention kernel; in a batch with a
     request whose K/V do not fit, by the streaming one.  Its results must not depend on the company."""
