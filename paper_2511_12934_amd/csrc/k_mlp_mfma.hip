@@ -128,13 +128,16 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(int64_t n_items, con
     using C = Chain<K1, H1, H2, H3, WAVES, SF, SLOTS>;
     constexpr int THREADS = WAVES * 64, ROWS = WAVES * 32, NF = C::nf(), NS = C::ns(), NT = C::nt(), D = SLOTS - 1;
     constexpr int RING = 4;
-    constexpr int IB = NS - D;                                  // stage whose first step sends the second tile's biases
+    // The second tile's biases are first read at step FB of the first tile.  Sent at the first step of stage IB they
+    // are older than every stage sent from there on, so the wait and barrier in the middle of stage IB + D - 1
+    // (which leave only the D - 2 youngest stages in flight) confirm them.
+    constexpr int FB = NF - C::ks(C::NH - 1) + C::kinit(C::ks(C::NH - 1));
+    constexpr int IB = (FB - SF / 2 - 1) / SF - (D - 1);
     static_assert(ROW_BLOCK % ROWS == 0, "tile");
     static_assert(SF / 2 >= RING, "fragment prefetch never runs past a confirmed stage");
     static_assert(NF % RING == 0 && NT % 2 == 0, "fragment registers and accumulators carry over into the second tile");
-    static_assert(NF - C::ks(C::NH - 1) + C::kinit(C::ks(C::NH - 1)) > (NS - 1) * SF + SF / 2,
-                  "the second tile's biases are first read after the last stage's barrier, which confirms them");
-    static_assert(IB >= 1 && H1 * 4 % 1024 == 0 && H1 * 4 / 1024 <= WAVES, "the second tile's biases: one 1 KB load per wave, landed D stages later");
+    static_assert(IB >= 1 && IB + D <= NS && (IB + D - 1) * SF + SF / 2 < FB, "the second tile's biases are confirmed before their first read");
+    static_assert(H1 * 4 % 1024 == 0 && H1 * 4 / 1024 <= WAVES, "the second tile's biases: one 1 KB load per wave");
     extern __shared__ __align__(16) char lds[];                 // the weight ring, then biases and last-layer weights
     float *sb1 = (float *)(lds + C::ring_bytes), *sb2 = sb1 + 2 * H1, *sb3 = sb2 + H2, *swl = sb3 + H3;
     // what the end of a tile needs of its request (two whole descriptors would not fit the scalar registers)
@@ -389,7 +392,8 @@ static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, con
     // the pairs, so that the launch ends evenly (a pair on a unit while others idle would cost more than the
     // pairs save), and a batch of up to that many tiles keeps every unit it can reach busy.
     const int n_tiles = b.n_blk * (ROW_BLOCK / ROWS);
-    int n_single = n_tiles < 2 * n_cu() ? n_tiles : 2 * n_cu();
+    const int per_cu = 2 * (8 / WAVES);               // blocks of eight waves' worth of registers a unit holds: 8 / WAVES
+    int n_single = n_tiles < per_cu * n_cu() ? n_tiles : per_cu * n_cu();
     if ((n_tiles - n_single) & 1) ++n_single;
     const int n_pairs = (n_tiles - n_single) / 2;
     hipLaunchKernelGGL(kern, dim3(n_pairs + n_single), dim3(WAVES * 64), LDS, s, m.n_items, b.reqs, b.blk_req, (const char *)X,
@@ -413,9 +417,13 @@ hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const
 {
     if (b.n_blk == 0) return hipSuccess;
     switch (variant) {
-    case 0: return launch_spec<192, 256, 128, 0, 8, 32, 4>(m, b, X, pk, bias1, s);
+    case 0:
+        // a batch that cannot give every compute unit a 256-candidate tile (a single request of 10^4 is 40) goes
+        // in 128-candidate tiles: twice the units at work
+        if (b.n_blk < n_cu()) return launch_spec<192, 256, 128, 0, 4, 16, 4>(m, b, X, pk, bias1, s);
+        return launch_spec<192, 256, 128, 0, 8, 32, 4>(m, b, X, pk, bias1, s);
     case 1: return launch_spec<192, 512, 256, 0, 8, 32, 4>(m, b, X, pk, bias1, s);
-    case 2: return launch_spec<384, 256, 0, 0, 8, 32, 4>(m, b, X, pk, bias1, s);
+    case 2: return launch_spec<384, 256, 0, 0, 4, 16, 4>(m, b, X, pk, bias1, s);
     default: return hipErrorInvalidValue;
     }
 }
