@@ -346,6 +346,10 @@ def main_async(args):
     over, _ = timed(True, False)
     ms_per_step = over / args.steps * 1e3
     work = algorithmic_work(cfg)
+    if p.ctx.aif_stage_kind("gather") == 2:          # the attention kernel indexed the table itself, see main()
+        B = 4 if cfg.dtype == "f32" else 2
+        work["attention"]["bytes"] += work["gather"]["bytes"] - cfg.d_item * B
+        work["gather"]["bytes"] = 0
     cands = p.total_candidates
     kernels = {}
     for stage in ("gather", "attention", "mlp", "topk"):
@@ -354,7 +358,7 @@ def main_async(args):
         ent = {"avg_ms": avg_ms, "kind": "mfma" if p.ctx.aif_stage_kind(stage) == 1 else "generic"}
         if "flops" in work[stage] and avg_ms > 0:
             ent["tflops"] = work[stage]["flops"] * cands / (avg_ms * 1e-3) / 1e12
-        if avg_ms > 0:
+        if avg_ms > 0 and work[stage]["bytes"] > 0:
             ent["gbs"] = work[stage]["bytes"] * cands / (avg_ms * 1e-3) / 1e9
         kernels[stage] = ent
     for st in ("project", "attention", "ffn_pool"):
@@ -470,30 +474,48 @@ def main():
         w.step()
     torch.cuda.synchronize()
 
-    w.ctx.aif_profile_begin(args.steps)
+    # Every stage's time comes from a few profiled steps BEFORE the timed region (two events per stage cost the
+    # stream some microseconds each); inside the timed region only the dominant kernel is bracketed by events,
+    # and its time there is the one the roofline line uses.
+    n_pre = max(3, min(10, args.steps))
+    w.ctx.aif_profile_begin(n_pre)
+    for _ in range(n_pre):
+        w.step()
+    torch.cuda.synchronize()
+    prof = w.ctx.aif_profile_end()
+    dom = max(("gather", "attention", "mlp"), key=lambda s: prof[s][0] / max(prof[s][1], 1))
+
+    w.ctx.aif_profile_begin_stages(args.steps, [dom])
     t0 = time.perf_counter()
     for _ in range(args.steps):
         w.step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    prof = w.ctx.aif_profile_end()
+    prof[dom] = w.ctx.aif_profile_end()[dom]
     ms_per_step = elapsed / args.steps * 1e3
     value = w.total_candidates * args.steps / elapsed
 
     work = algorithmic_work(cfg)
+    if w.ctx.aif_stage_kind("gather") == 2:
+        # the attention kernel indexed the table itself: id + table row read + item row written are its bytes
+        # (in place of the item row it would have read from the workspace); the gather stage moved none
+        B = 4 if cfg.dtype == "f32" else 2
+        work["attention"]["bytes"] += work["gather"]["bytes"] - cfg.d_item * B
+        work["gather"]["bytes"] = 0
     cands = w.total_candidates
     kernels = {}
     for stage in ("gather", "attention", "mlp", "topk"):
         ms, n = prof[stage]
         avg_ms = ms / max(n, 1)
-        ent = {"avg_ms": avg_ms, "kind": "mfma" if w.ctx.aif_stage_kind(stage) == 1 else "generic"}
+        ent = {"avg_ms": avg_ms,
+               "kind": ("generic", "mfma", "inside the attention kernel")[w.ctx.aif_stage_kind(stage)]}
         wk = work[stage]
         if "flops" in wk and avg_ms > 0:
             ent["tflops"] = wk["flops"] * cands / (avg_ms * 1e-3) / 1e12
-        if avg_ms > 0:
+        if avg_ms > 0 and wk["bytes"] > 0:
             ent["gbs"] = wk["bytes"] * cands / (avg_ms * 1e-3) / 1e9
         kernels[stage] = ent
-    dom = max(("gather", "attention", "mlp"), key=lambda s: kernels[s]["avg_ms"])
+    kernels[dom]["timed_in"] = "timed region"
     if dom == "gather":
         roof = {"kernel": "k_gather", "bound": "hbm", "achieved": kernels[dom]["gbs"], "peak": PEAK_HBM_GBS,
                 "unit": "GB/s"}

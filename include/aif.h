@@ -204,10 +204,20 @@ AIF_API aif_status aif_peek_features(aif_ctx *ctx, int32_t request, int32_t firs
 enum { AIF_STAGE_GATHER = 0, AIF_STAGE_USER_FOLD = 1, AIF_STAGE_ATTENTION = 2, AIF_STAGE_MLP = 3,
        AIF_STAGE_TOPK = 4, AIF_STAGE_COUNT = 5 };
 AIF_API aif_status aif_profile_begin(aif_ctx *ctx, int32_t max_calls);
+/* The same for a subset of the stages: stage_mask has bit (1 << AIF_STAGE_x) set
+ * for every stage to be timed; only the events that bound those stages are
+ * recorded (an event costs a few microseconds on the stream), the others'
+ * ms_sum and n_calls come back 0.  AIF_EINVAL if the mask names no stage. */
+AIF_API aif_status aif_profile_begin_stages(aif_ctx *ctx, int32_t max_calls, uint32_t stage_mask);
 AIF_API aif_status aif_profile_end(aif_ctx *ctx, double *ms_sum, int32_t *n_calls);
 
 /* Which kernel family serves a stage of this context: 0 = shape-agnostic fp32
- * kernels, 1 = bf16 MFMA kernels.  stage is one of the AIF_STAGE_* values. */
+ * kernels, 1 = bf16 MFMA kernels.  stage is one of the AIF_STAGE_* values.
+ * For AIF_STAGE_GATHER the answer describes the LAST scoring call: 0 = the table
+ * was indexed by a launch of its own (timed as that stage), 2 = by the attention
+ * kernel, which then reads the item vectors from the table and writes them to the
+ * workspace itself (the gather stage's time is then only the user fold and the
+ * packing of K/V; the gather's bytes are moved under the attention stage). */
 AIF_API int32_t aif_stage_kind(const aif_ctx *ctx, int32_t stage);
 
 #ifdef __cplusplus

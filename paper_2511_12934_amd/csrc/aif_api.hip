@@ -57,6 +57,7 @@ struct aif_ctx {
     DevBuf bad;                       // int32 counter
     size_t x_rows = 0;
     int n_cu = 256;                   // compute units of the device (sizes the attention groups)
+    bool attn_indexed = false;        // the last scoring call's attention kernel read the item table itself
 
     // descriptor staging ring
     char *h_stage = nullptr;          // pinned
@@ -72,6 +73,7 @@ struct aif_ctx {
     // optional per-kernel event timing
     bool prof_on = false;
     int prof_max = 0, prof_batch_calls = 0, prof_topk_calls = 0;
+    uint32_t prof_mask = 0;               // bit per AIF_STAGE_*: the stages whose bounding events are recorded
     std::vector<hipEvent_t> prof_batch;   // 5 events per recorded aif_score_batch
     std::vector<hipEvent_t> prof_topk;    // 2 events per recorded aif_topk
 };
@@ -366,25 +368,35 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
 
     hipEvent_t *pe = nullptr;
     if (c->prof_on && c->prof_batch_calls < c->prof_max) pe = &c->prof_batch[(size_t)5 * c->prof_batch_calls++];
-    if (pe) HIP_TRY(c, hipEventRecord(pe[0], s));
+    // event i stands before stage i of {gather, user fold, attention, MLP} and after stage i - 1
+    auto mark = [&](int i) -> hipError_t {
+        const uint32_t need = (i < 4 ? 1u << i : 0u) | (i > 0 ? 1u << (i - 1) : 0u);
+        return pe && (c->prof_mask & need) ? hipEventRecord(pe[i], s) : hipSuccess;
+    };
+    HIP_TRY(c, mark(0));
     const bool fused = stage_fusable(m, c->mfma);
+    // with the request's K/V resident and no W_q, the attention kernel takes its query pieces from the table itself
+    const bool attn_indexes = fused && attn_gathers(m, b, c->mfma);
+    c->attn_indexed = attn_indexes;
     if (fused) {
-        // gather, user fold and K/V packing as one launch; timed as the gather stage
+        // gather (unless the attention kernel does it), user fold and K/V packing as one launch; timed as the gather stage
         HIP_TRY(c, launch_stage(m, b, c->table, c->X.p, (int32_t *)c->bad.p, (const float *)c->w1u.p,
-                                c->has_bias[0] ? (const float *)c->bias[0].p : nullptr, (float *)c->bias1.p, c->mfma, s));
-        if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
+                                c->has_bias[0] ? (const float *)c->bias[0].p : nullptr, (float *)c->bias1.p, c->mfma,
+                                !attn_indexes, s));
+        HIP_TRY(c, mark(1));
     } else {
         HIP_TRY(c, launch_gather(m, b, c->table, c->X.p, (int32_t *)c->bad.p, s));
-        if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
+        HIP_TRY(c, mark(1));
         HIP_TRY(c, launch_user_fold(m, b, (const float *)c->w1u.p, c->has_bias[0] ? (const float *)c->bias[0].p : nullptr,
                                     (float *)c->bias1.p, s));
     }
-    if (pe) HIP_TRY(c, hipEventRecord(pe[2], s));
+    HIP_TRY(c, mark(2));
     if (c->mfma.attn)
-        HIP_TRY(c, launch_attn_mfma(m, b, c->X.p, c->mfma, fused, s));
+        HIP_TRY(c, launch_attn_mfma(m, b, c->X.p, c->mfma, fused, s, attn_indexes ? c->table : nullptr,
+                                    attn_indexes ? (int32_t *)c->bad.p : nullptr));
     else
         HIP_TRY(c, launch_attn_generic(m, b, c->X.p, c->has_wq ? (const float *)c->wq.p : nullptr, c->max_seq_len, s));
-    if (pe) HIP_TRY(c, hipEventRecord(pe[3], s));
+    HIP_TRY(c, mark(3));
     if (c->mfma.mlp) {
         const float *bf[MAX_LAYERS];
         for (int l = 0; l < m.n_layers; ++l) bf[l] = c->has_bias[l] ? (const float *)c->bias[l].p : nullptr;
@@ -398,10 +410,10 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         }
         HIP_TRY(c, launch_mlp_generic(m, b, c->X.p, gw, (const float *)c->bias1.p, s));
     }
-    if (pe) HIP_TRY(c, hipEventRecord(pe[4], s));
+    HIP_TRY(c, mark(4));
     if (k > 0) {
         hipEvent_t *pt = nullptr;
-        if (c->prof_on && c->prof_topk_calls < c->prof_max) pt = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
+        if (c->prof_on && (c->prof_mask & (1u << AIF_STAGE_TOPK)) && c->prof_topk_calls < c->prof_max) pt = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
         if (pt) HIP_TRY(c, hipEventRecord(pt[0], s));
         HIP_TRY(c, launch_topk((const TopkDesc *)(d + toff), n_req, k, idx_out, val_out, s));
         if (pt) HIP_TRY(c, hipEventRecord(pt[1], s));
@@ -459,7 +471,8 @@ aif_status aif_topk(aif_ctx *c, const float *const *logits, const int32_t *n_can
     }
     HIP_TRY(c, hipMemcpyAsync(d, h, (size_t)n_req * sizeof(TopkDesc), hipMemcpyHostToDevice, s));
     hipEvent_t *pe = nullptr;
-    if (c->prof_on && c->prof_topk_calls < c->prof_max) pe = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
+    if (c->prof_on && (c->prof_mask & (1u << AIF_STAGE_TOPK)) && c->prof_topk_calls < c->prof_max)
+        pe = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
     if (pe) HIP_TRY(c, hipEventRecord(pe[0], s));
     HIP_TRY(c, launch_topk(d, n_req, k, idx_out, val_out, s));
     if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
@@ -526,8 +539,14 @@ aif_status aif_peek_features(aif_ctx *c, int32_t request, int32_t first_row, int
 
 aif_status aif_profile_begin(aif_ctx *c, int32_t max_calls)
 {
+    return aif_profile_begin_stages(c, max_calls, (1u << AIF_STAGE_COUNT) - 1);
+}
+
+aif_status aif_profile_begin_stages(aif_ctx *c, int32_t max_calls, uint32_t stage_mask)
+{
     if (!c) return AIF_EINVAL;
     if (max_calls <= 0 || max_calls > 100000) return fail(c, AIF_EINVAL, "max_calls out of range");
+    if (stage_mask == 0 || stage_mask >= (1u << AIF_STAGE_COUNT)) return fail(c, AIF_EINVAL, "stage_mask names no stage");
     aif_status st = check_device(c);
     if (st != AIF_OK) return st;
     while ((int)c->prof_batch.size() < 5 * max_calls) {
@@ -541,6 +560,7 @@ aif_status aif_profile_begin(aif_ctx *c, int32_t max_calls)
         c->prof_topk.push_back(e);
     }
     c->prof_max = max_calls;
+    c->prof_mask = stage_mask;
     c->prof_batch_calls = c->prof_topk_calls = 0;
     c->prof_on = true;
     return AIF_OK;
@@ -557,8 +577,9 @@ aif_status aif_profile_end(aif_ctx *c, double *ms_sum, int32_t *n_calls)
     }
     for (int j = 0; j < c->prof_batch_calls; ++j) {
         hipEvent_t *pe = &c->prof_batch[(size_t)5 * j];
-        HIP_TRY(c, hipEventSynchronize(pe[4]));
         for (int st = 0; st < 4; ++st) {
+            if (!(c->prof_mask & (1u << st))) continue;
+            HIP_TRY(c, hipEventSynchronize(pe[st + 1]));
             float ms = 0.f;
             HIP_TRY(c, hipEventElapsedTime(&ms, pe[st], pe[st + 1]));
             ms_sum[st] += ms;
@@ -580,6 +601,7 @@ aif_status aif_profile_end(aif_ctx *c, double *ms_sum, int32_t *n_calls)
 int32_t aif_stage_kind(const aif_ctx *c, int32_t stage)
 {
     if (!c) return -1;
+    if (stage == AIF_STAGE_GATHER) return c->attn_indexed ? 2 : 0;
     if (stage == AIF_STAGE_ATTENTION) return c->mfma.attn ? 1 : 0;
     if (stage == AIF_STAGE_MLP) return c->mfma.mlp ? 1 : 0;
     return 0;

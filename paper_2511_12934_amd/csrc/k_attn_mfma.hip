@@ -314,6 +314,12 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
 // key tile t + 1 is issued before the exponentials of key tile t, so the matrix
 // cores work under the vector ALU.  Per candidate the arithmetic, and its order,
 // is that of k_attn_mfma: the two kernels give the same bits.
+//
+// GATHER: the kernel is also a1 (Sec. 3.2, the index into the table of item vectors).  Without W_q the query
+// pieces a lane needs ARE pieces of its candidate's item vector, so it takes them straight from the table
+// row its id names -- asked for a whole item ahead, like the workspace rows otherwise -- and sets them down in
+// the workspace for the MLP on the way.  The separate gather launch, its write of the item block and this
+// kernel's read of it fall away.  An id outside the table reads row 0 and is counted, as in the gather kernel.
 // ---------------------------------------------------------------------------
 constexpr int RES_WAVES = 16;
 constexpr int RES_LDS_FRAGS = 152;            // 1 KB fragments of K/V that may stay resident
@@ -321,10 +327,11 @@ constexpr int RES_MAX_HEADS = 64;
 constexpr int RES_MAX_ITEM_PIECES = 256;      // d_item / 8 the Hadamard operand may have to stay in LDS
 constexpr int RES_LDS_BYTES = RES_LDS_FRAGS * 1024 + RES_MAX_HEADS * 4 + RES_MAX_ITEM_PIECES * 16 + 16;
 
-template <int DH>
+template <int DH, bool GATHER>
 __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, char *__restrict__ X, XLayout xl,
                                                              const char *__restrict__ kvpack, size_t pack_stride,
-                                                             const float *__restrict__ kmax, int nktp)
+                                                             const float *__restrict__ kmax, int nktp,
+                                                             const char *__restrict__ table, int32_t *__restrict__ bad)
 {
     constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32;
     extern __shared__ __align__(16) char lds[];
@@ -390,12 +397,34 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         if (lane == 0) t = atomicAdd(s_next, 1);
         return __builtin_amdgcn_readfirstlane(t);
     };
+    // GATHER: the id of this lane's candidate in a tile as the request gives it (0 past the request's end), and
+    // the table row it names
+    auto raw_id = [&](int t) {
+        const int lc = (g.t0 + t) * 32 + col;
+        return lc < rd.n_cand ? rd.cand_ids[lc] : 0;
+    };
+    auto checked = [&](int raw) {
+        if (raw < 0 || (int64_t)raw >= m.n_items) {
+            if (h == 0) atomicAdd(bad, 1);
+            raw = 0;
+        }
+        return raw;
+    };
+    auto table_row = [&](int id) { return table + (size_t)id * (size_t)(m.d_item * 2); };
     bf16x8 q[JS];
     int tile = wave, hd = 0;
+    int id = 0;                             // GATHER: row of the table the current item's candidate has
     if (tile < n_tiles) {
-        const char *xr = row_of(tile);
+        if constexpr (GATHER) {
+            id = checked(raw_id(tile));
+            const char *tr = table_row(id);
 #pragma unroll
-        for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(2 * j + h) * xl.piece_stride);
+            for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(tr + (2 * j + h) * 16);
+        } else {
+            const char *xr = row_of(tile);
+#pragma unroll
+            for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(2 * j + h) * xl.piece_stride);
+        }
     }
     while (tile < n_tiles) {
         int next_tile = tile, next_hd = hd + 1;
@@ -403,10 +432,21 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
             next_hd = 0;
             next_tile = take_tile();
         }
+        // the next tile's id is asked for now and looked at only when this item's last S product has been issued
+        int next_raw = 0;
+        if constexpr (GATHER)
+            if (next_hd == 0 && next_tile < n_tiles) next_raw = raw_id(next_tile);
         const int local = (g.t0 + tile) * 32 + col;
         const bool live = local < rd.n_cand;
         char *xrow = row_of(tile);
         auto piece = [&](int p) { return (bf16x8 *)(xrow + (size_t)p * xl.piece_stride); };
+        if constexpr (GATHER) {
+            // a1: this head's slice of the item vector goes into the workspace
+            if (live) {
+#pragma unroll
+                for (int j = 0; j < JS; ++j) *piece(hd * (DH / 8) + 2 * j + h) = q[j];
+            }
+        }
 
         // real-time half of the cross features: the query pieces ARE item-vector pieces (no W_q here),
         // so the ones this lane holds are multiplied in place; the stores drain under the attention loop
@@ -422,16 +462,25 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                     store_stream(piece(pc_cross + pc), o8);
                 }
             }
-            // item-vector pieces beyond the attention width (d_item > d_attn)
-            if (hd == H - 1)
-                for (int pc = m.d_attn / 8 + h; pc < m.d_item / 8; pc += 2) {
-                    const bf16x8 e = *piece(pc), u = su[pc];
+        }
+        // item-vector pieces beyond the attention width (d_item > d_attn)
+        if ((hadamard || GATHER) && live && hd == H - 1)
+            for (int pc = m.d_attn / 8 + h; pc < m.d_item / 8; pc += 2) {
+                bf16x8 e;
+                if constexpr (GATHER) {
+                    e = *(const bf16x8 *)(table_row(id) + pc * 16);
+                    store_stream(piece(pc), e);
+                } else {
+                    e = *piece(pc);
+                }
+                if (hadamard) {
+                    const bf16x8 u = su[pc];
                     bf16x8 o8;
 #pragma unroll
                     for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)e[s] * (float)u[s]);
                     store_stream(piece(pc_cross + pc), o8);
                 }
-        }
+            }
 
         // Algorithm 1 step 4, once per tile: the row's bridge weights against the user-side vectors
         if (bea && hd == 0) {
@@ -545,9 +594,16 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         }
         // the last S product of this item is on its way: the next item's query may take the registers
         if (next_tile < n_tiles) {
-            const char *xr = row_of(next_tile);
+            if constexpr (GATHER) {
+                if (next_hd == 0) id = checked(next_raw);
+                const char *tr = table_row(id);
 #pragma unroll
-            for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(next_hd * (DH / 8) + 2 * j + h) * xl.piece_stride);
+                for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(tr + (next_hd * (DH / 8) + 2 * j + h) * 16);
+            } else {
+                const char *xr = row_of(next_tile);
+#pragma unroll
+                for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(next_hd * (DH / 8) + 2 * j + h) * xl.piece_stride);
+            }
         }
         if (nkt > 0) finish_tile(nkt - 1, S, 32 * nkt > L);
 
@@ -624,24 +680,32 @@ size_t attn_pack_stride(const Model &m, int max_seq_len, int *nktp_out)
 
 template <int DH, int WAVES>
 static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char *kvpack, size_t stride, float *kmax,
-                                   int nktp, bool kv_packed, hipStream_t s)
+                                   int nktp, bool kv_packed, const void *gather_table, int32_t *bad, hipStream_t s)
 {
     constexpr int LDS = 4 * 2 * (DH / 8) * 1024, ROWS = WAVES * 32;
     if (nktp > 0 && !kv_packed)
         hipLaunchKernelGGL(k_pack_kv<DH>, dim3(nktp / 2, m.n_heads, b.n_req), dim3(256), 0, s, m, b, kvpack, stride, kmax, nktp);
     if (b.n_groups > 0) {
         constexpr int RES_LDS = RES_LDS_BYTES;
-        auto kern = k_attn_res<DH>;
         static bool attr_set = false;
         if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, RES_LDS);
+            hipError_t e = hipFuncSetAttribute((const void *)k_attn_res<DH, false>, hipFuncAttributeMaxDynamicSharedMemorySize, RES_LDS);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute((const void *)k_attn_res<DH, true>, hipFuncAttributeMaxDynamicSharedMemorySize, RES_LDS);
             if (e != hipSuccess) return e;
             attr_set = true;
         }
-        hipLaunchKernelGGL(kern, dim3(b.n_groups), dim3(RES_WAVES * 64), RES_LDS, s, m, b, (char *)X, x_layout(m),
-                           (const char *)kvpack, stride, (const float *)kmax, nktp);
+        if (gather_table)
+            hipLaunchKernelGGL((k_attn_res<DH, true>), dim3(b.n_groups), dim3(RES_WAVES * 64), RES_LDS, s, m, b, (char *)X,
+                               x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp,
+                               (const char *)gather_table, bad);
+        else
+            hipLaunchKernelGGL((k_attn_res<DH, false>), dim3(b.n_groups), dim3(RES_WAVES * 64), RES_LDS, s, m, b, (char *)X,
+                               x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp, (const char *)nullptr,
+                               (int32_t *)nullptr);
         return hipGetLastError();
     }
+    if (gather_table) return hipErrorInvalidValue;      // only the resident kernel gathers: the caller asked attn_gathers()
     hipLaunchKernelGGL((k_attn_mfma<DH, WAVES>), dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), LDS, s, m, b,
                        (char *)X, x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp);
     return hipGetLastError();
@@ -662,7 +726,17 @@ static bool small_batch(const Batch &b)
     return b.n_blk < n_cu;
 }
 
-hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s)
+// Whether the attention launch of this batch also indexes the item table (k_attn_res with GATHER): K/V resident
+// (the batch has tile groups), no W_q (the plan's variants 0 and 1), and no cross block that reads the item row
+// through the workspace inside the kernel (BEA).
+bool attn_gathers(const Model &m, const Batch &b, const MfmaPlan &plan)
+{
+    return m.dtype == 1 && plan.attn && (plan.attn_variant == 0 || plan.attn_variant == 1) && b.n_groups > 0 && b.n_blk > 0 &&
+           m.cross_mode != 3;
+}
+
+hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed,
+                               const void *gather_table, int32_t *bad, hipStream_t s)
 {
     if (b.n_blk == 0) return hipSuccess;
     char *kvpack = plan.kvpack;
@@ -670,13 +744,13 @@ hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const Mf
     const size_t stride = plan.pack_stride;
     const int nktp = plan.nktp;
     switch (plan.attn_variant) {
-    case ATTN_VARIANT_PROJ: return launch_attn_proj(m, b, X, plan, small_batch(b), s);
+    case ATTN_VARIANT_PROJ: return gather_table ? hipErrorInvalidValue : launch_attn_proj(m, b, X, plan, small_batch(b), s);
     case 0:
-        return small_batch(b) ? launch_attn_spec<64, 2>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s)
-                              : launch_attn_spec<64, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s);
+        return small_batch(b) ? launch_attn_spec<64, 2>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s)
+                              : launch_attn_spec<64, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s);
     case 1:
-        return small_batch(b) ? launch_attn_spec<32, 2>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s)
-                              : launch_attn_spec<32, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, s);
+        return small_batch(b) ? launch_attn_spec<32, 2>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s)
+                              : launch_attn_spec<32, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -41,12 +41,16 @@ int attn_plan_groups(const Model &m, const ReqDesc *reqs /*host*/, int n_req, in
 size_t attn_max_groups(size_t x_rows, int max_users);
 
 // kv_packed: the batch's K/V are already in fragment order (launch_stage did it)
-hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s);
+// gather_table: non-null only when attn_gathers(m, b, plan): the attention kernel then reads the item vectors from
+// the table itself (the caller has not run the gather) and counts ids outside the table in *bad
+hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s,
+                            const void *gather_table = nullptr, int32_t *bad = nullptr);
+bool attn_gathers(const Model &m, const Batch &b, const MfmaPlan &plan);
 
 // k_stage.hip: gather + user fold + K/V packing as one launch (bf16 models served by the MFMA attention kernel)
 bool stage_fusable(const Model &m, const MfmaPlan &plan);
 hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad, const float *w1u,
-                        const float *b1, float *bias1, const MfmaPlan &plan, hipStream_t s);
+                        const float *b1, float *bias1, const MfmaPlan &plan, bool gather, hipStream_t s);
 
 // bias_f32[l] / wlast_f32: the context's fp32 copies (bias of layer l or null; last layer's weight row).
 hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const MfmaPlan &plan,
@@ -67,7 +71,8 @@ hipError_t launch_mlp_layers(const Model &m, const Batch &b, const void *X, cons
 // k_attn_mfma.hip
 int attn_mfma_variant(const Model &m, bool has_wq);
 size_t attn_pack_stride(const Model &m, int max_seq_len, int *nktp_out);
-hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s);
+hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed,
+                               const void *gather_table, int32_t *bad, hipStream_t s);
 constexpr int ATTN_VARIANT_PROJ = 2;      // attn_variant of the projection + 16-wide-heads kernel (k_attn_proj.hip)
 
 // k_attn_proj.hip: query projection, 16-wide heads, Hadamard / segment-dot cross

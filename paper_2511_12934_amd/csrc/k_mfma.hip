@@ -79,9 +79,10 @@ void mfma_release(MfmaPlan &plan)
     }
 }
 
-hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s)
+hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s,
+                            const void *gather_table, int32_t *bad)
 {
-    return launch_attn_variant(m, b, X, plan, kv_packed, s);
+    return launch_attn_variant(m, b, X, plan, kv_packed, gather_table, bad, s);
 }
 
 hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const MfmaPlan &plan,

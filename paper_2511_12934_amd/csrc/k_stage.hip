@@ -68,7 +68,7 @@ bool stage_fusable(const Model &m, const MfmaPlan &plan)
 }
 
 hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad, const float *w1u,
-                        const float *b1, float *bias1, const MfmaPlan &plan, hipStream_t s)
+                        const float *b1, float *bias1, const MfmaPlan &plan, bool gather, hipStream_t s)
 {
     if (b.n_req == 0) return hipSuccess;
     StageArgs a;
@@ -90,7 +90,8 @@ hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void 
     a.quads = (m.dims[1] + FOLD_FEATS - 1) / FOLD_FEATS;
     a.n_pack = b.n_req * m.n_heads * a.stages;
     a.n_fold = b.n_req * a.quads;
-    return m.d_head == 64 ? launch_stage_dh<64>(a, b.n_blk, s) : launch_stage_dh<32>(a, b.n_blk, s);
+    const int n_gather = gather ? b.n_blk : 0;      // none when the attention kernel indexes the table itself
+    return m.d_head == 64 ? launch_stage_dh<64>(a, n_gather, s) : launch_stage_dh<32>(a, n_gather, s);
 }
 
 }  // namespace aif

@@ -820,6 +820,40 @@ def test_bad_ids_on_the_fragment_order_workspace(R, torch, shape):
     assert ctx2.aif_poll_device_errors() == 0
 
 
+def test_profiling_times_the_selected_stages_only(R, torch):
+    """aif_profile_begin brackets every stage of a scoring call with events, aif_profile_begin_stages only the
+    stages named; the results are the same either way.  The batch's K/V fit one compute unit's LDS and there is
+    no W_q, so the attention kernel indexes the item table itself and the library says so."""
+    cfg = small_cfg("bf16", n_items=5000, seq_len=40, **MFMA_SHAPES["c3_like"])
+    _say("profiling")
+    rng = np.random.default_rng(5)
+    model = wl.make_model(cfg, seed=3)
+    table = wl.make_table_host(cfg, rng)
+    table_dev = R.to_device(table, cfg.dtype)
+    sampler = wl.IdSampler(cfg)
+    users_ids = [(wl.make_user(cfg, rng, seq_len=40), sampler.sample(rng, 300)) for _ in range(3)]
+    zs, _, drs, ctx = run_batch(R, torch, cfg, model, table_dev, users_ids, max_seq_len=40)
+    assert ctx.aif_stage_kind("gather") == 2 and ctx.aif_stage_kind("attention") == 1
+    ctx.aif_profile_begin(4)
+    for _ in range(2):
+        ctx.aif_score_batch([d.req for d in drs])
+    torch.cuda.synchronize()
+    prof = ctx.aif_profile_end()
+    for st in ("gather", "user_fold", "attention", "mlp"):
+        assert prof[st][1] == 2 and prof[st][0] >= 0.0, (st, prof[st])
+    assert prof["topk"][1] == 0
+    ctx.aif_profile_begin_stages(4, ["mlp"])
+    ctx.aif_score_batch([d.req for d in drs])
+    torch.cuda.synchronize()
+    prof = ctx.aif_profile_end()
+    assert prof["mlp"][1] == 1 and prof["mlp"][0] > 0.0
+    assert all(prof[st] == (0.0, 0) for st in ("gather", "user_fold", "attention", "topk")), prof
+    for d, z in zip(drs, zs):
+        assert np.array_equal(d.logits.cpu().numpy(), z)
+    with pytest.raises(Exception):
+        ctx.aif_profile_begin_stages(4, [])
+
+
 def test_host_side_errors_enqueue_nothing(R, torch):
     from paper_2511_12934_amd import binding as B
     cfg = small_cfg("f32")
