@@ -104,19 +104,27 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
         s_remaining[0] = (uint32_t)kk;
     }
     if (tid < 256) hist[tid] = 0;
+    // every load is issued before the first is looked at: positions past the end re-read the last logit (a load
+    // under a condition of its own would be waited for on the spot, twenty round trips in a row)
     uint32_t kreg[TK_CACHED];
+    {
+        float zv[TK_CACHED];
 #pragma unroll
-    for (int j = 0; j < TK_CACHED; ++j) {
-        const int i = tid + j * TK_THREADS;
-        kreg[j] = i < n ? logit_key(z[i]) : 0u;
+        for (int j = 0; j < TK_CACHED; ++j) {
+            const int i = tid + j * TK_THREADS;
+            zv[j] = z[i < n ? i : n - 1];
+        }
+#pragma unroll
+        for (int j = 0; j < TK_CACHED; ++j) kreg[j] = tid + j * TK_THREADS < n ? logit_key(zv[j]) : 0u;
     }
     // ---- shortcut: one counting pass over value bins -------------------------------------------------
     if (n <= TK_CACHED * TK_THREADS) {
+        const int nj = (n + TK_THREADS - 1) / TK_THREADS;                // register slots in use (the same in every thread)
         float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
         for (int j = 0; j < TK_CACHED; ++j) {
             const float v = key_logit(kreg[j]);
-            if (tid + j * TK_THREADS < n && fabsf(v) < INFINITY) {      // finite (a NaN compares false)
+            if (j < nj && tid + j * TK_THREADS < n && fabsf(v) < INFINITY) {      // finite (a NaN compares false)
                 lo = fminf(lo, v);
                 hi = fmaxf(hi, v);
             }
@@ -141,9 +149,15 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
         }
         const float scale = (float)TKF_BINS / (hi - lo);
         if (hi > lo && scale < INFINITY) {                              // the same decision in every thread
+            int bin[TK_CACHED];                                         // kept for the collection below (-1: no candidate)
 #pragma unroll
-            for (int j = 0; j < TK_CACHED; ++j)
-                if (tid + j * TK_THREADS < n) atomicAdd(&fhist[value_bin(kreg[j], lo, scale)], 1u);
+            for (int j = 0; j < TK_CACHED; ++j) {
+                bin[j] = -1;
+                if (j < nj && tid + j * TK_THREADS < n) {
+                    bin[j] = value_bin(kreg[j], lo, scale);
+                    atomicAdd(&fhist[bin[j]], 1u);
+                }
+            }
             __syncthreads();
             // suffix sums over the bins, two bins a thread: S[b] = candidates in bins >= b
             const uint32_t h0 = fhist[2 * tid], h1 = fhist[2 * tid + 1];
@@ -173,19 +187,34 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
 #pragma unroll
                 for (int j = 0; j < TK_CACHED; ++j) {
                     const int i = tid + j * TK_THREADS;
-                    if (i < n && value_bin(kreg[j], lo, scale) >= bstar)
+                    if (bin[j] >= bstar)
                         sel[atomicAdd(&s_cnt, 1u)] = ((unsigned long long)kreg[j] << 32) | (0xFFFFFFFFu - (uint32_t)i);
                 }
+                fhist[tid] = 0;                 // the bins are done with: their first words take the ranks
                 __syncthreads();
-                // rank by counting: the pairs are distinct, so the ranks are a permutation
-                if ((uint32_t)tid < total) {
-                    const unsigned long long mine = sel[tid];
-                    uint32_t rank = 0;
-                    for (uint32_t j = 0; j < total; ++j) rank += sel[j] > mine ? 1u : 0u;
+                // rank by counting: the pairs are distinct, so the ranks are a permutation.  All 1024 threads
+                // count: the list is cut into TK_THREADS / P runs (P = the power of two that holds the selected),
+                // thread (e, c) counts how many of run c beat candidate e, and the runs' counts are added up.
+                int lg = 6;
+                while ((1u << lg) < total) ++lg;
+                const uint32_t e = (uint32_t)tid & ((1u << lg) - 1u), c = (uint32_t)tid >> lg, runs = (uint32_t)TK_THREADS >> lg;
+                const uint32_t len = (total + runs - 1) / runs, j0 = c * len, j1 = j0 + len < total ? j0 + len : total;
+                unsigned long long mine = 0ull;
+                if (e < total) {
+                    mine = sel[e];
+                    uint32_t part = 0;
+                    for (uint32_t j = j0; j < j1; ++j) part += sel[j] > mine ? 1u : 0u;
+                    if (part) atomicAdd(&fhist[e], part);
+                }
+                __syncthreads();
+                if (c == 0 && e < total) {
+                    const uint32_t rank = fhist[e];
                     if (rank < (uint32_t)kk) {
                         const uint32_t i = 0xFFFFFFFFu - (uint32_t)(mine & 0xFFFFFFFFull);
+                        const uint32_t key = (uint32_t)(mine >> 32);
                         idx_o[rank] = (int32_t)i;
-                        val_o[rank] = z[i];
+                        // the key gives the logit back bit for bit, except where it merges values (NaNs, the two zeros)
+                        val_o[rank] = key == 0u || key == 0x80000000u ? z[i] : key_logit(key);
                     }
                 }
                 return;
