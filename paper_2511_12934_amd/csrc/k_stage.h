@@ -196,24 +196,48 @@ __device__ __forceinline__ void pack_kv_block(int r, int hd, int st, const Model
     const uint16_t *K = (const uint16_t *)rd->seq_keys, *V = (const uint16_t *)rd->seq_vals;
     const int da = m.d_attn, o = hd * DH;
     uint4 *dst = (uint4 *)(kvpack + (size_t)r * pack_stride + ((size_t)(hd * nktp + 2 * st) * FR) * 1024);
-    // one 16-byte piece (a lane's share of a fragment) per thread and step
-    for (int pc = threadIdx.x; pc < 2 * FR * 64; pc += 256) {
+    // One 16-byte piece (a lane's share of a fragment) per thread and step.  Every load is issued before the first
+    // is looked at: keys past the sequence's end re-read its last key and are zeroed afterwards (a load under a
+    // condition of its own is waited for on the spot -- eight round trips in a row for a piece of V).
+    constexpr int STEPS = 2 * FR * 64 / 256;
+    uint4 kpiece[STEPS];
+    uint32_t ve[STEPS][8];
+#pragma unroll
+    for (int it = 0; it < STEPS; ++it) {
+        const int pc = threadIdx.x + 256 * it;
         const int k2 = pc / (FR * 64), rem = pc - k2 * (FR * 64);
         const int frag = rem >> 6, lane = rem & 63;
         const int kt = 2 * st + k2, hh = lane >> 5;
-        uint4 out = make_uint4(0, 0, 0, 0);
-        if (frag < JS) {
+        if (frag < JS) {                                        // the same for a whole wave
             const int t = 32 * kt + (lane & 31);
-            if (t < L) out = *(const uint4 *)(K + (size_t)t * da + o + 16 * frag + 8 * hh);
+            kpiece[it] = *(const uint4 *)(K + (size_t)(t < L ? t : L - 1) * da + o + 16 * frag + 8 * hh);
         } else {
             const int fv = frag - JS, jj = fv / FT, ft = fv - jj * FT;
             const int f = o + 32 * ft + (lane & 31), t0 = 32 * kt + 16 * jj + 4 * hh;
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl) {                   // slot sl <-> key t0 + 8 (sl / 4) + sl % 4
+                const int t = t0 + 8 * (sl >> 2) + (sl & 3);
+                ve[it][sl] = V[(size_t)(t < L ? t : L - 1) * da + f];
+            }
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < STEPS; ++it) {
+        const int pc = threadIdx.x + 256 * it;
+        const int k2 = pc / (FR * 64), rem = pc - k2 * (FR * 64);
+        const int frag = rem >> 6, lane = rem & 63;
+        const int kt = 2 * st + k2, hh = lane >> 5;
+        uint4 out;
+        if (frag < JS) {
+            out = 32 * kt + (lane & 31) < L ? kpiece[it] : make_uint4(0, 0, 0, 0);
+        } else {
+            const int jj = (frag - JS) / FT, t0 = 32 * kt + 16 * jj + 4 * hh;
             uint32_t w[4];
 #pragma unroll
             for (int p2 = 0; p2 < 4; ++p2) {                 // slots 2 p2 and 2 p2 + 1
                 const int ta = t0 + 8 * ((2 * p2) >> 2) + ((2 * p2) & 3), tb = ta + 1;
-                const uint32_t lo = ta < L ? V[(size_t)ta * da + f] : 0u;
-                const uint32_t hi = tb < L ? V[(size_t)tb * da + f] : 0u;
+                const uint32_t lo = ta < L ? ve[it][2 * p2] : 0u;
+                const uint32_t hi = tb < L ? ve[it][2 * p2 + 1] : 0u;
                 w[p2] = lo | (hi << 16);
             }
             out = make_uint4(w[0], w[1], w[2], w[3]);
