@@ -24,7 +24,7 @@ struct MlpPack {
     const char *w[3];                  // hidden layers' weights in fragment order
     const float *bias[3];              // fp32 biases of hidden layers 2, 3 (index 1, 2), never null; [0] unused
     const float *wlast;                // fp32 weights of the final ->1 layer
-    const float *blast;                // its bias (1 float) or null
+    const float *blast;                // its bias (1 float), never null
 };
 
 // Decide which MFMA kernels can serve the model and pack their weights

@@ -95,7 +95,7 @@ hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const 
         pk.bias[l] = bias_f32[l] ? bias_f32[l] : plan.zeros;
     }
     pk.wlast = wlast_f32;
-    pk.blast = bias_f32[m.n_layers - 1];
+    pk.blast = bias_f32[m.n_layers - 1] ? bias_f32[m.n_layers - 1] : plan.zeros;
     if (plan.mlp_variant == MLP_VARIANT_LAYERS) return launch_mlp_layers(m, b, X, pk, bias1, plan.hbuf, s);
     return launch_mlp_variant(plan.mlp_variant, m, b, X, pk, bias1, s);
 }

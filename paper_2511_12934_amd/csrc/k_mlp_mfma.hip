@@ -72,7 +72,7 @@ template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS> struct C
     static constexpr int kinit(int KS) { return epos(3, KS) + 1; }
     static constexpr int LPW = SF / WAVES;                                      // loads per wave and stage
     static constexpr int HL = NH == 1 ? H1 : (NH == 2 ? H2 : H3);              // width entering the ->1 layer
-    static constexpr int bias_floats = 2 * H1 + H2 + H3 + HL;                  // layer-1 biases (per request): one set per tile of the pair
+    static constexpr int bias_floats = 2 * H1 + H2 + H3 + HL + 1;              // layer-1 biases (per request): one set per tile of the pair; the ->1 layer's bias last
     static constexpr int ring_bytes = SLOTS * SF * 1024;
     static constexpr int lds_bytes = ring_bytes + 4 * bias_floats;
     static_assert(SF % WAVES == 0, "every wave moves the same number of fragments per stage");
@@ -166,28 +166,63 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(int64_t n_items, con
         for (int j = 0; j < K1 / 16; ++j) xin[j] = *(const bf16x8 *)(xr + (size_t)(2 * j) * xl.piece_stride);
     };
     load_xin(tile0);
-    const int r0 = blk_req[tile0 / (ROW_BLOCK / ROWS)];
-    const int r1 = has_next ? blk_req[(tile0 + 1) / (ROW_BLOCK / ROWS)] : r0;
+    // ... and so are the layers' own biases and the ->1 weights (into registers; LDS gets them below)
+    constexpr int N1 = (H1 + THREADS - 1) / THREADS, N2 = (H2 + THREADS - 1) / THREADS, N3 = (H3 + THREADS - 1) / THREADS,
+                  NL = (C::HL + THREADS - 1) / THREADS;
+    float g2[N2 ? N2 : 1], g3[N3 ? N3 : 1], gl[NL], gb = pk.blast[0];
+    auto at = [&](const float *p, int n, int i) { return p[i < n ? i : n - 1]; };       // a thread past the end re-reads the last word
+    if (C::NH >= 2)
+#pragma unroll
+        for (int j = 0; j < N2; ++j) g2[j] = at(pk.bias[1], H2, threadIdx.x + j * THREADS);
+    if (C::NH >= 3)
+#pragma unroll
+        for (int j = 0; j < N3; ++j) g3[j] = at(pk.bias[2], H3, threadIdx.x + j * THREADS);
+#pragma unroll
+    for (int j = 0; j < NL; ++j) gl[j] = at(pk.wlast, C::HL, threadIdx.x + j * THREADS);
+    // The request lookup: tile -> request (both tiles' at once) -> descriptors (both at once) -> layer-1 biases and
+    // candidate ids (all at once).  Three round trips in a row, none of them behind a load it does not depend on.
+    const int t1 = has_next ? tile0 + 1 : tile0;
+    const int r0 = blk_req[tile0 / (ROW_BLOCK / ROWS)], r1 = blk_req[t1 / (ROW_BLOCK / ROWS)];
     const Out rd0 = out_of(r0), rd1 = out_of(r1);
+    float g1[N1];
+#pragma unroll
+    for (int j = 0; j < N1; ++j) g1[j] = at(bias1 + (size_t)r0 * H1, H1, threadIdx.x + j * THREADS);
     // Which lanes will store a result, and which of them carry an id outside the table, is settled here, as two
     // wave masks per tile: the tile's end then has no load to wait for before its stores.
-    uint64_t live0, bad0, live1, bad1;
-    auto id_masks = [&](int tile, const Out &rd, uint64_t &live, uint64_t &bad) {
-        const int local = tile * ROWS - rd.row_base + wave * 32 + col;
-        const bool lv = h == 0 && local < rd.n_cand;
-        const int64_t id = lv ? (int64_t)rd.cand_ids[local] : 0;
-        live = __ballot(lv);
-        bad = __ballot(lv && (id < 0 || id >= n_items));
-    };
-    id_masks(tile0, rd0, live0, bad0);
-    id_masks(has_next ? tile0 + 1 : tile0, rd1, live1, bad1);
-    const float bl = pk.blast ? pk.blast[0] : 0.f;
-    for (int i = threadIdx.x; i < H1; i += THREADS) sb1[i] = bias1[(size_t)r0 * H1 + i];
+    // (position 0 stands in for a lane with no candidate)
+    const int lc0 = tile0 * ROWS - rd0.row_base + wave * 32 + col, lc1 = t1 * ROWS - rd1.row_base + wave * 32 + col;
+    const bool lv0 = h == 0 && lc0 < rd0.n_cand, lv1 = h == 0 && lc1 < rd1.n_cand;
+    const int64_t id0 = rd0.cand_ids[lv0 ? lc0 : 0], id1 = rd1.cand_ids[lv1 ? lc1 : 0];
+    // Everything asked for above is pinned here, the ids still in flight: left alone the compiler moves a load down
+    // into the condition its value is stored under, behind the wait of whatever comes before it.
+#pragma unroll
+    for (int j = 0; j < N1; ++j) asm volatile("" : "+v"(g1[j])::"memory");
     if (C::NH >= 2)
-        for (int i = threadIdx.x; i < H2; i += THREADS) sb2[i] = pk.bias[1][i];
+#pragma unroll
+        for (int j = 0; j < N2; ++j) asm volatile("" : "+v"(g2[j])::"memory");
     if (C::NH >= 3)
-        for (int i = threadIdx.x; i < H3; i += THREADS) sb3[i] = pk.bias[2][i];
-    for (int i = threadIdx.x; i < C::HL; i += THREADS) swl[i] = pk.wlast[i];
+#pragma unroll
+        for (int j = 0; j < N3; ++j) asm volatile("" : "+v"(g3[j])::"memory");
+#pragma unroll
+    for (int j = 0; j < NL; ++j) asm volatile("" : "+v"(gl[j])::"memory");
+    asm volatile("" : "+v"(gb)::"memory");
+    const uint64_t live0 = __ballot(lv0), live1 = __ballot(lv1);
+    const uint64_t bad0 = __ballot(lv0 && (id0 < 0 || id0 >= n_items)), bad1 = __ballot(lv1 && (id1 < 0 || id1 >= n_items));
+    if (threadIdx.x == 0) swl[C::HL] = gb;
+#pragma unroll
+    for (int j = 0; j < N1; ++j)
+        if ((int)threadIdx.x + j * THREADS < H1) sb1[threadIdx.x + j * THREADS] = g1[j];
+    if (C::NH >= 2)
+#pragma unroll
+        for (int j = 0; j < N2; ++j)
+            if ((int)threadIdx.x + j * THREADS < H2) sb2[threadIdx.x + j * THREADS] = g2[j];
+    if (C::NH >= 3)
+#pragma unroll
+        for (int j = 0; j < N3; ++j)
+            if ((int)threadIdx.x + j * THREADS < H3) sb3[threadIdx.x + j * THREADS] = g3[j];
+#pragma unroll
+    for (int j = 0; j < NL; ++j)
+        if ((int)threadIdx.x + j * THREADS < C::HL) swl[threadIdx.x + j * THREADS] = gl[j];
     wait_vmcnt<0>();
     __syncthreads();
 
@@ -242,7 +277,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(int64_t n_items, con
         }
     };
     auto finish = [&](int tile, const Out &rd, uint64_t live, uint64_t bad) {      // the tile's logits and scores
-        float z = zpart + __shfl_xor(zpart, 32, 64) + bl;
+        float z = zpart + __shfl_xor(zpart, 32, 64) + swl[C::HL];
         const int local = tile * ROWS - rd.row_base + wave * 32 + col;
         if ((live >> lane) & 1) {
             if ((bad >> lane) & 1) z = __uint_as_float(0x7FC00000u);
