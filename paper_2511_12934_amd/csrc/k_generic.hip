@@ -53,6 +53,30 @@ hipError_t launch_user_fold(const Model &m, const Batch &b, const float *w1u, co
 // ---------------------------------------------------------------------------
 constexpr int ATTN_TS = 16;
 
+// sum_k a(k) * b(k) for k in [0, n), in order, with the loads of sixteen terms (then eight) issued before the first
+// is used: a loop of load-then-multiply is waited for once per term -- a memory round trip each.
+template <int U, class FA, class FB> __device__ __forceinline__ void dot_batches(int n, int &k, float &acc, FA a, FB b)
+{
+    for (; k + U <= n; k += U) {
+        float av[U], bv[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+            av[j] = a(k + j);
+            bv[j] = b(k + j);
+        }
+#pragma unroll
+        for (int j = 0; j < U; ++j) acc += av[j] * bv[j];
+    }
+}
+template <class FA, class FB> __device__ __forceinline__ float dot_in_order(int n, float acc, FA a, FB b)
+{
+    int k = 0;
+    dot_batches<16>(n, k, acc, a, b);
+    dot_batches<8>(n, k, acc, a, b);
+    for (; k < n; ++k) acc += a(k) * b(k);
+    return acc;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void k_attn_generic(Model m, Batch b, T *__restrict__ X,
                                                       const float *__restrict__ wq, int per_wave)
@@ -89,8 +113,8 @@ __global__ __launch_bounds__(256) void k_attn_generic(Model m, Batch b, T *__res
             for (int q = lane; q < da; q += 64) {
                 float acc;
                 if (wq) {
-                    acc = 0.f;
-                    for (int k = 0; k < m.d_item; ++k) acc += wq[(size_t)q * m.d_item + k] * sh_e[k];
+                    const float *wr = wq + (size_t)q * m.d_item;
+                    acc = dot_in_order(m.d_item, 0.f, [&](int k) { return wr[k]; }, [&](int k) { return sh_e[k]; });
                 } else
                     acc = sh_e[q];
                 sh_q[q] = acc;
@@ -102,8 +126,7 @@ __global__ __launch_bounds__(256) void k_attn_generic(Model m, Batch b, T *__res
             if (on)
                 for (int t = lane; t < L; t += 64) {
                     const T *kr = K + (size_t)t * da + o;
-                    float acc = 0.f;
-                    for (int k = 0; k < dh; ++k) acc += sh_q[o + k] * ld_f<T>(kr + k);
+                    float acc = dot_in_order(dh, 0.f, [&](int k) { return sh_q[o + k]; }, [&](int k) { return ld_f<T>(kr + k); });
                     acc *= scale;
                     sh_s[t] = acc;
                     mx = fmaxf(mx, acc);
@@ -120,8 +143,8 @@ __global__ __launch_bounds__(256) void k_attn_generic(Model m, Batch b, T *__res
             __syncthreads();
             if (on)
                 for (int k = lane; k < dh; k += 64) {
-                    float acc = 0.f;
-                    for (int t = 0; t < L; ++t) acc += sh_s[t] * ld_f<T>(V + (size_t)t * da + o + k);
+                    const float acc = dot_in_order(L, 0.f, [&](int t) { return sh_s[t]; },
+                                                   [&](int t) { return ld_f<T>(V + (size_t)t * da + o + k); });
                     st_f<T>(xrow + m.d_item + o + k, L > 0 ? acc / sum : 0.f);
                 }
             __syncthreads();
@@ -134,16 +157,16 @@ __global__ __launch_bounds__(256) void k_attn_generic(Model m, Batch b, T *__res
                 const int S = m.d_item / m.d_cv;
                 for (int idx = lane; idx < m.d_cross; idx += 64) {
                     const int j = idx / S, sg = idx - j * S;
-                    float acc = 0.f;
-                    for (int k = 0; k < m.d_cv; ++k) acc += ld_f<T>(uc + (size_t)j * m.d_cv + k) * sh_e[sg * m.d_cv + k];
+                    const float acc = dot_in_order(m.d_cv, 0.f, [&](int k) { return ld_f<T>(uc + (size_t)j * m.d_cv + k); },
+                                                   [&](int k) { return sh_e[sg * m.d_cv + k]; });
                     st_f<T>(xc + idx, acc);
                 }
             } else if (m.cross_mode == 3) {
                 // Algorithm 1 step 4: the row's trailing n_cross entries weigh the user-side vectors
                 const int w0 = m.d_item - m.n_cross;
                 for (int idx = lane; idx < m.d_cv; idx += 64) {
-                    float acc = 0.f;
-                    for (int j = 0; j < m.n_cross; ++j) acc += sh_e[w0 + j] * ld_f<T>(uc + (size_t)j * m.d_cv + idx);
+                    const float acc = dot_in_order(m.n_cross, 0.f, [&](int j) { return sh_e[w0 + j]; },
+                                                   [&](int j) { return ld_f<T>(uc + (size_t)j * m.d_cv + idx); });
                     st_f<T>(xc + idx, acc);
                 }
             }
@@ -217,8 +240,7 @@ __global__ __launch_bounds__(256) void k_mlp_generic(Model m, Batch b, const T *
             const float b0 = l == 0 ? bias1[(size_t)r * N + n] : (w.bias[l] ? w.bias[l][n] : 0.f);
 #pragma unroll
             for (int c = 0; c < MLP_TS; ++c) acc[c] = b0;
-            for (int k = 0; k < K; ++k) {
-                const float wv = wt[(size_t)k * N + n];
+            auto term = [&](int k, float wv) {
                 const float4 *xp = (const float4 *)(bufA + k * MLP_TS);
 #pragma unroll
                 for (int c4 = 0; c4 < MLP_TS / 4; ++c4) {
@@ -228,7 +250,24 @@ __global__ __launch_bounds__(256) void k_mlp_generic(Model m, Batch b, const T *
                     acc[c4 * 4 + 2] += wv * x.z;
                     acc[c4 * 4 + 3] += wv * x.w;
                 }
+            };
+            // sixteen weights in flight (terms still added in order of k): one at a time is a memory round trip per k
+            int k = 0;
+            for (; k + 16 <= K; k += 16) {
+                float wv[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) wv[j] = wt[(size_t)(k + j) * N + n];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) term(k + j, wv[j]);
             }
+            for (; k + 4 <= K; k += 4) {
+                float wv[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) wv[j] = wt[(size_t)(k + j) * N + n];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) term(k + j, wv[j]);
+            }
+            for (; k < K; ++k) term(k, wt[(size_t)k * N + n]);
 #pragma unroll
             for (int c = 0; c < MLP_TS; ++c) bufB[n * MLP_TS + c] = last ? acc[c] : fmaxf(acc[c], 0.f);
         }
