@@ -61,6 +61,7 @@ struct aif_ctx {
 
     // descriptor staging ring
     char *h_stage = nullptr;          // pinned
+    char *h_stage_dev = nullptr;      // its device mapping (null: none, uploads go through hipMemcpyAsync)
     DevBuf d_stage;
     size_t slot_bytes = 0;
     hipEvent_t ev[NSLOT] = {};
@@ -122,6 +123,15 @@ void destroy(aif_ctx *c)
     for (auto e : c->prof_batch) (void)hipEventDestroy(e);
     for (auto e : c->prof_topk) (void)hipEventDestroy(e);
     delete c;
+}
+
+// The first `bytes` of a staging slot, host -> device, on the caller's stream: by a kernel that reads the pinned
+// buffer through its device mapping (coherent host memory: never cached on the device), else by a copy command.
+static hipError_t upload(aif_ctx *c, int slot, size_t bytes, hipStream_t s)
+{
+    const size_t off = (size_t)slot * c->slot_bytes;
+    if (c->h_stage_dev) return launch_upload(c->h_stage_dev + off, (char *)c->d_stage.p + off, bytes, s);
+    return hipMemcpyAsync((char *)c->d_stage.p + off, c->h_stage + off, bytes, hipMemcpyHostToDevice, s);
 }
 
 // Take the next staging slot, waiting (normally not at all) for the call that
@@ -258,7 +268,16 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
     }
     sb += (size_t)c->max_users * sizeof(TopkDesc) + 16;     // aif_score_topk stages both tables in one slot
     c->slot_bytes = (sb + 255) / 256 * 256;
-    HIP_TRY(nullptr, hipHostMalloc((void **)&c->h_stage, c->slot_bytes * NSLOT, hipHostMallocDefault));
+    // coherent and mapped, so that a kernel may read it (upload()); if that is refused: plain pinned memory and copies
+    if (hipHostMalloc((void **)&c->h_stage, c->slot_bytes * NSLOT, hipHostMallocCoherent | hipHostMallocMapped) == hipSuccess) {
+        void *mapped = nullptr;
+        if (hipHostGetDevicePointer(&mapped, c->h_stage, 0) == hipSuccess) c->h_stage_dev = (char *)mapped;
+        else (void)hipGetLastError();
+    } else {
+        (void)hipGetLastError();
+        c->h_stage = nullptr;
+        HIP_TRY(nullptr, hipHostMalloc((void **)&c->h_stage, c->slot_bytes * NSLOT, hipHostMallocDefault));
+    }
     HIP_TRY(nullptr, c->d_stage.alloc(c->slot_bytes * NSLOT));
     for (int i = 0; i < NSLOT; ++i) HIP_TRY(nullptr, hipEventCreateWithFlags(&c->ev[i], hipEventDisableTiming | hipEventDisableSystemFence));
     HIP_TRY(nullptr, hipStreamSynchronize(s));
@@ -364,7 +383,7 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         }
         bytes = toff + (size_t)n_req * sizeof(TopkDesc);
     }
-    HIP_TRY(c, hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, s));
+    HIP_TRY(c, upload(c, slot, bytes, s));
 
     hipEvent_t *pe = nullptr;
     if (c->prof_on && c->prof_batch_calls < c->prof_max) pe = &c->prof_batch[(size_t)5 * c->prof_batch_calls++];
@@ -469,7 +488,7 @@ aif_status aif_topk(aif_ctx *c, const float *const *logits, const int32_t *n_can
         h[r].logits = logits[r];
         h[r].n = n_cand[r];
     }
-    HIP_TRY(c, hipMemcpyAsync(d, h, (size_t)n_req * sizeof(TopkDesc), hipMemcpyHostToDevice, s));
+    HIP_TRY(c, upload(c, slot, (size_t)n_req * sizeof(TopkDesc), s));
     hipEvent_t *pe = nullptr;
     if (c->prof_on && (c->prof_mask & (1u << AIF_STAGE_TOPK)) && c->prof_topk_calls < c->prof_max)
         pe = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];

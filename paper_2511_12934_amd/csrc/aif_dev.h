@@ -95,6 +95,9 @@ hipError_t launch_gather(const Model &m, const Batch &b, const void *table, void
                          hipStream_t s);
 
 // Sec. 3.4, incremental update: table[ids[i]] = rows[i] in 16-byte pieces; bad ids write nothing and bump *bad.
+// src_mapped: the device mapping of a pinned host buffer (hipHostGetDevicePointer); bytes are rounded up to 16,
+// both buffers must hold the rounded size
+hipError_t launch_upload(const void *src_mapped, void *dst, size_t bytes, hipStream_t s);
 hipError_t launch_update_rows(const Model &m, void *table, const int32_t *ids, const void *rows, int n, int32_t *bad,
                               hipStream_t s);
 

@@ -105,4 +105,23 @@ hipError_t launch_update_rows(const Model &m, void *table, const int32_t *ids, c
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// The per-call descriptor tables, pinned host memory -> device: a few KB.  As a kernel that reads the host
+// buffer through its device mapping the copy is one more launch on the caller's stream; as a copy command it
+// goes to a copy engine and back, which kept the stream idle for some 20 us between two calls.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_upload(const uint4 *__restrict__ src, uint4 *__restrict__ dst, int n16)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
+}
+
+hipError_t launch_upload(const void *src_mapped, void *dst, size_t bytes, hipStream_t s)
+{
+    const int n16 = (int)((bytes + 15) / 16);
+    if (n16 == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_upload, dim3((n16 + 255) / 256), dim3(256), 0, s, (const uint4 *)src_mapped, (uint4 *)dst, n16);
+    return hipGetLastError();
+}
+
 }  // namespace aif
