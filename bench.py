@@ -458,7 +458,7 @@ def main():
         args.warmup = 200 if sustained else 5
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (requests shard by user with no exchange; "
-                 "see DESIGN.md); run with --gpus 1")
+                 "one process per GPU); run with --gpus 1")
 
     if args.workload.startswith("L"):
         return main_lsh(args)

@@ -3,6 +3,8 @@
 // index.  The jobs do not depend on one another; all are read by the attention
 // kernel that follows.  The small, latency-bound jobs come first in the grid so
 // that they run under the HBM-bound gather instead of before or after it.
+// When the attention kernel that follows indexes the item table itself (k_attn_res with
+// GATHER) the grid has no gather blocks.
 #include "k_mfma.h"
 #include "k_stage.h"
 

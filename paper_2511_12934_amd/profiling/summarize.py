@@ -2,7 +2,7 @@
 of ``rocprofv3 --kernel-trace --stats``) into a short text table of per-kernel
 durations, and a ``--pmc`` database into per-kernel counter averages.
 
-    python -m paper_2511_12934_amd.profiling.summarize gpurun_out/prof/c3_results.db [--pmc]
+    python -m paper_2511_12934_amd.profiling.summarize prof/c3_results.db [--pmc]
 """
 from __future__ import annotations
 
