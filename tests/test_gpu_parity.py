@@ -298,9 +298,11 @@ def test_resident_and_streaming_attention_give_the_same_bits(R, torch):
     torch.cuda.synchronize()
     z_alone = da.logits.cpu().numpy().copy()
     x_alone = R.peek_features(ctx, cfg, 0, ia.size)
+    assert ctx.aif_stage_kind("gather") == 2, "the resident attention kernel indexes the item table itself"
     da.logits.fill_(float("nan"))
     ctx.aif_score_batch([da.req, db.req])
     torch.cuda.synchronize()
+    assert ctx.aif_stage_kind("gather") == 0, "with the streaming kernel the gather is a launch of its own"
     assert np.array_equal(R.peek_features(ctx, cfg, 0, ia.size), x_alone)
     assert np.array_equal(da.logits.cpu().numpy(), z_alone)
     assert_logits_close("bf16", z_alone, oracle_scores(cfg, model, table, ua, ia, n_threads=4).logits, "resident")
