@@ -448,6 +448,8 @@ def main():
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5", "B3", "A3", "U1", "U3", "N3", "L1", "L2", "L3"])
     ap.add_argument("--id-sets", type=int, default=4,
                     help="distinct candidate lists per user, taken in turn by consecutive steps")
+    ap.add_argument("--profile-every", type=int, default=8,
+                    help="inside the timed region the dominant kernel of every n-th step is timed with events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true")
     args = ap.parse_args()
@@ -492,7 +494,9 @@ def main():
     prof = w.ctx.aif_profile_end()
     dom = max(("gather", "attention", "mlp"), key=lambda s: prof[s][0] / max(prof[s][1], 1))
 
-    w.ctx.aif_profile_begin_stages(args.steps, [dom])
+    # ... and of it one launch in eight: an event keeps the stream idle for 4-5 us, two per step were 2 % of C3's step
+    every = args.profile_every if args.steps >= 8 * args.profile_every else 1
+    w.ctx.aif_profile_begin_sampled(args.steps, [dom], every)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         w.step()

@@ -209,6 +209,11 @@ AIF_API aif_status aif_profile_begin(aif_ctx *ctx, int32_t max_calls);
  * recorded (an event costs a few microseconds on the stream), the others'
  * ms_sum and n_calls come back 0.  AIF_EINVAL if the mask names no stage. */
 AIF_API aif_status aif_profile_begin_stages(aif_ctx *ctx, int32_t max_calls, uint32_t stage_mask);
+/* The same, recording only every `every`-th scoring call (and every `every`-th
+ * aif_topk) from the first on: max_calls bounds the RECORDED calls, n_calls of
+ * aif_profile_end counts them.  For long runs, where the events of every call
+ * would cost more stream time than the timing is worth.  AIF_EINVAL if every < 1. */
+AIF_API aif_status aif_profile_begin_sampled(aif_ctx *ctx, int32_t max_calls, uint32_t stage_mask, int32_t every);
 AIF_API aif_status aif_profile_end(aif_ctx *ctx, double *ms_sum, int32_t *n_calls);
 
 /* Which kernel family serves a stage of this context: 0 = shape-agnostic fp32

@@ -21,7 +21,7 @@ AIF_CROSS_NONE, AIF_CROSS_HADAMARD, AIF_CROSS_SEGDOT, AIF_CROSS_BEA = 0, 1, 2, 3
 EXPORTS = ("aif_score_init", "aif_score_request", "aif_score_batch", "aif_topk", "aif_score_destroy",
            "aif_last_error", "aif_poll_device_errors", "aif_peek_features", "aif_profile_begin",
            "aif_profile_end", "aif_stage_kind", "aif_update_rows", "aif_swap_table", "aif_score_topk",
-           "aif_profile_begin_stages")
+           "aif_profile_begin_stages", "aif_profile_begin_sampled")
 STAGES = ("gather", "user_fold", "attention", "mlp", "topk")
 LSH_EXPORTS = ("aif_lsh_init", "aif_lsh_batch", "aif_lsh_destroy", "aif_lsh_last_error",
                "aif_lsh_poll_device_errors", "aif_lsh_profile_begin", "aif_lsh_profile_end")
@@ -109,6 +109,8 @@ def load():
     lib.aif_profile_begin.argtypes = [vp, C.c_int32]
     lib.aif_profile_begin_stages.restype = C.c_int
     lib.aif_profile_begin_stages.argtypes = [vp, C.c_int32, C.c_uint32]
+    lib.aif_profile_begin_sampled.restype = C.c_int
+    lib.aif_profile_begin_sampled.argtypes = [vp, C.c_int32, C.c_uint32, C.c_int32]
     lib.aif_profile_end.restype = C.c_int
     lib.aif_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     lib.aif_stage_kind.restype = C.c_int32
@@ -267,6 +269,12 @@ class Context:
         for s in stages:
             mask |= 1 << STAGES.index(s)
         self._check(self._lib.aif_profile_begin_stages(self._h, max_calls, mask))
+
+    def aif_profile_begin_sampled(self, max_calls: int, stages, every: int):
+        mask = 0
+        for s in stages:
+            mask |= 1 << STAGES.index(s)
+        self._check(self._lib.aif_profile_begin_sampled(self._h, max_calls, mask, every))
 
     def aif_profile_end(self):
         """{stage: (summed ms, recorded calls)}"""

@@ -75,6 +75,7 @@ struct aif_ctx {
     bool prof_on = false;
     int prof_max = 0, prof_batch_calls = 0, prof_topk_calls = 0;
     uint32_t prof_mask = 0;               // bit per AIF_STAGE_*: the stages whose bounding events are recorded
+    int prof_every = 1, prof_seen_batch = 0, prof_seen_topk = 0;   // only every prof_every-th call is recorded
     std::vector<hipEvent_t> prof_batch;   // 5 events per recorded aif_score_batch
     std::vector<hipEvent_t> prof_topk;    // 2 events per recorded aif_topk
 };
@@ -386,7 +387,8 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
     HIP_TRY(c, upload(c, slot, bytes, s));
 
     hipEvent_t *pe = nullptr;
-    if (c->prof_on && c->prof_batch_calls < c->prof_max) pe = &c->prof_batch[(size_t)5 * c->prof_batch_calls++];
+    if (c->prof_on && c->prof_batch_calls < c->prof_max && c->prof_seen_batch++ % c->prof_every == 0)
+        pe = &c->prof_batch[(size_t)5 * c->prof_batch_calls++];
     // event i stands before stage i of {gather, user fold, attention, MLP} and after stage i - 1
     auto mark = [&](int i) -> hipError_t {
         const uint32_t need = (i < 4 ? 1u << i : 0u) | (i > 0 ? 1u << (i - 1) : 0u);
@@ -432,7 +434,9 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
     HIP_TRY(c, mark(4));
     if (k > 0) {
         hipEvent_t *pt = nullptr;
-        if (c->prof_on && (c->prof_mask & (1u << AIF_STAGE_TOPK)) && c->prof_topk_calls < c->prof_max) pt = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
+        if (c->prof_on && (c->prof_mask & (1u << AIF_STAGE_TOPK)) && c->prof_topk_calls < c->prof_max &&
+            c->prof_seen_topk++ % c->prof_every == 0)
+            pt = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
         if (pt) HIP_TRY(c, hipEventRecord(pt[0], s));
         HIP_TRY(c, launch_topk((const TopkDesc *)(d + toff), n_req, k, idx_out, val_out, s));
         if (pt) HIP_TRY(c, hipEventRecord(pt[1], s));
@@ -490,7 +494,8 @@ aif_status aif_topk(aif_ctx *c, const float *const *logits, const int32_t *n_can
     }
     HIP_TRY(c, upload(c, slot, (size_t)n_req * sizeof(TopkDesc), s));
     hipEvent_t *pe = nullptr;
-    if (c->prof_on && (c->prof_mask & (1u << AIF_STAGE_TOPK)) && c->prof_topk_calls < c->prof_max)
+    if (c->prof_on && (c->prof_mask & (1u << AIF_STAGE_TOPK)) && c->prof_topk_calls < c->prof_max &&
+        c->prof_seen_topk++ % c->prof_every == 0)
         pe = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
     if (pe) HIP_TRY(c, hipEventRecord(pe[0], s));
     HIP_TRY(c, launch_topk(d, n_req, k, idx_out, val_out, s));
@@ -563,7 +568,13 @@ aif_status aif_profile_begin(aif_ctx *c, int32_t max_calls)
 
 aif_status aif_profile_begin_stages(aif_ctx *c, int32_t max_calls, uint32_t stage_mask)
 {
+    return aif_profile_begin_sampled(c, max_calls, stage_mask, 1);
+}
+
+aif_status aif_profile_begin_sampled(aif_ctx *c, int32_t max_calls, uint32_t stage_mask, int32_t every)
+{
     if (!c) return AIF_EINVAL;
+    if (every < 1) return fail(c, AIF_EINVAL, "every must be at least 1");
     if (max_calls <= 0 || max_calls > 100000) return fail(c, AIF_EINVAL, "max_calls out of range");
     if (stage_mask == 0 || stage_mask >= (1u << AIF_STAGE_COUNT)) return fail(c, AIF_EINVAL, "stage_mask names no stage");
     aif_status st = check_device(c);
@@ -580,6 +591,8 @@ aif_status aif_profile_begin_stages(aif_ctx *c, int32_t max_calls, uint32_t stag
     }
     c->prof_max = max_calls;
     c->prof_mask = stage_mask;
+    c->prof_every = every;
+    c->prof_seen_batch = c->prof_seen_topk = 0;
     c->prof_batch_calls = c->prof_topk_calls = 0;
     c->prof_on = true;
     return AIF_OK;

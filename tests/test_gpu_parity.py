@@ -852,8 +852,16 @@ def test_profiling_times_the_selected_stages_only(R, torch):
     assert all(prof[st] == (0.0, 0) for st in ("gather", "user_fold", "attention", "topk")), prof
     for d, z in zip(drs, zs):
         assert np.array_equal(d.logits.cpu().numpy(), z)
+    ctx.aif_profile_begin_sampled(4, ["mlp"], 2)                 # every second call: calls 0 and 2 of 3
+    for _ in range(3):
+        ctx.aif_score_batch([d.req for d in drs])
+    torch.cuda.synchronize()
+    prof = ctx.aif_profile_end()
+    assert prof["mlp"][1] == 2 and prof["mlp"][0] > 0.0, prof
     with pytest.raises(Exception):
         ctx.aif_profile_begin_stages(4, [])
+    with pytest.raises(Exception):
+        ctx.aif_profile_begin_sampled(4, ["mlp"], 0)
 
 
 def test_host_side_errors_enqueue_nothing(R, torch):
