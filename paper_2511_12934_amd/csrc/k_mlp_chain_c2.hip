@@ -1,12 +1,12 @@
-// The fused MLP chain (k_mlp_chain.h) for one shape -- C2: 192 -> 256 -> 128 -> 1 after the user fold; waves per block, fragments per
-// stage, ring slots: 8, 32, 4.
+// The fused MLP chain (k_mlp_chain.h) for one shape -- C2: 192 -> 256 -> 128 -> 1 after the user fold; waves per block,
+// fragments per stage, ring slots: 4, 16, 4.
 #include "k_mlp_chain.h"
 
 namespace aif {
 
 hipError_t mlp_chain_c2(const Model &m, const Batch &b, const void *X, const MlpPack &pk, const float *bias1, hipStream_t s)
 {
-    return launch_spec<192, 256, 128, 0, 8, 32, 4>(m, b, X, pk, bias1, s);
+    return launch_spec<192, 256, 128, 0, 4, 16, 4>(m, b, X, pk, bias1, s);
 }
 
 }  // namespace aif

@@ -6,7 +6,7 @@ namespace aif {
 
 hipError_t mlp_chain_c3(const Model &m, const Batch &b, const void *X, const MlpPack &pk, const float *bias1, hipStream_t s)
 {
-    return launch_spec<192, 512, 256, 0, 8, 32, 4>(m, b, X, pk, bias1, s);
+    return launch_spec<192, 512, 256, 0, 4, 16, 4>(m, b, X, pk, bias1, s);
 }
 
 }  // namespace aif

@@ -26,7 +26,6 @@
 namespace aif {
 
 hipError_t mlp_chain_c2(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
-hipError_t mlp_chain_c2_small(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 hipError_t mlp_chain_c3(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 hipError_t mlp_chain_c4(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 
@@ -56,18 +55,6 @@ hipError_t pack_frag(const void *W, int n_in, int col0, int N, int K, bool from_
 }
 
 // ---- dispatch -----------------------------------------------------------------
-static int n_cu()
-{
-    static int n = 0;
-    if (!n) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        n = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
-                ? prop.multiProcessorCount : 256;
-    }
-    return n;
-}
-
 int mlp_mfma_variant(const Model &m)
 {
     if (m.dtype != 1) return -1;
@@ -84,11 +71,7 @@ hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const
 {
     if (b.n_blk == 0) return hipSuccess;
     switch (variant) {
-    case 0:
-        // a batch that cannot give every compute unit a 256-candidate tile (a single request of 10^4 is 40) goes
-        // in 128-candidate tiles: twice the units at work
-        if (b.n_blk < n_cu()) return mlp_chain_c2_small(m, b, X, pk, bias1, s);
-        return mlp_chain_c2(m, b, X, pk, bias1, s);
+    case 0: return mlp_chain_c2(m, b, X, pk, bias1, s);
     case 1: return mlp_chain_c3(m, b, X, pk, bias1, s);
     case 2: return mlp_chain_c4(m, b, X, pk, bias1, s);
     default: return hipErrorInvalidValue;
