@@ -403,11 +403,11 @@ static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, con
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    // Two tiles per block where there are tiles to spare: the last two per compute unit go one per block, after
-    // the pairs, so that the launch ends evenly (a pair on a unit while others idle would cost more than the
-    // pairs save), and a batch of up to that many tiles keeps every unit it can reach busy.
+    // Two tiles per block where there are tiles to spare: the last tile of every block a compute unit holds at a time
+    // goes one per block, after the pairs, so that the launch ends evenly (a pair on a unit while others idle would
+    // cost more than the pairs save), and a batch of up to that many tiles keeps every unit it can reach busy.
     const int n_tiles = b.n_blk * (ROW_BLOCK / ROWS);
-    const int per_cu = 2 * (8 / WAVES);               // blocks of eight waves' worth of registers a unit holds: 8 / WAVES
+    const int per_cu = 8 / WAVES;                     // blocks of eight waves' worth of registers a unit holds
     int n_single = n_tiles < per_cu * n_cu() ? n_tiles : per_cu * n_cu();
     if ((n_tiles - n_single) & 1) ++n_single;
     const int n_pairs = (n_tiles - n_single) / 2;
