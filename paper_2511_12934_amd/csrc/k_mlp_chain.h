@@ -103,7 +103,8 @@ __device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
 }
 
 // K1: layer-1 contraction after the user fold; H1..H3: hidden widths (0 = absent).
-// One wave = 32 candidates; a block = WAVES waves sharing the weight ring.
+// One wave = 32 candidates; a block = WAVES waves sharing the weight ring (four waves and a 64 KB ring in every
+// shape that is built: two such blocks share a compute unit, out of phase with each other).
 //
 // The body is one straight line of nf() steps, one MFMA each.  Step F
 //   - asks LDS for the fragment of step F + RING - 1 (a ring of RING fragment registers keeps the
@@ -117,7 +118,7 @@ __device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
 //     read by anyone) and refills the slot of stage I - 1 with stage I + SLOTS - 1.
 // The barrier is hand-issued: the compiler's own would first drain the LDS reads in flight.
 //
-// A block takes TWO tiles of 256 candidates, 2 g and 2 g + 1, and runs the body twice.  What a block has to
+// A block takes TWO tiles of WAVES * 32 candidates, 2 g and 2 g + 1, and runs the body twice.  What a block has to
 // wait for in a row before its first MFMA -- request lookup, then its biases, then the first weights: 12,000
 // cycles against the 36,000 of a tile's stream on the 256 -> 512 -> 256 head -- is paid once per pair: the
 // second tile's weight stream, fragment registers and bias preload are the first tile's running on (pass 1

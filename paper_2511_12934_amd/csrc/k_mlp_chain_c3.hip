@@ -1,5 +1,5 @@
 // The fused MLP chain (k_mlp_chain.h) for one shape -- C3: 192 -> 512 -> 256 -> 1 after the user fold; waves per block, fragments per
-// stage, ring slots: 8, 32, 4.
+// stage, ring slots: 4, 16, 4.
 #include "k_mlp_chain.h"
 
 namespace aif {
