@@ -131,8 +131,7 @@ void destroy(aif_ctx *c)
 static hipError_t upload(aif_ctx *c, int slot, size_t bytes, hipStream_t s)
 {
     const size_t off = (size_t)slot * c->slot_bytes;
-    if (c->h_stage_dev) return launch_upload(c->h_stage_dev + off, (char *)c->d_stage.p + off, bytes, s);
-    return hipMemcpyAsync((char *)c->d_stage.p + off, c->h_stage + off, bytes, hipMemcpyHostToDevice, s);
+    return staging_upload(c->h_stage, c->h_stage_dev, off, (char *)c->d_stage.p + off, bytes, s);
 }
 
 // Take the next staging slot, waiting (normally not at all) for the call that
@@ -269,16 +268,7 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
     }
     sb += (size_t)c->max_users * sizeof(TopkDesc) + 16;     // aif_score_topk stages both tables in one slot
     c->slot_bytes = (sb + 255) / 256 * 256;
-    // coherent and mapped, so that a kernel may read it (upload()); if that is refused: plain pinned memory and copies
-    if (hipHostMalloc((void **)&c->h_stage, c->slot_bytes * NSLOT, hipHostMallocCoherent | hipHostMallocMapped) == hipSuccess) {
-        void *mapped = nullptr;
-        if (hipHostGetDevicePointer(&mapped, c->h_stage, 0) == hipSuccess) c->h_stage_dev = (char *)mapped;
-        else (void)hipGetLastError();
-    } else {
-        (void)hipGetLastError();
-        c->h_stage = nullptr;
-        HIP_TRY(nullptr, hipHostMalloc((void **)&c->h_stage, c->slot_bytes * NSLOT, hipHostMallocDefault));
-    }
+    HIP_TRY(nullptr, staging_alloc(c->slot_bytes * NSLOT, &c->h_stage, &c->h_stage_dev));
     HIP_TRY(nullptr, c->d_stage.alloc(c->slot_bytes * NSLOT));
     for (int i = 0; i < NSLOT; ++i) HIP_TRY(nullptr, hipEventCreateWithFlags(&c->ev[i], hipEventDisableTiming | hipEventDisableSystemFence));
     HIP_TRY(nullptr, hipStreamSynchronize(s));

@@ -98,6 +98,11 @@ hipError_t launch_gather(const Model &m, const Batch &b, const void *table, void
 // src_mapped: the device mapping of a pinned host buffer (hipHostGetDevicePointer); bytes are rounded up to 16,
 // both buffers must hold the rounded size
 hipError_t launch_upload(const void *src_mapped, void *dst, size_t bytes, hipStream_t s);
+// Pinned host memory for the per-call descriptor tables: coherent and mapped, so that a kernel may read it
+// (*mapped = its device address); where that is refused plain pinned memory, *mapped = null.  Freed with hipHostFree.
+hipError_t staging_alloc(size_t bytes, char **host, char **mapped);
+// bytes [off, off + bytes) of such a buffer -> dst, on stream s: launch_upload if mapped, else a copy command
+hipError_t staging_upload(const char *host, const char *mapped, size_t off, void *dst, size_t bytes, hipStream_t s);
 hipError_t launch_update_rows(const Model &m, void *table, const int32_t *ids, const void *rows, int n, int32_t *bad,
                               hipStream_t s);
 

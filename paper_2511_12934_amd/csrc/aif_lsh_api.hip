@@ -3,6 +3,7 @@
 //   user-side partial sums -> their reduction -> LSH-DIN -> SimTier.
 #include "../../include/aif_lsh.h"
 #include "aif_lsh_dev.h"
+#include "aif_dev.h"
 
 #include <cstdarg>
 #include <cstdio>
@@ -25,7 +26,7 @@ struct aif_lsh_ctx {
     int max_seq_len = 0, max_candidates = 0, max_users = 0, max_chunks = 0;
     const uint8_t *table = nullptr;
     void *part = nullptr, *A = nullptr, *bad = nullptr;     // device workspace (owned)
-    char *h_stage = nullptr;                                // pinned ring of descriptor tables
+    char *h_stage = nullptr, *h_stage_dev = nullptr;        // pinned ring of descriptor tables, its device mapping (or null)
     void *d_stage = nullptr;
     size_t slot_bytes = 0;
     hipEvent_t ev[LSH_NSLOT] = {};
@@ -114,7 +115,7 @@ aif_status linit(const aif_lsh_config *cfg, const uint8_t *table, aif_lsh_ctx *c
     LSH_TRY(nullptr, hipMemset(c->bad, 0, 16));
     const size_t n_blk_max = (size_t)c->max_users * ((c->max_candidates + LSH_BLOCK - 1) / LSH_BLOCK);
     c->slot_bytes = ((size_t)c->max_users * sizeof(LshReqDesc) + n_blk_max * sizeof(int32_t) + 255) / 256 * 256;
-    LSH_TRY(nullptr, hipHostMalloc((void **)&c->h_stage, c->slot_bytes * LSH_NSLOT, hipHostMallocDefault));
+    LSH_TRY(nullptr, staging_alloc(c->slot_bytes * LSH_NSLOT, &c->h_stage, &c->h_stage_dev));
     LSH_TRY(nullptr, hipMalloc(&c->d_stage, c->slot_bytes * LSH_NSLOT));
     for (int i = 0; i < LSH_NSLOT; ++i)
         LSH_TRY(nullptr, hipEventCreateWithFlags(&c->ev[i], hipEventDisableTiming | hipEventDisableSystemFence));
@@ -197,7 +198,7 @@ aif_status aif_lsh_batch(aif_lsh_ctx *c, const aif_lsh_request *reqs, int32_t n_
     b.n_req = n_req;
     b.n_blk = slots / LSH_BLOCK;
     const size_t bytes = (size_t)n_req * sizeof(LshReqDesc) + (size_t)b.n_blk * sizeof(int32_t);
-    LSH_TRY(c, hipMemcpyAsync(d, h, bytes, hipMemcpyHostToDevice, s));
+    LSH_TRY(c, staging_upload(c->h_stage, c->h_stage_dev, (size_t)slot * c->slot_bytes, d, bytes, s));
 
     hipEvent_t *pe = nullptr;
     if (c->prof_on && c->prof_calls < c->prof_max) pe = &c->prof[(size_t)LSH_EV_PER_CALL * c->prof_calls++];

@@ -34,7 +34,7 @@ struct aif_user_ctx {
     void *wseq_frag = nullptr, *wffn_frag = nullptr;                                  // bf16 MFMA fragments (owned)
     void *X = nullptr, *part = nullptr;                                               // workspace (owned)
     MfmaPlan mfma{};
-    char *h_stage = nullptr;
+    char *h_stage = nullptr, *h_stage_dev = nullptr;   // pinned ring of descriptor tables, its device mapping (or null)
     void *d_stage = nullptr;
     size_t slot_bytes = 0;
     hipEvent_t ev[USER_NSLOT] = {};
@@ -166,7 +166,7 @@ aif_status uinit(const aif_user_config *cfg, const aif_user_weights *wts, aif_us
     const size_t sb = (size_t)c->max_users * (sizeof(ReqDesc) + sizeof(UserDesc)) + (n_blk_max + 4) * sizeof(int32_t) + 16 +
                       attn_max_groups(c->x_rows, c->max_users) * sizeof(AttnGroup);
     c->slot_bytes = (sb + 255) / 256 * 256;
-    USER_TRY(nullptr, hipHostMalloc((void **)&c->h_stage, c->slot_bytes * USER_NSLOT, hipHostMallocDefault));
+    USER_TRY(nullptr, staging_alloc(c->slot_bytes * USER_NSLOT, &c->h_stage, &c->h_stage_dev));
     USER_TRY(nullptr, hipMalloc(&c->d_stage, c->slot_bytes * USER_NSLOT));
     for (int i = 0; i < USER_NSLOT; ++i)
         USER_TRY(nullptr, hipEventCreateWithFlags(&c->ev[i], hipEventDisableTiming | hipEventDisableSystemFence));
@@ -251,7 +251,8 @@ aif_status aif_user_precompute(aif_user_ctx *c, const aif_user_request *users, i
     const size_t goff = ((size_t)n_users * (sizeof(ReqDesc) + sizeof(UserDesc)) + (size_t)b.n_blk * sizeof(int32_t) + 15) / 16 * 16;
     b.n_groups = c->mfma.attn ? attn_plan_groups(m, hr, n_users, c->n_cu, (AttnGroup *)(h + goff)) : 0;
     b.groups = (const AttnGroup *)(d + goff);
-    USER_TRY(c, hipMemcpyAsync(d, h, goff + (size_t)b.n_groups * sizeof(AttnGroup), hipMemcpyHostToDevice, s));
+    USER_TRY(c, staging_upload(c->h_stage, c->h_stage_dev, (size_t)slot * c->slot_bytes, d,
+                               goff + (size_t)b.n_groups * sizeof(AttnGroup), s));
 
     hipEvent_t *pe = nullptr;
     if (c->prof_on && c->prof_calls < c->prof_max) pe = &c->prof[(size_t)USER_EV_PER_CALL * c->prof_calls++];

@@ -124,4 +124,24 @@ hipError_t launch_upload(const void *src_mapped, void *dst, size_t bytes, hipStr
     return hipGetLastError();
 }
 
+hipError_t staging_alloc(size_t bytes, char **host, char **mapped)
+{
+    *host = *mapped = nullptr;
+    if (hipHostMalloc((void **)host, bytes, hipHostMallocCoherent | hipHostMallocMapped) == hipSuccess) {
+        void *dev = nullptr;
+        if (hipHostGetDevicePointer(&dev, *host, 0) == hipSuccess) *mapped = (char *)dev;
+        else (void)hipGetLastError();
+        return hipSuccess;
+    }
+    (void)hipGetLastError();
+    *host = nullptr;
+    return hipHostMalloc((void **)host, bytes, hipHostMallocDefault);
+}
+
+hipError_t staging_upload(const char *host, const char *mapped, size_t off, void *dst, size_t bytes, hipStream_t s)
+{
+    if (mapped) return launch_upload(mapped + off, dst, bytes, s);
+    return hipMemcpyAsync(dst, host + off, bytes, hipMemcpyHostToDevice, s);
+}
+
 }  // namespace aif
