@@ -62,7 +62,7 @@ typedef enum {
     AIF_CROSS_NONE = 0,
     AIF_CROSS_HADAMARD = 1, /* c = u (.) e, width d_item (Sec. 3.3)                        */
     AIF_CROSS_SEGDOT = 2,   /* c[j*S+s] = <Vc_j, e[s*d_c:(s+1)*d_c]>, S = d_item/d_c,
-                               the "n user-side vectors x item" shape of Sec. 4.1       */
+                               the shape of Sec. 4.1: n user-side vectors meet one item  */
     AIF_CROSS_BEA = 3       /* Bridge Embedding Approximation, Sec. 4.1, Algorithm 1 step 4
                                (the online weighted sum): the item row ENDS with the
                                candidate's n_cross bridge weights w^ (the nearline pipeline

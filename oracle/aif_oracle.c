@@ -11,8 +11,8 @@
  * a time, in the order the paper lays the online phase out:
  *
  *   1. look the candidate's nearline item vector up in the index table
- *      (Sec. 3.2, "stored in an indexing table"; combined with the user
- *      vectors at pre-ranking),
+ *      (Sec. 3.2: item vectors are kept in an index table and meet the
+ *      user vectors at pre-ranking),
  *   2. form the attention query from the item vector (projection of the
  *      Eq. 1 kind, or the leading slice when no projection is given),
  *   3. scaled dot-product attention of the candidate over the user's
@@ -23,7 +23,7 @@
  *   5. model input = [user | item | attention | cross] (Sec. 1, "constructs
  *      model input tensors"),
  *   6. shallow MLP head, ReLU between layers, linear last layer -> logit,
- *      sigmoid -> score (Sec. 1, "shallow multilayer perceptron"),
+ *      sigmoid -> score (Sec. 1: the head is a small MLP),
  *   7. keep the best k of the request (Sec. 1: about 10^4 -> about 10^2).
  *
  * Pins (tests/test_oracle_pins.py): softmax weights sum to one; L = 1 returns

@@ -12,7 +12,7 @@
  *          U^_seq     = U_seq W_seq^T           [l, d]
  *   Eq. 2  U_self_attention = Pooling(FFN(Softmax(U^_seq U^_seq^T / sqrt(d)) U^_seq))   [1, d]
  *   Eq. 3  U_profile_attention = Softmax(U^_profile U^_seq^T / sqrt(d)) U^_seq          [1, d]
- * and the "combined user vector" that is cached for the real-time phase.
+ * and the user vector combined from them, which is cached for the real-time phase.
  *
  * The paper names FFN, Pooling and the combination without defining them.
  * Readings taken here (and by the GPU library):

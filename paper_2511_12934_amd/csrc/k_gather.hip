@@ -1,6 +1,6 @@
 // a1 -- index the nearline item-vector table by candidate id (Sec. 3.2: the
-// vectors of all items are "stored in an indexing table"; at pre-ranking they
-// are combined with the user vectors).  Pure data movement: HBM-bound.
+// vectors of all items are kept in an index table; at pre-ranking they
+// meet the user vectors).  Pure data movement: HBM-bound.
 //
 // Rows are moved as 16-byte pieces.  A row of R bytes is handled by R/16
 // neighbouring lanes, so a wave reads 64*16 B spread over 1024/R rows with

@@ -198,7 +198,7 @@ hipError_t launch_attn_generic(const Model &m, const Batch &b, void *X, const fl
 }
 
 // ---------------------------------------------------------------------------
-// a6-a7 -- MLP head (Sec. 1: "shallow multilayer perceptron") over the
+// a6-a7 -- MLP head (Sec. 1: a small MLP) over the
 // virtual input [u | e | a | c]: the u block arrives as bias1 (user fold), the
 // rest is the workspace row.  MLP_TS candidates per block; activations live
 // in two LDS buffers laid out [feature][candidate]; thread n owns output

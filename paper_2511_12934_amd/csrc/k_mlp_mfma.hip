@@ -1,5 +1,5 @@
-// a6-a7 on the matrix cores -- the MLP head (Sec. 1: "shallow multilayer
-// perceptron") as one fused bf16 MFMA chain.
+// a6-a7 on the matrix cores -- the MLP head (Sec. 1: a small MLP) as one
+// fused bf16 MFMA chain.
 //
 // The products are formed transposed, H^T = W . X^T: the weights are the A
 // operand (rows = output features) and the candidates are the columns of the
