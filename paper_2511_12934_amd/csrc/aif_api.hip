@@ -374,7 +374,13 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         }
         bytes = toff + (size_t)n_req * sizeof(TopkDesc);
     }
-    HIP_TRY(c, upload(c, slot, bytes, s));
+    const bool fused = stage_fusable(m, c->mfma);
+    // with the request's K/V resident and no W_q, the attention kernel takes its query pieces from the table itself
+    const bool attn_indexes = fused && attn_gathers(m, b, c->mfma);
+    c->attn_indexed = attn_indexes;
+    // the staging launch then has few blocks and carries the tables to the device itself
+    const bool stage_uploads = attn_indexes && c->h_stage_dev;
+    if (!stage_uploads) HIP_TRY(c, upload(c, slot, bytes, s));
 
     hipEvent_t *pe = nullptr;
     if (c->prof_on && c->prof_batch_calls < c->prof_max && c->prof_seen_batch++ % c->prof_every == 0)
@@ -385,15 +391,16 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         return pe && (c->prof_mask & need) ? hipEventRecord(pe[i], s) : hipSuccess;
     };
     HIP_TRY(c, mark(0));
-    const bool fused = stage_fusable(m, c->mfma);
-    // with the request's K/V resident and no W_q, the attention kernel takes its query pieces from the table itself
-    const bool attn_indexes = fused && attn_gathers(m, b, c->mfma);
-    c->attn_indexed = attn_indexes;
     if (fused) {
         // gather (unless the attention kernel does it), user fold and K/V packing as one launch; timed as the gather stage
+        StageUpload up{};
+        if (stage_uploads) {
+            const char *mapped = c->h_stage_dev + (size_t)slot * c->slot_bytes;
+            up = {mapped, d, bytes, (const ReqDesc *)mapped};
+        }
         HIP_TRY(c, launch_stage(m, b, c->table, c->X.p, (int32_t *)c->bad.p, (const float *)c->w1u.p,
                                 c->has_bias[0] ? (const float *)c->bias[0].p : nullptr, (float *)c->bias1.p, c->mfma,
-                                !attn_indexes, s));
+                                !attn_indexes, s, stage_uploads ? &up : nullptr));
         HIP_TRY(c, mark(1));
     } else {
         HIP_TRY(c, launch_gather(m, b, c->table, c->X.p, (int32_t *)c->bad.p, s));

@@ -49,8 +49,18 @@ bool attn_gathers(const Model &m, const Batch &b, const MfmaPlan &plan);
 
 // k_stage.hip: gather + user fold + K/V packing as one launch (bf16 models served by the MFMA attention kernel)
 bool stage_fusable(const Model &m, const MfmaPlan &plan);
+// up (optional, only with gather == false): the same launch also carries the call's descriptor tables from mapped
+// pinned host memory to the device (bytes rounded up to 16, as launch_upload); its own blocks then read the request
+// descriptors through the mapping (reqs_mapped), every later kernel reads the device copy that `b` points to.
+struct StageUpload {
+    const void *src_mapped;
+    void *dst;
+    size_t bytes;
+    const ReqDesc *reqs_mapped;
+};
 hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad, const float *w1u,
-                        const float *b1, float *bias1, const MfmaPlan &plan, bool gather, hipStream_t s);
+                        const float *b1, float *bias1, const MfmaPlan &plan, bool gather, hipStream_t s,
+                        const StageUpload *up = nullptr);
 
 // bias_f32[l] / wlast_f32: the context's fp32 copies (bias of layer l or null; last layer's weight row).
 hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const MfmaPlan &plan,

@@ -4,7 +4,8 @@
 // kernel that follows.  The small, latency-bound jobs come first in the grid so
 // that they run under the HBM-bound gather instead of before or after it.
 // When the attention kernel that follows indexes the item table itself (k_attn_res with
-// GATHER) the grid has no gather blocks.
+// GATHER) the grid has no gather blocks; its first blocks may then carry the call's descriptor
+// tables from pinned host memory to the device, which saves the upload its own launch.
 #include "k_mfma.h"
 #include "k_stage.h"
 
@@ -25,12 +26,21 @@ struct StageArgs {
     int32_t nktp, row_vec;
     int32_t n_pack, n_fold;         // blocks of the first two jobs
     int32_t stages, quads;          // 64-key stages per head (nktp / 2); blocks of FOLD_FEATS layer-1 features
+    const uint4 *up_src;            // descriptor tables to copy (mapped host memory -> device), 16 bytes a thread
+    uint4 *up_dst;
+    int32_t up_n16, n_up;           // 16-byte pieces; blocks of this job (0: the tables are on the device already)
 };
 
 template <int LOG_RV, int DH>
 __global__ __launch_bounds__(256) void k_stage(StageArgs a)
 {
     int idx = blockIdx.x;
+    if (idx < a.n_up) {
+        const int i = idx * 256 + (int)threadIdx.x;
+        if (i < a.up_n16) a.up_dst[i] = a.up_src[i];
+        return;
+    }
+    idx -= a.n_up;
     if (idx < a.n_pack) {
         const int st = idx % a.stages, rest = idx / a.stages;
         pack_kv_block<DH>(rest / a.m.n_heads, rest % a.m.n_heads, st, a.m, a.b, a.kvpack, a.pack_stride, a.kmax, a.nktp);
@@ -54,7 +64,7 @@ __global__ __launch_bounds__(256) void k_stage(StageArgs a)
 template <int DH>
 static hipError_t launch_stage_dh(const StageArgs &a, int n_gather, hipStream_t s)
 {
-    const dim3 grid(a.n_pack + a.n_fold + n_gather);
+    const dim3 grid(a.n_up + a.n_pack + a.n_fold + n_gather);
     switch (a.row_vec) {
     case 8: hipLaunchKernelGGL((k_stage<3, DH>), grid, dim3(256), 0, s, a); break;
     case 16: hipLaunchKernelGGL((k_stage<4, DH>), grid, dim3(256), 0, s, a); break;
@@ -70,12 +80,24 @@ bool stage_fusable(const Model &m, const MfmaPlan &plan)
 }
 
 hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad, const float *w1u,
-                        const float *b1, float *bias1, const MfmaPlan &plan, bool gather, hipStream_t s)
+                        const float *b1, float *bias1, const MfmaPlan &plan, bool gather, hipStream_t s,
+                        const StageUpload *up)
 {
     if (b.n_req == 0) return hipSuccess;
+    if (up && gather) return hipErrorInvalidValue;      // the gather's many blocks read the device copy
     StageArgs a;
     a.m = m;
     a.b = b;
+    a.up_src = nullptr;
+    a.up_dst = nullptr;
+    a.up_n16 = a.n_up = 0;
+    if (up) {
+        a.b.reqs = up->reqs_mapped;
+        a.up_src = (const uint4 *)up->src_mapped;
+        a.up_dst = (uint4 *)up->dst;
+        a.up_n16 = (int32_t)((up->bytes + 15) / 16);
+        a.n_up = (a.up_n16 + 255) / 256;
+    }
     a.table = (const uint4 *)table;
     a.X = (char *)X;
     a.xl = x_layout(m);
