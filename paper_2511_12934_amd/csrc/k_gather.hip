@@ -9,6 +9,7 @@
 // UNROLL ids, then has UNROLL independent row loads in flight before its first
 // store.
 #include "k_stage.h"
+#include <cstdlib>
 
 namespace aif {
 
@@ -127,13 +128,15 @@ hipError_t launch_upload(const void *src_mapped, void *dst, size_t bytes, hipStr
 hipError_t staging_alloc(size_t bytes, char **host, char **mapped)
 {
     *host = *mapped = nullptr;
-    if (hipHostMalloc((void **)host, bytes, hipHostMallocCoherent | hipHostMallocMapped) == hipSuccess) {
+    const char *copy = getenv("AIF_STAGING_COPY");        // testing: the route taken where the mapping is refused
+    const bool try_mapped = !(copy && copy[0] == '1');
+    if (try_mapped && hipHostMalloc((void **)host, bytes, hipHostMallocCoherent | hipHostMallocMapped) == hipSuccess) {
         void *dev = nullptr;
         if (hipHostGetDevicePointer(&dev, *host, 0) == hipSuccess) *mapped = (char *)dev;
         else (void)hipGetLastError();
         return hipSuccess;
     }
-    (void)hipGetLastError();
+    if (try_mapped) (void)hipGetLastError();
     *host = nullptr;
     return hipHostMalloc((void **)host, bytes, hipHostMallocDefault);
 }

@@ -367,6 +367,25 @@ def test_mfma_kernels_on_row_major_workspace(R, torch, monkeypatch):
     assert_logits_close("bf16", z1, oracle_scores(cfg, model, table, u, ids).logits)
 
 
+def test_descriptor_tables_uploaded_by_kernel_or_by_copy_give_the_same_bits(R, torch, monkeypatch):
+    """The call's descriptor tables reach the device by a kernel that reads the mapped pinned slot (inside the staging
+    launch when the attention kernel indexes the table) or, where the mapping is refused, by a copy command."""
+    cfg = wl.CONFIGS["C3"].scaled(n_items=3000)
+    _say("C3 shape, descriptor upload by kernel vs by copy command")
+    rng = np.random.default_rng(13)
+    model = wl.make_model(cfg)
+    table = wl.make_table_host(cfg, rng, n_items=3000)
+    reqs = [(wl.make_user(cfg, rng), wl.IdSampler(cfg, 3000).sample(rng, n)) for n in (333, 1, 64, 700)]
+    z0, _, _, ctx0 = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), reqs)
+    assert ctx0.aif_stage_kind("gather") == 2
+    monkeypatch.setenv("AIF_STAGING_COPY", "1")
+    z1, _, _, ctx1 = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), reqs)
+    assert ctx1.aif_stage_kind("gather") == 2
+    for r, (u, ids) in enumerate(reqs):
+        assert np.array_equal(z0[r], z1[r]), f"request {r}"
+    assert_logits_close("bf16", z1[0], oracle_scores(cfg, model, table, reqs[0][0], reqs[0][1]).logits)
+
+
 def test_stale_workspace_rows_do_not_change_a_candidates_bits(R, torch):
     """Rows of the workspace past the end of a request keep what an earlier call left there.  A call with
     huge-valued rows (their softmax takes the true maximum instead of the norm bound) is followed, on the same
