@@ -488,8 +488,13 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                 f32x16 Cc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) Cc[i] = 0.f;
-                for (int ks = 0; ks < bg.ksb; ++ks)
-                    Cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(su[(ks * bg.ftc + ft) * 64 + lane], *piece(bg.piece0 + 2 * ks + h), Cc, 0, 0, 0);
+                for (int ks = 0; ks < bg.ksb; ++ks) {
+                    // the row's bridge weights: from the workspace, or (GATHER: the row is not there yet) from the table
+                    bf16x8 wrow;
+                    if constexpr (GATHER) wrow = *(const bf16x8 *)(table_row(id) + (bg.piece0 + 2 * ks + h) * 16);
+                    else wrow = *piece(bg.piece0 + 2 * ks + h);
+                    Cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(su[(ks * bg.ftc + ft) * 64 + lane], wrow, Cc, 0, 0, 0);
+                }
                 if (live) {
 #pragma unroll
                     for (int qd = 0; qd < 4; ++qd) {
@@ -727,12 +732,10 @@ static bool small_batch(const Batch &b)
 }
 
 // Whether the attention launch of this batch also indexes the item table (k_attn_res with GATHER): K/V resident
-// (the batch has tile groups), no W_q (the plan's variants 0 and 1), and no cross block that reads the item row
-// through the workspace inside the kernel (BEA).
+// (the batch has tile groups) and no W_q (the plan's variants 0 and 1).
 bool attn_gathers(const Model &m, const Batch &b, const MfmaPlan &plan)
 {
-    return m.dtype == 1 && plan.attn && (plan.attn_variant == 0 || plan.attn_variant == 1) && b.n_groups > 0 && b.n_blk > 0 &&
-           m.cross_mode != 3;
+    return m.dtype == 1 && plan.attn && (plan.attn_variant == 0 || plan.attn_variant == 1) && b.n_groups > 0 && b.n_blk > 0;
 }
 
 hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed,
