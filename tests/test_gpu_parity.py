@@ -464,6 +464,8 @@ def test_bea_cross_on_the_mfma_kernels(R, torch, shape):
     reqs = [(users[0], sampler.sample(rng, 333)), (users[1], sampler.sample(rng, 600))]
     zs, _, _, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), reqs)
     assert ctx.aif_stage_kind("attention") == 1
+    # the resident kernel indexes the table itself and takes the bridge weights from the table row
+    assert ctx.aif_stage_kind("gather") == (0 if shape == "streaming_16" else 2)
     for i, (u, ids) in enumerate(reqs):
         ref = oracle_scores(cfg, model, table, u, ids)
         X = R.peek_features(ctx, cfg, i, ids.size)
