@@ -375,11 +375,11 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         bytes = toff + (size_t)n_req * sizeof(TopkDesc);
     }
     const bool fused = stage_fusable(m, c->mfma);
-    // with the request's K/V resident and no W_q, the attention kernel takes its query pieces from the table itself
-    const bool attn_indexes = fused && attn_gathers(m, b, c->mfma);
+    // where it can, the attention kernel takes the item vectors from the table itself
+    const bool attn_indexes = c->mfma.attn && attn_gathers(m, b, c->mfma);
     c->attn_indexed = attn_indexes;
     // the staging launch then has few blocks and carries the tables to the device itself
-    const bool stage_uploads = attn_indexes && c->h_stage_dev;
+    const bool stage_uploads = fused && attn_indexes && c->h_stage_dev;
     if (!stage_uploads) HIP_TRY(c, upload(c, slot, bytes, s));
 
     hipEvent_t *pe = nullptr;
@@ -403,7 +403,7 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
                                 !attn_indexes, s, stage_uploads ? &up : nullptr));
         HIP_TRY(c, mark(1));
     } else {
-        HIP_TRY(c, launch_gather(m, b, c->table, c->X.p, (int32_t *)c->bad.p, s));
+        if (!attn_indexes) HIP_TRY(c, launch_gather(m, b, c->table, c->X.p, (int32_t *)c->bad.p, s));
         HIP_TRY(c, mark(1));
         HIP_TRY(c, launch_user_fold(m, b, (const float *)c->w1u.p, c->has_bias[0] ? (const float *)c->bias[0].p : nullptr,
                                     (float *)c->bias1.p, s));

@@ -731,11 +731,13 @@ static bool small_batch(const Batch &b)
     return b.n_blk < n_cu;
 }
 
-// Whether the attention launch of this batch also indexes the item table (k_attn_res with GATHER): K/V resident
-// (the batch has tile groups) and no W_q (the plan's variants 0 and 1).
+// Whether the attention launch of this batch also indexes the item table: k_attn_res with GATHER (no W_q, the
+// plan's variants 0 and 1) when K/V are resident (the batch has tile groups), k_attn_proj with GATHER always.
 bool attn_gathers(const Model &m, const Batch &b, const MfmaPlan &plan)
 {
-    return m.dtype == 1 && plan.attn && (plan.attn_variant == 0 || plan.attn_variant == 1) && b.n_groups > 0 && b.n_blk > 0;
+    if (m.dtype != 1 || !plan.attn || b.n_blk == 0) return false;
+    if (plan.attn_variant == ATTN_VARIANT_PROJ) return true;
+    return (plan.attn_variant == 0 || plan.attn_variant == 1) && b.n_groups > 0;
 }
 
 hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed,
@@ -747,7 +749,7 @@ hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const Mf
     const size_t stride = plan.pack_stride;
     const int nktp = plan.nktp;
     switch (plan.attn_variant) {
-    case ATTN_VARIANT_PROJ: return gather_table ? hipErrorInvalidValue : launch_attn_proj(m, b, X, plan, small_batch(b), s);
+    case ATTN_VARIANT_PROJ: return launch_attn_proj(m, b, X, plan, small_batch(b), s, gather_table, bad);
     case 0:
         return small_batch(b) ? launch_attn_spec<64, 2>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s)
                               : launch_attn_spec<64, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s);

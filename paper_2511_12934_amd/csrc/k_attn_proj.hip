@@ -141,11 +141,15 @@ __global__ __launch_bounds__(256) void k_pack_kv16(Model m, Batch b, char *__res
 // projection + attention + cross.  One wave = 32 candidates, all heads in turn.
 // NFT = d_attn / 32 feature tiles of the query = n_heads / 2.
 // ---------------------------------------------------------------------------
-template <int NFT, int WAVES>
+// GATHER: the kernel is also a1 (Sec. 3.2): a lane takes the pieces of its candidate's item vector from the table
+// row its id names instead of the workspace, and sets them down in the workspace for the MLP after the projection
+// has read them.  An id outside the table reads row 0 and is counted, as in the gather kernel.
+template <int NFT, int WAVES, bool GATHER>
 __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, char *__restrict__ X, XLayout xl,
                                                          const char *__restrict__ wq_pack,
                                                          const char *__restrict__ kvpack, size_t pack_stride,
-                                                         const float *__restrict__ kmax, int nktp)
+                                                         const float *__restrict__ kmax, int nktp,
+                                                         const char *__restrict__ table, int32_t *__restrict__ bad)
 {
     constexpr int ROWS = WAVES * 32, H = 2 * NFT;
     static_assert(ROW_BLOCK % ROWS == 0, "tile");
@@ -174,6 +178,20 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
     const int nkt = (L + 31) >> 5, nst = (nkt + P_NT - 1) / P_NT, total = H * nst, nstp = nktp / P_NT;
     const char *pk = kvpack + (size_t)r * pack_stride;
     const bool live = local0 + wave * 32 + col < rd.n_cand;
+    const char *trow = nullptr;                   // GATHER: this lane's row of the table (row 0 past the request's end)
+    if constexpr (GATHER) {
+        int id = live ? rd.cand_ids[local0 + wave * 32 + col] : 0;
+        if (id < 0 || (int64_t)id >= m.n_items) {
+            if (h == 0) atomicAdd(bad, 1);
+            id = 0;
+        }
+        trow = table + (size_t)id * (size_t)(m.d_item * 2);
+    }
+    // piece p < d_item / 8 of the lane's item vector
+    auto item_piece = [&](int p) -> bf16x8 {
+        if constexpr (GATHER) return *(const bf16x8 *)(trow + p * 16);
+        else return *piece(p);
+    };
     const uint32_t ring = lds_address(lds);
     auto stage_src = [&](int i) {
         const int sh = i / nst, ss = i - sh * nst;
@@ -224,7 +242,13 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
         for (int j0 = 0; j0 < KS; j0 += 4) {
             bf16x8 e[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) e[u] = *piece(2 * (j0 + u) + h);
+            for (int u = 0; u < 4; ++u) e[u] = item_piece(2 * (j0 + u) + h);
+            if constexpr (GATHER) {
+                if (live) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) *piece(2 * (j0 + u) + h) = e[u];
+                }
+            }
 #pragma unroll
             for (int ft = 0; ft < NFT; ++ft)
 #pragma unroll
@@ -244,7 +268,7 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
     if (m.cross_mode == 1 && live) {
         const bf16x8 *uc = (const bf16x8 *)rd.cross_vecs;
         for (int pc = h; pc < m.d_item / 8; pc += 2) {
-            const bf16x8 e = *piece(pc), uv = uc[pc];
+            const bf16x8 e = item_piece(pc), uv = uc[pc];
             bf16x8 o8;
 #pragma unroll
             for (int sl = 0; sl < 8; ++sl) o8[sl] = (__bf16)((float)e[sl] * (float)uv[sl]);
@@ -265,7 +289,7 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
                 bf16x8 e[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
-                    if (kk0 + u < ksc) e[u] = *piece(2 * (seg * ksc + kk0 + u) + h);
+                    if (kk0 + u < ksc) e[u] = item_piece(2 * (seg * ksc + kk0 + u) + h);
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
                     if (kk0 + u < ksc) Cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sa[(kk0 + u) * 64 + lane], e[u], Cc, 0, 0, 0);
@@ -379,11 +403,12 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
     }
 }
 
-template <int NFT, int WAVES>
-hipError_t launch_proj_spec(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, hipStream_t s)
+template <int NFT, int WAVES, bool GATHER>
+hipError_t launch_proj_spec(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, const void *table, int32_t *bad,
+                            hipStream_t s)
 {
     constexpr int ROWS = WAVES * 32;
-    auto kern = k_attn_proj<NFT, WAVES>;
+    auto kern = k_attn_proj<NFT, WAVES, GATHER>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS_BYTES);
@@ -392,8 +417,16 @@ hipError_t launch_proj_spec(const Model &m, const Batch &b, void *X, const MfmaP
     }
     hipLaunchKernelGGL(kern, dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), P_LDS_BYTES, s, m, b, (char *)X,
                        x_layout(m), (const char *)plan.wq_pack, (const char *)plan.kvpack, plan.pack_stride,
-                       (const float *)plan.kmax, plan.nktp);
+                       (const float *)plan.kmax, plan.nktp, (const char *)table, bad);
     return hipGetLastError();
+}
+
+template <int NFT, int WAVES>
+hipError_t launch_proj_gather(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, const void *table, int32_t *bad,
+                              hipStream_t s)
+{
+    if (table) return bad ? launch_proj_spec<NFT, WAVES, true>(m, b, X, plan, table, bad, s) : hipErrorInvalidValue;
+    return launch_proj_spec<NFT, WAVES, false>(m, b, X, plan, nullptr, nullptr, s);
 }
 
 }  // namespace
@@ -417,15 +450,16 @@ size_t attn_proj_pack_stride(const Model &m, int max_seq_len, int *nktp_out)
     return (size_t)m.n_heads * nktp * 3 * 1024;
 }
 
-hipError_t launch_attn_proj(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool small, hipStream_t s)
+hipError_t launch_attn_proj(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool small, hipStream_t s,
+                            const void *gather_table, int32_t *bad)
 {
     if (plan.nktp > 0)
         hipLaunchKernelGGL(k_pack_kv16, dim3(plan.nktp / P_NT, m.n_heads, b.n_req), dim3(256), 0, s, m, b, plan.kvpack,
                            plan.pack_stride, plan.kmax, plan.nktp);
     switch (m.n_heads) {
-    case 2: return small ? launch_proj_spec<1, 2>(m, b, X, plan, s) : launch_proj_spec<1, 8>(m, b, X, plan, s);
-    case 4: return small ? launch_proj_spec<2, 2>(m, b, X, plan, s) : launch_proj_spec<2, 8>(m, b, X, plan, s);
-    case 8: return small ? launch_proj_spec<4, 2>(m, b, X, plan, s) : launch_proj_spec<4, 8>(m, b, X, plan, s);
+    case 2: return small ? launch_proj_gather<1, 2>(m, b, X, plan, gather_table, bad, s) : launch_proj_gather<1, 8>(m, b, X, plan, gather_table, bad, s);
+    case 4: return small ? launch_proj_gather<2, 2>(m, b, X, plan, gather_table, bad, s) : launch_proj_gather<2, 8>(m, b, X, plan, gather_table, bad, s);
+    case 8: return small ? launch_proj_gather<4, 2>(m, b, X, plan, gather_table, bad, s) : launch_proj_gather<4, 8>(m, b, X, plan, gather_table, bad, s);
     default: return hipErrorInvalidValue;
     }
 }

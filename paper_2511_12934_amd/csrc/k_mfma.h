@@ -88,6 +88,8 @@ constexpr int ATTN_VARIANT_PROJ = 2;      // attn_variant of the projection + 16
 // k_attn_proj.hip: query projection, 16-wide heads, Hadamard / segment-dot cross
 bool attn_proj_ok(const Model &m, bool has_wq);
 size_t attn_proj_pack_stride(const Model &m, int max_seq_len, int *nktp_out);
-hipError_t launch_attn_proj(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool small, hipStream_t s);
+// gather_table, bad: as for launch_attn_mfma
+hipError_t launch_attn_proj(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool small, hipStream_t s,
+                            const void *gather_table = nullptr, int32_t *bad = nullptr);
 
 }  // namespace aif
