@@ -566,6 +566,7 @@ def test_projection_attention_with_16_wide_heads(R, torch, shape, sigma):
         users_ids.append((wl.make_user(cfg, rng, sigma=sigma, seq_len=L), sampler.sample(rng, n)))
     zs, ys, drs, ctx = run_batch(R, torch, cfg, model, table_dev, users_ids, max_seq_len=530)
     assert ctx.aif_stage_kind("attention") == 1, "MFMA attention not selected"
+    assert ctx.aif_stage_kind("gather") == 2, "the projection kernel indexes the item table itself"
     for r, ((u, ids), z) in enumerate(zip(users_ids, zs)):
         ref = oracle_scores(cfg, model, table, u, ids, n_threads=4)
         X = R.peek_features(ctx, cfg, r, ids.size)
@@ -833,6 +834,33 @@ def test_bad_ids_on_the_fragment_order_workspace(R, torch, shape):
     ids_bad[bad_pos] = [-1, 3000, 2_000_000_000, -5, 3001, -2_000_000_000]
     (z_bad,), _, _, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), [(u, ids_bad)])
     assert ctx.aif_stage_kind("attention") == 1 and ctx.aif_stage_kind("mlp") == 1
+    assert ctx.aif_poll_device_errors() == bad_pos.size
+    assert np.isnan(z_bad[bad_pos]).all()
+    good = np.setdiff1d(np.arange(ids.size), bad_pos)
+    ref = oracle_scores(cfg, model, table, u, ids[good], n_threads=4)
+    assert_logits_close("bf16", z_bad[good], ref.logits, "neighbours of bad ids")
+    (z_ok,), _, _, ctx2 = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), [(u, ids)])
+    assert np.array_equal(z_ok[good], z_bad[good])
+    assert ctx2.aif_poll_device_errors() == 0
+
+
+@pytest.mark.parametrize("shape", ["c5_like", "hadamard_4_heads", "segdot_6_vectors_2_heads"])
+def test_bad_ids_when_the_projection_kernel_indexes_the_table(R, torch, shape):
+    """W_q models: the attention kernel reads the table rows itself.  Out-of-range ids give NaN logits and are
+    counted once each, their neighbours keep their bits; with the layered MLP, the MLP chain and the
+    shape-agnostic MLP behind it."""
+    cfg = small_cfg("bf16", n_items=3000, seq_len=40, **PROJ_SHAPES[shape])
+    _say(f"bad ids, projection attention, {shape}")
+    rng = np.random.default_rng(33)
+    model = wl.make_model(cfg, seed=5, bias_scale=0.1)
+    table = wl.make_table_host(cfg, rng)
+    u = wl.make_user(cfg, rng)
+    ids = rng.integers(0, 3000, 300).astype(np.int32)
+    bad_pos = np.array([0, 31, 32, 255, 256, 299])
+    ids_bad = ids.copy()
+    ids_bad[bad_pos] = [-1, 3000, 2_000_000_000, -5, 3001, -2_000_000_000]
+    (z_bad,), _, _, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), [(u, ids_bad)])
+    assert ctx.aif_stage_kind("attention") == 1 and ctx.aif_stage_kind("gather") == 2
     assert ctx.aif_poll_device_errors() == bad_pos.size
     assert np.isnan(z_bad[bad_pos]).all()
     good = np.setdiff1d(np.arange(ids.size), bad_pos)
