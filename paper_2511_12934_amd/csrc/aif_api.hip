@@ -58,6 +58,7 @@ struct aif_ctx {
     size_t x_rows = 0;
     int n_cu = 256;                   // compute units of the device (sizes the attention groups)
     bool attn_indexed = false;        // the last scoring call's attention kernel read the item table itself
+    bool separate_gather = false;     // testing (AIF_SEPARATE_GATHER=1): the gather always as blocks or a launch of its own
 
     // descriptor staging ring
     char *h_stage = nullptr;          // pinned
@@ -242,6 +243,8 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
     {
         const char *rm = getenv("AIF_X_ROW_MAJOR");      // testing: the MFMA kernels on the row-major layout
         m.x_tiled = (c->mfma.attn && c->mfma.mlp && !(rm && rm[0] == '1')) ? 1 : 0;
+        const char *sg = getenv("AIF_SEPARATE_GATHER");  // testing: both gather routes must give the same bits
+        c->separate_gather = sg && sg[0] == '1';
     }
 
     const bool attn_ok = c->mfma.attn || attn_generic_lds_bytes(m, c->max_seq_len) <= 160 * 1024;
@@ -376,7 +379,7 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
     }
     const bool fused = stage_fusable(m, c->mfma);
     // where it can, the attention kernel takes the item vectors from the table itself
-    const bool attn_indexes = c->mfma.attn && attn_gathers(m, b, c->mfma);
+    const bool attn_indexes = c->mfma.attn && !c->separate_gather && attn_gathers(m, b, c->mfma);
     c->attn_indexed = attn_indexes;
     // the staging launch then has few blocks and carries the tables to the device itself
     const bool stage_uploads = fused && attn_indexes && c->h_stage_dev;

@@ -871,6 +871,33 @@ def test_bad_ids_when_the_projection_kernel_indexes_the_table(R, torch, shape):
     assert ctx2.aif_poll_device_errors() == 0
 
 
+@pytest.mark.parametrize("shape", ["c3", "b3", "c5_like"])
+def test_gather_inside_the_attention_kernel_or_on_its_own_gives_the_same_bits(R, torch, monkeypatch, shape):
+    """The attention kernels that index the item table themselves against the same kernels behind a separate gather
+    (AIF_SEPARATE_GATHER=1): workspace and logits bit for bit, ragged requests."""
+    if shape == "c3":
+        cfg = wl.CONFIGS["C3"].scaled(n_items=3000)
+    elif shape == "b3":
+        cfg = wl.CONFIGS["B3"].scaled(n_items=3000)
+    else:
+        cfg = small_cfg("bf16", n_items=3000, seq_len=300, **PROJ_SHAPES["c5_like"])
+    _say(f"gather routes, {shape}")
+    rng = np.random.default_rng(41)
+    model = wl.make_model(cfg, bias_scale=0.05)
+    table = wl.make_table_host(cfg, rng, n_items=3000)
+    sampler = wl.IdSampler(cfg, 3000)
+    reqs = [(wl.make_user(cfg, rng), sampler.sample(rng, n)) for n in (333, 1, 600, 32)]
+    z0, _, _, ctx0 = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), reqs)
+    assert ctx0.aif_stage_kind("gather") == 2
+    X0 = [R.peek_features(ctx0, cfg, i, ids.size) for i, (_, ids) in enumerate(reqs)]
+    monkeypatch.setenv("AIF_SEPARATE_GATHER", "1")
+    z1, _, _, ctx1 = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), reqs)
+    assert ctx1.aif_stage_kind("gather") != 2 and ctx1.aif_stage_kind("attention") == 1
+    for i, (_, ids) in enumerate(reqs):
+        assert np.array_equal(X0[i], R.peek_features(ctx1, cfg, i, ids.size)), f"workspace, request {i}"
+        assert np.array_equal(z0[i], z1[i]), f"logits, request {i}"
+
+
 def test_profiling_times_the_selected_stages_only(R, torch):
     """aif_profile_begin brackets every stage of a scoring call with events, aif_profile_begin_stages only the
     stages named; the results are the same either way.  The batch's K/V fit one compute unit's LDS and there is
