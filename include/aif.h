@@ -14,9 +14,9 @@
  *     features (Sec. 3.3),
  *   - runs the shallow MLP head on [user | item | attention | cross] (Sec. 1),
  *   - and selects the best k candidates (Sec. 1: about 10^4 -> about 10^2).
- * Mini-batches (Sec. 1, "e.g., 1,000 items per batch") are the caller's
- * choice of how many aif_request slices a candidate list is cut into; scores
- * do not depend on the slicing.
+ * Mini-batches (Sec. 1: a request's candidates are scored in slices of about a
+ * thousand) are the caller's choice of how many aif_request slices a candidate
+ * list is cut into; scores do not depend on the slicing.
  *
  * Conventions
  *   - Plain C, no exceptions.  Every call returns an aif_status; on failure
@@ -119,18 +119,29 @@ typedef struct {
     float *scores_out;        /* [n_cand] sigmoid(z), or NULL                             */
 } aif_request;
 
-/* Create a context on the current device: validates the configuration, sizes
- * the workspace for max_users requests of max_candidates candidates, repacks
- * the weights.  Synchronous.  *out is set only on AIF_OK. */
+/* Create a context on the current device for one deployed model of the real-time
+ * phase (Sec. 3.1, second call: the lightweight head and what it reads; Sec. 3.2:
+ * the index table of nearline item vectors it indexes): validates the
+ * configuration, sizes the workspace for max_users requests of max_candidates
+ * candidates, repacks the weights.  Synchronous.  *out is set only on AIF_OK.
+ * A bf16 model whose shapes the matrix-core kernels do not cover is still served,
+ * by the shape-agnostic fp32 kernels, at a fraction of the speed: after AIF_OK
+ * aif_last_error(*out) then holds a note that names the stage (empty string
+ * otherwise), and aif_stage_kind() answers per stage. */
 AIF_API aif_status aif_score_init(const aif_config *cfg, const aif_weights *weights, aif_ctx **out);
 
-/* Score the candidates of one request: logits (and optional sigmoid scores)
- * for every candidate, in candidate order.  Equivalent to aif_score_batch
- * with n_req = 1. */
+/* The real-time prediction call of Sec. 3.1 for one request (or one mini-batch
+ * slice of it, Sec. 1): the cached user-side tensors meet the candidates' item
+ * vectors (Sec. 3.2), the interaction-dependent terms are formed (Eq. 3's
+ * operator with the candidate as query; Sec. 3.3) and the head scores every
+ * candidate: logits (and optional sigmoid scores) in candidate order.
+ * Equivalent to aif_score_batch with n_req = 1. */
 AIF_API aif_status aif_score_request(aif_ctx *ctx, const aif_request *req, void *hip_stream);
 
-/* Score n_req requests (HOST array) in one pass: gather -> attention + cross
- * -> MLP.  Each candidate's result depends only on its own row and its
+/* The same for n_req requests (HOST array) in one pass -- concurrent users, or
+ * the mini-batch slices of one user's candidate list, which Sec. 1 has scored
+ * separately and in parallel: gather (Sec. 3.2) -> attention + cross (Eq. 3,
+ * Sec. 3.3) -> MLP head (Sec. 1).  Each candidate's result depends only on its own row and its
  * request's user tensors, so any slicing of a candidate list into requests
  * yields the same numbers.  A candidate id outside [0, n_items) does not
  * fault: its logit and score are NaN and a device counter is bumped (see
@@ -138,8 +149,10 @@ AIF_API aif_status aif_score_request(aif_ctx *ctx, const aif_request *req, void 
  * n_cand or seq_len above the context's limits). */
 AIF_API aif_status aif_score_batch(aif_ctx *ctx, const aif_request *reqs, int32_t n_req, void *hip_stream);
 
-/* Per request r, the positions (0-based, within its candidate list) of the k
- * largest logits, best first; equal logits keep the lower position first; a
+/* The cut that is the purpose of the pre-ranking stage (Sec. 1: of about 10^4
+ * retrieved candidates about 10^2 go on to ranking).  Per request r, the
+ * positions (0-based, within its candidate list) of the k largest logits, best
+ * first; equal logits keep the lower position first; a
  * NaN ranks below every number.  logits: HOST array of n_req DEVICE pointers;
  * n_cand: HOST array.  idx_out / val_out: DEVICE [n_req * k]; when
  * k > n_cand[r] the tail is idx = -1, val = -inf.  1 <= k <= 4096. */
@@ -154,8 +167,8 @@ AIF_API aif_status aif_topk(aif_ctx *ctx, const float *const *logits, const int3
 AIF_API aif_status aif_score_topk(aif_ctx *ctx, const aif_request *reqs, int32_t n_req, int32_t k, int32_t *idx_out,
                                   float *val_out, void *hip_stream);
 
-/* Nearline maintenance of the item table (Sec. 3.4: the index table of nearline results "supports both full
- * and incremental updates").
+/* Nearline maintenance of the item table (Sec. 3.4: the index table of nearline results is refreshed as a
+ * whole and also row by row).
  *
  * Incremental: row ids[i] of the context's item table becomes rows[i, :] (ids: DEVICE [n] int32; rows: DEVICE
  * [n, d_item] row-major, config.dtype, 16-byte aligned).  The table handed to aif_score_init (or
@@ -176,7 +189,8 @@ AIF_API aif_status aif_swap_table(aif_ctx *ctx, const void *new_table, int64_t n
 AIF_API void aif_score_destroy(aif_ctx *ctx);
 
 /* Message for the last failing call on this context (never NULL); with
- * ctx = NULL, the last failing aif_score_init of the calling thread. */
+ * ctx = NULL, the last failing aif_score_init of the calling thread.  Right
+ * after a successful aif_score_init: the fallback note described there. */
 AIF_API const char *aif_last_error(const aif_ctx *ctx);
 
 /* After the caller has synchronised the stream: number of out-of-range

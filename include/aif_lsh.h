@@ -4,8 +4,8 @@
  * Modeling"), the online part.
  *
  * Offline, every item's multi-modal embedding is hashed to a d'-bit signature
- * (Eq. 5) and the signatures form a uint8 index table (Sec. 4.3, "an uint8
- * embedding index table").  Online, for one request with about 10^4
+ * (Eq. 5) and the signatures form a byte-valued index table
+ * (Sec. 4.3).  Online, for one request with about 10^4
  * candidates and a long behaviour sequence, the library
  *   - looks each candidate's signature up in that table,
  *   - compares it with the signatures of the user's l history items: the

@@ -27,14 +27,39 @@ OK, EINVAL, ESHAPE, ENOMEM, ERANGE = 0, 1, 2, 3, 5
 CROSS_NONE, CROSS_HADAMARD, CROSS_SEGDOT, CROSS_BEA = 0, 1, 2, 3
 
 
-def build(force: bool = False) -> str:
-    """Compile the oracle with gcc -O2 (no fast-math) into a shared object."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS)
+_LIB_SAN = os.path.join(_HERE, "libaif_oracle_san.so")
+
+
+def sanitized() -> bool:
+    """True when this process was asked (AIF_ORACLE_SANITIZE=1) to run the oracle's AddressSanitizer +
+    UndefinedBehaviorSanitizer build; the process must then have been started with the sanitizer runtime
+    preloaded (see sanitizer_env)."""
+    return os.environ.get("AIF_ORACLE_SANITIZE", "") == "1"
+
+
+def build(force: bool = False, sanitize: bool = False) -> str:
+    """Compile the oracle with gcc -O2 (no fast-math) into a shared object; with ``sanitize`` the
+    -fsanitize=address,undefined flavour (-O1, frame pointers, any finding aborts) into a second one."""
+    out = _LIB_SAN if sanitize else _LIB
+    stale = (not os.path.exists(out)) or os.path.getmtime(out) < max(os.path.getmtime(f) for f in _SRCS)
     if force or stale:
-        subprocess.check_call(
-            ["gcc", "-O2", "-std=c99", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, *_SRCS, "-lm"]
-        )
-    return _LIB
+        flags = (["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                  "-fno-sanitize-recover=all"] if sanitize else ["-O2"])
+        subprocess.check_call(["gcc", *flags, "-std=c99", "-fopenmp", "-shared", "-fPIC", "-o", out, *_SRCS, "-lm"])
+    return out
+
+
+def sanitizer_env(env=None) -> dict:
+    """Environment for a child Python process that loads the sanitized oracle: the AddressSanitizer runtime goes
+    in front of whatever is already preloaded (an instrumented shared object cannot be loaded into a process
+    that started without it); leak reports are off (the interpreter itself never frees everything)."""
+    e = dict(os.environ if env is None else env)
+    rt = subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
+    e["LD_PRELOAD"] = rt + (":" + e["LD_PRELOAD"] if e.get("LD_PRELOAD") else "")
+    e["ASAN_OPTIONS"] = "detect_leaks=0:verify_asan_link_order=0:abort_on_error=1"
+    e["UBSAN_OPTIONS"] = "halt_on_error=1:print_stacktrace=1"
+    e["AIF_ORACLE_SANITIZE"] = "1"
+    return e
 
 
 _lib = None
@@ -43,7 +68,7 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        _lib = C.CDLL(build(sanitize=sanitized()))
         _lib.aifo_sigmoid.restype = C.c_double
         _lib.aifo_sigmoid.argtypes = [C.c_double]
     return _lib

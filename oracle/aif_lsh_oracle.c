@@ -101,8 +101,8 @@ void aifo_simtier(const int32_t *equal, int L, int d_bits, int n_tiers, int32_t 
     }
 }
 
-/* One request: for every candidate, look its signature up in the table (Sec. 4.3: "an uint8 embedding
- * index table"), compare it with the signatures of the user's history (Eq. 7), then Eq. 8 and Eq. 9
+/* One request: for every candidate, look its signature up in the table (Sec. 4.3: the signatures are kept
+ * as a byte-valued index table), compare it with the signatures of the user's history (Eq. 7), then Eq. 8 and Eq. 9
  * from the SAME similarities (the reuse Table 3 counts on).
  * sig_table [n_items, d'/8], seq_sig [L, d'/8], u_seq [L, d]; out: din [n, d], tiers [n, n_tiers],
  * equal_out [n, L] (may be NULL). */

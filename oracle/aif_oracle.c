@@ -20,8 +20,8 @@
  *      with the candidate in the place of the profile,
  *   4. real-time half of the cross features (Sec. 3.3): the cached user
  *      component combined with the item vector,
- *   5. model input = [user | item | attention | cross] (Sec. 1, "constructs
- *      model input tensors"),
+ *   5. model input = [user | item | attention | cross] (Sec. 1: the input
+ *      tensor is assembled before the forward pass),
  *   6. shallow MLP head, ReLU between layers, linear last layer -> logit,
  *      sigmoid -> score (Sec. 1: the head is a small MLP),
  *   7. keep the best k of the request (Sec. 1: about 10^4 -> about 10^2).
@@ -60,8 +60,8 @@ int aifo_gather(const float *table, int64_t n_items, int d_item,
     return AIFO_OK;
 }
 
-/* Nearline maintenance of the index table (Sec. 3.4: the table of nearline results "supports both full and
- * incremental updates").  Incremental update: row ids[i] of the table becomes rows[i, :], entries applied in
+/* Nearline maintenance of the index table (Sec. 3.4: the table of nearline results is replaced as a whole or
+ * patched row by row).  Incremental update: row ids[i] of the table becomes rows[i, :], entries applied in
  * order (a later entry for the same id replaces an earlier one); ids outside the table are skipped and
  * counted in *n_skipped.  A full update is a new table: nothing to compute. */
 void aifo_update_rows(float *table, int64_t n_items, int d_item,

@@ -227,6 +227,9 @@ class Context:
         if st != AIF_OK:
             raise AifError(st, self._lib.aif_last_error(self._h).decode())
 
+    def aif_last_error(self) -> str:
+        return self._lib.aif_last_error(self._h).decode()
+
     def aif_score_request(self, req: Request):
         arr = pack_requests([req])
         self._check(self._lib.aif_score_request(self._h, arr, _stream()))

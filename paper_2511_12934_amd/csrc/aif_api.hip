@@ -251,6 +251,15 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
     const bool mlp_ok = c->mfma.mlp || mlp_generic_lds_bytes(m) <= 160 * 1024;
     if (!attn_ok) return fail(nullptr, AIF_ESHAPE, "max_seq_len %d needs more LDS than a compute unit has", c->max_seq_len);
     if (!mlp_ok) return fail(nullptr, AIF_ESHAPE, "MLP layers wider than the LDS budget of the generic kernel");
+    // a bf16 model outside the matrix-core kernels' shapes still runs, much more slowly: say so where the caller can read it
+    if (m.dtype == 1 && !(c->mfma.attn && c->mfma.mlp)) {
+        const char *force = getenv("AIF_FORCE_GENERIC");
+        char note[256];
+        snprintf(note, sizeof note, "note: bf16 model served by the shape-agnostic fp32 kernels for%s%s%s (%s)",
+                 c->mfma.attn ? "" : " attention", !c->mfma.attn && !c->mfma.mlp ? " and" : "", c->mfma.mlp ? "" : " the MLP head",
+                 force && force[0] == '1' ? "AIF_FORCE_GENERIC=1" : "no matrix-core kernel for these widths");
+        c->err = note;
+    }
 
     // ---- workspace ---------------------------------------------------------
     c->x_rows = (size_t)c->max_users * round_up(c->max_candidates, ROW_BLOCK);

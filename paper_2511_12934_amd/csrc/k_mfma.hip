@@ -30,6 +30,10 @@ hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, size_t x_ro
     }
 
     plan.mlp_variant = mlp_mfma_variant(m);
+    {
+        const char *lay = getenv("AIF_MLP_LAYERED");    // testing and measurement: one launch per layer even where a fused chain serves the shape
+        if (lay && lay[0] == '1') plan.mlp_variant = -1;
+    }
     if (plan.mlp_variant < 0 && mlp_layers_ok(m)) {
         plan.mlp_variant = MLP_VARIANT_LAYERS;
         for (int i = 0; i < 2; ++i) {

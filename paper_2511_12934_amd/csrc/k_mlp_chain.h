@@ -1,5 +1,5 @@
-// a6-a7 on the matrix cores -- the MLP head (Sec. 1: "shallow multilayer
-// perceptron") as one fused bf16 MFMA chain.
+// a6-a7 on the matrix cores -- the MLP head (Sec. 1: a light MLP of few
+// layers) as one fused bf16 MFMA chain.
 //
 // The products are formed transposed, H^T = W . X^T: the weights are the A
 // operand (rows = output features) and the candidates are the columns of the
@@ -21,6 +21,8 @@
 // This header holds the kernel template and its launcher; each chain shape is instantiated in a translation unit
 // of its own (k_mlp_chain_*.hip) so that they compile side by side.
 #pragma once
+#include <utility>
+
 #include "k_mfma.h"
 #include "mfma_util.h"
 
@@ -34,11 +36,18 @@ typedef const f32x4 __attribute__((address_space(3))) *lds_f32x4_t;
 
 
 template <int N> struct IC { static constexpr int value = N; };
+template <int I0, class F, int... Is> __device__ __forceinline__ void static_for_seq(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(IC<I0 + Is>{}), ...);
+}
+// f(IC<I>{}), ..., f(IC<N - 1>{}): runs of at most 256 steps as one fold expression each -- the widest chain is a
+// straight line of 2,176 steps, more than the compiler's limits on template recursion or on the terms of one fold
 template <int I, int N, class F> __device__ __forceinline__ void static_for(F &&f)
 {
     if constexpr (I < N) {
-        f(IC<I>{});
-        static_for<I + 1, N>(f);
+        constexpr int n = N - I < 256 ? N - I : 256;
+        static_for_seq<I>(f, std::make_integer_sequence<int, n>{});
+        static_for<I + n, N>(f);
     }
 }
 
@@ -103,8 +112,11 @@ __device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
 }
 
 // K1: layer-1 contraction after the user fold; H1..H3: hidden widths (0 = absent).
-// One wave = 32 candidates; a block = WAVES waves sharing the weight ring (four waves and a 64 KB ring in every
-// shape that is built: two such blocks share a compute unit, out of phase with each other).
+// One wave = 32 candidates; a block = WAVES waves sharing the weight ring (four waves in every shape that is built).
+// PER_CU blocks share a compute unit: two, out of phase with each other, where a candidate's activations of two
+// consecutive layers fit in half the registers of a SIMD lane (256); one, with all 512 (the accumulation-register half
+// holds the activations the matrix cores read), for the widest head: 448 -> 1024 -> 512 -> 256, whose 1024-wide
+// hidden layer alone is 256 registers per lane -- still less than the trip through HBM a launch per layer costs.
 //
 // The body is one straight line of nf() steps, one MFMA each.  Step F
 //   - asks LDS for the fragment of step F + RING - 1 (a ring of RING fragment registers keeps the
@@ -126,8 +138,8 @@ __device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
 // scalar loads at the block's start and its layer-1 biases by a direct-to-LDS load into a second buffer.
 // Only its input rows cannot come early (no register is free before the first tile's last MFMA): they are
 // asked for at the first tile's end and the second tile's first MFMAs wait for them.
-template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS>
-__global__ __launch_bounds__(WAVES * 64, 2) void k_mlp_mfma(int64_t n_items, const ReqDesc *__restrict__ reqs,
+template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS, int PER_CU>
+__global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items, const ReqDesc *__restrict__ reqs,
                                                            const int32_t *__restrict__ blk_req, const char *__restrict__ X,
                                                            XLayout xl, MlpPack pk, const float *__restrict__ bias1, int n_pairs)
 {
@@ -390,14 +402,15 @@ static inline int n_cu()
     return n;
 }
 
-template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS>
+template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS, int PER_CU = 2>
 static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, const MlpPack &pk, const float *bias1,
                               hipStream_t s)
 {
     using C = Chain<K1, H1, H2, H3, WAVES, SF, SLOTS>;
     constexpr int LDS = C::lds_bytes;
     constexpr int ROWS = WAVES * 32;
-    auto kern = k_mlp_mfma<K1, H1, H2, H3, WAVES, SF, SLOTS>;
+    auto kern = k_mlp_mfma<K1, H1, H2, H3, WAVES, SF, SLOTS, PER_CU>;
+    static_assert(PER_CU * C::lds_bytes <= 160 * 1024, "the blocks of a compute unit share its LDS");
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -408,7 +421,7 @@ static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, con
     // goes one per block, after the pairs, so that the launch ends evenly (a pair on a unit while others idle would
     // cost more than the pairs save), and a batch of up to that many tiles keeps every unit it can reach busy.
     const int n_tiles = b.n_blk * (ROW_BLOCK / ROWS);
-    const int per_cu = 8 / WAVES;                     // blocks of eight waves' worth of registers a unit holds
+    const int per_cu = PER_CU;                        // blocks a unit holds at a time
     int n_single = n_tiles < per_cu * n_cu() ? n_tiles : per_cu * n_cu();
     if ((n_tiles - n_single) & 1) ++n_single;
     const int n_pairs = (n_tiles - n_single) / 2;

@@ -1,5 +1,5 @@
-// a6-a7 for WIDE heads on the matrix cores -- the MLP head (Sec. 1: "shallow
-// multilayer perceptron") one layer per launch, for models whose hidden layers
+// a6-a7 for WIDE heads on the matrix cores -- the MLP head (Sec. 1: a light MLP
+// of few layers) one layer per launch, for models whose hidden layers
 // are too wide for a candidate's activations to stay in registers across the
 // chain (k_mlp_mfma): e.g. 448 -> 1024 -> 512 -> 256 -> 1.
 //

@@ -28,6 +28,7 @@ namespace aif {
 hipError_t mlp_chain_c2(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 hipError_t mlp_chain_c3(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 hipError_t mlp_chain_c4(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
+hipError_t mlp_chain_c5(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 
 // ---- weights into fragment order --------------------------------------------
 // dst[((rt * KS + j) * 64 + lane) * 8 + s] = W[32 rt + lane % 32][col0 + k(j, lane / 32, s)]
@@ -63,6 +64,7 @@ int mlp_mfma_variant(const Model &m)
     if (nh == 2 && k1 == 192 && h1 == 256 && h2 == 128) return 0;
     if (nh == 2 && k1 == 192 && h1 == 512 && h2 == 256) return 1;
     if (nh == 1 && k1 == 384 && h1 == 256) return 2;
+    if (nh == 3 && k1 == 448 && h1 == 1024 && h2 == 512 && h3 == 256) return 3;
     return -1;
 }
 
@@ -74,6 +76,7 @@ hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const
     case 0: return mlp_chain_c2(m, b, X, pk, bias1, s);
     case 1: return mlp_chain_c3(m, b, X, pk, bias1, s);
     case 2: return mlp_chain_c4(m, b, X, pk, bias1, s);
+    case 3: return mlp_chain_c5(m, b, X, pk, bias1, s);
     default: return hipErrorInvalidValue;
     }
 }

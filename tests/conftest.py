@@ -12,6 +12,15 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_terminal_summary(terminalreporter):
+    try:
+        from helpers import USED
+    except Exception:
+        return
+    for what, frac in sorted(USED.items()):
+        terminalreporter.write_line(f"[tolerance] {what}: worst comparison used {frac:.2f} of its bound")
+
+
 def pytest_collection_modifyitems(config, items):
     try:
         import torch

@@ -11,6 +11,8 @@ from paper_2511_12934_amd import workloads as wl
 # the scale of the request; bf16 logits within 2e-2 absolute.
 F32_REL = 1e-5
 BF16_ABS = 2e-2
+# largest fraction of a tolerance that any comparison of this session used (printed at the end of the run)
+USED = {}
 
 
 def oracle_scores(cfg: wl.Config, model: wl.Model, table: np.ndarray, user: wl.User,
@@ -48,6 +50,49 @@ def assert_logits_close(dtype: str, z_gpu: np.ndarray, z_ref: np.ndarray, what: 
                                 f"err {err[worst]:.3e} tol {tol[worst]:.3e}")
 
 
+# Regression guard for bf16 logits AT THE CONFIGURATIONS' SCALE (logits of rms ~0.03, where the benchmark spec's 2e-2 is
+# most of the spread).  With u = 2^-8 the unit roundoff of bf16, the GPU path rounds the attention and cross blocks
+# and every hidden activation once (reading R16); each rounding is independent, about uniform in +-u of the value,
+# so one layer's roundings move a pre-activation by about (u / sqrt 3) * sqrt(sum_j w_j^2 h_j^2), which is the scale
+# of that pre-activation itself when the terms' signs are mixed.  Through d roundings in a row the logit's error is
+# therefore about N(0, (u * sqrt(d / 3) * rms z)^2): sqrt(d / 3) is 1 for the two-hidden-layer heads, 1.3 for
+# C5's (three hidden layers, the projected query rounded as well).  The guard: RMS of the error over a request
+# <= 2 u rms(z) = 2^-7 rms(z) (half again as much as the model's largest figure), and every single error
+# <= 2^-7 |z| + 2^-5 rms(z) (8 u rms z: beyond six standard deviations of that model, for the 10^4 .. 10^6 candidates compared).
+BF16_GUARD_RMS = 2.0 ** -7
+BF16_GUARD_MAX = (2.0 ** -7, 2.0 ** -5)
+
+
+def assert_bf16_logits_tight(z_gpu: np.ndarray, z_ref: np.ndarray, what: str = ""):
+    """The scale-aware guard above, for whole requests at a configuration's own scale.  Returns
+    (max |dz|, rms dz, rms z) for the caller to print."""
+    err = np.abs(z_gpu.astype(np.float64) - z_ref)
+    rms_z = float(np.sqrt(np.mean(np.square(z_ref))))
+    rms_e = float(np.sqrt(np.mean(np.square(err))))
+    tol = BF16_GUARD_MAX[0] * np.abs(z_ref) + BF16_GUARD_MAX[1] * rms_z
+    worst = int(np.argmax(err - tol))
+    assert np.all(err <= tol), (f"{what}: logit {worst}: gpu {z_gpu[worst]!r} oracle {z_ref[worst]!r} "
+                                f"err {err[worst]:.3e} guard {tol[worst]:.3e} (rms z {rms_z:.3e})")
+    assert rms_e <= BF16_GUARD_RMS * rms_z, f"{what}: rms error {rms_e:.3e} > 2^-7 * rms z {rms_z:.3e}"
+    return float(err.max()), rms_e, rms_z
+
+
+def topk_recall(idx_gpu: np.ndarray, z_ref: np.ndarray, k: int, band: float, what: str = "") -> float:
+    """The GPU's top-k (taken on its own logits) against the oracle's top-k of the oracle's logits.  With every
+    logit within `band` of the oracle's, a candidate can sit on the wrong side of the cut only if its oracle logit is
+    within 2 * band of the k-th best: the two sets may differ only inside that band.  Returns the recall."""
+    n = z_ref.size
+    kk = min(k, n)
+    got = set(idx_gpu[:kk].tolist())
+    order = np.argsort(-z_ref, kind="stable")
+    want = set(order[:kk].tolist())
+    zk = z_ref[order[kk - 1]]
+    for i in got ^ want:
+        assert abs(z_ref[i] - zk) <= 2 * band, (f"{what}: position {i} (oracle z {z_ref[i]:.6f}, k-th best {zk:.6f}) is on the "
+                                                f"wrong side of the cut by more than 2 * {band:.3e}")
+    return len(got & want) / kk
+
+
 def feature_tolerance(dtype: str, ref: np.ndarray) -> np.ndarray:
     """Attention / cross blocks of the workspace.
     fp32: 2e-5 of the block's scale (fp32 accumulation over <= a few thousand terms).
@@ -68,6 +113,10 @@ def assert_features_close(dtype: str, got: np.ndarray, ref: np.ndarray, what: st
     assert np.all(np.isfinite(got)), f"{what}: non-finite"
     w = np.unravel_index(int(np.argmax(err - tol)), err.shape) if err.size else ()
     assert np.all(err <= tol), f"{what}: worst at {w}: got {got[w]!r} ref {ref[w]!r} tol {tol[w]:.3e}"
+    used = float(np.max(err / tol)) if err.size else 0.0       # how much of the tolerance the worst element used
+    if dtype != "f32":
+        USED["bf16 feature tolerance"] = max(USED.get("bf16 feature tolerance", 0.0), used)
+    return used
 
 
 def check_topk_against_oracle_logits(dtype: str, idx_gpu: np.ndarray, z_ref: np.ndarray, k: int):

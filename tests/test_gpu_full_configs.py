@@ -1,14 +1,16 @@
 """Configurations 3-5 (and C3 with the BEA cross block) at full size, in the launch configuration the benchmark
-times (one aif_score_batch over all users + one aif_topk): sampled candidates
-against the oracle one by one, top-k of every user against the oracle's full
-stable sort of the GPU's logits, and the properties that hold at any size."""
+times (one aif_score_batch over all users + one aif_topk): every candidate of every user
+against the oracle (C5: of four users), to the benchmark spec's bound and to a scale-aware one that
+bites at these configurations' small logits; top-k of every user bit-exact against the oracle's
+full stable sort of the GPU's logits, and its recall against the oracle's own top-k."""
 import numpy as np
 import pytest
 
 import oracle
 from paper_2511_12934_amd import workloads as wl
 
-from helpers import assert_features_close, assert_logits_close, oracle_scores_rows
+from helpers import (BF16_GUARD_MAX, BF16_GUARD_RMS, assert_bf16_logits_tight, assert_features_close, assert_logits_close,
+                     oracle_scores_rows, topk_recall)
 
 pytestmark = pytest.mark.gpu
 
@@ -34,19 +36,30 @@ def test_full_size_batched_config(name):
         oi, ov = oracle.topk(z.astype(np.float64), cfg.top_k)
         assert np.array_equal(idx[u], oi), f"user {u}"
         assert np.array_equal(val[u].astype(np.float64), ov), f"user {u}"
-    # sampled candidates of sampled users against the oracle
-    users = sorted({0, 1, cfg.n_users - 1, int(rng.integers(0, cfg.n_users))})
+    # EVERY candidate of every user against the oracle (C5, whose oracle costs 3.4 Mflop per candidate: four whole users)
+    users = list(range(cfg.n_users)) if name != "C5" else sorted({0, 1, cfg.n_users - 1, int(rng.integers(0, cfg.n_users))})
+    all_pos = np.arange(cfg.n_cand)
+    recalls, worst_max, worst_rms, used_a, used_c = [], 0.0, 0.0, 0.0, 0.0
     for u in users:
-        pos = np.unique(np.concatenate([[0, 255, 256, cfg.n_cand - 1], rng.integers(0, cfg.n_cand, 124)]))
-        rows = w.rows_of(u, pos)
-        ref = oracle_scores_rows(cfg, w.model, rows, w.requests[u].user)
-        z = w.dev[u].logits.cpu().numpy()[pos]
-        assert_logits_close(cfg.dtype, z, ref.logits, f"{name} user {u}")
-        X = R.peek_features(w.ctx, cfg, u, cfg.n_cand)[pos]
+        rows = w.rows_of(u, all_pos)
+        ref = oracle_scores_rows(cfg, w.model, rows, w.requests[u].user, n_threads=16)
+        z = w.dev[u].logits.cpu().numpy()
+        assert_logits_close(cfg.dtype, z, ref.logits, f"{name} user {u}")                 # the benchmark spec's bound
+        e_max, e_rms, z_rms = assert_bf16_logits_tight(z, ref.logits, f"{name} user {u}")  # the bound that bites at this scale
+        worst_max, worst_rms = max(worst_max, e_max / z_rms), max(worst_rms, e_rms / z_rms)
+        X = R.peek_features(w.ctx, cfg, u, cfg.n_cand)
         assert np.array_equal(X[:, :cfg.d_item], rows), "gather is not an exact row copy"
-        assert_features_close(cfg.dtype, X[:, cfg.d_item:cfg.d_item + cfg.d_attn], ref.attn, "attention")
-        assert_features_close(cfg.dtype, X[:, cfg.d_item + cfg.d_attn:], ref.cross, "cross")
-        print(f"[case] user {u}: max |dz| = {np.abs(z - ref.logits).max():.3e}", flush=True)
+        used_a = max(used_a, assert_features_close(cfg.dtype, X[:, cfg.d_item:cfg.d_item + cfg.d_attn], ref.attn, "attention"))
+        used_c = max(used_c, assert_features_close(cfg.dtype, X[:, cfg.d_item + cfg.d_attn:], ref.cross, "cross"))
+        # the GPU's top-k against the ORACLE's top-k: sets may differ only within the guard's band of the cut
+        band = BF16_GUARD_MAX[0] * float(np.abs(ref.logits).max()) + BF16_GUARD_MAX[1] * z_rms
+        recalls.append(topk_recall(idx[u], ref.logits, cfg.top_k, band, f"{name} user {u}"))
+    print(f"[case] {name}: {len(users)} users x {cfg.n_cand} candidates: max |dz| = {worst_max:.4f} rms z, rms dz = {worst_rms:.5f} rms z "
+          f"(guards {BF16_GUARD_MAX[1]:.4f}, {BF16_GUARD_RMS:.5f}); feature tolerance used: attention {used_a:.2f}, cross {used_c:.2f}; "
+          f"top-{cfg.top_k} recall vs oracle: mean {np.mean(recalls):.4f}, min {np.min(recalls):.4f}", flush=True)
+    # errors of ~1 % of the logits' spread move one or two candidates across the cut (density of logits at the k-th
+    # best x error): the sets agree to a few positions
+    assert np.mean(recalls) >= 0.95 and np.min(recalls) >= 0.90, (np.mean(recalls), np.min(recalls))
     # determinism of the whole step
     z0 = [d.logits.clone() for d in w.dev[:2]]
     w.step()

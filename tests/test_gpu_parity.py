@@ -344,6 +344,14 @@ def test_forced_generic_kernels_on_bf16_config(R, torch, monkeypatch):
     (z,), _, drs, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), [(u, ids)])
     assert ctx.aif_stage_kind("attention") == 0 and ctx.aif_stage_kind("mlp") == 0
     assert_logits_close("bf16", z, oracle_scores(cfg, model, table, u, ids).logits)
+    # the fall-back is not silent: the context says which stages left the matrix cores
+    dm = R.DeviceModel(cfg, model)
+    ctx2 = R.make_context(cfg, dm, R.to_device(table, "bf16"), max_candidates=300, max_users=1)
+    note = ctx2.aif_last_error()
+    assert "shape-agnostic" in note and "attention" in note and "MLP" in note, note
+    monkeypatch.delenv("AIF_FORCE_GENERIC")
+    ctx3 = R.make_context(cfg, dm, R.to_device(table, "bf16"), max_candidates=300, max_users=1)
+    assert ctx3.aif_last_error() == ""
 
 
 def test_mfma_kernels_on_row_major_workspace(R, torch, monkeypatch):
@@ -593,6 +601,39 @@ def test_projection_attention_with_16_wide_heads(R, torch, shape, sigma):
     parts, _, _, _ = run_batch(R, torch, cfg, model, table_dev, [(u, ids[:256]), (u, ids[256:300]), (u, ids[300:])],
                                max_seq_len=530)
     assert np.array_equal(np.concatenate(parts), zs[7])
+
+
+def test_widest_head_as_one_fused_chain(R, torch, monkeypatch):
+    """C5's head (448 -> 1024 -> 512 -> 256 -> 1 after the user fold) runs as ONE launch with a candidate's activations
+    in registers.  Enough candidates (more 128-candidate tiles than compute units) that blocks take two tiles each as
+    well as one; non-zero biases; against the oracle to the scale-aware bound, against the one-launch-per-layer route
+    (AIF_MLP_LAYERED=1: same products, hidden activations through HBM) within two roundings, and sliced vs whole
+    bit for bit."""
+    from helpers import assert_bf16_logits_tight
+    cfg = wl.CONFIGS["C5"].scaled(n_items=20000, seq_len=64)
+    _say("C5 head, fused chain: 3 requests x 12000 candidates")
+    rng = np.random.default_rng(97)
+    model = wl.make_model(cfg, seed=5, bias_scale=0.02)
+    table = wl.make_table_host(cfg, rng, n_items=20000)
+    table_dev = R.to_device(table, "bf16")
+    sampler = wl.IdSampler(cfg, 20000)
+    reqs = [(wl.make_user(cfg, rng), sampler.sample(rng, n)) for n in (12000, 11999, 12001)]
+    zs, _, _, ctx = run_batch(R, torch, cfg, model, table_dev, reqs)
+    assert ctx.aif_stage_kind("mlp") == 1 and ctx.aif_last_error() == ""
+    for i, (u, ids) in enumerate(reqs):
+        ref = oracle_scores(cfg, model, table, u, ids, n_threads=16)
+        assert_logits_close("bf16", zs[i], ref.logits, f"request {i}")
+        e_max, e_rms, z_rms = assert_bf16_logits_tight(zs[i], ref.logits, f"request {i}")
+        print(f"[case] request {i}: max |dz| {e_max:.3e}, rms dz {e_rms:.3e}, rms z {z_rms:.3e}", flush=True)
+    u, ids = reqs[2]
+    parts, _, _, _ = run_batch(R, torch, cfg, model, table_dev, [(u, ids[:1000]), (u, ids[1000:1300]), (u, ids[1300:])])
+    assert np.array_equal(np.concatenate(parts), zs[2])
+    monkeypatch.setenv("AIF_MLP_LAYERED", "1")
+    zl, _, _, ctx_l = run_batch(R, torch, cfg, model, table_dev, reqs)
+    assert ctx_l.aif_stage_kind("mlp") == 1
+    for i in range(3):
+        d = np.abs(zl[i] - zs[i]).max()
+        assert d <= 2.0 ** -6 * np.sqrt(np.mean(np.square(zs[i]))) + 1e-6, (i, d)
 
 
 # ---------------------------------------------------------------------------
