@@ -239,6 +239,12 @@ AIF_API aif_status aif_profile_end(aif_ctx *ctx, double *ms_sum, int32_t *n_call
  * packing of K/V; the gather's bytes are moved under the attention stage). */
 AIF_API int32_t aif_stage_kind(const aif_ctx *ctx, int32_t stage);
 
+/* Number of distinct users the LAST scoring call staged (Sec. 3.1: user-side work is done per user, not per
+ * mini-batch).  Requests of one call whose user_vec, cross_vecs, seq_keys, seq_vals and seq_len are all equal --
+ * the slices of one candidate list -- count once: the user fold and the packing of K/V run once for them, and
+ * every slice reads the shared result.  -1 for a NULL context, 0 before the first call. */
+AIF_API int32_t aif_last_user_slots(const aif_ctx *ctx);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,7 +9,9 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <new>
+#include <tuple>
 #include <string>
 #include <vector>
 
@@ -18,6 +20,7 @@ using namespace aif;
 namespace {
 
 constexpr int NSLOT = 8;
+
 thread_local std::string g_init_error = "";
 
 struct DevBuf {
@@ -58,6 +61,7 @@ struct aif_ctx {
     size_t x_rows = 0;
     int n_cu = 256;                   // compute units of the device (sizes the attention groups)
     bool attn_indexed = false;        // the last scoring call's attention kernel read the item table itself
+    int last_slots = 0;               // distinct users (user slots) of the last scoring call
     bool separate_gather = false;     // testing (AIF_SEPARATE_GATHER=1): the gather always as blocks or a launch of its own
 
     // descriptor staging ring
@@ -269,8 +273,8 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
     HIP_TRY(nullptr, hipMemsetAsync(c->bad.p, 0, 4, s));
 
     const size_t n_blk_max = c->x_rows / ROW_BLOCK;
-    size_t sb = (size_t)c->max_users * sizeof(ReqDesc) + (n_blk_max + 4) * sizeof(int32_t) +
-                attn_max_groups(c->x_rows, c->max_users) * sizeof(AttnGroup);
+    size_t sb = (size_t)c->max_users * sizeof(ReqDesc) + 2 * (n_blk_max + 4) * sizeof(int32_t) +
+                (size_t)c->max_users * sizeof(int32_t) + 16 + attn_max_groups(c->x_rows, c->max_users) * sizeof(AttnGroup);
     {
         int dev = 0;
         hipDeviceProp_t prop;
@@ -345,12 +349,37 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
     char *h = c->h_stage + (size_t)slot * c->slot_bytes;
     char *d = (char *)c->d_stage.p + (size_t)slot * c->slot_bytes;
     ReqDesc *hd = (ReqDesc *)h;
-    int32_t *hb = (int32_t *)(h + (size_t)n_req * sizeof(ReqDesc));
     c->row_base.assign(n_req, 0);
+    // Rows per request first (the tables that follow the descriptors are sized by the block count), and the user
+    // slots: requests that bring the same user tensors -- the mini-batch slices of one candidate list -- share one
+    // slot, so that the user-side staging runs once per user and not once per slice (Sec. 3.1).
+    int n_blk_total = 0;
+    for (int r = 0; r < n_req; ++r) n_blk_total += round_up(reqs[r].n_cand, ROW_BLOCK) / ROW_BLOCK;
+    int32_t *hb = (int32_t *)(h + (size_t)n_req * sizeof(ReqDesc));       // blk_req [n_blk]
+    int32_t *hs = hb + n_blk_total;                                        // blk_slot [n_blk]
+    int32_t *hq = hs + n_blk_total;                                        // slot_req [n_slots]
+    int n_slots = 0;
+    {
+        typedef std::tuple<const void *, const void *, const void *, const void *, int32_t> UserKey;
+        std::map<UserKey, int> seen;
+        for (int r = 0; r < n_req; ++r) {
+            const aif_request &q = reqs[r];
+            const UserKey key(q.user_vec, q.cross_vecs, q.seq_keys, q.seq_vals, q.seq_len);
+            auto it = n_req > 1 ? seen.find(key) : seen.end();
+            if (it == seen.end()) {
+                if (n_req > 1) seen.emplace(key, n_slots);
+                hq[n_slots] = r;
+                hd[r].slot = n_slots++;
+            } else
+                hd[r].slot = it->second;
+        }
+    }
+    c->last_slots = n_slots;
     int rows = 0;
     for (int r = 0; r < n_req; ++r) {
         const aif_request &q = reqs[r];
         ReqDesc &e = hd[r];
+        e.pad_ = 0;
         e.user_vec = q.user_vec;
         e.cross_vecs = q.cross_vecs ? q.cross_vecs : q.user_vec;
         e.seq_keys = q.seq_keys;
@@ -364,16 +393,22 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         e.index = r;
         c->row_base[r] = rows;
         const int nb = round_up(q.n_cand, ROW_BLOCK) / ROW_BLOCK;
-        for (int j = 0; j < nb; ++j) hb[rows / ROW_BLOCK + j] = r;
+        for (int j = 0; j < nb; ++j) {
+            hb[rows / ROW_BLOCK + j] = r;
+            hs[rows / ROW_BLOCK + j] = e.slot;
+        }
         rows += nb * ROW_BLOCK;
     }
     Batch b;
     b.reqs = (const ReqDesc *)d;
-    b.blk_req = (const int32_t *)(d + (size_t)n_req * sizeof(ReqDesc));
+    b.blk_req = (const int32_t *)(d + ((char *)hb - h));
+    b.blk_slot = (const int32_t *)(d + ((char *)hs - h));
+    b.slot_req = (const int32_t *)(d + ((char *)hq - h));
     b.n_req = n_req;
     b.n_blk = rows / ROW_BLOCK;
-    // groups of tiles for the attention kernel that keeps K/V resident, 16-byte aligned after blk_req
-    const size_t goff = ((size_t)n_req * sizeof(ReqDesc) + (size_t)b.n_blk * sizeof(int32_t) + 15) / 16 * 16;
+    b.n_slots = n_slots;
+    // groups of tiles for the attention kernel that keeps K/V resident, 16-byte aligned after the three tables
+    const size_t goff = ((size_t)((char *)(hq + n_slots) - h) + 15) / 16 * 16;
     b.n_groups = c->mfma.attn ? attn_plan_groups(m, hd, n_req, c->n_cu, (AttnGroup *)(h + goff)) : 0;
     b.groups = (const AttnGroup *)(d + goff);
     size_t bytes = goff + (size_t)b.n_groups * sizeof(AttnGroup);
@@ -408,7 +443,7 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         StageUpload up{};
         if (stage_uploads) {
             const char *mapped = c->h_stage_dev + (size_t)slot * c->slot_bytes;
-            up = {mapped, d, bytes, (const ReqDesc *)mapped};
+            up = {mapped, d, bytes, (const ReqDesc *)mapped, (const int32_t *)(mapped + ((char *)hq - h))};
         }
         HIP_TRY(c, launch_stage(m, b, c->table, c->X.p, (int32_t *)c->bad.p, (const float *)c->w1u.p,
                                 c->has_bias[0] ? (const float *)c->bias[0].p : nullptr, (float *)c->bias1.p, c->mfma,
@@ -638,6 +673,8 @@ aif_status aif_profile_end(aif_ctx *c, double *ms_sum, int32_t *n_calls)
     c->prof_batch_calls = c->prof_topk_calls = 0;
     return AIF_OK;
 }
+
+int32_t aif_last_user_slots(const aif_ctx *c) { return c ? c->last_slots : -1; }
 
 int32_t aif_stage_kind(const aif_ctx *c, int32_t stage)
 {

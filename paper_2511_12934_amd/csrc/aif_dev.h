@@ -23,6 +23,9 @@ struct ReqDesc {
     int32_t n_cand;
     int32_t row_base;           // first workspace row of this request (multiple of ROW_BLOCK)
     int32_t index;              // position in the batch
+    int32_t slot;               // user slot: requests of one call that bring the same user tensors (the mini-batch
+                                // slices of one candidate list, Sec. 3.1) share one folded bias, one packed K/V
+    int32_t pad_;
 };
 
 // A run of 32-candidate tiles of ONE request, the unit of work of the attention kernel that keeps
@@ -36,10 +39,14 @@ struct Batch {
     const ReqDesc *reqs;        // device, [n_req]
     const int32_t *blk_req;     // device, [n_blk]: request owning each ROW_BLOCK of the workspace
     const AttnGroup *groups;    // device, [n_groups]; n_groups = 0: the batch does not use them
+    const int32_t *blk_slot;    // device, [n_blk]: user slot of the request owning each ROW_BLOCK (= reqs[blk_req[i]].slot)
+    const int32_t *slot_req;    // device, [n_slots]: a request that brings slot s's user tensors; null: slot s = request s
     int32_t n_req;
     int32_t n_blk;
     int32_t n_groups;
+    int32_t n_slots;            // distinct users of the call: the user-side staging (fold, K/V packing) runs once per slot
 };
+__device__ __forceinline__ int slot_request(const Batch &b, int slot) { return b.slot_req ? b.slot_req[slot] : slot; }
 
 struct Model {
     int32_t dtype;              // 0 fp32, 1 bf16
@@ -106,7 +113,7 @@ hipError_t staging_upload(const char *host, const char *mapped, size_t off, void
 hipError_t launch_update_rows(const Model &m, void *table, const int32_t *ids, const void *rows, int n, int32_t *bad,
                               hipStream_t s);
 
-// a2: per request, bias1[r, n] = b1[n] + sum_m W1[n, m] u[m] over the user columns (w1u: those columns
+// a2: per user slot s, bias1[s, n] = b1[n] + sum_m W1[n, m] u[m] over the user columns (w1u: those columns
 // transposed, fp32 [d_user, H1]).
 hipError_t launch_user_fold(const Model &m, const Batch &b, const float *w1u, const float *b1,
                             float *bias1, hipStream_t s);

@@ -237,6 +237,7 @@ aif_status aif_user_precompute(aif_user_ctx *c, const aif_user_request *users, i
         e.n_cand = q.seq_len + 1;           // every position, and the profile, is a query
         e.row_base = rows;
         e.index = r;
+        e.slot = r;                         // every user of the call is a user slot of its own
         hu[r] = UserDesc{q.profile, q.seq, q.user_vec_out, q.seq_out, q.seq_len, rows};
         const int nb = round_up(e.n_cand, ROW_BLOCK) / ROW_BLOCK;
         for (int j = 0; j < nb; ++j) hb[rows / ROW_BLOCK + j] = r;
@@ -247,6 +248,9 @@ aif_status aif_user_precompute(aif_user_ctx *c, const aif_user_request *users, i
     const UserDesc *du = (const UserDesc *)(d + (size_t)n_users * sizeof(ReqDesc));
     b.blk_req = (const int32_t *)(d + (size_t)n_users * (sizeof(ReqDesc) + sizeof(UserDesc)));
     b.n_req = n_users;
+    b.n_slots = n_users;
+    b.blk_slot = nullptr;                   // read by the MLP kernels only
+    b.slot_req = nullptr;                   // slot s = request s
     b.n_blk = rows / ROW_BLOCK;
     const size_t goff = ((size_t)n_users * (sizeof(ReqDesc) + sizeof(UserDesc)) + (size_t)b.n_blk * sizeof(int32_t) + 15) / 16 * 16;
     b.n_groups = c->mfma.attn ? attn_plan_groups(m, hr, n_users, c->n_cu, (AttnGroup *)(h + goff)) : 0;

@@ -124,7 +124,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
 
     const int L = rd.seq_len, H = m.n_heads;
     const int nkt = (L + 31) >> 5, nst = (nkt + 1) >> 1, total = H * nst;
-    const char *pk = kvpack + (size_t)r * pack_stride;
+    const int us = rd.slot;                         // K/V and key norms are kept per user, not per slice
+    const char *pk = kvpack + (size_t)us * pack_stride;
     const int local = local0 + wave * 32 + col;
     const bool live = local < rd.n_cand;
     const float c = LOG2E / sqrtf((float)DH);
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
     };
     auto load_kmax = [&](int hd) {
         float km = 0.f;
-        for (int i = lane; i < nst; i += 64) km = fmaxf(km, kmax[((size_t)r * H + hd) * (nktp / 2) + i]);
+        for (int i = lane; i < nst; i += 64) km = fmaxf(km, kmax[((size_t)us * H + hd) * (nktp / 2) + i]);
         return km;
     };
     // The compiler does not know of the hand-issued loads: wherever it waits for a load of its own it
@@ -345,7 +346,8 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     const ReqDesc rd = b.reqs[r];
     const int L = rd.seq_len, H = m.n_heads;
     const int nkt = (L + 31) >> 5, nkt2 = (nkt + 1) & ~1, head_frags = nkt2 * FR;
-    const char *pk = kvpack + (size_t)r * pack_stride;
+    const int us = rd.slot;                         // K/V and key norms are kept per user, not per slice
+    const char *pk = kvpack + (size_t)us * pack_stride;
 
     // the whole pack -> LDS, heads back to back (in the pack a head takes nktp key tiles)
     {
@@ -358,7 +360,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     }
     for (int hd = wave; hd < H; hd += RES_WAVES) {
         float km = 0.f;
-        for (int i = lane; i < nkt2 / 2; i += 64) km = fmaxf(km, kmax[((size_t)r * H + hd) * (nktp / 2) + i]);
+        for (int i = lane; i < nkt2 / 2; i += 64) km = fmaxf(km, kmax[((size_t)us * H + hd) * (nktp / 2) + i]);
 #pragma unroll
         for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
         if (lane == 0) skm[hd] = km;
@@ -689,7 +691,7 @@ static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char
 {
     constexpr int LDS = 4 * 2 * (DH / 8) * 1024, ROWS = WAVES * 32;
     if (nktp > 0 && !kv_packed)
-        hipLaunchKernelGGL(k_pack_kv<DH>, dim3(nktp / 2, m.n_heads, b.n_req), dim3(256), 0, s, m, b, kvpack, stride, kmax, nktp);
+        hipLaunchKernelGGL(k_pack_kv<DH>, dim3(nktp / 2, m.n_heads, b.n_slots), dim3(256), 0, s, m, b, kvpack, stride, kmax, nktp);
     if (b.n_groups > 0) {
         constexpr int RES_LDS = RES_LDS_BYTES;
         static bool attr_set = false;

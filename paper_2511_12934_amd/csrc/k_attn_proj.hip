@@ -76,8 +76,8 @@ __global__ __launch_bounds__(256) void k_pack_kv16(Model m, Batch b, char *__res
                                                    float *__restrict__ kmax, int nktp)
 {
     __shared__ float red[4];
-    const int st = blockIdx.x, hd = blockIdx.y, r = blockIdx.z;
-    const ReqDesc *rd = b.reqs + r;
+    const int st = blockIdx.x, hd = blockIdx.y, r = blockIdx.z;        // r: the user slot (one pack per distinct user of the call)
+    const ReqDesc *rd = b.reqs + slot_request(b, r);
     const int L = rd->seq_len, nkt = (L + 31) >> 5;
     if (P_NT * st >= nkt) return;
     const uint16_t *K = (const uint16_t *)rd->seq_keys, *V = (const uint16_t *)rd->seq_vals;
@@ -176,7 +176,8 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
 
     const int L = rd.seq_len;
     const int nkt = (L + 31) >> 5, nst = (nkt + P_NT - 1) / P_NT, total = H * nst, nstp = nktp / P_NT;
-    const char *pk = kvpack + (size_t)r * pack_stride;
+    const int us = rd.slot;                       // K/V and key norms are kept per user, not per slice
+    const char *pk = kvpack + (size_t)us * pack_stride;
     const bool live = local0 + wave * 32 + col < rd.n_cand;
     const char *trow = nullptr;                   // GATHER: this lane's row of the table (row 0 past the request's end)
     if constexpr (GATHER) {
@@ -210,7 +211,7 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
     for (int f = wave; f < NFT * KS; f += WAVES) dma16(wq_pack + (size_t)f * 1024 + lane * 16, ring + f * 1024);
     for (int hd = wave; hd < H; hd += WAVES) {
         float km = 0.f;
-        for (int i = lane; i < nst; i += 64) km = fmaxf(km, kmax[((size_t)r * H + hd) * nstp + i]);
+        for (int i = lane; i < nst; i += 64) km = fmaxf(km, kmax[((size_t)us * H + hd) * nstp + i]);
 #pragma unroll
         for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
         if (lane == 0) skm[hd] = km;
@@ -454,7 +455,7 @@ hipError_t launch_attn_proj(const Model &m, const Batch &b, void *X, const MfmaP
                             const void *gather_table, int32_t *bad)
 {
     if (plan.nktp > 0)
-        hipLaunchKernelGGL(k_pack_kv16, dim3(plan.nktp / P_NT, m.n_heads, b.n_req), dim3(256), 0, s, m, b, plan.kvpack,
+        hipLaunchKernelGGL(k_pack_kv16, dim3(plan.nktp / P_NT, m.n_heads, b.n_slots), dim3(256), 0, s, m, b, plan.kvpack,
                            plan.pack_stride, plan.kmax, plan.nktp);
     switch (m.n_heads) {
     case 2: return small ? launch_proj_gather<1, 2>(m, b, X, plan, gather_table, bad, s) : launch_proj_gather<1, 8>(m, b, X, plan, gather_table, bad, s);

@@ -37,7 +37,7 @@ hipError_t launch_user_fold(const Model &m, const Batch &b, const float *w1u, co
                             hipStream_t s)
 {
     if (b.n_req == 0) return hipSuccess;
-    dim3 grid((m.dims[1] + FOLD_FEATS - 1) / FOLD_FEATS, b.n_req);
+    dim3 grid((m.dims[1] + FOLD_FEATS - 1) / FOLD_FEATS, b.n_slots);      // once per distinct user of the call
     if (m.dtype == 0)
         hipLaunchKernelGGL(k_user_fold<float>, grid, dim3(256), 0, s, m, b, w1u, b1, bias1);
     else
@@ -217,6 +217,7 @@ __global__ __launch_bounds__(256) void k_mlp_generic(Model m, Batch b, const T *
     const int r = b.blk_req[tile / (ROW_BLOCK / MLP_TS)];
     if (r < 0) return;
     const ReqDesc rd = b.reqs[r];
+    const int us = rd.slot;                 // the folded layer-1 bias is kept per user slot
     const int row0 = tile * MLP_TS;
     const int local0 = row0 - rd.row_base;
     int nrows = rd.n_cand - local0;
@@ -237,7 +238,7 @@ __global__ __launch_bounds__(256) void k_mlp_generic(Model m, Batch b, const T *
         const bool last = l + 1 == m.n_layers;
         for (int n = threadIdx.x; n < N; n += 256) {
             float acc[MLP_TS];
-            const float b0 = l == 0 ? bias1[(size_t)r * N + n] : (w.bias[l] ? w.bias[l][n] : 0.f);
+            const float b0 = l == 0 ? bias1[(size_t)us * N + n] : (w.bias[l] ? w.bias[l][n] : 0.f);
 #pragma unroll
             for (int c = 0; c < MLP_TS; ++c) acc[c] = b0;
             auto term = [&](int k, float wv) {

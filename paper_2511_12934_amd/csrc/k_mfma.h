@@ -57,6 +57,7 @@ struct StageUpload {
     void *dst;
     size_t bytes;
     const ReqDesc *reqs_mapped;
+    const int32_t *slot_req_mapped;     // the batch's slot_req table through the same mapping
 };
 hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad, const float *w1u,
                         const float *b1, float *bias1, const MfmaPlan &plan, bool gather, hipStream_t s,

@@ -140,7 +140,8 @@ __device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
 // asked for at the first tile's end and the second tile's first MFMAs wait for them.
 template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS, int PER_CU>
 __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items, const ReqDesc *__restrict__ reqs,
-                                                           const int32_t *__restrict__ blk_req, const char *__restrict__ X,
+                                                           const int32_t *__restrict__ blk_req,
+                                                           const int32_t *__restrict__ blk_slot, const char *__restrict__ X,
                                                            XLayout xl, MlpPack pk, const float *__restrict__ bias1, int n_pairs)
 {
     using C = Chain<K1, H1, H2, H3, WAVES, SF, SLOTS>;
@@ -201,10 +202,12 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
     // candidate ids (all at once).  Three round trips in a row, none of them behind a load it does not depend on.
     const int t1 = has_next ? tile0 + 1 : tile0;
     const int r0 = blk_req[tile0 / (ROW_BLOCK / ROWS)], r1 = blk_req[t1 / (ROW_BLOCK / ROWS)];
+    // the folded layer-1 biases are kept per user slot (the slices of one candidate list share them): same round trip
+    const int s0 = blk_slot[tile0 / (ROW_BLOCK / ROWS)], s1 = blk_slot[t1 / (ROW_BLOCK / ROWS)];
     const Out rd0 = out_of(r0), rd1 = out_of(r1);
     float g1[N1];
 #pragma unroll
-    for (int j = 0; j < N1; ++j) g1[j] = at(bias1 + (size_t)r0 * H1, H1, threadIdx.x + j * THREADS);
+    for (int j = 0; j < N1; ++j) g1[j] = at(bias1 + (size_t)s0 * H1, H1, threadIdx.x + j * THREADS);
     // Which lanes will store a result, and which of them carry an id outside the table, is settled here, as two
     // wave masks per tile: the tile's end then has no load to wait for before its stores.
     // (position 0 stands in for a lane with no candidate)
@@ -321,7 +324,7 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
                 // the second tile's layer-1 biases travel to the second buffer (waves 0 .. H1 / 256 - 1, 1 KB each).
                 // They are older than the stages sent from here on, so D stages later they have landed, like a stage.
                 if (more && wave_u < H1 * 4 / 1024)
-                    dma16_s((const char *)(bias1 + (size_t)r1 * H1) + wave_u * 1024, lane_off16_now(),
+                    dma16_s((const char *)(bias1 + (size_t)s1 * H1) + wave_u * 1024, lane_off16_now(),
                             lds_address(sb1 + H1) + wave_u * 1024);
             }
             if constexpr (F % SF == SF / 2) {
@@ -425,7 +428,7 @@ static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, con
     int n_single = n_tiles < per_cu * n_cu() ? n_tiles : per_cu * n_cu();
     if ((n_tiles - n_single) & 1) ++n_single;
     const int n_pairs = (n_tiles - n_single) / 2;
-    hipLaunchKernelGGL(kern, dim3(n_pairs + n_single), dim3(WAVES * 64), LDS, s, m.n_items, b.reqs, b.blk_req, (const char *)X,
+    hipLaunchKernelGGL(kern, dim3(n_pairs + n_single), dim3(WAVES * 64), LDS, s, m.n_items, b.reqs, b.blk_req, b.blk_slot, (const char *)X,
                        x_layout(m), pk, bias1, n_pairs);
     return hipGetLastError();
 }

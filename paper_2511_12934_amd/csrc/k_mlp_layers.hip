@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void k_mlp_layer(Model m, Batch b, LayerArgs a
     float *sbias = (float *)(lds + GL_LDS_BYTES), *swl = sbias + 256;
     const int r = b.blk_req[bx];
     {
-        const float *bias = a.bias ? a.bias + (a.per_req_bias ? (size_t)r * a.M : 0) + by * 256 : nullptr;
+        const float *bias = a.bias ? a.bias + (a.per_req_bias ? (size_t)b.blk_slot[bx] * a.M : 0) + by * 256 : nullptr;
         sbias[threadIdx.x] = bias ? bias[threadIdx.x] : 0.f;
         if constexpr (LAST) swl[threadIdx.x] = a.wlast[threadIdx.x];
     }

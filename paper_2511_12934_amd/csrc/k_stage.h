@@ -143,14 +143,14 @@ __device__ __forceinline__ void gather_block_tiled(int blk, const uint4 *__restr
     }
 }
 
-// a2 -- user fold: FOLD_FEATS consecutive layer-1 features n = FOLD_FEATS * part + thread % 64 of request r,
-// bias1[r, n] = b1[n] + sum_k W1[n, k] u[k] over the user columns (w1ut = those columns transposed,
+// a2 -- user fold: FOLD_FEATS consecutive layer-1 features n = FOLD_FEATS * part + thread % 64 of user slot s,
+// bias1[s, n] = b1[n] + sum_k W1[n, k] u[k] over the user columns (w1ut = those columns transposed,
 // [d_user, H1], so that the threads of a wave read consecutive words).  The job is a chain of dependent
 // loads, so the columns are cut into four runs, one per wave of the 256-thread block, eight loads in flight
 // each; the four partial sums are added in run order (a fixed order: the same bits in every call).
 constexpr int FOLD_FEATS = 64;
 template <typename T>
-__device__ __forceinline__ void user_fold_block(int r, int part, const Model &m, const Batch &b,
+__device__ __forceinline__ void user_fold_block(int slot, int part, const Model &m, const Batch &b,
                                                 const float *__restrict__ w1ut, const float *__restrict__ b1,
                                                 float *__restrict__ bias1)
 {
@@ -159,7 +159,7 @@ __device__ __forceinline__ void user_fold_block(int r, int part, const Model &m,
     const int n = part * FOLD_FEATS + lane;
     const int h1 = m.dims[1];
     const bool on = n < h1;
-    const T *u = (const T *)b.reqs[r].user_vec;
+    const T *u = (const T *)b.reqs[slot_request(b, slot)].user_vec;
     const int per = (m.d_user + 3) / 4, k0 = run * per, k1 = min(m.d_user, k0 + per);
     float acc = 0.f;
     if (on) {
@@ -175,27 +175,27 @@ __device__ __forceinline__ void user_fold_block(int r, int part, const Model &m,
     }
     if (run > 0) part_sum[run - 1][lane] = acc;
     __syncthreads();
-    if (run == 0 && on) bias1[(size_t)r * h1 + n] = (((b1 ? b1[n] : 0.f) + acc) + part_sum[0][lane]) + (part_sum[1][lane] + part_sum[2][lane]);
+    if (run == 0 && on) bias1[(size_t)slot * h1 + n] = (((b1 ? b1[n] : 0.f) + acc) + part_sum[0][lane]) + (part_sum[1][lane] + part_sum[2][lane]);
 }
 
-// a2 -- K and V of request r, head hd, 64-key stage st into MFMA fragment order, and max |k_t| of the stage.
-// Layout per request: chunk(head, key tile kt) = FR fragments of 1 KB at
+// a2 -- K and V of user slot `slot` (the tensors of the request that stands for it), head hd, 64-key stage st into MFMA fragment order, and max |k_t| of the stage.
+// Layout per slot: chunk(head, key tile kt) = FR fragments of 1 KB at
 // ((head * nktp + kt) * FR) KB:  JS K-fragments  [lane][s] = K[32kt + lane%32][o + 16j + 8(lane/32) + s]
 // then 2*FT V-fragments (jj, ft): [lane][s] = V[32kt + 16jj + 8(s/4) + 4(lane/32) + s%4][o + 32ft + lane%32]
 // with o = head * DH; keys >= seq_len read as zero.
 template <int DH>
-__device__ __forceinline__ void pack_kv_block(int r, int hd, int st, const Model &m, const Batch &b,
+__device__ __forceinline__ void pack_kv_block(int slot, int hd, int st, const Model &m, const Batch &b,
                                               char *__restrict__ kvpack, size_t pack_stride,
                                               float *__restrict__ kmax_part, int nktp)
 {
     constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32;
-    const ReqDesc *rd = b.reqs + r;
+    const ReqDesc *rd = b.reqs + slot_request(b, slot);
     const int L = rd->seq_len;
     const int nkt2 = (((L + 31) >> 5) + 1) & ~1;
     if (2 * st >= nkt2) return;
     const uint16_t *K = (const uint16_t *)rd->seq_keys, *V = (const uint16_t *)rd->seq_vals;
     const int da = m.d_attn, o = hd * DH;
-    uint4 *dst = (uint4 *)(kvpack + (size_t)r * pack_stride + ((size_t)(hd * nktp + 2 * st) * FR) * 1024);
+    uint4 *dst = (uint4 *)(kvpack + (size_t)slot * pack_stride + ((size_t)(hd * nktp + 2 * st) * FR) * 1024);
     // One 16-byte piece (a lane's share of a fragment) per thread and step.  Every load is issued before the first
     // is looked at: keys past the sequence's end re-read its last key and are zeroed afterwards (a load under a
     // condition of its own is waited for on the spot -- eight round trips in a row for a piece of V).
@@ -265,7 +265,7 @@ __device__ __forceinline__ void pack_kv_block(int r, int hd, int st, const Model
 #pragma unroll
         for (int off = 32; off; off >>= 1) nrm = fmaxf(nrm, __shfl_xor(nrm, off, 64));
         // round the bound up a little: it must dominate the fp32-accumulated score
-        if (threadIdx.x == 0) kmax_part[((size_t)r * m.n_heads + hd) * (nktp / 2) + st] = nrm * 1.001f;
+        if (threadIdx.x == 0) kmax_part[((size_t)slot * m.n_heads + hd) * (nktp / 2) + st] = nrm * 1.001f;
     }
 }
 

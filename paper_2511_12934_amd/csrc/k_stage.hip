@@ -93,6 +93,7 @@ hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void 
     a.up_n16 = a.n_up = 0;
     if (up) {
         a.b.reqs = up->reqs_mapped;
+        a.b.slot_req = up->slot_req_mapped;
         a.up_src = (const uint4 *)up->src_mapped;
         a.up_dst = (uint4 *)up->dst;
         a.up_n16 = (int32_t)((up->bytes + 15) / 16);
@@ -112,8 +113,8 @@ hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void 
     a.row_vec = m.d_item * 2 / 16;
     a.stages = plan.nktp / 2;
     a.quads = (m.dims[1] + FOLD_FEATS - 1) / FOLD_FEATS;
-    a.n_pack = b.n_req * m.n_heads * a.stages;
-    a.n_fold = b.n_req * a.quads;
+    a.n_pack = b.n_slots * m.n_heads * a.stages;     // once per distinct user of the call, not per slice (Sec. 3.1)
+    a.n_fold = b.n_slots * a.quads;
     const int n_gather = gather ? b.n_blk : 0;      // none when the attention kernel indexes the table itself
     return m.d_head == 64 ? launch_stage_dh<64>(a, n_gather, s) : launch_stage_dh<32>(a, n_gather, s);
 }

@@ -145,6 +145,7 @@ def test_c2_bf16_whole_and_minibatched(R, torch):
     ctx.aif_score_batch([p.req for p in parts])
     torch.cuda.synchronize()
     assert np.array_equal(whole.logits.cpu().numpy(), z), "mini-batched scores differ from whole-request scores"
+    assert ctx.aif_last_user_slots() == 1, "ten slices of one user: the user side is staged once"
 
     idx = torch.empty(cfg.top_k, dtype=torch.int32, device="cuda")
     val = torch.empty(cfg.top_k, dtype=torch.float32, device="cuda")
@@ -154,6 +155,56 @@ def test_c2_bf16_whole_and_minibatched(R, torch):
     assert np.array_equal(idx.cpu().numpy(), oi)
     assert np.array_equal(val.cpu().numpy().astype(np.float64), ov)
     check_topk_against_oracle_logits("bf16", idx.cpu().numpy(), ref.logits, cfg.top_k)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3", "C4", "C5"])
+def test_user_side_is_staged_once_per_user_across_slices(R, torch, name):
+    """Sec. 3.1: user-level work is not repeated per mini-batch.  A call that mixes the slices of three users'
+    candidate lists (interleaved) stages three users -- one folded bias, one packed K/V each, shared by the slices --
+    and every candidate gets the bits it gets when its user is scored alone and whole.  The same tensors with another
+    sequence length are another user."""
+    cfg = wl.CONFIGS[name].scaled(n_items=4000, seq_len=min(wl.CONFIGS[name].seq_len, 300))
+    _say(f"{name} shape: slices of three users in one call")
+    rng = np.random.default_rng(1234)
+    model = wl.make_model(cfg, bias_scale=0.05)
+    table = wl.make_table_host(cfg, rng, n_items=4000)
+    table_dev = R.to_device(table, cfg.dtype)
+    dm = R.DeviceModel(cfg, model)
+    sampler = wl.IdSampler(cfg, 4000)
+    users = [wl.make_user(cfg, rng) for _ in range(3)]
+    ids = [sampler.sample(rng, n) for n in (900, 300, 517)]
+    ctx = R.make_context(cfg, dm, table_dev, max_users=8, max_candidates=1000)
+    wholes = [R.upload_request(cfg, u, i) for u, i in zip(users, ids)]
+    alone = []
+    for w in wholes:
+        ctx.aif_score_batch([w.req])
+        torch.cuda.synchronize()
+        assert ctx.aif_last_user_slots() == 1
+        alone.append(w.logits.cpu().numpy().copy())
+        w.logits.fill_(float("nan"))
+    a, b, c = wholes
+    parts = [R.slice_request(cfg, a, 0, 256), b, R.slice_request(cfg, c, 0, 100), R.slice_request(cfg, a, 256, 700),
+             R.slice_request(cfg, c, 100, 517), R.slice_request(cfg, a, 700, 900)]
+    ctx.aif_score_batch([p.req for p in parts])
+    torch.cuda.synchronize()
+    assert ctx.aif_last_user_slots() == 3
+    for w, z in zip(wholes, alone):
+        assert np.array_equal(w.logits.cpu().numpy(), z)
+    assert_logits_close(cfg.dtype, alone[0], oracle_scores(cfg, model, table, users[0], ids[0]).logits, "user 0")
+    # a shorter view of the same sequence is a different user-side input: a slot of its own, and its own scores
+    if cfg.seq_len > 40:
+        import copy
+        short = R.slice_request(cfg, a, 0, 300)
+        short.req = copy.copy(short.req)
+        short.req.seq_len = 40
+        z_short = torch.full((300,), float("nan"), device="cuda")
+        short.req.logits_out = z_short
+        ctx.aif_score_batch([R.slice_request(cfg, a, 300, 900).req, short.req])
+        torch.cuda.synchronize()
+        assert ctx.aif_last_user_slots() == 2
+        assert np.array_equal(a.logits.cpu().numpy()[300:], alone[0][300:])
+        u40 = wl.User(users[0].user_vec, users[0].seq_keys[:40], users[0].seq_vals[:40], users[0].cross_vecs)
+        assert_logits_close(cfg.dtype, z_short.cpu().numpy(), oracle_scores(cfg, model, table, u40, ids[0][:300]).logits, "40 keys")
 
 
 # ---------------------------------------------------------------------------
