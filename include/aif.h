@@ -167,6 +167,22 @@ AIF_API aif_status aif_topk(aif_ctx *ctx, const float *const *logits, const int3
 AIF_API aif_status aif_score_topk(aif_ctx *ctx, const aif_request *reqs, int32_t n_req, int32_t k, int32_t *idx_out,
                                   float *val_out, void *hip_stream);
 
+/* For callers that cannot allocate device memory at the time of the call -- code running under HIP graph capture,
+ * tight serving loops, harnesses that forbid it: aif_score_topk for ONE request, with every per-call buffer
+ * (descriptor tables, folded bias, packed K/V, the feature matrix [e | attention | cross], hidden activations of the
+ * layer-by-layer MLP) inside a fixed array of AIF_STATIC_SCRATCH_BYTES that the library holds on each GPU it runs
+ * on, from load until the process ends.  The call allocates and frees nothing, uses no pinned staging, event, copy
+ * or memset command -- only kernel launches on hip_stream, so it may be captured into a HIP graph and replayed (the
+ * request's pointers and sizes are then baked into the graph).  Same kernels and same bits as aif_score_topk; k = 0
+ * scores without selecting (idx_out, val_out may then be NULL).  Errors: as aif_score_topk, and AIF_ERANGE with the
+ * byte counts in aif_last_error when the request does not fit the array (about 10^4 candidates of configurations
+ * C1-C4, fewer for wider rows).  ALL calls on one GPU share that one array, whatever context or stream they come
+ * through: a call overwrites what the last one left, and calls that overlap in time on one GPU race -- order them
+ * on one stream or with events.  aif_peek_features does not see this call's features. */
+#define AIF_STATIC_SCRATCH_BYTES (16u << 20)
+AIF_API aif_status aif_score_topk_static(aif_ctx *ctx, const aif_request *req, int32_t k, int32_t *idx_out,
+                                         float *val_out, void *hip_stream);
+
 /* Nearline maintenance of the item table (Sec. 3.4: the index table of nearline results is refreshed as a
  * whole and also row by row).
  *

@@ -21,7 +21,7 @@ AIF_CROSS_NONE, AIF_CROSS_HADAMARD, AIF_CROSS_SEGDOT, AIF_CROSS_BEA = 0, 1, 2, 3
 EXPORTS = ("aif_score_init", "aif_score_request", "aif_score_batch", "aif_topk", "aif_score_destroy",
            "aif_last_error", "aif_poll_device_errors", "aif_peek_features", "aif_profile_begin",
            "aif_profile_end", "aif_stage_kind", "aif_update_rows", "aif_swap_table", "aif_score_topk",
-           "aif_profile_begin_stages", "aif_profile_begin_sampled", "aif_last_user_slots")
+           "aif_profile_begin_stages", "aif_profile_begin_sampled", "aif_last_user_slots", "aif_score_topk_static")
 STAGES = ("gather", "user_fold", "attention", "mlp", "topk")
 LSH_EXPORTS = ("aif_lsh_init", "aif_lsh_batch", "aif_lsh_destroy", "aif_lsh_last_error",
                "aif_lsh_poll_device_errors", "aif_lsh_profile_begin", "aif_lsh_profile_end")
@@ -115,6 +115,8 @@ def load():
     lib.aif_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
     lib.aif_stage_kind.restype = C.c_int32
     lib.aif_stage_kind.argtypes = [vp, C.c_int32]
+    lib.aif_score_topk_static.restype = C.c_int
+    lib.aif_score_topk_static.argtypes = [vp, C.POINTER(aif_request), C.c_int32, vp, vp, vp]
     lib.aif_last_user_slots.restype = C.c_int32
     lib.aif_last_user_slots.argtypes = [vp]
     lib.aif_score_topk.restype = C.c_int
@@ -243,6 +245,10 @@ class Context:
     def aif_score_topk(self, reqs: Sequence[Request], k: int, idx_out, val_out, packed=None):
         arr = pack_requests(reqs) if packed is None else packed
         self._check(self._lib.aif_score_topk(self._h, arr, len(reqs), k, _ptr(idx_out), _ptr(val_out), _stream()))
+
+    def aif_score_topk_static(self, req: Request, k: int, idx_out=None, val_out=None):
+        arr = pack_requests([req])
+        self._check(self._lib.aif_score_topk_static(self._h, arr, k, _ptr(idx_out), _ptr(val_out), _stream()))
 
     def aif_topk(self, logits: Sequence, k: int, idx_out, val_out, n_cand: Optional[Sequence[int]] = None):
         n = len(logits)

@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <mutex>
 #include <new>
 #include <tuple>
 #include <string>
@@ -17,10 +18,63 @@
 
 using namespace aif;
 
+// The per-call workspace of aif_score_topk_static (the entry point for callers that cannot allocate): every GPU the
+// library runs on holds its own copy of this array, at its own address, until the process ends.  In host code the
+// name is only a handle: the device address comes from hipGetSymbolAddress, once per device (scratch_of).
+static __device__ __align__(256) unsigned char scratch[AIF_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int NSLOT = 8;
+constexpr int MAX_DEVICES = 64;
+constexpr int STATIC_MAX_GROUPS = 1024;
+std::mutex g_scratch_mutex;
+unsigned char *g_scratch_ptr[MAX_DEVICES] = {};      // device address of `scratch` on each device, set at the first init there
 
+// The device address of `scratch` on the CURRENT device `dev`; resolved once per device.
+hipError_t scratch_of(int dev, unsigned char **out)
+{
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = (unsigned char *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+// Descriptor tables of a one-request batch, written by the device itself from kernel arguments (no pinned staging,
+// no copy command, nothing to wait for on the host): the request, block -> request and block -> user slot (all 0),
+// the attention groups (an even split of the request's tiles, as attn_plan_groups cuts them) and the top-k descriptor.
+struct StaticFill {
+    ReqDesc rd;
+    TopkDesc td;
+    ReqDesc *reqs;
+    int32_t *blk_req, *blk_slot, *slot_req;
+    AttnGroup *groups;
+    TopkDesc *topk;
+    int32_t n_blk, n_groups, tiles;
+};
+__global__ __launch_bounds__(256) void k_static_fill(StaticFill f)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i == 0) {
+        f.reqs[0] = f.rd;
+        f.slot_req[0] = 0;
+        f.topk[0] = f.td;
+    }
+    if (i < f.n_blk) {
+        f.blk_req[i] = 0;
+        f.blk_slot[i] = 0;
+    }
+    if (i < f.n_groups)
+        f.groups[i] = AttnGroup{0, (int)((long)f.tiles * i / f.n_groups), (int)((long)f.tiles * (i + 1) / f.n_groups), 0};
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 thread_local std::string g_init_error = "";
 
 struct DevBuf {
@@ -62,6 +116,7 @@ struct aif_ctx {
     int n_cu = 256;                   // compute units of the device (sizes the attention groups)
     bool attn_indexed = false;        // the last scoring call's attention kernel read the item table itself
     int last_slots = 0;               // distinct users (user slots) of the last scoring call
+    unsigned char *scratch_dev = nullptr;   // this device's copy of the file-scope scratch array (aif_score_topk_static)
     bool separate_gather = false;     // testing (AIF_SEPARATE_GATHER=1): the gather always as blocks or a launch of its own
 
     // descriptor staging ring
@@ -218,6 +273,7 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
     c->max_users = cfg->max_users;
     c->table = wts->item_table;
     HIP_TRY(nullptr, hipGetDevice(&c->device));
+    HIP_TRY(nullptr, scratch_of(c->device, &c->scratch_dev));
 
     // ---- weight copies ---------------------------------------------------
     hipStream_t s = nullptr;
@@ -501,6 +557,143 @@ aif_status aif_score_topk(aif_ctx *c, const aif_request *reqs, int32_t n_req, in
     if (!c) return AIF_EINVAL;
     if (k <= 0) return fail(c, AIF_EINVAL, "k must be positive");
     return score_impl(c, reqs, n_req, k, idx_out, val_out, hip_stream);
+}
+
+// One request scored (and its k best selected) with every per-call buffer inside the file-scope scratch array: the
+// same kernels as score_impl on a one-request batch, with the descriptor tables written by k_static_fill from kernel
+// arguments.  No allocation, no pinned staging, no event, no copy or memset command.
+aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, int32_t *idx_out, float *val_out,
+                                 void *hip_stream)
+{
+    if (!c) return AIF_EINVAL;
+    if (!req) return fail(c, AIF_EINVAL, "NULL request");
+    if (k < 0) return fail(c, AIF_EINVAL, "k must not be negative");
+    if (k > 0 && (!idx_out || !val_out)) return fail(c, AIF_EINVAL, "NULL idx_out or val_out");
+    if (k > TOPK_MAX) return fail(c, AIF_ERANGE, "k %d exceeds %d", k, TOPK_MAX);
+    const Model &m = c->m;
+    const aif_request &q = *req;
+    if (q.n_cand < 0 || q.seq_len < 0) return fail(c, AIF_EINVAL, "negative n_cand or seq_len");
+    if (q.seq_len > c->max_seq_len) return fail(c, AIF_ERANGE, "seq_len %d exceeds max_seq_len %d", q.seq_len, c->max_seq_len);
+    if ((m.d_user > 0 && !q.user_vec) || (q.seq_len > 0 && (!q.seq_keys || !q.seq_vals)) || (q.n_cand > 0 && (!q.cand_ids || !q.logits_out)))
+        return fail(c, AIF_EINVAL, "NULL tensor pointer");
+    if (((uintptr_t)q.user_vec | (uintptr_t)q.cross_vecs | (uintptr_t)q.seq_keys | (uintptr_t)q.seq_vals) % 16)
+        return fail(c, AIF_EINVAL, "user tensors must be 16-byte aligned");
+    if ((m.cross_mode == AIF_CROSS_SEGDOT || m.cross_mode == AIF_CROSS_BEA) && !q.cross_vecs)
+        return fail(c, AIF_EINVAL, "SEGDOT and BEA need cross_vecs");
+    if (m.cross_mode == AIF_CROSS_HADAMARD && !q.cross_vecs && m.d_user != m.d_item)
+        return fail(c, AIF_ESHAPE, "HADAMARD without cross_vecs needs d_user == d_item");
+    aif_status st = check_device(c);
+    if (st != AIF_OK) return st;
+
+    // ---- the call's buffers, laid out in the scratch array ------------------------------------------------------
+    const int esz = m.dtype == 0 ? 4 : 2, H1 = m.dims[1];
+    const int rows = round_up(q.n_cand, ROW_BLOCK), n_blk = rows / ROW_BLOCK, tiles = (q.n_cand + 31) / 32;
+    ReqDesc rd{};
+    rd.user_vec = q.user_vec;
+    rd.cross_vecs = q.cross_vecs ? q.cross_vecs : q.user_vec;
+    rd.seq_keys = q.seq_keys;
+    rd.seq_vals = q.seq_vals;
+    rd.cand_ids = q.cand_ids;
+    rd.logits_out = q.logits_out;
+    rd.scores_out = q.scores_out;
+    rd.seq_len = q.seq_len;
+    rd.n_cand = q.n_cand;
+    AttnGroup tmp[STATIC_MAX_GROUPS];
+    if (c->mfma.attn && attn_max_groups((size_t)rows, 1) > (size_t)STATIC_MAX_GROUPS)
+        return fail(c, AIF_ERANGE, "n_cand %d: more attention groups than the static call holds (%d)", q.n_cand, STATIC_MAX_GROUPS);
+    const int n_groups = c->mfma.attn ? attn_plan_groups(m, &rd, 1, c->n_cu, tmp) : 0;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    const size_t o_req = take(sizeof(ReqDesc)), o_blk = take((size_t)(n_blk + 1) * 4), o_bsl = take((size_t)(n_blk + 1) * 4),
+                 o_srq = take(4), o_grp = take((size_t)(n_groups + 1) * sizeof(AttnGroup)), o_tk = take(sizeof(TopkDesc)),
+                 o_b1 = take((size_t)H1 * 4);
+    size_t o_kmax = 0, o_kv = 0, o_h0 = 0, o_h1 = 0;
+    if (c->mfma.attn) {
+        o_kmax = take((size_t)m.n_heads * (c->mfma.nktp / 2 + 1) * 4);
+        o_kv = take(c->mfma.pack_stride + 16);
+    }
+    const bool layered = c->mfma.mlp && c->mfma.mlp_variant == MLP_VARIANT_LAYERS;
+    if (layered) {
+        o_h0 = take(mlp_layers_buf_bytes(m, (size_t)rows, 0));
+        o_h1 = take(mlp_layers_buf_bytes(m, (size_t)rows, 1));
+    }
+    const size_t o_x = take((size_t)rows * m.ldx * esz);
+    if (off > (size_t)AIF_STATIC_SCRATCH_BYTES)
+        return fail(c, AIF_ERANGE, "request of %d candidates (sequence of up to %d) needs %zu bytes of workspace, the static call holds %zu",
+                    q.n_cand, c->max_seq_len, off, (size_t)AIF_STATIC_SCRATCH_BYTES);
+    if (q.n_cand == 0) return AIF_OK;
+    hipStream_t s = (hipStream_t)hip_stream;
+    unsigned char *base = c->scratch_dev;        // the device address, never the array's name
+
+    StaticFill f{};
+    f.rd = rd;
+    f.td = TopkDesc{q.logits_out, q.n_cand};
+    f.reqs = (ReqDesc *)(base + o_req);
+    f.blk_req = (int32_t *)(base + o_blk);
+    f.blk_slot = (int32_t *)(base + o_bsl);
+    f.slot_req = (int32_t *)(base + o_srq);
+    f.groups = (AttnGroup *)(base + o_grp);
+    f.topk = (TopkDesc *)(base + o_tk);
+    f.n_blk = n_blk;
+    f.n_groups = n_groups;
+    f.tiles = tiles;
+    const int fill_n = n_blk > n_groups ? n_blk : n_groups;
+    hipLaunchKernelGGL(k_static_fill, dim3((fill_n + 255) / 256), dim3(256), 0, s, f);
+    HIP_TRY(c, hipGetLastError());
+
+    Batch b{};
+    b.reqs = f.reqs;
+    b.blk_req = f.blk_req;
+    b.blk_slot = f.blk_slot;
+    b.slot_req = f.slot_req;
+    b.groups = f.groups;
+    b.n_req = 1;
+    b.n_blk = n_blk;
+    b.n_groups = n_groups;
+    b.n_slots = 1;
+    MfmaPlan plan = c->mfma;                     // the context's packed weights, this call's buffers
+    plan.kmax = (float *)(base + o_kmax);
+    plan.kvpack = (char *)(base + o_kv);
+    plan.hbuf[0] = layered ? (char *)(base + o_h0) : nullptr;
+    plan.hbuf[1] = layered ? (char *)(base + o_h1) : nullptr;
+    void *X = base + o_x;
+    float *bias1 = (float *)(base + o_b1);
+    int32_t *bad = (int32_t *)c->bad.p;
+    const float *b1 = c->has_bias[0] ? (const float *)c->bias[0].p : nullptr;
+
+    c->row_base.clear();                         // aif_peek_features has nothing to show for this call
+    c->last_slots = 1;
+    const bool fused = stage_fusable(m, plan);
+    const bool attn_indexes = plan.attn && !c->separate_gather && attn_gathers(m, b, plan);
+    c->attn_indexed = attn_indexes;
+    if (fused) {
+        HIP_TRY(c, launch_stage(m, b, c->table, X, bad, (const float *)c->w1u.p, b1, bias1, plan, !attn_indexes, s, nullptr));
+    } else {
+        if (!attn_indexes) HIP_TRY(c, launch_gather(m, b, c->table, X, bad, s));
+        HIP_TRY(c, launch_user_fold(m, b, (const float *)c->w1u.p, b1, bias1, s));
+    }
+    if (plan.attn)
+        HIP_TRY(c, launch_attn_mfma(m, b, X, plan, fused, s, attn_indexes ? c->table : nullptr, attn_indexes ? bad : nullptr));
+    else
+        HIP_TRY(c, launch_attn_generic(m, b, X, c->has_wq ? (const float *)c->wq.p : nullptr, c->max_seq_len, s));
+    if (plan.mlp) {
+        const float *bf[MAX_LAYERS];
+        for (int l = 0; l < m.n_layers; ++l) bf[l] = c->has_bias[l] ? (const float *)c->bias[l].p : nullptr;
+        HIP_TRY(c, launch_mlp_mfma(m, b, X, plan, bf, (const float *)c->wt[m.n_layers - 1].p, bias1, s));
+    } else {
+        MlpGenericWeights gw{};
+        for (int l = 0; l < m.n_layers; ++l) {
+            gw.wt[l] = (const float *)c->wt[l].p;
+            gw.bias[l] = c->has_bias[l] ? (const float *)c->bias[l].p : nullptr;
+        }
+        HIP_TRY(c, launch_mlp_generic(m, b, X, gw, bias1, s));
+    }
+    if (k > 0) HIP_TRY(c, launch_topk(f.topk, 1, k, idx_out, val_out, s));
+    return AIF_OK;
 }
 
 aif_status aif_score_request(aif_ctx *ctx, const aif_request *req, void *hip_stream)
