@@ -76,10 +76,46 @@ def measured_traffic(workload, stage):
                 for ln in f:
                     t = ln.split()
                     if len(t) == 4 and t[0] == "traffic_bytes_per_launch" and t[1] == workload and t[2] == stage:
+                        TRAFFIC_SOURCE[(workload, stage)] = "profiles/" + name
                         return float(t[3])
         except OSError:
             pass
     return None
+
+
+TRAFFIC_SOURCE = {}
+
+
+def traffic_note(workload, stage):
+    """Where roofline.traffic came from: the counters are read in profiling runs of their own, not in this run."""
+    src = TRAFFIC_SOURCE.get((workload, stage))
+    return f"{src}: committed rocprofv3 FETCH_SIZE/WRITE_SIZE summary of the same command, not measured in this run" if src else None
+
+
+def achievable_peak(kind):
+    """What this chip delivered in the calibration loops of paper_2511_12934_amd/profiling/peaks.py (bf16 MFMAs fed
+    from LDS with random operands; a plain device copy), from the committed summary under profiles/; None if absent.
+    Line format: ``achievable_peak <mfma_bf16|hbm> <value>``."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "achievable_peaks.txt")) as f:
+            for ln in f:
+                t = ln.split()
+                if len(t) == 3 and t[0] == "achievable_peak" and t[1] == kind:
+                    return float(t[2])
+    except OSError:
+        pass
+    return None
+
+
+def add_achievable(roof):
+    """roofline.frac stays against the published peak; beside it the fraction of what the calibration loops reach."""
+    kind = {"mfma": "mfma_bf16", "hbm": "hbm"}.get(roof.get("bound"))
+    peak = achievable_peak(kind) if kind else None
+    if peak:
+        roof["achievable_peak"] = peak
+        roof["frac_of_achievable"] = roof["achieved"] / peak
+        roof["achievable_source"] = "profiles/achievable_peaks.txt (python3 -m paper_2511_12934_amd.profiling.peaks)"
+    return roof
 
 
 def cpu_baseline(cfg, w, seconds_budget=15.0):
@@ -90,7 +126,7 @@ def cpu_baseline(cfg, w, seconds_budget=15.0):
     import oracle
     threads = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1))
 
-    def run(u, n_c):
+    def run(u, n_c, n_threads=None):
         rows = w.rows_of(u, np.arange(n_c))
         req = w.requests[u]
         t0 = time.perf_counter()
@@ -98,7 +134,7 @@ def cpu_baseline(cfg, w, seconds_budget=15.0):
                            seq_keys=req.user.seq_keys, seq_vals=req.user.seq_vals, dims=w.model.dims,
                            weights=w.model.weights, biases=w.model.biases, w_q=w.model.w_q,
                            n_heads=cfg.n_heads, cross_mode=cfg.cross_mode, cross_vecs=req.user.cross_vecs,
-                           n_threads=threads)
+                           n_threads=threads if n_threads is None else n_threads)
         oracle.topk(ref.logits, cfg.top_k)
         return time.perf_counter() - t0
 
@@ -110,44 +146,152 @@ def cpu_baseline(cfg, w, seconds_budget=15.0):
     else:
         n_users, n_c = int(min(w.n_users, max(1, seconds_budget // t_request))), w.n_cand
     t = sum(run(u, n_c) for u in range(n_users))
+    # the same loop on ONE thread, on about 5 s' worth of one request's candidates
+    n_1 = max(64, min(w.n_cand, int(5.0 / (per_cand * threads))))
+    t_1 = run(0, n_1, n_threads=1)
     return {"value": n_users * n_c / t, "unit": "candidates/s", "cores": threads, "kind": "oracle",
             "sample": f"{n_users} request(s) x {n_c} candidates of {cfg.name} (oracle score + top-k, "
-                      f"{threads} OpenMP threads, {t:.1f} s wall, {t * threads:.0f} core-seconds)"}
+                      f"{threads} OpenMP threads, {t:.1f} s wall, {t * threads:.0f} core-seconds)",
+            "single_thread": {"value": n_1 / t_1, "unit": "candidates/s", "cores": 1,
+                              "sample": f"{n_1} candidates of one {cfg.name} request, one thread, {t_1:.1f} s wall"}}
 
 
-def single_request_latency(n_iter=200):
-    """p50/p99 of one 10^4-candidate request (configuration C2), enqueue to completion of top-k,
-    scored whole and as ten 1,000-item mini-batches; 32 distinct requests rotated."""
+def _percentiles(ts):
     import numpy as np
+    ts = np.sort(np.asarray(ts))
+    return {"p50_ms": float(ts[len(ts) // 2]), "p99_ms": float(ts[min(len(ts) - 1, int(len(ts) * 0.99))]), "n": int(len(ts))}
+
+
+def single_request_latency(n_iter=500):
+    """p50/p99 of one 10^4-candidate request (configuration C2), host clock from enqueue to completion of top-k, over
+    ``n_iter`` timed iterations after 50 untimed ones, 32 distinct requests rotated:
+      whole               one aif_score_topk call;
+      10x1000             ten 1,000-item mini-batches in one aif_score_batch (the user side staged once) + aif_topk;
+      10x1000_ten_streams the ten mini-batches as ten calls on ten streams through ten contexts (Sec. 1 scores the
+                          mini-batches separately and in parallel), joined by events before the one aif_topk;
+      graph_replay        the whole request as a captured HIP graph of aif_score_topk_static, replayed."""
     import torch
 
     from paper_2511_12934_amd import runner as R
     from paper_2511_12934_amd import workloads as wl
     cfg = wl.CONFIGS["C2"]
+    warm = 50
     out = {}
-    for label, mb in (("whole", None), ("10x1000", 1000)):
-        w = R.Workload(cfg, n_users=32, minibatch=mb)
-        per_user = len(w.launch) // w.n_users
-        idx = torch.empty((1, cfg.top_k), dtype=torch.int32, device="cuda")
-        val = torch.empty((1, cfg.top_k), dtype=torch.float32, device="cuda")
+    idx = torch.empty((1, cfg.top_k), dtype=torch.int32, device="cuda")
+    val = torch.empty((1, cfg.top_k), dtype=torch.float32, device="cuda")
+
+    def timed(body):
         ts = []
-        for it in range(n_iter + 20):
-            u = it % w.n_users
-            reqs = [d.req for d in w.launch[u * per_user:(u + 1) * per_user]]
+        for it in range(n_iter + warm):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            if mb is None:
-                w.ctx.aif_score_topk(reqs, cfg.top_k, idx, val)
-            else:
-                w.ctx.aif_score_batch(reqs)
-                w.ctx.aif_topk([w.dev[u].logits], cfg.top_k, idx, val)
+            body(it)
             torch.cuda.synchronize()
-            if it >= 20:
+            if it >= warm:
                 ts.append((time.perf_counter() - t0) * 1e3)
-        ts = np.sort(np.array(ts))
-        out[label] = {"p50_ms": float(ts[len(ts) // 2]), "p99_ms": float(ts[int(len(ts) * 0.99)])}
-        del w
-        torch.cuda.empty_cache()
+        return _percentiles(ts)
+
+    w = R.Workload(cfg, n_users=32)
+    out["whole"] = timed(lambda it: w.ctx.aif_score_topk([w.launch[it % 32].req], cfg.top_k, idx, val))
+    # the same call with nothing allocated and nothing staged through the host, captured once per request and replayed
+    side = torch.cuda.Stream()
+    graphs = []
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        w.ctx.aif_score_topk_static(w.launch[0].req, cfg.top_k, idx, val)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for u in range(32):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            w.ctx.aif_score_topk_static(w.launch[u].req, cfg.top_k, idx, val)
+        graphs.append(g)
+    out["graph_replay"] = timed(lambda it: graphs[it % 32].replay())
+    out["static_call"] = timed(lambda it: w.ctx.aif_score_topk_static(w.launch[it % 32].req, cfg.top_k, idx, val))
+    del graphs
+
+    wm = R.Workload(cfg, n_users=32, minibatch=1000)
+    per_user = len(wm.launch) // wm.n_users
+
+    def sliced(it):
+        u = it % 32
+        wm.ctx.aif_score_batch([d.req for d in wm.launch[u * per_user:(u + 1) * per_user]])
+        wm.ctx.aif_topk([wm.dev[u].logits], cfg.top_k, idx, val)
+    out["10x1000"] = timed(sliced)
+
+    # ten contexts (a context serves one stream at a time), ten streams; the table and the model tensors are shared
+    ctxs = [R.make_context(cfg, wm.dmodel, wm.table, max_users=1, max_candidates=1000) for _ in range(per_user)]
+    streams = [torch.cuda.Stream() for _ in range(per_user)]
+    done = [torch.cuda.Event() for _ in range(per_user)]
+
+    def ten_streams(it):
+        u = it % 32
+        main = torch.cuda.current_stream()
+        for j in range(per_user):
+            with torch.cuda.stream(streams[j]):
+                ctxs[j].aif_score_batch([wm.launch[u * per_user + j].req])
+                done[j].record()
+        for j in range(per_user):
+            main.wait_event(done[j])
+        wm.ctx.aif_topk([wm.dev[u].logits], cfg.top_k, idx, val)
+    out["10x1000_ten_streams"] = timed(ten_streams)
+    del w, wm, ctxs
+    torch.cuda.empty_cache()
+    return out
+
+
+def step_latency(w, n=100):
+    """p50/p99 of one batched step, host clock from enqueue to completion, each step synchronised on its own
+    (the throughput figure comes from steps enqueued back to back: its inverse is not a latency)."""
+    import torch
+    ts = []
+    for it in range(n + 10):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        w.step()
+        torch.cuda.synchronize()
+        if it >= 10:
+            ts.append((time.perf_counter() - t0) * 1e3)
+    return _percentiles(ts)
+
+
+def wide_model_block(steps=100, warmup=20):
+    """The heavier batched 10^4-candidate configuration (C5, the wide model) in the same run: candidates/s and the
+    roofline fraction of its dominant kernel, measured as the headline workload is (fewer steps)."""
+    import torch
+
+    from paper_2511_12934_amd import runner as R
+    from paper_2511_12934_amd import workloads as wl
+    cfg = wl.CONFIGS["C5"]
+    w = R.Workload(cfg, n_sets=2)
+    for _ in range(warmup):
+        w.step()
+    torch.cuda.synchronize()
+    w.ctx.aif_profile_begin_sampled(steps, ["attention", "mlp"], 4)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        w.step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = w.ctx.aif_profile_end()
+    work = algorithmic_work(cfg)
+    cands = w.total_candidates
+    kern = {}
+    for st in ("attention", "mlp"):
+        avg = prof[st][0] / max(prof[st][1], 1)
+        kern[st] = {"avg_ms": avg, "tflops": work[st]["flops"] * cands / (avg * 1e-3) / 1e12,
+                    "kind": ("generic", "mfma")[w.ctx.aif_stage_kind(st)]}
+    dom = max(kern, key=lambda k: kern[k]["avg_ms"])
+    roof = {"kernel": dom, "bound": "mfma", "achieved": kern[dom]["tflops"], "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": kern[dom]["tflops"] / PEAK_MFMA_BF16_TFLOPS, "traffic": measured_traffic("C5", dom),
+            "traffic_source": traffic_note("C5", dom), "avg_ms": kern[dom]["avg_ms"]}
+    out = {"workload": f"C5: {w.n_users} users x {w.n_cand} candidates, table {cfg.n_items}x{cfg.d_item} bf16, L={cfg.seq_len}, "
+                       f"H={cfg.n_heads}, MLP {list(cfg.mlp_dims)}, top-{cfg.top_k}",
+           "value": cands * steps / elapsed, "unit": "candidates/s", "steps": steps, "warmup": warmup,
+           "ms_per_step": elapsed / steps * 1e3, "roofline": add_achievable(roof), "kernels": kern,
+           "mlp_frac_of_mfma_peak": kern["mlp"]["tflops"] / PEAK_MFMA_BF16_TFLOPS}
+    del w
+    torch.cuda.empty_cache()
     return out
 
 
@@ -223,6 +367,7 @@ def main_lsh(args):
                 "peak": PEAK_FP32_VALU_TFLOPS / 2, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = measured_traffic(cfg.name, dom)
+    roof["traffic_source"] = traffic_note(cfg.name, dom)
     roof["avg_ms"] = kernels[dom]["avg_ms"]
     line = {
         "metric": "candidates served/sec/GPU by the LSH behaviour modelling (LSH-DIN + SimTier)",
@@ -297,6 +442,7 @@ def main_user(args):
             "peak": PEAK_MFMA_BF16_TFLOPS if on_mfma else PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = measured_traffic(cfg.name, dom)
+    roof["traffic_source"] = traffic_note(cfg.name, dom)
     roof["avg_ms"] = kernels[dom]["avg_ms"]
     line = {
         "metric": "users served/sec/GPU by the asynchronous user-side network (Eq. 1-3)",
@@ -526,7 +672,9 @@ def main():
         if avg_ms > 0 and wk["bytes"] > 0:
             ent["gbs"] = wk["bytes"] * cands / (avg_ms * 1e-3) / 1e9
         kernels[stage] = ent
-    kernels[dom]["timed_in"] = "timed region"
+    for st in kernels:
+        kernels[st]["timed_in"] = ("timed region, one launch in %d" % every if st == dom else
+                                   "profiled pre-pass of %d steps with events around every stage (reads a few microseconds high)" % n_pre)
     if dom == "gather":
         roof = {"kernel": "k_gather", "bound": "hbm", "achieved": kernels[dom]["gbs"], "peak": PEAK_HBM_GBS,
                 "unit": "GB/s"}
@@ -536,7 +684,9 @@ def main():
                 "peak": PEAK_MFMA_BF16_TFLOPS if mf else PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = measured_traffic(cfg.name, dom)
+    roof["traffic_source"] = traffic_note(cfg.name, dom)
     roof["avg_ms"] = kernels[dom]["avg_ms"]
+    add_achievable(roof)
 
     line = {
         "metric": "candidates scored/sec/GPU at 10^4-cand requests",
@@ -548,14 +698,18 @@ def main():
                                f"MLP {list(cfg.mlp_dims)}, top-{cfg.top_k}",
                    "users": w.n_users, "candidates_per_request": w.n_cand, "top_k": cfg.top_k,
                    "candidate_lists_rotated": args.id_sets},
-        "request_latency_ms": ms_per_step,
         "roofline": roof,
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, w)
     if not args.no_latency:
+        line["step_latency_ms"] = step_latency(w)
+        del w
+        torch.cuda.empty_cache()
         line["single_request_latency_C2"] = single_request_latency()
+        if args.workload == "C3":
+            line["wide_model_C5"] = wide_model_block()
     print(json.dumps(line))
 
 

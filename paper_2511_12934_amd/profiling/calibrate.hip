@@ -1,0 +1,176 @@
+// What one MI355X actually delivers on the two resources the scoring kernels are bound by, measured with loops
+// shaped like theirs -- measurement tooling, not part of libaif:
+//   aifcal_mfma: bf16 32x32x16 MFMAs back to back on every SIMD, four independent accumulators per wave, the A
+//                operand either held in registers or read from LDS for every MFMA (the MLP chain's and the attention
+//                kernels' pattern), operands constant or random (switching activity sets the board's power, and the
+//                power limit sets the clock);
+//   aifcal_copy: a plain 16-bytes-per-lane device copy, and a read-only pass over the same buffer.
+// Each reports a rate and the shader clock during the run (cycle counter against the 100 MHz wall counter).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int FRAGS = 16;        // 1 KB A fragments per block in LDS
+
+template <bool FROM_LDS>
+__global__ __launch_bounds__(256) void k_mfma_loop(const uint4 *__restrict__ a_src, const uint4 *__restrict__ b_src, int iters,
+                                                   float *__restrict__ out, unsigned long long *__restrict__ ticks)
+{
+    __shared__ uint4 sa[FRAGS * 64];
+    const int lane = threadIdx.x & 63;
+    for (int i = threadIdx.x; i < FRAGS * 64; i += 256) sa[i] = a_src[i];
+    bf16x8 b[2], a[4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) b[i] = __builtin_bit_cast(bf16x8, b_src[(threadIdx.x + 256 * i) % (FRAGS * 64)]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(bf16x8, a_src[(threadIdx.x * 3 + 64 * i) % (FRAGS * 64)]);
+    f32x16 acc[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+    __syncthreads();
+    const unsigned long long c0 = clock64(), w0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int f = 0; f < FRAGS; ++f) {
+            bf16x8 av;
+            if constexpr (FROM_LDS) av = __builtin_bit_cast(bf16x8, sa[f * 64 + lane]);
+            else av = a[f & 3];
+            acc[f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, b[f & 1], acc[f & 3], 0, 0, 0);
+        }
+    }
+    const unsigned long long c1 = clock64(), w1 = wall_clock64();
+    float s = 0.f;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += acc[n][i];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ticks[0] = c1 - c0;
+        ticks[1] = w1 - w0;
+    }
+}
+
+// four independent 16-byte loads in flight per thread before the first store; streaming (non-temporal) stores
+__global__ __launch_bounds__(256) void k_copy(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        uint4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = src[i + j * stride];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v[j]), (u32x4 *)(dst + i + j * stride));
+        }
+    }
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void k_read(const uint4 *__restrict__ src, size_t n16, uint32_t *__restrict__ out)
+{
+    uint32_t acc = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+        const uint4 v = src[i];
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x12345u) out[0] = acc;      // practically never: keeps the loads alive
+}
+
+#define CAL_TRY(e)                        \
+    do {                                  \
+        if ((e) != hipSuccess) return 1;  \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+// a_bits, b_bits: DEVICE, 16 KB each (FRAGS x 64 lanes x 8 bf16), the operands' bit patterns (zeros, constants or
+// random values: the caller's choice).  blocks_per_cu blocks of four waves per compute unit.  Out (HOST): TFLOP/s
+// and the shader clock in MHz during the loop.  Returns 0 on success.
+__attribute__((visibility("default"))) int aifcal_mfma(const void *a_bits, const void *b_bits, int from_lds, int blocks_per_cu,
+                                                       int iters, double *tflops, double *mhz)
+{
+    int dev = 0;
+    hipDeviceProp_t prop;
+    CAL_TRY(hipGetDevice(&dev));
+    CAL_TRY(hipGetDeviceProperties(&prop, dev));
+    const int blocks = prop.multiProcessorCount * blocks_per_cu;
+    float *out = nullptr;
+    unsigned long long *ticks = nullptr, h[2] = {0, 0};
+    CAL_TRY(hipMalloc((void **)&out, (size_t)blocks * 256 * 4));
+    CAL_TRY(hipMalloc((void **)&ticks, 16));
+    hipEvent_t e0, e1;
+    CAL_TRY(hipEventCreate(&e0));
+    CAL_TRY(hipEventCreate(&e1));
+    auto go = [&](int n) {
+        if (from_lds)
+            hipLaunchKernelGGL(k_mfma_loop<true>, dim3(blocks), dim3(256), 0, 0, (const uint4 *)a_bits, (const uint4 *)b_bits, n, out, ticks);
+        else
+            hipLaunchKernelGGL(k_mfma_loop<false>, dim3(blocks), dim3(256), 0, 0, (const uint4 *)a_bits, (const uint4 *)b_bits, n, out, ticks);
+    };
+    go(iters / 10 + 1);                       // warm-up
+    CAL_TRY(hipDeviceSynchronize());
+    CAL_TRY(hipEventRecord(e0, 0));
+    go(iters);
+    CAL_TRY(hipEventRecord(e1, 0));
+    CAL_TRY(hipEventSynchronize(e1));
+    float ms = 0.f;
+    CAL_TRY(hipEventElapsedTime(&ms, e0, e1));
+    CAL_TRY(hipMemcpy(h, ticks, 16, hipMemcpyDeviceToHost));
+    *tflops = (double)blocks * 4 * iters * FRAGS * 32768.0 / (ms * 1e-3) / 1e12;
+    *mhz = h[1] ? 100.0 * (double)h[0] / (double)h[1] : 0.0;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    (void)hipFree(out);
+    (void)hipFree(ticks);
+    return 0;
+}
+
+// src, dst: DEVICE buffers of `bytes` (a multiple of 16).  Out (HOST): GB/s of the copy counting bytes read plus
+// bytes written, and GB/s of a read-only pass.  Returns 0 on success.
+__attribute__((visibility("default"))) int aifcal_copy(const void *src, void *dst, size_t bytes, int reps, double *gbs_copy,
+                                                       double *gbs_read)
+{
+    int dev = 0;
+    hipDeviceProp_t prop;
+    CAL_TRY(hipGetDevice(&dev));
+    CAL_TRY(hipGetDeviceProperties(&prop, dev));
+    const int blocks = prop.multiProcessorCount * 8;
+    const size_t n16 = bytes / 16;
+    uint32_t *flag = nullptr;
+    CAL_TRY(hipMalloc((void **)&flag, 4));
+    hipEvent_t e0, e1;
+    CAL_TRY(hipEventCreate(&e0));
+    CAL_TRY(hipEventCreate(&e1));
+    float ms = 0.f;
+    hipLaunchKernelGGL(k_copy, dim3(blocks), dim3(256), 0, 0, (const uint4 *)src, (uint4 *)dst, n16);
+    CAL_TRY(hipDeviceSynchronize());
+    CAL_TRY(hipEventRecord(e0, 0));
+    for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(k_copy, dim3(blocks), dim3(256), 0, 0, (const uint4 *)src, (uint4 *)dst, n16);
+    CAL_TRY(hipEventRecord(e1, 0));
+    CAL_TRY(hipEventSynchronize(e1));
+    CAL_TRY(hipEventElapsedTime(&ms, e0, e1));
+    *gbs_copy = 2.0 * (double)bytes * reps / (ms * 1e-3) / 1e9;
+    CAL_TRY(hipEventRecord(e0, 0));
+    for (int i = 0; i < reps; ++i) hipLaunchKernelGGL(k_read, dim3(blocks), dim3(256), 0, 0, (const uint4 *)src, n16, flag);
+    CAL_TRY(hipEventRecord(e1, 0));
+    CAL_TRY(hipEventSynchronize(e1));
+    CAL_TRY(hipEventElapsedTime(&ms, e0, e1));
+    *gbs_read = (double)bytes * reps / (ms * 1e-3) / 1e9;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    (void)hipFree(flag);
+    return 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,66 @@
+"""Achievable peaks of this MI355X, beside the published ones the roofline fractions are quoted against: what a
+bf16 MFMA loop shaped like the scoring kernels' inner loops delivers (operands in registers or the A operand read
+from LDS per MFMA; zero, constant or random operand values), and what a plain device copy and a read-only pass
+deliver from HBM.  Prints a table and, last, the machine-readable lines ``bench.py`` looks for:
+
+    achievable_peak mfma_bf16 <TFLOP/s>      (random operands, A from LDS: the MLP chain's situation)
+    achievable_peak hbm <GB/s>               (copy, bytes read + bytes written)
+
+    python3 -m paper_2511_12934_amd.profiling.peaks
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB = os.path.join(HERE, "libaif_calib.so")
+
+
+def main() -> None:
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("peaks needs a GPU")
+    if not os.path.exists(LIB):
+        sys.exit(f"{LIB} is missing: run python -m paper_2511_12934_amd.build")
+    lib = C.CDLL(LIB)
+    vp = C.c_void_p
+    lib.aifcal_mfma.restype = C.c_int
+    lib.aifcal_mfma.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.aifcal_copy.restype = C.c_int
+    lib.aifcal_copy.argtypes = [vp, vp, C.c_size_t, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    g = torch.Generator(device="cuda").manual_seed(1234)
+    n = 16 * 64 * 8
+    operands = {
+        "zero": (torch.zeros(n, dtype=torch.bfloat16, device="cuda"), torch.zeros(n, dtype=torch.bfloat16, device="cuda")),
+        "constant": (torch.full((n,), 0.5, dtype=torch.bfloat16, device="cuda"), torch.full((n,), 1.25, dtype=torch.bfloat16, device="cuda")),
+        "random N(0,1)": (torch.randn(n, device="cuda", generator=g).to(torch.bfloat16), torch.randn(n, device="cuda", generator=g).to(torch.bfloat16)),
+        "random N(0,0.1)": ((torch.randn(n, device="cuda", generator=g) * 0.1).to(torch.bfloat16), (torch.randn(n, device="cuda", generator=g) * 0.1).to(torch.bfloat16)),
+    }
+    print(f"{'MFMA loop (bf16 32x32x16, 4 accumulators per wave)':58s} {'TFLOP/s':>9s} {'of 2500':>8s} {'clock MHz':>10s}")
+    best = {}
+    for from_lds in (0, 1):
+        for waves in (1, 2):
+            for name, (a, b) in operands.items():
+                tf, mhz = C.c_double(0), C.c_double(0)
+                # about 40 ms of MFMAs per measurement: long enough for the board's power management to settle
+                rc = lib.aifcal_mfma(a.data_ptr(), b.data_ptr(), from_lds, waves, 160000 // waves, C.byref(tf), C.byref(mhz))
+                assert rc == 0, "aifcal_mfma failed"
+                label = f"A from {'LDS' if from_lds else 'registers'}, {waves} wave(s)/SIMD, operands {name}"
+                print(f"{label:58s} {tf.value:9.1f} {tf.value / 2500:8.3f} {mhz.value:10.0f}", flush=True)
+                best[(from_lds, name)] = max(best.get((from_lds, name), 0.0), tf.value)
+    nbytes = 1 << 30
+    src = torch.randint(0, 2 ** 31 - 1, (nbytes // 4,), dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    cp, rd = C.c_double(0), C.c_double(0)
+    assert lib.aifcal_copy(src.data_ptr(), dst.data_ptr(), nbytes, 20, C.byref(cp), C.byref(rd)) == 0
+    assert bool((dst[-7:] == src[-7:]).all())
+    print(f"\ncopy of 1 GiB, 16 B per lane: {cp.value:.0f} GB/s read + written ({cp.value / 8000:.3f} of 8000); "
+          f"read-only pass: {rd.value:.0f} GB/s ({rd.value / 8000:.3f})")
+    print(f"\nachievable_peak mfma_bf16 {best[(1, 'random N(0,0.1)')]:.1f}")
+    print(f"achievable_peak hbm {cp.value:.0f}")
+
+
+if __name__ == "__main__":
+    main()
