@@ -129,6 +129,7 @@ struct aif_ctx {
     int next_slot = 0;
 
     std::vector<int32_t> row_base;    // host copy for aif_peek_features
+    std::vector<const void *> peek_cross;   // per request of the last batch: its Hadamard operand (device), for aif_peek_features
     std::string err;
 
     // optional per-kernel event timing
@@ -305,6 +306,8 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
         m.x_tiled = (c->mfma.attn && c->mfma.mlp && !(rm && rm[0] == '1')) ? 1 : 0;
         const char *sg = getenv("AIF_SEPARATE_GATHER");  // testing: both gather routes must give the same bits
         c->separate_gather = sg && sg[0] == '1';
+        const char *cm = getenv("AIF_CROSS_MATERIALIZED");   // testing: the Hadamard cross block written to the workspace even where the MLP chain could form it
+        m.cross_in_mlp = (c->mfma.mlp && mlp_chain_forms_cross(c->mfma.mlp_variant, m) && !(cm && cm[0] == '1')) ? 1 : 0;
     }
 
     const bool attn_ok = c->mfma.attn || attn_generic_lds_bytes(m, c->max_seq_len) <= 160 * 1024;
@@ -406,6 +409,7 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
     char *d = (char *)c->d_stage.p + (size_t)slot * c->slot_bytes;
     ReqDesc *hd = (ReqDesc *)h;
     c->row_base.assign(n_req, 0);
+    c->peek_cross.assign(n_req, nullptr);
     // Rows per request first (the tables that follow the descriptors are sized by the block count), and the user
     // slots: requests that bring the same user tensors -- the mini-batch slices of one candidate list -- share one
     // slot, so that the user-side staging runs once per user and not once per slice (Sec. 3.1).
@@ -448,6 +452,7 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         e.row_base = rows;
         e.index = r;
         c->row_base[r] = rows;
+        c->peek_cross[r] = e.cross_vecs;
         const int nb = round_up(q.n_cand, ROW_BLOCK) / ROW_BLOCK;
         for (int j = 0; j < nb; ++j) {
             hb[rows / ROW_BLOCK + j] = r;
@@ -795,6 +800,25 @@ aif_status aif_peek_features(aif_ctx *c, int32_t request, int32_t first_row, int
         for (uint32_t p = 0; p < pieces; ++p)
             memcpy((char *)out + (size_t)i * row_bytes + 16 * p,
                    tiles.data() + x_offset(xl, (uint32_t)(row0 + i - t0 * X_TILE), p), 16);
+    if (m.cross_in_mlp) {
+        // The workspace's cross block is not written on this route (the MLP chain forms c = u (.) e in registers): show
+        // what the chain forms -- the fp32 product of the two bf16 values, rounded to nearest even -- from the item block
+        // and the request's operand.
+        std::vector<uint16_t> u(m.d_item);
+        HIP_TRY(c, hipMemcpy(u.data(), c->peek_cross[request], (size_t)m.d_item * 2, hipMemcpyDeviceToHost));
+        auto widen = [](uint16_t b) { uint32_t w = (uint32_t)b << 16; float f; memcpy(&f, &w, 4); return f; };
+        auto narrow = [](float f) {
+            uint32_t w;
+            memcpy(&w, &f, 4);
+            if ((w & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((w >> 16) | 0x40u);
+            w += 0x7FFFu + ((w >> 16) & 1u);
+            return (uint16_t)(w >> 16);
+        };
+        for (int32_t i = 0; i < n_rows; ++i) {
+            uint16_t *row = (uint16_t *)((char *)out + (size_t)i * row_bytes);
+            for (int k = 0; k < m.d_item; ++k) row[m.d_item + m.d_attn + k] = narrow(widen(row[k]) * widen(u[k]));
+        }
+    }
     return AIF_OK;
 }
 

@@ -58,6 +58,9 @@ struct Model {
     int32_t n_layers;
     int32_t dims[MAX_LAYERS + 1];   // dims[0] = D_in
     int32_t k1;                 // D_in - d_user: layer-1 contraction left per candidate after the user fold
+    int32_t cross_in_mlp;       // Hadamard cross only: the MLP chain forms c = u (.) e itself from the item block it reads anyway
+                                // (same products, same rounding); the attention kernel then leaves the cross block of the
+                                // workspace unwritten -- a third of its stores, and of the MLP's loads
 };
 
 // Where the workspace keeps 16-byte piece `piece` of row `row` (byte offset).  Rows are grouped in

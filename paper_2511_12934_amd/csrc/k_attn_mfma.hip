@@ -24,6 +24,8 @@
 // is large enough to risk underflow (exponent range wider than 2^-80) the wave
 // first takes the true maximum in an extra pass over K.  Both are the exact
 // softmax up to rounding.
+#include <type_traits>
+
 #include "k_mfma.h"
 #include "k_stage.h"
 #include "mfma_util.h"
@@ -265,7 +267,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
         }
     }
 
-    if (m.cross_mode == 1 && live) {
+    if (m.cross_mode == 1 && !m.cross_in_mlp && live) {      // unless the MLP chain forms the Hadamard products itself
         const bf16x8 *uc = (const bf16x8 *)rd.cross_vecs;
         const int pc0 = (m.d_item + m.d_attn) / 8;
         for (int pc = h; pc < m.d_item / 8; pc += 2) {
@@ -322,7 +324,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
 // the workspace for the MLP on the way.  The separate gather launch, its write of the item block and this
 // kernel's read of it fall away.  An id outside the table reads row 0 and is counted, as in the gather kernel.
 // ---------------------------------------------------------------------------
-constexpr int RES_WAVES = 16;
+constexpr int RES_WAVES = 12;
 constexpr int RES_LDS_FRAGS = 152;            // 1 KB fragments of K/V that may stay resident
 constexpr int RES_MAX_HEADS = 64;
 constexpr int RES_MAX_ITEM_PIECES = 256;      // d_item / 8 the Hadamard operand may have to stay in LDS
@@ -365,7 +367,8 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
         if (lane == 0) skm[hd] = km;
     }
-    if (m.cross_mode == 1)
+    const bool hadamard = m.cross_mode == 1 && !m.cross_in_mlp;      // else the MLP chain forms the Hadamard products itself
+    if (hadamard)
         for (int i = threadIdx.x; i < m.d_item / 8; i += RES_WAVES * 64) su[i] = ((const bf16x8 *)rd.cross_vecs)[i];
     const bool bea = m.cross_mode == 3;
     const BeaGeom bg = bea_geom(m);
@@ -385,7 +388,6 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     const float c = LOG2E / sqrtf((float)DH);
     const char *kv0 = lds + lane * 16;
     const int pc_cross = (m.d_item + m.d_attn) / 8;             // first piece of the cross block
-    const bool hadamard = m.cross_mode == 1;
 
     // A wave's work is a sequence of (tile, head) items.  Tiles are handed out on demand -- the SIMD
     // favours its older waves, so with a fixed share per wave the young ones would finish the kernel
@@ -550,57 +552,114 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
 #pragma unroll
             for (int i = 0; i < 16; ++i) O[ft][i] = 0.f;
         float l = 0.f;
-        // exponentials, row sums and the second product of key tile kt
-        auto finish_tile = [&](int kt, const f32x16 &S, bool ragged) {
-            const char *base = kvh + kt * FR * 1024;
-            float p[16];
-#pragma unroll
-            for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(fmaf(S[v], c, -mc));
-            if (ragged) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
-                    if (t >= L) p[v] = 0.f;
-                }
-            }
-            bf16x8 P0, P1;
-#pragma unroll
-            for (int v = 0; v < 8; ++v) {
-                l += p[v] + p[8 + v];
-                P0[v] = (__bf16)p[v];
-                P1[v] = (__bf16)p[8 + v];
-            }
-#pragma unroll
-            for (int ft = 0; ft < FT; ++ft) {
-                O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + (JS + ft) * 1024), P0, O[ft], 0, 0, 0);
-                O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + (JS + FT + ft) * 1024), P1, O[ft], 0, 0, 0);
-            }
-        };
-        // S of key tile t + 1 goes to the matrix cores BEFORE the exponentials of key tile t (the
-        // scheduling barriers hold the order), two tiles per trip so the accumulators swap without copies
-        f32x16 S;
+        // ---- the key-tile loop, software-pipelined inside the wave ------------------------------------------
+        // A wave issues in order, so what must overlap has to alternate in its instruction stream.  Per key tile t:
+        //   - the S product of tile t + 1 is a chain of JS MFMAs, each waiting for the one before: one link per
+        //     slot, and in the same slot the exponents and exponentials of 16 / JS scores of tile t (about as many
+        //     issue cycles as the MFMA takes), so neither the matrix cores nor the vector ALU wait for the other;
+        //   - the K fragment a link has just consumed is refilled from LDS with tile t + 2's (a whole tile of lead),
+        //     V fragments of tile t are asked for at the top of the tile;
+        //   - the second product's MFMAs (feature tiles alternating, so consecutive ones are independent) carry the
+        //     row sums between them.
+        // Scheduling barriers pin the slots; within a slot the compiler is free.  Per candidate the arithmetic and
+        // its order are unchanged.
         if (nkt > 0) {
-            S = s_tile(0);
+            const char *kbase = kvh;                                   // K fragment j of tile t: kbase + (t FR + j) KB
+            bf16x8 kf[JS], vf[2 * FT];
+            f32x16 S, S1;
+#pragma unroll
+            for (int j = 0; j < JS; ++j) kf[j] = *(const bf16x8 *)(kbase + j * 1024);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) S[i] = 0.f;
+#pragma unroll
+            for (int j = 0; j < JS; ++j) S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], q[j], S, 0, 0, 0);
+            {
+                const int k1 = nkt > 1 ? 1 : 0;
+#pragma unroll
+                for (int j = 0; j < JS; ++j) kf[j] = *(const bf16x8 *)(kbase + (k1 * FR + j) * 1024);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // tile kt: exponentials of Sin, second product; with NEXT also the S product of tile kt + 1 into Sout
+            auto step = [&](int kt, const f32x16 &Sin, f32x16 &Sout, auto next_c, bool ragged) {
+                constexpr bool NEXT = decltype(next_c)::value;
+                const char *vbase = kbase + (kt * FR + JS) * 1024;
+#pragma unroll
+                for (int i = 0; i < 2 * FT; ++i) vf[i] = *(const bf16x8 *)(vbase + i * 1024);
+                const int kn = kt + 2 < nkt ? kt + 2 : nkt - 1;         // refill: the tile after next (clamped: read, not used)
+                __builtin_amdgcn_sched_barrier(0);
+                float p[16];
+#pragma unroll
+                for (int j = 0; j < JS; ++j) {
+                    if constexpr (NEXT) {
+                        if (j == 0) {
+                            f32x16 Z;
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) Z[i] = 0.f;
+                            Sout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], q[0], Z, 0, 0, 0);
+                        } else
+                            Sout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], q[j], Sout, 0, 0, 0);
+                        kf[j] = *(const bf16x8 *)(kbase + (kn * FR + j) * 1024);
+                    }
+#pragma unroll
+                    for (int v = 16 / JS * j; v < 16 / JS * (j + 1); ++v) {
+                        p[v] = __builtin_amdgcn_exp2f(fmaf(Sin[v], c, -mc));
+                        asm volatile("" : "+v"(p[v]));      // computed HERE: a value with no side effect would sink to its first use
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (ragged) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
+                        if (t >= L) p[v] = 0.f;
+                    }
+                }
+                bf16x8 P0, P1;
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    P0[v] = (__bf16)p[v];
+                    P1[v] = (__bf16)p[8 + v];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // per feature tile the P0 step, then the P1 step (the order the streaming kernel accumulates in);
+                // issued feature tile by feature tile within a step; the row sums ride between the MFMAs
+#pragma unroll
+                for (int i = 0; i < 2 * FT; ++i) {
+                    const int ft = i % FT;
+                    O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], i < FT ? P0 : P1, O[ft], 0, 0, 0);
+#pragma unroll
+                    for (int v = 8 / (2 * FT) * i; v < 8 / (2 * FT) * (i + 1); ++v) l += p[v] + p[8 + v];
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            using Yes = std::true_type;
+            using No = std::false_type;
             int kt = 0;
             for (; kt + 2 < nkt; kt += 2) {
-                const f32x16 S1 = s_tile(kt + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                finish_tile(kt, S, false);
-                __builtin_amdgcn_sched_barrier(0);
-                S = s_tile(kt + 2);
-                __builtin_amdgcn_sched_barrier(0);
-                finish_tile(kt + 1, S1, false);
-                __builtin_amdgcn_sched_barrier(0);
+                step(kt, S, S1, Yes{}, false);
+                step(kt + 1, S1, S, Yes{}, false);
             }
             if (kt + 1 < nkt) {
-                const f32x16 S1 = s_tile(kt + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                finish_tile(kt, S, false);
+                step(kt, S, S1, Yes{}, false);
                 S = S1;
+                ++kt;
             }
-        }
-        // the last S product of this item is on its way: the next item's query may take the registers
-        if (next_tile < n_tiles) {
+            // the last S product of this item has been issued: the next item's query may take the registers
+            if (next_tile < n_tiles) {
+                if constexpr (GATHER) {
+                    if (next_hd == 0) id = checked(next_raw);
+                    const char *tr = table_row(id);
+#pragma unroll
+                    for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(tr + (next_hd * (DH / 8) + 2 * j + h) * 16);
+                } else {
+                    const char *xr = row_of(next_tile);
+#pragma unroll
+                    for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(next_hd * (DH / 8) + 2 * j + h) * xl.piece_stride);
+                }
+            }
+            step(nkt - 1, S, S1, No{}, 32 * nkt > L);
+        } else if (next_tile < n_tiles) {
+            // an empty sequence: only the next item's query is fetched
             if constexpr (GATHER) {
                 if (next_hd == 0) id = checked(next_raw);
                 const char *tr = table_row(id);
@@ -612,7 +671,6 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                 for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(next_hd * (DH / 8) + 2 * j + h) * xl.piece_stride);
             }
         }
-        if (nkt > 0) finish_tile(nkt - 1, S, 32 * nkt > L);
 
         l += __shfl_xor(l, 32, 64);
         const float inv = L > 0 ? 1.0f / l : 0.f;

@@ -266,7 +266,7 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
     if (total > 0) stage_load(0);
 
     // ---- the cross block, from the same row pieces (a second pass over them, under the ring's first load) ----
-    if (m.cross_mode == 1 && live) {
+    if (m.cross_mode == 1 && !m.cross_in_mlp && live) {      // unless the MLP chain forms the Hadamard products itself
         const bf16x8 *uc = (const bf16x8 *)rd.cross_vecs;
         for (int pc = h; pc < m.d_item / 8; pc += 2) {
             const bf16x8 e = item_piece(pc), uv = uc[pc];

@@ -151,7 +151,9 @@ __global__ __launch_bounds__(256) void k_attn_generic(Model m, Batch b, T *__res
         }
         if (on) {
             T *xc = xrow + m.d_item + da;
-            if (m.cross_mode == 1) {
+            if (m.cross_mode == 1 && m.cross_in_mlp) {
+                // the MLP chain forms the Hadamard products itself
+            } else if (m.cross_mode == 1) {
                 for (int k = lane; k < m.d_item; k += 64) st_f<T>(xc + k, ld_f<T>(uc + k) * sh_e[k]);
             } else if (m.cross_mode == 2) {
                 const int S = m.d_item / m.d_cv;

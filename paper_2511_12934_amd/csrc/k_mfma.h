@@ -69,6 +69,7 @@ hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const 
 
 // k_mlp_mfma.hip
 int mlp_mfma_variant(const Model &m);
+bool mlp_chain_forms_cross(int variant, const Model &m);
 hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const void *X, const MlpPack &pk,
                               const float *bias1, hipStream_t s);
 hipError_t pack_frag(const void *W, int n_in, int col0, int N, int K, bool from_mfma, void *dst, hipStream_t s);

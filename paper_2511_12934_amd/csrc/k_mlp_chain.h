@@ -138,7 +138,10 @@ __device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
 // scalar loads at the block's start and its layer-1 biases by a direct-to-LDS load into a second buffer.
 // Only its input rows cannot come early (no register is free before the first tile's last MFMA): they are
 // asked for at the first tile's end and the second tile's first MFMAs wait for them.
-template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS, int PER_CU>
+// EH > 0: the last EH k-steps of layer 1 are the Hadamard cross block c = u (.) e (Sec. 3.3) of the first EH k-steps (the
+// item block): formed here, in registers, from the item fragments and the request's operand u (kept in LDS), rounded to
+// bf16 as the attention kernel would have stored it -- the workspace's cross block is then neither written nor read.
+template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS, int PER_CU, int EH>
 __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items, const ReqDesc *__restrict__ reqs,
                                                            const int32_t *__restrict__ blk_req,
                                                            const int32_t *__restrict__ blk_slot, const char *__restrict__ X,
@@ -159,6 +162,8 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
     static_assert(H1 * 4 % 1024 == 0 && H1 * 4 / 1024 <= WAVES, "the second tile's biases: one 1 KB load per wave");
     extern __shared__ __align__(16) char lds[];                 // the weight ring, then biases and last-layer weights
     float *sb1 = (float *)(lds + C::ring_bytes), *sb2 = sb1 + 2 * H1, *sb3 = sb2 + H2, *swl = sb3 + H3;
+    constexpr int KX = K1 / 16 - EH;                            // k-steps of layer 1 read from the workspace
+    uint32_t *su = (uint32_t *)(lds + C::ring_bytes + (4 * C::bias_floats + 15) / 16 * 16);    // Hadamard operands of both tiles, EH * 8 words each
     // what the end of a tile needs of its request (two whole descriptors would not fit the scalar registers)
     struct Out {
         const int32_t *cand_ids;
@@ -169,6 +174,7 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
         const ReqDesc *q = reqs + r;
         return Out{q->cand_ids, q->logits_out, q->scores_out, q->n_cand, q->row_base};
     };
+    auto cross_of = [&](int r) { return (const uint32_t *)reqs[r].cross_vecs; };
 
     // blocks 0 .. n_pairs - 1 take two tiles each, the blocks after them the remaining tiles one by one
     const bool has_next = (int)blockIdx.x < n_pairs;
@@ -182,7 +188,7 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
     auto load_xin = [&](int t) {
         const char *xr = X + x_offset(xl, t * ROWS + wave * 32 + col, h);
 #pragma unroll
-        for (int j = 0; j < K1 / 16; ++j) xin[j] = *(const bf16x8 *)(xr + (size_t)(2 * j) * xl.piece_stride);
+        for (int j = 0; j < KX; ++j) xin[j] = *(const bf16x8 *)(xr + (size_t)(2 * j) * xl.piece_stride);
     };
     load_xin(tile0);
     // ... and so are the layers' own biases and the ->1 weights (into registers; LDS gets them below)
@@ -214,6 +220,13 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
     const int lc0 = tile0 * ROWS - rd0.row_base + wave * 32 + col, lc1 = t1 * ROWS - rd1.row_base + wave * 32 + col;
     const bool lv0 = h == 0 && lc0 < rd0.n_cand, lv1 = h == 0 && lc1 < rd1.n_cand;
     const int64_t id0 = rd0.cand_ids[lv0 ? lc0 : 0], id1 = rd1.cand_ids[lv1 ? lc1 : 0];
+    // the two tiles' Hadamard operands, two bf16 a word (a thread past the end re-reads the last word)
+    uint32_t gu0 = 0, gu1 = 0;
+    if constexpr (EH > 0) {
+        const int w = (int)threadIdx.x < EH * 8 ? (int)threadIdx.x : EH * 8 - 1;
+        gu0 = cross_of(r0)[w];
+        gu1 = cross_of(r1)[w];
+    }
     // Everything asked for above is pinned here, the ids still in flight: left alone the compiler moves a load down
     // into the condition its value is stored under, behind the wait of whatever comes before it.
 #pragma unroll
@@ -230,6 +243,12 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
     const uint64_t live0 = __ballot(lv0), live1 = __ballot(lv1);
     const uint64_t bad0 = __ballot(lv0 && (id0 < 0 || id0 >= n_items)), bad1 = __ballot(lv1 && (id1 < 0 || id1 >= n_items));
     if (threadIdx.x == 0) swl[C::HL] = gb;
+    if constexpr (EH > 0) {
+        if ((int)threadIdx.x < EH * 8) {
+            su[threadIdx.x] = gu0;
+            su[EH * 8 + threadIdx.x] = gu1;
+        }
+    }
 #pragma unroll
     for (int j = 0; j < N1; ++j)
         if ((int)threadIdx.x + j * THREADS < H1) sb1[threadIdx.x + j * THREADS] = g1[j];
@@ -297,6 +316,16 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
             if constexpr ((Q & 1) == 1) asm volatile("" : "+v"(dst));
         }
     };
+    // k-step KX + j of layer 1 of pass P: the Hadamard products of item k-step j with the request's operand, whose
+    // element 16 j + 8 h + s meets slot s of this lane
+    auto make_cross = [&](auto pc, auto jc) {
+        constexpr int P = decltype(pc)::value, J = decltype(jc)::value;
+        const bf16x8 uf = *(const bf16x8 *)((const char *)su + P * EH * 32 + J * 32 + 16 * h);
+        bf16x8 cx;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) cx[s] = (__bf16)((float)xin[J][s] * (float)uf[s]);
+        xin[KX + J] = cx;
+    };
     auto finish = [&](int tile, const Out &rd, uint64_t live, uint64_t bad) {      // the tile's logits and scores
         float z = zpart + __shfl_xor(zpart, 32, 64) + swl[C::HL];
         const int local = tile * ROWS - rd.row_base + wave * 32 + col;
@@ -348,6 +377,8 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
                     }
                 }
             }
+            // the cross block's k-steps are first used at step KX of the first row tile: formed one per step before it
+            if constexpr (EH > 0 && T == 0 && K < EH) make_cross(pc, IC<K>{});
             if constexpr (F + RING - 1 < NF)
                 areg[(F + RING - 1) % RING] = *(const bf16x8 *)(wl0 + C::foff(F + RING - 1, P));
             else if constexpr (P == 0)      // the second tile's first fragments (read, and never used, when there is none:
@@ -405,15 +436,16 @@ static inline int n_cu()
     return n;
 }
 
-template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS, int PER_CU = 2>
+template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS, int PER_CU = 2, int EH = 0>
 static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, const MlpPack &pk, const float *bias1,
                               hipStream_t s)
 {
     using C = Chain<K1, H1, H2, H3, WAVES, SF, SLOTS>;
-    constexpr int LDS = C::lds_bytes;
+    constexpr int LDS = (C::lds_bytes + 15) / 16 * 16 + 2 * EH * 32;
     constexpr int ROWS = WAVES * 32;
-    auto kern = k_mlp_mfma<K1, H1, H2, H3, WAVES, SF, SLOTS, PER_CU>;
-    static_assert(PER_CU * C::lds_bytes <= 160 * 1024, "the blocks of a compute unit share its LDS");
+    auto kern = k_mlp_mfma<K1, H1, H2, H3, WAVES, SF, SLOTS, PER_CU, EH>;
+    static_assert(PER_CU * LDS <= 160 * 1024, "the blocks of a compute unit share its LDS");
+    static_assert(EH * 8 <= WAVES * 64 && 2 * EH < K1 / 16, "Hadamard operand: one word per thread; item and cross blocks inside layer 1");
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);

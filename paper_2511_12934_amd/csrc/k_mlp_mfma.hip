@@ -29,6 +29,19 @@ hipError_t mlp_chain_c2(const Model &, const Batch &, const void *, const MlpPac
 hipError_t mlp_chain_c3(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 hipError_t mlp_chain_c4(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 hipError_t mlp_chain_c5(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
+hipError_t mlp_chain_c2h(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
+hipError_t mlp_chain_c3h(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
+hipError_t mlp_chain_c4h(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
+
+// Can the chain of this variant form the Hadamard cross block itself (Model::cross_in_mlp)?  Layer 1 after the user
+// fold must be exactly [item | attention | item (.) u] with the item width the kernel was built for.
+bool mlp_chain_forms_cross(int variant, const Model &m)
+{
+    if (m.dtype != 1 || m.cross_mode != 1 || m.k1 != 2 * m.d_item + m.d_attn) return false;
+    if (variant == 0 || variant == 1) return m.d_item == 64;
+    if (variant == 2) return m.d_item == 128;
+    return false;
+}
 
 // ---- weights into fragment order --------------------------------------------
 // dst[((rt * KS + j) * 64 + lane) * 8 + s] = W[32 rt + lane % 32][col0 + k(j, lane / 32, s)]
@@ -73,9 +86,9 @@ hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const
 {
     if (b.n_blk == 0) return hipSuccess;
     switch (variant) {
-    case 0: return mlp_chain_c2(m, b, X, pk, bias1, s);
-    case 1: return mlp_chain_c3(m, b, X, pk, bias1, s);
-    case 2: return mlp_chain_c4(m, b, X, pk, bias1, s);
+    case 0: return m.cross_in_mlp ? mlp_chain_c2h(m, b, X, pk, bias1, s) : mlp_chain_c2(m, b, X, pk, bias1, s);
+    case 1: return m.cross_in_mlp ? mlp_chain_c3h(m, b, X, pk, bias1, s) : mlp_chain_c3(m, b, X, pk, bias1, s);
+    case 2: return m.cross_in_mlp ? mlp_chain_c4h(m, b, X, pk, bias1, s) : mlp_chain_c4(m, b, X, pk, bias1, s);
     case 3: return mlp_chain_c5(m, b, X, pk, bias1, s);
     default: return hipErrorInvalidValue;
     }

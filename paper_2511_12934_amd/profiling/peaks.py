@@ -30,6 +30,8 @@ def main() -> None:
     lib.aifcal_mfma.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.aifcal_copy.restype = C.c_int
     lib.aifcal_copy.argtypes = [vp, vp, C.c_size_t, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.aifcal_fill.restype = C.c_int
+    lib.aifcal_fill.argtypes = [vp, C.c_size_t, C.c_int, C.POINTER(C.c_double)]
     g = torch.Generator(device="cuda").manual_seed(1234)
     n = 16 * 64 * 8
     operands = {
@@ -56,10 +58,14 @@ def main() -> None:
     cp, rd = C.c_double(0), C.c_double(0)
     assert lib.aifcal_copy(src.data_ptr(), dst.data_ptr(), nbytes, 20, C.byref(cp), C.byref(rd)) == 0
     assert bool((dst[-7:] == src[-7:]).all())
-    print(f"\ncopy of 1 GiB, 16 B per lane: {cp.value:.0f} GB/s read + written ({cp.value / 8000:.3f} of 8000); "
-          f"read-only pass: {rd.value:.0f} GB/s ({rd.value / 8000:.3f})")
+    wr = C.c_double(0)
+    assert lib.aifcal_fill(dst.data_ptr(), nbytes, 20, C.byref(wr)) == 0
+    print(f"\n1 GiB, 16 B per lane: copy {cp.value:.0f} GB/s read + written ({cp.value / 8000:.3f} of 8000); "
+          f"read-only pass {rd.value:.0f} GB/s ({rd.value / 8000:.3f}); write-only pass {wr.value:.0f} GB/s ({wr.value / 8000:.3f})")
     print(f"\nachievable_peak mfma_bf16 {best[(1, 'random N(0,0.1)')]:.1f}")
     print(f"achievable_peak hbm {cp.value:.0f}")
+    print(f"achievable_peak hbm_read {rd.value:.0f}")
+    print(f"achievable_peak hbm_write {wr.value:.0f}")
 
 
 if __name__ == "__main__":

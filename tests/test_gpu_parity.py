@@ -654,6 +654,34 @@ def test_projection_attention_with_16_wide_heads(R, torch, shape, sigma):
     assert np.array_equal(np.concatenate(parts), zs[7])
 
 
+@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
+def test_hadamard_cross_formed_in_the_mlp_chain_gives_the_same_bits(R, torch, monkeypatch, name):
+    """Where the MLP is a fused chain and the cross block is u (.) e, the chain forms the products itself from the item
+    block it reads anyway, and the attention kernel leaves the workspace's cross block unwritten.  Same products, same
+    rounding: logits and scores are those of the route that writes the block (AIF_CROSS_MATERIALIZED=1, whose cross
+    block is compared with the oracle's element by element), bit for bit, and the feature matrix the library shows
+    is the same."""
+    base = wl.CONFIGS[name]
+    cfg = base.scaled(n_items=6000, seq_len=min(base.seq_len, 700))
+    _say(f"{name} shape: Hadamard cross in the MLP chain vs written to the workspace")
+    rng = np.random.default_rng(4242)
+    model = wl.make_model(cfg, bias_scale=0.05)
+    table = wl.make_table_host(cfg, rng, n_items=6000, sigma=1.0)
+    sampler = wl.IdSampler(cfg, 6000)
+    reqs = [(wl.make_user(cfg, rng, sigma=1.0), sampler.sample(rng, n)) for n in (1500, 1, 257, 700)]
+    table_dev = R.to_device(table, "bf16")
+    z0, y0, _, ctx0 = run_batch(R, torch, cfg, model, table_dev, reqs)
+    X0 = [R.peek_features(ctx0, cfg, r, ids.size) for r, (_, ids) in enumerate(reqs)]
+    monkeypatch.setenv("AIF_CROSS_MATERIALIZED", "1")
+    z1, y1, _, ctx1 = run_batch(R, torch, cfg, model, table_dev, reqs)
+    X1 = [R.peek_features(ctx1, cfg, r, ids.size) for r, (_, ids) in enumerate(reqs)]
+    for r, (u, ids) in enumerate(reqs):
+        assert np.array_equal(z0[r], z1[r]) and np.array_equal(y0[r], y1[r]), f"request {r}"
+        assert np.array_equal(X0[r], X1[r]), f"request {r}: feature matrix"
+        ref = oracle_scores(cfg, model, table, u, ids, n_threads=8)
+        assert_features_close("bf16", X1[r][:, cfg.d_item + cfg.d_attn:], ref.cross, f"request {r} cross")
+
+
 def test_widest_head_as_one_fused_chain(R, torch, monkeypatch):
     """C5's head (448 -> 1024 -> 512 -> 256 -> 1 after the user fold) runs as ONE launch with a candidate's activations
     in registers.  Enough candidates (more 128-candidate tiles than compute units) that blocks take two tiles each as
