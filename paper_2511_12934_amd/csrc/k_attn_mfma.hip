@@ -45,6 +45,27 @@ __device__ __forceinline__ void store_stream(bf16x4 *p, bf16x4 v) { __builtin_no
 
 constexpr float LOG2E = 1.4426950408889634f;
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+// acc + a[2i] b[2i] + a[2i + 1] b[2i + 1], i = 0..3, as four two-term dot products (one instruction each)
+__device__ __forceinline__ float dot8(const bf16x8 &a, const bf16x8 &b, float acc)
+{
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 0, 1), __builtin_shufflevector(b, b, 0, 1), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 2, 3), __builtin_shufflevector(b, b, 2, 3), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 4, 5), __builtin_shufflevector(b, b, 4, 5), acc, false);
+    acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(b, b, 6, 7), acc, false);
+    return acc;
+}
+// acc + the sum of elements [2 i0, 2 i0 + 2 n) of a (pairs i0 .. i0 + n - 1), pair by pair
+template <int I0, int N> __device__ __forceinline__ float sum_pairs(const bf16x8 &a, float acc)
+{
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    if constexpr (N >= 1 && I0 <= 0 && 0 < I0 + N) acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 0, 1), ones, acc, false);
+    if constexpr (N >= 1 && I0 <= 1 && 1 < I0 + N) acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 2, 3), ones, acc, false);
+    if constexpr (N >= 1 && I0 <= 2 && 2 < I0 + N) acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 4, 5), ones, acc, false);
+    if constexpr (N >= 1 && I0 <= 3 && 3 < I0 + N) acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 6, 7), ones, acc, false);
+    return acc;
+}
+
 // BEA cross block (Sec. 4.1, Algorithm 1 step 4) on the matrix cores: C^T = V^T w^T with the
 // candidates as columns.  The contraction runs over the row's last 16 * ksb entries (the "window",
 // ksb = ceil(n_cross / 16) k-steps); window entries in front of the n_cross bridge weights meet
@@ -158,12 +179,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
             for (int j = 0; j < JS; ++j) q[j] = *piece(hd * (DH / 8) + 2 * j + h);
             km = load_kmax(hd);
         }
-        float ss = 0.f;
+        float ss = 0.f;                     // |q|^2 of this half's pieces, two terms an instruction
 #pragma unroll
-        for (int j = 0; j < JS; ++j) {
-#pragma unroll
-            for (int s = 0; s < 8; ++s) ss += (float)q[j][s] * (float)q[j][s];
-        }
+        for (int j = 0; j < JS; ++j) ss = dot8(q[j], q[j], ss);
         ss += __shfl_xor(ss, 32, 64);
 #pragma unroll
         for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
@@ -224,13 +242,16 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
                         if (t >= L) p[v] = 0.f;
                     }
                 }
+                // the softmax denominator is the sum of the weights AS ROUNDED for the second product, P0's then P1's,
+                // two a step: the block then is an exact convex combination of the values the matrix cores see
                 bf16x8 P0, P1;
 #pragma unroll
                 for (int v = 0; v < 8; ++v) {
-                    l += p[v] + p[8 + v];
                     P0[v] = (__bf16)p[v];
                     P1[v] = (__bf16)p[8 + v];
                 }
+                l = sum_pairs<0, 4>(P0, l);
+                l = sum_pairs<0, 4>(P1, l);
 #pragma unroll
                 for (int ft = 0; ft < FT; ++ft) {
                     O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + (JS + ft) * 1024), P0, O[ft], 0, 0, 0);
@@ -511,12 +532,9 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
             }
         }
 
-        float ss = 0.f;
+        float ss = 0.f;                     // |q|^2 of this half's pieces, two terms an instruction
 #pragma unroll
-        for (int j = 0; j < JS; ++j) {
-#pragma unroll
-            for (int s = 0; s < 8; ++s) ss += (float)q[j][s] * (float)q[j][s];
-        }
+        for (int j = 0; j < JS; ++j) ss = dot8(q[j], q[j], ss);
         ss += __shfl_xor(ss, 32, 64);
         const char *kvh = kv0 + (size_t)hd * head_frags * 1024;
         auto s_tile = [&](int kt) {
@@ -560,13 +578,76 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         //   - the K fragment a link has just consumed is refilled from LDS with tile t + 2's (a whole tile of lead),
         //     V fragments of tile t are asked for at the top of the tile;
         //   - the second product's MFMAs (feature tiles alternating, so consecutive ones are independent) carry the
-        //     row sums between them.
+        //     row sums (of the rounded weights) between them.
         // Scheduling barriers pin the slots; within a slot the compiler is free.  Per candidate the arithmetic and
         // its order are unchanged.
+        const char *kbase = kvh;                                       // K fragment j of tile t: kbase + (t FR + j) KB
+        bf16x8 kf[JS], vf[2 * FT];
+        f32x16 S, S1;
+        // tile kt: exponentials of Sin, second product; with NEXT also the S product of tile kt + 1 into Sout
+        auto step = [&](int kt, const f32x16 &Sin, f32x16 &Sout, auto next_c, bool ragged) {
+            constexpr bool NEXT = decltype(next_c)::value;
+            const char *vbase = kbase + (kt * FR + JS) * 1024;
+#pragma unroll
+            for (int i = 0; i < 2 * FT; ++i) vf[i] = *(const bf16x8 *)(vbase + i * 1024);
+            const int kn = kt + 2 < nkt ? kt + 2 : nkt - 1;         // refill: the tile after next (clamped: read, not used)
+            __builtin_amdgcn_sched_barrier(0);
+            float p[16];
+#pragma unroll
+            for (int j = 0; j < JS; ++j) {
+                if constexpr (NEXT) {
+                    if (j == 0) {
+                        f32x16 Z;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) Z[i] = 0.f;
+                        Sout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], q[0], Z, 0, 0, 0);
+                    } else
+                        Sout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], q[j], Sout, 0, 0, 0);
+                    kf[j] = *(const bf16x8 *)(kbase + (kn * FR + j) * 1024);
+                }
+#pragma unroll
+                for (int v = 16 / JS * j; v < 16 / JS * (j + 1); ++v) {
+                    p[v] = __builtin_amdgcn_exp2f(fmaf(Sin[v], c, -mc));
+                    asm volatile("" : "+v"(p[v]));      // computed HERE: a value with no side effect would sink to its first use
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (ragged) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (t >= L) p[v] = 0.f;
+                }
+            }
+            bf16x8 P0, P1;
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                P0[v] = (__bf16)p[v];
+                P1[v] = (__bf16)p[8 + v];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // per feature tile the P0 step, then the P1 step (the order the streaming kernel accumulates in);
+            // issued feature tile by feature tile within a step; the row sums ride between the MFMAs
+#pragma unroll
+            for (int i = 0; i < 2 * FT; ++i) {
+                const int ft = i % FT;
+                O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], i < FT ? P0 : P1, O[ft], 0, 0, 0);
+                // the denominator: the weights as rounded, P0's pairs then P1's (the streaming kernel's order)
+                if constexpr (FT == 2) {
+                    if (i == 0) l = sum_pairs<0, 2>(P0, l);
+                    if (i == 1) l = sum_pairs<2, 2>(P0, l);
+                    if (i == 2) l = sum_pairs<0, 2>(P1, l);
+                    if (i == 3) l = sum_pairs<2, 2>(P1, l);
+                } else {
+                    if (i == 0) l = sum_pairs<0, 4>(P0, l);
+                    if (i == 1) l = sum_pairs<0, 4>(P1, l);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        using Yes = std::true_type;
+        using No = std::false_type;
         if (nkt > 0) {
-            const char *kbase = kvh;                                   // K fragment j of tile t: kbase + (t FR + j) KB
-            bf16x8 kf[JS], vf[2 * FT];
-            f32x16 S, S1;
 #pragma unroll
             for (int j = 0; j < JS; ++j) kf[j] = *(const bf16x8 *)(kbase + j * 1024);
 #pragma unroll
@@ -579,61 +660,6 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                 for (int j = 0; j < JS; ++j) kf[j] = *(const bf16x8 *)(kbase + (k1 * FR + j) * 1024);
             }
             __builtin_amdgcn_sched_barrier(0);
-            // tile kt: exponentials of Sin, second product; with NEXT also the S product of tile kt + 1 into Sout
-            auto step = [&](int kt, const f32x16 &Sin, f32x16 &Sout, auto next_c, bool ragged) {
-                constexpr bool NEXT = decltype(next_c)::value;
-                const char *vbase = kbase + (kt * FR + JS) * 1024;
-#pragma unroll
-                for (int i = 0; i < 2 * FT; ++i) vf[i] = *(const bf16x8 *)(vbase + i * 1024);
-                const int kn = kt + 2 < nkt ? kt + 2 : nkt - 1;         // refill: the tile after next (clamped: read, not used)
-                __builtin_amdgcn_sched_barrier(0);
-                float p[16];
-#pragma unroll
-                for (int j = 0; j < JS; ++j) {
-                    if constexpr (NEXT) {
-                        if (j == 0) {
-                            f32x16 Z;
-#pragma unroll
-                            for (int i = 0; i < 16; ++i) Z[i] = 0.f;
-                            Sout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], q[0], Z, 0, 0, 0);
-                        } else
-                            Sout = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j], q[j], Sout, 0, 0, 0);
-                        kf[j] = *(const bf16x8 *)(kbase + (kn * FR + j) * 1024);
-                    }
-#pragma unroll
-                    for (int v = 16 / JS * j; v < 16 / JS * (j + 1); ++v) {
-                        p[v] = __builtin_amdgcn_exp2f(fmaf(Sin[v], c, -mc));
-                        asm volatile("" : "+v"(p[v]));      // computed HERE: a value with no side effect would sink to its first use
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                if (ragged) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
-                        if (t >= L) p[v] = 0.f;
-                    }
-                }
-                bf16x8 P0, P1;
-#pragma unroll
-                for (int v = 0; v < 8; ++v) {
-                    P0[v] = (__bf16)p[v];
-                    P1[v] = (__bf16)p[8 + v];
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                // per feature tile the P0 step, then the P1 step (the order the streaming kernel accumulates in);
-                // issued feature tile by feature tile within a step; the row sums ride between the MFMAs
-#pragma unroll
-                for (int i = 0; i < 2 * FT; ++i) {
-                    const int ft = i % FT;
-                    O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], i < FT ? P0 : P1, O[ft], 0, 0, 0);
-#pragma unroll
-                    for (int v = 8 / (2 * FT) * i; v < 8 / (2 * FT) * (i + 1); ++v) l += p[v] + p[8 + v];
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            };
-            using Yes = std::true_type;
-            using No = std::false_type;
             int kt = 0;
             for (; kt + 2 < nkt; kt += 2) {
                 step(kt, S, S1, Yes{}, false);
@@ -642,24 +668,13 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
             if (kt + 1 < nkt) {
                 step(kt, S, S1, Yes{}, false);
                 S = S1;
-                ++kt;
             }
-            // the last S product of this item has been issued: the next item's query may take the registers
-            if (next_tile < n_tiles) {
-                if constexpr (GATHER) {
-                    if (next_hd == 0) id = checked(next_raw);
-                    const char *tr = table_row(id);
-#pragma unroll
-                    for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(tr + (next_hd * (DH / 8) + 2 * j + h) * 16);
-                } else {
-                    const char *xr = row_of(next_tile);
-#pragma unroll
-                    for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(next_hd * (DH / 8) + 2 * j + h) * xl.piece_stride);
-                }
-            }
-            step(nkt - 1, S, S1, No{}, 32 * nkt > L);
-        } else if (next_tile < n_tiles) {
-            // an empty sequence: only the next item's query is fetched
+        }
+        // The last S product of this item has been issued: the next item's query may take the registers.  (One site for
+        // both the ordinary and the empty sequence: a second copy of these loads on another path into this point makes
+        // the compiler wait, at the key-tile loop's first MFMA, for every memory operation in flight -- the item's
+        // stores included.)
+        if (next_tile < n_tiles) {
             if constexpr (GATHER) {
                 if (next_hd == 0) id = checked(next_raw);
                 const char *tr = table_row(id);
@@ -671,6 +686,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                 for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(next_hd * (DH / 8) + 2 * j + h) * xl.piece_stride);
             }
         }
+        if (nkt > 0) step(nkt - 1, S, S1, No{}, 32 * nkt > L);
 
         l += __shfl_xor(l, 32, 64);
         const float inv = L > 0 ? 1.0f / l : 0.f;
