@@ -596,6 +596,8 @@ def main():
                     help="distinct candidate lists per user, taken in turn by consecutive steps")
     ap.add_argument("--profile-every", type=int, default=8,
                     help="inside the timed region the dominant kernel of every n-th step is timed with events")
+    ap.add_argument("--settle-ms", type=float, default=300.0,
+                    help="untimed steps run for this long before the warm-up, so that the board's clocks have settled")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true")
     args = ap.parse_args()
@@ -625,6 +627,17 @@ def main():
         sys.exit("bench.py needs a GPU")
     cfg = wl.CONFIGS[args.workload]
     w = R.Workload(cfg, n_sets=args.id_sets)
+    # The workload is built on the host for seconds while the device idles at its lowest clocks, and a run of a few
+    # dozen steps would be over before the board has settled (its first 100 ms read 4-8 % slow): the same steps are run
+    # untimed for --settle-ms first.  They are not part of `warmup` (the W warm-up steps below still run) and are
+    # reported as `settle_steps`.
+    settle_steps = 0
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        for _ in range(8):
+            w.step()
+        torch.cuda.synchronize()
+        settle_steps += 8
     for _ in range(args.warmup):
         w.step()
     torch.cuda.synchronize()
@@ -691,7 +704,7 @@ def main():
     line = {
         "metric": "candidates scored/sec/GPU at 10^4-cand requests",
         "value": value, "unit": "candidates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "settle_steps": settle_steps, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {w.n_users} users x {w.n_cand} candidates, table {cfg.n_items}x{cfg.d_item} "
                                f"{cfg.dtype}, L={cfg.seq_len}, d_attn={cfg.d_attn}, H={cfg.n_heads}, "

@@ -79,11 +79,13 @@ __device__ __forceinline__ void gather_block_tiled(int blk, const uint4 *__restr
                                                    int32_t *__restrict__ bad)
 {
     constexpr int RV = 1 << LOG_RV;                      // pieces per row: 8, 16 or 32
-    constexpr int ROWS = 1024 >> LOG_RV;                 // rows per trip
+    constexpr int NV = LOG_RV == 3 ? 8 : 4;              // 16-byte loads in flight per thread (128-byte rows: the block's 256 rows in one trip)
+    constexpr int ROWS = (256 * NV) >> LOG_RV;           // rows per trip
     constexpr int PSTR = LOG_RV == 3 ? 544 : 528;        // LDS bytes per 32-row run of one piece: no bank conflicts either way
-    constexpr int BUF = 32 * PSTR;                       // 32 runs per trip
+    constexpr int BUF = 8 * NV * PSTR;                   // 8 NV runs per trip
+    constexpr int NBUF = ROW_BLOCK / ROWS > 1 ? 2 : 1;   // a single trip needs no second buffer
     static_assert(LOG_RV >= 3 && LOG_RV <= 5 && ROW_BLOCK % ROWS == 0, "row widths of 128, 256, 512 bytes");
-    __shared__ __align__(16) char buf[2 * BUF];
+    __shared__ __align__(16) char buf[NBUF * BUF];
     __shared__ int32_t sid[ROW_BLOCK];
 
     const int r = b.blk_req[blk];
@@ -108,10 +110,10 @@ __device__ __forceinline__ void gather_block_tiled(int blk, const uint4 *__restr
     }
     __syncthreads();
 
-    uint4 v[4];
+    uint4 v[NV];
     auto fetch = [&](int trip) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < NV; ++j) {
             const int idx = threadIdx.x + 256 * j, row = trip * ROWS + (idx >> LOG_RV), piece = idx & (RV - 1);
             v[j] = row < nrows ? table[(size_t)sid[row] * RV + piece] : make_uint4(0, 0, 0, 0);
         }
@@ -119,16 +121,16 @@ __device__ __forceinline__ void gather_block_tiled(int blk, const uint4 *__restr
     const int ntrip = (nrows + ROWS - 1) / ROWS;
     fetch(0);
     for (int trip = 0; trip < ntrip; ++trip) {
-        char *lb = buf + (trip & 1) * BUF;
+        char *lb = buf + (trip & (NBUF - 1)) * BUF;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < NV; ++j) {
             const int idx = threadIdx.x + 256 * j, row = idx >> LOG_RV, piece = idx & (RV - 1);
             *(uint4 *)(lb + ((row >> 5) * RV + piece) * PSTR + (row & 31) * 16) = v[j];
         }
         if (trip + 1 < ntrip) fetch(trip + 1);
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < NV; ++j) {
             const int idx = threadIdx.x + 256 * j, run = idx >> 5, row = idx & 31;      // run = (tile of the trip, piece)
             const int tt = run >> LOG_RV, piece = run & (RV - 1);
             if (trip * ROWS + tt * 32 + row < nrows) {
