@@ -19,6 +19,8 @@
 // order of the fp32 additions.
 #include "aif_lsh_dev.h"
 
+#include <cstdlib>
+
 namespace aif {
 
 __device__ __forceinline__ float lsh_ld(const void *p, int dtype, size_t i)
@@ -98,10 +100,123 @@ __global__ __launch_bounds__(256) void k_lsh_user_partial(LshModel m, LshBatch b
     }
 }
 
+// ---------------------------------------------------------------------------
+// The same partial sums on the matrix cores, for bf16 embeddings.  part[s][k][j] = sum_t [b_tk == s] U~[t][j] is a
+// contraction over the history: (bits as 0/1, inverted for s = 0) [2 d' x l] times U~ [l x d].  0, 1 and the
+// embeddings are exact in bf16 and the MFMA accumulates in fp32, so the values are those of the loop above up to the
+// order of the additions.  The contraction index t is the slow axis of both inputs as the caller stores them, so
+// both pass through LDS: 64 history items at a time, the embeddings set down transposed ([j][t]: a lane's eight
+// consecutive t are one 16-byte read), the signatures turned into bit planes over t by wave ballots (lane = t), from
+// which an A fragment -- eight consecutive t of one bit position -- is one byte, expanded to eight bf16 through a
+// 256-entry table in LDS.  Block = (chunk of LSH_TCHUNK items, request), four waves; the 2 d' / 32 x d / 32 result
+// tiles are dealt round the waves, TPW each.
+// ---------------------------------------------------------------------------
+typedef __bf16 lsh_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float lsh_f32x16 __attribute__((ext_vector_type(16)));
+constexpr int LSH_TS = 64;              // history items per trip through LDS: four MFMA k-steps
+
+template <int TPW>
+__global__ __launch_bounds__(256) void k_lsh_user_partial_mfma(LshModel m, LshBatch b, int max_chunks, float *__restrict__ part)
+{
+    extern __shared__ __align__(16) char lds[];
+    const int r = blockIdx.y, chunk = blockIdx.x;
+    const LshReqDesc rd = b.reqs[r];
+    const int t_lo = chunk * LSH_TCHUNK;
+    if (t_lo >= rd.seq_len) return;
+    const int t_hi = min(rd.seq_len, t_lo + LSH_TCHUNK);
+    const int d = m.d_out, db = m.d_bits, nb = db / 8, CT = d / 32;
+    constexpr int USTR = LSH_TS * 2 + 16;                        // bytes per transposed embedding row (64 t + padding)
+    uint4 *lut = (uint4 *)lds;                                   // [256] byte -> eight bf16 of 0 / 1, first bit = first slot
+    char *su = lds + 4096;                                       // [d][USTR]: U~ of the trip, transposed
+    uint32_t *bp = (uint32_t *)(su + (size_t)d * USTR);          // [d'][2]: bit k of the trip's 64 signatures, lane t = bit t
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, h = lane >> 5;
+    {
+        const uint32_t v = threadIdx.x;                          // slot s of the fragment = bit s of the byte (t0 + s)
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = ((v >> (2 * i)) & 1u) * 0x3F80u + ((v >> (2 * i + 1)) & 1u) * 0x3F800000u;
+        lut[threadIdx.x] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    lsh_f32x16 acc[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    const uint16_t *emb = (const uint16_t *)rd.seq_emb;
+
+    for (int ts = t_lo; ts < t_hi; ts += LSH_TS) {
+        __syncthreads();                                         // the last trip's fragments have been read
+        // embeddings: 16-byte pieces (eight features of one item) read in row order, written transposed
+        for (int pc = threadIdx.x; pc < LSH_TS * d / 8; pc += 256) {
+            const int t = pc / (d / 8), j0 = (pc - t * (d / 8)) * 8;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (ts + t < t_hi) v = *(const uint4 *)(emb + (size_t)(ts + t) * d + j0);
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                *(uint16_t *)(su + (size_t)(j0 + i) * USTR + 2 * t) = (uint16_t)(w[i >> 1] >> (16 * (i & 1)));
+        }
+        // signatures: lane = history item; bit k of all 64 items by one ballot; the waves share the bit positions
+        {
+            const int t = ts + lane;
+            const uint8_t *sg = rd.seq_sigs + (size_t)t * nb;
+            for (int k = wave; k < db; k += 4) {
+                const uint32_t byte = t < t_hi ? sg[k >> 3] : 0u;            // first bit most significant
+                const unsigned long long mask = __ballot((byte >> (7 - (k & 7))) & 1u);
+                if (lane == 0) {
+                    bp[2 * k] = (uint32_t)mask;
+                    bp[2 * k + 1] = (uint32_t)(mask >> 32);
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < LSH_TS / 16; ++ks) {
+            const int tb = 16 * ks + 8 * h;                      // this lane's eight items of the k-step
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const int idx = wave + 4 * i, rt = idx / CT, ct = idx - rt * CT;
+                const int row = 32 * rt + col, sbit = row / db, k = row - sbit * db;        // row = s d' + k
+                uint32_t byte = (bp[2 * k + (tb >> 5)] >> (tb & 31)) & 0xFFu;
+                if (sbit == 0) byte ^= 0xFFu;                    // the items whose bit is 0
+                const lsh_bf16x8 A = __builtin_bit_cast(lsh_bf16x8, lut[byte]);
+                const lsh_bf16x8 B = *(const lsh_bf16x8 *)(su + (size_t)(32 * ct + col) * USTR + 2 * tb);
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, B, acc[i], 0, 0, 0);
+            }
+        }
+    }
+    float *out = part + ((size_t)r * max_chunks + chunk) * 2 * db * d;
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int idx = wave + 4 * i, rt = idx / CT, ct = idx - rt * CT;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) out[(size_t)(32 * rt + 8 * (e >> 2) + 4 * h + (e & 3)) * d + 32 * ct + col] = acc[i][e];
+    }
+}
+
+// bf16 embeddings, whole 32-tiles, a number of result tiles the four waves share evenly: the matrix-core form
+static int lsh_user_mfma_tpw(const LshModel &m)
+{
+    if (m.dtype != 1 || m.d_out % 32 || m.d_bits % 32) return 0;
+    const int nt = (2 * m.d_bits / 32) * (m.d_out / 32);
+    return (nt == 8 || nt == 16 || nt == 32) ? nt / 4 : 0;
+}
+
 hipError_t launch_lsh_user_partial(const LshModel &m, const LshBatch &b, int grid_chunks, int max_chunks, float *part,
                                    hipStream_t s)
 {
     if (b.n_req == 0 || grid_chunks == 0) return hipSuccess;
+    if (const int tpw = lsh_user_mfma_tpw(m)) {
+        const char *off = getenv("AIF_LSH_USER_VALU");           // testing: the vector-ALU form on a shape the matrix cores serve
+        if (!(off && off[0] == '1')) {
+            const size_t bytes = 4096 + (size_t)m.d_out * (LSH_TS * 2 + 16) + (size_t)m.d_bits * 8;
+            const dim3 grid(grid_chunks, b.n_req), block(256);
+            if (tpw == 2) hipLaunchKernelGGL(k_lsh_user_partial_mfma<2>, grid, block, bytes, s, m, b, max_chunks, part);
+            else if (tpw == 4) hipLaunchKernelGGL(k_lsh_user_partial_mfma<4>, grid, block, bytes, s, m, b, max_chunks, part);
+            else hipLaunchKernelGGL(k_lsh_user_partial_mfma<8>, grid, block, bytes, s, m, b, max_chunks, part);
+            return hipGetLastError();
+        }
+    }
     const size_t lds = (size_t)LSH_TSUB * (m.d_out * 4 + m.d_bits / 8);
     static bool attr_set = false;
     if (!attr_set) {

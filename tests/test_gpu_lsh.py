@@ -72,7 +72,8 @@ def test_l1_full_size(R, torch):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("d_bits,d_out,n_tiers", [(64, 64, 8), (32, 16, 1), (96, 48, 5), (128, 128, 8), (256, 256, 7), (160, 32, 3)])
+@pytest.mark.parametrize("d_bits,d_out,n_tiers", [(64, 64, 8), (32, 16, 1), (96, 48, 5), (128, 128, 8), (256, 256, 7), (160, 32, 3),
+                                                   (128, 64, 4), (64, 128, 2)])
 def test_shapes_ragged(R, torch, dtype, d_bits, d_out, n_tiers):
     cfg = wl.LshConfig("S", 9, dtype, 1, 10, 3000, d_bits, d_out, n_tiers, 50, n_clusters=16, flip=0.2)
     _say(f"lsh {dtype} d'={d_bits} d={d_out} N={n_tiers}")
