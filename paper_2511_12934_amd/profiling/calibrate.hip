@@ -59,6 +59,45 @@ __global__ __launch_bounds__(256) void k_mfma_loop(const uint4 *__restrict__ a_s
 }
 
 // four independent 16-byte loads in flight per thread before the first store; streaming (non-temporal) stores
+// How much vector-ALU work fits beside the MFMAs of the same SIMD: groups of {1 MFMA, NF v_fma_f32, NE v_exp_f32}, all
+// independent of one another, three waves per SIMD (the attention kernel's occupancy), constant operands (full clock).
+template <int NF, int NE, int WITH_MFMA>
+__global__ __launch_bounds__(768) void k_coissue(float *__restrict__ out, int iters)
+{
+    bf16x8 a, b;
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)(threadIdx.x * 0.001f + i);
+        b[i] = (__bf16)(i * 0.5f);
+    }
+    f32x16 acc[2];
+    for (int n = 0; n < 2; ++n)
+        for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+    float x[16];
+    for (int i = 0; i < 16; ++i) x[i] = 0.001f * (threadIdx.x + i) + 0.5f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            if constexpr (WITH_MFMA) acc[r & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[r & 1], 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < NF; ++v) {
+                const int i = (r * NF + v) & 15;
+                x[i] = fmaf(x[i], 0.999f, 0.001f);
+            }
+#pragma unroll
+            for (int v = 0; v < NE; ++v) {
+                const int i = (r * NE + v + 5) & 15;
+                x[i] = __builtin_amdgcn_exp2f(x[i]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    float s = 0.f;
+    for (int n = 0; n < 2; ++n)
+        for (int i = 0; i < 16; ++i) s += acc[n][i];
+    for (int i = 0; i < 16; ++i) s += x[i];
+    out[(size_t)blockIdx.x * 768 + threadIdx.x] = s;
+}
+
 __global__ __launch_bounds__(256) void k_copy(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16)
 {
     const size_t stride = (size_t)gridDim.x * 256;
@@ -228,6 +267,46 @@ __attribute__((visibility("default"))) int aifcal_copy(const void *src, void *ds
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     (void)hipFree(flag);
+    return 0;
+}
+
+// ns_out (HOST, 8 values): nanoseconds per group and SIMD of {MFMA}, {MFMA + 4 fma}, {MFMA + 4 exp}, {MFMA + 4 fma + 4 exp},
+// {MFMA + 8 fma + 8 exp}, and without the MFMA {4 fma + 4 exp}, {8 fma + 8 exp}, {16 fma}.  Returns 0 on success.
+__attribute__((visibility("default"))) int aifcal_coissue(double *ns_out)
+{
+    int dev = 0;
+    hipDeviceProp_t prop;
+    CAL_TRY(hipGetDevice(&dev));
+    CAL_TRY(hipGetDeviceProperties(&prop, dev));
+    const int blocks = prop.multiProcessorCount, iters = 4000;
+    float *out = nullptr;
+    CAL_TRY(hipMalloc((void **)&out, (size_t)blocks * 768 * 4));
+    hipEvent_t e0, e1;
+    CAL_TRY(hipEventCreate(&e0));
+    CAL_TRY(hipEventCreate(&e1));
+    auto timed = [&](auto kern, double *ns) -> int {
+        for (int rep = 0; rep < 3; ++rep) hipLaunchKernelGGL(kern, dim3(blocks), dim3(768), 0, 0, out, iters);
+        CAL_TRY(hipDeviceSynchronize());
+        CAL_TRY(hipEventRecord(e0, 0));
+        hipLaunchKernelGGL(kern, dim3(blocks), dim3(768), 0, 0, out, iters);
+        CAL_TRY(hipEventRecord(e1, 0));
+        CAL_TRY(hipEventSynchronize(e1));
+        float ms = 0.f;
+        CAL_TRY(hipEventElapsedTime(&ms, e0, e1));
+        *ns = ms * 1e6 / ((double)iters * 8 * 3);       // groups issued on one SIMD: 3 waves x iters x 8
+        return 0;
+    };
+    for (int w = 0; w < 10; ++w) {                      // let the clocks rise
+        double d;
+        if (timed(k_coissue<4, 4, 1>, &d)) return 1;
+    }
+    if (timed(k_coissue<0, 0, 1>, ns_out + 0) || timed(k_coissue<4, 0, 1>, ns_out + 1) || timed(k_coissue<0, 4, 1>, ns_out + 2) ||
+        timed(k_coissue<4, 4, 1>, ns_out + 3) || timed(k_coissue<8, 8, 1>, ns_out + 4) || timed(k_coissue<4, 4, 0>, ns_out + 5) ||
+        timed(k_coissue<8, 8, 0>, ns_out + 6) || timed(k_coissue<16, 0, 0>, ns_out + 7))
+        return 1;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    (void)hipFree(out);
     return 0;
 }
 

@@ -62,6 +62,18 @@ def main() -> None:
     assert lib.aifcal_fill(dst.data_ptr(), nbytes, 20, C.byref(wr)) == 0
     print(f"\n1 GiB, 16 B per lane: copy {cp.value:.0f} GB/s read + written ({cp.value / 8000:.3f} of 8000); "
           f"read-only pass {rd.value:.0f} GB/s ({rd.value / 8000:.3f}); write-only pass {wr.value:.0f} GB/s ({wr.value / 8000:.3f})")
+    lib.aifcal_coissue.restype = C.c_int
+    lib.aifcal_coissue.argtypes = [C.POINTER(C.c_double)]
+    ns = (C.c_double * 8)()
+    assert lib.aifcal_coissue(ns) == 0
+    labels = ["1 MFMA", "1 MFMA + 4 v_fma_f32", "1 MFMA + 4 v_exp_f32", "1 MFMA + 4 v_fma_f32 + 4 v_exp_f32",
+              "1 MFMA + 8 v_fma_f32 + 8 v_exp_f32", "4 v_fma_f32 + 4 v_exp_f32 (no MFMA)", "8 v_fma_f32 + 8 v_exp_f32 (no MFMA)",
+              "16 v_fma_f32 (no MFMA)"]
+    print("\nVector-ALU work beside the matrix cores (independent instructions, 3 waves per SIMD, constant operands): ns per group per SIMD")
+    for lb, v in zip(labels, ns):
+        print(f"  {lb:40s} {v:7.2f}")
+    print(f"  => v_fma_f32 {ns[7] / 16:.2f} ns, v_exp_f32 {(ns[6] - ns[7] / 2) / 8:.2f} ns; an MFMA under which the vector work does not fit "
+          f"adds {ns[4] - ns[6]:.2f} ns (of its {ns[0]:.2f}) to the vector work's time")
     print(f"\nachievable_peak mfma_bf16 {best[(1, 'random N(0,0.1)')]:.1f}")
     print(f"achievable_peak hbm {cp.value:.0f}")
     print(f"achievable_peak hbm_read {rd.value:.0f}")
