@@ -5,6 +5,7 @@
 #include "../../include/aif.h"
 #include "aif_dev.h"
 #include "k_mfma.h"
+#include "k_stage.h"
 
 #include <cstdarg>
 #include <cstdio>
@@ -46,33 +47,9 @@ hipError_t scratch_of(int dev, unsigned char **out)
     return hipSuccess;
 }
 
-// Descriptor tables of a one-request batch, written by the device itself from kernel arguments (no pinned staging,
-// no copy command, nothing to wait for on the host): the request, block -> request and block -> user slot (all 0),
-// the attention groups (an even split of the request's tiles, as attn_plan_groups cuts them) and the top-k descriptor.
-struct StaticFill {
-    ReqDesc rd;
-    TopkDesc td;
-    ReqDesc *reqs;
-    int32_t *blk_req, *blk_slot, *slot_req;
-    AttnGroup *groups;
-    TopkDesc *topk;
-    int32_t n_blk, n_groups, tiles;
-};
-__global__ __launch_bounds__(256) void k_static_fill(StaticFill f)
-{
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i == 0) {
-        f.reqs[0] = f.rd;
-        f.slot_req[0] = 0;
-        f.topk[0] = f.td;
-    }
-    if (i < f.n_blk) {
-        f.blk_req[i] = 0;
-        f.blk_slot[i] = 0;
-    }
-    if (i < f.n_groups)
-        f.groups[i] = AttnGroup{0, (int)((long)f.tiles * i / f.n_groups), (int)((long)f.tiles * (i + 1) / f.n_groups), 0};
-}
+// The descriptor tables of a one-request batch written as a launch of its own (one_fill): for the models whose
+// staging is not the fused launch, which would carry them.
+__global__ __launch_bounds__(256) void k_static_fill(OneFill f) { one_fill(f, blockIdx.x * 256 + threadIdx.x); }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 thread_local std::string g_init_error = "";
@@ -470,7 +447,8 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
     b.n_slots = n_slots;
     // groups of tiles for the attention kernel that keeps K/V resident, 16-byte aligned after the three tables
     const size_t goff = ((size_t)((char *)(hq + n_slots) - h) + 15) / 16 * 16;
-    b.n_groups = c->mfma.attn ? attn_plan_groups(m, hd, n_req, c->n_cu, (AttnGroup *)(h + goff)) : 0;
+    b.n_streamed = 0;
+    b.n_groups = c->mfma.attn ? attn_plan_groups(m, hd, n_req, c->n_cu, (AttnGroup *)(h + goff), &b.n_streamed) : 0;
     b.groups = (const AttnGroup *)(d + goff);
     size_t bytes = goff + (size_t)b.n_groups * sizeof(AttnGroup);
     const size_t toff = (bytes + 15) / 16 * 16;
@@ -486,9 +464,26 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
     // where it can, the attention kernel takes the item vectors from the table itself
     const bool attn_indexes = c->mfma.attn && !c->separate_gather && attn_gathers(m, b, c->mfma);
     c->attn_indexed = attn_indexes;
-    // the staging launch then has few blocks and carries the tables to the device itself
-    const bool stage_uploads = fused && attn_indexes && c->h_stage_dev;
-    if (!stage_uploads) HIP_TRY(c, upload(c, slot, bytes, s));
+    // A single request (the latency case) sends its descriptor in the staging launch's arguments and that launch
+    // writes the tables on the device: nothing is uploaded.  Otherwise, when the staging launch has few blocks
+    // (no gather blocks) it carries the tables to the device itself.
+    const bool stage_fills = fused && n_req == 1;
+    const bool stage_uploads = fused && !stage_fills && attn_indexes && c->h_stage_dev;
+    OneFill fill{};
+    if (stage_fills) {
+        fill.rd = hd[0];
+        fill.td = TopkDesc{reqs[0].logits_out, reqs[0].n_cand};
+        fill.reqs = (ReqDesc *)d;
+        fill.blk_req = (int32_t *)(d + ((char *)hb - h));
+        fill.blk_slot = (int32_t *)(d + ((char *)hs - h));
+        fill.slot_req = (int32_t *)(d + ((char *)hq - h));
+        fill.groups = (AttnGroup *)(d + goff);
+        fill.topk = k > 0 ? (TopkDesc *)(d + toff) : nullptr;
+        fill.n_blk = b.n_blk;
+        fill.n_groups = b.n_groups;
+        fill.tiles = (reqs[0].n_cand + 31) / 32;
+    }
+    if (!stage_uploads && !stage_fills) HIP_TRY(c, upload(c, slot, bytes, s));
 
     hipEvent_t *pe = nullptr;
     if (c->prof_on && c->prof_batch_calls < c->prof_max && c->prof_seen_batch++ % c->prof_every == 0)
@@ -508,7 +503,7 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         }
         HIP_TRY(c, launch_stage(m, b, c->table, c->X.p, (int32_t *)c->bad.p, (const float *)c->w1u.p,
                                 c->has_bias[0] ? (const float *)c->bias[0].p : nullptr, (float *)c->bias1.p, c->mfma,
-                                !attn_indexes, s, stage_uploads ? &up : nullptr));
+                                !attn_indexes, s, stage_uploads ? &up : nullptr, stage_fills ? &fill : nullptr));
         HIP_TRY(c, mark(1));
     } else {
         if (!attn_indexes) HIP_TRY(c, launch_gather(m, b, c->table, c->X.p, (int32_t *)c->bad.p, s));
@@ -606,7 +601,8 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
     AttnGroup tmp[STATIC_MAX_GROUPS];
     if (c->mfma.attn && attn_max_groups((size_t)rows, 1) > (size_t)STATIC_MAX_GROUPS)
         return fail(c, AIF_ERANGE, "n_cand %d: more attention groups than the static call holds (%d)", q.n_cand, STATIC_MAX_GROUPS);
-    const int n_groups = c->mfma.attn ? attn_plan_groups(m, &rd, 1, c->n_cu, tmp) : 0;
+    int n_streamed = 0;
+    const int n_groups = c->mfma.attn ? attn_plan_groups(m, &rd, 1, c->n_cu, tmp, &n_streamed) : 0;
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -634,7 +630,7 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
     hipStream_t s = (hipStream_t)hip_stream;
     unsigned char *base = c->scratch_dev;        // the device address, never the array's name
 
-    StaticFill f{};
+    OneFill f{};
     f.rd = rd;
     f.td = TopkDesc{q.logits_out, q.n_cand};
     f.reqs = (ReqDesc *)(base + o_req);
@@ -646,9 +642,12 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
     f.n_blk = n_blk;
     f.n_groups = n_groups;
     f.tiles = tiles;
-    const int fill_n = n_blk > n_groups ? n_blk : n_groups;
-    hipLaunchKernelGGL(k_static_fill, dim3((fill_n + 255) / 256), dim3(256), 0, s, f);
-    HIP_TRY(c, hipGetLastError());
+    f.topk = k > 0 ? f.topk : nullptr;
+    const bool fused = stage_fusable(m, c->mfma);
+    if (!fused) {                                // else the staging launch writes the tables
+        hipLaunchKernelGGL(k_static_fill, dim3((one_fill_items(f) + 255) / 256), dim3(256), 0, s, f);
+        HIP_TRY(c, hipGetLastError());
+    }
 
     Batch b{};
     b.reqs = f.reqs;
@@ -659,6 +658,7 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
     b.n_req = 1;
     b.n_blk = n_blk;
     b.n_groups = n_groups;
+    b.n_streamed = n_streamed;
     b.n_slots = 1;
     MfmaPlan plan = c->mfma;                     // the context's packed weights, this call's buffers
     plan.kmax = (float *)(base + o_kmax);
@@ -672,11 +672,10 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
 
     c->row_base.clear();                         // aif_peek_features has nothing to show for this call
     c->last_slots = 1;
-    const bool fused = stage_fusable(m, plan);
     const bool attn_indexes = plan.attn && !c->separate_gather && attn_gathers(m, b, plan);
     c->attn_indexed = attn_indexes;
     if (fused) {
-        HIP_TRY(c, launch_stage(m, b, c->table, X, bad, (const float *)c->w1u.p, b1, bias1, plan, !attn_indexes, s, nullptr));
+        HIP_TRY(c, launch_stage(m, b, c->table, X, bad, (const float *)c->w1u.p, b1, bias1, plan, !attn_indexes, s, nullptr, &f));
     } else {
         if (!attn_indexes) HIP_TRY(c, launch_gather(m, b, c->table, X, bad, s));
         HIP_TRY(c, launch_user_fold(m, b, (const float *)c->w1u.p, b1, bias1, s));

@@ -44,6 +44,7 @@ struct Batch {
     int32_t n_req;
     int32_t n_blk;
     int32_t n_groups;
+    int32_t n_streamed;         // requests left to the streaming attention kernels (K/V too long for the resident one)
     int32_t n_slots;            // distinct users of the call: the user-side staging (fold, K/V packing) runs once per slot
 };
 __device__ __forceinline__ int slot_request(const Batch &b, int slot) { return b.slot_req ? b.slot_req[slot] : slot; }

@@ -253,7 +253,8 @@ aif_status aif_user_precompute(aif_user_ctx *c, const aif_user_request *users, i
     b.slot_req = nullptr;                   // slot s = request s
     b.n_blk = rows / ROW_BLOCK;
     const size_t goff = ((size_t)n_users * (sizeof(ReqDesc) + sizeof(UserDesc)) + (size_t)b.n_blk * sizeof(int32_t) + 15) / 16 * 16;
-    b.n_groups = c->mfma.attn ? attn_plan_groups(m, hr, n_users, c->n_cu, (AttnGroup *)(h + goff)) : 0;
+    b.n_streamed = 0;
+    b.n_groups = c->mfma.attn ? attn_plan_groups(m, hr, n_users, c->n_cu, (AttnGroup *)(h + goff), &b.n_streamed) : 0;
     b.groups = (const AttnGroup *)(d + goff);
     USER_TRY(c, staging_upload(c->h_stage, c->h_stage_dev, (size_t)slot * c->slot_bytes, d,
                                goff + (size_t)b.n_groups * sizeof(AttnGroup), s));

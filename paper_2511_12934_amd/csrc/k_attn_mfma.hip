@@ -24,6 +24,7 @@
 // is large enough to risk underflow (exponent range wider than 2^-80) the wave
 // first takes the true maximum in an extra pass over K.  Both are the exact
 // softmax up to rounding.
+#include <cstdlib>
 #include <type_traits>
 
 #include "k_mfma.h"
@@ -88,6 +89,23 @@ __device__ __forceinline__ uint16_t bea_a_element(const uint16_t *V, const Model
 }
 constexpr float BOUND_LIMIT = 40.f;      // exponents stay within [-80, 0]
 
+// The streaming kernels sum a candidate's keys in KEY_PARTS runs of whole 64-key stages, run q = stages
+// [q nst / KEY_PARTS, (q + 1) nst / KEY_PARTS), each run from zero, and add the runs' sums in the order of q.
+// One wave walking all runs in turn (k_attn_mfma) and one wave per run (k_attn_split, for batches too small
+// to fill the chip with a wave per 32 candidates) therefore give the same bits.
+constexpr int KEY_PARTS = 8;
+__host__ __device__ inline int key_part_begin(int q, int nst) { return q * nst / KEY_PARTS; }
+
+// Whether a request's packed K/V of all heads fit in the LDS the resident kernel keeps them in.  A request is
+// served by the resident kernel exactly when this holds (and the model has a resident kernel at all: the batch
+// then has tile groups), whatever else is in the batch -- its bits do not depend on the company.
+constexpr int RES_LDS_FRAGS = 152;            // 1 KB fragments of K/V that may stay resident
+__host__ __device__ inline bool res_fits(const Model &m, int seq_len)
+{
+    const int nkt2 = ((((seq_len + 31) >> 5) + 1) & ~1);
+    return (long)m.n_heads * nkt2 * (m.d_head / 8) <= RES_LDS_FRAGS;
+}
+
 // Copy NFRAG fragments of 1 KB global -> LDS; every wave moves NFRAG / WAVES of them.
 template <int NFRAG, int WAVES>
 __device__ __forceinline__ void stage_frags(const char *__restrict__ src, uint32_t lds_dst)
@@ -107,7 +125,7 @@ template <int DH>
 __global__ __launch_bounds__(256) void k_pack_kv(Model m, Batch b, char *__restrict__ kvpack, size_t pack_stride,
                                                  float *__restrict__ kmax_part, int nktp)
 {
-    pack_kv_block<DH>(blockIdx.z, blockIdx.y, blockIdx.x, m, b, kvpack, pack_stride, kmax_part, nktp);
+    pack_kv_block<DH>(blockIdx.z, blockIdx.y, blockIdx.x, m, TableReqs{b}, kvpack, pack_stride, kmax_part, nktp);
 }
 
 // ---------------------------------------------------------------------------
@@ -144,6 +162,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
     const ReqDesc rd = b.reqs[r];
     const int local0 = row0 - rd.row_base;
     if (rd.n_cand - local0 <= 0) return;
+    if (b.n_groups > 0 && res_fits(m, rd.seq_len)) return;      // the resident kernel's
 
     const int L = rd.seq_len, H = m.n_heads;
     const int nkt = (L + 31) >> 5, nst = (nkt + 1) >> 1, total = H * nst;
@@ -211,17 +230,34 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
             if (need_max) mc = c * mx;
         }
 
-        f32x16 O[FT];
+        // O, l: the current run of key tiles; Ot, lt: the runs before it (KEY_PARTS)
+        f32x16 O[FT], Ot[FT];
 #pragma unroll
         for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) O[ft][i] = 0.f;
-        float l = 0.f;
+            for (int i = 0; i < 16; ++i) O[ft][i] = Ot[ft][i] = 0.f;
+        float l = 0.f, lt = 0.f;
+        int qn = 1, bnd = key_part_begin(1, nst);          // the next run and its first stage
+        auto fold = [&]() {
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    Ot[ft][i] += O[ft][i];
+                    O[ft][i] = 0.f;
+                }
+            lt += l;
+            l = 0.f;
+        };
 
         for (int st = 0; st < nst; ++st) {
             // stage it + DIST goes into the slot stage it - 1 was read from
             if (it + DIST < total) stage_frags<2 * FR, WAVES>(stage_src(it + DIST), ring + ((it + DIST) % SLOTS) * STAGE_BYTES);
             const int buf = it % SLOTS;
+            while (st == bnd) {                             // a run ends here (empty runs: several)
+                fold();
+                bnd = key_part_begin(++qn, nst);
+            }
 #pragma unroll
             for (int k2 = 0; k2 < 2; ++k2) {
                 const int kt = 2 * st + k2;
@@ -271,9 +307,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
             __syncthreads();
             ++it;
         }
+        for (; qn <= KEY_PARTS; ++qn) fold();               // the last run, and the empty ones before it
 
-        l += __shfl_xor(l, 32, 64);
-        const float inv = L > 0 ? 1.0f / l : 0.f;
+        lt += __shfl_xor(lt, 32, 64);
+        const float inv = L > 0 ? 1.0f / lt : 0.f;
         if (live) {
 #pragma unroll
             for (int ft = 0; ft < FT; ++ft)
@@ -281,7 +318,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
                 for (int qd = 0; qd < 4; ++qd) {
                     bf16x4 o4;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(O[ft][4 * qd + i] * inv);
+                    for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(Ot[ft][4 * qd + i] * inv);
                     // features 8 qd + 4 h + i of this tile: half h of one piece
                     store_stream((bf16x4 *)piece((m.d_item + hd * DH) / 8 + 4 * ft + qd) + h, o4);
                 }
@@ -329,6 +366,255 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
 }
 
 // ---------------------------------------------------------------------------
+// The streaming computation for a batch too small to give every SIMD a wave at 32 candidates a wave (one
+// request of 10^4 candidates is 313 such waves for 1,024 SIMDs, each walking the whole sequence: a chain of
+// a few hundred cycles per key tile with nobody to share the SIMD).  Here a workgroup is ONE 32-candidate
+// tile and its KEY_PARTS waves take a run of 64-key stages each (the runs of k_attn_mfma), so the chain is an
+// eighth as long; the runs' sums meet in LDS and are added in the order of the runs -- the order in which
+// k_attn_mfma adds them, so the bits are the same.  A lone wave shares its K/V with nobody: fragments come
+// straight from memory (the L2s: every workgroup reads the same pack) into registers, three tiles in
+// rotation, two in flight.  Inside a tile the S product of the next tile alternates with this tile's
+// exponentials in the instruction stream, as in the resident kernel.
+// ---------------------------------------------------------------------------
+template <int DH> constexpr int split_lds_bytes() { return KEY_PARTS * (DH / 32 * 16 + 1) * 64 * 4; }
+
+template <int DH>
+__global__ __launch_bounds__(KEY_PARTS * 64) void k_attn_split(Model m, Batch b, char *__restrict__ X, XLayout xl,
+                                                              const char *__restrict__ kvpack, size_t pack_stride,
+                                                              const float *__restrict__ kmax, int nktp)
+{
+    constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32, NREG = FT * 16, NQ = KEY_PARTS;
+    extern __shared__ __align__(16) char lds[];
+    float *part = (float *)lds;                        // [run][register (NREG of O, then l)][lane]
+
+    const int tile = blockIdx.x, row0 = tile * 32;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), col = lane & 31, h = lane >> 5;
+    char *xrow = X + x_offset(xl, row0 + col, 0);
+    auto piece = [&](int p) { return (bf16x8 *)(xrow + (size_t)p * xl.piece_stride); };
+    bf16x8 q[JS];                                      // asked for before the request is looked up, as in k_attn_mfma
+#pragma unroll
+    for (int j = 0; j < JS; ++j) q[j] = *piece(2 * j + h);
+
+    const int r = b.blk_req[row0 / ROW_BLOCK];
+    if (r < 0) return;
+    const ReqDesc rd = b.reqs[r];
+    const int local0 = row0 - rd.row_base;
+    if (rd.n_cand - local0 <= 0) return;
+    if (b.n_groups > 0 && res_fits(m, rd.seq_len)) return;      // the resident kernel's
+
+    const int L = rd.seq_len, H = m.n_heads;
+    const int nkt = (L + 31) >> 5, nst = (nkt + 1) >> 1;
+    const int us = rd.slot;
+    const char *pk = kvpack + (size_t)us * pack_stride + lane * 16;
+    const bool live = local0 + col < rd.n_cand;
+    const float c = LOG2E / sqrtf((float)DH);
+    // this wave's run, in tiles: whole stages of two (the last one of an odd sequence ends in the pack's empty tile)
+    const int kt0 = 2 * key_part_begin(wave, nst), kt1 = 2 * key_part_begin(wave + 1, nst);
+
+    for (int hd = 0; hd < H; ++hd) {
+        if (hd > 0) {
+#pragma unroll
+            for (int j = 0; j < JS; ++j) q[j] = *piece(hd * (DH / 8) + 2 * j + h);
+        }
+        const char *kvh = pk + (size_t)hd * nktp * FR * 1024;           // fragment i of tile t: kvh + (t FR + i) KB
+        // two sets of K fragments and two of V fragments take turns: while tile t's V and tile t + 1's K are in use,
+        // tile t + 1's V and tile t + 2's K are in flight.  A tile index past the run re-reads the run's last tile
+        // (fetched, not used), so the loop body has no conditions.
+        const int ktl = kt1 > kt0 ? kt1 - 1 : 0;
+        auto tile_src = [&](int kt) { return kvh + (size_t)(kt < ktl ? kt : ktl) * FR * 1024; };
+        auto fetch_k = [&](bf16x8(&f)[JS], int kt) {
+            const char *src = tile_src(kt);
+#pragma unroll
+            for (int i = 0; i < JS; ++i) f[i] = *(const bf16x8 *)(src + i * 1024);
+        };
+        auto fetch_v = [&](bf16x8(&f)[2 * FT], int kt) {
+            const char *src = tile_src(kt) + JS * 1024;
+#pragma unroll
+            for (int i = 0; i < 2 * FT; ++i) f[i] = *(const bf16x8 *)(src + i * 1024);
+        };
+        // (the run's first K has a set of its own: a set that is both used and refilled ahead of the loop reaches the
+        // loop through a register copy, and a copy of a register that a load is still filling waits for that load)
+        bf16x8 k0[JS], ka[JS], kb[JS], va[2 * FT], vb[2 * FT];
+        if (nkt > 0) {
+            fetch_k(k0, kt0);
+            fetch_k(kb, kt0 + 1);
+            fetch_v(va, kt0);
+            fetch_k(ka, kt0 + 2);
+            fetch_v(vb, kt0 + 1);
+        }
+        float km = 0.f;                     // the key-norm bounds ride behind the fragments: one wait for all
+        for (int i = lane; i < nst; i += 64) km = fmaxf(km, kmax[((size_t)us * H + hd) * (nktp / 2) + i]);
+
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < JS; ++j) ss = dot8(q[j], q[j], ss);
+        ss += __shfl_xor(ss, 32, 64);
+#pragma unroll
+        for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
+        float mc = c * sqrtf(ss) * 1.001f * km;
+        const bool need_max = live && mc > BOUND_LIMIT;      // per candidate, as in k_attn_mfma
+        if (__any(need_max)) {
+            // rare: the true maximum, by an extra pass over all of K in every wave (the maximum has no order)
+            float mx = -INFINITY;
+            for (int kt = 0; kt < nkt; ++kt) {
+                const char *src = kvh + (size_t)kt * FR * 1024;
+                f32x16 S;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) S[i] = 0.f;
+#pragma unroll
+                for (int j = 0; j < JS; ++j)
+                    S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(src + j * 1024), q[j], S, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (t < L) mx = fmaxf(mx, S[v]);
+                }
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            if (need_max) mc = c * mx;
+        }
+
+        f32x16 O[FT];
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[ft][i] = 0.f;
+        float l = 0.f;
+        if (kt1 > kt0) {
+            f32x16 S;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) S[i] = 0.f;
+#pragma unroll
+            for (int j = 0; j < JS; ++j) S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0[j], q[j], S, 0, 0, 0);
+            // tile kt: exponentials of S (its scores), second product with vc (its V); meanwhile the S product of tile
+            // kt + 1 from kn (after the run's last tile: of that tile again, unused); both sets are refilled, two tiles on
+            auto body = [&](bf16x8(&vc)[2 * FT], bf16x8(&kn)[JS], int kt) {
+                f32x16 Sn;
+                float p[16];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < JS; ++j) {
+                    if (j == 0) {
+                        f32x16 Z;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) Z[i] = 0.f;
+                        Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kn[0], q[0], Z, 0, 0, 0);
+                    } else
+                        Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kn[j], q[j], Sn, 0, 0, 0);
+#pragma unroll
+                    for (int v = 16 / JS * j; v < 16 / JS * (j + 1); ++v) {
+                        p[v] = __builtin_amdgcn_exp2f(fmaf(S[v], c, -mc));
+                        asm volatile("" : "+v"(p[v]));      // computed HERE: a value with no side effect would sink to its first use
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                fetch_k(kn, kt + 3);
+                if (32 * kt + 32 > L) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
+                        if (t >= L) p[v] = 0.f;
+                    }
+                }
+                bf16x8 P0, P1;
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    P0[v] = (__bf16)p[v];
+                    P1[v] = (__bf16)p[8 + v];
+                }
+                l = sum_pairs<0, 4>(P0, l);                 // the weights as rounded, P0's pairs then P1's
+                l = sum_pairs<0, 4>(P1, l);
+#pragma unroll
+                for (int ft = 0; ft < FT; ++ft) {
+                    O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vc[ft], P0, O[ft], 0, 0, 0);
+                    O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vc[FT + ft], P1, O[ft], 0, 0, 0);
+                }
+                // the refill stays BEHIND the last use of the set (a load moved above it would need registers of its
+                // own, and the copy back at the loop's end would wait for every load in flight)
+                __builtin_amdgcn_sched_barrier(0);
+                fetch_v(vc, kt + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                S = Sn;
+            };
+            for (int kt = kt0; kt < kt1; kt += 2) {
+                body(va, kb, kt);
+                body(vb, ka, kt + 1);
+            }
+        }
+
+        // the runs' sums meet in LDS ...
+        if (hd > 0) __syncthreads();                        // the previous head's sums have been read
+        float *mine = part + (size_t)wave * (NREG + 1) * 64 + lane;
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mine[(ft * 16 + i) * 64] = O[ft][i];
+        mine[NREG * 64] = l;
+        __syncthreads();
+        // ... and are added in the order of the runs, from zero; wave w normalises and stores quads w, w + NQ, ...
+        float lt = 0.f;
+#pragma unroll
+        for (int qn = 0; qn < NQ; ++qn) lt += part[((size_t)qn * (NREG + 1) + NREG) * 64 + lane];
+        lt += __shfl_xor(lt, 32, 64);
+        const float inv = L > 0 ? 1.0f / lt : 0.f;
+        for (int g = wave; g < FT * 4; g += NQ) {
+            float t[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int qn = 0; qn < NQ; ++qn)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) t[i] += part[((size_t)qn * (NREG + 1) + 4 * g + i) * 64 + lane];
+            if (live) {
+                bf16x4 o4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(t[i] * inv);
+                // register 4 g + i = feature tile g / 4, quad g % 4: features 8 (g % 4) + 4 h + i of that tile
+                store_stream((bf16x4 *)piece((m.d_item + hd * DH) / 8 + g) + h, o4);
+            }
+        }
+    }
+
+    // the real-time half of the cross features, as in k_attn_mfma; the waves share the pieces / feature tiles
+    if (m.cross_mode == 1 && !m.cross_in_mlp && live) {
+        const bf16x8 *uc = (const bf16x8 *)rd.cross_vecs;
+        const int pc0 = (m.d_item + m.d_attn) / 8;
+        for (int pc = 2 * wave + h; pc < m.d_item / 8; pc += 2 * NQ) {
+            const bf16x8 e = *piece(pc), u = uc[pc];
+            bf16x8 o8;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) o8[s] = (__bf16)((float)e[s] * (float)u[s]);
+            store_stream(piece(pc0 + pc), o8);
+        }
+    }
+    if (m.cross_mode == 3) {
+        const BeaGeom g = bea_geom(m);
+        const uint16_t *Vu = (const uint16_t *)rd.cross_vecs;
+        const int pc0 = (m.d_item + m.d_attn) / 8;
+        for (int ft = wave; ft < g.ftc; ft += NQ) {
+            f32x16 Cc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) Cc[i] = 0.f;
+            for (int ks = 0; ks < g.ksb; ++ks) {
+                uint16_t a8[8];
+#pragma unroll
+                for (int sl = 0; sl < 8; ++sl) a8[sl] = bea_a_element(Vu, m, g, ks, ft, lane, sl);
+                bf16x8 A;
+                __builtin_memcpy(&A, a8, 16);
+                Cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A, *piece(g.piece0 + 2 * ks + h), Cc, 0, 0, 0);
+            }
+            if (live) {
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o4[i] = (__bf16)Cc[4 * qd + i];
+                    store_stream((bf16x4 *)piece(pc0 + 4 * ft + qd) + h, o4);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // The same computation with the request's K/V RESIDENT in LDS.  All candidates of
 // a request share its behaviour sequence (Sec. 3.1), so when the packed K/V of all
 // heads fit in one CU's LDS a workgroup loads them once and then serves a whole
@@ -346,7 +632,6 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
 // kernel's read of it fall away.  An id outside the table reads row 0 and is counted, as in the gather kernel.
 // ---------------------------------------------------------------------------
 constexpr int RES_WAVES = 12;
-constexpr int RES_LDS_FRAGS = 152;            // 1 KB fragments of K/V that may stay resident
 constexpr int RES_MAX_HEADS = 64;
 constexpr int RES_MAX_ITEM_PIECES = 256;      // d_item / 8 the Hadamard operand may have to stay in LDS
 constexpr int RES_LDS_BYTES = RES_LDS_FRAGS * 1024 + RES_MAX_HEADS * 4 + RES_MAX_ITEM_PIECES * 16 + 16;
@@ -706,20 +991,20 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     }
 }
 
-// Host: groups of tiles for k_attn_res, or 0 when some request's K/V do not fit.
+// Host: groups of tiles for k_attn_res -- of the requests whose K/V fit; *n_streamed = the requests left to the
+// streaming kernels (those that do not fit; all, when the model has no resident kernel).
 size_t attn_max_groups(size_t x_rows, int max_users) { return x_rows / (32 * RES_WAVES) + (size_t)max_users + 1; }
 
-int attn_plan_groups(const Model &m, const ReqDesc *reqs, int n_req, int n_cu, AttnGroup *out)
+int attn_plan_groups(const Model &m, const ReqDesc *reqs, int n_req, int n_cu, AttnGroup *out, int *n_streamed)
 {
+    *n_streamed = 0;
+    for (int r = 0; r < n_req; ++r) *n_streamed += reqs[r].n_cand > 0;
     if (m.n_heads > RES_MAX_HEADS || m.d_item / 8 > RES_MAX_ITEM_PIECES) return 0;
     if (m.d_head != 64 && m.d_head != 32) return 0;       // the resident kernel has these two head widths
-    const int FR = m.d_head / 8;
     long total = 0;
-    for (int r = 0; r < n_req; ++r) {
-        const int nkt2 = ((((reqs[r].seq_len + 31) >> 5) + 1) & ~1);
-        if ((long)m.n_heads * nkt2 * FR > RES_LDS_FRAGS) return 0;
-        total += (reqs[r].n_cand + 31) / 32;
-    }
+    for (int r = 0; r < n_req; ++r)
+        if (res_fits(m, reqs[r].seq_len)) total += (reqs[r].n_cand + 31) / 32;
+    if (total == 0) return 0;
     // about one group per CU, each a whole number of rounds of the 16 waves
     long per = (total + n_cu - 1) / n_cu;
     per = (per + RES_WAVES - 1) / RES_WAVES * RES_WAVES;
@@ -727,7 +1012,8 @@ int attn_plan_groups(const Model &m, const ReqDesc *reqs, int n_req, int n_cu, A
     int n = 0;
     for (int r = 0; r < n_req; ++r) {
         const int tiles = (reqs[r].n_cand + 31) / 32;
-        if (tiles == 0) continue;
+        if (tiles == 0 || !res_fits(m, reqs[r].seq_len)) continue;
+        --*n_streamed;
         const int ng = (int)((tiles + per - 1) / per);
         for (int i = 0; i < ng; ++i)          // even split: sizes differ by at most one tile
             out[n++] = AttnGroup{r, (int)((long)tiles * i / ng), (int)((long)tiles * (i + 1) / ng), 0};
@@ -759,43 +1045,7 @@ size_t attn_pack_stride(const Model &m, int max_seq_len, int *nktp_out)
     return (size_t)m.n_heads * nktp * (m.d_head / 8) * 1024;
 }
 
-template <int DH, int WAVES>
-static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char *kvpack, size_t stride, float *kmax,
-                                   int nktp, bool kv_packed, const void *gather_table, int32_t *bad, hipStream_t s)
-{
-    constexpr int LDS = 4 * 2 * (DH / 8) * 1024, ROWS = WAVES * 32;
-    if (nktp > 0 && !kv_packed)
-        hipLaunchKernelGGL(k_pack_kv<DH>, dim3(nktp / 2, m.n_heads, b.n_slots), dim3(256), 0, s, m, b, kvpack, stride, kmax, nktp);
-    if (b.n_groups > 0) {
-        constexpr int RES_LDS = RES_LDS_BYTES;
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute((const void *)k_attn_res<DH, false>, hipFuncAttributeMaxDynamicSharedMemorySize, RES_LDS);
-            if (e == hipSuccess)
-                e = hipFuncSetAttribute((const void *)k_attn_res<DH, true>, hipFuncAttributeMaxDynamicSharedMemorySize, RES_LDS);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
-        if (gather_table)
-            hipLaunchKernelGGL((k_attn_res<DH, true>), dim3(b.n_groups), dim3(RES_WAVES * 64), RES_LDS, s, m, b, (char *)X,
-                               x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp,
-                               (const char *)gather_table, bad);
-        else
-            hipLaunchKernelGGL((k_attn_res<DH, false>), dim3(b.n_groups), dim3(RES_WAVES * 64), RES_LDS, s, m, b, (char *)X,
-                               x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp, (const char *)nullptr,
-                               (int32_t *)nullptr);
-        return hipGetLastError();
-    }
-    if (gather_table) return hipErrorInvalidValue;      // only the resident kernel gathers: the caller asked attn_gathers()
-    hipLaunchKernelGGL((k_attn_mfma<DH, WAVES>), dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), LDS, s, m, b,
-                       (char *)X, x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp);
-    return hipGetLastError();
-}
-
-// A batch too small to give every compute unit an eight-wave block of the streaming kernel (a single
-// 10^4-candidate request is 40 of them) is cut into two-wave blocks instead: same arithmetic per candidate,
-// four times as many compute units at work.
-static bool small_batch(const Batch &b)
+static int n_compute_units()
 {
     static int n_cu = 0;
     if (!n_cu) {
@@ -804,7 +1054,73 @@ static bool small_batch(const Batch &b)
         n_cu = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
                    ? prop.multiProcessorCount : 256;
     }
-    return b.n_blk < n_cu;
+    return n_cu;
+}
+
+// Up to this many 32-candidate tiles in the batch the key-split kernel serves the streamed requests
+// (eight waves a tile: beyond two tiles per compute unit the SIMDs are full without it).
+static int split_max_tiles()
+{
+    static int n = -1;
+    if (n < 0) {
+        const char *e = getenv("AIF_SPLIT_TILES");      // measurement: where the key-split kernel stops paying
+        n = e ? atoi(e) : 2 * n_compute_units();
+    }
+    return n;
+}
+
+// A batch too small to give every compute unit an eight-wave block of the streaming kernels (a single
+// 10^4-candidate request is 40 of them) is cut finer: same arithmetic per candidate, more compute units at work.
+static bool small_batch(const Batch &b) { return b.n_blk < n_compute_units(); }
+
+template <int DH, int WAVES>
+static void launch_streaming(const Model &m, const Batch &b, void *X, char *kvpack, size_t stride, float *kmax, int nktp, hipStream_t s)
+{
+    constexpr int LDS = 4 * 2 * (DH / 8) * 1024, ROWS = WAVES * 32;
+    hipLaunchKernelGGL((k_attn_mfma<DH, WAVES>), dim3(b.n_blk * (ROW_BLOCK / ROWS)), dim3(WAVES * 64), LDS, s, m, b,
+                       (char *)X, x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp);
+}
+
+template <int DH>
+static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char *kvpack, size_t stride, float *kmax,
+                                   int nktp, bool kv_packed, const void *gather_table, int32_t *bad, hipStream_t s)
+{
+    if (nktp > 0 && !kv_packed)
+        hipLaunchKernelGGL(k_pack_kv<DH>, dim3(nktp / 2, m.n_heads, b.n_slots), dim3(256), 0, s, m, b, kvpack, stride, kmax, nktp);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)k_attn_res<DH, false>, hipFuncAttributeMaxDynamicSharedMemorySize, RES_LDS_BYTES);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)k_attn_res<DH, true>, hipFuncAttributeMaxDynamicSharedMemorySize, RES_LDS_BYTES);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)k_attn_split<DH>, hipFuncAttributeMaxDynamicSharedMemorySize, split_lds_bytes<DH>());
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    // the requests whose K/V fit in LDS: the resident kernel
+    if (b.n_groups > 0) {
+        if (gather_table)
+            hipLaunchKernelGGL((k_attn_res<DH, true>), dim3(b.n_groups), dim3(RES_WAVES * 64), RES_LDS_BYTES, s, m, b, (char *)X,
+                               x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp,
+                               (const char *)gather_table, bad);
+        else
+            hipLaunchKernelGGL((k_attn_res<DH, false>), dim3(b.n_groups), dim3(RES_WAVES * 64), RES_LDS_BYTES, s, m, b, (char *)X,
+                               x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp, (const char *)nullptr,
+                               (int32_t *)nullptr);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess || b.n_streamed == 0) return e;
+    }
+    // the others: the streaming kernels (their blocks leave the resident kernel's requests alone)
+    if (gather_table) return hipErrorInvalidValue;      // only the resident kernel gathers: the caller asked attn_gathers()
+    const int tiles = b.n_blk * (ROW_BLOCK / 32);
+    if (tiles <= split_max_tiles())
+        hipLaunchKernelGGL((k_attn_split<DH>), dim3(tiles), dim3(KEY_PARTS * 64), split_lds_bytes<DH>(), s, m, b, (char *)X,
+                           x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp);
+    else if (small_batch(b))
+        launch_streaming<DH, 2>(m, b, X, kvpack, stride, kmax, nktp, s);
+    else
+        launch_streaming<DH, 8>(m, b, X, kvpack, stride, kmax, nktp, s);
+    return hipGetLastError();
 }
 
 // Whether the attention launch of this batch also indexes the item table: k_attn_res with GATHER (no W_q, the
@@ -813,7 +1129,7 @@ bool attn_gathers(const Model &m, const Batch &b, const MfmaPlan &plan)
 {
     if (m.dtype != 1 || !plan.attn || b.n_blk == 0) return false;
     if (plan.attn_variant == ATTN_VARIANT_PROJ) return true;
-    return (plan.attn_variant == 0 || plan.attn_variant == 1) && b.n_groups > 0;
+    return (plan.attn_variant == 0 || plan.attn_variant == 1) && b.n_groups > 0 && b.n_streamed == 0;
 }
 
 hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed,
@@ -826,12 +1142,8 @@ hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const Mf
     const int nktp = plan.nktp;
     switch (plan.attn_variant) {
     case ATTN_VARIANT_PROJ: return launch_attn_proj(m, b, X, plan, small_batch(b), s, gather_table, bad);
-    case 0:
-        return small_batch(b) ? launch_attn_spec<64, 2>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s)
-                              : launch_attn_spec<64, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s);
-    case 1:
-        return small_batch(b) ? launch_attn_spec<32, 2>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s)
-                              : launch_attn_spec<32, 8>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s);
+    case 0: return launch_attn_spec<64>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s);
+    case 1: return launch_attn_spec<32>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void k_gather(const uint4 *__restrict__ table,
                                                 Batch b, char *__restrict__ X, XLayout xl,
                                                 int32_t *__restrict__ bad)
 {
-    gather_block<LOG_RV>(blockIdx.x, table, n_items, row_vec, b, X, xl, bad);
+    gather_block<LOG_RV>(blockIdx.x, table, n_items, row_vec, TableReqs{b}, X, xl, bad);
 }
 
 // the workspace in fragment order: through LDS (gather_block_tiled)
@@ -27,7 +27,7 @@ template <int LOG_RV>
 __global__ __launch_bounds__(256) void k_gather_tiled(const uint4 *__restrict__ table, int64_t n_items, Batch b,
                                                       char *__restrict__ X, XLayout xl, int32_t *__restrict__ bad)
 {
-    gather_block_tiled<LOG_RV>(blockIdx.x, table, n_items, b, X, xl, bad);
+    gather_block_tiled<LOG_RV>(blockIdx.x, table, n_items, TableReqs{b}, X, xl, bad);
 }
 
 hipError_t launch_gather(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad,

@@ -30,7 +30,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_user_fold(Model m, Batch b, const float *__restrict__ w1u,
                                                    const float *__restrict__ b1, float *__restrict__ bias1)
 {
-    user_fold_block<T>(blockIdx.y, blockIdx.x, m, b, w1u, b1, bias1);
+    user_fold_block<T>(blockIdx.y, blockIdx.x, m, TableReqs{b}, w1u, b1, bias1);
 }
 
 hipError_t launch_user_fold(const Model &m, const Batch &b, const float *w1u, const float *b1, float *bias1,

@@ -33,11 +33,13 @@ hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, size_t x_ro
                      MfmaPlan &plan, hipStream_t s);
 void mfma_release(MfmaPlan &plan);
 
-// Host side: can every request of the batch keep its packed K/V (all heads) in one CU's LDS?  If so,
-// cut the requests into groups of tiles for the resident attention kernel (about one group per CU and
-// round of 16 waves) and return their number; 0 if some request does not fit (the streaming kernel
-// serves the batch then).  `out` has room for attn_max_groups() entries.
-int attn_plan_groups(const Model &m, const ReqDesc *reqs /*host*/, int n_req, int n_cu, AttnGroup *out /*host*/);
+// Host side: which attention kernel serves which request.  A request whose packed K/V (all heads) fit in one
+// CU's LDS goes to the resident kernel: such requests are cut into groups of tiles (about one group per CU, whole
+// rounds of the kernel's waves), written to `out` (room for attn_max_groups() entries), their number returned.
+// The others are the streaming kernels': *n_streamed says how many (requests with candidates).  The choice
+// depends on the request alone, so its result does not depend on what else is in the batch.
+int attn_plan_groups(const Model &m, const ReqDesc *reqs /*host*/, int n_req, int n_cu, AttnGroup *out /*host*/,
+                     int *n_streamed);
 size_t attn_max_groups(size_t x_rows, int max_users);
 
 // kv_packed: the batch's K/V are already in fragment order (launch_stage did it)
@@ -59,9 +61,13 @@ struct StageUpload {
     const ReqDesc *reqs_mapped;
     const int32_t *slot_req_mapped;     // the batch's slot_req table through the same mapping
 };
+// one (optional, a batch of one request, not with up): the request's descriptor travels in the kernel's arguments,
+// the launch's blocks read it there and its first blocks write the device tables of the batch (k_stage.h: OneFill),
+// so no upload of any kind precedes the launch.
+struct OneFill;
 hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad, const float *w1u,
                         const float *b1, float *bias1, const MfmaPlan &plan, bool gather, hipStream_t s,
-                        const StageUpload *up = nullptr);
+                        const StageUpload *up = nullptr, const OneFill *one = nullptr);
 
 // bias_f32[l] / wlast_f32: the context's fp32 copies (bias of layer l or null; last layer's weight row).
 hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const MfmaPlan &plan,

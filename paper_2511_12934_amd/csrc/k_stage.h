@@ -11,16 +11,59 @@ namespace aif {
 
 constexpr int GATHER_UNROLL = 4;
 
+// Where a staging block finds its request: in the batch's device tables, or -- a batch of ONE request -- in the
+// kernel's own arguments (the tables are then still on their way: the same launch writes them, one_fill).
+struct TableReqs {
+    const Batch &b;
+    __device__ __forceinline__ int block_request(int blk) const { return b.blk_req[blk]; }
+    __device__ __forceinline__ const ReqDesc &request(int r) const { return b.reqs[r]; }
+    __device__ __forceinline__ const ReqDesc &slot_desc(int slot) const { return b.reqs[slot_request(b, slot)]; }
+};
+struct OneReq {
+    const ReqDesc &rd;
+    __device__ __forceinline__ int block_request(int) const { return 0; }
+    __device__ __forceinline__ const ReqDesc &request(int) const { return rd; }
+    __device__ __forceinline__ const ReqDesc &slot_desc(int) const { return rd; }
+};
+
+// Descriptor tables of a one-request batch, written by the device itself from kernel arguments (no pinned staging,
+// no copy command, nothing to wait for on the host): the request, block -> request and block -> user slot (all 0),
+// the attention groups (an even split of the request's tiles, as attn_plan_groups cuts them) and the top-k descriptor.
+struct OneFill {
+    ReqDesc rd;
+    TopkDesc td;
+    ReqDesc *reqs;
+    int32_t *blk_req, *blk_slot, *slot_req;
+    AttnGroup *groups;
+    TopkDesc *topk;             // null: the call selects nothing
+    int32_t n_blk, n_groups, tiles;
+};
+__device__ __forceinline__ void one_fill(const OneFill &f, int i)
+{
+    if (i == 0) {
+        f.reqs[0] = f.rd;
+        f.slot_req[0] = 0;
+        if (f.topk) f.topk[0] = f.td;
+    }
+    if (i < f.n_blk) {
+        f.blk_req[i] = 0;
+        f.blk_slot[i] = 0;
+    }
+    if (i < f.n_groups)
+        f.groups[i] = AttnGroup{0, (int)((long)f.tiles * i / f.n_groups), (int)((long)f.tiles * (i + 1) / f.n_groups), 0};
+}
+__host__ __device__ inline int one_fill_items(const OneFill &f) { return f.n_blk > f.n_groups ? (f.n_blk > 1 ? f.n_blk : 1) : f.n_groups; }
+
 // a1 -- one ROW_BLOCK of the workspace: X[row, 0:d_item] = table[id].
 // LOG_RV >= 0: a row is 2^LOG_RV pieces of 16 bytes (shift instead of divide); LOG_RV < 0: any count.
-template <int LOG_RV>
+template <int LOG_RV, class Reqs>
 __device__ __forceinline__ void gather_block(int blk, const uint4 *__restrict__ table, int64_t n_items, int row_vec,
-                                             const Batch &b, char *__restrict__ X, const XLayout &xl,
+                                             const Reqs &src, char *__restrict__ X, const XLayout &xl,
                                              int32_t *__restrict__ bad)
 {
-    const int r = b.blk_req[blk];
+    const int r = src.block_request(blk);
     if (r < 0) return;
-    const ReqDesc *rd = b.reqs + r;
+    const ReqDesc *rd = &src.request(r);
     const int row_base = rd->row_base;
     const int local0 = blk * ROW_BLOCK - row_base;
     int nrows = rd->n_cand - local0;
@@ -73,9 +116,9 @@ __device__ __forceinline__ void gather_block(int blk, const uint4 *__restrict__ 
 // four independent loads per thread), sets them down in LDS in tile order, and writes the tiles' item
 // blocks as contiguous 16 KB-per-32-piece runs; the next trip's rows are already in flight during the
 // exchange, and the two LDS buffers take turns so one barrier per trip is enough.
-template <int LOG_RV>
+template <int LOG_RV, class Reqs>
 __device__ __forceinline__ void gather_block_tiled(int blk, const uint4 *__restrict__ table, int64_t n_items,
-                                                   const Batch &b, char *__restrict__ X, const XLayout &xl,
+                                                   const Reqs &src, char *__restrict__ X, const XLayout &xl,
                                                    int32_t *__restrict__ bad)
 {
     constexpr int RV = 1 << LOG_RV;                      // pieces per row: 8, 16 or 32
@@ -88,9 +131,9 @@ __device__ __forceinline__ void gather_block_tiled(int blk, const uint4 *__restr
     __shared__ __align__(16) char buf[NBUF * BUF];
     __shared__ int32_t sid[ROW_BLOCK];
 
-    const int r = b.blk_req[blk];
+    const int r = src.block_request(blk);
     if (r < 0) return;
-    const ReqDesc *rd = b.reqs + r;
+    const ReqDesc *rd = &src.request(r);
     const int row_base = rd->row_base;
     const int local0 = blk * ROW_BLOCK - row_base;
     int nrows = rd->n_cand - local0;
@@ -151,8 +194,8 @@ __device__ __forceinline__ void gather_block_tiled(int blk, const uint4 *__restr
 // loads, so the columns are cut into four runs, one per wave of the 256-thread block, eight loads in flight
 // each; the four partial sums are added in run order (a fixed order: the same bits in every call).
 constexpr int FOLD_FEATS = 64;
-template <typename T>
-__device__ __forceinline__ void user_fold_block(int slot, int part, const Model &m, const Batch &b,
+template <typename T, class Reqs>
+__device__ __forceinline__ void user_fold_block(int slot, int part, const Model &m, const Reqs &src,
                                                 const float *__restrict__ w1ut, const float *__restrict__ b1,
                                                 float *__restrict__ bias1)
 {
@@ -161,7 +204,7 @@ __device__ __forceinline__ void user_fold_block(int slot, int part, const Model 
     const int n = part * FOLD_FEATS + lane;
     const int h1 = m.dims[1];
     const bool on = n < h1;
-    const T *u = (const T *)b.reqs[slot_request(b, slot)].user_vec;
+    const T *u = (const T *)src.slot_desc(slot).user_vec;
     const int per = (m.d_user + 3) / 4, k0 = run * per, k1 = min(m.d_user, k0 + per);
     float acc = 0.f;
     if (on) {
@@ -185,13 +228,13 @@ __device__ __forceinline__ void user_fold_block(int slot, int part, const Model 
 // ((head * nktp + kt) * FR) KB:  JS K-fragments  [lane][s] = K[32kt + lane%32][o + 16j + 8(lane/32) + s]
 // then 2*FT V-fragments (jj, ft): [lane][s] = V[32kt + 16jj + 8(s/4) + 4(lane/32) + s%4][o + 32ft + lane%32]
 // with o = head * DH; keys >= seq_len read as zero.
-template <int DH>
-__device__ __forceinline__ void pack_kv_block(int slot, int hd, int st, const Model &m, const Batch &b,
+template <int DH, class Reqs>
+__device__ __forceinline__ void pack_kv_block(int slot, int hd, int st, const Model &m, const Reqs &src,
                                               char *__restrict__ kvpack, size_t pack_stride,
                                               float *__restrict__ kmax_part, int nktp)
 {
     constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32;
-    const ReqDesc *rd = b.reqs + slot_request(b, slot);
+    const ReqDesc *rd = &src.slot_desc(slot);
     const int L = rd->seq_len;
     const int nkt2 = (((L + 31) >> 5) + 1) & ~1;
     if (2 * st >= nkt2) return;

@@ -6,6 +6,9 @@
 // When the attention kernel that follows indexes the item table itself (k_attn_res with
 // GATHER) the grid has no gather blocks; its first blocks may then carry the call's descriptor
 // tables from pinned host memory to the device, which saves the upload its own launch.
+// A batch of ONE request (the latency case: Sec. 5.3 measures a single request) needs neither: the request's
+// descriptor arrives in the kernel's arguments, every block reads it there, and the first blocks write the
+// device tables the later kernels read.
 #include "k_mfma.h"
 #include "k_stage.h"
 
@@ -30,41 +33,71 @@ struct StageArgs {
     uint4 *up_dst;
     int32_t up_n16, n_up;           // 16-byte pieces; blocks of this job (0: the tables are on the device already)
 };
+struct StageOneArgs {
+    StageArgs a;                    // a.n_up = blocks that write the tables (one_fill), a.up_* unused
+    OneFill fill;
+};
 
-template <int LOG_RV, int DH>
-__global__ __launch_bounds__(256) void k_stage(StageArgs a)
+template <int LOG_RV, int DH, class Reqs>
+__device__ __forceinline__ void stage_block(const StageArgs &a, const Reqs &src, int idx)
 {
-    int idx = blockIdx.x;
-    if (idx < a.n_up) {
-        const int i = idx * 256 + (int)threadIdx.x;
-        if (i < a.up_n16) a.up_dst[i] = a.up_src[i];
-        return;
-    }
-    idx -= a.n_up;
     if (idx < a.n_pack) {
         const int st = idx % a.stages, rest = idx / a.stages;
-        pack_kv_block<DH>(rest / a.m.n_heads, rest % a.m.n_heads, st, a.m, a.b, a.kvpack, a.pack_stride, a.kmax, a.nktp);
+        pack_kv_block<DH>(rest / a.m.n_heads, rest % a.m.n_heads, st, a.m, src, a.kvpack, a.pack_stride, a.kmax, a.nktp);
         return;
     }
     idx -= a.n_pack;
     if (idx < a.n_fold) {
-        user_fold_block<uint16_t>(idx / a.quads, idx % a.quads, a.m, a.b, a.w1u, a.b1, a.bias1);
+        user_fold_block<uint16_t>(idx / a.quads, idx % a.quads, a.m, src, a.w1u, a.b1, a.bias1);
         return;
     }
     idx -= a.n_fold;
     if constexpr (LOG_RV >= 3 && LOG_RV <= 5) {
         if (a.m.x_tiled) {
-            gather_block_tiled<LOG_RV>(idx, a.table, a.m.n_items, a.b, a.X, a.xl, a.bad);
+            gather_block_tiled<LOG_RV>(idx, a.table, a.m.n_items, src, a.X, a.xl, a.bad);
             return;
         }
     }
-    gather_block<LOG_RV>(idx, a.table, a.m.n_items, a.row_vec, a.b, a.X, a.xl, a.bad);
+    gather_block<LOG_RV>(idx, a.table, a.m.n_items, a.row_vec, src, a.X, a.xl, a.bad);
+}
+
+template <int LOG_RV, int DH>
+__global__ __launch_bounds__(256) void k_stage(StageArgs a)
+{
+    const int idx = blockIdx.x;
+    if (idx < a.n_up) {
+        const int i = idx * 256 + (int)threadIdx.x;
+        if (i < a.up_n16) a.up_dst[i] = a.up_src[i];
+        return;
+    }
+    stage_block<LOG_RV, DH>(a, TableReqs{a.b}, idx - a.n_up);
+}
+
+template <int LOG_RV, int DH>
+__global__ __launch_bounds__(256) void k_stage_one(StageOneArgs o)
+{
+    const int idx = blockIdx.x;
+    if (idx < o.a.n_up) {
+        one_fill(o.fill, idx * 256 + (int)threadIdx.x);
+        return;
+    }
+    stage_block<LOG_RV, DH>(o.a, OneReq{o.fill.rd}, idx - o.a.n_up);
 }
 
 template <int DH>
-static hipError_t launch_stage_dh(const StageArgs &a, int n_gather, hipStream_t s)
+static hipError_t launch_stage_dh(const StageArgs &a, int n_gather, const OneFill *one, hipStream_t s)
 {
     const dim3 grid(a.n_up + a.n_pack + a.n_fold + n_gather);
+    if (one) {
+        const StageOneArgs o{a, *one};
+        switch (a.row_vec) {
+        case 8: hipLaunchKernelGGL((k_stage_one<3, DH>), grid, dim3(256), 0, s, o); break;
+        case 16: hipLaunchKernelGGL((k_stage_one<4, DH>), grid, dim3(256), 0, s, o); break;
+        case 32: hipLaunchKernelGGL((k_stage_one<5, DH>), grid, dim3(256), 0, s, o); break;
+        default: hipLaunchKernelGGL((k_stage_one<-1, DH>), grid, dim3(256), 0, s, o); break;
+        }
+        return hipGetLastError();
+    }
     switch (a.row_vec) {
     case 8: hipLaunchKernelGGL((k_stage<3, DH>), grid, dim3(256), 0, s, a); break;
     case 16: hipLaunchKernelGGL((k_stage<4, DH>), grid, dim3(256), 0, s, a); break;
@@ -81,10 +114,11 @@ bool stage_fusable(const Model &m, const MfmaPlan &plan)
 
 hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad, const float *w1u,
                         const float *b1, float *bias1, const MfmaPlan &plan, bool gather, hipStream_t s,
-                        const StageUpload *up)
+                        const StageUpload *up, const OneFill *one)
 {
     if (b.n_req == 0) return hipSuccess;
     if (up && gather) return hipErrorInvalidValue;      // the gather's many blocks read the device copy
+    if (one && (up || b.n_req != 1 || b.n_slots != 1)) return hipErrorInvalidValue;
     StageArgs a;
     a.m = m;
     a.b = b;
@@ -99,6 +133,7 @@ hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void 
         a.up_n16 = (int32_t)((up->bytes + 15) / 16);
         a.n_up = (a.up_n16 + 255) / 256;
     }
+    if (one) a.n_up = (one_fill_items(*one) + 255) / 256;
     a.table = (const uint4 *)table;
     a.X = (char *)X;
     a.xl = x_layout(m);
@@ -116,7 +151,7 @@ hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void 
     a.n_pack = b.n_slots * m.n_heads * a.stages;     // once per distinct user of the call, not per slice (Sec. 3.1)
     a.n_fold = b.n_slots * a.quads;
     const int n_gather = gather ? b.n_blk : 0;      // none when the attention kernel indexes the table itself
-    return m.d_head == 64 ? launch_stage_dh<64>(a, n_gather, s) : launch_stage_dh<32>(a, n_gather, s);
+    return m.d_head == 64 ? launch_stage_dh<64>(a, n_gather, one, s) : launch_stage_dh<32>(a, n_gather, one, s);
 }
 
 }  // namespace aif

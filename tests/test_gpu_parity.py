@@ -360,6 +360,45 @@ def test_resident_and_streaming_attention_give_the_same_bits(R, torch):
     assert_logits_close("bf16", db.logits.cpu().numpy(), oracle_scores(cfg, model, table, ub, ib, n_threads=4).logits, "streaming")
 
 
+@pytest.mark.parametrize("shape", ["c2_like", "c4_like"])
+def test_streamed_requests_give_the_same_bits_alone_and_in_any_company(R, torch, shape):
+    """Requests whose K/V exceed LDS go to the streaming kernels: one workgroup per 32-candidate tile with the keys
+    split over its waves when the batch is small, one wave per tile otherwise (two- or eight-wave workgroups).  All
+    sum a candidate's keys in the same runs and add the runs in the same order, so a request has the same bits
+    alone, in a medium batch and in a large one.  Sequence lengths cover runs of one stage, empty runs (fewer
+    stages than waves), an odd number of key tiles and a ragged last tile; every request against the oracle."""
+    heads = MFMA_SHAPES[shape]["n_heads"]
+    long_l = 1100 if heads == 1 else 700            # > 152 KB of packed K/V either way
+    cfg = small_cfg("bf16", n_items=5000, seq_len=2100, **MFMA_SHAPES[shape])
+    _say(f"streamed requests alone / medium / large batch, {shape}")
+    rng = np.random.default_rng(2024)
+    model = wl.make_model(cfg, seed=9, bias_scale=0.2)
+    table = wl.make_table_host(cfg, rng)
+    table_dev = R.to_device(table, cfg.dtype)
+    sampler = wl.IdSampler(cfg)
+    dm = R.DeviceModel(cfg, model)
+    ctx = R.make_context(cfg, dm, table_dev, max_users=40, max_candidates=2048, max_seq_len=2100)
+    probes = [(long_l, 300), (long_l + 37, 33), (2100, 64), (long_l + 64 * 3 + 1, 257)]
+    probes = [(wl.make_user(cfg, rng, seq_len=L), sampler.sample(rng, n)) for L, n in probes]
+    alone = []
+    for u, ids in probes:
+        d = R.upload_request(cfg, u, ids)
+        ctx.aif_score_batch([d.req])
+        torch.cuda.synchronize()
+        z = d.logits.cpu().numpy().copy()
+        assert_logits_close("bf16", z, oracle_scores(cfg, model, table, u, ids, n_threads=4).logits, "alone")
+        alone.append(z)
+    filler_user = wl.make_user(cfg, rng, seq_len=long_l)
+    for n_fill, what in [(10, "medium batch: a wave per tile, two-wave workgroups"),
+                         (36, "large batch: eight-wave workgroups")]:
+        fill = [R.upload_request(cfg, filler_user, sampler.sample(rng, 2000)) for _ in range(n_fill)]
+        ds = [R.upload_request(cfg, u, ids) for u, ids in probes]
+        ctx.aif_score_batch([f.req for f in fill[: n_fill // 2]] + [d.req for d in ds] + [f.req for f in fill[n_fill // 2:]])
+        torch.cuda.synchronize()
+        for i, d in enumerate(ds):
+            assert np.array_equal(d.logits.cpu().numpy(), alone[i]), f"probe {i}: {what}"
+
+
 def test_mfma_attention_with_item_vector_wider_than_attention(R, torch):
     """d_item > d_attn without W_q: the query is the leading slice, the Hadamard cross still spans the whole
     item vector; the MLP of this shape has no MFMA variant, so the workspace stays row-major."""
