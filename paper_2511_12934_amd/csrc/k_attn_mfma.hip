@@ -369,8 +369,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
 // The streaming computation for a batch too small to give every SIMD a wave at 32 candidates a wave (one
 // request of 10^4 candidates is 313 such waves for 1,024 SIMDs, each walking the whole sequence: a chain of
 // a few hundred cycles per key tile with nobody to share the SIMD).  Here a workgroup is ONE 32-candidate
-// tile and its KEY_PARTS waves take a run of 64-key stages each (the runs of k_attn_mfma), so the chain is an
-// eighth as long; the runs' sums meet in LDS and are added in the order of the runs -- the order in which
+// tile and its waves take a run of 64-key stages each (the runs of k_attn_mfma; two runs each when the tiles
+// outnumber the compute units), so the chain is an eighth (a quarter) as long; the runs' sums meet in LDS and are added in the order of the runs -- the order in which
 // k_attn_mfma adds them, so the bits are the same.  A lone wave shares its K/V with nobody: fragments come
 // straight from memory (the L2s: every workgroup reads the same pack) into registers, three tiles in
 // rotation, two in flight.  Inside a tile the S product of the next tile alternates with this tile's
@@ -378,12 +378,16 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
 // ---------------------------------------------------------------------------
 template <int DH> constexpr int split_lds_bytes() { return KEY_PARTS * (DH / 32 * 16 + 1) * 64 * 4; }
 
-template <int DH>
-__global__ __launch_bounds__(KEY_PARTS * 64) void k_attn_split(Model m, Batch b, char *__restrict__ X, XLayout xl,
-                                                              const char *__restrict__ kvpack, size_t pack_stride,
-                                                              const float *__restrict__ kmax, int nktp)
+template <int DH, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_attn_split(Model m, Batch b, char *__restrict__ X, XLayout xl,
+                                                          const char *__restrict__ kvpack, size_t pack_stride,
+                                                          const float *__restrict__ kmax, int nktp)
 {
-    constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32, NREG = FT * 16, NQ = KEY_PARTS;
+    // WAVES = KEY_PARTS: a run a wave.  WAVES = KEY_PARTS / 2: two consecutive runs a wave, for the batches whose
+    // tiles outnumber the compute units -- a workgroup of eight waves takes a compute unit's registers alone, and
+    // the tiles beyond the first 256 would wait for a second round.
+    constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32, NREG = FT * 16, NQ = KEY_PARTS, RPW = KEY_PARTS / WAVES;
+    static_assert(KEY_PARTS % WAVES == 0, "whole runs per wave");
     extern __shared__ __align__(16) char lds[];
     float *part = (float *)lds;                        // [run][register (NREG of O, then l)][lane]
 
@@ -408,8 +412,8 @@ __global__ __launch_bounds__(KEY_PARTS * 64) void k_attn_split(Model m, Batch b,
     const char *pk = kvpack + (size_t)us * pack_stride + lane * 16;
     const bool live = local0 + col < rd.n_cand;
     const float c = LOG2E / sqrtf((float)DH);
-    // this wave's run, in tiles: whole stages of two (the last one of an odd sequence ends in the pack's empty tile)
-    const int kt0 = 2 * key_part_begin(wave, nst), kt1 = 2 * key_part_begin(wave + 1, nst);
+    // this wave's runs, in tiles: whole stages of two (the last one of an odd sequence ends in the pack's empty tile)
+    const int kt0 = 2 * key_part_begin(RPW * wave, nst), kt1 = 2 * key_part_begin(RPW * (wave + 1), nst);
 
     for (int hd = 0; hd < H; ++hd) {
         if (hd > 0) {
@@ -417,6 +421,10 @@ __global__ __launch_bounds__(KEY_PARTS * 64) void k_attn_split(Model m, Batch b,
             for (int j = 0; j < JS; ++j) q[j] = *piece(hd * (DH / 8) + 2 * j + h);
         }
         const char *kvh = pk + (size_t)hd * nktp * FR * 1024;           // fragment i of tile t: kvh + (t FR + i) KB
+        // the key-norm bounds are asked for first and looked at after the fragments have been asked for: a lane
+        // takes stage `lane` (an index past the end re-reads the last stage: no condition, no wait on the spot)
+        const float *kmh = kmax + ((size_t)us * H + hd) * (nktp / 2);
+        float km = nst > 0 ? kmh[lane < nst ? lane : nst - 1] : 0.f;
         // two sets of K fragments and two of V fragments take turns: while tile t's V and tile t + 1's K are in use,
         // tile t + 1's V and tile t + 2's K are in flight.  A tile index past the run re-reads the run's last tile
         // (fetched, not used), so the loop body has no conditions.
@@ -442,8 +450,7 @@ __global__ __launch_bounds__(KEY_PARTS * 64) void k_attn_split(Model m, Batch b,
             fetch_k(ka, kt0 + 2);
             fetch_v(vb, kt0 + 1);
         }
-        float km = 0.f;                     // the key-norm bounds ride behind the fragments: one wait for all
-        for (int i = lane; i < nst; i += 64) km = fmaxf(km, kmax[((size_t)us * H + hd) * (nktp / 2) + i]);
+        for (int i = lane + 64; i < nst; i += 64) km = fmaxf(km, kmh[i]);       // sequences beyond 4096 keys
 
         float ss = 0.f;
 #pragma unroll
@@ -480,6 +487,22 @@ __global__ __launch_bounds__(KEY_PARTS * 64) void k_attn_split(Model m, Batch b,
 #pragma unroll
             for (int i = 0; i < 16; ++i) O[ft][i] = 0.f;
         float l = 0.f;
+        // a finished run's sums go to LDS and the next run starts from zero
+        if (hd > 0) __syncthreads();                        // the previous head's sums have been read
+        int qn = RPW * wave;
+        auto flush = [&]() {
+            float *mine = part + (size_t)qn * (NREG + 1) * 64 + lane;
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    mine[(ft * 16 + i) * 64] = O[ft][i];
+                    O[ft][i] = 0.f;
+                }
+            mine[NREG * 64] = l;
+            l = 0.f;
+            ++qn;
+        };
         if (kt1 > kt0) {
             f32x16 S;
 #pragma unroll
@@ -536,28 +559,29 @@ __global__ __launch_bounds__(KEY_PARTS * 64) void k_attn_split(Model m, Batch b,
                 __builtin_amdgcn_sched_barrier(0);
                 S = Sn;
             };
+            int bnd = 2 * key_part_begin(qn + 1, nst);      // first tile of the next run
             for (int kt = kt0; kt < kt1; kt += 2) {
+                if constexpr (RPW > 1) {
+                    while (kt == bnd) {                     // a run ends here (empty runs: several)
+                        flush();
+                        bnd = 2 * key_part_begin(qn + 1, nst);
+                    }
+                }
                 body(va, kb, kt);
                 body(vb, ka, kt + 1);
             }
         }
+        while (qn < RPW * (wave + 1)) flush();              // the last run, and the empty ones around it
 
         // the runs' sums meet in LDS ...
-        if (hd > 0) __syncthreads();                        // the previous head's sums have been read
-        float *mine = part + (size_t)wave * (NREG + 1) * 64 + lane;
-#pragma unroll
-        for (int ft = 0; ft < FT; ++ft)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) mine[(ft * 16 + i) * 64] = O[ft][i];
-        mine[NREG * 64] = l;
         __syncthreads();
-        // ... and are added in the order of the runs, from zero; wave w normalises and stores quads w, w + NQ, ...
+        // ... and are added in the order of the runs, from zero; wave w normalises and stores quads w, w + WAVES, ...
         float lt = 0.f;
 #pragma unroll
         for (int qn = 0; qn < NQ; ++qn) lt += part[((size_t)qn * (NREG + 1) + NREG) * 64 + lane];
         lt += __shfl_xor(lt, 32, 64);
         const float inv = L > 0 ? 1.0f / lt : 0.f;
-        for (int g = wave; g < FT * 4; g += NQ) {
+        for (int g = wave; g < FT * 4; g += WAVES) {
             float t[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int qn = 0; qn < NQ; ++qn)
@@ -577,7 +601,7 @@ __global__ __launch_bounds__(KEY_PARTS * 64) void k_attn_split(Model m, Batch b,
     if (m.cross_mode == 1 && !m.cross_in_mlp && live) {
         const bf16x8 *uc = (const bf16x8 *)rd.cross_vecs;
         const int pc0 = (m.d_item + m.d_attn) / 8;
-        for (int pc = 2 * wave + h; pc < m.d_item / 8; pc += 2 * NQ) {
+        for (int pc = 2 * wave + h; pc < m.d_item / 8; pc += 2 * WAVES) {
             const bf16x8 e = *piece(pc), u = uc[pc];
             bf16x8 o8;
 #pragma unroll
@@ -589,7 +613,7 @@ __global__ __launch_bounds__(KEY_PARTS * 64) void k_attn_split(Model m, Batch b,
         const BeaGeom g = bea_geom(m);
         const uint16_t *Vu = (const uint16_t *)rd.cross_vecs;
         const int pc0 = (m.d_item + m.d_attn) / 8;
-        for (int ft = wave; ft < g.ftc; ft += NQ) {
+        for (int ft = wave; ft < g.ftc; ft += WAVES) {
             f32x16 Cc;
 #pragma unroll
             for (int i = 0; i < 16; ++i) Cc[i] = 0.f;
@@ -1093,7 +1117,9 @@ static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char
         if (e == hipSuccess)
             e = hipFuncSetAttribute((const void *)k_attn_res<DH, true>, hipFuncAttributeMaxDynamicSharedMemorySize, RES_LDS_BYTES);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)k_attn_split<DH>, hipFuncAttributeMaxDynamicSharedMemorySize, split_lds_bytes<DH>());
+            e = hipFuncSetAttribute((const void *)k_attn_split<DH, KEY_PARTS>, hipFuncAttributeMaxDynamicSharedMemorySize, split_lds_bytes<DH>());
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)k_attn_split<DH, KEY_PARTS / 2>, hipFuncAttributeMaxDynamicSharedMemorySize, split_lds_bytes<DH>());
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -1113,9 +1139,12 @@ static hipError_t launch_attn_spec(const Model &m, const Batch &b, void *X, char
     // the others: the streaming kernels (their blocks leave the resident kernel's requests alone)
     if (gather_table) return hipErrorInvalidValue;      // only the resident kernel gathers: the caller asked attn_gathers()
     const int tiles = b.n_blk * (ROW_BLOCK / 32);
-    if (tiles <= split_max_tiles())
-        hipLaunchKernelGGL((k_attn_split<DH>), dim3(tiles), dim3(KEY_PARTS * 64), split_lds_bytes<DH>(), s, m, b, (char *)X,
+    if (tiles <= n_compute_units() && tiles <= split_max_tiles())
+        hipLaunchKernelGGL((k_attn_split<DH, KEY_PARTS>), dim3(tiles), dim3(KEY_PARTS * 64), split_lds_bytes<DH>(), s, m, b, (char *)X,
                            x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp);
+    else if (tiles <= split_max_tiles())
+        hipLaunchKernelGGL((k_attn_split<DH, KEY_PARTS / 2>), dim3(tiles), dim3(KEY_PARTS / 2 * 64), split_lds_bytes<DH>(), s, m, b,
+                           (char *)X, x_layout(m), (const char *)kvpack, stride, (const float *)kmax, nktp);
     else if (small_batch(b))
         launch_streaming<DH, 2>(m, b, X, kvpack, stride, kmax, nktp, s);
     else
