@@ -681,15 +681,52 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     const int us = rd.slot;                         // K/V and key norms are kept per user, not per slice
     const char *pk = kvpack + (size_t)us * pack_stride;
 
-    // the whole pack -> LDS, heads back to back (in the pack a head takes nktp key tiles)
-    {
-        const uint32_t ring = lds_address(lds);
-        const int nfrag = H * head_frags;
-        for (int f = wave; f < nfrag; f += RES_WAVES) {
+    const int n_tiles = g.t1 - g.t0;
+    auto row_of = [&](int tile) { return X + x_offset(xl, rd.row_base + (g.t0 + tile) * 32 + col, 0); };
+    // GATHER: the id of this lane's candidate in a tile as the request gives it (0 past the request's end), and
+    // the table row it names
+    auto raw_id = [&](int t) {
+        const int lc = (g.t0 + t) * 32 + col;
+        return lc < rd.n_cand ? rd.cand_ids[lc] : 0;
+    };
+    auto checked = [&](int raw) {
+        if (raw < 0 || (int64_t)raw >= m.n_items) {
+            if (h == 0) atomicAdd(bad, 1);
+            raw = 0;
+        }
+        return raw;
+    };
+    auto table_row = [&](int id) { return table + (size_t)id * (size_t)(m.d_item * 2); };
+
+    // The whole pack -> LDS, heads back to back (in the pack a head takes nktp key tiles).  The wave's first query
+    // rides along: its id is asked for ahead of the first half of the pack and its row pieces between the halves, so
+    // that id -> row (two trips to memory) pass under the pack's flight instead of after the barrier.  (A wave with
+    // no tile in the group reads the group's last tile's: no condition around the loads.)
+    bf16x8 q[JS];
+    int id = 0;                             // GATHER: row of the table the current item's candidate has
+    const int tile_first = wave < n_tiles ? wave : n_tiles - 1;
+    int raw_first = 0;
+    if constexpr (GATHER) raw_first = raw_id(tile_first);
+    const uint32_t ring = lds_address(lds);
+    const int nfrag = H * head_frags, nhalf = nfrag / 2;
+    auto pack_to_lds = [&](int f0, int f1) {
+        for (int f = f0 + wave; f < f1; f += RES_WAVES) {
             const int hd = f / head_frags, rem = f - hd * head_frags;
             dma16(pk + ((size_t)hd * nktp * FR + rem) * 1024 + lane * 16, ring + f * 1024);
         }
+    };
+    pack_to_lds(0, nhalf);
+    if constexpr (GATHER) {
+        id = checked(wave < n_tiles ? raw_first : 0);       // (a stand-in id is not the request's: never counted as bad)
+        const char *tr = table_row(id);
+#pragma unroll
+        for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(tr + (2 * j + h) * 16);
+    } else {
+        const char *xr = row_of(tile_first);
+#pragma unroll
+        for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(2 * j + h) * xl.piece_stride);
     }
+    pack_to_lds(nhalf, nfrag);
     for (int hd = wave; hd < H; hd += RES_WAVES) {
         float km = 0.f;
         for (int i = lane; i < nkt2 / 2; i += 64) km = fmaxf(km, kmax[((size_t)us * H + hd) * (nktp / 2) + i]);
@@ -724,42 +761,12 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     // alone.  The only global reads an item needs are its query pieces; they are asked for as soon as
     // the previous item has issued its last S product (the registers are free from then on), so their
     // latency passes under that item's last exponentials, second product and stores.
-    const int n_tiles = g.t1 - g.t0;
-    auto row_of = [&](int tile) { return X + x_offset(xl, rd.row_base + (g.t0 + tile) * 32 + col, 0); };
     auto take_tile = [&]() {
         int t = 0;
         if (lane == 0) t = atomicAdd(s_next, 1);
         return __builtin_amdgcn_readfirstlane(t);
     };
-    // GATHER: the id of this lane's candidate in a tile as the request gives it (0 past the request's end), and
-    // the table row it names
-    auto raw_id = [&](int t) {
-        const int lc = (g.t0 + t) * 32 + col;
-        return lc < rd.n_cand ? rd.cand_ids[lc] : 0;
-    };
-    auto checked = [&](int raw) {
-        if (raw < 0 || (int64_t)raw >= m.n_items) {
-            if (h == 0) atomicAdd(bad, 1);
-            raw = 0;
-        }
-        return raw;
-    };
-    auto table_row = [&](int id) { return table + (size_t)id * (size_t)(m.d_item * 2); };
-    bf16x8 q[JS];
     int tile = wave, hd = 0;
-    int id = 0;                             // GATHER: row of the table the current item's candidate has
-    if (tile < n_tiles) {
-        if constexpr (GATHER) {
-            id = checked(raw_id(tile));
-            const char *tr = table_row(id);
-#pragma unroll
-            for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(tr + (2 * j + h) * 16);
-        } else {
-            const char *xr = row_of(tile);
-#pragma unroll
-            for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(2 * j + h) * xl.piece_stride);
-        }
-    }
     while (tile < n_tiles) {
         int next_tile = tile, next_hd = hd + 1;
         if (next_hd == H) {
