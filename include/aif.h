@@ -261,6 +261,13 @@ AIF_API int32_t aif_stage_kind(const aif_ctx *ctx, int32_t stage);
  * every slice reads the shared result.  -1 for a NULL context, 0 before the first call. */
 AIF_API int32_t aif_last_user_slots(const aif_ctx *ctx);
 
+/* Width of the contraction that layer 1 of the MLP head computes PER CANDIDATE in this context (Sec. 2: what does
+ * not depend on the candidate is done once).  D_in - d_user after the user fold; where the Hadamard cross block
+ * (Sec. 3.3) is folded into each user's layer-1 weights as well -- its share sum_k W1c[n,k] u_k e_k is linear in the
+ * item vector, so W'[n,k] = W1e[n,k] + u_k W1c[n,k] takes its place, once per user -- d_item + d_attn.  A
+ * measurement that counts the head's arithmetic counts this width (no credit for avoided work).  -1 for NULL. */
+AIF_API int32_t aif_mlp_layer1_width(const aif_ctx *ctx);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,8 @@ AIF_CROSS_NONE, AIF_CROSS_HADAMARD, AIF_CROSS_SEGDOT, AIF_CROSS_BEA = 0, 1, 2, 3
 EXPORTS = ("aif_score_init", "aif_score_request", "aif_score_batch", "aif_topk", "aif_score_destroy",
            "aif_last_error", "aif_poll_device_errors", "aif_peek_features", "aif_profile_begin",
            "aif_profile_end", "aif_stage_kind", "aif_update_rows", "aif_swap_table", "aif_score_topk",
-           "aif_profile_begin_stages", "aif_profile_begin_sampled", "aif_last_user_slots", "aif_score_topk_static")
+           "aif_profile_begin_stages", "aif_profile_begin_sampled", "aif_last_user_slots", "aif_score_topk_static",
+           "aif_mlp_layer1_width")
 STAGES = ("gather", "user_fold", "attention", "mlp", "topk")
 LSH_EXPORTS = ("aif_lsh_init", "aif_lsh_batch", "aif_lsh_destroy", "aif_lsh_last_error",
                "aif_lsh_poll_device_errors", "aif_lsh_profile_begin", "aif_lsh_profile_end")
@@ -119,6 +120,8 @@ def load():
     lib.aif_score_topk_static.argtypes = [vp, C.POINTER(aif_request), C.c_int32, vp, vp, vp]
     lib.aif_last_user_slots.restype = C.c_int32
     lib.aif_last_user_slots.argtypes = [vp]
+    lib.aif_mlp_layer1_width.restype = C.c_int32
+    lib.aif_mlp_layer1_width.argtypes = [vp]
     lib.aif_score_topk.restype = C.c_int
     lib.aif_score_topk.argtypes = [vp, C.POINTER(aif_request), C.c_int32, C.c_int32, vp, vp, vp]
     lib.aif_update_rows.restype = C.c_int
@@ -299,6 +302,9 @@ class Context:
 
     def aif_last_user_slots(self) -> int:
         return int(self._lib.aif_last_user_slots(self._h))
+
+    def aif_mlp_layer1_width(self) -> int:
+        return int(self._lib.aif_mlp_layer1_width(self._h))
 
     def close(self):
         if self._h:

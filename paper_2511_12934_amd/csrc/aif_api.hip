@@ -285,6 +285,13 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
         c->separate_gather = sg && sg[0] == '1';
         const char *cm = getenv("AIF_CROSS_MATERIALIZED");   // testing: the Hadamard cross block written to the workspace even where the MLP chain could form it
         m.cross_in_mlp = (c->mfma.mlp && mlp_chain_forms_cross(c->mfma.mlp_variant, m) && !(cm && cm[0] == '1')) ? 1 : 0;
+        // ... and where the staging launch can do it, the cross block is folded into each user's layer-1 weights instead
+        const char *cf = getenv("AIF_CROSS_FOLD");           // testing and measurement: "0" keeps the products in the chain
+        if (m.cross_in_mlp && stage_fusable(m, c->mfma) && !(cf && cf[0] == '0')) {
+            c->mfma.w0_stride = mlp_w0_user_bytes(m);
+            HIP_TRY(nullptr, hipMalloc((void **)&c->mfma.w0_user, c->mfma.w0_stride * (size_t)c->max_users));
+            m.cross_in_mlp = 2;
+        }
     }
 
     const bool attn_ok = c->mfma.attn || attn_generic_lds_bytes(m, c->max_seq_len) <= 160 * 1024;
@@ -622,6 +629,7 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
         o_h0 = take(mlp_layers_buf_bytes(m, (size_t)rows, 0));
         o_h1 = take(mlp_layers_buf_bytes(m, (size_t)rows, 1));
     }
+    const size_t o_w0 = m.cross_in_mlp == 2 ? take(c->mfma.w0_stride) : 0;
     const size_t o_x = take((size_t)rows * m.ldx * esz);
     if (off > (size_t)AIF_STATIC_SCRATCH_BYTES)
         return fail(c, AIF_ERANGE, "request of %d candidates (sequence of up to %d) needs %zu bytes of workspace, the static call holds %zu",
@@ -665,6 +673,7 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
     plan.kvpack = (char *)(base + o_kv);
     plan.hbuf[0] = layered ? (char *)(base + o_h0) : nullptr;
     plan.hbuf[1] = layered ? (char *)(base + o_h1) : nullptr;
+    plan.w0_user = m.cross_in_mlp == 2 ? (char *)(base + o_w0) : nullptr;
     void *X = base + o_x;
     float *bias1 = (float *)(base + o_b1);
     int32_t *bad = (int32_t *)c->bad.p;
@@ -891,6 +900,7 @@ aif_status aif_profile_end(aif_ctx *c, double *ms_sum, int32_t *n_calls)
 }
 
 int32_t aif_last_user_slots(const aif_ctx *c) { return c ? c->last_slots : -1; }
+int32_t aif_mlp_layer1_width(const aif_ctx *c) { return !c ? -1 : (c->m.cross_in_mlp == 2 ? c->m.d_item + c->m.d_attn : c->m.k1); }
 
 int32_t aif_stage_kind(const aif_ctx *c, int32_t stage)
 {

@@ -17,6 +17,8 @@ struct MfmaPlan {
     size_t pack_stride = 0;            // bytes of kvpack per request
     int nktp = 0;                      // key tiles per head the pack layout is sized for
     char *hbuf[2] = {};                // layered MLP: hidden activations between launches, ping-pong (owned workspace)
+    char *w0_user = nullptr;           // per user slot: layer 1's fragments with the Hadamard cross block folded in (owned workspace; Model::cross_in_mlp == 2)
+    size_t w0_stride = 0;              // bytes per slot
 };
 constexpr int MLP_VARIANT_LAYERS = 100;   // mlp_variant of the one-launch-per-layer path (k_mlp_layers.hip)
 
@@ -25,6 +27,8 @@ struct MlpPack {
     const float *bias[3];              // fp32 biases of hidden layers 2, 3 (index 1, 2), never null; [0] unused
     const float *wlast;                // fp32 weights of the final ->1 layer
     const float *blast;                // its bias (1 float), never null
+    const char *w0_user;               // layer 1's fragments per user slot with the Hadamard cross block folded in (k_mlp_chain.h: UW), or null
+    size_t w0_stride;                  // bytes per slot
 };
 
 // Decide which MFMA kernels can serve the model and pack their weights
@@ -76,6 +80,8 @@ hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const 
 // k_mlp_mfma.hip
 int mlp_mfma_variant(const Model &m);
 bool mlp_chain_forms_cross(int variant, const Model &m);
+// bytes per user slot of layer 1's weights with the Hadamard cross block folded in (k_stage.h: fold_w0_block)
+inline size_t mlp_w0_user_bytes(const Model &m) { return (size_t)m.dims[1] * (m.d_item + m.d_attn) * 2; }
 hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const void *X, const MlpPack &pk,
                               const float *bias1, hipStream_t s);
 hipError_t pack_frag(const void *W, int n_in, int col0, int N, int K, bool from_mfma, void *dst, hipStream_t s);

@@ -81,6 +81,8 @@ void mfma_release(MfmaPlan &plan)
         if (p) (void)hipFree(p);
         p = nullptr;
     }
+    if (plan.w0_user) (void)hipFree(plan.w0_user);
+    plan.w0_user = nullptr;
 }
 
 hipError_t launch_attn_mfma(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool kv_packed, hipStream_t s,
@@ -100,6 +102,8 @@ hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const 
     }
     pk.wlast = wlast_f32;
     pk.blast = bias_f32[m.n_layers - 1] ? bias_f32[m.n_layers - 1] : plan.zeros;
+    pk.w0_user = m.cross_in_mlp == 2 ? plan.w0_user : nullptr;
+    pk.w0_stride = plan.w0_stride;
     if (plan.mlp_variant == MLP_VARIANT_LAYERS) return launch_mlp_layers(m, b, X, pk, bias1, plan.hbuf, s);
     return launch_mlp_variant(plan.mlp_variant, m, b, X, pk, bias1, s);
 }

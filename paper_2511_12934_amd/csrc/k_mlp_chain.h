@@ -97,14 +97,18 @@ template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS> struct C
 
 // Copy stage I of the weight stream global -> LDS slot: a wave moves whole 1 KB
 // fragments, no register staging.
+// w0: layer 1's fragments when they are the tile's user's own (UW), else null: the model's (pk.w[0])
 template <class C, int WAVES, int SF, int SLOTS, int I, int P = 0>
-__device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
+__device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds, const char *w0 = nullptr)
 {
     if constexpr (I < C::ns()) {
         constexpr int l = C::flayer(I * SF);
         const int lane = threadIdx.x & 63;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const char *src = pk.w[l] + (size_t)(I * SF - C::fbase(l)) * 1024 + wave * 1024;     // wave-uniform
+        const char *base = pk.w[l];
+        if constexpr (l == 0)
+            if (w0) base = w0;
+        const char *src = base + (size_t)(I * SF - C::fbase(l)) * 1024 + wave * 1024;     // wave-uniform
         const uint32_t dst = lds_address(lds) + C::slot(I, P) * SF * 1024 + wave * 1024;
 #pragma unroll
         for (int f0 = 0; f0 < SF; f0 += WAVES) dma16_s(src + f0 * 1024, lane * 16, dst + f0 * 1024);
@@ -141,7 +145,12 @@ __device__ __forceinline__ void issue_stage(const MlpPack &pk, char *lds)
 // EH > 0: the last EH k-steps of layer 1 are the Hadamard cross block c = u (.) e (Sec. 3.3) of the first EH k-steps (the
 // item block): formed here, in registers, from the item fragments and the request's operand u (kept in LDS), rounded to
 // bf16 as the attention kernel would have stored it -- the workspace's cross block is then neither written nor read.
-template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS, int PER_CU, int EH>
+// UW: layer 1's weights are the tile's USER's own (MlpPack::w0_user, one set per user slot, made by the staging launch):
+// the Hadamard cross block's share of layer 1, sum_k W1c[n, k] u_k e_k, is linear in the item vector, so it is folded
+// into the item block's weights once per user, W'[n, k] = W1e[n, k] + u_k W1c[n, k] (Sec. 2: what does not depend on the
+// candidate is done once) -- layer 1 then contracts over [item | attention] only.  The first stages of the stream
+// then wait for the tile -> slot lookup.
+template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS, int PER_CU, int EH, int UW>
 __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items, const ReqDesc *__restrict__ reqs,
                                                            const int32_t *__restrict__ blk_req,
                                                            const int32_t *__restrict__ blk_slot, const char *__restrict__ X,
@@ -183,7 +192,7 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
     const int wave_u = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // The block's start is a chain of dependent memory round trips; keep it short: the weight stream
     // and the input rows do not depend on the request lookup, so they are asked for first.
-    static_for<0, D>([&](auto s) { issue_stage<C, WAVES, SF, SLOTS, decltype(s)::value>(pk, lds); });
+    if constexpr (!UW) static_for<0, D>([&](auto s) { issue_stage<C, WAVES, SF, SLOTS, decltype(s)::value>(pk, lds); });
     bf16x8 xin[K1 / 16];
     auto load_xin = [&](int t) {
         const char *xr = X + x_offset(xl, t * ROWS + wave * 32 + col, h);
@@ -210,6 +219,12 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
     const int r0 = blk_req[tile0 / (ROW_BLOCK / ROWS)], r1 = blk_req[t1 / (ROW_BLOCK / ROWS)];
     // the folded layer-1 biases are kept per user slot (the slices of one candidate list share them): same round trip
     const int s0 = blk_slot[tile0 / (ROW_BLOCK / ROWS)], s1 = blk_slot[t1 / (ROW_BLOCK / ROWS)];
+    const char *w0a = nullptr, *w0b = nullptr;                  // UW: the two tiles' users' layer-1 fragments
+    if constexpr (UW) {
+        w0a = pk.w0_user + (size_t)s0 * pk.w0_stride;
+        w0b = pk.w0_user + (size_t)s1 * pk.w0_stride;
+        static_for<0, D>([&](auto s) { issue_stage<C, WAVES, SF, SLOTS, decltype(s)::value>(pk, lds, w0a); });
+    }
     const Out rd0 = out_of(r0), rd1 = out_of(r1);
     float g1[N1];
 #pragma unroll
@@ -361,7 +376,7 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
                     // stage I + 1 must have landed; the D - 2 stages after it may stay in flight
                     wait_vmcnt<(D - 2) * C::LPW>();
                     asm volatile("s_barrier" ::: "memory");
-                    issue_stage<C, WAVES, SF, SLOTS, I + D, P>(pk, lds);
+                    issue_stage<C, WAVES, SF, SLOTS, I + D, P>(pk, lds, P == 0 ? w0a : w0b);
                 } else {
                     bool on = false;
                     if constexpr (P == 0) on = more;
@@ -369,7 +384,7 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
                         // the stream runs on into the second tile: stage I + D is its stage I + D - NS
                         wait_vmcnt<(D - 2) * C::LPW>();
                         asm volatile("s_barrier" ::: "memory");
-                        issue_stage<C, WAVES, SF, SLOTS, I + D - NS, 1>(pk, lds);
+                        issue_stage<C, WAVES, SF, SLOTS, I + D - NS, 1>(pk, lds, w0b);
                     } else if constexpr (I + 1 < NS) {
                         // the block's last tile: nothing more is sent; stages I + 2 .. NS - 1 may stay in flight
                         wait_vmcnt<(NS - 1 - (I + 1)) * C::LPW>();
@@ -436,14 +451,15 @@ static inline int n_cu()
     return n;
 }
 
-template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS, int PER_CU = 2, int EH = 0>
+template <int K1, int H1, int H2, int H3, int WAVES, int SF, int SLOTS, int PER_CU = 2, int EH = 0, int UW = 0>
 static hipError_t launch_spec(const Model &m, const Batch &b, const void *X, const MlpPack &pk, const float *bias1,
                               hipStream_t s)
 {
     using C = Chain<K1, H1, H2, H3, WAVES, SF, SLOTS>;
     constexpr int LDS = (C::lds_bytes + 15) / 16 * 16 + 2 * EH * 32;
     constexpr int ROWS = WAVES * 32;
-    auto kern = k_mlp_mfma<K1, H1, H2, H3, WAVES, SF, SLOTS, PER_CU, EH>;
+    auto kern = k_mlp_mfma<K1, H1, H2, H3, WAVES, SF, SLOTS, PER_CU, EH, UW>;
+    if (UW && !pk.w0_user) return hipErrorInvalidValue;
     static_assert(PER_CU * LDS <= 160 * 1024, "the blocks of a compute unit share its LDS");
     static_assert(EH * 8 <= WAVES * 64 && 2 * EH < K1 / 16, "Hadamard operand: one word per thread; item and cross blocks inside layer 1");
     static bool attr_set = false;

@@ -32,6 +32,9 @@ hipError_t mlp_chain_c5(const Model &, const Batch &, const void *, const MlpPac
 hipError_t mlp_chain_c2h(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 hipError_t mlp_chain_c3h(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 hipError_t mlp_chain_c4h(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
+hipError_t mlp_chain_c2f(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
+hipError_t mlp_chain_c3f(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
+hipError_t mlp_chain_c4f(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 
 // Can the chain of this variant form the Hadamard cross block itself (Model::cross_in_mlp)?  Layer 1 after the user
 // fold must be exactly [item | attention | item (.) u] with the item width the kernel was built for.
@@ -86,9 +89,11 @@ hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const
 {
     if (b.n_blk == 0) return hipSuccess;
     switch (variant) {
-    case 0: return m.cross_in_mlp ? mlp_chain_c2h(m, b, X, pk, bias1, s) : mlp_chain_c2(m, b, X, pk, bias1, s);
-    case 1: return m.cross_in_mlp ? mlp_chain_c3h(m, b, X, pk, bias1, s) : mlp_chain_c3(m, b, X, pk, bias1, s);
-    case 2: return m.cross_in_mlp ? mlp_chain_c4h(m, b, X, pk, bias1, s) : mlp_chain_c4(m, b, X, pk, bias1, s);
+    // cross_in_mlp: 0 the cross block is in the workspace, 1 the chain forms it from the item block, 2 it is folded into
+    // the user's layer-1 weights (the `f` chains: layer 1 over [item | attention])
+    case 0: return m.cross_in_mlp == 2 ? mlp_chain_c2f(m, b, X, pk, bias1, s) : m.cross_in_mlp ? mlp_chain_c2h(m, b, X, pk, bias1, s) : mlp_chain_c2(m, b, X, pk, bias1, s);
+    case 1: return m.cross_in_mlp == 2 ? mlp_chain_c3f(m, b, X, pk, bias1, s) : m.cross_in_mlp ? mlp_chain_c3h(m, b, X, pk, bias1, s) : mlp_chain_c3(m, b, X, pk, bias1, s);
+    case 2: return m.cross_in_mlp == 2 ? mlp_chain_c4f(m, b, X, pk, bias1, s) : m.cross_in_mlp ? mlp_chain_c4h(m, b, X, pk, bias1, s) : mlp_chain_c4(m, b, X, pk, bias1, s);
     case 3: return mlp_chain_c5(m, b, X, pk, bias1, s);
     default: return hipErrorInvalidValue;
     }

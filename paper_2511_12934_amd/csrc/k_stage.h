@@ -223,6 +223,48 @@ __device__ __forceinline__ void user_fold_block(int slot, int part, const Model 
     if (run == 0 && on) bias1[(size_t)slot * h1 + n] = (((b1 ? b1[n] : 0.f) + acc) + part_sum[0][lane]) + (part_sum[1][lane] + part_sum[2][lane]);
 }
 
+// a2 -- layer 1's weights of user slot `slot` with the Hadamard cross block folded in (Model::cross_in_mlp == 2):
+// the cross block's share of a layer-1 pre-activation, sum_k W1c[n, k] u_k e_k, is linear in the item vector e, so
+//   W'[n, k] = bf16(W1e[n, k] + u_k W1c[n, k])        (the product is exact in fp32, the sum rounded once)
+// takes its place and layer 1 contracts over [item | attention] only.  Source and result are in the MLP chain's
+// fragment order (k_mlp_mfma.hip): fragment (row tile rt, k-step j) = 64 lanes x 8 values, lane (n = 32 rt + lane % 32,
+// h = lane / 32) holding k = 16 j + 8 h + s; the source has K1 / 16 k-steps [item | attention | cross] per row tile,
+// the result (d_item + d_attn) / 16; the attention block's fragments are copied.  One 16-byte piece a thread.
+struct FoldW0 {
+    const uint4 *src;           // the model's layer-1 fragments, [H1 / 32][K1 / 16][64] pieces
+    uint4 *dst;                 // [slot][H1 / 32][(d_item + d_attn) / 16][64] pieces
+    size_t stride;              // bytes per slot
+    int32_t blocks_per_slot;
+};
+__device__ __forceinline__ uint32_t fold_pair(uint32_t we, uint32_t wc, uint32_t u)
+{
+    auto lo = [](uint32_t v) { return __uint_as_float(v << 16); };
+    auto hi = [](uint32_t v) { return __uint_as_float(v & 0xFFFF0000u); };
+    auto bf = [](float f) {                          // round to nearest even; the operands are finite
+        const uint32_t b = __float_as_uint(f);
+        return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+    };
+    return bf(fmaf(lo(u), lo(wc), lo(we))) | (bf(fmaf(hi(u), hi(wc), hi(we))) << 16);
+}
+template <class Reqs>
+__device__ __forceinline__ void fold_w0_block(int slot, int part, const Model &m, const Reqs &src, const FoldW0 &f)
+{
+    const int ks_e = m.d_item / 16, ks_new = (m.d_item + m.d_attn) / 16, ks_old = m.k1 / 16;
+    const int p = part * 256 + (int)threadIdx.x;                 // piece of the slot's result
+    if (p >= m.dims[1] / 32 * ks_new * 64) return;
+    const int lane = p & 63, j = (p >> 6) % ks_new, rt = (p >> 6) / ks_new, h = lane >> 5;
+    uint4 out = f.src[(size_t)(rt * ks_old + j) * 64 + lane];
+    if (j < ks_e) {
+        const uint4 wc = f.src[(size_t)(rt * ks_old + ks_new + j) * 64 + lane];
+        const uint4 u = ((const uint4 *)src.slot_desc(slot).cross_vecs)[2 * j + h];
+        out.x = fold_pair(out.x, wc.x, u.x);
+        out.y = fold_pair(out.y, wc.y, u.y);
+        out.z = fold_pair(out.z, wc.z, u.z);
+        out.w = fold_pair(out.w, wc.w, u.w);
+    }
+    f.dst[(size_t)slot * (f.stride / 16) + p] = out;
+}
+
 // a2 -- K and V of user slot `slot` (the tensors of the request that stands for it), head hd, 64-key stage st into MFMA fragment order, and max |k_t| of the stage.
 // Layout per slot: chunk(head, key tile kt) = FR fragments of 1 KB at
 // ((head * nktp + kt) * FR) KB:  JS K-fragments  [lane][s] = K[32kt + lane%32][o + 16j + 8(lane/32) + s]

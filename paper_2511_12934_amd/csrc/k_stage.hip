@@ -28,6 +28,8 @@ struct StageArgs {
     float *kmax;
     int32_t nktp, row_vec;
     int32_t n_pack, n_fold;         // blocks of the first two jobs
+    int32_t n_w0;                   // blocks that fold the Hadamard cross block into the slots' layer-1 weights (0: not this model)
+    FoldW0 w0;
     int32_t stages, quads;          // 64-key stages per head (nktp / 2); blocks of FOLD_FEATS layer-1 features
     const uint4 *up_src;            // descriptor tables to copy (mapped host memory -> device), 16 bytes a thread
     uint4 *up_dst;
@@ -52,6 +54,11 @@ __device__ __forceinline__ void stage_block(const StageArgs &a, const Reqs &src,
         return;
     }
     idx -= a.n_fold;
+    if (idx < a.n_w0) {
+        fold_w0_block(idx / a.w0.blocks_per_slot, idx % a.w0.blocks_per_slot, a.m, src, a.w0);
+        return;
+    }
+    idx -= a.n_w0;
     if constexpr (LOG_RV >= 3 && LOG_RV <= 5) {
         if (a.m.x_tiled) {
             gather_block_tiled<LOG_RV>(idx, a.table, a.m.n_items, src, a.X, a.xl, a.bad);
@@ -87,7 +94,7 @@ __global__ __launch_bounds__(256) void k_stage_one(StageOneArgs o)
 template <int DH>
 static hipError_t launch_stage_dh(const StageArgs &a, int n_gather, const OneFill *one, hipStream_t s)
 {
-    const dim3 grid(a.n_up + a.n_pack + a.n_fold + n_gather);
+    const dim3 grid(a.n_up + a.n_pack + a.n_fold + a.n_w0 + n_gather);
     if (one) {
         const StageOneArgs o{a, *one};
         switch (a.row_vec) {
@@ -150,6 +157,16 @@ hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void 
     a.quads = (m.dims[1] + FOLD_FEATS - 1) / FOLD_FEATS;
     a.n_pack = b.n_slots * m.n_heads * a.stages;     // once per distinct user of the call, not per slice (Sec. 3.1)
     a.n_fold = b.n_slots * a.quads;
+    a.n_w0 = 0;
+    a.w0 = FoldW0{};
+    if (m.cross_in_mlp == 2) {
+        if (!plan.w0_user || !plan.wpack[0]) return hipErrorInvalidValue;
+        a.w0.src = (const uint4 *)plan.wpack[0];
+        a.w0.dst = (uint4 *)plan.w0_user;
+        a.w0.stride = plan.w0_stride;
+        a.w0.blocks_per_slot = (m.dims[1] / 32 * ((m.d_item + m.d_attn) / 16) * 64 + 255) / 256;
+        a.n_w0 = b.n_slots * a.w0.blocks_per_slot;
+    }
     const int n_gather = gather ? b.n_blk : 0;      // none when the attention kernel indexes the table itself
     return m.d_head == 64 ? launch_stage_dh<64>(a, n_gather, one, s) : launch_stage_dh<32>(a, n_gather, one, s);
 }

@@ -48,6 +48,8 @@ def assert_logits_close(dtype: str, z_gpu: np.ndarray, z_ref: np.ndarray, what: 
     worst = int(np.argmax(err - tol)) if err.size else 0
     assert np.all(err <= tol), (f"{what}: logit {worst}: gpu {z_gpu[worst]!r} oracle {z_ref[worst]!r} "
                                 f"err {err[worst]:.3e} tol {tol[worst]:.3e}")
+    if err.size:
+        USED[f"{dtype} logit tolerance"] = max(USED.get(f"{dtype} logit tolerance", 0.0), float((err / tol).max()))
 
 
 # Regression guard for bf16 logits AT THE CONFIGURATIONS' SCALE (logits of rms ~0.03, where the benchmark spec's 2e-2 is
@@ -74,6 +76,8 @@ def assert_bf16_logits_tight(z_gpu: np.ndarray, z_ref: np.ndarray, what: str = "
     assert np.all(err <= tol), (f"{what}: logit {worst}: gpu {z_gpu[worst]!r} oracle {z_ref[worst]!r} "
                                 f"err {err[worst]:.3e} guard {tol[worst]:.3e} (rms z {rms_z:.3e})")
     assert rms_e <= BF16_GUARD_RMS * rms_z, f"{what}: rms error {rms_e:.3e} > 2^-7 * rms z {rms_z:.3e}"
+    USED["bf16 logit guard, rms"] = max(USED.get("bf16 logit guard, rms", 0.0), rms_e / (BF16_GUARD_RMS * rms_z))
+    USED["bf16 logit guard, max"] = max(USED.get("bf16 logit guard, max", 0.0), float((err / tol).max()))
     return float(err.max()), rms_e, rms_z
 
 

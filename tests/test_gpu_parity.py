@@ -695,11 +695,11 @@ def test_projection_attention_with_16_wide_heads(R, torch, shape, sigma):
 
 @pytest.mark.parametrize("name", ["C2", "C3", "C4"])
 def test_hadamard_cross_formed_in_the_mlp_chain_gives_the_same_bits(R, torch, monkeypatch, name):
-    """Where the MLP is a fused chain and the cross block is u (.) e, the chain forms the products itself from the item
-    block it reads anyway, and the attention kernel leaves the workspace's cross block unwritten.  Same products, same
-    rounding: logits and scores are those of the route that writes the block (AIF_CROSS_MATERIALIZED=1, whose cross
-    block is compared with the oracle's element by element), bit for bit, and the feature matrix the library shows
-    is the same."""
+    """Where the MLP is a fused chain and the cross block is u (.) e, the chain can form the products itself from the
+    item block it reads anyway (AIF_CROSS_FOLD=0), the attention kernel leaving the workspace's cross block unwritten.
+    Same products, same rounding: logits and scores are those of the route that writes the block
+    (AIF_CROSS_MATERIALIZED=1, whose cross block is compared with the oracle's element by element), bit for bit, and
+    the feature matrix the library shows is the same."""
     base = wl.CONFIGS[name]
     cfg = base.scaled(n_items=6000, seq_len=min(base.seq_len, 700))
     _say(f"{name} shape: Hadamard cross in the MLP chain vs written to the workspace")
@@ -709,7 +709,9 @@ def test_hadamard_cross_formed_in_the_mlp_chain_gives_the_same_bits(R, torch, mo
     sampler = wl.IdSampler(cfg, 6000)
     reqs = [(wl.make_user(cfg, rng, sigma=1.0), sampler.sample(rng, n)) for n in (1500, 1, 257, 700)]
     table_dev = R.to_device(table, "bf16")
+    monkeypatch.setenv("AIF_CROSS_FOLD", "0")
     z0, y0, _, ctx0 = run_batch(R, torch, cfg, model, table_dev, reqs)
+    assert ctx0.aif_mlp_layer1_width() == cfg.d_in - cfg.d_user
     X0 = [R.peek_features(ctx0, cfg, r, ids.size) for r, (_, ids) in enumerate(reqs)]
     monkeypatch.setenv("AIF_CROSS_MATERIALIZED", "1")
     z1, y1, _, ctx1 = run_batch(R, torch, cfg, model, table_dev, reqs)
@@ -719,6 +721,52 @@ def test_hadamard_cross_formed_in_the_mlp_chain_gives_the_same_bits(R, torch, mo
         assert np.array_equal(X0[r], X1[r]), f"request {r}: feature matrix"
         ref = oracle_scores(cfg, model, table, u, ids, n_threads=8)
         assert_features_close("bf16", X1[r][:, cfg.d_item + cfg.d_attn:], ref.cross, f"request {r} cross")
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
+@pytest.mark.parametrize("sigma", [0.1, 1.0])
+def test_hadamard_cross_folded_into_the_users_layer1_weights(R, torch, monkeypatch, name, sigma):
+    """The default route where the MLP is a fused chain and the cross block is u (.) e: the block's share of layer 1,
+    sum_k W1c[n, k] u_k e_k, is linear in the item vector, so the staging launch folds it into each user's layer-1
+    weights, W' = W1e + u W1c, and the chain contracts over [item | attention] only.  Not the same roundings as the
+    route that forms the block (W' is rounded to bf16 instead of the products): both against the oracle to the
+    scale-aware bound, whole requests; users in one call get their own weights (four users, one of them as two slices
+    that share a slot); the feature matrix the library shows is the same."""
+    from helpers import assert_bf16_logits_tight
+    base = wl.CONFIGS[name]
+    cfg = base.scaled(n_items=6000, seq_len=min(base.seq_len, 700))
+    _say(f"{name} shape, sigma {sigma}: Hadamard cross folded into the users' layer-1 weights")
+    rng = np.random.default_rng(777)
+    model = wl.make_model(cfg, bias_scale=0.05)
+    table = wl.make_table_host(cfg, rng, n_items=6000, sigma=sigma)
+    sampler = wl.IdSampler(cfg, 6000)
+    reqs = [(wl.make_user(cfg, rng, sigma=sigma), sampler.sample(rng, n)) for n in (1500, 1, 257, 700)]
+    table_dev = R.to_device(table, "bf16")
+    z0, y0, _, ctx0 = run_batch(R, torch, cfg, model, table_dev, reqs)
+    assert ctx0.aif_mlp_layer1_width() == cfg.d_item + cfg.d_attn, "the fold is the default on these shapes"
+    X0 = [R.peek_features(ctx0, cfg, r, ids.size) for r, (_, ids) in enumerate(reqs)]
+    monkeypatch.setenv("AIF_CROSS_MATERIALIZED", "1")
+    z1, y1, _, ctx1 = run_batch(R, torch, cfg, model, table_dev, reqs)
+    X1 = [R.peek_features(ctx1, cfg, r, ids.size) for r, (_, ids) in enumerate(reqs)]
+    monkeypatch.delenv("AIF_CROSS_MATERIALIZED")
+    for r, (u, ids) in enumerate(reqs):
+        ref = oracle_scores(cfg, model, table, u, ids, n_threads=8)
+        assert np.array_equal(X0[r], X1[r]), f"request {r}: feature matrix"
+        if ids.size > 1:
+            e0 = assert_bf16_logits_tight(z0[r], ref.logits, f"folded, request {r}")
+            e1 = assert_bf16_logits_tight(z1[r], ref.logits, f"materialized, request {r}")
+            print(f"    request {r}: rms error folded {e0[1]:.3e}, materialized {e1[1]:.3e}, rms z {e0[2]:.3e}", flush=True)
+        else:
+            assert_logits_close("bf16", z0[r], ref.logits, f"folded, request {r}")
+    # slices of one request share its user's weights and give the whole request's bits
+    u, ids = reqs[0]
+    whole = R.upload_request(cfg, u, ids)
+    parts = [R.slice_request(cfg, whole, lo, min(lo + 600, ids.size)) for lo in range(0, ids.size, 600)]
+    other = R.upload_request(cfg, reqs[3][0], reqs[3][1])
+    ctx0.aif_score_batch([p.req for p in parts[:1]] + [other.req] + [p.req for p in parts[1:]])
+    torch.cuda.synchronize()
+    assert ctx0.aif_last_user_slots() == 2
+    assert np.array_equal(whole.logits.cpu().numpy(), z0[0]) and np.array_equal(other.logits.cpu().numpy(), z0[3])
 
 
 def test_widest_head_as_one_fused_chain(R, torch, monkeypatch):
