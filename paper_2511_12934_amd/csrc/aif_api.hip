@@ -287,7 +287,8 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
         m.cross_in_mlp = (c->mfma.mlp && mlp_chain_forms_cross(c->mfma.mlp_variant, m) && !(cm && cm[0] == '1')) ? 1 : 0;
         // ... and where the staging launch can do it, the cross block is folded into each user's layer-1 weights instead
         const char *cf = getenv("AIF_CROSS_FOLD");           // testing and measurement: "0" keeps the products in the chain
-        if (m.cross_in_mlp && stage_fusable(m, c->mfma) && !(cf && cf[0] == '0')) {
+        const bool foldable = c->mfma.mlp && mlp_chain_folds_cross(c->mfma.mlp_variant, m) && !(cm && cm[0] == '1');
+        if (foldable && stage_fusable(m, c->mfma) && !(cf && cf[0] == '0')) {
             c->mfma.w0_stride = mlp_w0_user_bytes(m);
             HIP_TRY(nullptr, hipMalloc((void **)&c->mfma.w0_user, c->mfma.w0_stride * (size_t)c->max_users));
             m.cross_in_mlp = 2;
@@ -809,11 +810,12 @@ aif_status aif_peek_features(aif_ctx *c, int32_t request, int32_t first_row, int
             memcpy((char *)out + (size_t)i * row_bytes + 16 * p,
                    tiles.data() + x_offset(xl, (uint32_t)(row0 + i - t0 * X_TILE), p), 16);
     if (m.cross_in_mlp) {
-        // The workspace's cross block is not written on this route (the MLP chain forms c = u (.) e in registers): show
-        // what the chain forms -- the fp32 product of the two bf16 values, rounded to nearest even -- from the item block
-        // and the request's operand.
-        std::vector<uint16_t> u(m.d_item);
-        HIP_TRY(c, hipMemcpy(u.data(), c->peek_cross[request], (size_t)m.d_item * 2, hipMemcpyDeviceToHost));
+        // The workspace's cross block is not written on this route (the MLP chain forms c = u (.) e in registers, or the
+        // block is folded into the user's layer-1 weights): show the block as the kernels that write it would form it
+        // -- fp32 arithmetic on the bf16 values, rounded to nearest even -- from the item block and the request's operand.
+        const size_t n_op = m.cross_mode == 3 ? (size_t)m.n_cross * m.d_cv : (size_t)m.d_item;
+        std::vector<uint16_t> u(n_op);
+        HIP_TRY(c, hipMemcpy(u.data(), c->peek_cross[request], n_op * 2, hipMemcpyDeviceToHost));
         auto widen = [](uint16_t b) { uint32_t w = (uint32_t)b << 16; float f; memcpy(&f, &w, 4); return f; };
         auto narrow = [](float f) {
             uint32_t w;
@@ -824,7 +826,14 @@ aif_status aif_peek_features(aif_ctx *c, int32_t request, int32_t first_row, int
         };
         for (int32_t i = 0; i < n_rows; ++i) {
             uint16_t *row = (uint16_t *)((char *)out + (size_t)i * row_bytes);
-            for (int k = 0; k < m.d_item; ++k) row[m.d_item + m.d_attn + k] = narrow(widen(row[k]) * widen(u[k]));
+            if (m.cross_mode == 3) {            // Algorithm 1 step 4: the row's last n_cross entries weigh the user-side vectors
+                for (int f = 0; f < m.d_cv; ++f) {
+                    float acc = 0.f;
+                    for (int j = 0; j < m.n_cross; ++j) acc = fmaf(widen(row[m.d_item - m.n_cross + j]), widen(u[(size_t)j * m.d_cv + f]), acc);
+                    row[m.d_item + m.d_attn + f] = narrow(acc);
+                }
+            } else
+                for (int k = 0; k < m.d_item; ++k) row[m.d_item + m.d_attn + k] = narrow(widen(row[k]) * widen(u[k]));
         }
     }
     return AIF_OK;

@@ -336,7 +336,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
             store_stream(piece(pc0 + pc), o8);
         }
     }
-    if (m.cross_mode == 3) {
+    if (m.cross_mode == 3 && !m.cross_in_mlp) {      // unless the block is folded into the user's layer-1 weights
         const BeaGeom g = bea_geom(m);
         const uint16_t *Vu = (const uint16_t *)rd.cross_vecs;
         const int pc0 = (m.d_item + m.d_attn) / 8;
@@ -609,7 +609,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_split(Model m, Batch b, cha
             store_stream(piece(pc0 + pc), o8);
         }
     }
-    if (m.cross_mode == 3) {
+    if (m.cross_mode == 3 && !m.cross_in_mlp) {      // unless the block is folded into the user's layer-1 weights
         const BeaGeom g = bea_geom(m);
         const uint16_t *Vu = (const uint16_t *)rd.cross_vecs;
         const int pc0 = (m.d_item + m.d_attn) / 8;
@@ -737,7 +737,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     const bool hadamard = m.cross_mode == 1 && !m.cross_in_mlp;      // else the MLP chain forms the Hadamard products itself
     if (hadamard)
         for (int i = threadIdx.x; i < m.d_item / 8; i += RES_WAVES * 64) su[i] = ((const bf16x8 *)rd.cross_vecs)[i];
-    const bool bea = m.cross_mode == 3;
+    const bool bea = m.cross_mode == 3 && !m.cross_in_mlp;           // else it is folded into the user's layer-1 weights
     const BeaGeom bg = bea_geom(m);
     if (bea) {
         // the request's user-side vectors as A fragments (k-step major), in the LDS the Hadamard operand would take

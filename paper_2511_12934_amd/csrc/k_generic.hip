@@ -151,8 +151,8 @@ __global__ __launch_bounds__(256) void k_attn_generic(Model m, Batch b, T *__res
         }
         if (on) {
             T *xc = xrow + m.d_item + da;
-            if (m.cross_mode == 1 && m.cross_in_mlp) {
-                // the MLP chain forms the Hadamard products itself
+            if (m.cross_in_mlp) {
+                // the MLP chain forms the Hadamard products itself, or the block is folded into the user's layer-1 weights
             } else if (m.cross_mode == 1) {
                 for (int k = lane; k < m.d_item; k += 64) st_f<T>(xc + k, ld_f<T>(uc + k) * sh_e[k]);
             } else if (m.cross_mode == 2) {

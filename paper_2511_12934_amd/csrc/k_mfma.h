@@ -80,6 +80,7 @@ hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const 
 // k_mlp_mfma.hip
 int mlp_mfma_variant(const Model &m);
 bool mlp_chain_forms_cross(int variant, const Model &m);
+bool mlp_chain_folds_cross(int variant, const Model &m);
 // bytes per user slot of layer 1's weights with the Hadamard cross block folded in (k_stage.h: fold_w0_block)
 inline size_t mlp_w0_user_bytes(const Model &m) { return (size_t)m.dims[1] * (m.d_item + m.d_attn) * 2; }
 hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const void *X, const MlpPack &pk,

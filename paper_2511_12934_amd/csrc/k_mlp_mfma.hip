@@ -46,6 +46,20 @@ bool mlp_chain_forms_cross(int variant, const Model &m)
     return false;
 }
 
+// Can the cross block be folded into each user's layer-1 weights (Model::cross_in_mlp == 2; k_stage.h: fold_w0_block)?
+// It must be linear in the item vector with coefficients that depend on the user alone -- the Hadamard block
+// u (.) e, and BEA's w^ V, whose weights w^ are the item row's last entries (Sec. 4.1) -- and layer 1 without it,
+// [item | attention], must be a width the `f` chains are built for.
+bool mlp_chain_folds_cross(int variant, const Model &m)
+{
+    if (m.dtype != 1) return false;
+    if (m.cross_mode == 1) return mlp_chain_forms_cross(variant, m);
+    if (m.cross_mode != 3 || m.k1 != m.d_item + m.d_attn + m.d_cv || m.d_cv % 16 || m.n_cross > m.d_item) return false;
+    if (m.d_cv > 64 || m.n_cross * m.d_cv > 2048) return false;      // what a staging block keeps of the user's vectors (k_stage.h)
+    const int k = m.d_item + m.d_attn;
+    return ((variant == 0 || variant == 1) && k == 128) || (variant == 2 && k == 256);
+}
+
 // ---- weights into fragment order --------------------------------------------
 // dst[((rt * KS + j) * 64 + lane) * 8 + s] = W[32 rt + lane % 32][col0 + k(j, lane / 32, s)]
 // first layer (activations read from memory):   k = 16 j + 8 h + s

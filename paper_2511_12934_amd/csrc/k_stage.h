@@ -223,13 +223,20 @@ __device__ __forceinline__ void user_fold_block(int slot, int part, const Model 
     if (run == 0 && on) bias1[(size_t)slot * h1 + n] = (((b1 ? b1[n] : 0.f) + acc) + part_sum[0][lane]) + (part_sum[1][lane] + part_sum[2][lane]);
 }
 
-// a2 -- layer 1's weights of user slot `slot` with the Hadamard cross block folded in (Model::cross_in_mlp == 2):
-// the cross block's share of a layer-1 pre-activation, sum_k W1c[n, k] u_k e_k, is linear in the item vector e, so
+// a2 -- layer 1's weights of user slot `slot` with the cross block folded in (Model::cross_in_mlp == 2).
+// Hadamard (Sec. 3.3): the block's share of a layer-1 pre-activation, sum_k W1c[n, k] u_k e_k, is linear in the item
+// vector e, so
 //   W'[n, k] = bf16(W1e[n, k] + u_k W1c[n, k])        (the product is exact in fp32, the sum rounded once)
-// takes its place and layer 1 contracts over [item | attention] only.  Source and result are in the MLP chain's
+// takes its place and layer 1 contracts over [item | attention] only.
+// BEA (Sec. 4.1, Algorithm 1 step 4): the block is v^ = w^ V with the bridge weights w^ = the item row's last n_cross
+// entries, so its share is sum_j e[d_item - n_cross + j] M[n, j] with M = W1c V^T, a matrix of the user alone:
+//   W'[n, d_item - n_cross + j] = bf16(W1e[n, .] + sum_f W1c[n, f] V[j, f])   (fp32 sums in the order of f).  Source and result are in the MLP chain's
 // fragment order (k_mlp_mfma.hip): fragment (row tile rt, k-step j) = 64 lanes x 8 values, lane (n = 32 rt + lane % 32,
 // h = lane / 32) holding k = 16 j + 8 h + s; the source has K1 / 16 k-steps [item | attention | cross] per row tile,
 // the result (d_item + d_attn) / 16; the attention block's fragments are copied.  One 16-byte piece a thread.
+constexpr int FOLD_PIECES = 4;              // 16-byte pieces of the result a thread makes
+constexpr int FOLD_BEA_V = 2048;            // BEA: n_cross * d_cv values of the user's vectors a block keeps in LDS
+constexpr int FOLD_BEA_DCV = 64;            // ... and the widest vector
 struct FoldW0 {
     const uint4 *src;           // the model's layer-1 fragments, [H1 / 32][K1 / 16][64] pieces
     uint4 *dst;                 // [slot][H1 / 32][(d_item + d_attn) / 16][64] pieces
@@ -250,11 +257,67 @@ template <class Reqs>
 __device__ __forceinline__ void fold_w0_block(int slot, int part, const Model &m, const Reqs &src, const FoldW0 &f)
 {
     const int ks_e = m.d_item / 16, ks_new = (m.d_item + m.d_attn) / 16, ks_old = m.k1 / 16;
-    const int p = part * 256 + (int)threadIdx.x;                 // piece of the slot's result
-    if (p >= m.dims[1] / 32 * ks_new * 64) return;
+    const int n_piece = m.dims[1] / 32 * ks_new * 64;
+    // BEA: the user's vectors (at most FOLD_BEA_V values: 4 KB) once per block, in LDS: every lane of a wave reads the
+    // same entry at a time
+    __shared__ uint4 sV[FOLD_BEA_V / 8];
+    if (m.cross_mode == 3) {
+        const uint4 *Vg = (const uint4 *)src.slot_desc(slot).cross_vecs;            // [n_cross, d_cv]
+        for (int i = threadIdx.x; i < m.n_cross * m.d_cv / 8; i += 256) sV[i] = Vg[i];
+        __syncthreads();
+    }
+    // FOLD_PIECES pieces a thread (few, fat blocks: the launch's blocks all carry the gather's LDS, and a second round of
+    // them would cost more than the pieces do)
+#pragma unroll
+    for (int it = 0; it < FOLD_PIECES; ++it) {
+    const int p = min((part * FOLD_PIECES + it) * 256 + (int)threadIdx.x, n_piece - 1);     // piece of the slot's result (past the end: the last again)
     const int lane = p & 63, j = (p >> 6) % ks_new, rt = (p >> 6) / ks_new, h = lane >> 5;
     uint4 out = f.src[(size_t)(rt * ks_old + j) * 64 + lane];
-    if (j < ks_e) {
+    if (m.cross_mode == 3) {
+        const int w0 = m.d_item - m.n_cross, k0 = 16 * j + 8 * h;       // this piece holds k0 .. k0 + 7 of row n
+        if (j < ks_e && k0 + 8 > w0) {
+            auto lo = [](uint32_t v) { return __uint_as_float(v << 16); };
+            auto hi = [](uint32_t v) { return __uint_as_float(v & 0xFFFF0000u); };
+            // row n of W1c, eight entries a piece (a piece index past the row re-reads the last: no load under a condition)
+            const int nf8 = m.d_cv / 8;
+            uint4 wc[FOLD_BEA_DCV / 8];
+#pragma unroll
+            for (int f8 = 0; f8 < FOLD_BEA_DCV / 8; ++f8) {
+                const int g = f8 < nf8 ? f8 : nf8 - 1;
+                wc[f8] = f.src[(size_t)(rt * ks_old + ks_new + (g >> 1)) * 64 + (lane & 31) + 32 * (g & 1)];
+            }
+            float acc[8];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                acc[s] = 0.f;
+                const int jb = k0 + s - w0;
+                if (jb < 0) continue;
+#pragma unroll
+                for (int f8 = 0; f8 < FOLD_BEA_DCV / 8; ++f8) {
+                    if (f8 >= nf8) break;
+                    const uint4 vv = sV[jb * nf8 + f8];
+                    const uint32_t ww[4] = {wc[f8].x, wc[f8].y, wc[f8].z, wc[f8].w}, vw[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        acc[s] = fmaf(lo(ww[i]), lo(vw[i]), acc[s]);
+                        acc[s] = fmaf(hi(ww[i]), hi(vw[i]), acc[s]);
+                    }
+                }
+            }
+            auto bf = [](float v) {
+                const uint32_t b = __float_as_uint(v);
+                return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+            };
+            uint32_t ow[4] = {out.x, out.y, out.z, out.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t a = k0 + 2 * i >= w0 ? bf(lo(ow[i]) + acc[2 * i]) : (ow[i] & 0xFFFFu);
+                const uint32_t b2 = k0 + 2 * i + 1 >= w0 ? bf(hi(ow[i]) + acc[2 * i + 1]) : (ow[i] >> 16);
+                ow[i] = a | (b2 << 16);
+            }
+            out = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+        }
+    } else if (j < ks_e) {
         const uint4 wc = f.src[(size_t)(rt * ks_old + ks_new + j) * 64 + lane];
         const uint4 u = ((const uint4 *)src.slot_desc(slot).cross_vecs)[2 * j + h];
         out.x = fold_pair(out.x, wc.x, u.x);
@@ -263,6 +326,7 @@ __device__ __forceinline__ void fold_w0_block(int slot, int part, const Model &m
         out.w = fold_pair(out.w, wc.w, u.w);
     }
     f.dst[(size_t)slot * (f.stride / 16) + p] = out;
+    }
 }
 
 // a2 -- K and V of user slot `slot` (the tensors of the request that stands for it), head hd, 64-key stage st into MFMA fragment order, and max |k_t| of the stage.

@@ -164,7 +164,7 @@ hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void 
         a.w0.src = (const uint4 *)plan.wpack[0];
         a.w0.dst = (uint4 *)plan.w0_user;
         a.w0.stride = plan.w0_stride;
-        a.w0.blocks_per_slot = (m.dims[1] / 32 * ((m.d_item + m.d_attn) / 16) * 64 + 255) / 256;
+        a.w0.blocks_per_slot = (m.dims[1] / 32 * ((m.d_item + m.d_attn) / 16) * 64 + 256 * FOLD_PIECES - 1) / (256 * FOLD_PIECES);
         a.n_w0 = b.n_slots * a.w0.blocks_per_slot;
     }
     const int n_gather = gather ? b.n_blk : 0;      // none when the attention kernel indexes the table itself

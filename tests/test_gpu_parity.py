@@ -536,10 +536,16 @@ def test_bea_cross_on_the_shape_agnostic_kernels(R, torch, dtype, n_bridges, d_o
 
 @pytest.mark.parametrize("shape", ["resident_16", "resident_pad_10", "resident_two_ksteps_20", "streaming_16",
                                    "heads32_wide_item"])
-def test_bea_cross_on_the_mfma_kernels(R, torch, shape):
+@pytest.mark.parametrize("fold", [False, True])
+def test_bea_cross_on_the_mfma_kernels(R, torch, monkeypatch, shape, fold):
     """The weighted sum as an MFMA inside both attention kernels: 16 bridges (one k-step), 10 (window entries in
     front of the weights meet zero rows), 20 (two k-steps), the streaming kernel (L = 1000), and 4 heads of 32 with
-    a 128-wide row and a 32-wide output."""
+    a 128-wide row and a 32-wide output.  fold: the default route where the head is a fused chain -- the block's share
+    of layer 1, sum_j w^_j (W1c V^T)[n, j], is folded into each user's layer-1 weights at the bridge weights' columns
+    and no kernel forms the block (the library then shows it as computed from the row and the user's vectors);
+    without (AIF_CROSS_FOLD=0) the attention kernels write it."""
+    if not fold:
+        monkeypatch.setenv("AIF_CROSS_FOLD", "0")
     base = wl.CONFIGS["B3"]
     if shape == "resident_16":
         cfg = base.scaled(n_items=3000)
@@ -562,6 +568,8 @@ def test_bea_cross_on_the_mfma_kernels(R, torch, shape):
     reqs = [(users[0], sampler.sample(rng, 333)), (users[1], sampler.sample(rng, 600))]
     zs, _, _, ctx = run_batch(R, torch, cfg, model, R.to_device(table, "bf16"), reqs)
     assert ctx.aif_stage_kind("attention") == 1
+    folded = fold and shape != "heads32_wide_item"          # that head is no fused chain: nothing to fold into
+    assert ctx.aif_mlp_layer1_width() == (cfg.d_item + cfg.d_attn if folded else cfg.d_in - cfg.d_user)
     # the resident kernel indexes the table itself and takes the bridge weights from the table row
     assert ctx.aif_stage_kind("gather") == (0 if shape == "streaming_16" else 2)
     for i, (u, ids) in enumerate(reqs):
@@ -575,6 +583,9 @@ def test_bea_cross_on_the_mfma_kernels(R, torch, shape):
         assert np.all(np.abs(c - ref.cross) <= tol), f"BEA cross, request {i}"
         if i == 0:
             assert_logits_close("bf16", zs[i], ref.logits, f"BEA {shape}")
+        else:                                               # inputs of unit scale: relative to the request's logits
+            from helpers import assert_bf16_logits_tight
+            assert_bf16_logits_tight(zs[i], ref.logits, f"BEA {shape}, request {i}")
 
 
 # ---------------------------------------------------------------------------
