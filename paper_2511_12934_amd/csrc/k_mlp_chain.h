@@ -187,7 +187,14 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
 
     // blocks 0 .. n_pairs - 1 take two tiles each, the blocks after them the remaining tiles one by one
     const bool has_next = (int)blockIdx.x < n_pairs;
-    const int tile0 = has_next ? 2 * (int)blockIdx.x : (int)blockIdx.x + n_pairs;
+    // UW: workgroups go to the 8 XCDs in turn, each with an L2 of its own; every XCD takes a contiguous run of the pairs,
+    // so that the tiles that stream one user's layer-1 weights share an L2 instead of all eight fetching them
+    int pair = (int)blockIdx.x;
+    if constexpr (UW) {
+        const int per_xcd = n_pairs >> 3;
+        if (pair < 8 * per_xcd) pair = (pair & 7) * per_xcd + (pair >> 3);
+    }
+    const int tile0 = has_next ? 2 * pair : (int)blockIdx.x + n_pairs;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, col = lane & 31, h = lane >> 5;
     const int wave_u = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // The block's start is a chain of dependent memory round trips; keep it short: the weight stream
