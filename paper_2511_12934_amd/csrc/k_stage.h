@@ -258,12 +258,16 @@ __device__ __forceinline__ void fold_w0_block(int slot, int part, const Model &m
 {
     const int ks_e = m.d_item / 16, ks_new = (m.d_item + m.d_attn) / 16, ks_old = m.k1 / 16;
     const int n_piece = m.dims[1] / 32 * ks_new * 64;
-    // BEA: the user's vectors (at most FOLD_BEA_V values: 4 KB) once per block, in LDS: every lane of a wave reads the
-    // same entry at a time
-    __shared__ uint4 sV[FOLD_BEA_V / 8];
+    // BEA: the user's vectors (at most FOLD_BEA_V values) once per block, widened to fp32, in LDS: every lane of a
+    // wave reads the same entry at a time
+    __shared__ float4 sV[FOLD_BEA_V / 4];
     if (m.cross_mode == 3) {
-        const uint4 *Vg = (const uint4 *)src.slot_desc(slot).cross_vecs;            // [n_cross, d_cv]
-        for (int i = threadIdx.x; i < m.n_cross * m.d_cv / 8; i += 256) sV[i] = Vg[i];
+        const uint2 *Vg = (const uint2 *)src.slot_desc(slot).cross_vecs;            // [n_cross, d_cv], four values a step
+        for (int i = threadIdx.x; i < m.n_cross * m.d_cv / 4; i += 256) {
+            const uint2 v = Vg[i];
+            sV[i] = make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u), __uint_as_float(v.y << 16),
+                                __uint_as_float(v.y & 0xFFFF0000u));
+        }
         __syncthreads();
     }
     // FOLD_PIECES pieces a thread (few, fat blocks: the launch's blocks all carry the gather's LDS, and a second round of
@@ -286,6 +290,16 @@ __device__ __forceinline__ void fold_w0_block(int slot, int part, const Model &m
                 const int g = f8 < nf8 ? f8 : nf8 - 1;
                 wc[f8] = f.src[(size_t)(rt * ks_old + ks_new + (g >> 1)) * 64 + (lane & 31) + 32 * (g & 1)];
             }
+            float wf[FOLD_BEA_DCV];                                     // ... widened once
+#pragma unroll
+            for (int f8 = 0; f8 < FOLD_BEA_DCV / 8; ++f8) {
+                const uint32_t ww[4] = {wc[f8].x, wc[f8].y, wc[f8].z, wc[f8].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {                           // (entries past the row's end: zero, they add nothing)
+                    wf[8 * f8 + 2 * i] = f8 < nf8 ? lo(ww[i]) : 0.f;
+                    wf[8 * f8 + 2 * i + 1] = f8 < nf8 ? hi(ww[i]) : 0.f;
+                }
+            }
             float acc[8];
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
@@ -293,15 +307,12 @@ __device__ __forceinline__ void fold_w0_block(int slot, int part, const Model &m
                 const int jb = k0 + s - w0;
                 if (jb < 0) continue;
 #pragma unroll
-                for (int f8 = 0; f8 < FOLD_BEA_DCV / 8; ++f8) {
-                    if (f8 >= nf8) break;
-                    const uint4 vv = sV[jb * nf8 + f8];
-                    const uint32_t ww[4] = {wc[f8].x, wc[f8].y, wc[f8].z, wc[f8].w}, vw[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        acc[s] = fmaf(lo(ww[i]), lo(vw[i]), acc[s]);
-                        acc[s] = fmaf(hi(ww[i]), hi(vw[i]), acc[s]);
-                    }
+                for (int f4 = 0; f4 < FOLD_BEA_DCV / 4; ++f4) {         // in the order of f; no exit inside: the indices stay constants
+                    const float4 vv = sV[jb * 2 * nf8 + (f4 < 2 * nf8 ? f4 : 2 * nf8 - 1)];
+                    acc[s] = fmaf(wf[4 * f4 + 0], vv.x, acc[s]);
+                    acc[s] = fmaf(wf[4 * f4 + 1], vv.y, acc[s]);
+                    acc[s] = fmaf(wf[4 * f4 + 2], vv.z, acc[s]);
+                    acc[s] = fmaf(wf[4 * f4 + 3], vv.w, acc[s]);
                 }
             }
             auto bf = [](float v) {

@@ -40,6 +40,9 @@ struct StageOneArgs {
     OneFill fill;
 };
 
+// LOG_RV = STAGE_NO_GATHER: the launch has no gather blocks (the attention kernel indexes the table itself) -- built
+// without the gather's LDS buffers, which would otherwise limit how many of the small blocks a compute unit holds
+constexpr int STAGE_NO_GATHER = -2;
 template <int LOG_RV, int DH, class Reqs>
 __device__ __forceinline__ void stage_block(const StageArgs &a, const Reqs &src, int idx)
 {
@@ -59,6 +62,7 @@ __device__ __forceinline__ void stage_block(const StageArgs &a, const Reqs &src,
         return;
     }
     idx -= a.n_w0;
+    if constexpr (LOG_RV == STAGE_NO_GATHER) return;
     if constexpr (LOG_RV >= 3 && LOG_RV <= 5) {
         if (a.m.x_tiled) {
             gather_block_tiled<LOG_RV>(idx, a.table, a.m.n_items, src, a.X, a.xl, a.bad);
@@ -97,7 +101,8 @@ static hipError_t launch_stage_dh(const StageArgs &a, int n_gather, const OneFil
     const dim3 grid(a.n_up + a.n_pack + a.n_fold + a.n_w0 + n_gather);
     if (one) {
         const StageOneArgs o{a, *one};
-        switch (a.row_vec) {
+        switch (n_gather ? a.row_vec : STAGE_NO_GATHER) {
+        case STAGE_NO_GATHER: hipLaunchKernelGGL((k_stage_one<STAGE_NO_GATHER, DH>), grid, dim3(256), 0, s, o); break;
         case 8: hipLaunchKernelGGL((k_stage_one<3, DH>), grid, dim3(256), 0, s, o); break;
         case 16: hipLaunchKernelGGL((k_stage_one<4, DH>), grid, dim3(256), 0, s, o); break;
         case 32: hipLaunchKernelGGL((k_stage_one<5, DH>), grid, dim3(256), 0, s, o); break;
@@ -105,7 +110,8 @@ static hipError_t launch_stage_dh(const StageArgs &a, int n_gather, const OneFil
         }
         return hipGetLastError();
     }
-    switch (a.row_vec) {
+    switch (n_gather ? a.row_vec : STAGE_NO_GATHER) {
+    case STAGE_NO_GATHER: hipLaunchKernelGGL((k_stage<STAGE_NO_GATHER, DH>), grid, dim3(256), 0, s, a); break;
     case 8: hipLaunchKernelGGL((k_stage<3, DH>), grid, dim3(256), 0, s, a); break;
     case 16: hipLaunchKernelGGL((k_stage<4, DH>), grid, dim3(256), 0, s, a); break;
     case 32: hipLaunchKernelGGL((k_stage<5, DH>), grid, dim3(256), 0, s, a); break;
