@@ -262,7 +262,11 @@ __global__ __launch_bounds__(256) void k_lsh_din(LshModel m, LshBatch b, const u
 {
     extern __shared__ __align__(16) char lds[];
     float *sa = (float *)lds;                                   // [2][kc][d]
-    const int blk = blockIdx.x;
+    int blk = blockIdx.x;                                       // a contiguous run of blocks per XCD, as in k_lsh_simtier: a user's table in one L2
+    {
+        const int per_xcd = b.n_blk >> 3;
+        if (blk < 8 * per_xcd) blk = (blk & 7) * per_xcd + (blk >> 3);
+    }
     const int r = b.blk_req[blk];
     if (r < 0) return;
     const LshReqDesc rd = b.reqs[r];
@@ -352,7 +356,14 @@ hipError_t launch_lsh_din(const LshModel &m, const LshBatch &b, const uint8_t *s
 template <int DW>
 __global__ __launch_bounds__(256) void k_lsh_simtier(LshModel m, LshBatch b, const uint8_t *__restrict__ sig_table)
 {
-    const int blk = blockIdx.x;
+    // Workgroups go to the 8 XCDs in turn, each with an L2 of its own.  Every XCD takes a contiguous run of the
+    // blocks, so that the blocks of one user -- which all walk that user's history signatures -- share an L2 instead
+    // of all eight fetching them.
+    int blk = blockIdx.x;
+    {
+        const int per_xcd = b.n_blk >> 3;
+        if (blk < 8 * per_xcd) blk = (blk & 7) * per_xcd + (blk >> 3);
+    }
     const int r = b.blk_req[blk];
     if (r < 0) return;
     const LshReqDesc rd = b.reqs[r];
