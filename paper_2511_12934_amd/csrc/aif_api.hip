@@ -288,7 +288,7 @@ aif_status init_impl(const aif_config *cfg, const aif_weights *wts, aif_ctx *c)
         // ... and where the staging launch can do it, the cross block is folded into each user's layer-1 weights instead
         const char *cf = getenv("AIF_CROSS_FOLD");           // testing and measurement: "0" keeps the products in the chain
         const bool foldable = c->mfma.mlp && mlp_chain_folds_cross(c->mfma.mlp_variant, m) && !(cm && cm[0] == '1');
-        if (foldable && stage_fusable(m, c->mfma) && !(cf && cf[0] == '0')) {
+        if (foldable && !(cf && cf[0] == '0')) {
             c->mfma.w0_stride = mlp_w0_user_bytes(m);
             HIP_TRY(nullptr, hipMalloc((void **)&c->mfma.w0_user, c->mfma.w0_stride * (size_t)c->max_users));
             m.cross_in_mlp = 2;
@@ -469,6 +469,7 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         bytes = toff + (size_t)n_req * sizeof(TopkDesc);
     }
     const bool fused = stage_fusable(m, c->mfma);
+    const bool staged_proj = !fused && stage_proj_fusable(m, c->mfma);
     // where it can, the attention kernel takes the item vectors from the table itself
     const bool attn_indexes = c->mfma.attn && !c->separate_gather && attn_gathers(m, b, c->mfma);
     c->attn_indexed = attn_indexes;
@@ -516,12 +517,18 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
     } else {
         if (!attn_indexes) HIP_TRY(c, launch_gather(m, b, c->table, c->X.p, (int32_t *)c->bad.p, s));
         HIP_TRY(c, mark(1));
-        HIP_TRY(c, launch_user_fold(m, b, (const float *)c->w1u.p, c->has_bias[0] ? (const float *)c->bias[0].p : nullptr,
-                                    (float *)c->bias1.p, s));
+        if (staged_proj) {      // K/V packing, user fold and the users' layer-1 weights as one launch
+            HIP_TRY(c, launch_stage_proj(m, b, (const float *)c->w1u.p, c->has_bias[0] ? (const float *)c->bias[0].p : nullptr,
+                                         (float *)c->bias1.p, c->mfma, s));
+        } else {
+            HIP_TRY(c, launch_user_fold(m, b, (const float *)c->w1u.p, c->has_bias[0] ? (const float *)c->bias[0].p : nullptr,
+                                        (float *)c->bias1.p, s));
+            HIP_TRY(c, launch_fold_w0(m, b, c->mfma, s));
+        }
     }
     HIP_TRY(c, mark(2));
     if (c->mfma.attn)
-        HIP_TRY(c, launch_attn_mfma(m, b, c->X.p, c->mfma, fused, s, attn_indexes ? c->table : nullptr,
+        HIP_TRY(c, launch_attn_mfma(m, b, c->X.p, c->mfma, fused || staged_proj, s, attn_indexes ? c->table : nullptr,
                                     attn_indexes ? (int32_t *)c->bad.p : nullptr));
     else
         HIP_TRY(c, launch_attn_generic(m, b, c->X.p, c->has_wq ? (const float *)c->wq.p : nullptr, c->max_seq_len, s));
@@ -683,15 +690,21 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
     c->row_base.clear();                         // aif_peek_features has nothing to show for this call
     c->last_slots = 1;
     const bool attn_indexes = plan.attn && !c->separate_gather && attn_gathers(m, b, plan);
+    const bool staged_proj = !fused && stage_proj_fusable(m, plan);
     c->attn_indexed = attn_indexes;
     if (fused) {
         HIP_TRY(c, launch_stage(m, b, c->table, X, bad, (const float *)c->w1u.p, b1, bias1, plan, !attn_indexes, s, nullptr, &f));
     } else {
         if (!attn_indexes) HIP_TRY(c, launch_gather(m, b, c->table, X, bad, s));
-        HIP_TRY(c, launch_user_fold(m, b, (const float *)c->w1u.p, b1, bias1, s));
+        if (staged_proj) {
+            HIP_TRY(c, launch_stage_proj(m, b, (const float *)c->w1u.p, b1, bias1, plan, s));
+        } else {
+            HIP_TRY(c, launch_user_fold(m, b, (const float *)c->w1u.p, b1, bias1, s));
+            HIP_TRY(c, launch_fold_w0(m, b, plan, s));
+        }
     }
     if (plan.attn)
-        HIP_TRY(c, launch_attn_mfma(m, b, X, plan, fused, s, attn_indexes ? c->table : nullptr, attn_indexes ? bad : nullptr));
+        HIP_TRY(c, launch_attn_mfma(m, b, X, plan, fused || staged_proj, s, attn_indexes ? c->table : nullptr, attn_indexes ? bad : nullptr));
     else
         HIP_TRY(c, launch_attn_generic(m, b, X, c->has_wq ? (const float *)c->wq.p : nullptr, c->max_seq_len, s));
     if (plan.mlp) {
@@ -813,7 +826,7 @@ aif_status aif_peek_features(aif_ctx *c, int32_t request, int32_t first_row, int
         // The workspace's cross block is not written on this route (the MLP chain forms c = u (.) e in registers, or the
         // block is folded into the user's layer-1 weights): show the block as the kernels that write it would form it
         // -- fp32 arithmetic on the bf16 values, rounded to nearest even -- from the item block and the request's operand.
-        const size_t n_op = m.cross_mode == 3 ? (size_t)m.n_cross * m.d_cv : (size_t)m.d_item;
+        const size_t n_op = m.cross_mode == 1 ? (size_t)m.d_item : (size_t)m.n_cross * m.d_cv;
         std::vector<uint16_t> u(n_op);
         HIP_TRY(c, hipMemcpy(u.data(), c->peek_cross[request], n_op * 2, hipMemcpyDeviceToHost));
         auto widen = [](uint16_t b) { uint32_t w = (uint32_t)b << 16; float f; memcpy(&f, &w, 4); return f; };
@@ -832,6 +845,14 @@ aif_status aif_peek_features(aif_ctx *c, int32_t request, int32_t first_row, int
                     for (int j = 0; j < m.n_cross; ++j) acc = fmaf(widen(row[m.d_item - m.n_cross + j]), widen(u[(size_t)j * m.d_cv + f]), acc);
                     row[m.d_item + m.d_attn + f] = narrow(acc);
                 }
+            } else if (m.cross_mode == 2) {     // segment dots: c[j S + s] = <Vc_j, e_s>
+                const int S = m.d_item / m.d_cv;
+                for (int j = 0; j < m.n_cross; ++j)
+                    for (int sg = 0; sg < S; ++sg) {
+                        float acc = 0.f;
+                        for (int k = 0; k < m.d_cv; ++k) acc = fmaf(widen(u[(size_t)j * m.d_cv + k]), widen(row[sg * m.d_cv + k]), acc);
+                        row[m.d_item + m.d_attn + j * S + sg] = narrow(acc);
+                    }
             } else
                 for (int k = 0; k < m.d_item; ++k) row[m.d_item + m.d_attn + k] = narrow(widen(row[k]) * widen(u[k]));
         }

@@ -1177,7 +1177,7 @@ hipError_t launch_attn_variant(const Model &m, const Batch &b, void *X, const Mf
     const size_t stride = plan.pack_stride;
     const int nktp = plan.nktp;
     switch (plan.attn_variant) {
-    case ATTN_VARIANT_PROJ: return launch_attn_proj(m, b, X, plan, small_batch(b), s, gather_table, bad);
+    case ATTN_VARIANT_PROJ: return launch_attn_proj(m, b, X, plan, small_batch(b), kv_packed, s, gather_table, bad);
     case 0: return launch_attn_spec<64>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s);
     case 1: return launch_attn_spec<32>(m, b, X, kvpack, stride, kmax, nktp, kv_packed, gather_table, bad, s);
     default: return hipErrorInvalidValue;

@@ -37,6 +37,7 @@
 // K/V packed per request (k_pack_kv16) stream through a three-slot ring in
 // LDS, eight 32-key tiles (24 KB) per stage, by direct-to-LDS loads.
 #include "k_mfma.h"
+#include "k_stage.h"
 #include "mfma_util.h"
 
 namespace aif {
@@ -72,37 +73,56 @@ __device__ __forceinline__ void store_stream4(void *p, bf16x4 v)
 // Keys >= seq_len read as zero in all rows, the row of ones included; a stage is written whole, so the
 // tiles between the end of the sequence and the end of its last stage are zero and add nothing.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_pack_kv16(Model m, Batch b, char *__restrict__ kvpack, size_t pack_stride,
-                                                   float *__restrict__ kmax, int nktp)
+__device__ __forceinline__ void pack_kv16_block(int st, int hd, int r, const Model &m, const Batch &b, char *__restrict__ kvpack,
+                                                size_t pack_stride, float *__restrict__ kmax, int nktp)
 {
     __shared__ float red[4];
-    const int st = blockIdx.x, hd = blockIdx.y, r = blockIdx.z;        // r: the user slot (one pack per distinct user of the call)
+    // r: the user slot (one pack per distinct user of the call)
     const ReqDesc *rd = b.reqs + slot_request(b, r);
     const int L = rd->seq_len, nkt = (L + 31) >> 5;
     if (P_NT * st >= nkt) return;
     const uint16_t *K = (const uint16_t *)rd->seq_keys, *V = (const uint16_t *)rd->seq_vals;
     const int da = m.d_attn, o = hd * 16;
     uint4 *dst = (uint4 *)(kvpack + (size_t)r * pack_stride + ((size_t)(hd * nktp + P_NT * st) * 3) * 1024);
-    for (int pc = threadIdx.x; pc < P_STAGE_FRAGS * 64; pc += 256) {
+    // Every load of the block is issued before the first is looked at, and none stands under a condition of its own (a
+    // key past the sequence's end re-reads its last key and is zeroed afterwards): six trips of the piece loop would
+    // otherwise be six round trips to memory in a row, eight more inside a piece of V.
+    const int Lm = L - 1;                                   // L >= 1 here (the stage has a key tile)
+    constexpr int TRIPS = P_STAGE_FRAGS * 64 / 256;
+    static_assert(P_STAGE_FRAGS * 64 % 256 == 0, "whole trips");
+    uint32_t v[TRIPS][8];                                   // K: two 8-byte halves in [0..3]; V: eight keys
+#pragma unroll
+    for (int it = 0; it < TRIPS; ++it) {
+        const int pc = threadIdx.x + 256 * it;
+        const int tl = pc / 192, rem = pc - tl * 192, frag = rem >> 6, lane = rem & 63;
+        const int kt = P_NT * st + tl, hh = lane >> 5, row = lane & 31;
+        if (frag == 0) {                                    // the same for a whole wave
+            const uint16_t *kr = K + (size_t)min(32 * kt + row, Lm) * da + o;
+            const uint2 lo = *(const uint2 *)(kr + 4 * hh), hi = *(const uint2 *)(kr + 8 + 4 * hh);
+            v[it][0] = lo.x, v[it][1] = lo.y, v[it][2] = hi.x, v[it][3] = hi.y;
+        } else {
+            const int t0 = 32 * kt + 16 * (frag - 1) + 4 * hh, f = o + min(row, 15);
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl)                  // slot sl <-> key t0 + 8 (sl / 4) + sl % 4
+                v[it][sl] = V[(size_t)min(t0 + 8 * (sl >> 2) + (sl & 3), Lm) * da + f];
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < TRIPS; ++it) {
+        const int pc = threadIdx.x + 256 * it;
         const int tl = pc / 192, rem = pc - tl * 192, frag = rem >> 6, lane = rem & 63;
         const int kt = P_NT * st + tl, hh = lane >> 5, row = lane & 31;
         uint4 out = make_uint4(0, 0, 0, 0);
         if (frag == 0) {
-            const int t = 32 * kt + row;
-            if (t < L) {
-                const uint2 lo = *(const uint2 *)(K + (size_t)t * da + o + 4 * hh);
-                const uint2 hi = *(const uint2 *)(K + (size_t)t * da + o + 8 + 4 * hh);
-                out = make_uint4(lo.x, lo.y, hi.x, hi.y);
-            }
+            if (32 * kt + row < L) out = make_uint4(v[it][0], v[it][1], v[it][2], v[it][3]);
         } else if (row <= 16) {
             const int t0 = 32 * kt + 16 * (frag - 1) + 4 * hh;
             uint32_t w[4];
 #pragma unroll
-            for (int p2 = 0; p2 < 4; ++p2) {     // slots 2 p2 and 2 p2 + 1
+            for (int p2 = 0; p2 < 4; ++p2) {                // slots 2 p2 and 2 p2 + 1
                 const int ta = t0 + 8 * (p2 >> 1) + 2 * (p2 & 1), tb = ta + 1;
-                uint32_t lo = 0, hi = 0;
-                if (ta < L) lo = row < 16 ? V[(size_t)ta * da + o + row] : 0x3F80u;
-                if (tb < L) hi = row < 16 ? V[(size_t)tb * da + o + row] : 0x3F80u;
+                const uint32_t lo = ta < L ? (row < 16 ? v[it][2 * p2] : 0x3F80u) : 0u;
+                const uint32_t hi = tb < L ? (row < 16 ? v[it][2 * p2 + 1] : 0x3F80u) : 0u;
                 w[p2] = lo | (hi << 16);
             }
             out = make_uint4(w[0], w[1], w[2], w[3]);
@@ -135,6 +155,45 @@ __global__ __launch_bounds__(256) void k_pack_kv16(Model m, Batch b, char *__res
         if (threadIdx.x == 0)
             kmax[((size_t)r * m.n_heads + hd) * (nktp / P_NT) + st] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])) * 1.001f;
     }
+}
+
+__global__ __launch_bounds__(256) void k_pack_kv16(Model m, Batch b, char *__restrict__ kvpack, size_t pack_stride,
+                                                   float *__restrict__ kmax, int nktp)
+{
+    pack_kv16_block(blockIdx.x, blockIdx.y, blockIdx.z, m, b, kvpack, pack_stride, kmax, nktp);
+}
+
+// The user-side staging of a call as ONE launch: K/V packing, user fold and (Model::cross_in_mlp == 2) the users'
+// layer-1 weights are independent of one another and small -- one after the other they are three launches' worth
+// of latency in front of the attention kernel.
+struct StageProjArgs {
+    Model m;
+    Batch b;
+    char *kvpack;
+    size_t pack_stride;
+    float *kmax;
+    int32_t nktp, stages;
+    const float *w1u, *b1;
+    float *bias1;
+    int32_t quads;
+    int32_t n_pack, n_fold, n_w0;       // blocks of the three jobs
+    FoldW0 w0;
+};
+__global__ __launch_bounds__(256) void k_stage_proj(StageProjArgs a)
+{
+    int idx = blockIdx.x;
+    if (idx < a.n_pack) {
+        const int st = idx % a.stages, rest = idx / a.stages;
+        pack_kv16_block(st, rest % a.m.n_heads, rest / a.m.n_heads, a.m, a.b, a.kvpack, a.pack_stride, a.kmax, a.nktp);
+        return;
+    }
+    idx -= a.n_pack;
+    if (idx < a.n_fold) {
+        user_fold_block<uint16_t>(idx / a.quads, idx % a.quads, a.m, TableReqs{a.b}, a.w1u, a.b1, a.bias1);
+        return;
+    }
+    idx -= a.n_fold;
+    if (idx < a.n_w0) fold_w0_block(idx / a.w0.blocks_per_slot, idx % a.w0.blocks_per_slot, a.m, TableReqs{a.b}, a.w0);
 }
 
 // ---------------------------------------------------------------------------
@@ -217,7 +276,8 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
         if (lane == 0) skm[hd] = km;
     }
     const int ksc = m.d_cv / 16;                  // SEGDOT: k-steps per segment of the item vector
-    if (m.cross_mode == 2) {
+    const bool segdot = m.cross_mode == 2 && !m.cross_in_mlp;      // else the block is folded into the user's layer-1 weights
+    if (segdot) {
         // fragment kk: [lane][s] = Vc[lane % 32][16 kk + 8 (lane / 32) + s], rows >= n_cross zero
         const uint16_t *Vc = (const uint16_t *)rd.cross_vecs;
         uint16_t *sa16 = (uint16_t *)sa;
@@ -276,7 +336,7 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
             *piece(pc_cross + pc) = o8;
         }
     }
-    if (m.cross_mode == 2) {
+    if (segdot) {
         // A lane ends up with single features of its candidate, 2 bytes each and far apart in the row: they
         // are gathered in LDS (a private strip of the ring's last two slots per wave, rows padded by 16
         // bytes) and leave as whole 16-byte pieces.
@@ -451,10 +511,42 @@ size_t attn_proj_pack_stride(const Model &m, int max_seq_len, int *nktp_out)
     return (size_t)m.n_heads * nktp * 3 * 1024;
 }
 
-hipError_t launch_attn_proj(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool small, hipStream_t s,
-                            const void *gather_table, int32_t *bad)
+bool stage_proj_fusable(const Model &m, const MfmaPlan &plan)
 {
-    if (plan.nktp > 0)
+    return m.dtype == 1 && plan.attn && plan.attn_variant == ATTN_VARIANT_PROJ;
+}
+
+hipError_t launch_stage_proj(const Model &m, const Batch &b, const float *w1u, const float *b1, float *bias1,
+                             const MfmaPlan &plan, hipStream_t s)
+{
+    if (b.n_req == 0) return hipSuccess;
+    StageProjArgs a{};
+    a.m = m;
+    a.b = b;
+    a.kvpack = plan.kvpack;
+    a.pack_stride = plan.pack_stride;
+    a.kmax = plan.kmax;
+    a.nktp = plan.nktp;
+    a.stages = plan.nktp / P_NT;
+    a.w1u = w1u;
+    a.b1 = b1;
+    a.bias1 = bias1;
+    a.quads = (m.dims[1] + FOLD_FEATS - 1) / FOLD_FEATS;
+    a.n_pack = b.n_slots * m.n_heads * a.stages;
+    a.n_fold = b.n_slots * a.quads;
+    if (m.cross_in_mlp == 2) {
+        const hipError_t e = fold_w0_args(m, plan, a.w0);
+        if (e != hipSuccess) return e;
+        a.n_w0 = b.n_slots * a.w0.blocks_per_slot;
+    }
+    hipLaunchKernelGGL(k_stage_proj, dim3(a.n_pack + a.n_fold + a.n_w0), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_proj(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool small, bool kv_packed,
+                            hipStream_t s, const void *gather_table, int32_t *bad)
+{
+    if (plan.nktp > 0 && !kv_packed)
         hipLaunchKernelGGL(k_pack_kv16, dim3(plan.nktp / P_NT, m.n_heads, b.n_slots), dim3(256), 0, s, m, b, plan.kvpack,
                            plan.pack_stride, plan.kmax, plan.nktp);
     switch (m.n_heads) {

@@ -55,6 +55,8 @@ bool attn_gathers(const Model &m, const Batch &b, const MfmaPlan &plan);
 
 // k_stage.hip: gather + user fold + K/V packing as one launch (bf16 models served by the MFMA attention kernel)
 bool stage_fusable(const Model &m, const MfmaPlan &plan);
+// Model::cross_in_mlp == 2 on a model whose staging is not launch_stage: the users' layer-1 weights as a launch of its own
+hipError_t launch_fold_w0(const Model &m, const Batch &b, const MfmaPlan &plan, hipStream_t s);
 // up (optional, only with gather == false): the same launch also carries the call's descriptor tables from mapped
 // pinned host memory to the device (bytes rounded up to 16, as launch_upload); its own blocks then read the request
 // descriptors through the mapping (reqs_mapped), every later kernel reads the device copy that `b` points to.
@@ -104,7 +106,14 @@ constexpr int ATTN_VARIANT_PROJ = 2;      // attn_variant of the projection + 16
 bool attn_proj_ok(const Model &m, bool has_wq);
 size_t attn_proj_pack_stride(const Model &m, int max_seq_len, int *nktp_out);
 // gather_table, bad: as for launch_attn_mfma
-hipError_t launch_attn_proj(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool small, hipStream_t s,
-                            const void *gather_table = nullptr, int32_t *bad = nullptr);
+hipError_t launch_attn_proj(const Model &m, const Batch &b, void *X, const MfmaPlan &plan, bool small, bool kv_packed,
+                            hipStream_t s, const void *gather_table = nullptr, int32_t *bad = nullptr);
+// the user-side staging of this attention kernel's models as one launch: K/V packing, user fold and (Model::cross_in_mlp
+// == 2) the users' layer-1 weights; the attention launch that follows takes kv_packed = true
+bool stage_proj_fusable(const Model &m, const MfmaPlan &plan);
+hipError_t launch_stage_proj(const Model &m, const Batch &b, const float *w1u, const float *b1, float *bias1,
+                             const MfmaPlan &plan, hipStream_t s);
+struct FoldW0;
+hipError_t fold_w0_args(const Model &m, const MfmaPlan &plan, FoldW0 &f);      // k_stage.hip
 
 }  // namespace aif

@@ -35,6 +35,7 @@ hipError_t mlp_chain_c4h(const Model &, const Batch &, const void *, const MlpPa
 hipError_t mlp_chain_c2f(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 hipError_t mlp_chain_c3f(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 hipError_t mlp_chain_c4f(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
+hipError_t mlp_chain_c5f(const Model &, const Batch &, const void *, const MlpPack &, const float *, hipStream_t);
 
 // Can the chain of this variant form the Hadamard cross block itself (Model::cross_in_mlp)?  Layer 1 after the user
 // fold must be exactly [item | attention | item (.) u] with the item width the kernel was built for.
@@ -54,6 +55,9 @@ bool mlp_chain_folds_cross(int variant, const Model &m)
 {
     if (m.dtype != 1) return false;
     if (m.cross_mode == 1) return mlp_chain_forms_cross(variant, m);
+    if (m.cross_mode == 2)      // segment dots: whole k-steps per segment, what a staging block keeps of the vectors (k_stage.h)
+        return variant == 3 && m.k1 == m.d_item + m.d_attn + m.d_cross && m.d_item + m.d_attn == 384 && m.d_cv % 16 == 0 &&
+               m.d_item % m.d_cv == 0 && m.n_cross <= 32 && m.n_cross * m.d_cv <= 2048;
     if (m.cross_mode != 3 || m.k1 != m.d_item + m.d_attn + m.d_cv || m.d_cv % 16 || m.n_cross > m.d_item) return false;
     if (m.d_cv > 64 || m.n_cross * m.d_cv > 2048) return false;      // what a staging block keeps of the user's vectors (k_stage.h)
     const int k = m.d_item + m.d_attn;
@@ -108,7 +112,7 @@ hipError_t launch_mlp_variant(int variant, const Model &m, const Batch &b, const
     case 0: return m.cross_in_mlp == 2 ? mlp_chain_c2f(m, b, X, pk, bias1, s) : m.cross_in_mlp ? mlp_chain_c2h(m, b, X, pk, bias1, s) : mlp_chain_c2(m, b, X, pk, bias1, s);
     case 1: return m.cross_in_mlp == 2 ? mlp_chain_c3f(m, b, X, pk, bias1, s) : m.cross_in_mlp ? mlp_chain_c3h(m, b, X, pk, bias1, s) : mlp_chain_c3(m, b, X, pk, bias1, s);
     case 2: return m.cross_in_mlp == 2 ? mlp_chain_c4f(m, b, X, pk, bias1, s) : m.cross_in_mlp ? mlp_chain_c4h(m, b, X, pk, bias1, s) : mlp_chain_c4(m, b, X, pk, bias1, s);
-    case 3: return mlp_chain_c5(m, b, X, pk, bias1, s);
+    case 3: return m.cross_in_mlp == 2 ? mlp_chain_c5f(m, b, X, pk, bias1, s) : mlp_chain_c5(m, b, X, pk, bias1, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -230,13 +230,17 @@ __device__ __forceinline__ void user_fold_block(int slot, int part, const Model 
 // takes its place and layer 1 contracts over [item | attention] only.
 // BEA (Sec. 4.1, Algorithm 1 step 4): the block is v^ = w^ V with the bridge weights w^ = the item row's last n_cross
 // entries, so its share is sum_j e[d_item - n_cross + j] M[n, j] with M = W1c V^T, a matrix of the user alone:
-//   W'[n, d_item - n_cross + j] = bf16(W1e[n, .] + sum_f W1c[n, f] V[j, f])   (fp32 sums in the order of f).  Source and result are in the MLP chain's
+//   W'[n, d_item - n_cross + j] = bf16(W1e[n, .] + sum_f W1c[n, f] V[j, f])   (fp32 sums in the order of f).
+// Segment dots (Sec. 3.3; c[j S + s] = <Vc_j, e_s> over the S = d_item / d_cv segments e_s of the item vector): the
+// share is sum_s sum_k e[s d_cv + k] sum_j W1c[n, j S + s] Vc[j, k], so
+//   W'[n, s d_cv + k] = bf16(W1e[n, .] + sum_j W1c[n, j S + s] Vc[j, k])      (fp32 sums in the order of j).  Source and result are in the MLP chain's
 // fragment order (k_mlp_mfma.hip): fragment (row tile rt, k-step j) = 64 lanes x 8 values, lane (n = 32 rt + lane % 32,
 // h = lane / 32) holding k = 16 j + 8 h + s; the source has K1 / 16 k-steps [item | attention | cross] per row tile,
 // the result (d_item + d_attn) / 16; the attention block's fragments are copied.  One 16-byte piece a thread.
 constexpr int FOLD_PIECES = 4;              // 16-byte pieces of the result a thread makes
 constexpr int FOLD_BEA_V = 2048;            // BEA: n_cross * d_cv values of the user's vectors a block keeps in LDS
 constexpr int FOLD_BEA_DCV = 64;            // ... and the widest vector
+constexpr int FOLD_SEG_VECS = 32;           // segment dots: the most vectors
 struct FoldW0 {
     const uint4 *src;           // the model's layer-1 fragments, [H1 / 32][K1 / 16][64] pieces
     uint4 *dst;                 // [slot][H1 / 32][(d_item + d_attn) / 16][64] pieces
@@ -261,7 +265,7 @@ __device__ __forceinline__ void fold_w0_block(int slot, int part, const Model &m
     // BEA: the user's vectors (at most FOLD_BEA_V values) once per block, widened to fp32, in LDS: every lane of a
     // wave reads the same entry at a time
     __shared__ float4 sV[FOLD_BEA_V / 4];
-    if (m.cross_mode == 3) {
+    if (m.cross_mode == 3 || m.cross_mode == 2) {
         const uint2 *Vg = (const uint2 *)src.slot_desc(slot).cross_vecs;            // [n_cross, d_cv], four values a step
         for (int i = threadIdx.x; i < m.n_cross * m.d_cv / 4; i += 256) {
             const uint2 v = Vg[i];
@@ -269,6 +273,65 @@ __device__ __forceinline__ void fold_w0_block(int slot, int part, const Model &m
                                 __uint_as_float(v.y & 0xFFFF0000u));
         }
         __syncthreads();
+    }
+    if (m.cross_mode == 2) {
+        // Segment dots: a thread takes one k-step (two 16-byte pieces) of one (row n, segment sg) of the user's weights --
+        // entries W'[n, sg d_cv + 16 qk ..], which use the n_cross weights W1c[n, jv S + sg] -- and its share of the
+        // attention block's pieces (copies).
+        const int S = m.d_item / m.d_cv, H1 = m.dims[1], ksc = m.d_cv / 16;
+        const int t = part * 256 + (int)threadIdx.x;                    // row-minor: a wave's lanes are consecutive rows
+        if (t >= H1 * S * ksc) return;
+        const int qk = t / (H1 * S), sg = (t / H1) % S, n = t % H1, rt = n >> 5, ln = n & 31;
+        auto lo = [](uint32_t v) { return __uint_as_float(v << 16); };
+        auto hi = [](uint32_t v) { return __uint_as_float(v & 0xFFFF0000u); };
+        auto bf = [](float v) {
+            const uint32_t b = __float_as_uint(v);
+            return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+        };
+        // entry c of row n of W1c is slot c % 8 of lane n % 32 + 32 ((c % 16) / 8) of cross k-step c / 16; a vector past
+        // the last re-reads the last and counts for nothing
+        const uint16_t *src16 = (const uint16_t *)f.src;
+        float wj[FOLD_SEG_VECS];
+#pragma unroll
+        for (int jv = 0; jv < FOLD_SEG_VECS; ++jv) {
+            const int c = (jv < m.n_cross ? jv : m.n_cross - 1) * S + sg;
+            const uint16_t w = src16[((size_t)(rt * ks_old + ks_new + (c >> 4)) * 64 + ln + 32 * ((c >> 3) & 1)) * 8 + (c & 7)];
+            wj[jv] = jv < m.n_cross ? __uint_as_float((uint32_t)w << 16) : 0.f;
+        }
+        uint4 *dslot = f.dst + (size_t)slot * (f.stride / 16);
+        // the two halves of k-step sg ksc + qk; both asked for before the first is looked at
+        const int j = sg * ksc + qk;
+        const uint4 wes[2] = {f.src[(size_t)(rt * ks_old + j) * 64 + ln], f.src[(size_t)(rt * ks_old + j) * 64 + ln + 32]};
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int kk0 = 16 * qk + 8 * h;
+            const uint4 we = wes[h];
+            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int jv = 0; jv < FOLD_SEG_VECS; ++jv) {                // in the order of the vectors; no exit inside
+                const int row = jv < m.n_cross ? jv : m.n_cross - 1;
+                const float4 va = sV[(row * m.d_cv + kk0) / 4], vb = sV[(row * m.d_cv + kk0) / 4 + 1];
+                acc[0] = fmaf(wj[jv], va.x, acc[0]);
+                acc[1] = fmaf(wj[jv], va.y, acc[1]);
+                acc[2] = fmaf(wj[jv], va.z, acc[2]);
+                acc[3] = fmaf(wj[jv], va.w, acc[3]);
+                acc[4] = fmaf(wj[jv], vb.x, acc[4]);
+                acc[5] = fmaf(wj[jv], vb.y, acc[5]);
+                acc[6] = fmaf(wj[jv], vb.z, acc[6]);
+                acc[7] = fmaf(wj[jv], vb.w, acc[7]);
+            }
+            uint32_t ow[4] = {we.x, we.y, we.z, we.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ow[i] = bf(lo(ow[i]) + acc[2 * i]) | (bf(hi(ow[i]) + acc[2 * i + 1]) << 16);
+            dslot[(size_t)(rt * ks_new + j) * 64 + ln + 32 * h] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+        }
+        // the attention block's fragments, copied: piece (row tile, k-step ks_e + ja, lane)
+        const int ks_a = ks_new - ks_e, n_copy = H1 / 32 * ks_a * 64;
+        for (int i = t; i < n_copy; i += H1 * S * ksc) {
+            const int lane = i & 63, ja = (i >> 6) % ks_a, rt2 = (i >> 6) / ks_a;
+            dslot[(size_t)(rt2 * ks_new + ks_e + ja) * 64 + lane] = f.src[(size_t)(rt2 * ks_old + ks_e + ja) * 64 + lane];
+        }
+        return;
     }
     // FOLD_PIECES pieces a thread (few, fat blocks: the launch's blocks all carry the gather's LDS, and a second round of
     // them would cost more than the pieces do)

@@ -120,6 +120,33 @@ static hipError_t launch_stage_dh(const StageArgs &a, int n_gather, const OneFil
     return hipGetLastError();
 }
 
+// the fold of the cross block into the users' layer-1 weights as a launch of its own (models whose staging is not k_stage)
+__global__ __launch_bounds__(256) void k_fold_w0(Model m, Batch b, FoldW0 f)
+{
+    fold_w0_block(blockIdx.x / f.blocks_per_slot, blockIdx.x % f.blocks_per_slot, m, TableReqs{b}, f);
+}
+
+hipError_t fold_w0_args(const Model &m, const MfmaPlan &plan, FoldW0 &f)
+{
+    if (!plan.w0_user || !plan.wpack[0]) return hipErrorInvalidValue;
+    f.src = (const uint4 *)plan.wpack[0];
+    f.dst = (uint4 *)plan.w0_user;
+    f.stride = plan.w0_stride;
+    f.blocks_per_slot = m.cross_mode == 2 ? (m.dims[1] * (m.d_item / 16) + 255) / 256             // a thread per (row, item k-step)
+                                          : (m.dims[1] / 32 * ((m.d_item + m.d_attn) / 16) * 64 + 256 * FOLD_PIECES - 1) / (256 * FOLD_PIECES);
+    return hipSuccess;
+}
+
+hipError_t launch_fold_w0(const Model &m, const Batch &b, const MfmaPlan &plan, hipStream_t s)
+{
+    if (m.cross_in_mlp != 2 || b.n_slots == 0) return hipSuccess;
+    FoldW0 f{};
+    const hipError_t e = fold_w0_args(m, plan, f);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_fold_w0, dim3(b.n_slots * f.blocks_per_slot), dim3(256), 0, s, m, b, f);
+    return hipGetLastError();
+}
+
 bool stage_fusable(const Model &m, const MfmaPlan &plan)
 {
     return m.dtype == 1 && plan.attn && (m.d_head == 64 || m.d_head == 32);
@@ -166,11 +193,8 @@ hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void 
     a.n_w0 = 0;
     a.w0 = FoldW0{};
     if (m.cross_in_mlp == 2) {
-        if (!plan.w0_user || !plan.wpack[0]) return hipErrorInvalidValue;
-        a.w0.src = (const uint4 *)plan.wpack[0];
-        a.w0.dst = (uint4 *)plan.w0_user;
-        a.w0.stride = plan.w0_stride;
-        a.w0.blocks_per_slot = (m.dims[1] / 32 * ((m.d_item + m.d_attn) / 16) * 64 + 256 * FOLD_PIECES - 1) / (256 * FOLD_PIECES);
+        const hipError_t e = fold_w0_args(m, plan, a.w0);
+        if (e != hipSuccess) return e;
         a.n_w0 = b.n_slots * a.w0.blocks_per_slot;
     }
     const int n_gather = gather ? b.n_blk : 0;      // none when the attention kernel indexes the table itself

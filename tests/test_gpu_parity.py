@@ -783,9 +783,10 @@ def test_hadamard_cross_folded_into_the_users_layer1_weights(R, torch, monkeypat
 def test_widest_head_as_one_fused_chain(R, torch, monkeypatch):
     """C5's head (448 -> 1024 -> 512 -> 256 -> 1 after the user fold) runs as ONE launch with a candidate's activations
     in registers.  Enough candidates (more 128-candidate tiles than compute units) that blocks take two tiles each as
-    well as one; non-zero biases; against the oracle to the scale-aware bound, against the one-launch-per-layer route
-    (AIF_MLP_LAYERED=1: same products, hidden activations through HBM) within two roundings, and sliced vs whole
-    bit for bit."""
+    well as one; non-zero biases; against the oracle to the scale-aware bound -- with the segment-dot cross block
+    folded into the users' layer-1 weights (the default: layer 1 over 384 columns) and with the block written by the
+    attention kernel (AIF_CROSS_FOLD=0) --, the latter against the one-launch-per-layer route (AIF_MLP_LAYERED=1: same
+    products, hidden activations through HBM) within two roundings, and sliced vs whole bit for bit."""
     from helpers import assert_bf16_logits_tight
     cfg = wl.CONFIGS["C5"].scaled(n_items=20000, seq_len=64)
     _say("C5 head, fused chain: 3 requests x 12000 candidates")
@@ -797,14 +798,24 @@ def test_widest_head_as_one_fused_chain(R, torch, monkeypatch):
     reqs = [(wl.make_user(cfg, rng), sampler.sample(rng, n)) for n in (12000, 11999, 12001)]
     zs, _, _, ctx = run_batch(R, torch, cfg, model, table_dev, reqs)
     assert ctx.aif_stage_kind("mlp") == 1 and ctx.aif_last_error() == ""
+    assert ctx.aif_mlp_layer1_width() == cfg.d_item + cfg.d_attn
+    X_fold = R.peek_features(ctx, cfg, 1, 500)
+    refs = [oracle_scores(cfg, model, table, u, ids, n_threads=16) for u, ids in reqs]
     for i, (u, ids) in enumerate(reqs):
-        ref = oracle_scores(cfg, model, table, u, ids, n_threads=16)
-        assert_logits_close("bf16", zs[i], ref.logits, f"request {i}")
-        e_max, e_rms, z_rms = assert_bf16_logits_tight(zs[i], ref.logits, f"request {i}")
-        print(f"[case] request {i}: max |dz| {e_max:.3e}, rms dz {e_rms:.3e}, rms z {z_rms:.3e}", flush=True)
+        assert_logits_close("bf16", zs[i], refs[i].logits, f"request {i}")
+        e_max, e_rms, z_rms = assert_bf16_logits_tight(zs[i], refs[i].logits, f"request {i}")
+        print(f"[case] folded, request {i}: max |dz| {e_max:.3e}, rms dz {e_rms:.3e}, rms z {z_rms:.3e}", flush=True)
     u, ids = reqs[2]
     parts, _, _, _ = run_batch(R, torch, cfg, model, table_dev, [(u, ids[:1000]), (u, ids[1000:1300]), (u, ids[1300:])])
     assert np.array_equal(np.concatenate(parts), zs[2])
+    monkeypatch.setenv("AIF_CROSS_FOLD", "0")
+    zs, _, _, ctx = run_batch(R, torch, cfg, model, table_dev, reqs)
+    assert ctx.aif_stage_kind("mlp") == 1 and ctx.aif_mlp_layer1_width() == cfg.d_in - cfg.d_user
+    assert_features_close("bf16", X_fold[:, cfg.d_item + cfg.d_attn:], R.peek_features(ctx, cfg, 1, 500)[:, cfg.d_item + cfg.d_attn:],
+                          "the cross block the library shows on the two routes")
+    for i in range(3):
+        e_max, e_rms, z_rms = assert_bf16_logits_tight(zs[i], refs[i].logits, f"request {i}, cross block written")
+        print(f"[case] written, request {i}: max |dz| {e_max:.3e}, rms dz {e_rms:.3e}, rms z {z_rms:.3e}", flush=True)
     monkeypatch.setenv("AIF_MLP_LAYERED", "1")
     zl, _, _, ctx_l = run_batch(R, torch, cfg, model, table_dev, reqs)
     assert ctx_l.aif_stage_kind("mlp") == 1
