@@ -780,6 +780,29 @@ def test_hadamard_cross_folded_into_the_users_layer1_weights(R, torch, monkeypat
     assert np.array_equal(whole.logits.cpu().numpy(), z0[0]) and np.array_equal(other.logits.cpu().numpy(), z0[3])
 
 
+def test_cross_fold_with_the_shape_agnostic_attention_kernel(R, torch):
+    """A bf16 model whose attention has no matrix-core kernel (four heads of 16 without W_q) but whose head is a
+    fused chain: the cross block is still folded into the users' layer-1 weights -- by a launch of its own, the
+    staging not being the fused one -- and the shape-agnostic attention kernel leaves the block unwritten."""
+    from helpers import assert_bf16_logits_tight
+    cfg = small_cfg("bf16", n_items=4000, seq_len=150, d_item=64, d_user=64, d_attn=64, n_heads=4, mlp_dims=(256, 512, 256, 1))
+    _say("cross fold beside the generic attention kernel")
+    rng = np.random.default_rng(515)
+    model = wl.make_model(cfg, seed=3, bias_scale=0.1)
+    table = wl.make_table_host(cfg, rng)
+    sampler = wl.IdSampler(cfg)
+    reqs = [(wl.make_user(cfg, rng, seq_len=L), sampler.sample(rng, n)) for n, L in ((700, 150), (33, 7), (256, 64))]
+    zs, _, _, ctx = run_batch(R, torch, cfg, model, R.to_device(table, cfg.dtype), reqs, max_seq_len=150)
+    assert ctx.aif_stage_kind("attention") == 0 and ctx.aif_stage_kind("mlp") == 1
+    assert ctx.aif_mlp_layer1_width() == cfg.d_item + cfg.d_attn
+    for i, (u, ids) in enumerate(reqs):
+        ref = oracle_scores(cfg, model, table, u, ids, n_threads=4)
+        assert_logits_close("bf16", zs[i], ref.logits, f"request {i}")
+        assert_bf16_logits_tight(zs[i], ref.logits, f"request {i}")
+        X = R.peek_features(ctx, cfg, i, ids.size)
+        assert_features_close("bf16", X[:, cfg.d_item + cfg.d_attn:], ref.cross, f"request {i}: the cross block the library shows")
+
+
 def test_widest_head_as_one_fused_chain(R, torch, monkeypatch):
     """C5's head (448 -> 1024 -> 512 -> 256 -> 1 after the user fold) runs as ONE launch with a candidate's activations
     in registers.  Enough candidates (more 128-candidate tiles than compute units) that blocks take two tiles each as
