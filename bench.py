@@ -51,7 +51,9 @@ def algorithmic_work(cfg, k1=None):
     dims = cfg.mlp_dims
     mlp = 2 * (k1 * dims[1] + sum(dims[l] * dims[l + 1] for l in range(1, len(dims) - 1)))
     attn = 4 * cfg.seq_len * cfg.d_attn + (2 * cfg.d_item * cfg.d_attn if cfg.use_wq else 0)
-    if cfg.cross_mode == 2:
+    if d_cross_moved == 0:
+        pass                                                # folded into the users' weights: no kernel forms the block
+    elif cfg.cross_mode == 2:
         attn += 2 * cfg.d_cross * cfg.d_cross_vec
     elif cfg.cross_mode == 1:
         attn += cfg.d_item
