@@ -36,6 +36,7 @@
 //
 // K/V packed per request (k_pack_kv16) stream through a three-slot ring in
 // LDS, eight 32-key tiles (24 KB) per stage, by direct-to-LDS loads.
+#include <cstdlib>
 #include "k_mfma.h"
 #include "k_stage.h"
 #include "mfma_util.h"
@@ -84,29 +85,32 @@ __device__ __forceinline__ void pack_kv16_block(int st, int hd, int r, const Mod
     const uint16_t *K = (const uint16_t *)rd->seq_keys, *V = (const uint16_t *)rd->seq_vals;
     const int da = m.d_attn, o = hd * 16;
     uint4 *dst = (uint4 *)(kvpack + (size_t)r * pack_stride + ((size_t)(hd * nktp + P_NT * st) * 3) * 1024);
-    // Every load of the block is issued before the first is looked at, and none stands under a condition of its own (a
-    // key past the sequence's end re-reads its last key and is zeroed afterwards): six trips of the piece loop would
-    // otherwise be six round trips to memory in a row, eight more inside a piece of V.
+    // V is needed transposed (a lane holds eight keys of ONE feature), which read straight from memory is eight 2-byte
+    // loads at the row stride per piece.  Instead a thread brings its key's 32-byte slice of V into LDS (thread = key of
+    // the stage; a key past the sequence's end re-reads the last key and is zeroed on the way out) and the pieces are
+    // put together from there.  K's pieces are 16 contiguous bytes of a row each: all asked for before the barrier too,
+    // none under a condition of its own, so the block makes one trip to memory.
+    __shared__ __align__(16) uint16_t sv[32 * P_NT][16];
     const int Lm = L - 1;                                   // L >= 1 here (the stage has a key tile)
     constexpr int TRIPS = P_STAGE_FRAGS * 64 / 256;
-    static_assert(P_STAGE_FRAGS * 64 % 256 == 0, "whole trips");
-    uint32_t v[TRIPS][8];                                   // K: two 8-byte halves in [0..3]; V: eight keys
+    static_assert(P_STAGE_FRAGS * 64 % 256 == 0 && 32 * P_NT == 256, "whole trips; a key per thread");
+    {
+        const uint4 *vr = (const uint4 *)(V + (size_t)min(32 * P_NT * st + (int)threadIdx.x, Lm) * da + o);
+        const uint4 v0 = vr[0], v1 = vr[1];
+        *(uint4 *)&sv[threadIdx.x][0] = v0;
+        *(uint4 *)&sv[threadIdx.x][8] = v1;
+    }
+    uint2 klo[TRIPS], khi[TRIPS];
 #pragma unroll
     for (int it = 0; it < TRIPS; ++it) {
         const int pc = threadIdx.x + 256 * it;
-        const int tl = pc / 192, rem = pc - tl * 192, frag = rem >> 6, lane = rem & 63;
+        const int tl = pc / 192, rem = pc - tl * 192, lane = rem & 63;
         const int kt = P_NT * st + tl, hh = lane >> 5, row = lane & 31;
-        if (frag == 0) {                                    // the same for a whole wave
-            const uint16_t *kr = K + (size_t)min(32 * kt + row, Lm) * da + o;
-            const uint2 lo = *(const uint2 *)(kr + 4 * hh), hi = *(const uint2 *)(kr + 8 + 4 * hh);
-            v[it][0] = lo.x, v[it][1] = lo.y, v[it][2] = hi.x, v[it][3] = hi.y;
-        } else {
-            const int t0 = 32 * kt + 16 * (frag - 1) + 4 * hh, f = o + min(row, 15);
-#pragma unroll
-            for (int sl = 0; sl < 8; ++sl)                  // slot sl <-> key t0 + 8 (sl / 4) + sl % 4
-                v[it][sl] = V[(size_t)min(t0 + 8 * (sl >> 2) + (sl & 3), Lm) * da + f];
-        }
+        const uint16_t *kr = K + (size_t)min(32 * kt + row, Lm) * da + o;     // (asked for by the V pieces' lanes too: no condition)
+        klo[it] = *(const uint2 *)(kr + 4 * hh);
+        khi[it] = *(const uint2 *)(kr + 8 + 4 * hh);
     }
+    __syncthreads();
 #pragma unroll
     for (int it = 0; it < TRIPS; ++it) {
         const int pc = threadIdx.x + 256 * it;
@@ -114,15 +118,15 @@ __device__ __forceinline__ void pack_kv16_block(int st, int hd, int r, const Mod
         const int kt = P_NT * st + tl, hh = lane >> 5, row = lane & 31;
         uint4 out = make_uint4(0, 0, 0, 0);
         if (frag == 0) {
-            if (32 * kt + row < L) out = make_uint4(v[it][0], v[it][1], v[it][2], v[it][3]);
+            if (32 * kt + row < L) out = make_uint4(klo[it].x, klo[it].y, khi[it].x, khi[it].y);
         } else if (row <= 16) {
-            const int t0 = 32 * kt + 16 * (frag - 1) + 4 * hh;
+            const int t0 = 32 * kt + 16 * (frag - 1) + 4 * hh, s0 = t0 - 32 * P_NT * st, f = min(row, 15);
             uint32_t w[4];
 #pragma unroll
-            for (int p2 = 0; p2 < 4; ++p2) {                // slots 2 p2 and 2 p2 + 1
-                const int ta = t0 + 8 * (p2 >> 1) + 2 * (p2 & 1), tb = ta + 1;
-                const uint32_t lo = ta < L ? (row < 16 ? v[it][2 * p2] : 0x3F80u) : 0u;
-                const uint32_t hi = tb < L ? (row < 16 ? v[it][2 * p2 + 1] : 0x3F80u) : 0u;
+            for (int p2 = 0; p2 < 4; ++p2) {                // slots 2 p2 and 2 p2 + 1 <-> keys t0 + 8 (p2 / 2) + 2 (p2 % 2) and the next
+                const int d = 8 * (p2 >> 1) + 2 * (p2 & 1), ta = t0 + d, tb = ta + 1;
+                const uint32_t lo = ta < L ? (row < 16 ? (uint32_t)sv[s0 + d][f] : 0x3F80u) : 0u;
+                const uint32_t hi = tb < L ? (row < 16 ? (uint32_t)sv[s0 + d + 1][f] : 0x3F80u) : 0u;
                 w[p2] = lo | (hi << 16);
             }
             out = make_uint4(w[0], w[1], w[2], w[3]);

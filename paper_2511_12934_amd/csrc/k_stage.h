@@ -240,7 +240,7 @@ __device__ __forceinline__ void user_fold_block(int slot, int part, const Model 
 constexpr int FOLD_PIECES = 4;              // 16-byte pieces of the result a thread makes
 constexpr int FOLD_BEA_V = 2048;            // BEA: n_cross * d_cv values of the user's vectors a block keeps in LDS
 constexpr int FOLD_BEA_DCV = 64;            // ... and the widest vector
-constexpr int FOLD_SEG_VECS = 32;           // segment dots: the most vectors
+constexpr int FOLD_SEG_CHUNK = 16;          // segment dots: vectors taken at a time
 struct FoldW0 {
     const uint4 *src;           // the model's layer-1 fragments, [H1 / 32][K1 / 16][64] pieces
     uint4 *dst;                 // [slot][H1 / 32][(d_item + d_attn) / 16][64] pieces
@@ -291,38 +291,48 @@ __device__ __forceinline__ void fold_w0_block(int slot, int part, const Model &m
         // entry c of row n of W1c is slot c % 8 of lane n % 32 + 32 ((c % 16) / 8) of cross k-step c / 16; a vector past
         // the last re-reads the last and counts for nothing
         const uint16_t *src16 = (const uint16_t *)f.src;
-        float wj[FOLD_SEG_VECS];
-#pragma unroll
-        for (int jv = 0; jv < FOLD_SEG_VECS; ++jv) {
-            const int c = (jv < m.n_cross ? jv : m.n_cross - 1) * S + sg;
-            const uint16_t w = src16[((size_t)(rt * ks_old + ks_new + (c >> 4)) * 64 + ln + 32 * ((c >> 3) & 1)) * 8 + (c & 7)];
-            wj[jv] = jv < m.n_cross ? __uint_as_float((uint32_t)w << 16) : 0.f;
-        }
         uint4 *dslot = f.dst + (size_t)slot * (f.stride / 16);
         // the two halves of k-step sg ksc + qk; both asked for before the first is looked at
         const int j = sg * ksc + qk;
         const uint4 wes[2] = {f.src[(size_t)(rt * ks_old + j) * 64 + ln], f.src[(size_t)(rt * ks_old + j) * 64 + ln + 32]};
+        float acc[2][8];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[h][i] = 0.f;
+        // the vectors in the order of jv, FOLD_SEG_CHUNK at a time (no exit inside a chunk: a vector past the last
+        // re-reads the last and counts for nothing)
+        for (int jv0 = 0; jv0 < m.n_cross; jv0 += FOLD_SEG_CHUNK) {
+            float wj[FOLD_SEG_CHUNK];
+#pragma unroll
+            for (int u = 0; u < FOLD_SEG_CHUNK; ++u) {
+                const int jv = jv0 + u, c = (jv < m.n_cross ? jv : m.n_cross - 1) * S + sg;
+                const uint16_t w = src16[((size_t)(rt * ks_old + ks_new + (c >> 4)) * 64 + ln + 32 * ((c >> 3) & 1)) * 8 + (c & 7)];
+                wj[u] = jv < m.n_cross ? __uint_as_float((uint32_t)w << 16) : 0.f;
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int kk0 = 16 * qk + 8 * h;
+#pragma unroll
+                for (int u = 0; u < FOLD_SEG_CHUNK; ++u) {
+                    const int jv = jv0 + u, row = jv < m.n_cross ? jv : m.n_cross - 1;
+                    const float4 va = sV[(row * m.d_cv + kk0) / 4], vb = sV[(row * m.d_cv + kk0) / 4 + 1];
+                    acc[h][0] = fmaf(wj[u], va.x, acc[h][0]);
+                    acc[h][1] = fmaf(wj[u], va.y, acc[h][1]);
+                    acc[h][2] = fmaf(wj[u], va.z, acc[h][2]);
+                    acc[h][3] = fmaf(wj[u], va.w, acc[h][3]);
+                    acc[h][4] = fmaf(wj[u], vb.x, acc[h][4]);
+                    acc[h][5] = fmaf(wj[u], vb.y, acc[h][5]);
+                    acc[h][6] = fmaf(wj[u], vb.z, acc[h][6]);
+                    acc[h][7] = fmaf(wj[u], vb.w, acc[h][7]);
+                }
+            }
+        }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const int kk0 = 16 * qk + 8 * h;
-            const uint4 we = wes[h];
-            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            uint32_t ow[4] = {wes[h].x, wes[h].y, wes[h].z, wes[h].w};
 #pragma unroll
-            for (int jv = 0; jv < FOLD_SEG_VECS; ++jv) {                // in the order of the vectors; no exit inside
-                const int row = jv < m.n_cross ? jv : m.n_cross - 1;
-                const float4 va = sV[(row * m.d_cv + kk0) / 4], vb = sV[(row * m.d_cv + kk0) / 4 + 1];
-                acc[0] = fmaf(wj[jv], va.x, acc[0]);
-                acc[1] = fmaf(wj[jv], va.y, acc[1]);
-                acc[2] = fmaf(wj[jv], va.z, acc[2]);
-                acc[3] = fmaf(wj[jv], va.w, acc[3]);
-                acc[4] = fmaf(wj[jv], vb.x, acc[4]);
-                acc[5] = fmaf(wj[jv], vb.y, acc[5]);
-                acc[6] = fmaf(wj[jv], vb.z, acc[6]);
-                acc[7] = fmaf(wj[jv], vb.w, acc[7]);
-            }
-            uint32_t ow[4] = {we.x, we.y, we.z, we.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) ow[i] = bf(lo(ow[i]) + acc[2 * i]) | (bf(hi(ow[i]) + acc[2 * i + 1]) << 16);
+            for (int i = 0; i < 4; ++i) ow[i] = bf(lo(ow[i]) + acc[h][2 * i]) | (bf(hi(ow[i]) + acc[h][2 * i + 1]) << 16);
             dslot[(size_t)(rt * ks_new + j) * 64 + ln + 32 * h] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
         }
         // the attention block's fragments, copied: piece (row tile, k-step ks_e + ja, lane)
