@@ -49,7 +49,7 @@ hipError_t scratch_of(int dev, unsigned char **out)
 
 // The descriptor tables of a one-request batch written as a launch of its own (one_fill): for the models whose
 // staging is not the fused launch, which would carry them.
-__global__ __launch_bounds__(256) void k_static_fill(OneFill f) { one_fill(f, blockIdx.x * 256 + threadIdx.x); }
+__global__ __launch_bounds__(256) void k_static_fill(FewFill f) { few_fill(f, blockIdx.x * 256 + threadIdx.x); }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 thread_local std::string g_init_error = "";
@@ -456,7 +456,8 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
     // groups of tiles for the attention kernel that keeps K/V resident, 16-byte aligned after the three tables
     const size_t goff = ((size_t)((char *)(hq + n_slots) - h) + 15) / 16 * 16;
     b.n_streamed = 0;
-    b.n_groups = c->mfma.attn ? attn_plan_groups(m, hd, n_req, c->n_cu, (AttnGroup *)(h + goff), &b.n_streamed) : 0;
+    AttnPlanInfo plan_info{};
+    b.n_groups = c->mfma.attn ? attn_plan_groups(m, hd, n_req, c->n_cu, (AttnGroup *)(h + goff), &b.n_streamed, &plan_info) : 0;
     b.groups = (const AttnGroup *)(d + goff);
     size_t bytes = goff + (size_t)b.n_groups * sizeof(AttnGroup);
     const size_t toff = (bytes + 15) / 16 * 16;
@@ -473,24 +474,30 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
     // where it can, the attention kernel takes the item vectors from the table itself
     const bool attn_indexes = c->mfma.attn && !c->separate_gather && attn_gathers(m, b, c->mfma);
     c->attn_indexed = attn_indexes;
-    // A single request (the latency case) sends its descriptor in the staging launch's arguments and that launch
-    // writes the tables on the device: nothing is uploaded.  Otherwise, when the staging launch has few blocks
-    // (no gather blocks) it carries the tables to the device itself.
-    const bool stage_fills = fused && n_req == 1;
+    // A few requests (the latency cases: one request, or one cut into mini-batches) send their descriptors in the
+    // staging launch's arguments and that launch writes the tables on the device: nothing is uploaded.  Otherwise, when
+    // the staging launch has few blocks (no gather blocks) it carries the tables to the device itself.
+    const bool stage_fills = fused && n_req <= FEW_MAX;
     const bool stage_uploads = fused && !stage_fills && attn_indexes && c->h_stage_dev;
-    OneFill fill{};
+    FewFill fill{};
     if (stage_fills) {
-        fill.rd = hd[0];
-        fill.td = TopkDesc{reqs[0].logits_out, reqs[0].n_cand};
+        for (int r = 0; r < n_req; ++r) {
+            fill.rd[r] = hd[r];
+            fill.td[r] = TopkDesc{reqs[r].logits_out, reqs[r].n_cand};
+        }
+        for (int sl = 0; sl < n_slots; ++sl) fill.slot_req[sl] = hq[sl];
         fill.reqs = (ReqDesc *)d;
         fill.blk_req = (int32_t *)(d + ((char *)hb - h));
         fill.blk_slot = (int32_t *)(d + ((char *)hs - h));
-        fill.slot_req = (int32_t *)(d + ((char *)hq - h));
+        fill.slot_req_dev = (int32_t *)(d + ((char *)hq - h));
         fill.groups = (AttnGroup *)(d + goff);
         fill.topk = k > 0 ? (TopkDesc *)(d + toff) : nullptr;
+        fill.n_req = n_req;
+        fill.n_slots = n_slots;
         fill.n_blk = b.n_blk;
         fill.n_groups = b.n_groups;
-        fill.tiles = (reqs[0].n_cand + 31) / 32;
+        fill.per = plan_info.per;
+        fill.resident = plan_info.resident;
     }
     if (!stage_uploads && !stage_fills) HIP_TRY(c, upload(c, slot, bytes, s));
 
@@ -602,7 +609,7 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
 
     // ---- the call's buffers, laid out in the scratch array ------------------------------------------------------
     const int esz = m.dtype == 0 ? 4 : 2, H1 = m.dims[1];
-    const int rows = round_up(q.n_cand, ROW_BLOCK), n_blk = rows / ROW_BLOCK, tiles = (q.n_cand + 31) / 32;
+    const int rows = round_up(q.n_cand, ROW_BLOCK), n_blk = rows / ROW_BLOCK;
     ReqDesc rd{};
     rd.user_vec = q.user_vec;
     rd.cross_vecs = q.cross_vecs ? q.cross_vecs : q.user_vec;
@@ -617,7 +624,8 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
     if (c->mfma.attn && attn_max_groups((size_t)rows, 1) > (size_t)STATIC_MAX_GROUPS)
         return fail(c, AIF_ERANGE, "n_cand %d: more attention groups than the static call holds (%d)", q.n_cand, STATIC_MAX_GROUPS);
     int n_streamed = 0;
-    const int n_groups = c->mfma.attn ? attn_plan_groups(m, &rd, 1, c->n_cu, tmp, &n_streamed) : 0;
+    AttnPlanInfo plan_info{};
+    const int n_groups = c->mfma.attn ? attn_plan_groups(m, &rd, 1, c->n_cu, tmp, &n_streamed, &plan_info) : 0;
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -646,22 +654,24 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
     hipStream_t s = (hipStream_t)hip_stream;
     unsigned char *base = c->scratch_dev;        // the device address, never the array's name
 
-    OneFill f{};
-    f.rd = rd;
-    f.td = TopkDesc{q.logits_out, q.n_cand};
+    FewFill f{};
+    f.rd[0] = rd;
+    f.td[0] = TopkDesc{q.logits_out, q.n_cand};
     f.reqs = (ReqDesc *)(base + o_req);
     f.blk_req = (int32_t *)(base + o_blk);
     f.blk_slot = (int32_t *)(base + o_bsl);
-    f.slot_req = (int32_t *)(base + o_srq);
+    f.slot_req_dev = (int32_t *)(base + o_srq);
     f.groups = (AttnGroup *)(base + o_grp);
-    f.topk = (TopkDesc *)(base + o_tk);
+    f.topk = k > 0 ? (TopkDesc *)(base + o_tk) : nullptr;
+    f.n_req = 1;
+    f.n_slots = 1;
     f.n_blk = n_blk;
     f.n_groups = n_groups;
-    f.tiles = tiles;
-    f.topk = k > 0 ? f.topk : nullptr;
+    f.per = plan_info.per;
+    f.resident = plan_info.resident;
     const bool fused = stage_fusable(m, c->mfma);
     if (!fused) {                                // else the staging launch writes the tables
-        hipLaunchKernelGGL(k_static_fill, dim3((one_fill_items(f) + 255) / 256), dim3(256), 0, s, f);
+        hipLaunchKernelGGL(k_static_fill, dim3((few_fill_items(f) + 255) / 256), dim3(256), 0, s, f);
         HIP_TRY(c, hipGetLastError());
     }
 
@@ -669,7 +679,7 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
     b.reqs = f.reqs;
     b.blk_req = f.blk_req;
     b.blk_slot = f.blk_slot;
-    b.slot_req = f.slot_req;
+    b.slot_req = f.slot_req_dev;
     b.groups = f.groups;
     b.n_req = 1;
     b.n_blk = n_blk;
@@ -747,6 +757,18 @@ aif_status aif_topk(aif_ctx *c, const float *const *logits, const int32_t *n_can
     if (st != AIF_OK) return st;
     if (n_req == 0) return AIF_OK;
     hipStream_t s = (hipStream_t)hip_stream;
+    if (n_req <= TOPK_FEW) {                     // the descriptors in the kernel's arguments: no staging slot, no upload
+        TopkDesc few[TOPK_FEW];
+        for (int r = 0; r < n_req; ++r) few[r] = TopkDesc{logits[r], n_cand[r]};
+        hipEvent_t *pe = nullptr;
+        if (c->prof_on && (c->prof_mask & (1u << AIF_STAGE_TOPK)) && c->prof_topk_calls < c->prof_max &&
+            c->prof_seen_topk++ % c->prof_every == 0)
+            pe = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
+        if (pe) HIP_TRY(c, hipEventRecord(pe[0], s));
+        HIP_TRY(c, launch_topk_few(few, n_req, k, idx_out, val_out, s));
+        if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
+        return AIF_OK;
+    }
     int slot;
     st = take_slot(c, &slot);
     if (st != AIF_OK) return st;

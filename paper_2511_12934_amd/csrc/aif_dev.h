@@ -143,6 +143,10 @@ struct TopkDesc {
 };
 hipError_t launch_topk(const TopkDesc *descs /*device*/, int n_req, int k, int32_t *idx_out, float *val_out,
                        hipStream_t s);
+// at most TOPK_FEW lists whose descriptors are on the HOST: they travel in the kernel's arguments, nothing is uploaded
+constexpr int TOPK_FEW = 16;
+hipError_t launch_topk_few(const TopkDesc *descs /*host*/, int n_req, int k, int32_t *idx_out, float *val_out,
+                           hipStream_t s);
 
 // init-time repacking (device -> device, any storage type -> fp32)
 hipError_t launch_pack_transposed(int dtype, const void *w, int n_out, int n_in, int col0, int ncols,

@@ -1026,8 +1026,9 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
 // streaming kernels (those that do not fit; all, when the model has no resident kernel).
 size_t attn_max_groups(size_t x_rows, int max_users) { return x_rows / (32 * RES_WAVES) + (size_t)max_users + 1; }
 
-int attn_plan_groups(const Model &m, const ReqDesc *reqs, int n_req, int n_cu, AttnGroup *out, int *n_streamed)
+int attn_plan_groups(const Model &m, const ReqDesc *reqs, int n_req, int n_cu, AttnGroup *out, int *n_streamed, AttnPlanInfo *info)
 {
+    if (info) *info = AttnPlanInfo{RES_WAVES, 0u};
     *n_streamed = 0;
     for (int r = 0; r < n_req; ++r) *n_streamed += reqs[r].n_cand > 0;
     if (m.n_heads > RES_MAX_HEADS || m.d_item / 8 > RES_MAX_ITEM_PIECES) return 0;
@@ -1040,11 +1041,13 @@ int attn_plan_groups(const Model &m, const ReqDesc *reqs, int n_req, int n_cu, A
     long per = (total + n_cu - 1) / n_cu;
     per = (per + RES_WAVES - 1) / RES_WAVES * RES_WAVES;
     if (per < RES_WAVES) per = RES_WAVES;
+    if (info) info->per = (int32_t)per;
     int n = 0;
     for (int r = 0; r < n_req; ++r) {
         const int tiles = (reqs[r].n_cand + 31) / 32;
         if (tiles == 0 || !res_fits(m, reqs[r].seq_len)) continue;
         --*n_streamed;
+        if (info && r < 32) info->resident |= 1u << r;
         const int ng = (int)((tiles + per - 1) / per);
         for (int i = 0; i < ng; ++i)          // even split: sizes differ by at most one tile
             out[n++] = AttnGroup{r, (int)((long)tiles * i / ng), (int)((long)tiles * (i + 1) / ng), 0};

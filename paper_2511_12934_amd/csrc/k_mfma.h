@@ -42,8 +42,14 @@ void mfma_release(MfmaPlan &plan);
 // rounds of the kernel's waves), written to `out` (room for attn_max_groups() entries), their number returned.
 // The others are the streaming kernels': *n_streamed says how many (requests with candidates).  The choice
 // depends on the request alone, so its result does not depend on what else is in the batch.
+// info (optional): what a device-side rebuild of the groups needs (few_fill): the tiles per group at most, and which
+// of the first 32 requests are the resident kernel's.
+struct AttnPlanInfo {
+    int32_t per;
+    uint32_t resident;
+};
 int attn_plan_groups(const Model &m, const ReqDesc *reqs /*host*/, int n_req, int n_cu, AttnGroup *out /*host*/,
-                     int *n_streamed);
+                     int *n_streamed, AttnPlanInfo *info = nullptr);
 size_t attn_max_groups(size_t x_rows, int max_users);
 
 // kv_packed: the batch's K/V are already in fragment order (launch_stage did it)
@@ -67,13 +73,13 @@ struct StageUpload {
     const ReqDesc *reqs_mapped;
     const int32_t *slot_req_mapped;     // the batch's slot_req table through the same mapping
 };
-// one (optional, a batch of one request, not with up): the request's descriptor travels in the kernel's arguments,
-// the launch's blocks read it there and its first blocks write the device tables of the batch (k_stage.h: OneFill),
-// so no upload of any kind precedes the launch.
-struct OneFill;
+// few (optional, a batch of at most FEW_MAX requests, not with up): the requests' descriptors travel in the kernel's
+// arguments, the launch's blocks read them there and its first blocks write the device tables of the batch (k_stage.h:
+// FewFill), so no upload of any kind precedes the launch.
+struct FewFill;
 hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad, const float *w1u,
                         const float *b1, float *bias1, const MfmaPlan &plan, bool gather, hipStream_t s,
-                        const StageUpload *up = nullptr, const OneFill *one = nullptr);
+                        const StageUpload *up = nullptr, const FewFill *few = nullptr);
 
 // bias_f32[l] / wlast_f32: the context's fp32 copies (bias of layer l or null; last layer's weight row).
 hipError_t launch_mlp_mfma(const Model &m, const Batch &b, const void *X, const MfmaPlan &plan,

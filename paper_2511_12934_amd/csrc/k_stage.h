@@ -11,48 +11,101 @@ namespace aif {
 
 constexpr int GATHER_UNROLL = 4;
 
-// Where a staging block finds its request: in the batch's device tables, or -- a batch of ONE request -- in the
-// kernel's own arguments (the tables are then still on their way: the same launch writes them, one_fill).
+// Where a staging block finds its request: in the batch's device tables, or -- a batch of few requests -- in the
+// kernel's own arguments (the tables are then still on their way: the same launch writes them, few_fill).
 struct TableReqs {
     const Batch &b;
     __device__ __forceinline__ int block_request(int blk) const { return b.blk_req[blk]; }
-    __device__ __forceinline__ const ReqDesc &request(int r) const { return b.reqs[r]; }
-    __device__ __forceinline__ const ReqDesc &slot_desc(int slot) const { return b.reqs[slot_request(b, slot)]; }
-};
-struct OneReq {
-    const ReqDesc &rd;
-    __device__ __forceinline__ int block_request(int) const { return 0; }
-    __device__ __forceinline__ const ReqDesc &request(int) const { return rd; }
-    __device__ __forceinline__ const ReqDesc &slot_desc(int) const { return rd; }
+    __device__ __forceinline__ ReqDesc request(int r) const { return b.reqs[r]; }
+    __device__ __forceinline__ ReqDesc slot_desc(int slot) const { return b.reqs[slot_request(b, slot)]; }
 };
 
-// Descriptor tables of a one-request batch, written by the device itself from kernel arguments (no pinned staging,
-// no copy command, nothing to wait for on the host): the request, block -> request and block -> user slot (all 0),
-// the attention groups (an even split of the request's tiles, as attn_plan_groups cuts them) and the top-k descriptor.
-struct OneFill {
-    ReqDesc rd;
-    TopkDesc td;
+// Descriptor tables of a batch of at most FEW_MAX requests -- the latency cases: one request, or one request cut into
+// mini-batches (Sec. 5.3) -- written by the device itself from kernel arguments (no pinned staging, no copy command,
+// nothing to wait for on the host): the requests, block -> request and block -> user slot, slot -> request, the
+// attention groups (as attn_plan_groups cuts them) and the top-k descriptors.  Every index into the argument arrays
+// is a constant after unrolling: an argument array indexed by a variable would be copied to scratch memory first.
+constexpr int FEW_MAX = 16;
+struct FewFill {
+    ReqDesc rd[FEW_MAX];
+    TopkDesc td[FEW_MAX];
+    int32_t slot_req[FEW_MAX];  // slot -> a request that brings the slot's user tensors
     ReqDesc *reqs;
-    int32_t *blk_req, *blk_slot, *slot_req;
+    int32_t *blk_req, *blk_slot, *slot_req_dev;
     AttnGroup *groups;
     TopkDesc *topk;             // null: the call selects nothing
-    int32_t n_blk, n_groups, tiles;
+    int32_t n_req, n_slots, n_blk, n_groups;
+    int32_t per;                // tiles per attention group at most (attn_plan_groups)
+    uint32_t resident;          // bit r: request r is the resident attention kernel's (it has groups)
 };
-__device__ __forceinline__ void one_fill(const OneFill &f, int i)
+__device__ __forceinline__ ReqDesc few_request(const FewFill &f, int r)
 {
-    if (i == 0) {
-        f.reqs[0] = f.rd;
-        f.slot_req[0] = 0;
-        if (f.topk) f.topk[0] = f.td;
+    ReqDesc out = f.rd[0];
+#pragma unroll
+    for (int i = 1; i < FEW_MAX; ++i)
+        if (r == i) out = f.rd[i];
+    return out;
+}
+__device__ __forceinline__ int few_block_request(const FewFill &f, int blk)
+{
+    int r = -1;
+#pragma unroll
+    for (int i = 0; i < FEW_MAX; ++i) {
+        const int b0 = f.rd[i].row_base / ROW_BLOCK, nb = (f.rd[i].n_cand + ROW_BLOCK - 1) / ROW_BLOCK;
+        if (i < f.n_req && blk >= b0 && blk < b0 + nb) r = i;
+    }
+    return r;
+}
+struct FewReqs {
+    const FewFill &f;
+    __device__ __forceinline__ int block_request(int blk) const { return few_block_request(f, blk); }
+    __device__ __forceinline__ ReqDesc request(int r) const { return few_request(f, r); }
+    __device__ __forceinline__ ReqDesc slot_desc(int slot) const
+    {
+        int r = f.slot_req[0];
+#pragma unroll
+        for (int i = 1; i < FEW_MAX; ++i)
+            if (slot == i) r = f.slot_req[i];
+        return few_request(f, r);
+    }
+};
+__device__ __forceinline__ void few_fill(const FewFill &f, int i)
+{
+#pragma unroll
+    for (int r = 0; r < FEW_MAX; ++r) {
+        if (i == r && r < f.n_req) {
+            f.reqs[r] = f.rd[r];
+            if (f.topk) f.topk[r] = f.td[r];
+        }
+        if (i == r && r < f.n_slots) f.slot_req_dev[r] = f.slot_req[r];
     }
     if (i < f.n_blk) {
-        f.blk_req[i] = 0;
-        f.blk_slot[i] = 0;
+        const int r = few_block_request(f, i);
+        f.blk_req[i] = r;
+        f.blk_slot[i] = r < 0 ? 0 : few_request(f, r).slot;
     }
-    if (i < f.n_groups)
-        f.groups[i] = AttnGroup{0, (int)((long)f.tiles * i / f.n_groups), (int)((long)f.tiles * (i + 1) / f.n_groups), 0};
+    if (i < f.n_groups) {
+        // group i: the requests in order, each resident one cut evenly into ceil(tiles / per) groups
+        int acc = 0;
+        AttnGroup g{0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < FEW_MAX; ++r) {
+            const int tiles = (f.rd[r].n_cand + 31) / 32;
+            if (r < f.n_req && ((f.resident >> r) & 1u) && tiles > 0) {
+                const int ng = (tiles + f.per - 1) / f.per;
+                if (i >= acc && i < acc + ng)
+                    g = AttnGroup{r, (int)((long)tiles * (i - acc) / ng), (int)((long)tiles * (i - acc + 1) / ng), 0};
+                acc += ng;
+            }
+        }
+        f.groups[i] = g;
+    }
 }
-__host__ __device__ inline int one_fill_items(const OneFill &f) { return f.n_blk > f.n_groups ? (f.n_blk > 1 ? f.n_blk : 1) : f.n_groups; }
+__host__ __device__ inline int few_fill_items(const FewFill &f)
+{
+    int n = f.n_blk > f.n_groups ? f.n_blk : f.n_groups;
+    return n > FEW_MAX ? n : FEW_MAX;
+}
 
 // a1 -- one ROW_BLOCK of the workspace: X[row, 0:d_item] = table[id].
 // LOG_RV >= 0: a row is 2^LOG_RV pieces of 16 bytes (shift instead of divide); LOG_RV < 0: any count.
@@ -63,7 +116,7 @@ __device__ __forceinline__ void gather_block(int blk, const uint4 *__restrict__ 
 {
     const int r = src.block_request(blk);
     if (r < 0) return;
-    const ReqDesc *rd = &src.request(r);
+    const ReqDesc rdv = src.request(r), *rd = &rdv;
     const int row_base = rd->row_base;
     const int local0 = blk * ROW_BLOCK - row_base;
     int nrows = rd->n_cand - local0;
@@ -133,7 +186,7 @@ __device__ __forceinline__ void gather_block_tiled(int blk, const uint4 *__restr
 
     const int r = src.block_request(blk);
     if (r < 0) return;
-    const ReqDesc *rd = &src.request(r);
+    const ReqDesc rdv = src.request(r), *rd = &rdv;
     const int row_base = rd->row_base;
     const int local0 = blk * ROW_BLOCK - row_base;
     int nrows = rd->n_cand - local0;
@@ -204,7 +257,8 @@ __device__ __forceinline__ void user_fold_block(int slot, int part, const Model 
     const int n = part * FOLD_FEATS + lane;
     const int h1 = m.dims[1];
     const bool on = n < h1;
-    const T *u = (const T *)src.slot_desc(slot).user_vec;
+    const ReqDesc rdv = src.slot_desc(slot);
+    const T *u = (const T *)rdv.user_vec;
     const int per = (m.d_user + 3) / 4, k0 = run * per, k1 = min(m.d_user, k0 + per);
     float acc = 0.f;
     if (on) {
@@ -424,7 +478,7 @@ __device__ __forceinline__ void pack_kv_block(int slot, int hd, int st, const Mo
                                               float *__restrict__ kmax_part, int nktp)
 {
     constexpr int FR = DH / 8, JS = DH / 16, FT = DH / 32;
-    const ReqDesc *rd = &src.slot_desc(slot);
+    const ReqDesc rdv = src.slot_desc(slot), *rd = &rdv;
     const int L = rd->seq_len;
     const int nkt2 = (((L + 31) >> 5) + 1) & ~1;
     if (2 * st >= nkt2) return;

@@ -6,9 +6,9 @@
 // When the attention kernel that follows indexes the item table itself (k_attn_res with
 // GATHER) the grid has no gather blocks; its first blocks may then carry the call's descriptor
 // tables from pinned host memory to the device, which saves the upload its own launch.
-// A batch of ONE request (the latency case: Sec. 5.3 measures a single request) needs neither: the request's
-// descriptor arrives in the kernel's arguments, every block reads it there, and the first blocks write the
-// device tables the later kernels read.
+// A batch of few requests (the latency cases: Sec. 5.3 measures a single request, alone or cut into mini-batches)
+// needs neither: the requests' descriptors arrive in the kernel's arguments, every block reads them there, and the
+// first blocks write the device tables the later kernels read.
 #include "k_mfma.h"
 #include "k_stage.h"
 
@@ -35,9 +35,9 @@ struct StageArgs {
     uint4 *up_dst;
     int32_t up_n16, n_up;           // 16-byte pieces; blocks of this job (0: the tables are on the device already)
 };
-struct StageOneArgs {
-    StageArgs a;                    // a.n_up = blocks that write the tables (one_fill), a.up_* unused
-    OneFill fill;
+struct StageFewArgs {
+    StageArgs a;                    // a.n_up = blocks that write the tables (few_fill), a.up_* unused
+    FewFill fill;
 };
 
 // LOG_RV = STAGE_NO_GATHER: the launch has no gather blocks (the attention kernel indexes the table itself) -- built
@@ -85,28 +85,28 @@ __global__ __launch_bounds__(256) void k_stage(StageArgs a)
 }
 
 template <int LOG_RV, int DH>
-__global__ __launch_bounds__(256) void k_stage_one(StageOneArgs o)
+__global__ __launch_bounds__(256) void k_stage_few(StageFewArgs o)
 {
     const int idx = blockIdx.x;
     if (idx < o.a.n_up) {
-        one_fill(o.fill, idx * 256 + (int)threadIdx.x);
+        few_fill(o.fill, idx * 256 + (int)threadIdx.x);
         return;
     }
-    stage_block<LOG_RV, DH>(o.a, OneReq{o.fill.rd}, idx - o.a.n_up);
+    stage_block<LOG_RV, DH>(o.a, FewReqs{o.fill}, idx - o.a.n_up);
 }
 
 template <int DH>
-static hipError_t launch_stage_dh(const StageArgs &a, int n_gather, const OneFill *one, hipStream_t s)
+static hipError_t launch_stage_dh(const StageArgs &a, int n_gather, const FewFill *one, hipStream_t s)
 {
     const dim3 grid(a.n_up + a.n_pack + a.n_fold + a.n_w0 + n_gather);
     if (one) {
-        const StageOneArgs o{a, *one};
+        const StageFewArgs o{a, *one};
         switch (n_gather ? a.row_vec : STAGE_NO_GATHER) {
-        case STAGE_NO_GATHER: hipLaunchKernelGGL((k_stage_one<STAGE_NO_GATHER, DH>), grid, dim3(256), 0, s, o); break;
-        case 8: hipLaunchKernelGGL((k_stage_one<3, DH>), grid, dim3(256), 0, s, o); break;
-        case 16: hipLaunchKernelGGL((k_stage_one<4, DH>), grid, dim3(256), 0, s, o); break;
-        case 32: hipLaunchKernelGGL((k_stage_one<5, DH>), grid, dim3(256), 0, s, o); break;
-        default: hipLaunchKernelGGL((k_stage_one<-1, DH>), grid, dim3(256), 0, s, o); break;
+        case STAGE_NO_GATHER: hipLaunchKernelGGL((k_stage_few<STAGE_NO_GATHER, DH>), grid, dim3(256), 0, s, o); break;
+        case 8: hipLaunchKernelGGL((k_stage_few<3, DH>), grid, dim3(256), 0, s, o); break;
+        case 16: hipLaunchKernelGGL((k_stage_few<4, DH>), grid, dim3(256), 0, s, o); break;
+        case 32: hipLaunchKernelGGL((k_stage_few<5, DH>), grid, dim3(256), 0, s, o); break;
+        default: hipLaunchKernelGGL((k_stage_few<-1, DH>), grid, dim3(256), 0, s, o); break;
         }
         return hipGetLastError();
     }
@@ -154,11 +154,11 @@ bool stage_fusable(const Model &m, const MfmaPlan &plan)
 
 hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void *X, int32_t *bad, const float *w1u,
                         const float *b1, float *bias1, const MfmaPlan &plan, bool gather, hipStream_t s,
-                        const StageUpload *up, const OneFill *one)
+                        const StageUpload *up, const FewFill *one)
 {
     if (b.n_req == 0) return hipSuccess;
     if (up && gather) return hipErrorInvalidValue;      // the gather's many blocks read the device copy
-    if (one && (up || b.n_req != 1 || b.n_slots != 1)) return hipErrorInvalidValue;
+    if (one && (up || b.n_req > FEW_MAX || b.n_req != one->n_req || b.n_slots != one->n_slots)) return hipErrorInvalidValue;
     StageArgs a;
     a.m = m;
     a.b = b;
@@ -173,7 +173,7 @@ hipError_t launch_stage(const Model &m, const Batch &b, const void *table, void 
         a.up_n16 = (int32_t)((up->bytes + 15) / 16);
         a.n_up = (a.up_n16 + 255) / 256;
     }
-    if (one) a.n_up = (one_fill_items(*one) + 255) / 256;
+    if (one) a.n_up = (few_fill_items(*one) + 255) / 256;
     a.table = (const uint4 *)table;
     a.X = (char *)X;
     a.xl = x_layout(m);

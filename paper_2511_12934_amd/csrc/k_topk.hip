@@ -74,7 +74,14 @@ __device__ __forceinline__ int value_bin(uint32_t key, float lo, float scale)
     return b < TKF_BINS - 1 ? b : TKF_BINS - 1;
 }
 
-__global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict__ descs, int k, int kpad,
+// FEW: the descriptors of at most TK_FEW lists arrive in the kernel's arguments (a call that has them on the host
+// needs no upload then); every index into the argument array is a constant after unrolling.
+constexpr int TK_FEW = TOPK_FEW;
+struct TopkFew {
+    TopkDesc d[TK_FEW];
+};
+template <bool FEW>
+__global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict__ descs, TopkFew few, int k, int kpad,
                                                      int32_t *__restrict__ idx_out, float *__restrict__ val_out)
 {
     extern __shared__ __align__(16) unsigned long long sel[];   // [kpad]
@@ -86,8 +93,16 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
     __shared__ uint32_t s_bstar, s_total, s_cnt;
 
     const int r = blockIdx.x;
-    const float *z = descs[r].logits;
-    const int n = descs[r].n;
+    TopkDesc desc;
+    if constexpr (FEW) {
+        desc = few.d[0];
+#pragma unroll
+        for (int i = 1; i < TK_FEW; ++i)
+            if (r == i) desc = few.d[i];
+    } else
+        desc = descs[r];
+    const float *z = desc.logits;
+    const int n = desc.n;
     const int tid = threadIdx.x;
     const int kk = k < n ? k : n;
     int32_t *idx_o = idx_out + (size_t)r * k;
@@ -385,7 +400,21 @@ hipError_t launch_topk(const TopkDesc *descs, int n_req, int k, int32_t *idx_out
     int kpad = 2;
     while (kpad < k) kpad <<= 1;
     const int sel_slots = kpad > TKF_SELMAX ? kpad : TKF_SELMAX;
-    hipLaunchKernelGGL(k_topk, dim3(n_req), dim3(TK_THREADS), (size_t)sel_slots * 8, s, descs, k, kpad, idx_out, val_out);
+    hipLaunchKernelGGL(k_topk<false>, dim3(n_req), dim3(TK_THREADS), (size_t)sel_slots * 8, s, descs, TopkFew{}, k, kpad, idx_out, val_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_topk_few(const TopkDesc *descs_host, int n_req, int k, int32_t *idx_out, float *val_out, hipStream_t s)
+{
+    if (n_req == 0) return hipSuccess;
+    if (n_req > TK_FEW) return hipErrorInvalidValue;
+    TopkFew few{};
+    for (int r = 0; r < n_req; ++r) few.d[r] = descs_host[r];
+    int kpad = 2;
+    while (kpad < k) kpad <<= 1;
+    const int sel_slots = kpad > TKF_SELMAX ? kpad : TKF_SELMAX;
+    hipLaunchKernelGGL(k_topk<true>, dim3(n_req), dim3(TK_THREADS), (size_t)sel_slots * 8, s, (const TopkDesc *)nullptr, few, k, kpad,
+                       idx_out, val_out);
     return hipGetLastError();
 }
 
