@@ -49,7 +49,7 @@ hipError_t scratch_of(int dev, unsigned char **out)
 
 // The descriptor tables of a one-request batch written as a launch of its own (one_fill): for the models whose
 // staging is not the fused launch, which would carry them.
-__global__ __launch_bounds__(256) void k_static_fill(FewFill f) { few_fill(f, blockIdx.x * 256 + threadIdx.x); }
+__global__ __launch_bounds__(256) void k_static_fill(FewFill f) { few_fill<1>(f, blockIdx.x * 256 + threadIdx.x); }
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 thread_local std::string g_init_error = "";

@@ -38,41 +38,42 @@ struct FewFill {
     int32_t per;                // tiles per attention group at most (attn_plan_groups)
     uint32_t resident;          // bit r: request r is the resident attention kernel's (it has groups)
 };
-__device__ __forceinline__ ReqDesc few_request(const FewFill &f, int r)
+// N: how many entries of the argument arrays the code looks at (1: the single request; FEW_MAX otherwise)
+template <int N> __device__ __forceinline__ ReqDesc few_request(const FewFill &f, int r)
 {
     ReqDesc out = f.rd[0];
 #pragma unroll
-    for (int i = 1; i < FEW_MAX; ++i)
+    for (int i = 1; i < N; ++i)
         if (r == i) out = f.rd[i];
     return out;
 }
-__device__ __forceinline__ int few_block_request(const FewFill &f, int blk)
+template <int N> __device__ __forceinline__ int few_block_request(const FewFill &f, int blk)
 {
     int r = -1;
 #pragma unroll
-    for (int i = 0; i < FEW_MAX; ++i) {
+    for (int i = 0; i < N; ++i) {
         const int b0 = f.rd[i].row_base / ROW_BLOCK, nb = (f.rd[i].n_cand + ROW_BLOCK - 1) / ROW_BLOCK;
         if (i < f.n_req && blk >= b0 && blk < b0 + nb) r = i;
     }
     return r;
 }
-struct FewReqs {
+template <int N> struct FewReqs {
     const FewFill &f;
-    __device__ __forceinline__ int block_request(int blk) const { return few_block_request(f, blk); }
-    __device__ __forceinline__ ReqDesc request(int r) const { return few_request(f, r); }
+    __device__ __forceinline__ int block_request(int blk) const { return few_block_request<N>(f, blk); }
+    __device__ __forceinline__ ReqDesc request(int r) const { return few_request<N>(f, r); }
     __device__ __forceinline__ ReqDesc slot_desc(int slot) const
     {
         int r = f.slot_req[0];
 #pragma unroll
-        for (int i = 1; i < FEW_MAX; ++i)
+        for (int i = 1; i < N; ++i)
             if (slot == i) r = f.slot_req[i];
-        return few_request(f, r);
+        return few_request<N>(f, r);
     }
 };
-__device__ __forceinline__ void few_fill(const FewFill &f, int i)
+template <int N> __device__ __forceinline__ void few_fill(const FewFill &f, int i)
 {
 #pragma unroll
-    for (int r = 0; r < FEW_MAX; ++r) {
+    for (int r = 0; r < N; ++r) {
         if (i == r && r < f.n_req) {
             f.reqs[r] = f.rd[r];
             if (f.topk) f.topk[r] = f.td[r];
@@ -80,16 +81,16 @@ __device__ __forceinline__ void few_fill(const FewFill &f, int i)
         if (i == r && r < f.n_slots) f.slot_req_dev[r] = f.slot_req[r];
     }
     if (i < f.n_blk) {
-        const int r = few_block_request(f, i);
+        const int r = few_block_request<N>(f, i);
         f.blk_req[i] = r;
-        f.blk_slot[i] = r < 0 ? 0 : few_request(f, r).slot;
+        f.blk_slot[i] = r < 0 ? 0 : few_request<N>(f, r).slot;
     }
     if (i < f.n_groups) {
         // group i: the requests in order, each resident one cut evenly into ceil(tiles / per) groups
         int acc = 0;
         AttnGroup g{0, 0, 0, 0};
 #pragma unroll
-        for (int r = 0; r < FEW_MAX; ++r) {
+        for (int r = 0; r < N; ++r) {
             const int tiles = (f.rd[r].n_cand + 31) / 32;
             if (r < f.n_req && ((f.resident >> r) & 1u) && tiles > 0) {
                 const int ng = (tiles + f.per - 1) / f.per;

@@ -84,15 +84,24 @@ __global__ __launch_bounds__(256) void k_stage(StageArgs a)
     stage_block<LOG_RV, DH>(a, TableReqs{a.b}, idx - a.n_up);
 }
 
-template <int LOG_RV, int DH>
+template <int LOG_RV, int DH, int N>
 __global__ __launch_bounds__(256) void k_stage_few(StageFewArgs o)
 {
     const int idx = blockIdx.x;
     if (idx < o.a.n_up) {
-        few_fill(o.fill, idx * 256 + (int)threadIdx.x);
+        few_fill<N>(o.fill, idx * 256 + (int)threadIdx.x);
         return;
     }
-    stage_block<LOG_RV, DH>(o.a, FewReqs{o.fill}, idx - o.a.n_up);
+    stage_block<LOG_RV, DH>(o.a, FewReqs<N>{o.fill}, idx - o.a.n_up);
+}
+
+template <int LOG_RV, int DH>
+static void launch_stage_few(const StageFewArgs &o, dim3 grid, hipStream_t s)
+{
+    if (o.fill.n_req == 1 && o.fill.n_slots == 1)
+        hipLaunchKernelGGL((k_stage_few<LOG_RV, DH, 1>), grid, dim3(256), 0, s, o);
+    else
+        hipLaunchKernelGGL((k_stage_few<LOG_RV, DH, FEW_MAX>), grid, dim3(256), 0, s, o);
 }
 
 template <int DH>
@@ -102,11 +111,11 @@ static hipError_t launch_stage_dh(const StageArgs &a, int n_gather, const FewFil
     if (one) {
         const StageFewArgs o{a, *one};
         switch (n_gather ? a.row_vec : STAGE_NO_GATHER) {
-        case STAGE_NO_GATHER: hipLaunchKernelGGL((k_stage_few<STAGE_NO_GATHER, DH>), grid, dim3(256), 0, s, o); break;
-        case 8: hipLaunchKernelGGL((k_stage_few<3, DH>), grid, dim3(256), 0, s, o); break;
-        case 16: hipLaunchKernelGGL((k_stage_few<4, DH>), grid, dim3(256), 0, s, o); break;
-        case 32: hipLaunchKernelGGL((k_stage_few<5, DH>), grid, dim3(256), 0, s, o); break;
-        default: hipLaunchKernelGGL((k_stage_few<-1, DH>), grid, dim3(256), 0, s, o); break;
+        case STAGE_NO_GATHER: launch_stage_few<STAGE_NO_GATHER, DH>(o, grid, s); break;
+        case 8: launch_stage_few<3, DH>(o, grid, s); break;
+        case 16: launch_stage_few<4, DH>(o, grid, s); break;
+        case 32: launch_stage_few<5, DH>(o, grid, s); break;
+        default: launch_stage_few<-1, DH>(o, grid, s); break;
         }
         return hipGetLastError();
     }
