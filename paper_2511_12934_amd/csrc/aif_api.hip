@@ -560,7 +560,10 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
             c->prof_seen_topk++ % c->prof_every == 0)
             pt = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
         if (pt) HIP_TRY(c, hipEventRecord(pt[0], s));
-        HIP_TRY(c, launch_topk((const TopkDesc *)(d + toff), n_req, k, idx_out, val_out, s));
+        if (n_req <= TOPK_FEW)                   // the lists' descriptors in the kernel's arguments: a round trip less in its chain
+            HIP_TRY(c, launch_topk_few((const TopkDesc *)(h + toff), n_req, k, idx_out, val_out, s));
+        else
+            HIP_TRY(c, launch_topk((const TopkDesc *)(d + toff), n_req, k, idx_out, val_out, s));
         if (pt) HIP_TRY(c, hipEventRecord(pt[1], s));
     }
     HIP_TRY(c, hipEventRecord(c->ev[slot], s));
@@ -729,7 +732,7 @@ aif_status aif_score_topk_static(aif_ctx *c, const aif_request *req, int32_t k, 
         }
         HIP_TRY(c, launch_mlp_generic(m, b, X, gw, bias1, s));
     }
-    if (k > 0) HIP_TRY(c, launch_topk(f.topk, 1, k, idx_out, val_out, s));
+    if (k > 0) HIP_TRY(c, launch_topk_few(&f.td[0], 1, k, idx_out, val_out, s));
     return AIF_OK;
 }
 
