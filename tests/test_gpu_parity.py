@@ -780,6 +780,54 @@ def test_hadamard_cross_folded_into_the_users_layer1_weights(R, torch, monkeypat
     assert np.array_equal(whole.logits.cpu().numpy(), z0[0]) and np.array_equal(other.logits.cpu().numpy(), z0[3])
 
 
+def test_descriptors_in_the_launch_arguments_and_uploaded_give_the_same_results(R, torch):
+    """Up to 16 requests travel in the staging launch's arguments and the device tables (block -> request, slot ->
+    request, attention groups, top-k lists) are written by that launch; more are uploaded from the pinned slot.
+    The same 16 requests -- users that repeat (shared slots), an empty request, one whose K/V exceed LDS beside
+    resident ones -- scored as a batch of 16 and inside a batch of 17: same logits, same selection; each request
+    against the oracle."""
+    cfg = small_cfg("bf16", n_items=5000, seq_len=1100, **MFMA_SHAPES["c3_like"])
+    _say("16 requests in the arguments vs 17 uploaded")
+    rng = np.random.default_rng(1617)
+    model = wl.make_model(cfg, seed=21, bias_scale=0.1)
+    table = wl.make_table_host(cfg, rng)
+    table_dev = R.to_device(table, cfg.dtype)
+    sampler = wl.IdSampler(cfg)
+    users = [wl.make_user(cfg, rng, seq_len=L) for L in (200, 64, 1100, 333, 1)]
+    sizes = [300, 1, 257, 0, 700, 33, 256, 100, 512, 31, 32, 1000, 7, 64, 129, 400]
+    dm = R.DeviceModel(cfg, model)
+    ctx = R.make_context(cfg, dm, table_dev, max_users=17, max_candidates=1024, max_seq_len=1100)
+    du = [R.upload_request(cfg, u, sampler.sample(rng, 1)) for u in users]           # the users' tensors on the device, once
+    def request(u, ids):                                    # a request that brings user u's tensors (same pointers: same slot)
+        d = R.upload_request(cfg, users[u], ids)
+        q, b = d.req, du[u].req
+        d.req = type(q)(b.user_vec, b.seq_keys, b.seq_vals, q.cand_ids, q.logits_out, q.scores_out, b.cross_vecs, b.seq_len)
+        return d
+    ids = [sampler.sample(rng, n) for n in sizes]
+    who = [i % len(users) for i in range(16)]
+    k = 20
+    out = {}
+    for n_req in (16, 17):
+        ds = [request(who[i], ids[i]) for i in range(16)]
+        extra = [request(2, sampler.sample(rng, 50))] if n_req == 17 else []
+        idx = torch.full((n_req, k), -7, dtype=torch.int32, device="cuda")
+        val = torch.zeros((n_req, k), dtype=torch.float32, device="cuda")
+        ctx.aif_score_topk([d.req for d in ds + extra], k, idx, val)
+        torch.cuda.synchronize()
+        assert ctx.aif_last_user_slots() == len(users)
+        out[n_req] = ([d.logits.cpu().numpy().copy() for d in ds], idx.cpu().numpy()[:16].copy(), val.cpu().numpy()[:16].copy())
+    for i in range(16):
+        assert np.array_equal(out[16][0][i], out[17][0][i]), f"request {i}: logits"
+        assert np.array_equal(out[16][1][i], out[17][1][i]) and np.array_equal(out[16][2][i], out[17][2][i]), f"request {i}: top-k"
+        if sizes[i]:
+            ref = oracle_scores(cfg, model, table, users[who[i]], ids[i], n_threads=4)
+            assert_logits_close("bf16", out[16][0][i], ref.logits, f"request {i}")
+            oi, ov = oracle.topk(out[16][0][i].astype(np.float64), k)           # the selection alone, on the GPU's own logits
+            assert np.array_equal(out[16][1][i], oi), f"request {i}: selection"
+        else:
+            assert np.all(out[16][1][i] == -1) and np.all(np.isneginf(out[16][2][i]))
+
+
 def test_cross_fold_with_the_shape_agnostic_attention_kernel(R, torch):
     """A bf16 model whose attention has no matrix-core kernel (four heads of 16 without W_q) but whose head is a
     fused chain: the cross block is still folded into the users' layer-1 weights -- by a launch of its own, the
