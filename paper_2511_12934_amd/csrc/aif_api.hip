@@ -7,6 +7,7 @@
 #include "k_mfma.h"
 #include "k_stage.h"
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -562,8 +563,11 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         if (pt) HIP_TRY(c, hipEventRecord(pt[0], s));
         if (n_req <= TOPK_FEW)                   // the lists' descriptors in the kernel's arguments: a round trip less in its chain
             HIP_TRY(c, launch_topk_few((const TopkDesc *)(h + toff), n_req, k, idx_out, val_out, s));
-        else
-            HIP_TRY(c, launch_topk((const TopkDesc *)(d + toff), n_req, k, idx_out, val_out, s));
+        else {
+            int n_max = 0;
+            for (int r = 0; r < n_req; ++r) n_max = std::max(n_max, (int)((const TopkDesc *)(h + toff))[r].n);
+            HIP_TRY(c, launch_topk((const TopkDesc *)(d + toff), n_req, n_max, k, idx_out, val_out, s));
+        }
         if (pt) HIP_TRY(c, hipEventRecord(pt[1], s));
     }
     HIP_TRY(c, hipEventRecord(c->ev[slot], s));
@@ -787,7 +791,7 @@ aif_status aif_topk(aif_ctx *c, const float *const *logits, const int32_t *n_can
         c->prof_seen_topk++ % c->prof_every == 0)
         pe = &c->prof_topk[(size_t)2 * c->prof_topk_calls++];
     if (pe) HIP_TRY(c, hipEventRecord(pe[0], s));
-    HIP_TRY(c, launch_topk(d, n_req, k, idx_out, val_out, s));
+    HIP_TRY(c, launch_topk(d, n_req, *std::max_element(n_cand, n_cand + n_req), k, idx_out, val_out, s));
     if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
     HIP_TRY(c, hipEventRecord(c->ev[slot], s));
     c->ev_live[slot] = true;

@@ -141,7 +141,8 @@ struct TopkDesc {
     const float *logits;
     int32_t n;
 };
-hipError_t launch_topk(const TopkDesc *descs /*device*/, int n_req, int k, int32_t *idx_out, float *val_out,
+// n_max: the longest list (the kernel keeps that many logits in registers; a longer list is still selected from, slower)
+hipError_t launch_topk(const TopkDesc *descs /*device*/, int n_req, int n_max, int k, int32_t *idx_out, float *val_out,
                        hipStream_t s);
 // at most TOPK_FEW lists whose descriptors are on the HOST: they travel in the kernel's arguments, nothing is uploaded
 constexpr int TOPK_FEW = 16;

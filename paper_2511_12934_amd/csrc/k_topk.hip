@@ -3,8 +3,8 @@
 //
 // Logits map to order-preserving 32-bit keys (NaN -> 0, the lowest; -0 -> +0).
 // Four 8-bit radix passes over LDS histograms find the exact key T of the
-// k-th best and how many candidates with key == T are needed (the keys of the
-// first 20 K candidates stay in registers between the passes; logits of one
+// k-th best and how many candidates with key == T are needed (the keys of up to
+// the first 20 K candidates stay in registers between the passes; logits of one
 // request crowd into a few bins of the leading byte, so each wave first counts
 // its lanes per bin by ballot and adds once per bin); a gather pass
 // takes every key > T plus the first ties in position order (block-wide
@@ -18,8 +18,10 @@
 // monotone map, so every candidate of a higher bin beats every candidate of a
 // lower one and equal logits share a bin.  The bin b* that holds the k-th best
 // is read off the suffix sums; the candidates of the bins >= b* (k plus a
-// handful when the logits are spread out) are collected and each finds its rank
-// among them by counting, on the same (key, ~position) pairs as the sort.  When
+// handful when the logits are spread out) are laid out bin by bin, the highest
+// bin first (the suffix sums say where each bin starts), and each finds its rank
+// as its bin's start plus how many of its own bin beat it, on the same
+// (key, ~position) pairs as the sort.  When
 // those bins hold more than 1024 candidates (logits piled on one value) or the
 // request has no two distinct finite logits, the radix passes take over.  Both
 // routes give the same result: the exact top k in the order stated above.
@@ -28,7 +30,7 @@
 namespace aif {
 
 constexpr int TK_THREADS = 1024;
-constexpr int TK_CACHED = 20;              // keys per thread kept in registers (20 K candidates: the largest configured request)
+constexpr int TK_MAX_SLOTS = 20;           // logits per thread kept in registers at most (20 K candidates: the largest configured request)
 
 // hist[bin] += 1 for every active lane.  Up to TK_AGG distinct bins of the wave are added with one
 // atomic each (lanes counted by ballot); lanes left after that add on their own.
@@ -65,22 +67,23 @@ __device__ __forceinline__ float key_logit(uint32_t key)      // inverse of logi
 constexpr int TKF_BINS = 2048;              // two per thread
 constexpr int TKF_SELMAX = 1024;            // candidates the shortcut may have to rank
 
-__device__ __forceinline__ int value_bin(uint32_t key, float lo, float scale)
+// NaN and -inf: the lowest bin, +inf: the highest (the key orders them inside it)
+__device__ __forceinline__ int value_bin(float v, float lo, float scale)
 {
-    const float v = key_logit(key);
-    if (key == 0u || v == -INFINITY) return 0;                  // NaN and -inf: lowest bin (the key orders them inside it)
-    if (v == INFINITY) return TKF_BINS - 1;
-    const int b = (int)((v - lo) * scale);
-    return b < TKF_BINS - 1 ? b : TKF_BINS - 1;
+    const float f = fminf(fmaxf((v - lo) * scale, 0.f), (float)(TKF_BINS - 1));       // fmaxf(NaN, 0) = 0
+    return (int)f;
 }
 
 // FEW: the descriptors of at most TK_FEW lists arrive in the kernel's arguments (a call that has them on the host
 // needs no upload then); every index into the argument array is a constant after unrolling.
+// SLOTS: logits per thread kept in registers between the passes.  The block's work per pass grows with SLOTS whether
+// the slots are filled or not (one compute unit does all of it), so the launch picks the smallest that holds the
+// longest list; a longer list still works (its tail is re-read from memory in every radix pass).
 constexpr int TK_FEW = TOPK_FEW;
 struct TopkFew {
     TopkDesc d[TK_FEW];
 };
-template <bool FEW>
+template <bool FEW, int SLOTS>
 __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict__ descs, TopkFew few, int k, int kpad,
                                                      int32_t *__restrict__ idx_out, float *__restrict__ val_out)
 {
@@ -88,9 +91,9 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
     __shared__ uint32_t hist[256];
     __shared__ uint32_t wave_cnt[TK_THREADS / 64];
     __shared__ uint32_t s_prefix[2], s_remaining[2], s_ngreater, s_key_count;   // [pass parity]
-    __shared__ uint32_t fhist[TKF_BINS];
+    __shared__ uint32_t fhist[TKF_BINS], fabove[TKF_BINS], ftaken[TKF_BINS];
     __shared__ float s_lo[TK_THREADS / 64], s_hi[TK_THREADS / 64];
-    __shared__ uint32_t s_bstar, s_total, s_cnt;
+    __shared__ uint32_t s_bstar, s_total;
 
     const int r = blockIdx.x;
     TopkDesc desc;
@@ -119,29 +122,36 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
         s_remaining[0] = (uint32_t)kk;
     }
     if (tid < 256) hist[tid] = 0;
-    // every load is issued before the first is looked at: positions past the end re-read the last logit (a load
-    // under a condition of its own would be waited for on the spot, twenty round trips in a row)
-    uint32_t kreg[TK_CACHED];
-    {
-        float zv[TK_CACHED];
+    // every load is issued before the first is looked at: in the last slot in use the positions past the end re-read
+    // the last logit (a load under a lane's own condition would be waited for on the spot, a round trip per slot);
+    // the slots past that one are skipped by the whole block
+    float zv[SLOTS];
 #pragma unroll
-        for (int j = 0; j < TK_CACHED; ++j) {
-            const int i = tid + j * TK_THREADS;
-            zv[j] = z[i < n ? i : n - 1];
-        }
-#pragma unroll
-        for (int j = 0; j < TK_CACHED; ++j) kreg[j] = tid + j * TK_THREADS < n ? logit_key(zv[j]) : 0u;
+    for (int j = 0; j < SLOTS; ++j) {
+        const int i = tid + j * TK_THREADS;
+        zv[j] = 0.f;
+        if (j * TK_THREADS < n) zv[j] = z[i < n ? i : n - 1];
     }
     // ---- shortcut: one counting pass over value bins -------------------------------------------------
-    if (n <= TK_CACHED * TK_THREADS) {
-        const int nj = (n + TK_THREADS - 1) / TK_THREADS;                // register slots in use (the same in every thread)
+    if (n <= SLOTS * TK_THREADS) {
+        // the range of the finite logits (the re-read last logit changes neither end; a NaN is passed over by fminf / fmaxf)
         float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
-        for (int j = 0; j < TK_CACHED; ++j) {
-            const float v = key_logit(kreg[j]);
-            if (j < nj && tid + j * TK_THREADS < n && fabsf(v) < INFINITY) {      // finite (a NaN compares false)
-                lo = fminf(lo, v);
-                hi = fmaxf(hi, v);
+        for (int j = 0; j < SLOTS; ++j) {
+            if (j * TK_THREADS < n) {
+                lo = fminf(lo, zv[j]);
+                hi = fmaxf(hi, zv[j]);
+            }
+        }
+        if (__any(!(lo > -INFINITY) || !(hi < INFINITY))) {             // an infinity among them: leave those out
+            lo = INFINITY;
+            hi = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < SLOTS; ++j) {
+                if (j * TK_THREADS < n && fabsf(zv[j]) < INFINITY) {
+                    lo = fminf(lo, zv[j]);
+                    hi = fmaxf(hi, zv[j]);
+                }
             }
         }
 #pragma unroll
@@ -155,7 +165,8 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
         }
         fhist[tid] = 0;
         fhist[tid + TK_THREADS] = 0;
-        if (tid == 0) s_cnt = 0;
+        ftaken[tid] = 0;
+        ftaken[tid + TK_THREADS] = 0;
         __syncthreads();
 #pragma unroll
         for (int w = 0; w < TK_THREADS / 64; ++w) {
@@ -164,13 +175,16 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
         }
         const float scale = (float)TKF_BINS / (hi - lo);
         if (hi > lo && scale < INFINITY) {                              // the same decision in every thread
-            int bin[TK_CACHED];                                         // kept for the collection below (-1: no candidate)
+            int bin[SLOTS];                                             // kept for the collection below (-1: no candidate)
 #pragma unroll
-            for (int j = 0; j < TK_CACHED; ++j) {
+            for (int j = 0; j < SLOTS; ++j) {
                 bin[j] = -1;
-                if (j < nj && tid + j * TK_THREADS < n) {
-                    bin[j] = value_bin(kreg[j], lo, scale);
-                    atomicAdd(&fhist[bin[j]], 1u);
+                if (j * TK_THREADS < n) {
+                    const int b = value_bin(zv[j], lo, scale);
+                    if (tid + j * TK_THREADS < n) {
+                        bin[j] = b;
+                        atomicAdd(&fhist[b], 1u);
+                    }
                 }
             }
             __syncthreads();
@@ -187,6 +201,8 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
             uint32_t s_even = sfx;                                      // S[2 tid]
             for (int w = (tid >> 6) + 1; w < TK_THREADS / 64; ++w) s_even += wave_cnt[w];
             const uint32_t s_odd = s_even - h0;                         // S[2 tid + 1]
+            fabove[2 * tid] = s_odd;                                    // candidates in the bins above this one
+            fabove[2 * tid + 1] = s_odd - h1;
             if (s_even >= (uint32_t)kk && s_odd < (uint32_t)kk) {
                 s_bstar = 2 * tid;
                 s_total = s_even;
@@ -196,39 +212,41 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
                 s_total = s_odd;
             }
             __syncthreads();
-            const uint32_t total = s_total;
-            if (total <= (uint32_t)TKF_SELMAX) {
+            if (s_total <= (uint32_t)TKF_SELMAX) {
+                // a counting sort by bin: the candidates of bin b take the slots [above[b], above[b] + count[b]) in
+                // any order, so a higher bin's come first and a candidate's rank is above[b] plus how many of its own
+                // bin beat it -- a look at the few that share its bin (one or two where the logits are spread out).
+                // A thread seldom holds more than one or two of them: it takes them one at a time, every wave as many
+                // turns as its busiest lane needs (a branch per register slot would cost every wave a turn per slot).
                 const int bstar = (int)s_bstar;
+                uint32_t mine_slots = 0;
 #pragma unroll
-                for (int j = 0; j < TK_CACHED; ++j) {
-                    const int i = tid + j * TK_THREADS;
-                    if (bin[j] >= bstar)
-                        sel[atomicAdd(&s_cnt, 1u)] = ((unsigned long long)kreg[j] << 32) | (0xFFFFFFFFu - (uint32_t)i);
-                }
-                fhist[tid] = 0;                 // the bins are done with: their first words take the ranks
-                __syncthreads();
-                // rank by counting: the pairs are distinct, so the ranks are a permutation.  All 1024 threads
-                // count: the list is cut into TK_THREADS / P runs (P = the power of two that holds the selected),
-                // thread (e, c) counts how many of run c beat candidate e, and the runs' counts are added up.
-                int lg = 6;
-                while ((1u << lg) < total) ++lg;
-                const uint32_t e = (uint32_t)tid & ((1u << lg) - 1u), c = (uint32_t)tid >> lg, runs = (uint32_t)TK_THREADS >> lg;
-                const uint32_t len = (total + runs - 1) / runs, j0 = c * len, j1 = j0 + len < total ? j0 + len : total;
-                unsigned long long mine = 0ull;
-                if (e < total) {
-                    mine = sel[e];
-                    uint32_t part = 0;
-                    for (uint32_t j = j0; j < j1; ++j) part += sel[j] > mine ? 1u : 0u;
-                    if (part) atomicAdd(&fhist[e], part);
+                for (int j = 0; j < SLOTS; ++j) mine_slots |= bin[j] >= bstar ? 1u << j : 0u;
+                while (__any(mine_slots != 0u)) {
+                    const bool have = mine_slots != 0u;
+                    const int j = __ffs((int)mine_slots) - 1;
+                    mine_slots &= mine_slots - 1u;
+                    float v = 0.f;
+#pragma unroll
+                    for (int jj = 0; jj < SLOTS; ++jj) v = jj == j ? zv[jj] : v;
+                    if (have) {
+                        const int b = value_bin(v, lo, scale);          // the bin it was counted in
+                        sel[fabove[b] + atomicAdd(&ftaken[b], 1u)] =
+                            ((unsigned long long)logit_key(v) << 32) | (0xFFFFFFFFu - (uint32_t)(tid + j * TK_THREADS));
+                    }
                 }
                 __syncthreads();
-                if (c == 0 && e < total) {
-                    const uint32_t rank = fhist[e];
+                if ((uint32_t)tid < s_total) {
+                    const unsigned long long mine = sel[tid];
+                    const uint32_t key = (uint32_t)(mine >> 32), i = 0xFFFFFFFFu - (uint32_t)(mine & 0xFFFFFFFFull);
+                    // its bin again, from the key: the key gives the logit back bit for bit, except where it merges
+                    // values (NaNs, the two zeros), and those it merges share a bin
+                    const int b = value_bin(key_logit(key), lo, scale);
+                    const uint32_t first = fabove[b], count = fhist[b];
+                    uint32_t rank = first;                              // the pairs are distinct: the ranks are a permutation
+                    for (uint32_t t = 0; t < count; ++t) rank += sel[first + t] > mine ? 1u : 0u;
                     if (rank < (uint32_t)kk) {
-                        const uint32_t i = 0xFFFFFFFFu - (uint32_t)(mine & 0xFFFFFFFFull);
-                        const uint32_t key = (uint32_t)(mine >> 32);
                         idx_o[rank] = (int32_t)i;
-                        // the key gives the logit back bit for bit, except where it merges values (NaNs, the two zeros)
                         val_o[rank] = key == 0u || key == 0x80000000u ? z[i] : key_logit(key);
                     }
                 }
@@ -237,6 +255,9 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
         }
     }
 
+    uint32_t kreg[SLOTS];
+#pragma unroll
+    for (int j = 0; j < SLOTS; ++j) kreg[j] = tid + j * TK_THREADS < n ? logit_key(zv[j]) : 0u;
     // ---- radix select -----------------------------------------------------------------------------------
     __syncthreads();
     uint32_t mask = 0;
@@ -244,12 +265,12 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
     for (int shift = 24; shift >= 0; shift -= 8, par ^= 1) {
         const uint32_t prefix = s_prefix[par];
 #pragma unroll
-        for (int j = 0; j < TK_CACHED; ++j) {
+        for (int j = 0; j < SLOTS; ++j) {
             const int i = tid + j * TK_THREADS;
             if (j * TK_THREADS < n)                                 // uniform over the block
                 hist_add(hist, i < n && (kreg[j] & mask) == prefix, (kreg[j] >> shift) & 255u);
         }
-        for (int i0 = TK_CACHED * TK_THREADS; i0 < n; i0 += TK_THREADS) {
+        for (int i0 = SLOTS * TK_THREADS; i0 < n; i0 += TK_THREADS) {
             const int i = i0 + tid;
             const uint32_t key = i < n ? logit_key(z[i]) : 0u;
             hist_add(hist, i < n && (key & mask) == prefix, (key >> shift) & 255u);
@@ -297,14 +318,14 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
     if (all_ties) {
         // the usual case (no duplicates straddling the cut): everything with key >= T, any slot order
 #pragma unroll
-        for (int j = 0; j < TK_CACHED; ++j) {
+        for (int j = 0; j < SLOTS; ++j) {
             const int i = tid + j * TK_THREADS;
             if (i < n && kreg[j] >= T) {
                 const uint32_t slot = atomicAdd(&s_ngreater, 1u);
                 sel[slot] = ((unsigned long long)kreg[j] << 32) | (0xFFFFFFFFu - (uint32_t)i);
             }
         }
-        for (int i = TK_CACHED * TK_THREADS + tid; i < n; i += TK_THREADS) {
+        for (int i = SLOTS * TK_THREADS + tid; i < n; i += TK_THREADS) {
             const uint32_t key = logit_key(z[i]);
             if (key >= T) {
                 const uint32_t slot = atomicAdd(&s_ngreater, 1u);
@@ -394,13 +415,30 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
     }
 }
 
-hipError_t launch_topk(const TopkDesc *descs, int n_req, int k, int32_t *idx_out, float *val_out, hipStream_t s)
+template <bool FEW>
+static void launch_topk_slots(int n_max, dim3 grid, size_t lds, hipStream_t s, const TopkDesc *descs, const TopkFew &few, int k,
+                              int kpad, int32_t *idx_out, float *val_out)
+{
+    const dim3 blk(TK_THREADS);
+    if (n_max <= 1 * TK_THREADS)
+        hipLaunchKernelGGL((k_topk<FEW, 1>), grid, blk, lds, s, descs, few, k, kpad, idx_out, val_out);
+    else if (n_max <= 2 * TK_THREADS)
+        hipLaunchKernelGGL((k_topk<FEW, 2>), grid, blk, lds, s, descs, few, k, kpad, idx_out, val_out);
+    else if (n_max <= 5 * TK_THREADS)
+        hipLaunchKernelGGL((k_topk<FEW, 5>), grid, blk, lds, s, descs, few, k, kpad, idx_out, val_out);
+    else if (n_max <= 10 * TK_THREADS)
+        hipLaunchKernelGGL((k_topk<FEW, 10>), grid, blk, lds, s, descs, few, k, kpad, idx_out, val_out);
+    else
+        hipLaunchKernelGGL((k_topk<FEW, TK_MAX_SLOTS>), grid, blk, lds, s, descs, few, k, kpad, idx_out, val_out);
+}
+
+hipError_t launch_topk(const TopkDesc *descs, int n_req, int n_max, int k, int32_t *idx_out, float *val_out, hipStream_t s)
 {
     if (n_req == 0) return hipSuccess;
     int kpad = 2;
     while (kpad < k) kpad <<= 1;
     const int sel_slots = kpad > TKF_SELMAX ? kpad : TKF_SELMAX;
-    hipLaunchKernelGGL(k_topk<false>, dim3(n_req), dim3(TK_THREADS), (size_t)sel_slots * 8, s, descs, TopkFew{}, k, kpad, idx_out, val_out);
+    launch_topk_slots<false>(n_max, dim3(n_req), (size_t)sel_slots * 8, s, descs, TopkFew{}, k, kpad, idx_out, val_out);
     return hipGetLastError();
 }
 
@@ -409,12 +447,15 @@ hipError_t launch_topk_few(const TopkDesc *descs_host, int n_req, int k, int32_t
     if (n_req == 0) return hipSuccess;
     if (n_req > TK_FEW) return hipErrorInvalidValue;
     TopkFew few{};
-    for (int r = 0; r < n_req; ++r) few.d[r] = descs_host[r];
+    int n_max = 0;
+    for (int r = 0; r < n_req; ++r) {
+        few.d[r] = descs_host[r];
+        n_max = descs_host[r].n > n_max ? descs_host[r].n : n_max;
+    }
     int kpad = 2;
     while (kpad < k) kpad <<= 1;
     const int sel_slots = kpad > TKF_SELMAX ? kpad : TKF_SELMAX;
-    hipLaunchKernelGGL(k_topk<true>, dim3(n_req), dim3(TK_THREADS), (size_t)sel_slots * 8, s, (const TopkDesc *)nullptr, few, k, kpad,
-                       idx_out, val_out);
+    launch_topk_slots<true>(n_max, dim3(n_req), (size_t)sel_slots * 8, s, nullptr, few, k, kpad, idx_out, val_out);
     return hipGetLastError();
 }
 
