@@ -1013,6 +1013,14 @@ def _topk_cases(rng):
     h = z.copy()
     h[[1, 2]] = [3e38, -3e38]
     cases["huge_range"] = h
+    # lengths between the register sizes the kernel is built for, with the special values among them
+    t = rng.standard_normal(2_000).astype(np.float32)
+    t[[0, 1999]] = np.inf
+    t[[7, 1024]] = -np.inf
+    t[[3, 1023, 1025]] = np.nan
+    cases["two_thousand"] = t
+    cases["five_thousand"] = np.round(rng.standard_normal(5_000).astype(np.float32), 1)
+    cases["one_past"] = rng.standard_normal(10_241).astype(np.float32)
     return cases
 
 
@@ -1039,6 +1047,16 @@ def test_topk_equals_full_stable_sort(R, torch, k):
         assert np.array_equal(idx[r], oi), (nm, k)
         assert np.array_equal(val[r].astype(np.float64), ov, equal_nan=True), (nm, k)
     assert np.all(idx[-1] == -1) and np.all(np.isneginf(val[-1]))
+    # every list alone: the kernel is then the one built for that list's length (together, the longest decides)
+    i1 = torch.empty((1, k), dtype=torch.int32, device="cuda")
+    v1 = torch.empty((1, k), dtype=torch.float32, device="cuda")
+    for r, nm in enumerate(names):
+        i1.fill_(-7)
+        v1.fill_(-7.0)
+        ctx.aif_topk([dev[r]], k, i1, v1)
+        torch.cuda.synchronize()
+        assert np.array_equal(i1.cpu().numpy()[0], idx[r]), (nm, k)
+        assert np.array_equal(v1.cpu().numpy()[0], val[r], equal_nan=True), (nm, k)
     for kk in (2, 3, 4):                                                   # k around n for the 3-element case
         i2 = torch.empty((1, kk), dtype=torch.int32, device="cuda")
         v2 = torch.empty((1, kk), dtype=torch.float32, device="cuda")
