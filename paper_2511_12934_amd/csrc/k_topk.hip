@@ -64,6 +64,44 @@ __device__ __forceinline__ float key_logit(uint32_t key)      // inverse of logi
     return __uint_as_float((key & 0x80000000u) ? (key ^ 0x80000000u) : ~key);
 }
 
+// Wave-wide reductions on the data-parallel-primitive lanes of the vector ALU (a permute through the LDS path costs a
+// round trip per step, and the steps depend on one another).  Every lane must be active.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t x)        // the lane CTRL names; 0 where it names none or the row is masked
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xF, false);
+}
+template <bool MAX, int CTRL>
+__device__ __forceinline__ float min_max_with(float x)
+{
+    const float y = __uint_as_float(dpp_or_zero<CTRL>(__float_as_uint(x)));
+    return MAX ? fmaxf(x, y) : fminf(x, y);
+}
+__device__ __forceinline__ float lane_value(float x, int lane)
+{
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(x), lane));
+}
+template <bool MAX>
+__device__ __forceinline__ float wave_min_max(float x)
+{
+    x = min_max_with<MAX, 0xB1>(x);             // quad_perm [1,0,3,2]: the neighbour
+    x = min_max_with<MAX, 0x4E>(x);             // quad_perm [2,3,0,1]: the other pair of the quad
+    x = min_max_with<MAX, 0x141>(x);            // row_half_mirror: the other quad of the eight
+    x = min_max_with<MAX, 0x140>(x);            // row_mirror: the other eight of the row of 16
+    const float r0 = lane_value(x, 0), r1 = lane_value(x, 16), r2 = lane_value(x, 32), r3 = lane_value(x, 48);
+    return MAX ? fmaxf(fmaxf(r0, r1), fmaxf(r2, r3)) : fminf(fminf(r0, r1), fminf(r2, r3));
+}
+__device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t x)     // inclusive, over the lanes 0 .. own
+{
+    x += dpp_or_zero<0x111>(x);                 // row_shr:1, 2, 4, 8: the prefix inside each row of 16
+    x += dpp_or_zero<0x112>(x);
+    x += dpp_or_zero<0x114>(x);
+    x += dpp_or_zero<0x118>(x);
+    x += dpp_or_zero<0x142, 0xA>(x);            // row_bcast:15 into rows 1 and 3: the row before
+    x += dpp_or_zero<0x143, 0xC>(x);            // row_bcast:31 into rows 2 and 3: the first two rows
+    return x;
+}
+
 constexpr int TKF_BINS = 2048;              // two per thread
 constexpr int TKF_SELMAX = 1024;            // candidates the shortcut may have to rank
 
@@ -154,11 +192,8 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
                 }
             }
         }
-#pragma unroll
-        for (int o = 32; o; o >>= 1) {
-            lo = fminf(lo, __shfl_xor(lo, o, 64));
-            hi = fmaxf(hi, __shfl_xor(hi, o, 64));
-        }
+        lo = wave_min_max<false>(lo);
+        hi = wave_min_max<true>(hi);
         if ((tid & 63) == 0) {
             s_lo[tid >> 6] = lo;
             s_hi[tid >> 6] = hi;
@@ -188,27 +223,24 @@ __global__ __launch_bounds__(TK_THREADS) void k_topk(const TopkDesc *__restrict_
                 }
             }
             __syncthreads();
-            // suffix sums over the bins, two bins a thread: S[b] = candidates in bins >= b
-            const uint32_t h0 = fhist[2 * tid], h1 = fhist[2 * tid + 1];
-            uint32_t sfx = h0 + h1;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const uint32_t v = __shfl_down(sfx, o, 64);
-                if ((tid & 63) + o < 64) sfx += v;
-            }
-            if ((tid & 63) == 0) wave_cnt[tid >> 6] = sfx;
+            // suffix sums over the bins, S[b] = candidates in bins >= b.  A thread has two bins, the higher threads the
+            // lower bins, so that the sums run up the lanes.
+            const int b_even = TKF_BINS - 2 - 2 * tid;
+            const uint32_t h0 = fhist[b_even], h1 = fhist[b_even + 1];
+            const uint32_t pfx = wave_prefix_sum(h0 + h1);
+            if ((tid & 63) == 63) wave_cnt[tid >> 6] = pfx;
             __syncthreads();
-            uint32_t s_even = sfx;                                      // S[2 tid]
-            for (int w = (tid >> 6) + 1; w < TK_THREADS / 64; ++w) s_even += wave_cnt[w];
-            const uint32_t s_odd = s_even - h0;                         // S[2 tid + 1]
-            fabove[2 * tid] = s_odd;                                    // candidates in the bins above this one
-            fabove[2 * tid + 1] = s_odd - h1;
+            uint32_t s_even = pfx;                                      // S[b_even]
+            for (int w = 0; w < (tid >> 6); ++w) s_even += wave_cnt[w];
+            const uint32_t s_odd = s_even - h0;                         // S[b_even + 1]
+            fabove[b_even] = s_odd;                                     // candidates in the bins above this one
+            fabove[b_even + 1] = s_odd - h1;
             if (s_even >= (uint32_t)kk && s_odd < (uint32_t)kk) {
-                s_bstar = 2 * tid;
+                s_bstar = b_even;
                 s_total = s_even;
             }
             if (s_odd >= (uint32_t)kk && s_odd - h1 < (uint32_t)kk) {
-                s_bstar = 2 * tid + 1;
+                s_bstar = b_even + 1;
                 s_total = s_odd;
             }
             __syncthreads();
