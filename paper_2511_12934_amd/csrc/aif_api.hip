@@ -570,8 +570,11 @@ static aif_status score_impl(aif_ctx *c, const aif_request *reqs, int32_t n_req,
         }
         if (pt) HIP_TRY(c, hipEventRecord(pt[1], s));
     }
-    HIP_TRY(c, hipEventRecord(c->ev[slot], s));
-    c->ev_live[slot] = true;
+    // The event guards the slot's pinned host memory against the next call that takes the slot.  When the descriptors
+    // travelled in the launch arguments the device never reads that memory: no event, and the stream ends on the last
+    // kernel (an event after it is one more thing the device completes before the caller's wait returns).
+    c->ev_live[slot] = !stage_fills;
+    if (!stage_fills) HIP_TRY(c, hipEventRecord(c->ev[slot], s));
     return AIF_OK;
 }
 
