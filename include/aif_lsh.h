@@ -83,6 +83,12 @@ AIF_API const char *aif_lsh_last_error(const aif_lsh_ctx *ctx);
  * last poll (the counter is reset).  Synchronous device read. */
 AIF_API aif_status aif_lsh_poll_device_errors(aif_lsh_ctx *ctx, int32_t *n_bad_ids);
 
+/* Which kernel forms the equal-bit counts of Eq. 6-7 and the tier counts of Eq. 9 in this context:
+ * 0 = vector ALU (XNOR + population count; any signature width and tier count), 1 = matrix cores (the
+ * bits as +1 / -1 int8, the count as a dot product; signatures of 32, 64 or 128 bits whose tiers are
+ * 2 d' / N = a power of two equal-bit counts wide).  Same counts either way.  -1 for a NULL context. */
+AIF_API int32_t aif_lsh_simtier_kind(const aif_lsh_ctx *ctx);
+
 /* Per-kernel timing with HIP events on the caller's stream, as aif_profile_begin / _end of aif.h:
  * stages AIF_LSH_STAGE_USER (user-side sums), _DIN, _SIMTIER; ms[] and calls[] have AIF_LSH_N_STAGES
  * entries. */

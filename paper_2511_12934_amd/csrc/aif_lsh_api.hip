@@ -7,6 +7,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -26,6 +27,9 @@ struct aif_lsh_ctx {
     int max_seq_len = 0, max_candidates = 0, max_users = 0, max_chunks = 0;
     const uint8_t *table = nullptr;
     void *part = nullptr, *A = nullptr, *bad = nullptr;     // device workspace (owned)
+    void *hist = nullptr;                                   // the requests' history signatures as matrix operands (or null: SimTier on the vector ALU)
+    void *parts = nullptr;                                  // partial tier counts of a batch whose histories are cut into parts
+    size_t hist_stride = 0;
     char *h_stage = nullptr, *h_stage_dev = nullptr;        // pinned ring of descriptor tables, its device mapping (or null)
     void *d_stage = nullptr;
     size_t slot_bytes = 0;
@@ -68,6 +72,8 @@ void ldestroy(aif_lsh_ctx *c)
     if (c->part) (void)hipFree(c->part);
     if (c->A) (void)hipFree(c->A);
     if (c->bad) (void)hipFree(c->bad);
+    if (c->hist) (void)hipFree(c->hist);
+    if (c->parts) (void)hipFree(c->parts);
     if (c->d_stage) (void)hipFree(c->d_stage);
     if (c->h_stage) (void)hipHostFree(c->h_stage);
     for (int i = 0; i < LSH_NSLOT; ++i)
@@ -111,6 +117,14 @@ aif_status linit(const aif_lsh_config *cfg, const uint8_t *table, aif_lsh_ctx *c
     const size_t tab = (size_t)2 * m.d_bits * m.d_out * 4;
     LSH_TRY(nullptr, hipMalloc(&c->part, tab * (size_t)c->max_users * (c->max_chunks > 0 ? c->max_chunks : 1)));
     LSH_TRY(nullptr, hipMalloc(&c->A, tab * (size_t)c->max_users));
+    {
+        const char *valu = getenv("AIF_LSH_SIMTIER_VALU");      // testing and measurement: SimTier on the vector ALU whatever the shape
+        if (lsh_simtier_on_mfma(m) && c->max_seq_len > 0 && !(valu && valu[0] == '1')) {
+            c->hist_stride = lsh_hist_stride(m, c->max_seq_len);
+            LSH_TRY(nullptr, hipMalloc(&c->hist, c->hist_stride * 16 * (size_t)c->max_users));
+            LSH_TRY(nullptr, hipMalloc(&c->parts, lsh_simtier_parts_bytes()));
+        }
+    }
     LSH_TRY(nullptr, hipMalloc(&c->bad, 16));
     LSH_TRY(nullptr, hipMemset(c->bad, 0, 16));
     const size_t n_blk_max = (size_t)c->max_users * ((c->max_candidates + LSH_BLOCK - 1) / LSH_BLOCK);
@@ -173,7 +187,7 @@ aif_status aif_lsh_batch(aif_lsh_ctx *c, const aif_lsh_request *reqs, int32_t n_
     char *d = (char *)c->d_stage + (size_t)slot * c->slot_bytes;
     LshReqDesc *hd = (LshReqDesc *)h;
     int32_t *hb = (int32_t *)(h + (size_t)n_req * sizeof(LshReqDesc));
-    int slots = 0, max_chunks = 0;
+    int slots = 0, max_chunks = 0, longest = 0;
     for (int r = 0; r < n_req; ++r) {
         const aif_lsh_request &q = reqs[r];
         LshReqDesc &e = hd[r];
@@ -191,6 +205,7 @@ aif_status aif_lsh_batch(aif_lsh_ctx *c, const aif_lsh_request *reqs, int32_t n_
         slots += nb * LSH_BLOCK;
         const int ch = (q.seq_len + LSH_TCHUNK - 1) / LSH_TCHUNK;
         if (ch > max_chunks) max_chunks = ch;
+        if (q.seq_len > longest) longest = q.seq_len;
     }
     LshBatch b;
     b.reqs = (const LshReqDesc *)d;
@@ -208,12 +223,17 @@ aif_status aif_lsh_batch(aif_lsh_ctx *c, const aif_lsh_request *reqs, int32_t n_
     if (pe) LSH_TRY(c, hipEventRecord(pe[1], s));
     LSH_TRY(c, launch_lsh_din(m, b, c->table, (const float *)c->A, (int32_t *)c->bad, s));
     if (pe) LSH_TRY(c, hipEventRecord(pe[2], s));
-    LSH_TRY(c, launch_lsh_simtier(m, b, c->table, s));
+    if (c->hist)
+        LSH_TRY(c, launch_lsh_simtier_mfma(m, b, c->table, c->hist, c->hist_stride, longest, c->parts, s));
+    else
+        LSH_TRY(c, launch_lsh_simtier(m, b, c->table, s));
     if (pe) LSH_TRY(c, hipEventRecord(pe[3], s));
     LSH_TRY(c, hipEventRecord(c->ev[slot], s));
     c->ev_live[slot] = true;
     return AIF_OK;
 }
+
+int32_t aif_lsh_simtier_kind(const aif_lsh_ctx *ctx) { return !ctx ? -1 : (ctx->hist ? 1 : 0); }
 
 aif_status aif_lsh_poll_device_errors(aif_lsh_ctx *c, int32_t *n_bad_ids)
 {

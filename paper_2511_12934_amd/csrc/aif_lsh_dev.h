@@ -48,5 +48,14 @@ hipError_t launch_lsh_din(const LshModel &m, const LshBatch &b, const uint8_t *s
                           hipStream_t s);
 // Eq. 6, 7, 9: equal-bit counts against every history item, counted into tiers
 hipError_t launch_lsh_simtier(const LshModel &m, const LshBatch &b, const uint8_t *sig_table, hipStream_t s);
+// The same with the equal-bit counts formed on the matrix cores (signatures of 32, 64 or 128 bits; 2 d' / N a power of
+// two up to 256).  hist: workspace of lsh_hist_stride() 16-byte pieces per request, written by the launch itself (the
+// history signatures as the matrix instruction's operand); longest: the longest history of the batch; parts: workspace
+// of lsh_simtier_parts_bytes() for the partial counts of a batch too small to fill the chip uncut.
+bool lsh_simtier_on_mfma(const LshModel &m);
+size_t lsh_hist_stride(const LshModel &m, int max_seq_len);
+size_t lsh_simtier_parts_bytes();
+hipError_t launch_lsh_simtier_mfma(const LshModel &m, const LshBatch &b, const uint8_t *sig_table, void *hist, size_t req_stride,
+                                   int longest, void *parts, hipStream_t s);
 
 }  // namespace aif

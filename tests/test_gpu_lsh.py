@@ -73,7 +73,8 @@ def test_l1_full_size(R, torch):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("d_bits,d_out,n_tiers", [(64, 64, 8), (32, 16, 1), (96, 48, 5), (128, 128, 8), (256, 256, 7), (160, 32, 3),
-                                                   (128, 64, 4), (64, 128, 2)])
+                                                   (128, 64, 4), (64, 128, 2), (32, 16, 8), (64, 32, 4), (32, 32, 2), (128, 16, 1),
+                                                   (128, 32, 2), (64, 16, 1), (256, 64, 8), (64, 64, 7)])
 def test_shapes_ragged(R, torch, dtype, d_bits, d_out, n_tiers):
     cfg = wl.LshConfig("S", 9, dtype, 1, 10, 3000, d_bits, d_out, n_tiers, 50, n_clusters=16, flip=0.2)
     _say(f"lsh {dtype} d'={d_bits} d={d_out} N={n_tiers}")
@@ -82,7 +83,44 @@ def test_shapes_ragged(R, torch, dtype, d_bits, d_out, n_tiers):
     users_ids = []
     for n, L in [(1, 1), (5, 0), (255, 15), (256, 16), (257, 17), (700, 255), (33, 256), (64, 513), (300, 1100)]:
         users_ids.append((wl.make_lsh_user(cfg, rng, seq_len=L, sigma=1.0), rng.integers(0, cfg.n_items, n).astype(np.int32)))
-    check(R, torch, cfg, table, users_ids)
+    ctx, _ = check(R, torch, cfg, table, users_ids)
+    # the matrix-core SimTier serves exactly the shapes whose tiers are a power of two of equal-bit counts wide
+    width = 2 * d_bits / n_tiers
+    assert ctx.aif_lsh_simtier_kind() == int(d_bits in (32, 64, 128) and width == int(width) and int(width) & (int(width) - 1) == 0)
+
+
+@pytest.mark.parametrize("d_bits,n_tiers", [(64, 8), (128, 8), (32, 4)])
+def test_simtier_on_the_vector_alu_gives_the_same_counts(R, torch, monkeypatch, d_bits, n_tiers):
+    """The two SimTier kernels against the oracle on the same requests (a context reads the switch when it is made)."""
+    cfg = wl.LshConfig("S", 12, "bf16", 1, 10, 3000, d_bits, 32, n_tiers, 50, n_clusters=16, flip=0.2)
+    _say(f"lsh SimTier, both kernels, d'={d_bits} N={n_tiers}")
+    table = wl.make_sig_table_host(cfg)
+    rng = np.random.default_rng(5)
+    users_ids = [(wl.make_lsh_user(cfg, rng, seq_len=L, sigma=1.0), rng.integers(0, cfg.n_items, n).astype(np.int32))
+                 for n, L in [(300, 777), (17, 31), (256, 128)]]
+    ctx, drs = check(R, torch, cfg, table, users_ids)
+    assert ctx.aif_lsh_simtier_kind() == 1
+    on_mfma = [d.tiers.cpu().numpy().copy() for d in drs]
+    monkeypatch.setenv("AIF_LSH_SIMTIER_VALU", "1")
+    ctx2, drs2 = check(R, torch, cfg, table, users_ids)
+    assert ctx2.aif_lsh_simtier_kind() == 0
+    for a, d in zip(on_mfma, drs2):
+        assert np.array_equal(a, d.tiers.cpu().numpy())
+
+
+@pytest.mark.parametrize("d_bits,seq_len", [(64, 250_123), (128, 130_001), (32, 40_000)])
+def test_simtier_long_history_few_candidates(R, torch, d_bits, seq_len):
+    """A batch too small to fill the chip: the histories are cut into parts, a block each, and a second kernel adds the
+    parts' counts up; a history this long also makes every wave read its counting planes out more than once."""
+    cfg = wl.LshConfig("S", 13, "bf16", 1, 10, 5000, d_bits, 16, 8, 50, n_clusters=16, flip=0.2)
+    _say(f"lsh long history d'={d_bits} L={seq_len}")
+    table = wl.make_sig_table_host(cfg)
+    rng = np.random.default_rng(6)
+    users_ids = [(wl.make_lsh_user(cfg, rng, seq_len=seq_len, sigma=1.0), rng.integers(0, cfg.n_items, 300).astype(np.int32)),
+                 (wl.make_lsh_user(cfg, rng, seq_len=999, sigma=1.0), rng.integers(0, cfg.n_items, 70).astype(np.int32))]
+    users_ids[0][0].seq_sigs[seq_len // 2] = table[users_ids[0][1][5]]         # one history item equal to a candidate
+    ctx, _ = check(R, torch, cfg, table, users_ids)
+    assert ctx.aif_lsh_simtier_kind() == 1
 
 
 def test_extreme_similarities_and_tier_edges(R, torch):
