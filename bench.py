@@ -33,6 +33,7 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 PEAK_MFMA_BF16_TFLOPS = 2500.0   # dense bf16
+PEAK_MFMA_I8_TOPS = 5000.0       # dense int8
 PEAK_FP32_VALU_TFLOPS = 157.3
 # 32-bit integer vector ALU: the fp32 figure counts 2 flops per FMA and 2 lanes per packed instruction
 PEAK_INT_VALU_TOPS = PEAK_FP32_VALU_TFLOPS / 4
@@ -370,7 +371,21 @@ def main_lsh(args):
     # LSH-DIN: bytes the method needs per candidate: id + signature read, d_out fp32 written
     kernels["din"]["gbs"] = (4 + cfg.d_bits // 8 + 4 * cfg.d_out) * cands / (kernels["din"]["avg_ms"] * 1e-3) / 1e9
     dom = max(kernels, key=lambda k: kernels[k]["avg_ms"])
-    if dom == "simtier":
+    on_mfma = w.ctx.aif_lsh_simtier_kind() == 1
+    if on_mfma:
+        # equal-bit counts as int8 dot products on the matrix cores: d' multiply-adds per pair; the tier counting left on
+        # the vector ALU is 448 instructions per 256 pairs and lane in the kernel's loop (1.75 per pair)
+        t = kernels["simtier"]["avg_ms"] * 1e-3
+        kernels["simtier"]["mfma_tops"] = 2.0 * cfg.d_bits * pairs / t / 1e12
+        kernels["simtier"]["valu_tops"] = 1.75 * pairs / t / 1e12
+        kernels["simtier"]["valu_frac_of_int_peak"] = kernels["simtier"]["valu_tops"] / PEAK_INT_VALU_TOPS
+        kernels["simtier"]["tops_note"] = ("tops = the vector-ALU kernel's algorithmic count (2 d'/32 + 4 per pair) over this "
+                                           "kernel's time, for comparison with it only")
+    if dom == "simtier" and on_mfma:
+        roof = {"kernel": "k_lsh_simtier_mfma", "bound": "mfma", "achieved": kernels[dom]["mfma_tops"], "peak": PEAK_MFMA_I8_TOPS,
+                "unit": "Top/s", "binding_unit": "vector ALU (tier counting), %.2f of its integer peak"
+                                                 % kernels[dom]["valu_frac_of_int_peak"]}
+    elif dom == "simtier":
         roof = {"kernel": "k_lsh_simtier", "bound": "alu", "achieved": kernels[dom]["tops"], "peak": PEAK_INT_VALU_TOPS,
                 "unit": "Top/s"}
     elif dom == "din":
@@ -387,7 +402,7 @@ def main_lsh(args):
         "metric": "candidates served/sec/GPU by the LSH behaviour modelling (LSH-DIN + SimTier)",
         "value": cands * args.steps / elapsed, "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "u32" if dom == "simtier" else "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": ("i8" if on_mfma else "u32") if dom == "simtier" else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {w.n_users} users x {w.n_cand} candidates x {w.seq_len} history items, "
                                f"{cfg.d_bits}-bit signatures (table {cfg.n_items} rows), d={cfg.d_out} {cfg.dtype}, "
                                f"{cfg.n_tiers} tiers",
