@@ -89,6 +89,12 @@ AIF_API aif_status aif_lsh_poll_device_errors(aif_lsh_ctx *ctx, int32_t *n_bad_i
  * 2 d' / N = a power of two equal-bit counts wide).  Same counts either way.  -1 for a NULL context. */
 AIF_API int32_t aif_lsh_simtier_kind(const aif_lsh_ctx *ctx);
 
+/* Which kernel forms Eq. 8 in this context: 0 = vector ALU (one table row added per bit), 1 = matrix
+ * cores (the candidates' bits one-hot against the fp32 tables cut exactly into three bf16 pieces;
+ * d_out a multiple of 32 up to 128).  Same value up to the order of the fp32 additions.  -1 for a NULL
+ * context. */
+AIF_API int32_t aif_lsh_din_kind(const aif_lsh_ctx *ctx);
+
 /* Per-kernel timing with HIP events on the caller's stream, as aif_profile_begin / _end of aif.h:
  * stages AIF_LSH_STAGE_USER (user-side sums), _DIN, _SIMTIER; ms[] and calls[] have AIF_LSH_N_STAGES
  * entries. */

@@ -25,7 +25,7 @@ EXPORTS = ("aif_score_init", "aif_score_request", "aif_score_batch", "aif_topk",
            "aif_mlp_layer1_width")
 STAGES = ("gather", "user_fold", "attention", "mlp", "topk")
 LSH_EXPORTS = ("aif_lsh_init", "aif_lsh_batch", "aif_lsh_destroy", "aif_lsh_last_error",
-               "aif_lsh_poll_device_errors", "aif_lsh_simtier_kind", "aif_lsh_profile_begin", "aif_lsh_profile_end")
+               "aif_lsh_poll_device_errors", "aif_lsh_simtier_kind", "aif_lsh_din_kind", "aif_lsh_profile_begin", "aif_lsh_profile_end")
 LSH_STAGES = ("user", "din", "simtier")
 USER_EXPORTS = ("aif_user_init", "aif_user_precompute", "aif_user_destroy", "aif_user_last_error",
                 "aif_user_attention_kind", "aif_user_profile_begin", "aif_user_profile_end")
@@ -140,6 +140,8 @@ def load():
     lib.aif_lsh_poll_device_errors.argtypes = [vp, C.POINTER(C.c_int32)]
     lib.aif_lsh_simtier_kind.restype = C.c_int32
     lib.aif_lsh_simtier_kind.argtypes = [vp]
+    lib.aif_lsh_din_kind.restype = C.c_int32
+    lib.aif_lsh_din_kind.argtypes = [vp]
     lib.aif_lsh_profile_begin.restype = C.c_int
     lib.aif_lsh_profile_begin.argtypes = [vp, C.c_int32]
     lib.aif_lsh_profile_end.restype = C.c_int
@@ -375,6 +377,9 @@ class LshContext:
 
     def aif_lsh_simtier_kind(self) -> int:
         return int(self._lib.aif_lsh_simtier_kind(self._h))
+
+    def aif_lsh_din_kind(self) -> int:
+        return int(self._lib.aif_lsh_din_kind(self._h))
 
     def aif_lsh_profile_begin(self, max_calls: int):
         self._check(self._lib.aif_lsh_profile_begin(self._h, max_calls))

@@ -29,6 +29,7 @@ struct aif_lsh_ctx {
     void *part = nullptr, *A = nullptr, *bad = nullptr;     // device workspace (owned)
     void *hist = nullptr;                                   // the requests' history signatures as matrix operands (or null: SimTier on the vector ALU)
     void *parts = nullptr;                                  // partial tier counts of a batch whose histories are cut into parts
+    void *din_pieces = nullptr;                             // the requests' LSH-DIN tables as bf16 matrix operands (or null: LSH-DIN on the vector ALU)
     size_t hist_stride = 0;
     char *h_stage = nullptr, *h_stage_dev = nullptr;        // pinned ring of descriptor tables, its device mapping (or null)
     void *d_stage = nullptr;
@@ -74,6 +75,7 @@ void ldestroy(aif_lsh_ctx *c)
     if (c->bad) (void)hipFree(c->bad);
     if (c->hist) (void)hipFree(c->hist);
     if (c->parts) (void)hipFree(c->parts);
+    if (c->din_pieces) (void)hipFree(c->din_pieces);
     if (c->d_stage) (void)hipFree(c->d_stage);
     if (c->h_stage) (void)hipHostFree(c->h_stage);
     for (int i = 0; i < LSH_NSLOT; ++i)
@@ -124,6 +126,11 @@ aif_status linit(const aif_lsh_config *cfg, const uint8_t *table, aif_lsh_ctx *c
             LSH_TRY(nullptr, hipMalloc(&c->hist, c->hist_stride * 16 * (size_t)c->max_users));
             LSH_TRY(nullptr, hipMalloc(&c->parts, lsh_simtier_parts_bytes()));
         }
+    }
+    {
+        const char *valu = getenv("AIF_LSH_DIN_VALU");          // testing and measurement: LSH-DIN on the vector ALU whatever the shape
+        if (lsh_din_on_mfma(m) && !(valu && valu[0] == '1'))
+            LSH_TRY(nullptr, hipMalloc(&c->din_pieces, lsh_din_pieces_stride(m) * 16 * (size_t)c->max_users));
     }
     LSH_TRY(nullptr, hipMalloc(&c->bad, 16));
     LSH_TRY(nullptr, hipMemset(c->bad, 0, 16));
@@ -221,7 +228,10 @@ aif_status aif_lsh_batch(aif_lsh_ctx *c, const aif_lsh_request *reqs, int32_t n_
     LSH_TRY(c, launch_lsh_user_partial(m, b, max_chunks, c->max_chunks, (float *)c->part, s));
     LSH_TRY(c, launch_lsh_user_reduce(m, b, c->max_chunks, (const float *)c->part, (float *)c->A, s));
     if (pe) LSH_TRY(c, hipEventRecord(pe[1], s));
-    LSH_TRY(c, launch_lsh_din(m, b, c->table, (const float *)c->A, (int32_t *)c->bad, s));
+    if (c->din_pieces)
+        LSH_TRY(c, launch_lsh_din_mfma(m, b, c->table, (const float *)c->A, c->din_pieces, (int32_t *)c->bad, s));
+    else
+        LSH_TRY(c, launch_lsh_din(m, b, c->table, (const float *)c->A, (int32_t *)c->bad, s));
     if (pe) LSH_TRY(c, hipEventRecord(pe[2], s));
     if (c->hist)
         LSH_TRY(c, launch_lsh_simtier_mfma(m, b, c->table, c->hist, c->hist_stride, longest, c->parts, s));
@@ -234,6 +244,8 @@ aif_status aif_lsh_batch(aif_lsh_ctx *c, const aif_lsh_request *reqs, int32_t n_
 }
 
 int32_t aif_lsh_simtier_kind(const aif_lsh_ctx *ctx) { return !ctx ? -1 : (ctx->hist ? 1 : 0); }
+
+int32_t aif_lsh_din_kind(const aif_lsh_ctx *ctx) { return !ctx ? -1 : (ctx->din_pieces ? 1 : 0); }
 
 aif_status aif_lsh_poll_device_errors(aif_lsh_ctx *c, int32_t *n_bad_ids)
 {

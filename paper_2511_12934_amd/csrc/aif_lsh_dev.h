@@ -46,6 +46,12 @@ hipError_t launch_lsh_user_reduce(const LshModel &m, const LshBatch &b, int max_
 // Eq. 8: din[i][j] = (1 / d') sum_k A[b_ik][k][j]
 hipError_t launch_lsh_din(const LshModel &m, const LshBatch &b, const uint8_t *sig_table, const float *A, int32_t *bad,
                           hipStream_t s);
+// Eq. 8 on the matrix cores (d a multiple of 32 up to 128): the candidates' bits one-hot against the tables cut into three
+// bf16 pieces.  pieces: workspace of lsh_din_pieces_stride() 16-byte pieces per request, written by the launch itself.
+bool lsh_din_on_mfma(const LshModel &m);
+size_t lsh_din_pieces_stride(const LshModel &m);
+hipError_t launch_lsh_din_mfma(const LshModel &m, const LshBatch &b, const uint8_t *sig_table, const float *A, void *pieces,
+                               int32_t *bad, hipStream_t s);
 // Eq. 6, 7, 9: equal-bit counts against every history item, counted into tiers
 hipError_t launch_lsh_simtier(const LshModel &m, const LshBatch &b, const uint8_t *sig_table, hipStream_t s);
 // The same with the equal-bit counts formed on the matrix cores (signatures of 32, 64 or 128 bits; 2 d' / N a power of

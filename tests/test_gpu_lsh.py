@@ -87,23 +87,26 @@ def test_shapes_ragged(R, torch, dtype, d_bits, d_out, n_tiers):
     # the matrix-core SimTier serves exactly the shapes whose tiers are a power of two of equal-bit counts wide
     width = 2 * d_bits / n_tiers
     assert ctx.aif_lsh_simtier_kind() == int(d_bits in (32, 64, 128) and width == int(width) and int(width) & (int(width) - 1) == 0)
+    assert ctx.aif_lsh_din_kind() == int(d_out % 32 == 0 and d_out <= 128)
 
 
-@pytest.mark.parametrize("d_bits,n_tiers", [(64, 8), (128, 8), (32, 4)])
-def test_simtier_on_the_vector_alu_gives_the_same_counts(R, torch, monkeypatch, d_bits, n_tiers):
-    """The two SimTier kernels against the oracle on the same requests (a context reads the switch when it is made)."""
-    cfg = wl.LshConfig("S", 12, "bf16", 1, 10, 3000, d_bits, 32, n_tiers, 50, n_clusters=16, flip=0.2)
-    _say(f"lsh SimTier, both kernels, d'={d_bits} N={n_tiers}")
+@pytest.mark.parametrize("d_bits,d_out,n_tiers", [(64, 64, 8), (128, 128, 8), (32, 32, 4), (256, 96, 8)])
+def test_vector_alu_kernels_give_the_same_results(R, torch, monkeypatch, d_bits, d_out, n_tiers):
+    """SimTier and LSH-DIN on the matrix cores and on the vector ALU, both against the oracle on the same requests (a
+    context reads the switches when it is made): the same counts, the same DIN within the fp32 bound."""
+    cfg = wl.LshConfig("S", 12, "bf16", 1, 10, 3000, d_bits, d_out, n_tiers, 50, n_clusters=16, flip=0.2)
+    _say(f"lsh both kernel families, d'={d_bits} d={d_out} N={n_tiers}")
     table = wl.make_sig_table_host(cfg)
     rng = np.random.default_rng(5)
     users_ids = [(wl.make_lsh_user(cfg, rng, seq_len=L, sigma=1.0), rng.integers(0, cfg.n_items, n).astype(np.int32))
                  for n, L in [(300, 777), (17, 31), (256, 128)]]
     ctx, drs = check(R, torch, cfg, table, users_ids)
-    assert ctx.aif_lsh_simtier_kind() == 1
+    assert ctx.aif_lsh_simtier_kind() == int(d_bits <= 128) and ctx.aif_lsh_din_kind() == 1
     on_mfma = [d.tiers.cpu().numpy().copy() for d in drs]
     monkeypatch.setenv("AIF_LSH_SIMTIER_VALU", "1")
+    monkeypatch.setenv("AIF_LSH_DIN_VALU", "1")
     ctx2, drs2 = check(R, torch, cfg, table, users_ids)
-    assert ctx2.aif_lsh_simtier_kind() == 0
+    assert ctx2.aif_lsh_simtier_kind() == 0 and ctx2.aif_lsh_din_kind() == 0
     for a, d in zip(on_mfma, drs2):
         assert np.array_equal(a, d.tiers.cpu().numpy())
 
