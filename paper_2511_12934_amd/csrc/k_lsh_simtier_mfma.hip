@@ -97,6 +97,9 @@ __device__ __forceinline__ void simtier_store(const LshModel &m, const LshReqDes
 // (COLS = 4) two waves share a group and halve the history.  gridDim.y > 1: the history is cut into that many parts as
 // well, a block each, and the counts go to `parts` [part][candidate slot][tier] for k_lsh_simtier_finish -- for batches
 // too small to fill the chip otherwise (a handful of users with long histories).
+// Every wave reads its row tiles from L2 itself: with 128-bit signatures (4 KB a tile) that stream, not the vector ALU,
+// is what binds, and four column tiles a wave (a tile's bytes serve 128 candidates, two tiles in flight) is what the
+// registers allow.
 template <int KS, int COLS>
 __global__ __launch_bounds__(256, 2) void k_lsh_simtier_mfma(LshModel m, LshBatch b, const uint8_t *__restrict__ sig_table,
                                                              const v4i *__restrict__ hist, size_t req_stride, int sh,
@@ -195,20 +198,23 @@ __global__ __launch_bounds__(256, 2) void k_lsh_simtier_mfma(LshModel m, LshBatc
     };
 
     int passes = 0, rt0 = rt_begin;
-    // the rows of a pass are asked for a pass ahead, tile by tile (the last pass asks for its own rows again)
-    v4i rows[SMT_GROUP][KS];
+    // a row tile is asked for AHEAD tiles before its turn, into the registers of the tile just read (past the last
+    // whole pass the last tile is asked for again)
+    constexpr int AHEAD = KS * COLS > 8 ? 2 : SMT_GROUP;        // the registers a long signature's operands leave
+    static_assert(SMT_GROUP % AHEAD == 0, "a tile's registers are the same in every pass");
+    v4i rows[AHEAD][KS];
+    const int rt_last = rt_begin + (rt_end - rt_begin) / SMT_GROUP * SMT_GROUP - 1;      // of the whole passes
     if (rt0 + SMT_GROUP <= rt_end)
 #pragma unroll
-        for (int u = 0; u < SMT_GROUP; ++u) load_rows(rt0 + u, rows[u]);
+        for (int u = 0; u < AHEAD; ++u) load_rows(rt0 + u, rows[u]);
     for (; rt0 + SMT_GROUP <= rt_end; rt0 += SMT_GROUP) {
         uint32_t f[SMT_COLS], e[SMT_COLS];                      // carries of weight 4 and 8 waiting for their partner
-        const int rt_ahead = rt0 + 2 * SMT_GROUP <= rt_end ? rt0 + SMT_GROUP : rt0;
 #pragma unroll
         for (int u = 0; u < SMT_GROUP; ++u) {
             uint32_t w[SMT_COLS][4];
 #pragma unroll
-            for (int ct = 0; ct < SMT_COLS; ++ct) tile_words(rows[u], ct, w[ct]);
-            load_rows(rt_ahead + u, rows[u]);                   // the same row tile of the next pass, into the registers just read
+            for (int ct = 0; ct < SMT_COLS; ++ct) tile_words(rows[u % AHEAD], ct, w[ct]);
+            load_rows(min(rt0 + u + AHEAD, rt_last), rows[u % AHEAD]);
 #pragma unroll
             for (int ct = 0; ct < SMT_COLS; ++ct) {
                 uint32_t ca, cb, fu;
@@ -347,7 +353,7 @@ hipError_t launch_lsh_simtier_mfma(const LshModel &m, const LshBatch &b, const u
     switch (ks) {
     case 1: hipLaunchKernelGGL((k_lsh_simtier_mfma<1, 4>), grid, dim3(256), 0, s, m, b, sig_table, (const v4i *)hist, req_stride, sh, pp); break;
     case 2: hipLaunchKernelGGL((k_lsh_simtier_mfma<2, 4>), grid, dim3(256), 0, s, m, b, sig_table, (const v4i *)hist, req_stride, sh, pp); break;
-    default: hipLaunchKernelGGL((k_lsh_simtier_mfma<4, 2>), grid, dim3(256), 0, s, m, b, sig_table, (const v4i *)hist, req_stride, sh, pp); break;
+    default: hipLaunchKernelGGL((k_lsh_simtier_mfma<4, 4>), grid, dim3(256), 0, s, m, b, sig_table, (const v4i *)hist, req_stride, sh, pp); break;
     }
     if (n_parts > 1) hipLaunchKernelGGL(k_lsh_simtier_finish, dim3(b.n_blk), dim3(256), 0, s, m, b, sh, (const int32_t *)pp, n_parts);
     return hipGetLastError();
