@@ -5,6 +5,7 @@
 #include "aif_lsh_dev.h"
 #include "aif_dev.h"
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -114,7 +115,7 @@ aif_status linit(const aif_lsh_config *cfg, const uint8_t *table, aif_lsh_ctx *c
     c->max_seq_len = cfg->max_seq_len;
     c->max_candidates = cfg->max_candidates;
     c->max_users = cfg->max_users;
-    c->max_chunks = (cfg->max_seq_len + LSH_TCHUNK - 1) / LSH_TCHUNK;
+    c->max_chunks = std::min(LSH_MAX_CHUNKS, (cfg->max_seq_len + LSH_TCHUNK - 1) / LSH_TCHUNK);   // a shorter history never has more chunks than a longer one's cap
     LSH_TRY(nullptr, hipGetDevice(&c->device));
     const size_t tab = (size_t)2 * m.d_bits * m.d_out * 4;
     LSH_TRY(nullptr, hipMalloc(&c->part, tab * (size_t)c->max_users * (c->max_chunks > 0 ? c->max_chunks : 1)));
@@ -210,7 +211,7 @@ aif_status aif_lsh_batch(aif_lsh_ctx *c, const aif_lsh_request *reqs, int32_t n_
         const int nb = (q.n_cand + LSH_BLOCK - 1) / LSH_BLOCK;
         for (int j = 0; j < nb; ++j) hb[slots / LSH_BLOCK + j] = r;
         slots += nb * LSH_BLOCK;
-        const int ch = (q.seq_len + LSH_TCHUNK - 1) / LSH_TCHUNK;
+        const int ch = lsh_chunks(q.seq_len);
         if (ch > max_chunks) max_chunks = ch;
         if (q.seq_len > longest) longest = q.seq_len;
     }

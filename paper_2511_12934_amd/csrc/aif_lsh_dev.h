@@ -6,7 +6,22 @@
 namespace aif {
 
 constexpr int LSH_BLOCK = 256;          // candidates per scheduling block
-constexpr int LSH_TCHUNK = 512;         // history items whose user-side sums one block forms
+constexpr int LSH_TCHUNK = 512;         // history items whose user-side sums one block forms (more for a long history)
+constexpr int LSH_MAX_CHUNKS = 64;      // chunks of one history at most
+// Chunk length of a history of L items: LSH_TCHUNK times the smallest whole factor that keeps the chunks within
+// LSH_MAX_CHUNKS -- every chunk's partial sums (2 d' d floats) are written to memory and read back, which a history of
+// 10^5 items would otherwise do 196 times.  A function of the request's own history only, like everything that
+// decides the order of its sums.
+__host__ __device__ inline int lsh_chunk_len(int L)
+{
+    const int chunks = (L + LSH_TCHUNK - 1) / LSH_TCHUNK;
+    return LSH_TCHUNK * ((chunks + LSH_MAX_CHUNKS - 1) / LSH_MAX_CHUNKS > 1 ? (chunks + LSH_MAX_CHUNKS - 1) / LSH_MAX_CHUNKS : 1);
+}
+__host__ __device__ inline int lsh_chunks(int L)
+{
+    const int len = lsh_chunk_len(L);
+    return (L + len - 1) / len;
+}
 constexpr int LSH_MAX_TIERS = 8;
 
 struct LshReqDesc {

@@ -38,9 +38,10 @@ __global__ __launch_bounds__(256) void k_lsh_user_partial(LshModel m, LshBatch b
     extern __shared__ __align__(16) char lds[];
     const int r = blockIdx.y, chunk = blockIdx.x;
     const LshReqDesc rd = b.reqs[r];
-    const int t_lo = chunk * LSH_TCHUNK;
+    const int chunk_len = lsh_chunk_len(rd.seq_len);
+    const int t_lo = chunk * chunk_len;
     if (t_lo >= rd.seq_len) return;
-    const int t_hi = min(rd.seq_len, t_lo + LSH_TCHUNK);
+    const int t_hi = min(rd.seq_len, t_lo + chunk_len);
     const int d = m.d_out, nb = m.d_bits / 8, jg = d / 16, items = m.d_bits * jg;
     float *su = (float *)lds;                               // [LSH_TSUB][d]
     uint8_t *ss = (uint8_t *)(su + LSH_TSUB * d);           // [LSH_TSUB][nb]
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(256) void k_lsh_user_partial(LshModel m, LshBatch b
 // both pass through LDS: 64 history items at a time, the embeddings set down transposed ([j][t]: a lane's eight
 // consecutive t are one 16-byte read), the signatures turned into bit planes over t by wave ballots (lane = t), from
 // which an A fragment -- eight consecutive t of one bit position -- is one byte, expanded to eight bf16 through a
-// 256-entry table in LDS.  Block = (chunk of LSH_TCHUNK items, request), four waves; the 2 d' / 32 x d / 32 result
+// 256-entry table in LDS.  Block = (chunk of lsh_chunk_len items, request), four waves; the 2 d' / 32 x d / 32 result
 // tiles are dealt round the waves, TPW each.
 // ---------------------------------------------------------------------------
 typedef __bf16 lsh_bf16x8 __attribute__((ext_vector_type(8)));
@@ -121,9 +122,10 @@ __global__ __launch_bounds__(256) void k_lsh_user_partial_mfma(LshModel m, LshBa
     extern __shared__ __align__(16) char lds[];
     const int r = blockIdx.y, chunk = blockIdx.x;
     const LshReqDesc rd = b.reqs[r];
-    const int t_lo = chunk * LSH_TCHUNK;
+    const int chunk_len = lsh_chunk_len(rd.seq_len);
+    const int t_lo = chunk * chunk_len;
     if (t_lo >= rd.seq_len) return;
-    const int t_hi = min(rd.seq_len, t_lo + LSH_TCHUNK);
+    const int t_hi = min(rd.seq_len, t_lo + chunk_len);
     const int d = m.d_out, db = m.d_bits, nb = db / 8, CT = d / 32;
     constexpr int USTR = LSH_TS * 2 + 16;                        // bytes per transposed embedding row (64 t + padding)
     uint4 *lut = (uint4 *)lds;                                   // [256] byte -> eight bf16 of 0 / 1, first bit = first slot
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(256) void k_lsh_user_reduce(LshModel m, LshBatch b,
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
     const int L = b.reqs[r].seq_len;
-    const int chunks = (L + LSH_TCHUNK - 1) / LSH_TCHUNK;
+    const int chunks = lsh_chunks(L);
     float acc = 0.f;
     for (int c = 0; c < chunks; ++c) acc += part[((size_t)r * max_chunks + c) * n + i];
     A[(size_t)r * n + i] = acc;

@@ -29,7 +29,9 @@ def din_tolerance(u_seq, L, d_bits):
     """Per output feature j.  Every U~[t, j] enters the GPU's sum exactly d' times (once per bit, in the table
     of the value the candidate's bit takes) through chains of at most 128 (staged items) + 4 (stagings per
     chunk of 512) + chunks + d' (bits) fp32 additions, then one division by d'.  The standard bound for a sum,
-    n u sum|x| with u = 2^-24, over the d' copies and divided by d' gives  n 2^-24 sum_t |U~[t, j]|."""
+    n u sum|x| with u = 2^-24, over the d' copies and divided by d' gives  n 2^-24 sum_t |U~[t, j]|.
+    (A history of more than 64 chunks is cut into 64 longer ones: 4 m stagings and about chunks / m partial sums with
+    m = ceil(chunks / 64), fewer additions in a row than the 4 + chunks counted here.)"""
     n = 128 + 4 + (L + 511) // 512 + d_bits + 2
     return n * 2.0 ** -24 * np.abs(u_seq.astype(np.float64)).sum(0) + 1e-30
 
@@ -115,7 +117,7 @@ def test_vector_alu_kernels_give_the_same_results(R, torch, monkeypatch, d_bits,
 def test_simtier_long_history_few_candidates(R, torch, d_bits, seq_len):
     """A batch too small to fill the chip: the histories are cut into parts, a block each, and a second kernel adds the
     parts' counts up; a history this long also makes every wave read its counting planes out more than once."""
-    cfg = wl.LshConfig("S", 13, "bf16", 1, 10, 5000, d_bits, 16, 8, 50, n_clusters=16, flip=0.2)
+    cfg = wl.LshConfig("S", 13, "bf16", 1, 10, 5000, d_bits, 64 if d_bits == 128 else 16, 8, 50, n_clusters=16, flip=0.2)
     _say(f"lsh long history d'={d_bits} L={seq_len}")
     table = wl.make_sig_table_host(cfg)
     rng = np.random.default_rng(6)
