@@ -18,12 +18,16 @@
 // through a four-slot ring in LDS, two 32-key tiles per stage, three stages in
 // flight, with direct-to-LDS loads; all waves of a block share them.
 //
-// Softmax is shift invariant, so instead of a running maximum (and the
-// rescaling of O it forces) each candidate subtracts the bound
-// |q| max_t |k_t| / sqrt(d_h) >= every score (Cauchy-Schwarz).  If that bound
-// is large enough to risk underflow (exponent range wider than 2^-80) the wave
-// first takes the true maximum in an extra pass over K.  Both are the exact
-// softmax up to rounding.
+// The keys are packed times log2(e) / sqrt(d_h) (pack_kv_block), so the first
+// product is the weight's exponent in base 2 and a weight costs one
+// exponential.  Softmax is shift invariant: no running maximum (and none of
+// the rescaling of O it forces).  Every exponent is bounded in size by
+// |q| max_t |k'_t| (Cauchy-Schwarz, k' the packed key); while that bound is
+// small enough for fp32 (2^+-40) the exponents are used as they are, and if it
+// is not, the wave first takes the candidate's true maximum in an extra pass
+// over K and subtracts it (under a scalar branch, or in a plain loop beside
+// the pipelined one: it is rare).
+// Both are the exact softmax up to rounding.
 #include <cstdlib>
 #include <type_traits>
 
@@ -44,7 +48,6 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void store_stream(bf16x8 *p, bf16x8 v) { __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), (u32x4 *)p); }
 __device__ __forceinline__ void store_stream(bf16x4 *p, bf16x4 v) { __builtin_nontemporal_store(__builtin_bit_cast(u32x2, v), (u32x2 *)p); }
 
-constexpr float LOG2E = 1.4426950408889634f;
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // acc + a[2i] b[2i] + a[2i + 1] b[2i + 1], i = 0..3, as four two-term dot products (one instruction each)
@@ -87,7 +90,10 @@ __device__ __forceinline__ uint16_t bea_a_element(const uint16_t *V, const Model
     const int w = 16 * ks + 8 * (lane >> 5) + s - g.pad;
     return w >= 0 ? V[(size_t)w * m.d_cv + 32 * ft + (lane & 31)] : (uint16_t)0;
 }
-constexpr float BOUND_LIMIT = 40.f;      // exponents stay within [-80, 0]
+// The first product is the weight's exponent in base 2.  Its size is bounded by |q| times the largest packed key norm;
+// within this limit the exponent is used as it is -- weights between 2^-40 and 2^40, their sums far inside fp32, and the
+// common factor cancels in the division -- beyond it the candidate's true maximum is found and subtracted.
+constexpr float BOUND_LIMIT = 40.f;
 
 // The streaming kernels sum a candidate's keys in KEY_PARTS runs of whole 64-key stages, run q = stages
 // [q nst / KEY_PARTS, (q + 1) nst / KEY_PARTS), each run from zero, and add the runs' sums in the order of q.
@@ -170,7 +176,6 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
     const char *pk = kvpack + (size_t)us * pack_stride;
     const int local = local0 + wave * 32 + col;
     const bool live = local < rd.n_cand;
-    const float c = LOG2E / sqrtf((float)DH);
 
     constexpr int SLOTS = 4, DIST = SLOTS - 1, LPW = 2 * FR / WAVES;      // ring, prefetch distance, loads per wave and stage
     const uint32_t ring = lds_address(lds);
@@ -204,12 +209,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
         ss += __shfl_xor(ss, 32, 64);
 #pragma unroll
         for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
-        float mc = c * sqrtf(ss) * 1.001f * km;
+        float mc = sqrtf(ss) * 1.001f * km;
         // A candidate's choice between the bound and the true maximum depends on its own row only
         // (rows past the end of the request hold whatever the workspace held before and take no part),
         // so its bits do not depend on which candidates share its wave.
         const bool need_max = live && mc > BOUND_LIMIT;
-        if (__any(need_max)) {
+        const bool shifted = __any(need_max);                // the same in every lane: a scalar branch
+        if (shifted) {
             // rare: take the true maximum with an extra pass over K (read straight from memory)
             float mx = -INFINITY;
             for (int kt = 0; kt < nkt; ++kt) {
@@ -227,7 +233,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
                 }
             }
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            if (need_max) mc = c * mx;
+            mc = need_max ? mx : 0.f;       // a candidate within the limit keeps its exponents as they are: x - 0 = x
         }
 
         // O, l: the current run of key tiles; Ot, lt: the runs before it (KEY_PARTS)
@@ -270,7 +276,12 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
                     S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + j * 1024), q[j], S, 0, 0, 0);
                 float p[16];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(fmaf(S[v], c, -mc));
+                for (int v = 0; v < 16; ++v) p[v] = S[v];
+                if (shifted)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) p[v] -= mc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) p[v] = __builtin_amdgcn_exp2f(p[v]);
                 if (32 * kt + 32 > L) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
@@ -411,7 +422,6 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_split(Model m, Batch b, cha
     const int us = rd.slot;
     const char *pk = kvpack + (size_t)us * pack_stride + lane * 16;
     const bool live = local0 + col < rd.n_cand;
-    const float c = LOG2E / sqrtf((float)DH);
     // this wave's runs, in tiles: whole stages of two (the last one of an odd sequence ends in the pack's empty tile)
     const int kt0 = 2 * key_part_begin(RPW * wave, nst), kt1 = 2 * key_part_begin(RPW * (wave + 1), nst);
 
@@ -458,9 +468,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_split(Model m, Batch b, cha
         ss += __shfl_xor(ss, 32, 64);
 #pragma unroll
         for (int off = 32; off; off >>= 1) km = fmaxf(km, __shfl_xor(km, off, 64));
-        float mc = c * sqrtf(ss) * 1.001f * km;
+        float mc = sqrtf(ss) * 1.001f * km;
         const bool need_max = live && mc > BOUND_LIMIT;      // per candidate, as in k_attn_mfma
-        if (__any(need_max)) {
+        const bool shifted = __any(need_max);                // the same in every lane: a scalar branch
+        if (shifted) {
             // rare: the true maximum, by an extra pass over all of K in every wave (the maximum has no order)
             float mx = -INFINITY;
             for (int kt = 0; kt < nkt; ++kt) {
@@ -478,7 +489,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_split(Model m, Batch b, cha
                 }
             }
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            if (need_max) mc = c * mx;
+            mc = need_max ? mx : 0.f;       // a candidate within the limit keeps its exponents as they are: x - 0 = x
         }
 
         f32x16 O[FT];
@@ -514,6 +525,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_split(Model m, Batch b, cha
             auto body = [&](bf16x8(&vc)[2 * FT], bf16x8(&kn)[JS], int kt) {
                 f32x16 Sn;
                 float p[16];
+                if (shifted) {              // rare: the candidate's maximum comes off every exponent (a scalar branch)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) S[v] -= mc;
+                }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int j = 0; j < JS; ++j) {
@@ -526,7 +541,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_split(Model m, Batch b, cha
                         Sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kn[j], q[j], Sn, 0, 0, 0);
 #pragma unroll
                     for (int v = 16 / JS * j; v < 16 / JS * (j + 1); ++v) {
-                        p[v] = __builtin_amdgcn_exp2f(fmaf(S[v], c, -mc));
+                        p[v] = __builtin_amdgcn_exp2f(S[v]);
                         asm volatile("" : "+v"(p[v]));      // computed HERE: a value with no side effect would sink to its first use
                     }
                     __builtin_amdgcn_sched_barrier(0);
@@ -752,7 +767,6 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     wait_vmcnt<0>();
     __syncthreads();
 
-    const float c = LOG2E / sqrtf((float)DH);
     const char *kv0 = lds + lane * 16;
     const int pc_cross = (m.d_item + m.d_attn) / 8;             // first piece of the cross block
 
@@ -863,9 +877,10 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                 S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + j * 1024), q[j], S, 0, 0, 0);
             return S;
         };
-        float mc = c * sqrtf(ss) * 1.001f * skm[hd];
+        float mc = sqrtf(ss) * 1.001f * skm[hd];
         const bool need_max = live && mc > BOUND_LIMIT;      // per candidate, as in k_attn_mfma
-        if (__any(need_max)) {
+        const bool shifted = __any(need_max);                // the same in every lane: a scalar branch
+        if (shifted) {
             // rare: take the true maximum with an extra pass over K
             float mx = -INFINITY;
             for (int kt = 0; kt < nkt; ++kt) {
@@ -877,7 +892,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                 }
             }
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            if (need_max) mc = c * mx;
+            mc = need_max ? mx : 0.f;       // a candidate within the limit keeps its exponents as they are: x - 0 = x
         }
 
         f32x16 O[FT];
@@ -923,7 +938,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                 }
 #pragma unroll
                 for (int v = 16 / JS * j; v < 16 / JS * (j + 1); ++v) {
-                    p[v] = __builtin_amdgcn_exp2f(fmaf(Sin[v], c, -mc));
+                    p[v] = __builtin_amdgcn_exp2f(Sin[v]);
                     asm volatile("" : "+v"(p[v]));      // computed HERE: a value with no side effect would sink to its first use
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -963,7 +978,31 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         };
         using Yes = std::true_type;
         using No = std::false_type;
-        if (nkt > 0) {
+        if (shifted) {
+            // rare: the candidate's maximum is subtracted from every exponent.  A plain loop over the key tiles, the
+            // arithmetic and its order those of the pipelined steps.
+            for (int kt = 0; kt < nkt; ++kt) {
+                const f32x16 Sk = s_tile(kt);
+                const char *vbase = kbase + (kt * FR + JS) * 1024;
+                float p[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int t = 32 * kt + 8 * (v >> 2) + 4 * h + (v & 3);
+                    p[v] = t < L ? __builtin_amdgcn_exp2f(Sk[v] - mc) : 0.f;
+                }
+                bf16x8 P0, P1;
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    P0[v] = (__bf16)p[v];
+                    P1[v] = (__bf16)p[8 + v];
+                }
+                l = sum_pairs<0, 4>(P0, l);
+                l = sum_pairs<0, 4>(P1, l);
+#pragma unroll
+                for (int i = 0; i < 2 * FT; ++i)
+                    O[i % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(vbase + i * 1024), i < FT ? P0 : P1, O[i % FT], 0, 0, 0);
+            }
+        } else if (nkt > 0) {
 #pragma unroll
             for (int j = 0; j < JS; ++j) kf[j] = *(const bf16x8 *)(kbase + j * 1024);
 #pragma unroll
@@ -1002,7 +1041,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                 for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(next_hd * (DH / 8) + 2 * j + h) * xl.piece_stride);
             }
         }
-        if (nkt > 0) step(nkt - 1, S, S1, No{}, 32 * nkt > L);
+        if (!shifted && nkt > 0) step(nkt - 1, S, S1, No{}, 32 * nkt > L);
 
         l += __shfl_xor(l, 32, 64);
         const float inv = L > 0 ? 1.0f / l : 0.f;

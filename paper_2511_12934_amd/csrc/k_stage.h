@@ -473,6 +473,26 @@ __device__ __forceinline__ void fold_w0_block(int slot, int part, const Model &m
 // ((head * nktp + kt) * FR) KB:  JS K-fragments  [lane][s] = K[32kt + lane%32][o + 16j + 8(lane/32) + s]
 // then 2*FT V-fragments (jj, ft): [lane][s] = V[32kt + 16jj + 8(s/4) + 4(lane/32) + s%4][o + 32ft + lane%32]
 // with o = head * DH; keys >= seq_len read as zero.
+// Eight keys' elements of one piece, each times `scale` and rounded to bf16 again (nearest even: the hardware's
+// conversion, two values an instruction).
+__device__ __forceinline__ uint4 scaled_bf16x8(uint4 v, float scale)
+{
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        bf16x2_t r;
+        r[0] = (__bf16)(__uint_as_float(w[j] << 16) * scale);
+        r[1] = (__bf16)(__uint_as_float(w[j] & 0xFFFF0000u) * scale);
+        w[j] = __builtin_bit_cast(uint32_t, r);
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// The keys are packed times log2(e) / sqrt(d_head): the first product of the attention kernels then IS the exponent of
+// the softmax weight in base 2 (Sec. 3.3's scaled dot product, the scale and the change of base done once per user and
+// key instead of once per candidate and key; one more rounding of the key to bf16).
+constexpr float ATTN_LOG2E = 1.4426950408889634f;
 template <int DH, class Reqs>
 __device__ __forceinline__ void pack_kv_block(int slot, int hd, int st, const Model &m, const Reqs &src,
                                               char *__restrict__ kvpack, size_t pack_stride,
@@ -483,6 +503,7 @@ __device__ __forceinline__ void pack_kv_block(int slot, int hd, int st, const Mo
     const int L = rd->seq_len;
     const int nkt2 = (((L + 31) >> 5) + 1) & ~1;
     if (2 * st >= nkt2) return;
+    const float kscale = ATTN_LOG2E / sqrtf((float)DH);
     const uint16_t *K = (const uint16_t *)rd->seq_keys, *V = (const uint16_t *)rd->seq_vals;
     const int da = m.d_attn, o = hd * DH;
     uint4 *dst = (uint4 *)(kvpack + (size_t)slot * pack_stride + ((size_t)(hd * nktp + 2 * st) * FR) * 1024);
@@ -519,7 +540,7 @@ __device__ __forceinline__ void pack_kv_block(int slot, int hd, int st, const Mo
         const int kt = 2 * st + k2, hh = lane >> 5;
         uint4 out;
         if (frag < JS) {
-            out = 32 * kt + (lane & 31) < L ? kpiece[it] : make_uint4(0, 0, 0, 0);
+            out = 32 * kt + (lane & 31) < L ? scaled_bf16x8(kpiece[it], kscale) : make_uint4(0, 0, 0, 0);
         } else {
             const int jj = (frag - JS) / FT, t0 = 32 * kt + 16 * jj + 4 * hh;
             uint32_t w[4];
@@ -554,8 +575,9 @@ __device__ __forceinline__ void pack_kv_block(int slot, int hd, int st, const Mo
         float nrm = sqrtf(ss);
 #pragma unroll
         for (int off = 32; off; off >>= 1) nrm = fmaxf(nrm, __shfl_xor(nrm, off, 64));
-        // round the bound up a little: it must dominate the fp32-accumulated score
-        if (threadIdx.x == 0) kmax_part[((size_t)slot * m.n_heads + hd) * (nktp / 2) + st] = nrm * 1.001f;
+        // the packed key is the key times kscale, rounded (each element at most 1 + 2^-8 times as large); the bound is
+        // rounded up a little more: it must dominate the fp32-accumulated first product
+        if (threadIdx.x == 0) kmax_part[((size_t)slot * m.n_heads + hd) * (nktp / 2) + st] = nrm * kscale * (1.f + 1.f / 256.f) * 1.001f;
     }
 }
 

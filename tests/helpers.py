@@ -111,8 +111,32 @@ def feature_tolerance(dtype: str, ref: np.ndarray) -> np.ndarray:
     return 2.0 ** -7 * np.abs(ref) + 2.0 ** -6 * rms + 1e-30
 
 
-def assert_features_close(dtype: str, got: np.ndarray, ref: np.ndarray, what: str):
+def key_rounding_term(cfg, model, rows: np.ndarray, user) -> np.ndarray:
+    """bf16 target attention without a query projection.  The GPU path packs each key times log2(e) / sqrt(d_h) and
+    rounds it to bf16 again (unit roundoff u = 2^-8); the oracle never rounds.  A weight's exponent (base 2) moves by at
+    most ds = u log2(e) sum_k |q_k K_tk| / sqrt(d_h), the weight by a factor within 2^(+-ds), the normalised weights
+    together by at most 2 ln(2) max_t ds, the output by that times max |V|:  2 u max_t (sum_k |q_k K_tk|) / sqrt(d_h) max |V|
+    per feature -- added to the block's bf16 tolerance.  About 1e-4 at the configurations' scale (rows, keys, values of
+    N(0, 0.1)); it grows with the square of the inputs' scale, as the error itself does.  [n, d_attn]; zeros where the
+    model projects the query (that route rounds the query instead, and is judged by its own rule) or has no keys."""
+    dh = cfg.d_attn // cfg.n_heads
+    out = np.zeros((rows.shape[0], cfg.d_attn))
+    K = np.abs(user.seq_keys.astype(np.float64))
+    if model.w_q is not None or K.shape[0] == 0:
+        return out
+    q = np.abs(rows.astype(np.float64))[:, :cfg.d_attn]
+    vmax = np.abs(user.seq_vals.astype(np.float64)).max(axis=0)
+    for h in range(cfg.n_heads):
+        sl = slice(h * dh, (h + 1) * dh)
+        ds = 2.0 ** -8 * (q[:, sl] @ K[:, sl].T).max(axis=1) / np.sqrt(dh)
+        out[:, sl] = 2.0 * ds[:, None] * vmax[None, sl]
+    return out
+
+
+def assert_features_close(dtype: str, got: np.ndarray, ref: np.ndarray, what: str, extra=None):
     tol = feature_tolerance(dtype, ref)
+    if extra is not None and dtype != "f32":
+        tol = tol + extra
     err = np.abs(got.astype(np.float64) - ref)
     assert np.all(np.isfinite(got)), f"{what}: non-finite"
     w = np.unravel_index(int(np.argmax(err - tol)), err.shape) if err.size else ()

@@ -9,7 +9,7 @@ import pytest
 import oracle
 from paper_2511_12934_amd import workloads as wl
 
-from helpers import (BF16_GUARD_MAX, BF16_GUARD_RMS, assert_bf16_logits_tight, assert_features_close, assert_logits_close,
+from helpers import (BF16_GUARD_MAX, BF16_GUARD_RMS, assert_bf16_logits_tight, assert_features_close, assert_logits_close, key_rounding_term,
                      oracle_scores_rows, topk_recall)
 
 pytestmark = pytest.mark.gpu
@@ -49,7 +49,8 @@ def test_full_size_batched_config(name):
         worst_max, worst_rms = max(worst_max, e_max / z_rms), max(worst_rms, e_rms / z_rms)
         X = R.peek_features(w.ctx, cfg, u, cfg.n_cand)
         assert np.array_equal(X[:, :cfg.d_item], rows), "gather is not an exact row copy"
-        used_a = max(used_a, assert_features_close(cfg.dtype, X[:, cfg.d_item:cfg.d_item + cfg.d_attn], ref.attn, "attention"))
+        used_a = max(used_a, assert_features_close(cfg.dtype, X[:, cfg.d_item:cfg.d_item + cfg.d_attn], ref.attn, "attention",
+                                                   key_rounding_term(cfg, w.model, rows, w.requests[u].user)))
         used_c = max(used_c, assert_features_close(cfg.dtype, X[:, cfg.d_item + cfg.d_attn:], ref.cross, "cross"))
         # the GPU's top-k against the ORACLE's top-k: sets may differ only within the guard's band of the cut
         band = BF16_GUARD_MAX[0] * float(np.abs(ref.logits).max()) + BF16_GUARD_MAX[1] * z_rms
