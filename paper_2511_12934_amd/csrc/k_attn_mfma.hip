@@ -685,7 +685,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     extern __shared__ __align__(16) char lds[];
     float *skm = (float *)(lds + RES_LDS_FRAGS * 1024);         // [n_heads] max |k_t|
     bf16x8 *su = (bf16x8 *)(skm + RES_MAX_HEADS);               // the request's Hadamard operand
-    int *s_next = (int *)(su + RES_MAX_ITEM_PIECES);            // next tile of the group nobody has taken yet
+    int *s_next = (int *)(su + RES_MAX_ITEM_PIECES);            // next item of the group nobody has taken yet
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), col = lane & 31, h = lane >> 5;
     const AttnGroup g = b.groups[blockIdx.x];
@@ -704,9 +704,9 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         const int lc = (g.t0 + t) * 32 + col;
         return lc < rd.n_cand ? rd.cand_ids[lc] : 0;
     };
-    auto checked = [&](int raw) {
+    auto checked = [&](int raw, bool count) {           // count: once per candidate (by the item of its first head)
         if (raw < 0 || (int64_t)raw >= m.n_items) {
-            if (h == 0) atomicAdd(bad, 1);
+            if (h == 0 && count) atomicAdd(bad, 1);
             raw = 0;
         }
         return raw;
@@ -717,9 +717,21 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     // rides along: its id is asked for ahead of the first half of the pack and its row pieces between the halves, so
     // that id -> row (two trips to memory) pass under the pack's flight instead of after the barrier.  (A wave with
     // no tile in the group reads the group's last tile's: no condition around the loads.)
+    // A wave's unit of work is an item = (tile, head), item i = tile i / H, head i % H: with several heads a group's
+    // items divide over the waves far more evenly than its tiles would.
+    const int n_items = n_tiles * H;
+    const float inv_h = 1.0f / (float)H;
+    auto tile_of = [&](int item) {                      // item / H (exact: the estimate is off by one at most)
+        if (H == 1) return item;
+        int t = (int)((float)item * inv_h);
+        const int rem = item - t * H;
+        t += rem >= H ? 1 : (rem < 0 ? -1 : 0);
+        return t;
+    };
     bf16x8 q[JS];
     int id = 0;                             // GATHER: row of the table the current item's candidate has
-    const int tile_first = wave < n_tiles ? wave : n_tiles - 1;
+    const int item_first = wave < n_items ? wave : n_items - 1;
+    const int tile_first = tile_of(item_first), hd_first = item_first - tile_first * H;
     int raw_first = 0;
     if constexpr (GATHER) raw_first = raw_id(tile_first);
     const uint32_t ring = lds_address(lds);
@@ -732,14 +744,14 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     };
     pack_to_lds(0, nhalf);
     if constexpr (GATHER) {
-        id = checked(wave < n_tiles ? raw_first : 0);       // (a stand-in id is not the request's: never counted as bad)
+        id = checked(wave < n_items ? raw_first : 0, hd_first == 0);     // (a stand-in id is not the request's: never counted as bad)
         const char *tr = table_row(id);
 #pragma unroll
-        for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(tr + (2 * j + h) * 16);
+        for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(tr + (hd_first * (DH / 8) + 2 * j + h) * 16);
     } else {
         const char *xr = row_of(tile_first);
 #pragma unroll
-        for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(2 * j + h) * xl.piece_stride);
+        for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(hd_first * (DH / 8) + 2 * j + h) * xl.piece_stride);
     }
     pack_to_lds(nhalf, nfrag);
     for (int hd = wave; hd < H; hd += RES_WAVES) {
@@ -770,27 +782,24 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     const char *kv0 = lds + lane * 16;
     const int pc_cross = (m.d_item + m.d_attn) / 8;             // first piece of the cross block
 
-    // A wave's work is a sequence of (tile, head) items.  Tiles are handed out on demand -- the SIMD
+    // A wave's work is a sequence of (tile, head) items, handed out on demand -- the SIMD
     // favours its older waves, so with a fixed share per wave the young ones would finish the kernel
     // alone.  The only global reads an item needs are its query pieces; they are asked for as soon as
     // the previous item has issued its last S product (the registers are free from then on), so their
     // latency passes under that item's last exponentials, second product and stores.
-    auto take_tile = [&]() {
+    auto take_item = [&]() {
         int t = 0;
         if (lane == 0) t = atomicAdd(s_next, 1);
         return __builtin_amdgcn_readfirstlane(t);
     };
-    int tile = wave, hd = 0;
-    while (tile < n_tiles) {
-        int next_tile = tile, next_hd = hd + 1;
-        if (next_hd == H) {
-            next_hd = 0;
-            next_tile = take_tile();
-        }
-        // the next tile's id is asked for now and looked at only when this item's last S product has been issued
+    int item = wave, tile = tile_first, hd = hd_first;
+    while (item < n_items) {
+        const int next_item = take_item();
+        const int next_tile = tile_of(next_item), next_hd = next_item - next_tile * H;
+        // the next item's id is asked for now and looked at only when this item's last S product has been issued
         int next_raw = 0;
         if constexpr (GATHER)
-            if (next_hd == 0 && next_tile < n_tiles) next_raw = raw_id(next_tile);
+            if (next_item < n_items) next_raw = raw_id(next_tile);
         const int local = (g.t0 + tile) * 32 + col;
         const bool live = local < rd.n_cand;
         char *xrow = row_of(tile);
@@ -1029,9 +1038,9 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         // both the ordinary and the empty sequence: a second copy of these loads on another path into this point makes
         // the compiler wait, at the key-tile loop's first MFMA, for every memory operation in flight -- the item's
         // stores included.)
-        if (next_tile < n_tiles) {
+        if (next_item < n_items) {
             if constexpr (GATHER) {
-                if (next_hd == 0) id = checked(next_raw);
+                id = checked(next_raw, next_hd == 0);
                 const char *tr = table_row(id);
 #pragma unroll
                 for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(tr + (next_hd * (DH / 8) + 2 * j + h) * 16);
@@ -1056,6 +1065,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                     store_stream((bf16x4 *)piece((m.d_item + hd * DH) / 8 + 4 * ft + qd) + h, o4);
                 }
         }
+        item = next_item;
         tile = next_tile;
         hd = next_hd;
     }
@@ -1076,9 +1086,8 @@ int attn_plan_groups(const Model &m, const ReqDesc *reqs, int n_req, int n_cu, A
     for (int r = 0; r < n_req; ++r)
         if (res_fits(m, reqs[r].seq_len)) total += (reqs[r].n_cand + 31) / 32;
     if (total == 0) return 0;
-    // about one group per CU, each a whole number of rounds of the 16 waves
+    // about one group per CU (its waves take the (tile, head) items one at a time, so a group need not be whole rounds)
     long per = (total + n_cu - 1) / n_cu;
-    per = (per + RES_WAVES - 1) / RES_WAVES * RES_WAVES;
     if (per < RES_WAVES) per = RES_WAVES;
     if (info) info->per = (int32_t)per;
     int n = 0;

@@ -38,8 +38,7 @@ hipError_t mfma_plan(const Model &m, int max_seq_len, int max_users, size_t x_ro
 void mfma_release(MfmaPlan &plan);
 
 // Host side: which attention kernel serves which request.  A request whose packed K/V (all heads) fit in one
-// CU's LDS goes to the resident kernel: such requests are cut into groups of tiles (about one group per CU, whole
-// rounds of the kernel's waves), written to `out` (room for attn_max_groups() entries), their number returned.
+// CU's LDS goes to the resident kernel: such requests are cut into groups of tiles (about one group per CU), written to `out` (room for attn_max_groups() entries), their number returned.
 // The others are the streaming kernels': *n_streamed says how many (requests with candidates).  The choice
 // depends on the request alone, so its result does not depend on what else is in the batch.
 // info (optional): what a device-side rebuild of the groups needs (few_fill): the tiles per group at most, and which
