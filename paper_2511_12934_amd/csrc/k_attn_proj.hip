@@ -263,7 +263,7 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
     };
     auto stage_load = [&](int i) {
         const char *src = stage_src(i) + lane * 16;
-        const uint32_t dst = ring + (i % P_SLOTS) * P_STAGE_BYTES;
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(ring + (i % P_SLOTS) * P_STAGE_BYTES);     // (the stage count is the same in every lane)
 #pragma unroll
         for (int f0 = 0; f0 < P_STAGE_FRAGS; f0 += WAVES) dma16(src + (f0 + wave) * 1024, dst + (f0 + wave) * 1024);
     };
@@ -380,6 +380,17 @@ __global__ __launch_bounds__(WAVES * 64, 4) void k_attn_proj(Model m, Batch b, c
 
     const char *kv0 = lds + lane * 16;
     int it = 0;
+    // a wave whose 32 rows lie past the request's end (the last block of a request) computes nothing: it only keeps
+    // its place in the ring -- its share of every stage's loads and the stage's barrier
+    const bool idle = __builtin_amdgcn_readfirstlane((int)(local0 + wave * 32 >= rd.n_cand)) != 0;     // the same in every lane
+    if (idle) {
+        for (int i = 0; i < total; ++i) {
+            wait_vmcnt<0>();
+            asm volatile("s_barrier" ::: "memory");
+            if (i + P_DIST < total) stage_load(i + P_DIST);
+        }
+        return;
+    }
 #pragma unroll
     for (int hd = 0; hd < H; ++hd) {
         float ss = 0.f;
