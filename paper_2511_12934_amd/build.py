@@ -13,8 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libaif.so")
-# measurement tooling, a library of its own: the MFMA-loop and copy calibrators of profiling/peaks.py
-CALIB_SRC = os.path.join(HERE, "profiling", "calibrate.hip")
+# measurement tooling, a library of its own: the MFMA-loop and copy calibrators and the attention loop of profiling/peaks.py
+CALIB_SRCS = [os.path.join(HERE, "profiling", f) for f in ("calibrate.hip", "attention_loop.hip")]
 CALIB_LIB = os.path.join(HERE, "profiling", "libaif_calib.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -53,10 +53,10 @@ def build(force: bool = False) -> str:
         objs = list(ex.map(lambda f: _compile(f, force), sources()))
     if force or not os.path.exists(LIB) or any(os.path.getmtime(o) > os.path.getmtime(LIB) for o in objs):
         subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
-    if force or not os.path.exists(CALIB_LIB) or os.path.getmtime(CALIB_LIB) < os.path.getmtime(CALIB_SRC):
-        r = subprocess.run([HIPCC, *FLAGS, "-shared", CALIB_SRC, "-o", CALIB_LIB], capture_output=True, text=True)
+    if force or not os.path.exists(CALIB_LIB) or os.path.getmtime(CALIB_LIB) < max(os.path.getmtime(f) for f in CALIB_SRCS):
+        r = subprocess.run([HIPCC, *FLAGS, "-shared", *CALIB_SRCS, "-o", CALIB_LIB], capture_output=True, text=True)
         if r.returncode != 0:
-            raise RuntimeError("hipcc failed on calibrate.hip:\n" + "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l))
+            raise RuntimeError("hipcc failed on the calibration sources:\n" + "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l))
     return LIB
 
 

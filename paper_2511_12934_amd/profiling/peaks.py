@@ -74,6 +74,30 @@ def main() -> None:
         print(f"  {lb:40s} {v:7.2f}")
     print(f"  => v_fma_f32 {ns[7] / 16:.2f} ns, v_exp_f32 {(ns[6] - ns[7] / 2) / 8:.2f} ns; an MFMA under which the vector work does not fit "
           f"adds {ns[4] - ns[6]:.2f} ns (of its {ns[0]:.2f}) to the vector work's time")
+    lib.aifcal_valu_costs.restype = C.c_int
+    lib.aifcal_valu_costs.argtypes = [C.POINTER(C.c_double)]
+    vc = (C.c_double * 8)()
+    assert lib.aifcal_valu_costs(vc) == 0
+    print("\nOne kind of vector instruction at a time (16 independent ones per group, 3 waves per SIMD): ns each per SIMD,")
+    print("and what one MFMA (14 ns of the matrix cores) per group adds to the group's time")
+    for i, nm in enumerate(["v_fma_f32", "v_exp_f32", "v_cvt_pk_bf16_f32", "v_dot2c_f32_bf16"]):
+        print(f"  {nm:20s} {vc[i] / 16:5.2f} ns   + MFMA: {vc[4 + i] - vc[i]:+6.2f} ns per group")
+    lib.aifcal_attn_loop.restype = C.c_int
+    lib.aifcal_attn_loop.argtypes = [vp, vp, C.POINTER(C.c_double)]
+    rows = ["whole loop, 3 waves per SIMD", "whole loop, 2 waves per SIMD", "whole loop, 1 wave per SIMD", "without the row sums",
+            "without the exponentials", "without the conversions", "without the LDS reads", "MFMAs alone",
+            "row sums as fp32 adds of the unrounded weights", "whole loop once more"]
+    print("\nThe resident attention kernel's key-tile loop in isolation (heads of 64: 8 MFMAs, 16 v_exp_f32, 8 v_cvt_pk_bf16_f32,")
+    print("8 v_dot2c_f32_bf16, 8 LDS fragment reads per 32-key tile): ns per key tile and SIMD (3 waves per SIMD unless stated)")
+    print(f"  {'':48s} {'zeros':>8s} {'N(0,0.1)':>9s}")
+    kvz, qz = torch.zeros(64 * 1024, dtype=torch.bfloat16, device="cuda"), torch.zeros(32 * 1024, dtype=torch.bfloat16, device="cuda")
+    kvr = (torch.randn(64 * 1024, device="cuda", generator=g) * 0.1).to(torch.bfloat16)
+    qr = (torch.randn(32 * 1024, device="cuda", generator=g) * 0.1).to(torch.bfloat16)
+    lz, lr = (C.c_double * 10)(), (C.c_double * 10)()
+    assert lib.aifcal_attn_loop(kvz.data_ptr(), qz.data_ptr(), lz) == 0
+    assert lib.aifcal_attn_loop(kvr.data_ptr(), qr.data_ptr(), lr) == 0
+    for i, nm in enumerate(rows):
+        print(f"  {nm:48s} {lz[i]:8.1f} {lr[i]:9.1f}")
     print(f"\nachievable_peak mfma_bf16 {best[(1, 'random N(0,0.1)')]:.1f}")
     print(f"achievable_peak hbm {cp.value:.0f}")
     print(f"achievable_peak hbm_read {rd.value:.0f}")
