@@ -59,17 +59,6 @@ __device__ __forceinline__ float dot8(const bf16x8 &a, const bf16x8 &b, float ac
     acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(b, b, 6, 7), acc, false);
     return acc;
 }
-// acc + the sum of elements [2 i0, 2 i0 + 2 n) of a (pairs i0 .. i0 + n - 1), pair by pair
-template <int I0, int N> __device__ __forceinline__ float sum_pairs(const bf16x8 &a, float acc)
-{
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    if constexpr (N >= 1 && I0 <= 0 && 0 < I0 + N) acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 0, 1), ones, acc, false);
-    if constexpr (N >= 1 && I0 <= 1 && 1 < I0 + N) acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 2, 3), ones, acc, false);
-    if constexpr (N >= 1 && I0 <= 2 && 2 < I0 + N) acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 4, 5), ones, acc, false);
-    if constexpr (N >= 1 && I0 <= 3 && 3 < I0 + N) acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 6, 7), ones, acc, false);
-    return acc;
-}
-
 // BEA cross block (Sec. 4.1, Algorithm 1 step 4) on the matrix cores: C^T = V^T w^T with the
 // candidates as columns.  The contraction runs over the row's last 16 * ksb entries (the "window",
 // ksb = ceil(n_cross / 16) k-steps); window entries in front of the n_cross bridge weights meet
@@ -242,7 +231,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
         for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
             for (int i = 0; i < 16; ++i) O[ft][i] = Ot[ft][i] = 0.f;
-        float l = 0.f, lt = 0.f;
+        float l4[4] = {0.f, 0.f, 0.f, 0.f}, lt = 0.f;      // the run's denominator: weight v of every key tile into partial sum v % 4
         int qn = 1, bnd = key_part_begin(1, nst);          // the next run and its first stage
         auto fold = [&]() {
 #pragma unroll
@@ -252,8 +241,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
                     Ot[ft][i] += O[ft][i];
                     O[ft][i] = 0.f;
                 }
-            lt += l;
-            l = 0.f;
+            lt += (l4[0] + l4[1]) + (l4[2] + l4[3]);
+            l4[0] = l4[1] = l4[2] = l4[3] = 0.f;
         };
 
         for (int st = 0; st < nst; ++st) {
@@ -289,16 +278,16 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_mfma(Model m, Batch b, char
                         if (t >= L) p[v] = 0.f;
                     }
                 }
-                // the softmax denominator is the sum of the weights AS ROUNDED for the second product, P0's then P1's,
-                // two a step: the block then is an exact convex combination of the values the matrix cores see
+                // the softmax denominator is the fp32 sum of the weights as they leave the exponential; the second
+                // product takes them rounded to bf16
                 bf16x8 P0, P1;
 #pragma unroll
                 for (int v = 0; v < 8; ++v) {
                     P0[v] = (__bf16)p[v];
                     P1[v] = (__bf16)p[8 + v];
                 }
-                l = sum_pairs<0, 4>(P0, l);
-                l = sum_pairs<0, 4>(P1, l);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) l4[v & 3] += p[v];
 #pragma unroll
                 for (int ft = 0; ft < FT; ++ft) {
                     O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(base + (JS + ft) * 1024), P0, O[ft], 0, 0, 0);
@@ -497,7 +486,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_split(Model m, Batch b, cha
         for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
             for (int i = 0; i < 16; ++i) O[ft][i] = 0.f;
-        float l = 0.f;
+        float l4[4] = {0.f, 0.f, 0.f, 0.f};                 // as in k_attn_mfma
         // a finished run's sums go to LDS and the next run starts from zero
         if (hd > 0) __syncthreads();                        // the previous head's sums have been read
         int qn = RPW * wave;
@@ -510,8 +499,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_split(Model m, Batch b, cha
                     mine[(ft * 16 + i) * 64] = O[ft][i];
                     O[ft][i] = 0.f;
                 }
-            mine[NREG * 64] = l;
-            l = 0.f;
+            mine[NREG * 64] = (l4[0] + l4[1]) + (l4[2] + l4[3]);
+            l4[0] = l4[1] = l4[2] = l4[3] = 0.f;
             ++qn;
         };
         if (kt1 > kt0) {
@@ -560,8 +549,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_split(Model m, Batch b, cha
                     P0[v] = (__bf16)p[v];
                     P1[v] = (__bf16)p[8 + v];
                 }
-                l = sum_pairs<0, 4>(P0, l);                 // the weights as rounded, P0's pairs then P1's
-                l = sum_pairs<0, 4>(P1, l);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) l4[v & 3] += p[v];
 #pragma unroll
                 for (int ft = 0; ft < FT; ++ft) {
                     O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vc[ft], P0, O[ft], 0, 0, 0);
@@ -909,7 +898,9 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         for (int ft = 0; ft < FT; ++ft)
 #pragma unroll
             for (int i = 0; i < 16; ++i) O[ft][i] = 0.f;
-        float l = 0.f;
+        // the softmax denominator: the weights as they leave the exponential (fp32; the second product takes them
+        // rounded to bf16), weight v of every key tile into partial sum v % 4
+        float l4[4] = {0.f, 0.f, 0.f, 0.f};
         // ---- the key-tile loop, software-pipelined inside the wave ------------------------------------------
         // A wave issues in order, so what must overlap has to alternate in its instruction stream.  Per key tile t:
         //   - the S product of tile t + 1 is a chain of JS MFMAs, each waiting for the one before: one link per
@@ -918,7 +909,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         //   - the K fragment a link has just consumed is refilled from LDS with tile t + 2's (a whole tile of lead),
         //     V fragments of tile t are asked for at the top of the tile;
         //   - the second product's MFMAs (feature tiles alternating, so consecutive ones are independent) carry the
-        //     row sums (of the rounded weights) between them.
+        //     adds of the row sums (the softmax denominator) between them.
         // Scheduling barriers pin the slots; within a slot the compiler is free.  Per candidate the arithmetic and
         // its order are unchanged.
         const char *kbase = kvh;                                       // K fragment j of tile t: kbase + (t FR + j) KB
@@ -966,22 +957,16 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                 P1[v] = (__bf16)p[8 + v];
             }
             __builtin_amdgcn_sched_barrier(0);
-            // per feature tile the P0 step, then the P1 step (the order the streaming kernel accumulates in);
-            // issued feature tile by feature tile within a step; the row sums ride between the MFMAs
+            // per feature tile the P0 step, then the P1 step; issued feature tile by feature tile within a step; the
+            // row sums ride between the MFMAs
 #pragma unroll
             for (int i = 0; i < 2 * FT; ++i) {
                 const int ft = i % FT;
                 O[ft] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], i < FT ? P0 : P1, O[ft], 0, 0, 0);
-                // the denominator: the weights as rounded, P0's pairs then P1's (the streaming kernel's order)
-                if constexpr (FT == 2) {
-                    if (i == 0) l = sum_pairs<0, 2>(P0, l);
-                    if (i == 1) l = sum_pairs<2, 2>(P0, l);
-                    if (i == 2) l = sum_pairs<0, 2>(P1, l);
-                    if (i == 3) l = sum_pairs<2, 2>(P1, l);
-                } else {
-                    if (i == 0) l = sum_pairs<0, 4>(P0, l);
-                    if (i == 1) l = sum_pairs<0, 4>(P1, l);
-                }
+                // the denominator's share of this slot: plain fp32 adds run beside the MFMAs, the two-term dot products
+                // that summed the rounded weights and the MFMAs exclude each other
+#pragma unroll
+                for (int v = 16 / (2 * FT) * i; v < 16 / (2 * FT) * (i + 1); ++v) l4[v & 3] += p[v];
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
@@ -1005,8 +990,8 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
                     P0[v] = (__bf16)p[v];
                     P1[v] = (__bf16)p[8 + v];
                 }
-                l = sum_pairs<0, 4>(P0, l);
-                l = sum_pairs<0, 4>(P1, l);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) l4[v & 3] += p[v];
 #pragma unroll
                 for (int i = 0; i < 2 * FT; ++i)
                     O[i % FT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8 *)(vbase + i * 1024), i < FT ? P0 : P1, O[i % FT], 0, 0, 0);
@@ -1052,6 +1037,7 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         }
         if (!shifted && nkt > 0) step(nkt - 1, S, S1, No{}, 32 * nkt > L);
 
+        float l = (l4[0] + l4[1]) + (l4[2] + l4[3]);
         l += __shfl_xor(l, 32, 64);
         const float inv = L > 0 ? 1.0f / l : 0.f;
         if (live) {

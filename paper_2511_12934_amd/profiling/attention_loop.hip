@@ -3,7 +3,7 @@
 // measurement tooling, part of libaif_calib, not of libaif.
 //   aifcal_attn_loop:  K and V fragments of one request resident in LDS, every wave walks items of 16 key tiles with
 //                      the kernel's schedule (score product of tile t + 1 interleaved with the exponentials of tile t,
-//                      conversions, second product with the row sums between its MFMAs).  Parts of the loop can be left
+//                      conversions, second product with the row sums' fp32 adds between its MFMAs).  Parts of the loop can be left
 //                      out (timing only: the results are then meaningless), which prices each part; the operand values
 //                      come from the caller (zeros hold the full clock, random values meet the power limit).
 //   aifcal_valu_costs: sixteen independent instructions of one kind per group, three waves per SIMD, with and without
@@ -23,7 +23,7 @@ constexpr int NKT = 16, FR = 8, JS = 4, FT = 2;         // key tiles per item; 1
 constexpr int LDS_BYTES = NKT * FR * 1024;
 
 // parts of the loop that can be left out
-constexpr int NO_SUMS = 1, NO_EXP = 2, NO_LDS = 4, NO_CVT = 8, SUMS_AS_ADDS = 16;
+constexpr int NO_SUMS = 1, NO_EXP = 2, NO_LDS = 4, NO_CVT = 8, SUMS_AS_DOTS = 16;
 
 template <int I0, int N> __device__ __forceinline__ float sum_pairs(const bf16x8 &a, float acc)
 {
@@ -110,14 +110,14 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_loop(const uint4 *__restric
 #pragma unroll
             for (int i = 0; i < 2 * FT; ++i) {
                 O[i % FT] = MFMA(vf[i], i < FT ? P0 : P1, O[i % FT]);
-                if constexpr (LEAVE_OUT & SUMS_AS_ADDS) {
-#pragma unroll
-                    for (int v = 4 * i; v < 4 * (i + 1); ++v) l4[v & 3] += p[v];
-                } else if constexpr (!(LEAVE_OUT & NO_SUMS)) {
+                if constexpr (LEAVE_OUT & SUMS_AS_DOTS) {       // the rounded weights, two a v_dot2c_f32_bf16
                     if (i == 0) l = sum_pairs<0, 2>(P0, l);
                     if (i == 1) l = sum_pairs<2, 2>(P0, l);
                     if (i == 2) l = sum_pairs<0, 2>(P1, l);
                     if (i == 3) l = sum_pairs<2, 2>(P1, l);
+                } else if constexpr (!(LEAVE_OUT & NO_SUMS)) {  // the kernel's: fp32 adds of the weights before rounding
+#pragma unroll
+                    for (int v = 4 * i; v < 4 * (i + 1); ++v) l4[v & 3] += p[v];
                 }
                 SLOT_END;
             }
@@ -140,8 +140,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_loop(const uint4 *__restric
         }
         step(kt, S, S1, true);
         step(kt + 1, S1, S, false);
-        if constexpr (LEAVE_OUT & SUMS_AS_ADDS) l = (l4[0] + l4[1]) + (l4[2] + l4[3]);
-        else if constexpr (LEAVE_OUT & NO_SUMS) l = 1.0f + O[0][0];
+        if constexpr (!(LEAVE_OUT & SUMS_AS_DOTS)) l = (LEAVE_OUT & NO_SUMS) ? 1.0f + O[0][0] : (l4[0] + l4[1]) + (l4[2] + l4[3]);
         l += __shfl_xor(l, 32, 64);
         const float inv = 1.0f / l;
         for (int ft = 0; ft < FT; ++ft)
@@ -213,7 +212,8 @@ extern "C" {
 // kv: DEVICE, 128 KB of bf16 (the request's K and V fragments); q: DEVICE, 64 KB of bf16 (queries).  ns_out (HOST, 10
 // values): nanoseconds per key tile and SIMD of the whole loop at 3, 2 and 1 waves per SIMD, then at 3 waves per SIMD
 // without the row sums, without the exponentials, without the conversions, without the LDS reads, with the MFMAs
-// alone, with the row sums as fp32 adds of the unrounded weights, and the whole loop once more.  Returns 0 on success.
+// alone, with the row sums as two-term dot products of the rounded weights (eight v_dot2c_f32_bf16 a key tile: the
+// kernel's former way), and the whole loop once more.  Returns 0 on success.
 __attribute__((visibility("default"))) int aifcal_attn_loop(const void *kv, const void *q, double *ns_out)
 {
     int dev = 0;
@@ -246,7 +246,7 @@ __attribute__((visibility("default"))) int aifcal_attn_loop(const void *kv, cons
              timed(k_attn_loop<12, NO_SUMS>, 12, ns_out + 3) || timed(k_attn_loop<12, NO_EXP>, 12, ns_out + 4) ||
              timed(k_attn_loop<12, NO_CVT>, 12, ns_out + 5) || timed(k_attn_loop<12, NO_LDS>, 12, ns_out + 6) ||
              timed(k_attn_loop<12, NO_SUMS | NO_EXP | NO_CVT | NO_LDS>, 12, ns_out + 7) ||
-             timed(k_attn_loop<12, NO_SUMS | SUMS_AS_ADDS>, 12, ns_out + 8) || timed(k_attn_loop<12, 0>, 12, ns_out + 9);
+             timed(k_attn_loop<12, SUMS_AS_DOTS>, 12, ns_out + 8) || timed(k_attn_loop<12, 0>, 12, ns_out + 9);
     (void)hipFree(out);
     return rc;
 }
