@@ -49,6 +49,19 @@ __device__ __forceinline__ void store_stream(bf16x8 *p, bf16x8 v) { __builtin_no
 __device__ __forceinline__ void store_stream(bf16x4 *p, bf16x4 v) { __builtin_nontemporal_store(__builtin_bit_cast(u32x2, v), (u32x2 *)p); }
 
 
+// Loads the compiler does not track: completion is waited for by hand (wait_vmcnt), so that the wait can name how many
+// YOUNGER memory operations may still be in flight.  The compiler's own wait at the head of the item loop is whole
+// (the first pass's loads and the later passes' meet there, and a load through a pointer of unknown address space is
+// waited for together with everything else): every item then began by waiting for the previous item's stores.
+__device__ __forceinline__ void load16_untracked(bf16x8 &dst, const char *p)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void load4_untracked(int &dst, const void *p)
+{
+    asm volatile("global_load_dword %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
+}
+
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // acc + a[2i] b[2i] + a[2i + 1] b[2i + 1], i = 0..3, as four two-term dot products (one instruction each)
 __device__ __forceinline__ float dot8(const bf16x8 &a, const bf16x8 &b, float acc)
@@ -693,6 +706,12 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         const int lc = (g.t0 + t) * 32 + col;
         return lc < rd.n_cand ? rd.cand_ids[lc] : 0;
     };
+    // the same as an untracked load (a lane past the request's end reads the request's first id and drops it)
+    auto raw_id_untracked = [&](int &dst, int t) {
+        const int lc = (g.t0 + t) * 32 + col;
+        load4_untracked(dst, rd.cand_ids + (lc < rd.n_cand ? lc : 0));
+    };
+    auto in_request = [&](int t) { return (g.t0 + t) * 32 + col < rd.n_cand; };
     auto checked = [&](int raw, bool count) {           // count: once per candidate (by the item of its first head)
         if (raw < 0 || (int64_t)raw >= m.n_items) {
             if (h == 0 && count) atomicAdd(bad, 1);
@@ -736,11 +755,11 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         id = checked(wave < n_items ? raw_first : 0, hd_first == 0);     // (a stand-in id is not the request's: never counted as bad)
         const char *tr = table_row(id);
 #pragma unroll
-        for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(tr + (hd_first * (DH / 8) + 2 * j + h) * 16);
+        for (int j = 0; j < JS; ++j) load16_untracked(q[j], tr + (hd_first * (DH / 8) + 2 * j + h) * 16);
     } else {
         const char *xr = row_of(tile_first);
 #pragma unroll
-        for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(hd_first * (DH / 8) + 2 * j + h) * xl.piece_stride);
+        for (int j = 0; j < JS; ++j) load16_untracked(q[j], xr + (size_t)(hd_first * (DH / 8) + 2 * j + h) * xl.piece_stride);
     }
     pack_to_lds(nhalf, nfrag);
     for (int hd = wave; hd < H; hd += RES_WAVES) {
@@ -783,12 +802,17 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
     };
     int item = wave, tile = tile_first, hd = hd_first;
     while (item < n_items) {
+        // the item's query: asked for when the previous item had issued its last S product; younger than those loads
+        // are only that item's 4 FT output stores (before the first item the kernel's opening wait has covered them)
+        wait_vmcnt<4 * FT>();
+#pragma unroll
+        for (int j = 0; j < JS; ++j) asm volatile("" : "+v"(q[j]));
         const int next_item = take_item();
         const int next_tile = tile_of(next_item), next_hd = next_item - next_tile * H;
         // the next item's id is asked for now and looked at only when this item's last S product has been issued
         int next_raw = 0;
         if constexpr (GATHER)
-            if (next_item < n_items) next_raw = raw_id(next_tile);
+            if (next_item < n_items) raw_id_untracked(next_raw, next_tile);
         const int local = (g.t0 + tile) * 32 + col;
         const bool live = local < rd.n_cand;
         char *xrow = row_of(tile);
@@ -1025,17 +1049,24 @@ __global__ __launch_bounds__(RES_WAVES * 64) void k_attn_res(Model m, Batch b, c
         // stores included.)
         if (next_item < n_items) {
             if constexpr (GATHER) {
-                id = checked(next_raw, next_hd == 0);
+                // the id asked for at the item's start: younger than it are at least this item's JS stores of the item block
+                if (__any(live)) wait_vmcnt<JS>();
+                else wait_vmcnt<0>();
+                asm volatile("" : "+v"(next_raw));
+                id = checked(in_request(next_tile) ? next_raw : 0, next_hd == 0);
                 const char *tr = table_row(id);
 #pragma unroll
-                for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(tr + (next_hd * (DH / 8) + 2 * j + h) * 16);
+                for (int j = 0; j < JS; ++j) load16_untracked(q[j], tr + (next_hd * (DH / 8) + 2 * j + h) * 16);
             } else {
                 const char *xr = row_of(next_tile);
 #pragma unroll
-                for (int j = 0; j < JS; ++j) q[j] = *(const bf16x8 *)(xr + (size_t)(next_hd * (DH / 8) + 2 * j + h) * xl.piece_stride);
+                for (int j = 0; j < JS; ++j) load16_untracked(q[j], xr + (size_t)(next_hd * (DH / 8) + 2 * j + h) * xl.piece_stride);
             }
         }
         if (!shifted && nkt > 0) step(nkt - 1, S, S1, No{}, 32 * nkt > L);
+        // The next item waits for these loads with this item's 4 FT output stores still in flight (they are younger).  A
+        // tile always has a candidate; should none of its lanes be live the stores are skipped, and the wait is whole.
+        if (!__any(live)) wait_vmcnt<0>();
 
         float l = (l4[0] + l4[1]) + (l4[2] + l4[3]);
         l += __shfl_xor(l, 32, 64);
