@@ -151,6 +151,103 @@ __global__ __launch_bounds__(WAVES * 64) void k_attn_loop(const uint4 *__restric
     out[(size_t)blockIdx.x * WAVES * 64 + threadIdx.x] = tot;
 }
 
+// The same work with TWO 32-candidate tiles a wave (tiles a and b), each the other's partner in the pipeline: while the
+// vector ALU takes the exponentials of one tile's scores the matrix cores form the other's, and a K or V fragment read
+// from LDS serves both -- half the LDS reads per candidate, one S buffer per tile instead of two.
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void k_attn_loop2(const uint4 *__restrict__ kv, const uint4 *__restrict__ qsrc,
+                                                           float *__restrict__ out, int items)
+{
+    extern __shared__ __align__(16) char lds[];
+    for (int i = threadIdx.x; i < LDS_BYTES / 16; i += WAVES * 64) ((uint4 *)lds)[i] = kv[i];
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const char *kbase = lds + lane * 16;
+    bf16x8 qa[JS], qb[JS];
+    for (int j = 0; j < JS; ++j) {
+        qa[j] = __builtin_bit_cast(bf16x8, qsrc[(threadIdx.x * JS + j) & 4095]);
+        qb[j] = __builtin_bit_cast(bf16x8, qsrc[(threadIdx.x * JS + j + 2048) & 4095]);
+    }
+    float tot = 0.f;
+    for (int it = 0; it < items; ++it) {
+        f32x16 Oa[FT], Ob[FT];
+        for (int ft = 0; ft < FT; ++ft)
+            for (int i = 0; i < 16; ++i) Oa[ft][i] = Ob[ft][i] = 0.f;
+        float la[4] = {0.f, 0.f, 0.f, 0.f}, lb[4] = {0.f, 0.f, 0.f, 0.f};
+        bf16x8 kf[JS], vf[2 * FT];
+        f32x16 Sa, Sb;
+        // one phase: the S product of `other` (scores into So, query qo) beside the exponentials of Sin, then the
+        // second product of Sin's tile into O; REFILL_K: the K fragments are the next key tile's from here on;
+        // REFILL_V: so are the V fragments
+        auto phase = [&](const f32x16 &Sin, f32x16 &So, const bf16x8(&qo)[JS], f32x16(&O)[FT], float(&l4)[4], bool s_next, int k_refill,
+                         int v_refill) {
+            float p[16];
+#pragma unroll
+            for (int j = 0; j < JS; ++j) {
+                if (s_next) {
+                    if (j == 0) {
+                        f32x16 Z;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) Z[i] = 0.f;
+                        So = MFMA(kf[0], qo[0], Z);
+                    } else
+                        So = MFMA(kf[j], qo[j], So);
+                    if (k_refill >= 0) kf[j] = *(const bf16x8 *)(kbase + (k_refill * FR + j) * 1024);
+                }
+#pragma unroll
+                for (int v = 4 * j; v < 4 * (j + 1); ++v) {
+                    p[v] = __builtin_amdgcn_exp2f(Sin[v]);
+                    asm volatile("" : "+v"(p[v]));
+                }
+                SLOT_END;
+            }
+            bf16x8 P0, P1;
+#pragma unroll
+            for (int v = 0; v < 8; ++v) {
+                P0[v] = (__bf16)p[v];
+                P1[v] = (__bf16)p[8 + v];
+            }
+            SLOT_END;
+#pragma unroll
+            for (int i = 0; i < 2 * FT; ++i) {
+                O[i % FT] = MFMA(vf[i], i < FT ? P0 : P1, O[i % FT]);
+                if (v_refill >= 0) vf[i] = *(const bf16x8 *)(kbase + (v_refill * FR + JS + i) * 1024);
+#pragma unroll
+                for (int v = 4 * i; v < 4 * (i + 1); ++v) l4[v & 3] += p[v];
+                SLOT_END;
+            }
+        };
+#pragma unroll
+        for (int j = 0; j < JS; ++j) kf[j] = *(const bf16x8 *)(kbase + j * 1024);
+#pragma unroll
+        for (int i = 0; i < 2 * FT; ++i) vf[i] = *(const bf16x8 *)(kbase + (JS + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) Sa[i] = 0.f;
+#pragma unroll
+        for (int j = 0; j < JS; ++j) Sa = MFMA(kf[j], qa[j], Sa);
+        SLOT_END;
+        for (int kt = 0; kt < NKT; ++kt) {
+            const int kn = kt + 1 < NKT ? kt + 1 : NKT - 1;
+            // tile a's weights and second product beside tile b's scores (same key tile); K moves on to the next key tile
+            phase(Sa, Sb, qb, Oa, la, true, kn, -1);
+            // tile b's weights and second product beside tile a's scores of the next key tile; V moves on
+            phase(Sb, Sa, qa, Ob, lb, kt + 1 < NKT, -1, kn);
+        }
+        float l0 = (la[0] + la[1]) + (la[2] + la[3]), l1 = (lb[0] + lb[1]) + (lb[2] + lb[3]);
+        l0 += __shfl_xor(l0, 32, 64);
+        l1 += __shfl_xor(l1, 32, 64);
+        const float i0 = 1.0f / l0, i1 = 1.0f / l1;
+        for (int ft = 0; ft < FT; ++ft)
+            for (int i = 0; i < 16; ++i) tot += Oa[ft][i] * i0 + Ob[ft][i] * i1;
+#pragma unroll
+        for (int j = 0; j < JS; ++j) {
+            qa[j] = __builtin_bit_cast(bf16x8, qsrc[(threadIdx.x * JS + j + 64 * (it + 1)) & 4095]);
+            qb[j] = __builtin_bit_cast(bf16x8, qsrc[(threadIdx.x * JS + j + 2048 + 64 * (it + 1)) & 4095]);
+        }
+    }
+    out[(size_t)blockIdx.x * WAVES * 64 + threadIdx.x] = tot;
+}
+
 // OP: 0 v_fma_f32, 1 v_exp_f32, 2 v_cvt_pk_bf16_f32, 3 v_dot2c_f32_bf16
 template <int OP, int WITH_MFMA>
 __global__ __launch_bounds__(768) void k_valu_cost(float *__restrict__ out, int iters)
@@ -209,11 +306,12 @@ struct Timer {
 
 extern "C" {
 
-// kv: DEVICE, 128 KB of bf16 (the request's K and V fragments); q: DEVICE, 64 KB of bf16 (queries).  ns_out (HOST, 10
+// kv: DEVICE, 128 KB of bf16 (the request's K and V fragments); q: DEVICE, 64 KB of bf16 (queries).  ns_out (HOST, 11
 // values): nanoseconds per key tile and SIMD of the whole loop at 3, 2 and 1 waves per SIMD, then at 3 waves per SIMD
 // without the row sums, without the exponentials, without the conversions, without the LDS reads, with the MFMAs
 // alone, with the row sums as two-term dot products of the rounded weights (eight v_dot2c_f32_bf16 a key tile: the
-// kernel's former way), and the whole loop once more.  Returns 0 on success.
+// kernel's former way), the whole loop once more, and two candidate tiles a wave at 2 waves per SIMD (k_attn_loop2; per 32
+// candidates).  Returns 0 on success.
 __attribute__((visibility("default"))) int aifcal_attn_loop(const void *kv, const void *q, double *ns_out)
 {
     int dev = 0;
@@ -246,7 +344,9 @@ __attribute__((visibility("default"))) int aifcal_attn_loop(const void *kv, cons
              timed(k_attn_loop<12, NO_SUMS>, 12, ns_out + 3) || timed(k_attn_loop<12, NO_EXP>, 12, ns_out + 4) ||
              timed(k_attn_loop<12, NO_CVT>, 12, ns_out + 5) || timed(k_attn_loop<12, NO_LDS>, 12, ns_out + 6) ||
              timed(k_attn_loop<12, NO_SUMS | NO_EXP | NO_CVT | NO_LDS>, 12, ns_out + 7) ||
-             timed(k_attn_loop<12, SUMS_AS_DOTS>, 12, ns_out + 8) || timed(k_attn_loop<12, 0>, 12, ns_out + 9);
+             timed(k_attn_loop<12, SUMS_AS_DOTS>, 12, ns_out + 8) || timed(k_attn_loop<12, 0>, 12, ns_out + 9) ||
+             timed(k_attn_loop2<8>, 8, ns_out + 10);
+    ns_out[10] *= 0.5;          // two candidate tiles a wave: per 32 candidates, like the others
     (void)hipFree(out);
     return rc;
 }

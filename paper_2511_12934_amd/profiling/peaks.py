@@ -86,14 +86,15 @@ def main() -> None:
     lib.aifcal_attn_loop.argtypes = [vp, vp, C.POINTER(C.c_double)]
     rows = ["whole loop, 3 waves per SIMD", "whole loop, 2 waves per SIMD", "whole loop, 1 wave per SIMD", "without the row sums",
             "without the exponentials", "without the conversions", "without the LDS reads", "MFMAs alone",
-            "row sums as 8 v_dot2c_f32_bf16 of the rounded weights", "whole loop once more"]
+            "row sums as 8 v_dot2c_f32_bf16 of the rounded weights", "whole loop once more",
+            "two candidate tiles a wave, 2 waves per SIMD"]
     print("\nThe resident attention kernel's key-tile loop in isolation (heads of 64: 8 MFMAs, 16 v_exp_f32, 8 v_cvt_pk_bf16_f32,")
     print("16 v_add_f32, 8 LDS fragment reads per 32-key tile): ns per key tile and SIMD (3 waves per SIMD unless stated)")
     print(f"  {'':48s} {'zeros':>8s} {'N(0,0.1)':>9s}")
     kvz, qz = torch.zeros(64 * 1024, dtype=torch.bfloat16, device="cuda"), torch.zeros(32 * 1024, dtype=torch.bfloat16, device="cuda")
     kvr = (torch.randn(64 * 1024, device="cuda", generator=g) * 0.1).to(torch.bfloat16)
     qr = (torch.randn(32 * 1024, device="cuda", generator=g) * 0.1).to(torch.bfloat16)
-    lz, lr = (C.c_double * 10)(), (C.c_double * 10)()
+    lz, lr = (C.c_double * 11)(), (C.c_double * 11)()
     assert lib.aifcal_attn_loop(kvz.data_ptr(), qz.data_ptr(), lz) == 0
     assert lib.aifcal_attn_loop(kvr.data_ptr(), qr.data_ptr(), lr) == 0
     for i, nm in enumerate(rows):
