@@ -353,8 +353,11 @@ __global__ __launch_bounds__(WAVES * 64, PER_CU) void k_mlp_mfma(int64_t n_items
         const int local = tile * ROWS - rd.row_base + wave * 32 + col;
         if ((live >> lane) & 1) {
             if ((bad >> lane) & 1) z = __uint_as_float(0x7FC00000u);
-            rd.logits_out[local] = z;
-            if (rd.scores_out) rd.scores_out[local] = 1.0f / (1.0f + __expf(-z));
+            // (stores through pointers known to be global memory: behind a store whose address space the compiler does
+            // not know, the second tile's wait for its input rows becomes a wait for every memory operation in flight)
+            typedef float __attribute__((address_space(1))) *gfloat_t;
+            ((gfloat_t)rd.logits_out)[local] = z;
+            if (rd.scores_out) ((gfloat_t)rd.scores_out)[local] = 1.0f / (1.0f + __expf(-z));
         }
     };
 
