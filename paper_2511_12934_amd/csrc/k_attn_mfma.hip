@@ -53,6 +53,10 @@ __device__ __forceinline__ void store_stream(bf16x4 *p, bf16x4 v) { __builtin_no
 // YOUNGER memory operations may still be in flight.  The compiler's own wait at the head of the item loop is whole
 // (the first pass's loads and the later passes' meet there, and a load through a pointer of unknown address space is
 // waited for together with everything else): every item then began by waiting for the previous item's stores.
+// The price: the compiler believes the destination final at once.  A value loaded this way must have ONE load site per
+// loop (a second site gets registers of its own and is "copied" into place before anything has arrived) and must not be
+// read, copied or carried into another variable before the hand-placed wait; the item block that the gather tests
+// compare bit for bit is made of exactly these registers, so a violation shows there at once.
 __device__ __forceinline__ void load16_untracked(bf16x8 &dst, const char *p)
 {
     asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
