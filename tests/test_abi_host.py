@@ -59,3 +59,16 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         B.load()
+
+
+def test_calibration_library_exports_what_the_peaks_driver_calls():
+    """The measurement tooling is a library of its own (profiling/libaif_calib.so); profiling/peaks.py calls these."""
+    from paper_2511_12934_amd import build
+    if not os.path.exists(build.CALIB_LIB):
+        build.build()
+    lib = ctypes.CDLL(build.CALIB_LIB)
+    src = open(os.path.join(ROOT, "paper_2511_12934_amd", "profiling", "peaks.py")).read()
+    called = sorted(set(re.findall(r"lib\.(aifcal_\w+)", src)))
+    assert {"aifcal_mfma", "aifcal_copy", "aifcal_coissue", "aifcal_attn_loop", "aifcal_valu_costs"} <= set(called)
+    for name in called:
+        assert hasattr(lib, name), name
